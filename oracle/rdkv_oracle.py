@@ -1,0 +1,611 @@
+"""CPU oracle for the RDKV hot path.  TEST INFRASTRUCTURE ONLY.
+
+Plain, slow NumPy written from the paper (arxiv 2605.08317, "RDKV: Rate-Distortion
+Bit Allocation for Joint Eviction and Quantization of the KV Cache").  Only the
+tests, the smoke check and the benchmark's cpu_baseline leg may import it; the
+product (the HIP library and its Python binding) never does, and this file
+imports nothing from the product.
+
+Every function cites the passage it follows.  Floating point is fp64 except the
+reference quantizer, which is fp32 in a fixed operation order so that its codes
+can be compared bit for bit.
+
+Conventions
+-----------
+* One "item" is one (sequence, KV head).  K, V of one sequence: float32 arrays
+  [Hkv, T, d] whose values are exactly representable in bf16.
+* Query head j belongs to KV head j // g, g = Hq // Hkv (Sec. 3, GQA).
+* Tiers (bit-widths) B = {0, 2, 4, 8, 16} (Sec. 3); tier 16 keeps the input
+  16-bit pattern, tier 0 stores nothing.
+
+Parity pins for each function are listed in tests/test_oracle_*.py; every
+function here has at least one pin that is not a retyping of its own formula.
+End-to-end accuracy on the paper's benchmarks is "parity unpinned" (the data
+sets and models are not available).
+"""
+import math
+
+import numpy as np
+
+TIERS = (0, 2, 4, 8, 16)
+PACK_ORDER = (16, 8, 4, 2)          # order of tier segments inside an item
+GROUP = 32                          # quantization group size
+ROW_PAD = 32                        # tier segments are padded to whole 32-row tiles
+SEG_ALIGN = 256                     # byte alignment of every segment in the arena
+
+# Table 9 (App. I), LLaMA-3.1-8B row; eps(0) = 1 and eps(16) = 0 for every model.
+EPS_V_LLAMA31_8B = (1.0, 0.313, 0.0140, 4.9e-5, 0.0)
+EPS_K_LLAMA31_8B = (1.0, 0.149, 0.0062, 2.2e-5, 0.0)
+# Bennett-style table: per-coordinate RMSE proportional to 2^-b (Eq. 5).
+EPS_BENNETT = tuple(2.0 ** (-b) for b in TIERS)
+
+
+# --------------------------------------------------------------------------
+# helpers
+# --------------------------------------------------------------------------
+def _check_bf16_exact(x, name):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if np.any(x.view(np.uint32) & np.uint32(0xFFFF)):
+        raise ValueError(f"{name}: values are not bf16-representable")
+    return x
+
+
+def bf16_bits(x):
+    """uint16 bit patterns of a bf16-exact float32 array."""
+    x = _check_bf16_exact(x, "bf16_bits")
+    return (x.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_from_bits(bits):
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# --------------------------------------------------------------------------
+# Stage 1: distortion weights
+# --------------------------------------------------------------------------
+def token_weights(K, Q_obs, causal=True):
+    """Token weights w_t = sum over window queries and group heads of a_{tau,t}.
+
+    Prop. 3.1 / Eq. 2 and Alg. 1 Stage 1: A = softmax(Q_window K^T / sqrt(d)),
+    w_t^{(h)} = sum_{tau, g} a_{tau,g,t}.  The window holds the last S_w prefill
+    positions; row i sits at absolute position T - S_w + i and (reading taken:
+    weights come from the prefill forward pass, which is causal) attends only
+    keys t <= that position.
+
+    K: [Hkv, T, d]; Q_obs: [Hq, S_w, d].  Returns float64 [Hkv, T] (not pooled).
+    """
+    K = np.asarray(K, dtype=np.float64)
+    Q_obs = np.asarray(Q_obs, dtype=np.float64)
+    Hkv, T, d = K.shape
+    Hq, Sw, d2 = Q_obs.shape
+    assert d2 == d and Hq % Hkv == 0 and T >= Sw
+    g = Hq // Hkv
+    w = np.zeros((Hkv, T), dtype=np.float64)
+    for h in range(Hkv):
+        for j in range(g):
+            Z = Q_obs[h * g + j] @ K[h].T / math.sqrt(d)          # [S_w, T]
+            if causal:
+                for i in range(Sw):
+                    Z[i, T - Sw + i + 1:] = -np.inf
+            Z = Z - Z.max(axis=1, keepdims=True)
+            A = np.exp(Z)
+            A = A / A.sum(axis=1, keepdims=True)
+            w[h] += A.sum(axis=0)
+    return w
+
+
+def avg_pool(w, kernel=5):
+    """AvgPool1d along t (Alg. 1 Stage 1, pooling kernel w = 5).
+
+    Reading taken: stride 1, zero padding kernel//2 on both sides, divisor always
+    `kernel` (padding counted), no renormalisation.
+    """
+    w = np.asarray(w, dtype=np.float64)
+    if kernel <= 1:
+        return w.copy()
+    assert kernel % 2 == 1
+    r = kernel // 2
+    T = w.shape[-1]
+    padded = np.zeros(w.shape[:-1] + (T + 2 * r,), dtype=np.float64)
+    padded[..., r:r + T] = w
+    out = np.zeros_like(w)
+    for k in range(kernel):
+        out += padded[..., k:k + T]
+    return out / kernel
+
+
+def channel_weights(K, Q_obs):
+    """Channel weights w_c = ||Q[:,c]||_2 ||K[:,c]||_2 / sqrt(d)  (Prop. 3.2, Eq. 4).
+
+    Q[:,c] stacks the window queries of all g query heads of the group (the only
+    queries the probe provides); K[:,c] runs over all T keys of the uncompressed
+    cache (Sec. 3.2 Stage 1).  Returns float64 [Hkv, d].
+    """
+    K = np.asarray(K, dtype=np.float64)
+    Q_obs = np.asarray(Q_obs, dtype=np.float64)
+    Hkv, T, d = K.shape
+    Hq = Q_obs.shape[0]
+    g = Hq // Hkv
+    out = np.zeros((Hkv, d), dtype=np.float64)
+    for h in range(Hkv):
+        Qg = Q_obs[h * g:(h + 1) * g].reshape(-1, d)
+        qn = np.sqrt((Qg * Qg).sum(axis=0))
+        kn = np.sqrt((K[h] * K[h]).sum(axis=0))
+        out[h] = qn * kn / math.sqrt(d)
+    return out
+
+
+# --------------------------------------------------------------------------
+# Continuous reverse water-filling (Thm 3.3) -- check-only, never shipped
+# --------------------------------------------------------------------------
+def water_filling(c, B):
+    """Minimise sum_u c_u 2^{-b_u} s.t. sum_u b_u <= B, b_u >= 0  (Eq. 5, Thm 3.3).
+
+    c_u = w_u sigma_u > 0.  Returns (b, theta, lam): b_u = [log2(c_u/theta)]_+,
+    theta = lam / ln 2 is the water level; the budget binds when B > 0.
+    """
+    c = np.asarray(c, dtype=np.float64)
+    assert np.all(c > 0) and B >= 0
+    order = np.argsort(-c, kind="stable")
+    cs = c[order]
+    logc = np.log2(cs)
+    csum = np.cumsum(logc)
+    U = len(c)
+    theta = None
+    for m in range(1, U + 1):
+        log_theta = (csum[m - 1] - B) / m
+        lower_ok = (m == U) or (logc[m] <= log_theta)
+        if logc[m - 1] > log_theta - 1e-15 and lower_ok:
+            theta = 2.0 ** log_theta
+            break
+    assert theta is not None
+    b = np.maximum(0.0, np.log2(c / theta))
+    return b, theta, theta * math.log(2.0)
+
+
+# --------------------------------------------------------------------------
+# Stage 2/3: discrete allocation (MCKP, Eq. 6) by Lagrangian bisection (Alg. 2)
+# --------------------------------------------------------------------------
+def hull_thresholds(tiers, eps):
+    """Lower convex hull of the points (b_k, eps(b_k)) and its slope ratios.
+
+    For a multiplier lam, argmin_b w eps(b) + lam b (Alg. 2, per-unit step) moves
+    from hull vertex k-1 to k exactly when
+        w (eps_{k-1} - eps_k) > lam (b_k - b_{k-1})  <=>  w > lam r_k,
+    r_k = (b_k - b_{k-1}) / (eps_{k-1} - eps_k), increasing along the hull.
+    Strict '>' means a tie takes the lower bit-width.  Tiers off the hull are
+    never optimal.  Returns (hull_tiers, r) with hull_tiers[0] the lowest tier and
+    r[k-1] the ratio of the edge into hull_tiers[k].
+    """
+    pts = sorted((int(b), float(np.float64(np.float32(e)))) for b, e in zip(tiers, eps))
+    hull = []
+    for p in pts:
+        while len(hull) >= 2:
+            (b0, e0), (b1, e1) = hull[-2], hull[-1]
+            cross = (b1 - b0) * (p[1] - e0) - (e1 - e0) * (p[0] - b0)
+            if cross <= 0.0:
+                hull.pop()
+            else:
+                break
+        hull.append(p)
+    # keep the descending part only: an edge that does not lower eps is never taken
+    keep = [hull[0]]
+    for p in hull[1:]:
+        if keep[-1][1] - p[1] > 0.0:
+            keep.append(p)
+        else:
+            break
+    hb = [p[0] for p in keep]
+    r = [(keep[k][0] - keep[k - 1][0]) / (keep[k - 1][1] - keep[k][1]) for k in range(1, len(keep))]
+    return hb, r
+
+
+def classify(w, lam, hull_tiers, r):
+    """Bit-width of each unit at multiplier lam: the highest hull tier k whose
+    threshold lam * r_k is strictly exceeded by (double) w_u."""
+    w64 = np.asarray(w, dtype=np.float32).astype(np.float64)
+    idx = np.zeros(w64.shape, dtype=np.int64)
+    for k, rk in enumerate(r):
+        thr = np.float64(lam) * np.float64(rk)
+        idx += (w64 > thr)
+    return np.asarray(hull_tiers, dtype=np.uint8)[idx]
+
+
+def argmin_bits(w, lam, tiers, eps):
+    """Alg. 2 per-unit step in its printed form: argmin_b w_u eps(b) + lam b
+    (lowest b on ties).  Used to pin `classify`."""
+    w64 = np.asarray(w, dtype=np.float32).astype(np.float64)
+    tiers = np.asarray(tiers, dtype=np.float64)
+    e = np.asarray([np.float64(np.float32(x)) for x in eps])
+    order = np.argsort(tiers)
+    cost = w64[:, None] * e[order][None, :] + lam * tiers[order][None, :]
+    return tiers[order][np.argmin(cost, axis=1)].astype(np.uint8)
+
+
+def budget_units(avg_bits, U):
+    """Integer budget in summed bit-widths: floor(avg_bits * U), fp64."""
+    return int(math.floor(float(np.float64(avg_bits)) * U))
+
+
+def mckp_bisect(w, avg_bits, tiers=TIERS, eps=EPS_V_LLAMA31_8B, rel_tol=np.float32(1e-2),
+                max_iters=64, return_info=False):
+    """Lagrangian bisection knapsack solver (Alg. 2; constants of App. B:
+    lam in [0, max w], relative tolerance 1e-2, at most 64 steps).
+
+    Readings taken where the listing and Eq. 6 disagree: the returned allocation
+    always satisfies sum b_u <= B (strict feasibility); the search stops at the
+    first feasible iterate within the tolerance band below the budget, and
+    otherwise returns the feasible iterate with the smallest multiplier seen.
+    Integer comparisons on the summed bits avoid dividing by a zero budget.
+
+    w: float32 [U].  avg_bits: float32 target average bits per unit.
+    """
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    U = w.shape[0]
+    hull_tiers, r = hull_thresholds(tiers, eps)
+    top, low = hull_tiers[-1], (hull_tiers[1] if len(hull_tiers) > 1 else 0)
+    B_int = budget_units(np.float32(avg_bits), U)
+    info = {"B_int": B_int, "iters": 0, "lam": None}
+    if U == 0:
+        bits = np.zeros(0, dtype=np.uint8)
+    elif B_int >= top * U:
+        bits = np.full(U, top, dtype=np.uint8)
+    elif len(hull_tiers) == 1 or B_int < low:
+        bits = np.full(U, hull_tiers[0], dtype=np.uint8)
+    else:
+        need = int(math.ceil((1.0 - float(np.float64(np.float32(rel_tol)))) * B_int))
+        lo, hi = 0.0, float(np.float64(w.max()))
+        best = None
+        for it in range(max_iters):
+            lam = (lo + hi) * 0.5
+            cand = classify(w, lam, hull_tiers, r)
+            S = int(cand.astype(np.int64).sum())
+            info["iters"] = it + 1
+            if S <= B_int:
+                best, hi = (cand, lam), lam
+                if S >= need:
+                    break
+            else:
+                lo = lam
+        if best is None:
+            bits = np.full(U, hull_tiers[0], dtype=np.uint8)
+        else:
+            bits, info["lam"] = best
+    if return_info:
+        return bits, info
+    return bits
+
+
+def mixed_budgets(avg_bits, r_k, T, n_kept, d):
+    """Stage 2/3 budgets of Alg. 1 in average-bit form.
+
+    B_head = 2 B_tok d 16 is split B_K = r_K B_head, B_V = (1 - r_K) B_head
+    (r_K = 1/2 in the paper).  With avg_bits the average over all 2 T d cache
+    scalars: V gets avg 2 (1 - r_K) avg_bits per token unit; K's budget is spread
+    over kept tokens only, k_avg = 2 r_K avg_bits T / n_kept, capped at 16.
+    """
+    a = float(np.float64(np.float32(avg_bits)))
+    rk = float(np.float64(np.float32(r_k)))
+    v_avg = 2.0 * (1.0 - rk) * a
+    if n_kept is None:
+        return v_avg, None
+    k_avg = 16.0 if n_kept == 0 else min(16.0, 2.0 * rk * a * T / n_kept)
+    return v_avg, k_avg
+
+
+# --------------------------------------------------------------------------
+# Reference quantizer (App. B "K-cache dequantization fusion": k_hat = s (code - z))
+# --------------------------------------------------------------------------
+def quantize_groups(x, bits):
+    """Asymmetric uniform quantizer on groups along the last axis.
+
+    The paper fixes the form k_hat = s (code - z) with codes in [0, 2^b - 1] and
+    leaves rounding and the scale format open.  Layout fixed by this build: fp32
+    arithmetic in exactly this order, fp16 scale s and fp16 offset m = group
+    minimum (z = -m/s), so x_hat = s*code + m:
+        mn = min x, mx = max x
+        s  = fp16_rn((mx - mn) / Q),  Q = 2^b - 1        (IEEE fp32 divide)
+        m  = fp16_rn(mn)
+        code = clamp(rint((x - m) / s), 0, Q)  (ties to even);  all 0 if s == 0
+    x: float32 [..., n] (n <= 32 for one group).  Returns (codes uint8, s fp16,
+    m fp16) with s, m of shape x.shape[:-1].
+    """
+    assert bits in (2, 4, 8)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    Q = np.float32((1 << bits) - 1)
+    mn = x.min(axis=-1)
+    mx = x.max(axis=-1)
+    with np.errstate(over="ignore"):
+        s = ((mx - mn) / Q).astype(np.float32).astype(np.float16)
+        m = mn.astype(np.float16)
+    sf = s.astype(np.float32)[..., None]
+    mf = m.astype(np.float32)[..., None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = ((x - mf).astype(np.float32) / sf).astype(np.float32)
+    t = np.rint(t)
+    t = np.minimum(np.maximum(t, np.float32(0.0)), Q)
+    t = np.where(sf == 0, np.float32(0.0), t)
+    return t.astype(np.uint8), s, m
+
+
+def dequantize_groups(codes, s, m):
+    """x_hat = s*code + m in fp64 (exact: code is an integer, s and m are fp16)."""
+    return s.astype(np.float64)[..., None] * codes.astype(np.float64) + m.astype(np.float64)[..., None]
+
+
+# --------------------------------------------------------------------------
+# Stage 4: partition and packing (token-wise mode)
+# --------------------------------------------------------------------------
+def partition(bits):
+    """Kept units grouped by tier (16, 8, 4, 2), ascending position inside a tier
+    (Alg. 1 Stage 4: sort the kept tokens by bit-width into sub-segments)."""
+    bits = np.asarray(bits, dtype=np.uint8)
+    return {b: np.nonzero(bits == b)[0].astype(np.int32) for b in PACK_ORDER}
+
+
+def pack_codes(codes, bits):
+    """Little-endian bit packing of one row: element i sits at bit i*b of the row
+    (App. B: 2-bit -> four elements per byte at offsets 0,2,4,6; 4-bit -> two per
+    byte at offsets 0,4; 8-bit -> one per byte).  codes: uint8 [..., n]."""
+    per = 8 // bits
+    n = codes.shape[-1]
+    assert n % per == 0
+    c = codes.reshape(codes.shape[:-1] + (n // per, per)).astype(np.uint32)
+    out = np.zeros(c.shape[:-1], dtype=np.uint32)
+    for j in range(per):
+        out |= c[..., j] << np.uint32(j * bits)
+    return out.astype(np.uint8)
+
+
+def unpack_codes(data, bits):
+    per = 8 // bits
+    mask = np.uint32((1 << bits) - 1)
+    d32 = data.astype(np.uint32)
+    parts = [(d32 >> np.uint32(j * bits)) & mask for j in range(per)]
+    return np.stack(parts, axis=-1).reshape(data.shape[:-1] + (data.shape[-1] * per,)).astype(np.uint8)
+
+
+def _round_up(x, a):
+    return (x + a - 1) // a * a
+
+
+def row_bytes(bits, d=128):
+    return d * bits // 8
+
+
+def meta_bytes(bits, d=128):
+    return 0 if bits == 16 else (d // GROUP) * 4
+
+
+def canonical_item(Kh, Vh, bits_tok):
+    """Canonical (layout-free) record of one item in token-wise mode: per tier the
+    kept positions and, for K and V, per-element codes plus fp16 scale / offset
+    bit patterns per group of 32 channels; tier 16 keeps the input bf16 bits.
+    In token-wise mode a token's K row and V row share its bit-width.
+    Kh, Vh: float32 [T, d] bf16-exact."""
+    Kh = _check_bf16_exact(Kh, "K")
+    Vh = _check_bf16_exact(Vh, "V")
+    T, d = Kh.shape
+    assert d % GROUP == 0
+    idx = partition(bits_tok)
+    rec = {}
+    for b in PACK_ORDER:
+        pos = idx[b]
+        ent = {"pos": pos}
+        for name, X in (("k", Kh), ("v", Vh)):
+            rows = X[pos]
+            if b == 16:
+                ent[name + "_codes"] = bf16_bits(rows).reshape(len(pos), d)
+                ent[name + "_scale"] = np.zeros((len(pos), 0), dtype=np.uint16)
+                ent[name + "_off"] = np.zeros((len(pos), 0), dtype=np.uint16)
+            else:
+                c, s, m = quantize_groups(rows.reshape(len(pos), d // GROUP, GROUP), b)
+                ent[name + "_codes"] = c.reshape(len(pos), d)
+                ent[name + "_scale"] = s.view(np.uint16)
+                ent[name + "_off"] = m.view(np.uint16)
+        rec[b] = ent
+    return rec
+
+
+def physical_segments(rec, d=128):
+    """Row-major physical form of one item's canonical record.
+
+    Per tier b with n rows, padded with zero rows to np = roundup(n, 32):
+      K data  [np][d*b/8]  bit-packed rows (tier 16: little-endian bf16)
+      K meta  [np][d/32][2] fp16 (scale, offset) per group   (absent for tier 16)
+      V data, V meta        the same for V
+    Returns {b: (kd, km, vd, vm)} as uint8 arrays.
+    """
+    out = {}
+    for b in PACK_ORDER:
+        ent = rec[b]
+        n = len(ent["pos"])
+        npad = _round_up(n, ROW_PAD)
+        segs = []
+        for name in ("k", "v"):
+            data = np.zeros((npad, row_bytes(b, d)), dtype=np.uint8)
+            if b == 16:
+                data[:n] = ent[name + "_codes"].astype("<u2").view(np.uint8).reshape(n, 2 * d)
+                meta = np.zeros((npad, 0), dtype=np.uint8)
+            else:
+                data[:n] = pack_codes(ent[name + "_codes"], b)
+                mm = np.zeros((npad, d // GROUP, 2), dtype="<u2")
+                mm[:n, :, 0] = ent[name + "_scale"]
+                mm[:n, :, 1] = ent[name + "_off"]
+                meta = mm.view(np.uint8).reshape(npad, meta_bytes(b, d))
+            segs += [data, meta]
+        out[b] = tuple(segs)
+    return out
+
+
+def build_cache_tokenwise(K_list, V_list, bits_list):
+    """Pack a ragged batch in token-wise mode.
+
+    K_list[s], V_list[s]: float32 [Hkv, T_s, d]; bits_list[s]: uint8 [Hkv, T_s].
+    Items are ordered sequence-major, head-minor.  The arena concatenates, per
+    item and per tier in the order 16, 8, 4, 2, the four segments K data, K meta,
+    V data, V meta, each starting on a 256-byte boundary (empty segments take no
+    space).  Returns a dict with
+      counts   int32 [items][4]         rows per tier (16, 8, 4, 2)
+      tier_idx int32 [sum kept]         kept positions, item-major, tier order
+      seg_off  int64 [items][4][4]      byte offset of each segment in the arena
+      arena    uint8 [bytes]
+      canon    list of canonical records (for tests)
+    """
+    items = []
+    for Ks, Vs, bs in zip(K_list, V_list, bits_list):
+        for h in range(Ks.shape[0]):
+            items.append((Ks[h], Vs[h], bs[h]))
+    d = K_list[0].shape[2]
+    n_items = len(items)
+    counts = np.zeros((n_items, 4), dtype=np.int32)
+    seg_off = np.zeros((n_items, 4, 4), dtype=np.int64)
+    chunks, tier_idx, canon = [], [], []
+    cur = 0
+    for i, (Kh, Vh, bh) in enumerate(items):
+        rec = canonical_item(Kh, Vh, bh)
+        canon.append(rec)
+        phys = physical_segments(rec, d)
+        for ti, b in enumerate(PACK_ORDER):
+            counts[i, ti] = len(rec[b]["pos"])
+            tier_idx.append(rec[b]["pos"])
+            for si, seg in enumerate(phys[b]):
+                cur = _round_up(cur, SEG_ALIGN)
+                seg_off[i, ti, si] = cur
+                flat = seg.reshape(-1)
+                if flat.size:
+                    chunks.append((cur, flat))
+                    cur += flat.size
+    total = _round_up(cur, SEG_ALIGN)
+    arena = np.zeros(total, dtype=np.uint8)
+    for off, flat in chunks:
+        arena[off:off + flat.size] = flat
+    return {
+        "counts": counts,
+        "tier_idx": np.concatenate(tier_idx).astype(np.int32) if tier_idx else np.zeros(0, np.int32),
+        "seg_off": seg_off,
+        "arena": arena,
+        "canon": canon,
+        "d": d,
+        "hkv": K_list[0].shape[0],
+        "seq_lens": [k.shape[1] for k in K_list],
+    }
+
+
+def stored_bytes(counts, d=128):
+    """Bytes a decode step must read for the given per-tier row counts (unpadded):
+    sum over tiers of n * 2 * (row bytes + metadata bytes)."""
+    counts = np.asarray(counts, dtype=np.int64).reshape(-1, 4)
+    per_row = np.array([2 * (row_bytes(b, d) + meta_bytes(b, d)) for b in PACK_ORDER], dtype=np.int64)
+    return int((counts * per_row[None, :]).sum())
+
+
+def unpack_item(cache, item):
+    """Dequantised K_hat, V_hat (float64 [n_kept, d]) and positions of one item,
+    read back from the physical arena (not from the canonical record)."""
+    d = cache["d"]
+    arena, seg_off, counts = cache["arena"], cache["seg_off"], cache["counts"]
+    ks, vs = [], []
+    for ti, b in enumerate(PACK_ORDER):
+        n = int(counts[item, ti])
+        if n == 0:
+            continue
+        mats = []
+        for which in (0, 2):
+            d_off = int(seg_off[item, ti, which])
+            raw = arena[d_off:d_off + n * row_bytes(b, d)].reshape(n, row_bytes(b, d))
+            if b == 16:
+                mats.append(bf16_from_bits(raw.view("<u2").astype(np.uint16)).astype(np.float64))
+            else:
+                m_off = int(seg_off[item, ti, which + 1])
+                meta = arena[m_off:m_off + n * meta_bytes(b, d)].view("<u2").reshape(n, d // GROUP, 2)
+                s = meta[:, :, 0].copy().view(np.float16)
+                m = meta[:, :, 1].copy().view(np.float16)
+                codes = unpack_codes(raw, b).reshape(n, d // GROUP, GROUP)
+                mats.append(dequantize_groups(codes, s, m).reshape(n, d))
+        ks.append(mats[0])
+        vs.append(mats[1])
+    if not ks:
+        return np.zeros((0, d)), np.zeros((0, d))
+    return np.concatenate(ks), np.concatenate(vs)
+
+
+# --------------------------------------------------------------------------
+# Decode (Sec. 3.3, Eq. 7): dense attention on the compressed cache (K_hat, V_hat)
+# --------------------------------------------------------------------------
+def attention_rows(q, Kh, Vh):
+    """softmax(q K^T / sqrt(d)) V for each row of q over the given rows; fp64.
+    q: [g, d]; Kh, Vh: [n, d].  Returns (out [g, d], lse [g]); n == 0 gives
+    out = 0, lse = -inf."""
+    q = np.asarray(q, dtype=np.float64)
+    g, d = q.shape
+    if Kh.shape[0] == 0:
+        return np.zeros((g, d)), np.full(g, -np.inf)
+    z = q @ Kh.T / math.sqrt(d)
+    zmax = z.max(axis=1, keepdims=True)
+    e = np.exp(z - zmax)
+    l = e.sum(axis=1, keepdims=True)
+    return (e / l) @ Vh, (zmax + np.log(l))[:, 0]
+
+
+def decode(cache, q):
+    """One decode step over a packed token-wise cache.  q: [batch, Hq, d] (bf16
+    exact).  Every retained token enters with its dequantised K row and V row;
+    evicted tokens (tier 0) are absent (Eq. 7 without the new-token zone).
+    Returns out float64 [batch, Hq, d], lse float64 [batch, Hq]."""
+    q = np.asarray(q, dtype=np.float64)
+    batch, Hq, d = q.shape
+    hkv = cache["hkv"]
+    g = Hq // hkv
+    out = np.zeros((batch, Hq, d))
+    lse = np.zeros((batch, Hq))
+    for s in range(batch):
+        for h in range(hkv):
+            Kh, Vh = unpack_item(cache, s * hkv + h)
+            o, l = attention_rows(q[s, h * g:(h + 1) * g], Kh, Vh)
+            out[s, h * g:(h + 1) * g] = o
+            lse[s, h * g:(h + 1) * g] = l
+    return out, lse
+
+
+def decode_dense(K_list, V_list, q):
+    """Uncompressed decode: softmax(q K^T / sqrt(d)) V over all T tokens (Sec. 3)."""
+    q = np.asarray(q, dtype=np.float64)
+    batch, Hq, d = q.shape
+    out = np.zeros((batch, Hq, d))
+    lse = np.zeros((batch, Hq))
+    for s in range(batch):
+        Ks = np.asarray(K_list[s], dtype=np.float64)
+        Vs = np.asarray(V_list[s], dtype=np.float64)
+        hkv = Ks.shape[0]
+        g = Hq // hkv
+        for h in range(hkv):
+            o, l = attention_rows(q[s, h * g:(h + 1) * g], Ks[h], Vs[h])
+            out[s, h * g:(h + 1) * g] = o
+            lse[s, h * g:(h + 1) * g] = l
+    return out, lse
+
+
+# --------------------------------------------------------------------------
+# Whole compression pass, token-wise mode (Alg. 1 with K sharing the token map)
+# --------------------------------------------------------------------------
+def compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B,
+                       pool_kernel=5, causal=True, rel_tol=np.float32(1e-2), max_iters=64,
+                       weights_override=None):
+    """Weights -> pooling -> per-item bisection -> pack.  `weights_override`, if
+    given, is a list of float32 [Hkv, T_s] arrays used instead of the computed
+    weights (the bit-exact comparisons feed both sides identical fp32 weights)."""
+    bits_list, w_list = [], []
+    for s, (Ks, Qs) in enumerate(zip(K_list, Qobs_list)):
+        if weights_override is not None:
+            w = np.asarray(weights_override[s], dtype=np.float32)
+        else:
+            w = avg_pool(token_weights(Ks, Qs, causal), pool_kernel).astype(np.float32)
+        w_list.append(w)
+        bits = np.stack([mckp_bisect(w[h], budgets[s], tiers, eps, rel_tol, max_iters)
+                         for h in range(w.shape[0])])
+        bits_list.append(bits)
+    cache = build_cache_tokenwise(K_list, V_list, bits_list)
+    cache["bits"] = bits_list
+    cache["weights"] = w_list
+    return cache

@@ -1,0 +1,614 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Each test checks an oracle function against something other than its own
+formula: brute force on tiny inputs, closed forms, library routines reached by a
+special case, values printed in the paper (tests/golden/), and invariants.
+None of these needs a GPU.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import rdkv_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bf16_round(x):
+    """Round float32 to the nearest bf16 (ties to even), returned as float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
+def rand_bf16(rng, shape, scale=1.0):
+    return bf16_round(rng.standard_normal(shape).astype(np.float32) * np.float32(scale))
+
+
+# ----------------------------------------------------------------------------
+# O1 token weights (Prop. 3.1, Eq. 2, Alg. 1 Stage 1)
+# ----------------------------------------------------------------------------
+def _softmax_list(z):
+    m = max(z)
+    e = [math.exp(v - m) for v in z]
+    s = sum(e)
+    return [v / s for v in e]
+
+
+def test_token_weights_equal_summed_tv_distance_bruteforce():
+    # Prop. 3.1: evicting token t changes query tau's attention by TV distance a_{tau,t};
+    # w_t is that distance summed over queries.  Pure-Python loops, renormalised softmax.
+    rng = np.random.default_rng(1)
+    Hkv, g, T, Sw, d = 2, 2, 11, 3, 8
+    K = rand_bf16(rng, (Hkv, T, d))
+    Q = rand_bf16(rng, (Hkv * g, Sw, d))
+    w = O.token_weights(K, Q, causal=True)
+    for h in range(Hkv):
+        for t in range(T):
+            tv_sum = 0.0
+            for j in range(g):
+                for i in range(Sw):
+                    last = T - Sw + i                      # causal: keys 0..last
+                    z = [sum(float(Q[h * g + j, i, c]) * float(K[h, u, c]) for c in range(d)) / math.sqrt(d)
+                         for u in range(last + 1)]
+                    a = _softmax_list(z)
+                    if t > last:
+                        continue                            # token not visible: no change
+                    if last == 0:
+                        continue
+                    a_hat = [0.0 if u == t else a[u] / (1.0 - a[t]) for u in range(last + 1)]
+                    tv_sum += 0.5 * sum(abs(x - y) for x, y in zip(a, a_hat))
+            assert w[h, t] == pytest.approx(tv_sum, rel=1e-10, abs=1e-12)
+
+
+def test_token_weights_mass_and_causal_edge():
+    rng = np.random.default_rng(2)
+    Hkv, g, T, Sw, d = 2, 4, 300, 32, 16
+    K = rand_bf16(rng, (Hkv, T, d))
+    Q = rand_bf16(rng, (Hkv * g, Sw, d))
+    w = O.token_weights(K, Q, causal=True)
+    # every softmax row sums to one: total mass = number of rows
+    np.testing.assert_allclose(w.sum(axis=1), g * Sw, rtol=1e-12)
+    # the last key is visible to the last window row only
+    for h in range(Hkv):
+        exp = 0.0
+        for j in range(g):
+            z = K[h].astype(np.float64) @ Q[h * g + j, Sw - 1].astype(np.float64) / math.sqrt(d)
+            exp += _softmax_list(list(z))[T - 1]
+        assert w[h, T - 1] == pytest.approx(exp, rel=1e-10)
+    # without the mask every row sees all keys: more mass lands on the last keys
+    w_nc = O.token_weights(K, Q, causal=False)
+    np.testing.assert_allclose(w_nc.sum(axis=1), g * Sw, rtol=1e-12)
+    assert not np.allclose(w_nc[:, -Sw:], w[:, -Sw:])
+    # keys before the window are unaffected by the mask only through normalisation:
+    # with one window row (Sw = 1) the mask is void
+    w1 = O.token_weights(K, Q[:, -1:, :], causal=True)
+    w1n = O.token_weights(K, Q[:, -1:, :], causal=False)
+    np.testing.assert_allclose(w1, w1n, rtol=1e-13)
+
+
+def test_token_weights_uniform_when_keys_identical():
+    # identical keys -> uniform attention over the visible prefix (closed form)
+    Hkv, g, T, Sw, d = 1, 1, 9, 2, 4
+    K = np.ones((Hkv, T, d), dtype=np.float32)
+    Q = rand_bf16(np.random.default_rng(3), (1, Sw, d))
+    w = O.token_weights(K, Q, causal=True)
+    exp = np.zeros(T)
+    for i in range(Sw):
+        last = T - Sw + i
+        exp[:last + 1] += 1.0 / (last + 1)
+    np.testing.assert_allclose(w[0], exp, rtol=1e-12)
+
+
+def test_avg_pool_against_convolution_and_mass():
+    rng = np.random.default_rng(4)
+    w = rng.random((3, 50))
+    p = O.avg_pool(w, 5)
+    for r in range(3):
+        np.testing.assert_allclose(p[r], np.convolve(w[r], np.ones(5) / 5.0, mode="same"), rtol=1e-12)
+    # a unit impulse away from the edges spreads to five taps of 1/5 and keeps its mass
+    e = np.zeros(20)
+    e[10] = 1.0
+    pe = O.avg_pool(e, 5)
+    assert pe[8:13].tolist() == [0.2] * 5 and pe.sum() == pytest.approx(1.0)
+    # at the edge the zero padding loses mass (divisor stays 5)
+    e0 = np.zeros(20)
+    e0[0] = 1.0
+    assert O.avg_pool(e0, 5).sum() == pytest.approx(0.6)
+    np.testing.assert_array_equal(O.avg_pool(w, 1), w)
+
+
+# ----------------------------------------------------------------------------
+# O2 channel weights (Prop. 3.2, Eq. 3-4)
+# ----------------------------------------------------------------------------
+def test_channel_weight_is_spectral_and_frobenius_norm_of_logit_deviation():
+    rng = np.random.default_rng(5)
+    Hkv, g, T, Sw, d = 2, 2, 40, 5, 8
+    K = rand_bf16(rng, (Hkv, T, d))
+    Q = rand_bf16(rng, (Hkv * g, Sw, d))
+    wc = O.channel_weights(K, Q)
+    for h in range(Hkv):
+        Qg = Q[h * g:(h + 1) * g].reshape(-1, d).astype(np.float64)
+        Kh = K[h].astype(np.float64)
+        Z = Qg @ Kh.T / math.sqrt(d)
+        for c in range(d):
+            K0 = Kh.copy()
+            K0[:, c] = 0.0
+            dZ = Qg @ K0.T / math.sqrt(d) - Z                 # zeroing channel c (Eq. 3)
+            sv = np.linalg.svd(dZ, compute_uv=False)
+            assert sv[0] == pytest.approx(wc[h, c], rel=1e-9)
+            assert np.linalg.norm(dZ, "fro") == pytest.approx(wc[h, c], rel=1e-9)   # Remark after Prop. 3.2
+            assert sv[1] < 1e-9 * max(sv[0], 1e-30) + 1e-12   # rank one
+
+
+# ----------------------------------------------------------------------------
+# O3 continuous reverse water-filling (Thm 3.3)
+# ----------------------------------------------------------------------------
+def test_water_filling_worked_example():
+    # c = (8, 2, 0.5), B = 4: water level theta = 1 -> b = (3, 1, 0), D = c 2^-b = (1, 1, 0.5)
+    b, theta, lam = O.water_filling([8.0, 2.0, 0.5], 4.0)
+    assert theta == pytest.approx(1.0)
+    np.testing.assert_allclose(b, [3.0, 1.0, 0.0], atol=1e-12)
+    np.testing.assert_allclose(np.array([8.0, 2.0, 0.5]) * 2.0 ** (-b), [1.0, 1.0, 0.5])
+    assert lam == pytest.approx(math.log(2.0))
+
+
+def test_water_filling_matches_classical_reverse_water_filling():
+    # Classical form (Cover & Thomas): R_i = max(0, 1/2 log2(sigma_i^2 / theta_c)),
+    # D_i = min(theta_c, sigma_i^2) with sigma_i = c_u and theta_c = theta^2.
+    rng = np.random.default_rng(6)
+    c = np.exp(rng.normal(0, 2.0, 200))
+    B = 300.0
+    b, theta, lam = O.water_filling(c, B)
+    assert b.sum() == pytest.approx(B, rel=1e-10)                  # budget binds
+    D = c * 2.0 ** (-b)
+    np.testing.assert_allclose(D, np.minimum(theta, c), rtol=1e-10)
+    R = np.maximum(0.0, 0.5 * np.log2(c ** 2 / theta ** 2))
+    np.testing.assert_allclose(b, R, atol=1e-10)
+    # phase transition at c_u = lam / ln 2
+    assert np.all((b > 0) == (c > lam / math.log(2.0) * (1 + 1e-12)))
+    # KKT/optimality: moving a little rate between any two units cannot lower the objective
+    obj = D.sum()
+    for _ in range(200):
+        i, j = rng.integers(0, len(c), 2)
+        if i == j:
+            continue
+        b2 = b.copy()
+        delta = min(0.05, b2[i])
+        b2[i] -= delta
+        b2[j] += delta
+        assert (c * 2.0 ** (-b2)).sum() >= obj - 1e-12
+
+
+# ----------------------------------------------------------------------------
+# O4 discrete allocation (Eq. 6, Alg. 2, Prop. A.3)
+# ----------------------------------------------------------------------------
+def _read_fig2():
+    rows = {}
+    with open(os.path.join(GOLDEN, "fig2_thresholds.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            p = line.split()
+            rows[p[0]] = ([float(x) for x in p[1:5]], [float(x) for x in p[5:13]], [int(x) for x in p[13:21]])
+    return rows
+
+
+def test_fig2_four_thresholds_five_zones():
+    # The figure's thresholds (16, 8, 4, 2 from the top) and bar heights: classification
+    # with thresholds lam * r_k must reproduce the printed zones.
+    for kind, (thr, scores, bits) in _read_fig2().items():
+        r = list(reversed(thr))                       # ascending: thresholds into tiers 2, 4, 8, 16
+        got = O.classify(np.array(scores, dtype=np.float32), 1.0, [0, 2, 4, 8, 16], r)
+        assert got.tolist() == bits, kind
+    tok_bits = _read_fig2()["token"][2]
+    assert [i + 1 for i, b in enumerate(tok_bits) if b > 0] == [1, 2, 4, 5, 7, 8]   # T_kept in the caption
+
+
+def _read_table9():
+    tab = {}
+    with open(os.path.join(GOLDEN, "table9_eps.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            p = line.split()
+            tab[p[0]] = ([1.0] + [float(x) for x in p[1:4]] + [0.0], [1.0] + [float(x) for x in p[4:7]] + [0.0])
+    return tab
+
+
+def test_default_tables_are_the_printed_llama31_row_and_convex():
+    tab = _read_table9()
+    ek, ev = tab["LLaMA-3.1-8B"]
+    assert list(O.EPS_K_LLAMA31_8B) == ek and list(O.EPS_V_LLAMA31_8B) == ev
+    for name, (ek, ev) in tab.items():
+        for e in (ek, ev):
+            hb, r = O.hull_thresholds(O.TIERS, e)
+            assert hb == [0, 2, 4, 8, 16], name          # every printed table is convex: all tiers on the hull
+            assert all(r[i] < r[i + 1] for i in range(3))
+
+
+def test_hull_drops_dominated_tiers():
+    # a tier above the chord between its neighbours is never optimal
+    hb, r = O.hull_thresholds([0, 2, 4, 8, 16], [1.0, 0.9, 0.1, 0.05, 0.0])
+    assert hb == [0, 4, 8, 16]
+    assert r[0] == pytest.approx(4 / np.float64(np.float32(1.0) - np.float32(0.1)), rel=1e-7)
+    # and then argmin never selects it
+    rng = np.random.default_rng(7)
+    w = rng.random(500).astype(np.float32) * 10
+    for lam in (0.01, 0.1, 0.5, 2.0):
+        assert 2 not in O.argmin_bits(w, lam, [0, 2, 4, 8, 16], [1.0, 0.9, 0.1, 0.05, 0.0])
+
+
+@pytest.mark.parametrize("eps", [O.EPS_V_LLAMA31_8B, O.EPS_K_LLAMA31_8B, O.EPS_BENNETT])
+def test_threshold_form_equals_printed_argmin_form(eps):
+    rng = np.random.default_rng(8)
+    w = np.exp(rng.normal(0, 3, 4000)).astype(np.float32)
+    hb, r = O.hull_thresholds(O.TIERS, eps)
+    for lam in (1e-4, 1e-2, 0.3, 1.0, 7.0, 200.0):
+        a = O.classify(w, lam, hb, r)
+        b = O.argmin_bits(w, lam, O.TIERS, eps)
+        # away from exact ties the two forms agree
+        near_tie = np.zeros(len(w), dtype=bool)
+        for rk in r:
+            near_tie |= np.abs(w.astype(np.float64) - lam * rk) <= 1e-9 * lam * rk
+        assert np.array_equal(a[~near_tie], b[~near_tie])
+
+
+def test_mckp_bruteforce_optimality_and_weak_duality():
+    # tiny instances: enumerate all 5^U allocations (Eq. 6) and check
+    #   g(lam) <= OPT(B) <= primal(returned)                       (Prop. A.3)
+    #   returned allocation is optimal for the bits it actually uses (Lagrangian optimality)
+    rng = np.random.default_rng(9)
+    tiers = list(O.TIERS)
+    for trial in range(25):
+        U = int(rng.integers(3, 8))
+        w = np.exp(rng.normal(0, 1.5, U)).astype(np.float32)
+        eps = [O.EPS_V_LLAMA31_8B, O.EPS_BENNETT][trial % 2]
+        e = np.array([np.float64(np.float32(x)) for x in eps])
+        avg = np.float32(rng.choice([0.7, 1.5, 3.0, 6.0, 11.0]))
+        bits, info = O.mckp_bisect(w, avg, tiers, eps, return_info=True)
+        B = info["B_int"]
+        S = int(bits.sum())
+        assert S <= B
+        cost = lambda alloc: sum(float(w[u]) * e[tiers.index(int(alloc[u]))] for u in range(U))
+        best_B, best_S = math.inf, math.inf
+        for alloc in itertools.product(tiers, repeat=U):
+            s = sum(alloc)
+            c = cost(alloc)
+            if s <= B:
+                best_B = min(best_B, c)
+            if s <= S:
+                best_S = min(best_S, c)
+        primal = cost(bits)
+        assert primal >= best_B - 1e-12
+        assert primal == pytest.approx(best_S, rel=1e-12, abs=1e-15)
+        if info["lam"] is not None:
+            lam = info["lam"]
+            g_lam = sum(min(float(w[u]) * e[k] + lam * tiers[k] for k in range(5)) for u in range(U)) - lam * B
+            assert g_lam <= best_B + 1e-12
+
+
+def test_mckp_feasible_monotone_and_within_band_on_smooth_weights():
+    rng = np.random.default_rng(10)
+    U = 20000
+    w = np.exp(rng.normal(0, 2.0, U)).astype(np.float32)
+    prev = None
+    for avg in (0.4, 1.0, 2.0, 4.0, 8.0, 12.0):
+        bits, info = O.mckp_bisect(w, np.float32(avg), return_info=True)
+        S = int(bits.astype(np.int64).sum())
+        assert set(np.unique(bits)) <= set(O.TIERS)
+        assert S <= info["B_int"]
+        assert S >= math.ceil(0.99 * info["B_int"]) - 16            # smooth weights: the 1 % band is reached
+        assert info["iters"] <= 64
+        # a unit's bit-width is a non-decreasing function of its weight
+        order = np.argsort(w, kind="stable")
+        assert np.all(np.diff(bits[order].astype(int)) >= 0)
+        if prev is not None:
+            assert np.all(bits >= prev)                             # a larger budget takes bits from no unit
+        prev = bits
+
+
+def test_mckp_shortcuts_and_degenerate_inputs():
+    w = np.array([3.0, 1.0, 0.0, 2.0], dtype=np.float32)
+    assert O.mckp_bisect(w, np.float32(16.0)).tolist() == [16] * 4      # budget covers everything
+    assert O.mckp_bisect(w, np.float32(20.0)).tolist() == [16] * 4
+    assert O.mckp_bisect(w, np.float32(0.0)).tolist() == [0] * 4        # zero budget: no division by zero
+    assert O.mckp_bisect(w, np.float32(0.3)).tolist() == [0] * 4        # floor(1.2) = 1 < 2 bits
+    assert O.mckp_bisect(np.zeros(0, np.float32), np.float32(2.0)).shape == (0,)
+    # equal weights: units move together, so only all-or-nothing is feasible
+    we = np.ones(10, dtype=np.float32)
+    b = O.mckp_bisect(we, np.float32(3.0))
+    assert len(set(b.tolist())) == 1 and int(b.sum()) <= 30
+    # all-zero weights: nothing is worth a bit
+    assert O.mckp_bisect(np.zeros(5, np.float32), np.float32(4.0)).tolist() == [0] * 5
+    # budget for exactly one 2-bit unit goes to the heaviest unit
+    assert O.mckp_bisect(w, np.float32(0.5)).tolist() == [2, 0, 0, 0]
+
+
+def test_mckp_on_fine_grid_approaches_water_filling():
+    # With tiers {0,1,...,16} and eps(b) = 2^-b the discrete problem is Eq. 5 on a grid:
+    # the allocation stays within about one bit of Thm 3.3's closed form.
+    rng = np.random.default_rng(11)
+    U = 5000
+    w = np.exp(rng.normal(0, 2.0, U)).astype(np.float32)
+    tiers = list(range(17))
+    eps = [2.0 ** (-b) for b in tiers]
+    avg = np.float32(3.0)
+    bits = O.mckp_bisect(w, avg, tiers, eps).astype(np.float64)
+    b_cont, theta, lam = O.water_filling(w.astype(np.float64), float(bits.sum()))
+    b_cont = np.minimum(b_cont, 16.0)
+    assert np.max(np.abs(bits - b_cont)) <= 1.25
+    assert abs(np.mean(bits - b_cont)) < 0.05
+
+
+def test_mixed_budgets_match_alg1_bookkeeping():
+    # Alg. 1: B_head = 2 B_tok d 16; B_V = B_K = B_head / 2; Bbar_V = B_V / d per token-unit sum;
+    # k_avg = B_K / (n_kept d).
+    d, T, B_tok = 128, 1000, 64
+    B_head = 2 * B_tok * d * 16
+    avg_bits = B_head / (2 * T * d)                  # average over all K and V scalars
+    n_kept = 300
+    v_avg, k_avg = O.mixed_budgets(np.float32(avg_bits), np.float32(0.5), T, n_kept, d)
+    assert v_avg * T == pytest.approx((B_head / 2) / d, rel=1e-6)
+    assert k_avg == pytest.approx((B_head / 2) / (n_kept * d), rel=1e-6)
+    assert O.mixed_budgets(np.float32(8.0), np.float32(0.5), T, 10, d)[1] == 16.0   # capped at full precision
+
+
+# ----------------------------------------------------------------------------
+# O5 reference quantizer
+# ----------------------------------------------------------------------------
+def test_quantizer_hand_worked_groups_and_ties_to_even():
+    # 2-bit, range [0, 3]: s = 1, m = 0, codes are the values
+    c, s, m = O.quantize_groups(np.array([[0.0, 1.0, 2.0, 3.0]], np.float32), 2)
+    assert c.tolist() == [[0, 1, 2, 3]] and float(s[0]) == 1.0 and float(m[0]) == 0.0
+    # ties go to the even code: (x - m)/s = 0.5 -> 0, 1.5 -> 2, 2.5 -> 2
+    c, s, m = O.quantize_groups(np.array([[-1.5, -1.0, 0.0, 1.0, 1.5]], np.float32), 2)
+    assert float(s[0]) == 1.0 and float(m[0]) == -1.5
+    assert c.tolist() == [[0, 0, 2, 2, 3]]
+    # 4-bit: 16 levels over [-7.5, 7.5] -> s = 1, code = x + 7.5 rounded to even on ties
+    x = np.array([[-7.5, -7.0, 0.0, 0.5, 7.5]], np.float32)
+    c, s, m = O.quantize_groups(x, 4)
+    assert float(s[0]) == 1.0 and c.tolist() == [[0, 0, 8, 8, 15]]
+    # 8-bit: 256 levels over [0, 255]
+    x = np.arange(0, 256, 17, dtype=np.float32)[None, :]
+    c, s, m = O.quantize_groups(x, 8)
+    assert float(s[0]) == 1.0 and c[0].tolist() == list(range(0, 256, 17))
+    # constant group: zero scale, exact reconstruction
+    c, s, m = O.quantize_groups(np.full((1, 32), 2.5, np.float32), 4)
+    assert float(s[0]) == 0.0 and not c.any()
+    assert np.all(O.dequantize_groups(c, s, m) == 2.5)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_quantizer_error_bound_and_ranges(bits):
+    rng = np.random.default_rng(12 + bits)
+    x = rand_bf16(rng, (2000, 4, 32))
+    x[:, 1, 5] *= 10.0                                  # outlier channel inside a group
+    x = bf16_round(x)
+    c, s, m = O.quantize_groups(x, bits)
+    Q = (1 << bits) - 1
+    assert c.min() >= 0 and c.max() <= Q
+    assert np.all(c.max(axis=-1) == Q) and np.all(c.min(axis=-1) == 0)      # both ends of the range are hit
+    # bf16 inputs are exact in fp16's normal range: the offset is the group minimum itself
+    np.testing.assert_array_equal(m.astype(np.float32), x.min(axis=-1))
+    xh = O.dequantize_groups(c, s, m)
+    err = np.abs(xh - x.astype(np.float64))
+    bound = 0.5 * s.astype(np.float64)[..., None] * (1 + 2.0 ** -10)
+    assert np.all(err <= bound)
+    # scale is the fp16 rounding of range / Q
+    rng_over_q = (x.max(-1).astype(np.float64) - x.min(-1).astype(np.float64)) / Q
+    assert np.all(np.abs(s.astype(np.float64) - rng_over_q) <= rng_over_q * 2.0 ** -11 + 1e-12)
+
+
+def test_quantizer_uniform_data_has_bennett_mse():
+    # Lemma A.1: a uniform quantizer of cell width Delta has per-coordinate MSE Delta^2 / 12.
+    rng = np.random.default_rng(15)
+    x = bf16_round(rng.uniform(-4, 4, (4000, 32)).astype(np.float32))
+    for bits in (4, 8):
+        c, s, m = O.quantize_groups(x, bits)
+        xh = O.dequantize_groups(c, s, m)
+        mse = np.mean((xh - x) ** 2)
+        delta2 = np.mean(s.astype(np.float64) ** 2)
+        # bf16 inputs at 8 bits sit on a grid comparable to the cell width, so allow a wide band there
+        tol = 0.08 if bits == 4 else 0.35
+        assert mse == pytest.approx(delta2 / 12.0, rel=tol)
+
+
+# ----------------------------------------------------------------------------
+# O6 packing
+# ----------------------------------------------------------------------------
+def test_pack_bit_positions_as_printed():
+    # App. B: 2-bit -> four elements per byte at offsets 0,2,4,6; 4-bit -> two at offsets 0,4
+    assert O.pack_codes(np.array([[1, 2, 3, 0]], np.uint8), 2).tolist() == [[1 | (2 << 2) | (3 << 4)]]
+    assert O.pack_codes(np.array([[0, 0, 0, 3]], np.uint8), 2).tolist() == [[0xC0]]
+    assert O.pack_codes(np.array([[0xA, 0x5]], np.uint8), 4).tolist() == [[0x5A]]
+    assert O.pack_codes(np.array([[7, 200]], np.uint8), 8).tolist() == [[7, 200]]
+    rng = np.random.default_rng(16)
+    for bits in (2, 4, 8):
+        codes = rng.integers(0, 1 << bits, (37, 128)).astype(np.uint8)
+        data = O.pack_codes(codes, bits)
+        assert data.shape == (37, 128 * bits // 8)
+        np.testing.assert_array_equal(O.unpack_codes(data, bits), codes)
+
+
+def _small_case(rng, Hkv=2, T=150, d=128, batch=1):
+    Ks = [rand_bf16(rng, (Hkv, T + 7 * s, d)) for s in range(batch)]
+    Vs = [rand_bf16(rng, (Hkv, T + 7 * s, d)) for s in range(batch)]
+    for K in Ks:
+        K[:, :, 3] = bf16_round(K[:, :, 3] * 10)
+    return Ks, Vs
+
+
+def test_cache_layout_counts_offsets_and_bytes():
+    rng = np.random.default_rng(17)
+    Ks, Vs = _small_case(rng, batch=2)
+    bits = [rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=K.shape[:2], p=[.4, .25, .2, .1, .05]) for K in Ks]
+    cache = O.build_cache_tokenwise(Ks, Vs, bits)
+    n_items = 4
+    assert cache["counts"].shape == (n_items, 4)
+    it = 0
+    pos_cursor = 0
+    for s in range(2):
+        for h in range(2):
+            for ti, b in enumerate(O.PACK_ORDER):
+                pos = np.nonzero(bits[s][h] == b)[0]
+                n = len(pos)
+                assert cache["counts"][it, ti] == n
+                np.testing.assert_array_equal(cache["tier_idx"][pos_cursor:pos_cursor + n], pos)   # ascending, stable
+                pos_cursor += n
+                assert np.all(cache["seg_off"][it, ti] % 256 == 0)
+            it += 1
+    assert pos_cursor == len(cache["tier_idx"])
+    # closed-form stored bytes: 2 * (16 b + 16) per row for b in {2,4,8}, 512 for b = 16
+    c = cache["counts"].sum(axis=0)
+    assert O.stored_bytes(cache["counts"]) == c[0] * 512 + c[1] * 2 * 144 + c[2] * 2 * 80 + c[3] * 2 * 48
+    # segments do not overlap and the arena is just large enough
+    spans = []
+    for i in range(n_items):
+        for ti, b in enumerate(O.PACK_ORDER):
+            npad = (int(cache["counts"][i, ti]) + 31) // 32 * 32
+            sizes = [npad * O.row_bytes(b), npad * O.meta_bytes(b)] * 2
+            for si in range(4):
+                if sizes[si]:
+                    spans.append((int(cache["seg_off"][i, ti, si]), sizes[si]))
+    spans.sort()
+    for (o0, s0), (o1, _) in zip(spans, spans[1:]):
+        assert o0 + s0 <= o1
+    assert spans[-1][0] + spans[-1][1] <= len(cache["arena"]) < spans[-1][0] + spans[-1][1] + 256
+
+
+def test_physical_roundtrip_equals_canonical_dequant():
+    rng = np.random.default_rng(18)
+    Ks, Vs = _small_case(rng)
+    bits = [rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=Ks[0].shape[:2])]
+    cache = O.build_cache_tokenwise(Ks, Vs, bits)
+    for item in range(2):
+        Kh, Vh = O.unpack_item(cache, item)
+        rec = cache["canon"][item]
+        rows_k, rows_v = [], []
+        for b in O.PACK_ORDER:
+            ent = rec[b]
+            n = len(ent["pos"])
+            if b == 16:
+                rows_k.append(Ks[0][item][ent["pos"]].astype(np.float64))
+                rows_v.append(Vs[0][item][ent["pos"]].astype(np.float64))
+            else:
+                for name, dst in (("k", rows_k), ("v", rows_v)):
+                    s = ent[name + "_scale"].view(np.float16).astype(np.float64)
+                    m = ent[name + "_off"].view(np.float16).astype(np.float64)
+                    codes = ent[name + "_codes"].reshape(n, 4, 32).astype(np.float64)
+                    dst.append((codes * s[:, :, None] + m[:, :, None]).reshape(n, 128))
+        np.testing.assert_array_equal(Kh, np.concatenate(rows_k))
+        np.testing.assert_array_equal(Vh, np.concatenate(rows_v))
+
+
+# ----------------------------------------------------------------------------
+# O7 decode (Sec. 3.3, Eq. 7)
+# ----------------------------------------------------------------------------
+def _bruteforce_attention(q, K, V):
+    """softmax(q K^T / sqrt(d)) V with Python loops."""
+    n, d = K.shape
+    z = [sum(float(q[c]) * float(K[t, c]) for c in range(d)) / math.sqrt(d) for t in range(n)]
+    a = _softmax_list(z)
+    return [sum(a[t] * float(V[t, c]) for t in range(n)) for c in range(d)], max(z) + math.log(sum(math.exp(v - max(z)) for v in z))
+
+
+def test_all_16_bit_cache_reproduces_bruteforce_attention():
+    rng = np.random.default_rng(19)
+    Hkv, g, T, d = 2, 2, 70, 128
+    Ks, Vs = [rand_bf16(rng, (Hkv, T, d))], [rand_bf16(rng, (Hkv, T, d))]
+    q = rand_bf16(rng, (1, Hkv * g, d))
+    cache = O.build_cache_tokenwise(Ks, Vs, [np.full((Hkv, T), 16, np.uint8)])
+    out, lse = O.decode(cache, q)
+    for j in range(Hkv * g):
+        o, l = _bruteforce_attention(q[0, j], Ks[0][j // g], Vs[0][j // g])
+        np.testing.assert_allclose(out[0, j], o, rtol=1e-11, atol=1e-13)
+        assert lse[0, j] == pytest.approx(l, rel=1e-12)
+    out_d, lse_d = O.decode_dense(Ks, Vs, q)
+    np.testing.assert_allclose(out, out_d, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lse, lse_d, rtol=1e-12)
+
+
+def test_zero_bit_units_are_exactly_eviction():
+    rng = np.random.default_rng(20)
+    Hkv, g, T, d = 1, 4, 90, 128
+    Ks, Vs = [rand_bf16(rng, (Hkv, T, d))], [rand_bf16(rng, (Hkv, T, d))]
+    q = rand_bf16(rng, (1, g, d))
+    bits = np.where(rng.random((Hkv, T)) < 0.6, 0, 16).astype(np.uint8)
+    cache = O.build_cache_tokenwise(Ks, Vs, [bits])
+    out, lse = O.decode(cache, q)
+    keep = np.nonzero(bits[0])[0]
+    for j in range(g):
+        o, l = _bruteforce_attention(q[0, j], Ks[0][0][keep], Vs[0][0][keep])
+        np.testing.assert_allclose(out[0, j], o, rtol=1e-11, atol=1e-13)
+        assert lse[0, j] == pytest.approx(l, rel=1e-12)
+    # a head whose tokens are all evicted: zero output, lse = -inf
+    cache0 = O.build_cache_tokenwise(Ks, Vs, [np.zeros((Hkv, T), np.uint8)])
+    o0, l0 = O.decode(cache0, q)
+    assert not o0.any() and np.all(np.isneginf(l0))
+
+
+def test_decode_over_quantized_tiers_equals_attention_over_dequantized_rows_any_order():
+    # Eq. 7: the zone sums are dense attention over (K_hat, V_hat); softmax attention does not
+    # depend on the order of the rows, on a shift of the logits, or on how the rows are split
+    # (LSE merge of partial results).
+    rng = np.random.default_rng(21)
+    Hkv, g, T, d = 1, 2, 200, 128
+    Ks, Vs = _small_case(rng, Hkv=Hkv, T=T)
+    q = rand_bf16(rng, (1, g, d))
+    bits = rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(Hkv, T))
+    cache = O.build_cache_tokenwise(Ks, Vs, [bits])
+    out, lse = O.decode(cache, q)
+    Kh, Vh = O.unpack_item(cache, 0)
+    perm = rng.permutation(len(Kh))
+    o_p, l_p = O.attention_rows(q[0], Kh[perm], Vh[perm])
+    np.testing.assert_allclose(out[0], o_p, rtol=1e-11, atol=1e-13)
+    # split into three parts and merge with log-sum-exp weights
+    parts = np.array_split(np.arange(len(Kh)), 3)
+    os_, ls_ = zip(*[O.attention_rows(q[0], Kh[p], Vh[p]) for p in parts])
+    ls_ = np.stack(ls_)
+    lmax = ls_.max(axis=0)
+    wts = np.exp(ls_ - lmax)
+    merged = sum(wts[i][:, None] * os_[i] for i in range(3)) / wts.sum(axis=0)[:, None]
+    np.testing.assert_allclose(merged, out[0], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(lmax + np.log(wts.sum(axis=0)), lse[0], rtol=1e-12)
+    # the quantised rows differ from the originals by at most scale/2 per element, so the result is close
+    # to (but not equal to) attention over the original kept rows
+    bits8 = np.where(bits == 0, 0, np.where(bits == 16, 16, 8)).astype(np.uint8)
+    out8, _ = O.decode(O.build_cache_tokenwise(Ks, Vs, [bits8]), q)
+    keep = np.concatenate([np.nonzero(bits8[0] == b)[0] for b in O.PACK_ORDER])
+    o_ref, _ = O.attention_rows(q[0], Ks[0][0][keep].astype(np.float64), Vs[0][0][keep].astype(np.float64))
+    assert 0 < np.max(np.abs(o_ref - out8[0])) < 0.02
+
+
+def test_k_dequant_fusion_identity():
+    # App. B: q . k_hat = sum_c (s q_c) code_c - sum_c s z q_c; with offsets m = -s z per group
+    # this reads sum_g s_g (q_g . code_g) + sum_g m_g sum(q_g).
+    rng = np.random.default_rng(22)
+    x = rand_bf16(rng, (50, 4, 32))
+    q = rand_bf16(rng, (4, 32)).astype(np.float64)
+    for bits in (2, 4, 8):
+        c, s, m = O.quantize_groups(x, bits)
+        xh = O.dequantize_groups(c, s, m)
+        lhs = (xh * q[None]).sum(axis=(1, 2))
+        rhs = (s.astype(np.float64) * (c.astype(np.float64) * q[None]).sum(-1)).sum(-1) \
+            + (m.astype(np.float64) * q.sum(-1)[None]).sum(-1)
+        np.testing.assert_allclose(lhs, rhs, rtol=1e-12, atol=1e-12)
+
+
+def test_compress_tokenwise_end_to_end_small():
+    rng = np.random.default_rng(23)
+    Hkv, g, T, d, Sw = 2, 2, 400, 128, 32
+    Ks, Vs = _small_case(rng, Hkv=Hkv, T=T)
+    Qo = [rand_bf16(rng, (Hkv * g, Sw, d))]
+    cache = O.compress_tokenwise(Ks, Vs, Qo, [np.float32(2.0)])
+    for h in range(Hkv):
+        assert int(cache["bits"][0][h].astype(int).sum()) <= 2 * T
+    assert O.stored_bytes(cache["counts"]) > 0
+    q = rand_bf16(rng, (1, Hkv * g, d))
+    out, lse = O.decode(cache, q)
+    assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))

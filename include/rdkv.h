@@ -1,0 +1,197 @@
+/*
+ * rdkv.h -- C ABI of librdkv: decode attention read directly from a
+ * rate-distortion-compressed KV cache, and the one-shot post-prefill
+ * compression pass that builds that cache, for AMD MI355X (gfx950).
+ *
+ * Method: "RDKV: Rate-Distortion Bit Allocation for Joint Eviction and
+ * Quantization of the KV Cache" (arxiv 2605.08317).  Section / equation /
+ * algorithm numbers below refer to that paper.
+ *
+ * General rules
+ *  - Every pointer argument says whether it is HOST or DEVICE memory.  Device
+ *    buffers are owned by the caller unless stated otherwise and must stay valid
+ *    until the stream has executed the call's work.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue their kernels on it.  Calls that return a cache
+ *    (rdkv_pack, rdkv_compress) read tier counts back and therefore synchronise
+ *    the stream once; all other calls are asynchronous.
+ *  - Every function returns an rdkv_status and never throws or aborts; host-side
+ *    arguments are validated before anything is launched; on failure `*out`
+ *    handles are left NULL and rdkv_last_error() holds a message (thread local).
+ *  - Shapes: head_dim must be 128, hq a multiple of hkv with hq/hkv in
+ *    {1,2,4,8}, quantization group size 32.
+ *  - Ragged batch layout: K, V (and per-token arrays) hold, per sequence s in
+ *    batch order, a block [hkv][T_s][head_dim] (resp. [hkv][T_s]); blocks are
+ *    concatenated without padding.  One "item" is one (sequence, KV head), item
+ *    index = s*hkv + h.  Query head j reads KV head j / (hq/hkv).
+ */
+#ifndef RDKV_H
+#define RDKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rdkv_cache rdkv_cache; /* opaque; created by rdkv_pack / rdkv_compress */
+
+typedef enum {
+  RDKV_OK = 0,
+  RDKV_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad enum */
+  RDKV_ERR_SHAPE = 2,       /* unsupported or inconsistent shape */
+  RDKV_ERR_UNSUPPORTED = 3, /* valid request this build does not implement */
+  RDKV_ERR_ALLOC = 4,       /* device or host allocation failed */
+  RDKV_ERR_HIP = 5,         /* a HIP runtime call failed */
+  RDKV_ERR_INTERNAL = 6
+} rdkv_status;
+
+enum { RDKV_K_TOKENWISE = 0, RDKV_K_CHANNELWISE = 1 };
+enum { RDKV_MAX_TIERS = 5 };
+
+/* Device allocator hooks (e.g. a framework's caching allocator). */
+typedef void* (*rdkv_alloc_fn)(size_t bytes, void* user);
+typedef void (*rdkv_free_fn)(void* ptr, void* user);
+
+/*
+ * Problem statement of Sec. 3 and the inputs of Alg. 1, as one POD struct.
+ * Fill with rdkv_config_default() and override fields.
+ */
+typedef struct rdkv_config {
+  int32_t batch;            /* number of sequences */
+  int32_t hq, hkv;          /* query heads, KV heads (GQA group g = hq/hkv) */
+  int32_t head_dim;         /* d; must be 128 */
+  const int32_t* seq_lens;  /* HOST [batch]: prefill length T_s of each sequence, T_s >= s_obs */
+  int32_t s_obs;            /* observation window S_w (App. B: 32) */
+  int32_t pool_kernel;      /* AvgPool1d kernel w (App. B: 5); odd; 1 disables pooling */
+  int32_t causal;           /* 1: window row i attends keys t <= T - s_obs + i */
+  int32_t k_mode;           /* RDKV_K_TOKENWISE: K rows share the token bit map;
+                               RDKV_K_CHANNELWISE: Sec. 3.2 Stage 3 (per-channel K on kept tokens) */
+  int32_t group_size;       /* quantization group; must be 32 */
+  const float* budget_bits; /* HOST [batch]: average bits per cache element for each sequence */
+  float kv_split_rk;        /* r_K: share of the bit budget given to K in channel-wise mode (0.5) */
+  int32_t n_tiers;          /* number of entries of tiers[] (<= 5) */
+  int32_t tiers[RDKV_MAX_TIERS];   /* ascending bit-widths out of {0,2,4,8,16} (Sec. 3: B) */
+  float eps_v[RDKV_MAX_TIERS];     /* distortion table eps_V(b) aligned with tiers[] (Eq. 6, App. I) */
+  float eps_k[RDKV_MAX_TIERS];     /* distortion table eps_K(b) */
+  float rel_tol;            /* bisection tolerance delta (App. B: 1e-2) */
+  int32_t max_iters;        /* bisection steps I (App. B: 64) */
+  rdkv_alloc_fn alloc;      /* NULL: hipMalloc */
+  rdkv_free_fn free_;       /* NULL: hipFree */
+  void* alloc_user;
+} rdkv_config;
+
+/* Summary of a packed cache (all HOST values). */
+typedef struct rdkv_stats {
+  int64_t n_items;          /* batch * hkv */
+  int64_t rows[4];          /* kept tokens per tier, order 16, 8, 4, 2, summed over items */
+  int64_t evicted;          /* tokens at 0 bits, summed over items */
+  int64_t stored_bytes;     /* bytes a decode step must read: codes + scale/offset metadata, unpadded */
+  int64_t arena_bytes;      /* bytes allocated for the packed arena (with padding and alignment) */
+  int64_t index_bytes;      /* kept-position lists, segment tables, split schedule */
+  int64_t n_chunks;         /* work items of one decode launch */
+  int64_t dense_bytes;      /* 2 * sum_s hkv*T_s*head_dim*2: the uncompressed bf16 K+V */
+} rdkv_stats;
+
+/* What rdkv_cache_export copies out (all to HOST memory). */
+enum {
+  RDKV_EXPORT_COUNTS = 0,   /* int32 [items][4]: rows per tier (16, 8, 4, 2) */
+  RDKV_EXPORT_TIER_IDX = 1, /* int32 [sum kept]: kept positions, item-major, tier order 16,8,4,2, ascending */
+  RDKV_EXPORT_SEG_OFF = 2,  /* int64 [items][4 tiers][4]: arena byte offsets of K data, K meta, V data, V meta */
+  RDKV_EXPORT_ARENA = 3,    /* uint8 [arena_bytes]: the physical packed buffers */
+  RDKV_EXPORT_BITS_TOK = 4, /* uint8 [sum_s hkv*T_s]: token bit map */
+  RDKV_EXPORT_BITS_CH = 5   /* uint8 [items][head_dim]: K channel bit map (channel-wise mode) */
+};
+
+const char* rdkv_version(void);
+const char* rdkv_last_error(void);
+
+/* Defaults of App. B: S_w = 32, w = 5, causal, token-wise K, group 32, r_K = 0.5,
+ * tiers {0,2,4,8,16}, the LLaMA-3.1-8B row of Table 9 (eps(0)=1, eps(16)=0),
+ * delta = 1e-2, I = 64.  batch/heads/seq_lens/budget_bits are left zero. */
+rdkv_status rdkv_config_default(rdkv_config* cfg);
+
+/*
+ * Stage 1 of Alg. 1 (Eq. 2, Eq. 4).
+ *   K      DEVICE bf16, ragged [hkv][T_s][d] blocks
+ *   Q_obs  DEVICE bf16 [batch][hq][s_obs][d]: the last s_obs prefill queries
+ *   w_tok  DEVICE fp32 out, ragged [hkv][T_s]: pooled token weights
+ *          w_t = AvgPool(sum over window rows and group heads of softmax(q k^T/sqrt d)_t)
+ *   w_ch   DEVICE fp32 out [items][d] or NULL: channel weights
+ *          w_c = ||Q_obs[:,c]||_2 ||K[:,c]||_2 / sqrt(d)
+ */
+rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_obs,
+                         float* w_tok, float* w_ch, void* stream);
+
+/*
+ * Stages 2-3 of Alg. 1: the multiple-choice knapsack of Eq. 6 solved by the
+ * Lagrangian bisection of Alg. 2, once per item.  The result never exceeds the
+ * budget: sum_t bits <= floor(avg_bits * T).
+ *   w_tok    DEVICE fp32 ragged [hkv][T_s]
+ *   w_ch     DEVICE fp32 [items][d]; required in channel-wise mode, else ignored
+ *   bits_tok DEVICE uint8 out, ragged [hkv][T_s]
+ *   bits_ch  DEVICE uint8 out [items][d]; required in channel-wise mode, else ignored
+ * Token-wise mode: every sequence's budget_bits is the average over K and V alike.
+ * Channel-wise mode: V tokens get 2(1-r_K)*budget, then K channels get
+ * min(16, 2 r_K budget T / n_kept) average bits over kept tokens.
+ */
+rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const float* w_ch,
+                          uint8_t* bits_tok, uint8_t* bits_ch, void* stream);
+
+/*
+ * Stage 4 of Alg. 1: partition kept tokens by tier, quantize groups of 32 with an
+ * fp16 scale and fp16 offset, bit-pack into per-tier segments, and build the
+ * decode split schedule.  Bit maps may hold any mix of {0,2,4,8,16}.
+ *   K, V     DEVICE bf16 ragged
+ *   bits_tok DEVICE uint8 ragged [hkv][T_s]
+ *   bits_ch  DEVICE uint8 [items][d] (channel-wise mode) or NULL
+ *   out      HOST: receives the cache handle (library-owned; rdkv_cache_free)
+ */
+rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V,
+                      const uint8_t* bits_tok, const uint8_t* bits_ch, void* stream,
+                      rdkv_cache** out);
+
+/* The whole one-shot pass: rdkv_weights -> rdkv_allocate -> rdkv_pack (Alg. 1). */
+rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V,
+                          const void* Q_obs, void* stream, rdkv_cache** out);
+
+/*
+ * One decode step over the packed cache (Sec. 3.3, Eq. 7 without the new-token
+ * zone): for every sequence and query head, softmax(q K_hat^T / sqrt d) V_hat
+ * over the retained tokens, dequantization fused into the attention kernel.
+ *   q    DEVICE bf16 [batch][hq][d]
+ *   out  DEVICE fp32 [batch][hq][d]
+ *   lse  DEVICE fp32 [batch][hq] or NULL: natural-log sum of exp of the logits
+ * An item with no retained token gives out = 0, lse = -inf.  Calls on one cache
+ * share its split workspace: issue them on one stream (or serialise them).
+ */
+rdkv_status rdkv_decode_attn(const rdkv_cache* cache, const void* q, float* out, float* lse,
+                             void* stream);
+
+/*
+ * The same decode step over an uncompressed bf16 cache (the full-cache baseline
+ * of Sec. 4.2), for ratio comparisons.
+ *   K, V          DEVICE bf16 ragged [hkv][T_s][d] blocks
+ *   seq_lens      HOST [batch]
+ *   workspace     DEVICE scratch of at least rdkv_decode_bf16_workspace_bytes()
+ */
+size_t rdkv_decode_bf16_workspace_bytes(const int32_t* seq_lens, int32_t batch, int32_t hq,
+                                        int32_t hkv, int32_t head_dim);
+rdkv_status rdkv_decode_attn_bf16(const void* K, const void* V, const int32_t* seq_lens,
+                                  int32_t batch, int32_t hq, int32_t hkv, int32_t head_dim,
+                                  const void* q, float* out, float* lse, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/* Introspection (tests, benchmarks). */
+rdkv_status rdkv_cache_stats(const rdkv_cache* cache, rdkv_stats* out);
+/* Size in bytes of an export; 0 for an unknown `what`. */
+size_t rdkv_cache_export_bytes(const rdkv_cache* cache, int what);
+/* Copies the export to HOST memory `dst` of `bytes` >= rdkv_cache_export_bytes(); synchronous. */
+rdkv_status rdkv_cache_export(const rdkv_cache* cache, int what, void* dst, size_t bytes);
+void rdkv_cache_free(rdkv_cache* cache);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RDKV_H */

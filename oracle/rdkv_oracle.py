@@ -303,7 +303,7 @@ def quantize_groups(x, bits):
     leaves rounding and the scale format open.  Layout fixed by this build: fp32
     arithmetic in exactly this order, fp16 scale s and fp16 offset m = group
     minimum (z = -m/s), so x_hat = s*code + m:
-        mn = min x, mx = max x
+        mn = min x + 0.0 (so that -0 becomes +0), mx = max x
         s  = fp16_rn((mx - mn) / Q),  Q = 2^b - 1        (IEEE fp32 divide)
         m  = fp16_rn(mn)
         code = clamp(rint((x - m) / s), 0, Q)  (ties to even);  all 0 if s == 0
@@ -313,7 +313,7 @@ def quantize_groups(x, bits):
     assert bits in (2, 4, 8)
     x = np.ascontiguousarray(x, dtype=np.float32)
     Q = np.float32((1 << bits) - 1)
-    mn = x.min(axis=-1)
+    mn = x.min(axis=-1) + np.float32(0.0)
     mx = x.max(axis=-1)
     with np.errstate(over="ignore"):
         s = ((mx - mn) / Q).astype(np.float32).astype(np.float16)

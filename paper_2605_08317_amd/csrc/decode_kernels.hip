@@ -1,0 +1,382 @@
+// Split-K flash-decode over row-major tier segments (Sec. 3.3, Eq. 7) for gfx950.
+//
+// One workgroup (4 wavefronts) streams one chunk of rows of one tier of one
+// (sequence, KV head).  Sixteen lanes share a token: each lane owns 8 of the 128
+// channels, so a wavefront covers 4 tokens per load and a K/V byte is read once
+// for all g query heads of the group.  Low-bit codes are unpacked in registers;
+// the K product uses the fusion identity of App. B (scale and offset applied to
+// the per-group partial sums, not to every element).  Online softmax runs per
+// 16-lane row with DPP reductions; rows, wavefronts and chunks are merged by
+// log-sum-exp weights (rows and wavefronts in LDS, chunks by merge_kernel).
+#include "rdkv_internal.h"
+
+namespace rdkv {
+
+namespace {
+
+constexpr int kWG = 256;
+constexpr int kWaves = 4;
+constexpr float kNegBig = -1.0e30f;   // finite "minus infinity": keeps exp2(m_old - m_new) defined
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane receives the same bits.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_mov<0x141>(v);   // row_half_mirror
+  v += dpp_mov<0x140>(v);   // row_mirror
+  return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
+  return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<unsigned short>(h & 0xFFFFu)));
+}
+
+// Raw bytes one lane holds for one row: 8 channels at TIER bits each.
+template <int TIER>
+struct LaneRaw;
+template <>
+struct LaneRaw<16> { uint4 v; };
+template <>
+struct LaneRaw<8> { uint2 v; };
+template <>
+struct LaneRaw<4> { uint32_t v; };
+template <>
+struct LaneRaw<2> { uint16_t v; };
+
+template <int TIER>
+__device__ __forceinline__ LaneRaw<TIER> load_lane(const uint8_t* __restrict__ base, int row, int c16) {
+  LaneRaw<TIER> r;
+  const uint8_t* p = base + static_cast<int64_t>(row) * (TIER * 16) + c16 * TIER;
+  if constexpr (TIER == 16) r.v = *reinterpret_cast<const uint4*>(p);
+  if constexpr (TIER == 8) r.v = *reinterpret_cast<const uint2*>(p);
+  if constexpr (TIER == 4) r.v = *reinterpret_cast<const uint32_t*>(p);
+  if constexpr (TIER == 2) r.v = *reinterpret_cast<const uint16_t*>(p);
+  return r;
+}
+
+// 8 channel values as floats: bf16 values for tier 16, integer codes otherwise.
+template <int TIER>
+__device__ __forceinline__ void unpack8(const LaneRaw<TIER>& r, float (&x)[8]) {
+  if constexpr (TIER == 16) {
+    const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  } else if constexpr (TIER == 8) {
+    const uint32_t w[2] = {r.v.x, r.v.y};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = static_cast<float>((w[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+  } else if constexpr (TIER == 4) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = static_cast<float>((r.v >> (4 * i)) & 0xFu);
+  } else {
+    const uint32_t w = r.v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = static_cast<float>((w >> (2 * i)) & 0x3u);
+  }
+}
+
+// Streams `rows` rows and leaves the chunk's unnormalised result in part_acc / part_ml.
+template <int TIER, int G>
+__device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ km,
+                                             const uint8_t* __restrict__ vd, const uint8_t* __restrict__ vm,
+                                             int rows, const uint16_t* __restrict__ q,
+                                             float* __restrict__ part_acc, float* __restrict__ part_ml,
+                                             float* smem) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane >> 4, c16 = lane & 15;
+  // logits are kept in the log2 domain: q is scaled by log2(e) / sqrt(d)
+  const float qscale = 1.4426950408889634f * 0.08838834764831845f;
+
+  float qv[G][8], qsum[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    LaneRaw<16> raw;
+    raw.v = *reinterpret_cast<const uint4*>(q + h * kHeadDim + c16 * 8);
+    unpack8<16>(raw, qv[h]);
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      qv[h][c] *= qscale;
+      s += qv[h][c];
+    }
+    qsum[h] = s;
+  }
+
+  float m[G], l[G], acc[G][8];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    m[h] = kNegBig;
+    l[h] = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
+  }
+
+  const int last = rows - 1;
+  for (int base = wave * 16; base < rows; base += kWaves * 16) {
+    LaneRaw<TIER> kr[4], vr[4];
+    uint32_t kmeta[4], vmeta[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = min(base + u * 4 + r, last);
+      kr[u] = load_lane<TIER>(kd, row, c16);
+      if constexpr (TIER != 16)
+        kmeta[u] = *reinterpret_cast<const uint32_t*>(km + static_cast<int64_t>(row) * 16 + (c16 >> 2) * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = min(base + u * 4 + r, last);
+      vr[u] = load_lane<TIER>(vd, row, c16);
+      if constexpr (TIER != 16)
+        vmeta[u] = *reinterpret_cast<const uint32_t*>(vm + static_cast<int64_t>(row) * 16 + (c16 >> 2) * 4);
+    }
+
+    float s[4][G];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float kx[8];
+      unpack8<TIER>(kr[u], kx);
+      float sc = 1.f, off = 0.f;
+      if constexpr (TIER != 16) {
+        sc = half_bits_to_float(kmeta[u]);
+        off = half_bits_to_float(kmeta[u] >> 16);
+      }
+      const bool valid = (base + u * 4 + r) < rows;
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        float dot = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) dot = __builtin_fmaf(qv[h][c], kx[c], dot);
+        if constexpr (TIER != 16) dot = __builtin_fmaf(dot, sc, off * qsum[h]);
+        dot = row16_sum(dot);
+        s[u][h] = valid ? dot : -INFINITY;
+      }
+    }
+
+    // online softmax, one update per 4 rows
+    float p[4][G];
+    bool changed = false;
+    float alpha[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const float mt = fmaxf(fmaxf(s[0][h], s[1][h]), fmaxf(s[2][h], s[3][h]));
+      const float mn = fmaxf(m[h], mt);
+      alpha[h] = fast_exp2(m[h] - mn);
+      changed |= (mn != m[h]);
+      m[h] = mn;
+      float ls = 0.f;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        p[u][h] = fast_exp2(s[u][h] - mn);
+        ls += p[u][h];
+      }
+      l[h] = __builtin_fmaf(l[h], alpha[h], ls);
+    }
+    if (__any(changed)) {
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[h][c] *= alpha[h];
+    }
+
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float vx[8];
+      unpack8<TIER>(vr[u], vx);
+      if constexpr (TIER != 16) {
+        const float sc = half_bits_to_float(vmeta[u]);
+        const float off = half_bits_to_float(vmeta[u] >> 16);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) vx[c] = __builtin_fmaf(vx[c], sc, off);
+      }
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[h][c] = __builtin_fmaf(p[u][h], vx[c], acc[h][c]);
+    }
+  }
+
+  // ---- merge the 16 (wavefront, row) streams of this workgroup -------------
+  float* s_ml = smem;                    // [16][G][2]
+  float* s_acc = smem + 16 * G * 2;      // [4][G][128]
+  const int sid = wave * 4 + r;
+  if (c16 == 0) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      s_ml[(sid * G + h) * 2] = m[h];
+      s_ml[(sid * G + h) * 2 + 1] = l[h];
+    }
+  }
+  __syncthreads();
+  float mstar[G], lstar[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    float mm = kNegBig;
+    for (int i = 0; i < 16; ++i) mm = fmaxf(mm, s_ml[(i * G + h) * 2]);
+    float ll = 0.f;
+    for (int i = 0; i < 16; ++i) ll += s_ml[(i * G + h) * 2 + 1] * fast_exp2(s_ml[(i * G + h) * 2] - mm);
+    mstar[h] = mm;
+    lstar[h] = ll;
+    const float f = fast_exp2(m[h] - mm);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      float v = acc[h][c] * f;
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      acc[h][c] = v;
+    }
+  }
+  if (r == 0) {
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) s_acc[(wave * G + h) * kHeadDim + c16 * 8 + c] = acc[h][c];
+  }
+  __syncthreads();
+  for (int i = tid; i < G * kHeadDim; i += kWG) {
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) v += s_acc[w * G * kHeadDim + i];
+    part_acc[i] = v;
+  }
+  if (tid < G) {
+    part_ml[tid * 2] = mstar[tid];
+    part_ml[tid * 2 + 1] = lstar[tid];
+  }
+}
+
+template <int G>
+__global__ __launch_bounds__(kWG) void decode_dense_kernel(DenseArgs a) {
+  __shared__ float smem[16 * G * 2 + kWaves * G * kHeadDim];
+  const int split = blockIdx.x, head = blockIdx.y, sl = blockIdx.z;
+  const int T = a.T[sl];
+  const int row0 = split * a.chunk_rows;
+  if (row0 >= T) return;
+  const int rows = min(a.chunk_rows, T - row0);
+  const int64_t first = a.row_off[sl] + static_cast<int64_t>(head) * T + row0;
+  const uint8_t* kd = reinterpret_cast<const uint8_t*>(a.K) + first * (kHeadDim * 2);
+  const uint8_t* vd = reinterpret_cast<const uint8_t*>(a.V) + first * (kHeadDim * 2);
+  const int seq = a.seq_base + sl;
+  const uint16_t* q = a.q + (static_cast<int64_t>(seq) * a.hq + head * G) * kHeadDim;
+  const int64_t slot = (static_cast<int64_t>(sl) * a.hkv + head) * a.max_splits + split;
+  process_rows<16, G>(kd, nullptr, vd, nullptr, rows, q, a.part_acc + slot * G * kHeadDim,
+                      a.part_ml + slot * G * 2, smem);
+}
+
+template <int G>
+__global__ __launch_bounds__(kWG) void decode_tiered_kernel(const Chunk* __restrict__ chunks,
+                                                            const uint8_t* __restrict__ arena,
+                                                            const uint16_t* __restrict__ q, float* part_acc,
+                                                            float* part_ml, int hq, int hkv) {
+  __shared__ float smem[16 * G * 2 + kWaves * G * kHeadDim];
+  const Chunk ch = chunks[blockIdx.x];
+  const int seq = ch.item / hkv, head = ch.item % hkv;
+  const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * G) * kHeadDim;
+  float* pa = part_acc + static_cast<int64_t>(ch.slot) * G * kHeadDim;
+  float* pm = part_ml + static_cast<int64_t>(ch.slot) * G * 2;
+  const uint8_t* kd = arena + ch.k_data;
+  const uint8_t* km = arena + ch.k_meta;
+  const uint8_t* vd = arena + ch.v_data;
+  const uint8_t* vm = arena + ch.v_meta;
+  switch (ch.tier) {
+    case 16: process_rows<16, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
+    case 8: process_rows<8, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
+    case 4: process_rows<4, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
+    default: process_rows<2, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
+  }
+}
+
+// Log-sum-exp merge of the partial results of one (item, query head): 128 threads, one per channel.
+__device__ __forceinline__ void merge_slots(const float* __restrict__ part_acc, const float* __restrict__ part_ml,
+                                            int64_t slot0, int n, int g, int h, float* __restrict__ out,
+                                            float* __restrict__ lse) {
+  const int c = threadIdx.x;
+  float mstar = kNegBig;
+  for (int i = 0; i < n; ++i) mstar = fmaxf(mstar, part_ml[((slot0 + i) * g + h) * 2]);
+  float l = 0.f, o = 0.f;
+  for (int i = 0; i < n; ++i) {
+    const int64_t s = slot0 + i;
+    const float f = fast_exp2(part_ml[(s * g + h) * 2] - mstar);
+    l = __builtin_fmaf(part_ml[(s * g + h) * 2 + 1], f, l);
+    o = __builtin_fmaf(part_acc[(s * g + h) * kHeadDim + c], f, o);
+  }
+  const bool empty = !(l > 0.f);
+  out[c] = empty ? 0.f : o / l;
+  if (lse != nullptr && c == 0) *lse = empty ? -INFINITY : (mstar + __log2f(l)) * 0.6931471805599453f;
+}
+
+__global__ __launch_bounds__(kHeadDim) void merge_dense_kernel(DenseArgs a, int g) {
+  const int h = blockIdx.x % g;
+  const int item = blockIdx.x / g;            // local: sl * hkv + head
+  const int sl = item / a.hkv, head = item % a.hkv;
+  const int T = a.T[sl];
+  const int n = (T + a.chunk_rows - 1) / a.chunk_rows;
+  const int64_t qh = static_cast<int64_t>(a.seq_base + sl) * a.hq + head * g + h;
+  merge_slots(a.part_acc, a.part_ml, static_cast<int64_t>(item) * a.max_splits, n, g, h,
+              a.out + qh * kHeadDim, a.lse ? a.lse + qh : nullptr);
+}
+
+__global__ __launch_bounds__(kHeadDim) void merge_tiered_kernel(const float* __restrict__ part_acc,
+                                                                const float* __restrict__ part_ml,
+                                                                const int32_t* __restrict__ slot_begin,
+                                                                const int32_t* __restrict__ slot_count, int g,
+                                                                int hq, int hkv, float* __restrict__ out,
+                                                                float* __restrict__ lse) {
+  const int h = blockIdx.x % g;
+  const int item = blockIdx.x / g;
+  const int seq = item / hkv, head = item % hkv;
+  const int64_t qh = static_cast<int64_t>(seq) * hq + head * g + h;
+  merge_slots(part_acc, part_ml, slot_begin[item], slot_count[item], g, h, out + qh * kHeadDim,
+              lse ? lse + qh : nullptr);
+}
+
+}  // namespace
+
+hipError_t launch_decode_dense(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
+  dim3 grid(a.max_splits, a.hkv, n_seqs), block(kWG);
+  switch (g) {
+    case 1: hipLaunchKernelGGL(decode_dense_kernel<1>, grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL(decode_dense_kernel<2>, grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL(decode_dense_kernel<4>, grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL(decode_dense_kernel<8>, grid, block, 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(merge_dense_kernel, dim3(n_seqs * a.hkv * g), dim3(kHeadDim), 0, st, a, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_tiered(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
+                                float* part_acc, float* part_ml, const int32_t* slot_begin,
+                                const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
+                                float* lse, hipStream_t st) {
+  const int g = hq / hkv;
+  if (n_chunks > 0) {
+    dim3 grid(n_chunks), block(kWG);
+    switch (g) {
+      case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+      case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+      case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+      case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+      default: return hipErrorInvalidValue;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(merge_tiered_kernel, dim3(n_items * g), dim3(kHeadDim), 0, st, part_acc, part_ml,
+                     slot_begin, slot_count, g, hq, hkv, out, lse);
+  return hipGetLastError();
+}
+
+}  // namespace rdkv

@@ -1,0 +1,593 @@
+// Host side of librdkv: argument validation, planning (segment table, split
+// schedule) and kernel launches behind the C ABI of include/rdkv.h.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "rdkv_internal.h"
+
+namespace rdkv {
+hipError_t launch_tier_count(const uint8_t* bits, const int64_t* item_tok_off, const int32_t* item_T,
+                             const int32_t* item_blk_off, int32_t* blk_counts, int32_t* item_counts,
+                             int n_items, int max_T, hipStream_t st);
+hipError_t launch_tier_scatter(const uint8_t* bits, const int64_t* item_tok_off, const int32_t* item_T,
+                               const int32_t* item_blk_off, const int32_t* blk_offsets, const int64_t* idx_base,
+                               int32_t* tier_idx, int n_items, int max_T, hipStream_t st);
+hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t* tier_idx,
+                             const int64_t* idx_base, const int32_t* counts, const int64_t* seg_off,
+                             const int64_t* item_row_off, uint8_t* arena, int n_items,
+                             const int32_t max_count[4], hipStream_t st);
+int partition_block();
+hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off, const int32_t* d_item_T,
+                          const std::vector<int32_t>& item_T, const uint16_t* K, const uint16_t* Q_obs,
+                          float* w_tok, float* w_ch, float* scratch, hipStream_t st);
+size_t weights_scratch_floats(const rdkv_config& cfg, int64_t n_items);
+hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
+                           const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
+                           const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, hipStream_t st);
+}  // namespace rdkv
+
+using namespace rdkv;
+
+namespace {
+
+thread_local std::string g_err;
+
+rdkv_status fail(rdkv_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return s;
+}
+
+#define RDKV_HIP(expr)                                                                      \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(RDKV_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+struct Allocator {
+  rdkv_alloc_fn alloc = nullptr;
+  rdkv_free_fn free_ = nullptr;
+  void* user = nullptr;
+  void* get(size_t bytes) const {
+    if (bytes == 0) bytes = 16;
+    if (alloc) return alloc(bytes, user);
+    void* p = nullptr;
+    return hipMalloc(&p, bytes) == hipSuccess ? p : nullptr;
+  }
+  void put(void* p) const {
+    if (!p) return;
+    if (free_) free_(p, user); else (void)hipFree(p);
+  }
+};
+
+// Device scratch that is released when the call returns.
+struct Temp {
+  const Allocator& al;
+  std::vector<void*> ptrs;
+  explicit Temp(const Allocator& a) : al(a) {}
+  ~Temp() { for (void* p : ptrs) al.put(p); }
+  template <typename T>
+  T* get(size_t n) {
+    void* p = al.get(n * sizeof(T));
+    if (p) ptrs.push_back(p);
+    return static_cast<T*>(p);
+  }
+};
+
+// Geometry of a ragged batch: one entry per item (sequence-major, head-minor).
+struct Items {
+  int64_t n_items = 0, total_tokens = 0;
+  int32_t max_T = 0;
+  std::vector<int32_t> T;          // [items]
+  std::vector<int64_t> tok_off;    // [items]: first token of the item in ragged [hkv][T_s] arrays
+  std::vector<int32_t> blk_off;    // [items]: first partition block
+  int64_t n_blocks = 0;
+};
+
+Items make_items(const int32_t* seq_lens, int batch, int hkv) {
+  Items it;
+  const int pb = partition_block();
+  int64_t off = 0;
+  int64_t blk = 0;
+  for (int s = 0; s < batch; ++s) {
+    const int32_t T = seq_lens[s];
+    it.max_T = std::max(it.max_T, T);
+    for (int h = 0; h < hkv; ++h) {
+      it.T.push_back(T);
+      it.tok_off.push_back(off);
+      it.blk_off.push_back(static_cast<int32_t>(blk));
+      off += T;
+      blk += (T + pb - 1) / pb;
+    }
+  }
+  it.n_items = static_cast<int64_t>(batch) * hkv;
+  it.total_tokens = off;
+  it.n_blocks = blk;
+  return it;
+}
+
+bool valid_tier(int b) { return b == 0 || b == 2 || b == 4 || b == 8 || b == 16; }
+
+rdkv_status check_shape(int batch, int hq, int hkv, int d, const int32_t* seq_lens) {
+  if (batch < 0 || hq <= 0 || hkv <= 0) return fail(RDKV_ERR_INVALID_ARG, "batch/hq/hkv must be positive");
+  if (d != kHeadDim) return fail(RDKV_ERR_SHAPE, "head_dim %d unsupported (must be 128)", d);
+  if (hq % hkv != 0) return fail(RDKV_ERR_SHAPE, "hq %d is not a multiple of hkv %d", hq, hkv);
+  const int g = hq / hkv;
+  if (!(g == 1 || g == 2 || g == 4 || g == 8)) return fail(RDKV_ERR_SHAPE, "hq/hkv = %d unsupported (1,2,4,8)", g);
+  if (batch > 0 && seq_lens == nullptr) return fail(RDKV_ERR_INVALID_ARG, "seq_lens is null");
+  int64_t total = 0;
+  for (int s = 0; s < batch; ++s) {
+    if (seq_lens[s] < 0) return fail(RDKV_ERR_SHAPE, "seq_lens[%d] = %d is negative", s, seq_lens[s]);
+    total += static_cast<int64_t>(seq_lens[s]) * hkv;
+  }
+  if (total >= (1ll << 31)) return fail(RDKV_ERR_SHAPE, "sum of hkv*T_s exceeds 2^31 rows");
+  return RDKV_OK;
+}
+
+rdkv_status check_config(const rdkv_config* cfg, bool need_budget, bool need_probe) {
+  if (cfg == nullptr) return fail(RDKV_ERR_INVALID_ARG, "config is null");
+  rdkv_status s = check_shape(cfg->batch, cfg->hq, cfg->hkv, cfg->head_dim, cfg->seq_lens);
+  if (s != RDKV_OK) return s;
+  if (cfg->group_size != kGroup) return fail(RDKV_ERR_SHAPE, "group_size %d unsupported (must be 32)", cfg->group_size);
+  if (cfg->k_mode != RDKV_K_TOKENWISE && cfg->k_mode != RDKV_K_CHANNELWISE)
+    return fail(RDKV_ERR_INVALID_ARG, "k_mode %d unknown", cfg->k_mode);
+  if (need_probe) {
+    if (cfg->s_obs <= 0 || cfg->s_obs > 64) return fail(RDKV_ERR_SHAPE, "s_obs %d out of range (1..64)", cfg->s_obs);
+    if (cfg->pool_kernel < 1 || cfg->pool_kernel % 2 == 0 || cfg->pool_kernel > 15)
+      return fail(RDKV_ERR_INVALID_ARG, "pool_kernel %d must be odd, 1..15", cfg->pool_kernel);
+    for (int i = 0; i < cfg->batch; ++i)
+      if (cfg->seq_lens[i] < cfg->s_obs)
+        return fail(RDKV_ERR_SHAPE, "seq_lens[%d] = %d is shorter than s_obs = %d", i, cfg->seq_lens[i], cfg->s_obs);
+  }
+  if (need_budget) {
+    if (cfg->batch > 0 && cfg->budget_bits == nullptr) return fail(RDKV_ERR_INVALID_ARG, "budget_bits is null");
+    for (int i = 0; i < cfg->batch; ++i)
+      if (!(cfg->budget_bits[i] >= 0.0f) || !std::isfinite(cfg->budget_bits[i]))
+        return fail(RDKV_ERR_INVALID_ARG, "budget_bits[%d] must be finite and >= 0", i);
+    if (cfg->n_tiers < 1 || cfg->n_tiers > RDKV_MAX_TIERS) return fail(RDKV_ERR_INVALID_ARG, "n_tiers out of range");
+    for (int i = 0; i < cfg->n_tiers; ++i) {
+      if (!valid_tier(cfg->tiers[i])) return fail(RDKV_ERR_INVALID_ARG, "tiers[%d] = %d not in {0,2,4,8,16}", i, cfg->tiers[i]);
+      if (i > 0 && cfg->tiers[i] <= cfg->tiers[i - 1]) return fail(RDKV_ERR_INVALID_ARG, "tiers must be ascending");
+      if (!std::isfinite(cfg->eps_v[i]) || !std::isfinite(cfg->eps_k[i]))
+        return fail(RDKV_ERR_INVALID_ARG, "distortion table entry %d is not finite", i);
+    }
+    if (!(cfg->rel_tol >= 0.0f) || cfg->rel_tol >= 1.0f) return fail(RDKV_ERR_INVALID_ARG, "rel_tol must be in [0,1)");
+    if (cfg->max_iters < 1 || cfg->max_iters > 200) return fail(RDKV_ERR_INVALID_ARG, "max_iters must be in 1..200");
+    if (!(cfg->kv_split_rk > 0.0f) || !(cfg->kv_split_rk < 1.0f))
+      return fail(RDKV_ERR_INVALID_ARG, "kv_split_rk must be in (0,1)");
+  }
+  return RDKV_OK;
+}
+
+// chunk size policy of the dense path; used by the workspace query and the launch alike
+void dense_plan(const int32_t* seq_lens, int batch, int hkv, int* chunk_rows, int* max_splits) {
+  int64_t total = 0;
+  int max_T = 0;
+  for (int s = 0; s < batch; ++s) {
+    total += static_cast<int64_t>(seq_lens[s]) * hkv;
+    max_T = std::max(max_T, seq_lens[s]);
+  }
+  int64_t cr = round_up(std::max<int64_t>(256, (total + 1023) / 1024), 64);
+  *chunk_rows = static_cast<int>(cr);
+  *max_splits = std::max(1, static_cast<int>((max_T + cr - 1) / cr));
+}
+
+void free_cache_buffers(rdkv_cache* c) {
+  Allocator al{c->alloc, c->free_, c->alloc_user};
+  al.put(c->d_arena);
+  al.put(c->d_tier_idx);
+  al.put(c->d_chunks);
+  al.put(c->d_slot_begin);
+  al.put(c->d_slot_count);
+  al.put(c->d_part_acc);
+  al.put(c->d_part_ml);
+  al.put(c->d_bits_tok);
+  al.put(c->d_bits_ch);
+}
+
+// Lower convex hull of (b_k, eps_k) and the threshold ratios r_k = db / (-d eps) of its edges.
+void hull_thresholds(const rdkv_config* cfg, const float* eps, std::vector<int>* tiers, std::vector<double>* r) {
+  struct P { double b, e; };
+  std::vector<P> h;
+  for (int i = 0; i < cfg->n_tiers; ++i) {
+    const P p{static_cast<double>(cfg->tiers[i]), static_cast<double>(eps[i])};
+    while (h.size() >= 2) {
+      const P& a = h[h.size() - 2];
+      const P& b = h[h.size() - 1];
+      const double cross = (b.b - a.b) * (p.e - a.e) - (b.e - a.e) * (p.b - a.b);
+      if (cross <= 0.0) h.pop_back(); else break;
+    }
+    h.push_back(p);
+  }
+  tiers->clear();
+  r->clear();
+  tiers->push_back(static_cast<int>(h[0].b));
+  for (size_t k = 1; k < h.size(); ++k) {
+    const double de = h[k - 1].e - h[k].e;
+    if (!(de > 0.0)) break;
+    tiers->push_back(static_cast<int>(h[k].b));
+    r->push_back((h[k].b - h[k - 1].b) / de);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rdkv_version(void) { return "rdkv-mi355x 0.1 (gfx950)"; }
+const char* rdkv_last_error(void) { return g_err.c_str(); }
+
+rdkv_status rdkv_config_default(rdkv_config* cfg) {
+  if (!cfg) return fail(RDKV_ERR_INVALID_ARG, "config is null");
+  std::memset(cfg, 0, sizeof(*cfg));
+  cfg->head_dim = kHeadDim;
+  cfg->s_obs = 32;
+  cfg->pool_kernel = 5;
+  cfg->causal = 1;
+  cfg->k_mode = RDKV_K_TOKENWISE;
+  cfg->group_size = kGroup;
+  cfg->kv_split_rk = 0.5f;
+  cfg->n_tiers = 5;
+  const int t[5] = {0, 2, 4, 8, 16};
+  const float ev[5] = {1.0f, 0.313f, 0.0140f, 4.9e-5f, 0.0f};
+  const float ek[5] = {1.0f, 0.149f, 0.0062f, 2.2e-5f, 0.0f};
+  for (int i = 0; i < 5; ++i) {
+    cfg->tiers[i] = t[i];
+    cfg->eps_v[i] = ev[i];
+    cfg->eps_k[i] = ek[i];
+  }
+  cfg->rel_tol = 1e-2f;
+  cfg->max_iters = 64;
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_obs, float* w_tok,
+                         float* w_ch, void* stream) {
+  rdkv_status s = check_config(cfg, false, true);
+  if (s != RDKV_OK) return s;
+  if (!K || !Q_obs || !w_tok) return fail(RDKV_ERR_INVALID_ARG, "K, Q_obs and w_tok must not be null");
+  if (cfg->batch == 0) return RDKV_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al);
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  int64_t* d_off = tmp.get<int64_t>(it.n_items);
+  int32_t* d_T = tmp.get<int32_t>(it.n_items);
+  const size_t nscr = weights_scratch_floats(*cfg, it.n_items);
+  float* scratch = tmp.get<float>(nscr);
+  if (!d_off || !d_T || !scratch) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(launch_weights(*cfg, d_off, d_T, it.T, static_cast<const uint16_t*>(K),
+                          static_cast<const uint16_t*>(Q_obs), w_tok, w_ch, scratch, st));
+  RDKV_HIP(hipStreamSynchronize(st));   // scratch is released on return
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const float* w_ch, uint8_t* bits_tok,
+                          uint8_t* bits_ch, void* stream) {
+  rdkv_status s = check_config(cfg, true, false);
+  if (s != RDKV_OK) return s;
+  if (!w_tok || !bits_tok) return fail(RDKV_ERR_INVALID_ARG, "w_tok and bits_tok must not be null");
+  if (cfg->k_mode == RDKV_K_CHANNELWISE)
+    return fail(RDKV_ERR_UNSUPPORTED, "channel-wise K allocation is not implemented yet");
+  if (cfg->batch == 0) return RDKV_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al);
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  std::vector<int> ht;
+  std::vector<double> hr;
+  hull_thresholds(cfg, cfg->eps_v, &ht, &hr);
+  std::vector<double> budget(it.n_items);
+  for (int64_t i = 0; i < it.n_items; ++i) budget[i] = static_cast<double>(cfg->budget_bits[i / cfg->hkv]);
+  int64_t* d_off = tmp.get<int64_t>(it.n_items);
+  int32_t* d_T = tmp.get<int32_t>(it.n_items);
+  double* d_budget = tmp.get<double>(it.n_items);
+  if (!d_off || !d_T || !d_budget) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_budget, budget.data(), it.n_items * sizeof(double), hipMemcpyHostToDevice, st));
+  RDKV_HIP(launch_allocate(w_tok, d_off, d_T, d_budget, static_cast<int>(it.n_items), static_cast<int>(ht.size()),
+                           ht.data(), hr.data(), 1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters,
+                           bits_tok, st));
+  RDKV_HIP(hipStreamSynchronize(st));
+  (void)w_ch;
+  (void)bits_ch;
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, const uint8_t* bits_tok,
+                      const uint8_t* bits_ch, void* stream, rdkv_cache** out) {
+  if (out) *out = nullptr;
+  rdkv_status s = check_config(cfg, false, false);
+  if (s != RDKV_OK) return s;
+  if (!out) return fail(RDKV_ERR_INVALID_ARG, "out is null");
+  if (cfg->k_mode == RDKV_K_CHANNELWISE)
+    return fail(RDKV_ERR_UNSUPPORTED, "channel-wise K packing is not implemented yet");
+  (void)bits_ch;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  if (it.total_tokens > 0 && (!K || !V || !bits_tok))
+    return fail(RDKV_ERR_INVALID_ARG, "K, V and bits_tok must not be null");
+  const int g = cfg->hq / cfg->hkv;
+
+  rdkv_cache* c = new (std::nothrow) rdkv_cache();
+  if (!c) return fail(RDKV_ERR_ALLOC, "host allocation failed");
+  c->batch = cfg->batch; c->hq = cfg->hq; c->hkv = cfg->hkv; c->d = cfg->head_dim; c->k_mode = cfg->k_mode;
+  c->seq_lens.assign(cfg->seq_lens, cfg->seq_lens + cfg->batch);
+  c->n_items = it.n_items; c->total_tokens = it.total_tokens;
+  c->alloc = cfg->alloc; c->free_ = cfg->free_; c->alloc_user = cfg->alloc_user;
+  auto bail = [&](rdkv_status code) { free_cache_buffers(c); delete c; return code; };
+#define PACK_HIP(expr)                                                                             \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return bail(fail(RDKV_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_))); \
+  } while (0)
+
+  const int64_t n = it.n_items;
+  c->counts.assign(n * 4, 0);
+  c->seg_off.assign(n * 16, 0);
+  Temp tmp(al);
+  int64_t* d_tok_off = tmp.get<int64_t>(std::max<int64_t>(n, 1));
+  int32_t* d_T = tmp.get<int32_t>(std::max<int64_t>(n, 1));
+  int32_t* d_blk_off = tmp.get<int32_t>(std::max<int64_t>(n, 1));
+  int32_t* d_blk_counts = tmp.get<int32_t>(std::max<int64_t>(it.n_blocks * 4, 1));
+  int32_t* d_counts = tmp.get<int32_t>(std::max<int64_t>(n * 4, 1));
+  int64_t* d_idx_base = tmp.get<int64_t>(std::max<int64_t>(n * 4, 1));
+  int64_t* d_seg_off = tmp.get<int64_t>(std::max<int64_t>(n * 16, 1));
+  if (!d_tok_off || !d_T || !d_blk_off || !d_blk_counts || !d_counts || !d_idx_base || !d_seg_off)
+    return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
+
+  if (n > 0) {
+    PACK_HIP(hipMemcpyAsync(d_tok_off, it.tok_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    PACK_HIP(hipMemcpyAsync(d_T, it.T.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    PACK_HIP(hipMemcpyAsync(d_blk_off, it.blk_off.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    PACK_HIP(launch_tier_count(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_counts, static_cast<int>(n),
+                               it.max_T, st));
+    if (it.max_T > 0)
+      PACK_HIP(hipMemcpyAsync(c->counts.data(), d_counts, n * 4 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    PACK_HIP(hipStreamSynchronize(st));
+  }
+
+  // ---- plan: kept-position lists, arena segments, split schedule -------------------------
+  std::vector<int64_t> idx_base(n * 4, 0);
+  int64_t kept = 0, cur = 0, stored = 0;
+  int32_t max_count[4] = {0, 0, 0, 0};
+  for (int64_t i = 0; i < n; ++i) {
+    for (int ti = 0; ti < 4; ++ti) {
+      const int bits = pack_tier_bits(ti);
+      const int64_t cnt = c->counts[i * 4 + ti];
+      idx_base[i * 4 + ti] = kept;
+      kept += cnt;
+      max_count[ti] = std::max<int32_t>(max_count[ti], static_cast<int32_t>(cnt));
+      const int64_t npad = round_up(cnt, kRowPad);
+      const int64_t sizes[4] = {npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits),
+                                npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits)};
+      for (int si = 0; si < 4; ++si) {
+        cur = round_up(cur, kSegAlign);
+        c->seg_off[(i * 4 + ti) * 4 + si] = cur;
+        cur += sizes[si];
+      }
+      stored += cnt * 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+    }
+  }
+  c->arena_bytes = round_up(cur, kSegAlign);
+  c->kept_total = kept;
+
+  // byte-balanced chunks: every workgroup streams about the same number of stored bytes
+  const int64_t target_chunks = 2048;
+  const int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>(32 << 10, stored / target_chunks));
+  std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
+  for (int64_t i = 0; i < n; ++i) {
+    slot_begin[i] = static_cast<int32_t>(c->chunks.size());
+    for (int ti = 0; ti < 4; ++ti) {
+      const int bits = pack_tier_bits(ti);
+      const int64_t cnt = c->counts[i * 4 + ti];
+      if (cnt == 0) continue;
+      const int64_t per_row = 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+      const int64_t want = std::max<int64_t>(64, chunk_bytes / per_row);
+      const int64_t nch = (cnt + want - 1) / want;
+      const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
+      const int64_t* so = &c->seg_off[(i * 4 + ti) * 4];
+      for (int64_t r0 = 0; r0 < cnt; r0 += rows_per) {
+        Chunk ch;
+        ch.k_data = so[0] + r0 * tier_row_bytes(bits);
+        ch.k_meta = so[1] + r0 * tier_meta_bytes(bits);
+        ch.v_data = so[2] + r0 * tier_row_bytes(bits);
+        ch.v_meta = so[3] + r0 * tier_meta_bytes(bits);
+        ch.rows = static_cast<int32_t>(std::min<int64_t>(rows_per, cnt - r0));
+        ch.tier = bits;
+        ch.item = static_cast<int32_t>(i);
+        ch.slot = static_cast<int32_t>(c->chunks.size());
+        c->chunks.push_back(ch);
+      }
+    }
+    slot_count[i] = static_cast<int32_t>(c->chunks.size()) - slot_begin[i];
+  }
+  const int64_t n_chunks = static_cast<int64_t>(c->chunks.size());
+
+  // ---- allocate what the cache owns ------------------------------------------------------
+  c->d_arena = static_cast<uint8_t*>(al.get(c->arena_bytes));
+  c->d_tier_idx = static_cast<int32_t*>(al.get(std::max<int64_t>(kept, 1) * sizeof(int32_t)));
+  c->d_chunks = static_cast<Chunk*>(al.get(std::max<int64_t>(n_chunks, 1) * sizeof(Chunk)));
+  c->d_slot_begin = static_cast<int32_t*>(al.get(std::max<int64_t>(n, 1) * sizeof(int32_t)));
+  c->d_slot_count = static_cast<int32_t*>(al.get(std::max<int64_t>(n, 1) * sizeof(int32_t)));
+  c->d_part_acc = static_cast<float*>(al.get(std::max<int64_t>(n_chunks, 1) * g * kHeadDim * sizeof(float)));
+  c->d_part_ml = static_cast<float*>(al.get(std::max<int64_t>(n_chunks, 1) * g * 2 * sizeof(float)));
+  c->d_bits_tok = static_cast<uint8_t*>(al.get(std::max<int64_t>(it.total_tokens, 1)));
+  if (!c->d_arena || !c->d_tier_idx || !c->d_chunks || !c->d_slot_begin || !c->d_slot_count || !c->d_part_acc ||
+      !c->d_part_ml || !c->d_bits_tok)
+    return bail(fail(RDKV_ERR_ALLOC, "device allocation of the packed cache failed (%lld arena bytes)",
+                     static_cast<long long>(c->arena_bytes)));
+  c->index_bytes = kept * 4 + n_chunks * static_cast<int64_t>(sizeof(Chunk)) + n * 8 + n * 16 * 8;
+
+  if (n > 0) {
+    if (c->arena_bytes > 0) PACK_HIP(hipMemsetAsync(c->d_arena, 0, c->arena_bytes, st));
+    PACK_HIP(hipMemcpyAsync(d_idx_base, idx_base.data(), n * 4 * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    PACK_HIP(hipMemcpyAsync(d_seg_off, c->seg_off.data(), n * 16 * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    if (n_chunks > 0)
+      PACK_HIP(hipMemcpyAsync(c->d_chunks, c->chunks.data(), n_chunks * sizeof(Chunk), hipMemcpyHostToDevice, st));
+    PACK_HIP(hipMemcpyAsync(c->d_slot_begin, slot_begin.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    PACK_HIP(hipMemcpyAsync(c->d_slot_count, slot_count.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    if (it.total_tokens > 0)
+      PACK_HIP(hipMemcpyAsync(c->d_bits_tok, bits_tok, it.total_tokens, hipMemcpyDeviceToDevice, st));
+    if (kept > 0) {
+      PACK_HIP(launch_tier_scatter(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_idx_base, c->d_tier_idx,
+                                   static_cast<int>(n), it.max_T, st));
+      PACK_HIP(launch_quant_pack(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), c->d_tier_idx,
+                                 d_idx_base, d_counts, d_seg_off, d_tok_off, c->d_arena, static_cast<int>(n),
+                                 max_count, st));
+    }
+    PACK_HIP(hipStreamSynchronize(st));   // host vectors and scratch go out of scope
+  }
+#undef PACK_HIP
+  *out = c;
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, const void* Q_obs, void* stream,
+                          rdkv_cache** out) {
+  if (out) *out = nullptr;
+  rdkv_status s = check_config(cfg, true, true);
+  if (s != RDKV_OK) return s;
+  if (!out) return fail(RDKV_ERR_INVALID_ARG, "out is null");
+  if (cfg->k_mode == RDKV_K_CHANNELWISE)
+    return fail(RDKV_ERR_UNSUPPORTED, "channel-wise K compression is not implemented yet");
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al);
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  float* w = tmp.get<float>(std::max<int64_t>(it.total_tokens, 1));
+  uint8_t* bits = tmp.get<uint8_t>(std::max<int64_t>(it.total_tokens, 1));
+  if (!w || !bits) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  s = rdkv_weights(cfg, K, Q_obs, w, nullptr, stream);
+  if (s != RDKV_OK) return s;
+  s = rdkv_allocate(cfg, w, nullptr, bits, nullptr, stream);
+  if (s != RDKV_OK) return s;
+  return rdkv_pack(cfg, K, V, bits, nullptr, stream, out);
+}
+
+rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, float* lse, void* stream) {
+  if (!c || !q || !out) return fail(RDKV_ERR_INVALID_ARG, "cache, q and out must not be null");
+  if (c->n_items == 0) return RDKV_OK;
+  RDKV_HIP(launch_decode_tiered(c->d_chunks, static_cast<int>(c->chunks.size()), c->d_arena,
+                                static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml, c->d_slot_begin,
+                                c->d_slot_count, static_cast<int>(c->n_items), c->hq, c->hkv, out, lse,
+                                static_cast<hipStream_t>(stream)));
+  return RDKV_OK;
+}
+
+size_t rdkv_decode_bf16_workspace_bytes(const int32_t* seq_lens, int32_t batch, int32_t hq, int32_t hkv,
+                                        int32_t head_dim) {
+  if (check_shape(batch, hq, hkv, head_dim, seq_lens) != RDKV_OK || batch == 0) return 0;
+  int chunk_rows, max_splits;
+  dense_plan(seq_lens, batch, hkv, &chunk_rows, &max_splits);
+  const int64_t slots = static_cast<int64_t>(std::min(batch, kDenseMaxSeqs)) * hkv * max_splits;
+  return static_cast<size_t>(slots) * (hq / hkv) * (kHeadDim + 2) * sizeof(float);
+}
+
+rdkv_status rdkv_decode_attn_bf16(const void* K, const void* V, const int32_t* seq_lens, int32_t batch, int32_t hq,
+                                  int32_t hkv, int32_t head_dim, const void* q, float* out, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  rdkv_status s = check_shape(batch, hq, hkv, head_dim, seq_lens);
+  if (s != RDKV_OK) return s;
+  if (batch == 0) return RDKV_OK;
+  if (!K || !V || !q || !out || !workspace) return fail(RDKV_ERR_INVALID_ARG, "K, V, q, out, workspace must not be null");
+  const size_t need = rdkv_decode_bf16_workspace_bytes(seq_lens, batch, hq, hkv, head_dim);
+  if (workspace_bytes < need)
+    return fail(RDKV_ERR_INVALID_ARG, "workspace of %zu bytes is smaller than the %zu required", workspace_bytes, need);
+  const int g = hq / hkv;
+  int chunk_rows, max_splits;
+  dense_plan(seq_lens, batch, hkv, &chunk_rows, &max_splits);
+  const int64_t slots = static_cast<int64_t>(std::min(batch, kDenseMaxSeqs)) * hkv * max_splits;
+  int64_t row_off = 0;
+  for (int s0 = 0; s0 < batch; s0 += kDenseMaxSeqs) {
+    const int ns = std::min(kDenseMaxSeqs, batch - s0);
+    DenseArgs a;
+    a.K = static_cast<const uint16_t*>(K);
+    a.V = static_cast<const uint16_t*>(V);
+    a.q = static_cast<const uint16_t*>(q);
+    a.part_acc = static_cast<float*>(workspace);
+    a.part_ml = a.part_acc + slots * g * kHeadDim;
+    a.out = out;
+    a.lse = lse;
+    a.hq = hq; a.hkv = hkv; a.batch = batch; a.chunk_rows = chunk_rows; a.max_splits = max_splits; a.seq_base = s0;
+    for (int i = 0; i < ns; ++i) {
+      a.T[i] = seq_lens[s0 + i];
+      a.row_off[i] = row_off;
+      row_off += static_cast<int64_t>(seq_lens[s0 + i]) * hkv;
+    }
+    RDKV_HIP(launch_decode_dense(a, g, ns, static_cast<hipStream_t>(stream)));
+  }
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_cache_stats(const rdkv_cache* c, rdkv_stats* out) {
+  if (!c || !out) return fail(RDKV_ERR_INVALID_ARG, "cache and out must not be null");
+  std::memset(out, 0, sizeof(*out));
+  out->n_items = c->n_items;
+  int64_t kept = 0;
+  for (int64_t i = 0; i < c->n_items; ++i)
+    for (int ti = 0; ti < 4; ++ti) {
+      const int bits = pack_tier_bits(ti);
+      const int64_t cnt = c->counts[i * 4 + ti];
+      out->rows[ti] += cnt;
+      kept += cnt;
+      out->stored_bytes += cnt * 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+    }
+  out->evicted = c->total_tokens - kept;
+  out->arena_bytes = c->arena_bytes;
+  out->index_bytes = c->index_bytes;
+  out->n_chunks = static_cast<int64_t>(c->chunks.size());
+  out->dense_bytes = c->total_tokens * kHeadDim * 2 * 2;
+  return RDKV_OK;
+}
+
+size_t rdkv_cache_export_bytes(const rdkv_cache* c, int what) {
+  if (!c) return 0;
+  switch (what) {
+    case RDKV_EXPORT_COUNTS: return c->counts.size() * sizeof(int32_t);
+    case RDKV_EXPORT_TIER_IDX: return static_cast<size_t>(c->kept_total) * sizeof(int32_t);
+    case RDKV_EXPORT_SEG_OFF: return c->seg_off.size() * sizeof(int64_t);
+    case RDKV_EXPORT_ARENA: return static_cast<size_t>(c->arena_bytes);
+    case RDKV_EXPORT_BITS_TOK: return static_cast<size_t>(c->total_tokens);
+    case RDKV_EXPORT_BITS_CH: return c->d_bits_ch ? static_cast<size_t>(c->n_items) * kHeadDim : 0;
+    default: return 0;
+  }
+}
+
+rdkv_status rdkv_cache_export(const rdkv_cache* c, int what, void* dst, size_t bytes) {
+  if (!c || (!dst && bytes > 0)) return fail(RDKV_ERR_INVALID_ARG, "cache and dst must not be null");
+  const size_t need = rdkv_cache_export_bytes(c, what);
+  if (what < RDKV_EXPORT_COUNTS || what > RDKV_EXPORT_BITS_CH) return fail(RDKV_ERR_INVALID_ARG, "unknown export %d", what);
+  if (bytes < need) return fail(RDKV_ERR_INVALID_ARG, "destination of %zu bytes is smaller than the %zu required", bytes, need);
+  if (need == 0) return RDKV_OK;
+  switch (what) {
+    case RDKV_EXPORT_COUNTS: std::memcpy(dst, c->counts.data(), need); break;
+    case RDKV_EXPORT_SEG_OFF: std::memcpy(dst, c->seg_off.data(), need); break;
+    case RDKV_EXPORT_TIER_IDX: RDKV_HIP(hipMemcpy(dst, c->d_tier_idx, need, hipMemcpyDeviceToHost)); break;
+    case RDKV_EXPORT_ARENA: RDKV_HIP(hipMemcpy(dst, c->d_arena, need, hipMemcpyDeviceToHost)); break;
+    case RDKV_EXPORT_BITS_TOK: RDKV_HIP(hipMemcpy(dst, c->d_bits_tok, need, hipMemcpyDeviceToHost)); break;
+    case RDKV_EXPORT_BITS_CH: RDKV_HIP(hipMemcpy(dst, c->d_bits_ch, need, hipMemcpyDeviceToHost)); break;
+  }
+  return RDKV_OK;
+}
+
+void rdkv_cache_free(rdkv_cache* c) {
+  if (!c) return;
+  free_cache_buffers(c);
+  delete c;
+}
+
+}  // extern "C"

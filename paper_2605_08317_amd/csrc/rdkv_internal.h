@@ -1,0 +1,84 @@
+// Internal declarations shared by the host side of librdkv and its kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "rdkv.h"
+
+namespace rdkv {
+
+constexpr int kHeadDim = 128;
+constexpr int kGroup = 32;             // quantization group (channels)
+constexpr int kGroupsPerRow = kHeadDim / kGroup;
+constexpr int kRowPad = 32;            // tier segments are padded to whole 32-row tiles
+constexpr int kSegAlign = 256;         // byte alignment of arena segments
+constexpr int kNumPackTiers = 4;       // stored tiers, order 16, 8, 4, 2
+constexpr int kDenseMaxSeqs = 64;      // sequences per dense-decode launch (kernel-argument table)
+
+__host__ __device__ inline int pack_tier_bits(int ti) { return 16 >> ti; }          // 0..3 -> 16,8,4,2
+__host__ __device__ inline int tier_row_bytes(int bits) { return kHeadDim * bits / 8; }
+__host__ __device__ inline int tier_meta_bytes(int bits) { return bits == 16 ? 0 : kGroupsPerRow * 4; }
+
+// One unit of decode work: a run of rows of one tier of one item.
+struct Chunk {
+  int64_t k_data, k_meta, v_data, v_meta;   // byte offsets into the arena
+  int32_t rows;                             // valid rows in this chunk
+  int32_t tier;                             // 16, 8, 4, 2
+  int32_t item;                             // sequence * hkv + kv head
+  int32_t slot;                             // partial-result slot
+};
+
+struct DenseArgs {
+  const uint16_t* K;
+  const uint16_t* V;
+  const uint16_t* q;
+  float* part_acc;     // [slots][g][128]
+  float* part_ml;      // [slots][g][2]
+  float* out;
+  float* lse;
+  int32_t hq, hkv, batch, chunk_rows, max_splits, seq_base;
+  int32_t T[kDenseMaxSeqs];
+  int64_t row_off[kDenseMaxSeqs];           // first row of the sequence block in K / V
+};
+
+// ---- launchers implemented in the .hip files ------------------------------
+hipError_t launch_decode_dense(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
+hipError_t launch_decode_tiered(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
+                                float* part_acc, float* part_ml, const int32_t* slot_begin,
+                                const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
+                                float* lse, hipStream_t st);
+
+struct PackItemDesc;   // compress_kernels
+
+}  // namespace rdkv
+
+// The opaque handle of the C ABI.
+struct rdkv_cache {
+  int32_t batch = 0, hq = 0, hkv = 0, d = 0, k_mode = 0;
+  std::vector<int32_t> seq_lens;
+  int64_t n_items = 0;
+  int64_t total_tokens = 0;             // sum_s hkv * T_s
+  // host copies
+  std::vector<int32_t> counts;          // [items][4]
+  std::vector<int64_t> seg_off;         // [items][4][4]
+  std::vector<rdkv::Chunk> chunks;
+  int64_t arena_bytes = 0;
+  int64_t kept_total = 0;
+  // device memory (owned)
+  uint8_t* d_arena = nullptr;
+  int32_t* d_tier_idx = nullptr;        // [kept_total]
+  rdkv::Chunk* d_chunks = nullptr;
+  int32_t* d_slot_begin = nullptr;      // [items]
+  int32_t* d_slot_count = nullptr;      // [items]
+  float* d_part_acc = nullptr;
+  float* d_part_ml = nullptr;
+  uint8_t* d_bits_tok = nullptr;        // copy of the token bit map
+  uint8_t* d_bits_ch = nullptr;
+  int64_t index_bytes = 0;
+  rdkv_alloc_fn alloc = nullptr;
+  rdkv_free_fn free_ = nullptr;
+  void* alloc_user = nullptr;
+};

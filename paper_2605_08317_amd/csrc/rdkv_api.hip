@@ -21,10 +21,12 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
                              const int64_t* item_row_off, uint8_t* arena, int n_items,
                              const int32_t max_count[4], hipStream_t st);
 int partition_block();
+int weights_block();
+size_t weights_scratch_floats(int64_t n_blocks, int64_t n_items, int64_t total_tokens, int R_pad, bool want_ch);
 hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off, const int32_t* d_item_T,
-                          const std::vector<int32_t>& item_T, const uint16_t* K, const uint16_t* Q_obs,
-                          float* w_tok, float* w_ch, float* scratch, hipStream_t st);
-size_t weights_scratch_floats(const rdkv_config& cfg, int64_t n_items);
+                          const int32_t* d_item_blk_off, int64_t n_blocks, int64_t n_items, int64_t total_tokens,
+                          int max_T, const uint16_t* K, const uint16_t* Q_obs, float* w_tok, float* w_ch,
+                          float* scratch, hipStream_t st);
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
                            const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, hipStream_t st);
@@ -261,15 +263,26 @@ rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_ob
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
   Temp tmp(al);
   Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  const int wb = weights_block();
+  std::vector<int32_t> wblk_off(it.n_items);
+  int64_t n_wblk = 0;
+  for (int64_t i = 0; i < it.n_items; ++i) {
+    wblk_off[i] = static_cast<int32_t>(n_wblk);
+    n_wblk += (it.T[i] + wb - 1) / wb;
+  }
+  const int R_pad = (cfg->hq / cfg->hkv * cfg->s_obs + 15) / 16 * 16;
   int64_t* d_off = tmp.get<int64_t>(it.n_items);
   int32_t* d_T = tmp.get<int32_t>(it.n_items);
-  const size_t nscr = weights_scratch_floats(*cfg, it.n_items);
+  int32_t* d_wblk = tmp.get<int32_t>(it.n_items);
+  const size_t nscr = weights_scratch_floats(n_wblk, it.n_items, it.total_tokens, R_pad, w_ch != nullptr);
   float* scratch = tmp.get<float>(nscr);
-  if (!d_off || !d_T || !scratch) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  if (!d_off || !d_T || !d_wblk || !scratch) return fail(RDKV_ERR_ALLOC, "device allocation failed");
   RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
   RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(launch_weights(*cfg, d_off, d_T, it.T, static_cast<const uint16_t*>(K),
-                          static_cast<const uint16_t*>(Q_obs), w_tok, w_ch, scratch, st));
+  RDKV_HIP(hipMemcpyAsync(d_wblk, wblk_off.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(launch_weights(*cfg, d_off, d_T, d_wblk, n_wblk, it.n_items, it.total_tokens, it.max_T,
+                          static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(Q_obs), w_tok, w_ch,
+                          scratch, st));
   RDKV_HIP(hipStreamSynchronize(st));   // scratch is released on return
   return RDKV_OK;
 }

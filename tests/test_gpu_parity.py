@@ -202,3 +202,85 @@ def test_allocate_is_bit_exact(seq_lens, budgets, eps):
             np.testing.assert_array_equal(got[off:off + T], ref)
             assert int(ref.astype(np.int64).sum()) <= int(np.floor(np.float64(np.float32(budgets[s])) * T))
             off += T
+
+
+# ----------------------------------------------------------------------------
+# C1-C3: weights (fp32 on the GPU, bf16 MFMA products are exact; fp64 in the oracle)
+# ----------------------------------------------------------------------------
+WEIGHT_RTOL = 5e-4   # fp32 logits of magnitude <= ~100 in the log2 domain carry ~1e-5 absolute error -> ~1e-5
+                     # relative in each exp; the hardware exp2 adds a few ulp; sums over <= 512 rows
+
+
+@pytest.mark.parametrize("name,kw,pool,causal", [
+    ("tiny", {"seq_lens": (1000,)}, 5, 1),
+    ("tiny", {"seq_lens": (4096,)}, 5, 1),
+    ("tiny", {"seq_lens": (700,)}, 1, 0),
+    ("tiny", {"seq_lens": (33,), "s_obs": 32}, 5, 1),
+    ("tiny", {"seq_lens": (300,), "s_obs": 5, "hq": 2, "hkv": 2}, 3, 1),
+    ("layer8b", {"seq_lens": (3000,)}, 5, 1),
+    ("stack128k", {"seq_lens": (5000,)}, 5, 1),
+    ("batch70b", {"batch": 3, "len_range": (300, 1200)}, 5, 1),
+])
+def test_weights_match_oracle(name, kw, pool, causal):
+    b = B()
+    wl, inp, dev = _inputs(name, **kw)
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, s_obs=wl.s_obs, pool_kernel=pool, causal=causal)
+    w_tok, w_ch = b.rdkv_weights(cfg, dev["K"], dev["Q_obs"], want_channel=True)
+    torch.cuda.synchronize()
+    w_tok = w_tok.cpu().numpy().astype(np.float64)
+    w_ch = w_ch.cpu().numpy().astype(np.float64).reshape(-1, wl.d)
+    Ks = _split(inp["K"], inp["seq_lens"], wl.hkv, wl.d)
+    off = 0
+    for s, T in enumerate(inp["seq_lens"]):
+        Qs = _np(inp["Q_obs"][s])
+        ref = O.avg_pool(O.token_weights(Ks[s], Qs, causal=bool(causal)), pool)
+        got = w_tok[off:off + wl.hkv * T].reshape(wl.hkv, T)
+        off += wl.hkv * T
+        err = np.abs(got - ref) / (np.abs(ref) + 1e-6 * ref.max())
+        print(f"[weights] seq {s}: max rel err {err.max():.3e}", flush=True)
+        assert err.max() <= WEIGHT_RTOL
+        ref_c = O.channel_weights(Ks[s], Qs)
+        np.testing.assert_allclose(w_ch[s * wl.hkv:(s + 1) * wl.hkv], ref_c, rtol=1e-5)
+
+
+# ----------------------------------------------------------------------------
+# the fused pass: weights -> allocation -> pack, then decode
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("name,kw", [
+    ("tiny", {}),
+    ("layer8b", {"seq_lens": (6000,)}),
+    ("stack128k", {"seq_lens": (8192,)}),
+    ("batch70b", {"batch": 3, "len_range": (500, 2500)}),
+])
+def test_compress_then_decode(name, kw):
+    b = B()
+    wl, inp, dev = _inputs(name, **kw)
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs)
+    cache = b.rdkv_compress(cfg, dev["K"], dev["V"], dev["Q_obs"])
+    # the library's own weights, fed to the oracle's allocator and packer: everything after must be bit-exact
+    w_tok, _ = b.rdkv_weights(cfg, dev["K"], dev["Q_obs"])
+    torch.cuda.synchronize()
+    w_list = [x.cpu().numpy() for x in W.split_sequences(w_tok, inp["seq_lens"], wl.hkv, None)]
+    Ks = _split(inp["K"], inp["seq_lens"], wl.hkv, wl.d)
+    Vs = _split(inp["V"], inp["seq_lens"], wl.hkv, wl.d)
+    Qs = [_np(inp["Q_obs"][s]) for s in range(len(inp["seq_lens"]))]
+    ref = O.compress_tokenwise(Ks, Vs, Qs, [np.float32(x) for x in inp["budgets"]], weights_override=w_list)
+    bits = cache.export(b.RDKV_EXPORT_BITS_TOK, np.uint8)
+    np.testing.assert_array_equal(bits, np.concatenate([x.reshape(-1) for x in ref["bits"]]))
+    _assert_cache_equal(b, cache, ref)
+    for s, T in enumerate(inp["seq_lens"]):
+        for h in range(wl.hkv):
+            assert int(ref["bits"][s][h].astype(np.int64).sum()) <= int(np.floor(np.float64(np.float32(inp["budgets"][s])) * T))
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    ref_out, ref_lse = O.decode(ref, _np(inp["q"]))
+    _check_decode(out, lse, ref_out, ref_lse)
+    st = cache.stats()
+    print(f"[compress] rows(16,8,4,2)={st['rows']} evicted={st['evicted']} stored={st['stored_bytes']} "
+          f"dense={st['dense_bytes']} chunks={st['n_chunks']}", flush=True)
+    # the oracle's own fp64 weights select nearly the same tokens (weights agree to ~1e-4)
+    ref2 = O.compress_tokenwise(Ks, Vs, Qs, [np.float32(x) for x in inp["budgets"]])
+    differ = sum(int((a != c).sum()) for a, c in zip(ref["bits"], ref2["bits"]))
+    total = sum(a.size for a in ref["bits"])
+    assert differ <= max(2, 2e-3 * total)
+    cache.free()

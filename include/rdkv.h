@@ -183,6 +183,26 @@ rdkv_status rdkv_decode_attn_bf16(const void* K, const void* V, const int32_t* s
                                   const void* q, float* out, float* lse, void* workspace,
                                   size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid (benchmarks).  While enabled, the calls above bracket their
+ * main kernel with HIP events on the call's own stream: the split-K decode
+ * kernel of rdkv_decode_attn / rdkv_decode_attn_bf16, the two MFMA passes of
+ * rdkv_weights, the bisection kernel of rdkv_allocate, the quantize-and-pack
+ * kernels of rdkv_pack.  rdkv_kernel_timing_read waits for the recorded events,
+ * returns the number of bracketed launches of one kind and their summed
+ * duration in milliseconds, and clears that kind.  Not for use under graph capture.
+ */
+enum {
+  RDKV_TIME_DECODE_TIERED = 0,
+  RDKV_TIME_DECODE_BF16 = 1,
+  RDKV_TIME_WEIGHTS = 2,
+  RDKV_TIME_ALLOCATE = 3,
+  RDKV_TIME_PACK = 4,
+  RDKV_TIME_KINDS = 5
+};
+rdkv_status rdkv_kernel_timing_enable(int32_t enable);
+rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* total_ms);
+
 /* Introspection (tests, benchmarks). */
 rdkv_status rdkv_cache_stats(const rdkv_cache* cache, rdkv_stats* out);
 /* Size in bytes of an export; 0 for an unknown `what`. */

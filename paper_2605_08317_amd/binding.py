@@ -25,7 +25,9 @@ EXPORTED_SYMBOLS = [
     "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_pack",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
     "rdkv_cache_stats", "rdkv_cache_export_bytes", "rdkv_cache_export", "rdkv_cache_free",
+    "rdkv_kernel_timing_enable", "rdkv_kernel_timing_read",
 ]
+(RDKV_TIME_DECODE_TIERED, RDKV_TIME_DECODE_BF16, RDKV_TIME_WEIGHTS, RDKV_TIME_ALLOCATE, RDKV_TIME_PACK) = range(5)
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -83,6 +85,8 @@ def _load():
     lib.rdkv_cache_export.argtypes = [vp, i32, vp, sz]
     lib.rdkv_cache_free.argtypes = [vp]
     lib.rdkv_cache_free.restype = None
+    lib.rdkv_kernel_timing_enable.argtypes = [i32]
+    lib.rdkv_kernel_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
     return lib
 
 
@@ -229,3 +233,14 @@ def rdkv_decode_attn_bf16(K, V, seq_lens, hq, hkv, q, head_dim=128, out=None, ls
     _check(lib.rdkv_decode_attn_bf16(_ptr(K), _ptr(V), arr, len(seq_lens), hq, hkv, head_dim, _ptr(q), _ptr(out),
                                      _ptr(lse), _ptr(workspace), workspace.numel(), _stream()))
     return out, lse
+
+
+def rdkv_kernel_timing_enable(enable):
+    _check(lib.rdkv_kernel_timing_enable(1 if enable else 0))
+
+
+def rdkv_kernel_timing_read(kind):
+    """(launches, total_ms) of the bracketed main kernel of one kind since the last read."""
+    n, ms = ctypes.c_int64(), ctypes.c_double()
+    _check(lib.rdkv_kernel_timing_read(kind, ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value

@@ -296,26 +296,68 @@ __global__ __launch_bounds__(kWG) void decode_tiered_kernel(const Chunk* __restr
   }
 }
 
-// Log-sum-exp merge of the partial results of one (item, query head): 128 threads, one per channel.
+// Log-sum-exp merge of the partial results of one (item, query head).  512 threads: 4 slot groups x 128
+// channels; the slot loop of each group is unrolled so that its loads overlap; fixed summation order.
+constexpr int kMergeThreads = 512;
+
+__device__ __forceinline__ float merge_block_reduce(float v, bool is_max, float* sm) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float t = __shfl_xor(v, o);
+    v = is_max ? fmaxf(v, t) : v + t;
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sm[0];
+#pragma unroll
+  for (int i = 1; i < kMergeThreads / 64; ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
+  return r;
+}
+
 __device__ __forceinline__ void merge_slots(const float* __restrict__ part_acc, const float* __restrict__ part_ml,
                                             int64_t slot0, int n, int g, int h, float* __restrict__ out,
                                             float* __restrict__ lse) {
-  const int c = threadIdx.x;
-  float mstar = kNegBig;
-  for (int i = 0; i < n; ++i) mstar = fmaxf(mstar, part_ml[((slot0 + i) * g + h) * 2]);
-  float l = 0.f, o = 0.f;
-  for (int i = 0; i < n; ++i) {
-    const int64_t s = slot0 + i;
-    const float f = fast_exp2(part_ml[(s * g + h) * 2] - mstar);
-    l = __builtin_fmaf(part_ml[(s * g + h) * 2 + 1], f, l);
-    o = __builtin_fmaf(part_acc[(s * g + h) * kHeadDim + c], f, o);
+  __shared__ float sm_red[kMergeThreads / 64];
+  __shared__ float sm_o[4][kHeadDim];
+  const int tid = threadIdx.x, c = tid & (kHeadDim - 1), grp = tid >> 7;
+  float mx = kNegBig;
+  for (int i = tid; i < n; i += kMergeThreads) mx = fmaxf(mx, part_ml[((slot0 + i) * g + h) * 2]);
+  const float mstar = merge_block_reduce(mx, true, sm_red);
+  float lp = 0.f;
+  for (int i = tid; i < n; i += kMergeThreads) {
+    const float* ml = part_ml + ((slot0 + i) * g + h) * 2;
+    lp = __builtin_fmaf(ml[1], fast_exp2(ml[0] - mstar), lp);
   }
-  const bool empty = !(l > 0.f);
-  out[c] = empty ? 0.f : o / l;
-  if (lse != nullptr && c == 0) *lse = empty ? -INFINITY : (mstar + __log2f(l)) * 0.6931471805599453f;
+  const float l = merge_block_reduce(lp, false, sm_red);
+  float o = 0.f;
+  int i = grp;
+  for (; i + 12 < n; i += 16) {
+    float f[4], a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t s = slot0 + i + 4 * u;
+      f[u] = part_ml[(s * g + h) * 2];
+      a[u] = part_acc[(s * g + h) * kHeadDim + c];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) o = __builtin_fmaf(a[u], fast_exp2(f[u] - mstar), o);
+  }
+  for (; i < n; i += 4) {
+    const int64_t s = slot0 + i;
+    o = __builtin_fmaf(part_acc[(s * g + h) * kHeadDim + c], fast_exp2(part_ml[(s * g + h) * 2] - mstar), o);
+  }
+  sm_o[grp][c] = o;
+  __syncthreads();
+  if (grp == 0) {
+    const float t = (sm_o[0][c] + sm_o[1][c]) + (sm_o[2][c] + sm_o[3][c]);
+    const bool empty = !(l > 0.f);
+    out[c] = empty ? 0.f : t / l;
+    if (lse != nullptr && c == 0) *lse = empty ? -INFINITY : (mstar + __log2f(l)) * 0.6931471805599453f;
+  }
 }
 
-__global__ __launch_bounds__(kHeadDim) void merge_dense_kernel(DenseArgs a, int g) {
+__global__ __launch_bounds__(kMergeThreads) void merge_dense_kernel(DenseArgs a, int g) {
   const int h = blockIdx.x % g;
   const int item = blockIdx.x / g;            // local: sl * hkv + head
   const int sl = item / a.hkv, head = item % a.hkv;
@@ -326,7 +368,7 @@ __global__ __launch_bounds__(kHeadDim) void merge_dense_kernel(DenseArgs a, int 
               a.out + qh * kHeadDim, a.lse ? a.lse + qh : nullptr);
 }
 
-__global__ __launch_bounds__(kHeadDim) void merge_tiered_kernel(const float* __restrict__ part_acc,
+__global__ __launch_bounds__(kMergeThreads) void merge_tiered_kernel(const float* __restrict__ part_acc,
                                                                 const float* __restrict__ part_ml,
                                                                 const int32_t* __restrict__ slot_begin,
                                                                 const int32_t* __restrict__ slot_count, int g,
@@ -342,7 +384,7 @@ __global__ __launch_bounds__(kHeadDim) void merge_tiered_kernel(const float* __r
 
 }  // namespace
 
-hipError_t launch_decode_dense(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
+hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
   dim3 grid(a.max_splits, a.hkv, n_seqs), block(kWG);
   switch (g) {
     case 1: hipLaunchKernelGGL(decode_dense_kernel<1>, grid, block, 0, st, a); break;
@@ -351,30 +393,34 @@ hipError_t launch_decode_dense(const DenseArgs& a, int g, int n_seqs, hipStream_
     case 8: hipLaunchKernelGGL(decode_dense_kernel<8>, grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(merge_dense_kernel, dim3(n_seqs * a.hkv * g), dim3(kHeadDim), 0, st, a, g);
   return hipGetLastError();
 }
 
-hipError_t launch_decode_tiered(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                float* part_acc, float* part_ml, const int32_t* slot_begin,
-                                const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
-                                float* lse, hipStream_t st) {
+hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
+  hipLaunchKernelGGL(merge_dense_kernel, dim3(n_seqs * a.hkv * g), dim3(kMergeThreads), 0, st, a, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
+                                      float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st) {
   const int g = hq / hkv;
-  if (n_chunks > 0) {
-    dim3 grid(n_chunks), block(kWG);
-    switch (g) {
-      case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
-      case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
-      case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
-      case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
-      default: return hipErrorInvalidValue;
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+  if (n_chunks == 0) return hipSuccess;
+  dim3 grid(n_chunks), block(kWG);
+  switch (g) {
+    case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    default: return hipErrorInvalidValue;
   }
-  hipLaunchKernelGGL(merge_tiered_kernel, dim3(n_items * g), dim3(kHeadDim), 0, st, part_acc, part_ml,
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
+                                      const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
+                                      float* lse, hipStream_t st) {
+  const int g = hq / hkv;
+  hipLaunchKernelGGL(merge_tiered_kernel, dim3(n_items * g), dim3(kMergeThreads), 0, st, part_acc, part_ml,
                      slot_begin, slot_count, g, hq, hkv, out, lse);
   return hipGetLastError();
 }

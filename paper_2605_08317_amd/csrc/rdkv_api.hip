@@ -5,7 +5,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <utility>
 
 #include "rdkv_internal.h"
 
@@ -34,6 +36,7 @@ hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int3
 
 using namespace rdkv;
 
+
 namespace {
 
 thread_local std::string g_err;
@@ -55,6 +58,20 @@ rdkv_status fail(rdkv_status s, const char* fmt, ...) {
   } while (0)
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// ---- optional event bracketing of the main kernels ----------------------------------
+struct KernelTiming {
+  std::mutex mu;
+  bool enabled = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[RDKV_TIME_KINDS];
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    return hipEventCreate(&e) == hipSuccess ? e : nullptr;
+  }
+};
+KernelTiming g_timing;
 
 struct Allocator {
   rdkv_alloc_fn alloc = nullptr;
@@ -224,7 +241,50 @@ void hull_thresholds(const rdkv_config* cfg, const float* eps, std::vector<int>*
 
 }  // namespace
 
+namespace rdkv {
+void timing_begin(int kind, hipStream_t st) {
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  if (!g_timing.enabled) return;
+  hipEvent_t a = g_timing.get(), b = g_timing.get();
+  if (!a || !b) return;
+  (void)hipEventRecord(a, st);
+  g_timing.ev[kind].emplace_back(a, b);
+}
+void timing_end(int kind, hipStream_t st) {
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  if (!g_timing.enabled || g_timing.ev[kind].empty()) return;
+  (void)hipEventRecord(g_timing.ev[kind].back().second, st);
+}
+}  // namespace rdkv
+
 extern "C" {
+
+rdkv_status rdkv_kernel_timing_enable(int32_t enable) {
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  g_timing.enabled = enable != 0;
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* total_ms) {
+  if (kind < 0 || kind >= RDKV_TIME_KINDS || !launches || !total_ms)
+    return fail(RDKV_ERR_INVALID_ARG, "bad timing kind or null output");
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  double sum = 0.0;
+  int64_t n = 0;
+  for (auto& pr : g_timing.ev[kind]) {
+    float ms = 0.f;
+    if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+      sum += ms;
+      ++n;
+    }
+    g_timing.pool.push_back(pr.first);
+    g_timing.pool.push_back(pr.second);
+  }
+  g_timing.ev[kind].clear();
+  *launches = n;
+  *total_ms = sum;
+  return RDKV_OK;
+}
 
 const char* rdkv_version(void) { return "rdkv-mi355x 0.1 (gfx950)"; }
 const char* rdkv_last_error(void) { return g_err.c_str(); }
@@ -280,9 +340,12 @@ rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_ob
   RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
   RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
   RDKV_HIP(hipMemcpyAsync(d_wblk, wblk_off.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  {
+  TimedScope ts(RDKV_TIME_WEIGHTS, st);
   RDKV_HIP(launch_weights(*cfg, d_off, d_T, d_wblk, n_wblk, it.n_items, it.total_tokens, it.max_T,
                           static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(Q_obs), w_tok, w_ch,
                           scratch, st));
+  }
   RDKV_HIP(hipStreamSynchronize(st));   // scratch is released on return
   return RDKV_OK;
 }
@@ -311,9 +374,12 @@ rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const floa
   RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
   RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
   RDKV_HIP(hipMemcpyAsync(d_budget, budget.data(), it.n_items * sizeof(double), hipMemcpyHostToDevice, st));
+  {
+  TimedScope ts(RDKV_TIME_ALLOCATE, st);
   RDKV_HIP(launch_allocate(w_tok, d_off, d_T, d_budget, static_cast<int>(it.n_items), static_cast<int>(ht.size()),
                            ht.data(), hr.data(), 1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters,
                            bits_tok, st));
+  }
   RDKV_HIP(hipStreamSynchronize(st));
   (void)w_ch;
   (void)bits_ch;
@@ -459,6 +525,7 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
     if (kept > 0) {
       PACK_HIP(launch_tier_scatter(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_idx_base, c->d_tier_idx,
                                    static_cast<int>(n), it.max_T, st));
+      TimedScope ts(RDKV_TIME_PACK, st);
       PACK_HIP(launch_quant_pack(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), c->d_tier_idx,
                                  d_idx_base, d_counts, d_seg_off, d_tok_off, c->d_arena, static_cast<int>(n),
                                  max_count, st));
@@ -494,10 +561,15 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, 
 rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, float* lse, void* stream) {
   if (!c || !q || !out) return fail(RDKV_ERR_INVALID_ARG, "cache, q and out must not be null");
   if (c->n_items == 0) return RDKV_OK;
-  RDKV_HIP(launch_decode_tiered(c->d_chunks, static_cast<int>(c->chunks.size()), c->d_arena,
-                                static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml, c->d_slot_begin,
-                                c->d_slot_count, static_cast<int>(c->n_items), c->hq, c->hkv, out, lse,
-                                static_cast<hipStream_t>(stream)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  {
+    TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
+    RDKV_HIP(launch_decode_tiered_split(c->d_chunks, static_cast<int>(c->chunks.size()), c->d_arena,
+                                        static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml, c->hq, c->hkv,
+                                        st));
+  }
+  RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
+                                      static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));
   return RDKV_OK;
 }
 
@@ -541,7 +613,12 @@ rdkv_status rdkv_decode_attn_bf16(const void* K, const void* V, const int32_t* s
       a.row_off[i] = row_off;
       row_off += static_cast<int64_t>(seq_lens[s0 + i]) * hkv;
     }
-    RDKV_HIP(launch_decode_dense(a, g, ns, static_cast<hipStream_t>(stream)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+      TimedScope ts(RDKV_TIME_DECODE_BF16, st);
+      RDKV_HIP(launch_decode_dense_split(a, g, ns, st));
+    }
+    RDKV_HIP(launch_decode_dense_merge(a, g, ns, st));
   }
   return RDKV_OK;
 }

@@ -45,11 +45,23 @@ struct DenseArgs {
 };
 
 // ---- launchers implemented in the .hip files ------------------------------
-hipError_t launch_decode_dense(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
-hipError_t launch_decode_tiered(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                float* part_acc, float* part_ml, const int32_t* slot_begin,
-                                const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
-                                float* lse, hipStream_t st);
+hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
+hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
+hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
+                                      float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
+hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
+                                      const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
+                                      float* lse, hipStream_t st);
+
+// Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
+void timing_begin(int kind, hipStream_t st);
+void timing_end(int kind, hipStream_t st);
+struct TimedScope {
+  int kind;
+  hipStream_t st;
+  TimedScope(int k, hipStream_t s) : kind(k), st(s) { timing_begin(kind, st); }
+  ~TimedScope() { timing_end(kind, st); }
+};
 
 struct PackItemDesc;   // compress_kernels
 

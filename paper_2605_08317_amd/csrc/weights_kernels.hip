@@ -196,21 +196,25 @@ __global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
   }
 }
 
-// log-sum-exp of every window row over the key blocks of its item (log2 domain)
-__global__ void row_lse_kernel(WeightArgs a) {
-  const int item = blockIdx.x;
+// log-sum-exp of every window row over the key blocks of its item (log2 domain);
+// one wavefront per row, lanes stride over the blocks
+__global__ __launch_bounds__(256) void row_lse_kernel(WeightArgs a) {
+  const int item = blockIdx.y;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.R_pad) return;
+  const int lane = threadIdx.x & 63;
   const int T = a.item_T[item];
   const int nblk = (T + kTokPerWG - 1) / kTokPerWG;
   const int64_t b0 = a.item_blk_off[item];
-  for (int r = threadIdx.x; r < a.R_pad; r += blockDim.x) {
-    float m = kNegBig;
-    for (int b = 0; b < nblk; ++b) m = fmaxf(m, a.row_part[((b0 + b) * a.R_pad + r) * 2]);
-    float l = 0.f;
-    for (int b = 0; b < nblk; ++b)
-      l += a.row_part[((b0 + b) * a.R_pad + r) * 2 + 1] * fast_exp2(a.row_part[((b0 + b) * a.R_pad + r) * 2] - m);
-    // a padded row has no visible key: give it +inf so that exp2(x - lse) = 0
-    a.lse[static_cast<int64_t>(item) * a.R_pad + r] = (l > 0.f) ? m + __log2f(l) : INFINITY;
-  }
+  float m = kNegBig;
+  for (int b = lane; b < nblk; b += 64) m = fmaxf(m, a.row_part[((b0 + b) * a.R_pad + r) * 2]);
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  float l = 0.f;
+  for (int b = lane; b < nblk; b += 64)
+    l += a.row_part[((b0 + b) * a.R_pad + r) * 2 + 1] * fast_exp2(a.row_part[((b0 + b) * a.R_pad + r) * 2] - m);
+  for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+  // a padded row has no visible key: give it +inf so that exp2(x - lse) = 0
+  if (lane == 0) a.lse[static_cast<int64_t>(item) * a.R_pad + r] = (l > 0.f) ? m + __log2f(l) : INFINITY;
 }
 
 // AvgPool1d(kernel, stride 1, zero padding kernel/2, divisor kernel) along the keys of each item
@@ -284,7 +288,7 @@ hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off,
   if (e != hipSuccess) return e;
   dim3 grid(max_blk, static_cast<unsigned>(n_items));
   hipLaunchKernelGGL(weights_kernel<1>, grid, dim3(256), lds, st, a);
-  hipLaunchKernelGGL(row_lse_kernel, dim3(static_cast<unsigned>(n_items)), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(row_lse_kernel, dim3((a.R_pad + 3) / 4, static_cast<unsigned>(n_items)), dim3(256), 0, st, a);
   hipLaunchKernelGGL(weights_kernel<2>, grid, dim3(256), lds, st, a);
   const bool pooled = cfg.pool_kernel > 1;
   if (pooled) {

@@ -1,0 +1,116 @@
+"""Host-only checks of the C ABI: the shared library loads, exports every symbol
+include/rdkv.h declares, and rejects bad arguments before anything is launched
+(no compute call reaches a GPU here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2605_08317_amd", "librdkv.so")
+
+
+@pytest.fixture(scope="module")
+def b():
+    if not os.path.exists(LIB):
+        import __graft_entry__ as g
+        g.build()
+    from paper_2605_08317_amd import binding
+    return binding
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "rdkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(rdkv_[a-z0-9_]+)\s*\(", text))
+    return sorted(n for n in names if not n.endswith("_fn"))
+
+
+def test_library_exports_every_declared_symbol(b):
+    declared = _declared_functions()
+    assert len(declared) >= 14
+    for name in declared:
+        assert hasattr(b.lib, name), f"{name} is declared in rdkv.h but not exported"
+    assert sorted(b.EXPORTED_SYMBOLS) == declared
+    assert "gfx950" in b.rdkv_version()
+
+
+def test_config_default_matches_paper_constants(b):
+    cfg = b.Config([4096], 8, 2)
+    c = cfg.c
+    assert (c.s_obs, c.pool_kernel, c.causal, c.group_size, c.max_iters) == (32, 5, 1, 32, 64)
+    assert list(c.tiers) == [0, 2, 4, 8, 16] and c.n_tiers == 5
+    assert c.rel_tol == pytest.approx(1e-2) and c.kv_split_rk == 0.5
+    # Table 9, LLaMA-3.1-8B row (tests/golden/table9_eps.txt)
+    row = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "table9_eps.txt")) if l.startswith("LLaMA-3.1-8B")][0]
+    assert [c.eps_k[i] for i in (1, 2, 3)] == pytest.approx([float(x) for x in row[1:4]], rel=1e-6)
+    assert [c.eps_v[i] for i in (1, 2, 3)] == pytest.approx([float(x) for x in row[4:7]], rel=1e-6)
+    assert c.eps_v[0] == 1.0 and c.eps_v[4] == 0.0 and c.eps_k[0] == 1.0 and c.eps_k[4] == 0.0
+
+
+def _pack_status(b, cfg):
+    h = ctypes.c_void_p(1234)
+    st = b.lib.rdkv_pack(cfg.ref(), None, None, None, None, None, ctypes.byref(h))
+    return st, h.value, b.lib.rdkv_last_error().decode()
+
+
+def test_shape_errors_are_reported_before_any_launch(b):
+    st, h, msg = _pack_status(b, b.Config([100], 8, 2, head_dim=64))
+    assert st == 2 and h is None and "head_dim" in msg
+    st, h, msg = _pack_status(b, b.Config([100], 7, 2))
+    assert st == 2 and "multiple" in msg
+    st, h, msg = _pack_status(b, b.Config([100], 32, 2))          # g = 16
+    assert st == 2
+    st, h, msg = _pack_status(b, b.Config([-5], 8, 2))
+    assert st == 2 and "negative" in msg
+    st, h, msg = _pack_status(b, b.Config([100], 8, 2, group_size=64))
+    assert st == 2 and "group_size" in msg
+    st, h, msg = _pack_status(b, b.Config([100], 8, 2))           # null K/V/bits with tokens to pack
+    assert st == 1 and h is None
+    assert b.lib.rdkv_pack(None, None, None, None, None, None, ctypes.byref(ctypes.c_void_p())) == 1
+
+
+def test_allocate_and_compress_argument_checks(b):
+    null = None
+    cfg = b.Config([100], 8, 2)                                    # no budgets
+    assert b.lib.rdkv_allocate(cfg.ref(), null, null, null, null, null) == 1
+    cfg = b.Config([100], 8, 2, budget_bits=[-1.0])
+    assert b.lib.rdkv_allocate(cfg.ref(), null, null, null, null, null) == 1
+    cfg = b.Config([100], 8, 2, budget_bits=[1.0], tiers=[0, 4, 2])
+    assert b.lib.rdkv_allocate(cfg.ref(), null, null, null, null, null) == 1
+    cfg = b.Config([100], 8, 2, budget_bits=[1.0], tiers=[0, 3, 16])
+    assert b.lib.rdkv_allocate(cfg.ref(), null, null, null, null, null) == 1
+    cfg = b.Config([100], 8, 2, budget_bits=[1.0], max_iters=0)
+    assert b.lib.rdkv_allocate(cfg.ref(), null, null, null, null, null) == 1
+    cfg = b.Config([100], 8, 2, budget_bits=[1.0])                  # valid config, null buffers
+    assert b.lib.rdkv_allocate(cfg.ref(), null, null, null, null, null) == 1
+    h = ctypes.c_void_p()
+    cfg = b.Config([20], 8, 2, budget_bits=[1.0])                   # shorter than the observation window
+    assert b.lib.rdkv_compress(cfg.ref(), null, null, null, null, ctypes.byref(h)) == 2 and h.value is None
+    cfg = b.Config([100], 8, 2, budget_bits=[1.0], pool_kernel=4)
+    assert b.lib.rdkv_weights(cfg.ref(), null, null, null, null, null) == 1
+    cfg = b.Config([100], 8, 2, budget_bits=[1.0], s_obs=65)
+    assert b.lib.rdkv_weights(cfg.ref(), null, null, null, null, null) == 2
+
+
+def test_decode_argument_checks_and_workspace_size(b):
+    assert b.lib.rdkv_decode_attn(None, None, None, None, None) == 1
+    seq = (ctypes.c_int32 * 1)(4096)
+    assert b.lib.rdkv_decode_attn_bf16(None, None, seq, 1, 8, 2, 128, None, None, None, None, 0, None) == 1
+    assert b.lib.rdkv_decode_attn_bf16(None, None, seq, 1, 8, 2, 64, None, None, None, None, 0, None) == 2
+    assert b.rdkv_decode_bf16_workspace_bytes([4096], 8, 2) > 0
+    assert b.rdkv_decode_bf16_workspace_bytes([4096], 8, 2, head_dim=64) == 0
+    assert b.lib.rdkv_cache_export_bytes(None, 0) == 0
+    assert b.lib.rdkv_cache_stats(None, None) == 1
+    b.lib.rdkv_cache_free(None)                                     # a null handle is a no-op
+    n, ms = ctypes.c_int64(), ctypes.c_double()
+    assert b.lib.rdkv_kernel_timing_read(99, ctypes.byref(n), ctypes.byref(ms)) == 1
+    assert b.lib.rdkv_kernel_timing_read(0, ctypes.byref(n), ctypes.byref(ms)) == 0 and n.value == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0 and "one GPU" in p.stderr

@@ -23,6 +23,7 @@ function here has at least one pin that is not a retyping of its own formula.
 End-to-end accuracy on the paper's benchmarks is "parity unpinned" (the data
 sets and models are not available).
 """
+import functools
 import math
 
 import numpy as np
@@ -407,15 +408,124 @@ def canonical_item(Kh, Vh, bits_tok):
     return rec
 
 
-def physical_segments(rec, d=128):
-    """Row-major physical form of one item's canonical record.
+TILE_ROWS = 32                      # tokens per tile of a quantized tier segment
+TILE_META_BYTES = 512               # per tile: 128 fp16 scales then 128 fp16 offsets
 
-    Per tier b with n rows, padded with zero rows to np = roundup(n, 32):
-      K data  [np][d*b/8]  bit-packed rows (tier 16: little-endian bf16)
-      K meta  [np][d/32][2] fp16 (scale, offset) per group   (absent for tier 16)
-      V data, V meta        the same for V
-    Returns {b: (kd, km, vd, vm)} as uint8 arrays.
+
+@functools.lru_cache(maxsize=None)
+def tile_code_positions(bits, which):
+    """Where the code of (row r of a 32-row tile, channel c) lives inside the tile's data block.
+
+    Layout fixed by this build (the paper's own layout, App. B, is row-major per
+    token; any documented bijection serves Eq. 7).  The 64 lanes of a wavefront
+    are indexed lane = 16*quad + l16; every lane owns eight 8-slot "operands":
+      K: operand o = 4*(r // 16) + c // 32, lane = 16*((c // 8) % 4) + r % 16, slot s = c % 8
+      V: operand o = c // 16,            lane = 16*((r % 16) // 4) + c % 16,
+         slot s = 4*(r // 16) + r % 4
+    and the code of (lane, o, s) sits at
+      8-bit: byte B = 8*o + s of the lane's run, at 1024*(B // 16) + 16*lane + B % 16
+      4-bit: 32-bit word o at 1024*(o // 4) + 16*lane + 4*(o % 4), nibble s//2 + 4*(s%2)
+      2-bit: 32-bit word o//2 at 16*lane + 4*(o // 2), 2-bit field 4*(o%2) + s//2 + 8*(s%2)
+    (fields counted from the least significant bit of the little-endian word).
+    Returns (byte_offset [32,128] int64, bit_shift [32,128] int64) of each code's
+    byte and its shift inside that byte.
     """
+    assert bits in (2, 4, 8) and which in ("k", "v")
+    byte_off = np.zeros((TILE_ROWS, 128), dtype=np.int64)
+    shift = np.zeros((TILE_ROWS, 128), dtype=np.int64)
+    for r in range(TILE_ROWS):
+        for c in range(128):
+            if which == "k":
+                o, lane, sl = 4 * (r // 16) + c // 32, 16 * ((c // 8) % 4) + r % 16, c % 8
+            else:
+                o, lane, sl = c // 16, 16 * ((r % 16) // 4) + c % 16, 4 * (r // 16) + r % 4
+            if bits == 8:
+                B = 8 * o + sl
+                bit = 8 * (1024 * (B // 16) + 16 * lane + B % 16)
+            elif bits == 4:
+                bit = 8 * (1024 * (o // 4) + 16 * lane + 4 * (o % 4)) + 4 * (sl // 2 + 4 * (sl % 2))
+            else:
+                bit = 8 * (16 * lane + 4 * (o // 2)) + 2 * (4 * (o % 2) + sl // 2 + 8 * (sl % 2))
+            byte_off[r, c], shift[r, c] = bit // 8, bit % 8
+    return byte_off, shift
+
+
+@functools.lru_cache(maxsize=None)
+def tile_meta_positions(which):
+    """fp16 element index (0..255) of the scale and of the offset of (row r, group)
+    inside the tile's 512-byte metadata block (scales in elements 0..127, offsets in
+    128..255).  With mb = r // 16, quad = (r % 16) // 4, i = r % 4, j = 4*mb + i:
+      K scales  ((quad*2 + mb)*4 + grp)*4 + i        K offsets 128 + r*4 + grp
+      V scales  (quad*4 + grp)*8 + j                 V offsets 128 + (quad*4 + grp)*8 + j
+    """
+    sc = np.zeros((TILE_ROWS, 4), dtype=np.int64)
+    of = np.zeros((TILE_ROWS, 4), dtype=np.int64)
+    for r in range(TILE_ROWS):
+        mb, quad, i = r // 16, (r % 16) // 4, r % 4
+        for grp in range(4):
+            if which == "k":
+                sc[r, grp] = ((quad * 2 + mb) * 4 + grp) * 4 + i
+                of[r, grp] = 128 + r * 4 + grp
+            else:
+                sc[r, grp] = (quad * 4 + grp) * 8 + 4 * mb + i
+                of[r, grp] = 128 + (quad * 4 + grp) * 8 + 4 * mb + i
+    return sc, of
+
+
+def tile_data_bytes(bits):
+    return TILE_ROWS * 128 * bits // 8
+
+
+def pack_tiles(codes, scale_bits, off_bits, bits, which):
+    """Physical tiles of n rows (zero-padded to whole tiles).  codes uint8 [n,128];
+    scale_bits, off_bits uint16 [n,4].  Returns (data uint8 [tiles*tile_bytes],
+    meta uint8 [tiles*512])."""
+    n = codes.shape[0]
+    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    cp = np.zeros((nt * TILE_ROWS, 128), dtype=np.uint8)
+    cp[:n] = codes
+    sp = np.zeros((nt * TILE_ROWS, 4), dtype=np.uint16)
+    op = np.zeros((nt * TILE_ROWS, 4), dtype=np.uint16)
+    sp[:n], op[:n] = scale_bits, off_bits
+    byte_off, shift = tile_code_positions(bits, which)
+    sc_idx, of_idx = tile_meta_positions(which)
+    tb = tile_data_bytes(bits)
+    data = np.zeros((nt, tb), dtype=np.uint8)
+    meta = np.zeros((nt, TILE_META_BYTES // 2), dtype="<u2")
+    cp = cp.reshape(nt, TILE_ROWS, 128)
+    for t in range(nt):
+        contrib = (cp[t].astype(np.uint32) << shift.astype(np.uint32)).astype(np.uint8)
+        np.bitwise_or.at(data[t], byte_off.reshape(-1), contrib.reshape(-1))
+        meta[t, sc_idx.reshape(-1)] = sp[t * TILE_ROWS:(t + 1) * TILE_ROWS].reshape(-1)
+        meta[t, of_idx.reshape(-1)] = op[t * TILE_ROWS:(t + 1) * TILE_ROWS].reshape(-1)
+    return data.reshape(-1), meta.view(np.uint8).reshape(-1)
+
+
+def unpack_tiles(data, meta, n, bits, which):
+    """Inverse of pack_tiles for the first n rows."""
+    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    byte_off, shift = tile_code_positions(bits, which)
+    sc_idx, of_idx = tile_meta_positions(which)
+    data = np.asarray(data, dtype=np.uint8).reshape(nt, tile_data_bytes(bits))
+    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape(nt, TILE_META_BYTES // 2)
+    mask = (1 << bits) - 1
+    codes = ((data[:, byte_off] >> shift.astype(np.uint8)) & mask).astype(np.uint8)      # [nt,32,128]
+    sc = meta[:, sc_idx].astype(np.uint16)
+    of = meta[:, of_idx].astype(np.uint16)
+    return (codes.reshape(nt * TILE_ROWS, 128)[:n], sc.reshape(nt * TILE_ROWS, 4)[:n],
+            of.reshape(nt * TILE_ROWS, 4)[:n])
+
+
+def physical_segments(rec, d=128):
+    """Physical form of one item's canonical record.
+
+    Per tier b with n rows, padded with zero rows to whole 32-row tiles:
+      tier 16:      K data and V data are the bf16 rows, row-major; no metadata
+      tiers 8,4,2:  K data = tiles of 32*16*b bytes (tile_code_positions(b, 'k')),
+                    K meta = tiles of 512 bytes (tile_meta_positions('k')), same for V
+    Returns {b: (kd, km, vd, vm)} as flat uint8 arrays.
+    """
+    assert d == 128
     out = {}
     for b in PACK_ORDER:
         ent = rec[b]
@@ -423,17 +533,13 @@ def physical_segments(rec, d=128):
         npad = _round_up(n, ROW_PAD)
         segs = []
         for name in ("k", "v"):
-            data = np.zeros((npad, row_bytes(b, d)), dtype=np.uint8)
             if b == 16:
+                data = np.zeros((npad, 2 * d), dtype=np.uint8)
                 data[:n] = ent[name + "_codes"].astype("<u2").view(np.uint8).reshape(n, 2 * d)
-                meta = np.zeros((npad, 0), dtype=np.uint8)
+                segs += [data.reshape(-1), np.zeros(0, dtype=np.uint8)]
             else:
-                data[:n] = pack_codes(ent[name + "_codes"], b)
-                mm = np.zeros((npad, d // GROUP, 2), dtype="<u2")
-                mm[:n, :, 0] = ent[name + "_scale"]
-                mm[:n, :, 1] = ent[name + "_off"]
-                meta = mm.view(np.uint8).reshape(npad, meta_bytes(b, d))
-            segs += [data, meta]
+                data, meta = pack_tiles(ent[name + "_codes"], ent[name + "_scale"], ent[name + "_off"], b, name)
+                segs += [data, meta]
         out[b] = tuple(segs)
     return out
 
@@ -501,8 +607,8 @@ def stored_bytes(counts, d=128):
 
 
 def unpack_item(cache, item):
-    """Dequantised K_hat, V_hat (float64 [n_kept, d]) and positions of one item,
-    read back from the physical arena (not from the canonical record)."""
+    """Dequantised K_hat, V_hat (float64 [n_kept, d]) of one item, read back from the
+    physical arena (not from the canonical record)."""
     d = cache["d"]
     arena, seg_off, counts = cache["arena"], cache["seg_off"], cache["counts"]
     ks, vs = [], []
@@ -511,18 +617,19 @@ def unpack_item(cache, item):
         if n == 0:
             continue
         mats = []
-        for which in (0, 2):
+        for which, name in ((0, "k"), (2, "v")):
             d_off = int(seg_off[item, ti, which])
-            raw = arena[d_off:d_off + n * row_bytes(b, d)].reshape(n, row_bytes(b, d))
             if b == 16:
+                raw = arena[d_off:d_off + n * 2 * d].reshape(n, 2 * d)
                 mats.append(bf16_from_bits(raw.view("<u2").astype(np.uint16)).astype(np.float64))
             else:
+                nt = (n + TILE_ROWS - 1) // TILE_ROWS
                 m_off = int(seg_off[item, ti, which + 1])
-                meta = arena[m_off:m_off + n * meta_bytes(b, d)].view("<u2").reshape(n, d // GROUP, 2)
-                s = meta[:, :, 0].copy().view(np.float16)
-                m = meta[:, :, 1].copy().view(np.float16)
-                codes = unpack_codes(raw, b).reshape(n, d // GROUP, GROUP)
-                mats.append(dequantize_groups(codes, s, m).reshape(n, d))
+                codes, sc, of = unpack_tiles(arena[d_off:d_off + nt * tile_data_bytes(b)],
+                                             arena[m_off:m_off + nt * TILE_META_BYTES], n, b, name)
+                s = sc.copy().view(np.float16)
+                m = of.copy().view(np.float16)
+                mats.append(dequantize_groups(codes.reshape(n, d // GROUP, GROUP), s, m).reshape(n, d))
         ks.append(mats[0])
         vs.append(mats[1])
     if not ks:

@@ -1,5 +1,5 @@
 // Stage 4 of Alg. 1 on the GPU: stable per-tier partition of the token bit map and
-// group-wise quantize-and-pack into row-major tier segments.
+// group-wise quantize-and-pack into tier segments (16-bit rows row-major, quantized tiers in 32-row tiles).
 //
 // The quantizer is fp32 in a fixed operation order (this file is compiled with
 // floating-point contraction off) so that codes, scales and offsets are
@@ -8,7 +8,7 @@
 //   s  = fp16_rn((mx - mn) / Q)        Q = 2^b - 1, IEEE divide
 //   m  = fp16_rn(mn)
 //   code = clamp(rint((x - m) / s), 0, Q), all zero when s == 0
-// Codes are packed little-endian: element i of a row sits at bit i*b (App. B).
+// Codes occupy b-bit fields of little-endian words (App. B: fields at bit offsets 0,2,4,6 / 0,4 of a byte).
 #include "rdkv_internal.h"
 
 namespace rdkv {
@@ -119,40 +119,6 @@ __global__ __launch_bounds__(256) void tier_scatter_kernel(const uint8_t* __rest
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// Quantize one group of 32 values (already in registers) and store codes + metadata.
-template <int BITS>
-__device__ __forceinline__ void quant_store_group(const float (&x)[32], uint8_t* __restrict__ data,
-                                                  uint8_t* __restrict__ meta) {
-  float mn = x[0], mx = x[0];
-#pragma unroll
-  for (int i = 1; i < 32; ++i) {
-    mn = fminf(mn, x[i]);
-    mx = fmaxf(mx, x[i]);
-  }
-  mn = mn + 0.0f;   // canonical +0
-  constexpr float Q = static_cast<float>((1 << BITS) - 1);
-  const _Float16 sh = static_cast<_Float16>((mx - mn) / Q);   // round to nearest even
-  const _Float16 mh = static_cast<_Float16>(mn);
-  const float s = static_cast<float>(sh), m = static_cast<float>(mh);
-  uint32_t words[BITS];   // 32 codes * BITS bits = BITS 32-bit words
-#pragma unroll
-  for (int w = 0; w < BITS; ++w) words[w] = 0u;
-#pragma unroll
-  for (int i = 0; i < 32; ++i) {
-    float t = rintf((x[i] - m) / s);
-    t = fminf(fmaxf(t, 0.0f), Q);
-    const uint32_t code = (s == 0.0f) ? 0u : static_cast<uint32_t>(t);
-    const int bit = i * BITS;
-    words[bit >> 5] |= code << (bit & 31);
-  }
-  uint32_t* dst = reinterpret_cast<uint32_t*>(data);
-#pragma unroll
-  for (int w = 0; w < BITS; ++w) dst[w] = words[w];
-  *reinterpret_cast<uint32_t*>(meta) =
-      static_cast<uint32_t>(__builtin_bit_cast(unsigned short, sh)) |
-      (static_cast<uint32_t>(__builtin_bit_cast(unsigned short, mh)) << 16);
-}
-
 struct PackArgs {
   const uint16_t* K;
   const uint16_t* V;
@@ -165,38 +131,154 @@ struct PackArgs {
   int32_t ti;                  // which stored tier this launch packs
 };
 
-// one thread = one group of 32 channels of one kept row, for K and for V
-template <int BITS>
-__global__ __launch_bounds__(256) void quant_pack_kernel(PackArgs a) {
+// 16-bit tier: the kept bf16 rows are copied verbatim, row-major (one thread = 64 bytes of K and of V)
+__global__ __launch_bounds__(256) void copy_rows_kernel(PackArgs a) {
   const int item = blockIdx.y;
   const int n = a.counts[item * 4 + a.ti];
   const int row = blockIdx.x * 64 + (threadIdx.x >> 2);
   if (row >= n) return;
-  const int grp = threadIdx.x & 3;
+  const int part = threadIdx.x & 3;
   const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + row];
   const int64_t src_row = a.item_row_off[item] + pos;
   const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
 #pragma unroll
   for (int which = 0; which < 2; ++which) {
-    const uint16_t* src = (which == 0 ? a.K : a.V) + src_row * kHeadDim + grp * kGroup;
-    uint8_t* data = a.arena + so[which * 2] + static_cast<int64_t>(row) * (kHeadDim * BITS / 8);
-    const uint4* s4 = reinterpret_cast<const uint4*>(src);
-    if constexpr (BITS == 16) {
-      uint4* d4 = reinterpret_cast<uint4*>(data + grp * 64);
+    const uint4* s4 = reinterpret_cast<const uint4*>((which == 0 ? a.K : a.V) + src_row * kHeadDim + part * 32);
+    uint4* d4 = reinterpret_cast<uint4*>(a.arena + so[which * 2] + static_cast<int64_t>(row) * (kHeadDim * 2) + part * 64);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) d4[i] = s4[i];
-    } else {
-      float x[32];
+    for (int i = 0; i < 4; ++i) d4[i] = s4[i];
+  }
+}
+
+// (row, channel) of the code held by (lane, operand o, slot s) of a tile; see the layout notes below
+__device__ __forceinline__ void tile_rc(bool is_v, int lane, int o, int s, int* r, int* c) {
+  const int quad = lane >> 4, l16 = lane & 15;
+  if (!is_v) {
+    *r = 16 * (o >> 2) + l16;
+    *c = 32 * (o & 3) + 8 * quad + s;
+  } else {
+    *r = 16 * (s >> 2) + 4 * quad + (s & 3);
+    *c = 16 * o + l16;
+  }
+}
+
+// Quantized tiers: one workgroup = one tile of 32 kept rows, K and V.
+//
+// Tile layout (what the decode kernel's MFMA operands want).  Lanes are indexed lane = 16*quad + l16; every lane
+// owns eight 8-slot operands:
+//   K: operand o = 4*(r/16) + c/32, lane = 16*((c/8)%4) + r%16, slot s = c%8
+//   V: operand o = c/16,            lane = 16*((r%16)/4) + c%16, slot s = 4*(r/16) + r%4
+// and the code of (lane, o, s) sits at
+//   8-bit: byte B = 8o+s of the lane's run, stored at 1024*(B/16) + 16*lane + B%16
+//   4-bit: word o at 1024*(o/4) + 16*lane + 4*(o%4), nibble s/2 + 4*(s%2)
+//   2-bit: word o/2 at 16*lane + 4*(o/2), field 4*(o%2) + s/2 + 8*(s%2)
+// Metadata tile = 128 fp16 scales then 128 fp16 offsets; with mb = r/16, quad = (r%16)/4, i = r%4, j = 4mb+i:
+//   K scale ((quad*2+mb)*4+grp)*4+i, K offset 128 + 4r + grp; V scale and offset (128 +) (quad*4+grp)*8 + j.
+template <int BITS>
+__global__ __launch_bounds__(256) void quant_pack_tile_kernel(PackArgs a) {
+  constexpr int kRowStride = kHeadDim + 8;                 // bf16 elements; 272-byte rows
+  __shared__ __align__(16) uint16_t s_rows[2][kRowPad][kRowStride];
+  __shared__ __align__(16) uint8_t s_codes[2][kRowPad][kHeadDim];
+  const int item = blockIdx.y;
+  const int n = a.counts[item * 4 + a.ti];
+  const int r0 = blockIdx.x * kRowPad;
+  if (r0 >= n) return;
+  const int valid = min(kRowPad, n - r0);
+  const int tid = threadIdx.x;
+  const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
+
+  {  // gather the tile's rows: 8 threads per row, 32 bytes of K and of V each
+    const int row = tid >> 3, part = tid & 7;
+    uint4 kv[2][2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint4 v = s4[i];
-        x[8 * i + 0] = bf16_lo(v.x); x[8 * i + 1] = bf16_hi(v.x);
-        x[8 * i + 2] = bf16_lo(v.y); x[8 * i + 3] = bf16_hi(v.y);
-        x[8 * i + 4] = bf16_lo(v.z); x[8 * i + 5] = bf16_hi(v.z);
-        x[8 * i + 6] = bf16_lo(v.w); x[8 * i + 7] = bf16_hi(v.w);
+    for (int w = 0; w < 2; ++w) kv[w][0] = kv[w][1] = make_uint4(0, 0, 0, 0);
+    if (row < valid) {
+      const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + r0 + row];
+      const int64_t src = (a.item_row_off[item] + pos) * kHeadDim + part * 16;
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const uint4* p = reinterpret_cast<const uint4*>((w == 0 ? a.K : a.V) + src);
+        kv[w][0] = p[0];
+        kv[w][1] = p[1];
       }
-      uint8_t* meta = a.arena + so[which * 2 + 1] + static_cast<int64_t>(row) * 16 + grp * 4;
-      quant_store_group<BITS>(x, data + grp * (kGroup * BITS / 8), meta);
+    }
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      uint4* d = reinterpret_cast<uint4*>(&s_rows[w][row][part * 16]);
+      d[0] = kv[w][0];
+      d[1] = kv[w][1];
+    }
+  }
+  __syncthreads();
+
+  {  // quantize: one thread = one group of 32 channels of one row of K or V (fixed-order fp32)
+    const int w = tid >> 7, row = (tid >> 2) & 31, grp = tid & 3;
+    float x[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) x[i] = __uint_as_float(static_cast<uint32_t>(s_rows[w][row][grp * 32 + i]) << 16);
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int i = 1; i < 32; ++i) {
+      mn = fminf(mn, x[i]);
+      mx = fmaxf(mx, x[i]);
+    }
+    mn = mn + 0.0f;   // canonical +0
+    constexpr float Q = static_cast<float>((1 << BITS) - 1);
+    const _Float16 sh = static_cast<_Float16>((mx - mn) / Q);   // round to nearest even
+    const _Float16 mh = static_cast<_Float16>(mn);
+    const float s = static_cast<float>(sh), m = static_cast<float>(mh);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      float t = rintf((x[i] - m) / s);
+      t = fminf(fmaxf(t, 0.0f), Q);
+      s_codes[w][row][grp * 32 + i] = (s == 0.0f) ? uint8_t(0) : static_cast<uint8_t>(t);
+    }
+    if (row < valid) {
+      const int mb = row >> 4, quad = (row & 15) >> 2, i = row & 3;
+      int si, oi;
+      if (w == 0) {
+        si = ((quad * 2 + mb) * 4 + grp) * 4 + i;
+        oi = 128 + row * 4 + grp;
+      } else {
+        si = (quad * 4 + grp) * 8 + 4 * mb + i;
+        oi = 128 + si;
+      }
+      uint16_t* meta = reinterpret_cast<uint16_t*>(a.arena + so[w * 2 + 1] + static_cast<int64_t>(blockIdx.x) * 512);
+      meta[si] = __builtin_bit_cast(unsigned short, sh);
+      meta[oi] = __builtin_bit_cast(unsigned short, mh);
+    }
+  }
+  __syncthreads();
+
+  // emit the tile's data words in their physical order (coalesced 32-bit stores)
+  constexpr int kWords = kRowPad * kHeadDim * BITS / 32;      // 1024 / 512 / 256
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[w * 2] +
+                                                static_cast<int64_t>(blockIdx.x) * (kRowPad * kHeadDim * BITS / 8));
+    for (int word = tid; word < kWords; word += 256) {
+      const int chunk = word >> 8, lane = (word >> 2) & 63, dd = word & 3;
+      uint32_t out = 0;
+      constexpr int kFields = 32 / BITS;
+#pragma unroll
+      for (int f = 0; f < kFields; ++f) {
+        int o, sl;
+        if constexpr (BITS == 8) {
+          const int B = 16 * chunk + 4 * dd + f;
+          o = B >> 3;
+          sl = B & 7;
+        } else if constexpr (BITS == 4) {
+          o = 4 * chunk + dd;
+          sl = (f < 4) ? 2 * f : 2 * (f - 4) + 1;
+        } else {
+          o = 2 * dd + ((f & 7) >> 2);
+          sl = 2 * (f & 3) + (f >> 3);
+        }
+        int r, c;
+        tile_rc(w == 1, lane, o, sl, &r, &c);
+        out |= static_cast<uint32_t>(s_codes[w][r][c]) << (f * BITS);
+      }
+      dst[word] = out;
     }
   }
 }
@@ -232,12 +314,13 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
   for (int ti = 0; ti < 4; ++ti) {
     if (max_count[ti] == 0) continue;
     PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti};
-    dim3 grid((max_count[ti] + 63) / 64, n_items), block(256);
+    dim3 grid_rows((max_count[ti] + 63) / 64, n_items), grid_tiles((max_count[ti] + kRowPad - 1) / kRowPad, n_items);
+    dim3 block(256);
     switch (ti) {
-      case 0: hipLaunchKernelGGL(quant_pack_kernel<16>, grid, block, 0, st, a); break;
-      case 1: hipLaunchKernelGGL(quant_pack_kernel<8>, grid, block, 0, st, a); break;
-      case 2: hipLaunchKernelGGL(quant_pack_kernel<4>, grid, block, 0, st, a); break;
-      default: hipLaunchKernelGGL(quant_pack_kernel<2>, grid, block, 0, st, a); break;
+      case 0: hipLaunchKernelGGL(copy_rows_kernel, grid_rows, block, 0, st, a); break;
+      case 1: hipLaunchKernelGGL(quant_pack_tile_kernel<8>, grid_tiles, block, 0, st, a); break;
+      case 2: hipLaunchKernelGGL(quant_pack_tile_kernel<4>, grid_tiles, block, 0, st, a); break;
+      default: hipLaunchKernelGGL(quant_pack_tile_kernel<2>, grid_tiles, block, 0, st, a); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

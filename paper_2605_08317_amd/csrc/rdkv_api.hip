@@ -496,6 +496,14 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
     slot_count[i] = static_cast<int32_t>(c->chunks.size()) - slot_begin[i];
   }
   const int64_t n_chunks = static_cast<int64_t>(c->chunks.size());
+  // launch order: 16-bit chunks first (their own kernel), then quantized chunks, largest first
+  std::stable_sort(c->chunks.begin(), c->chunks.end(), [](const Chunk& x, const Chunk& y) {
+    const bool x16 = x.tier == 16, y16 = y.tier == 16;
+    if (x16 != y16) return x16;
+    return static_cast<int64_t>(x.rows) * x.tier > static_cast<int64_t>(y.rows) * y.tier;
+  });
+  c->n_chunks16 = 0;
+  for (const Chunk& ch : c->chunks) c->n_chunks16 += ch.tier == 16;
 
   // ---- allocate what the cache owns ------------------------------------------------------
   c->d_arena = static_cast<uint8_t*>(al.get(c->arena_bytes));
@@ -564,9 +572,11 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
   hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
-    RDKV_HIP(launch_decode_tiered_split(c->d_chunks, static_cast<int>(c->chunks.size()), c->d_arena,
-                                        static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml, c->hq, c->hkv,
-                                        st));
+    const int n16 = static_cast<int>(c->n_chunks16), nq = static_cast<int>(c->chunks.size()) - n16;
+    RDKV_HIP(launch_decode_tiered_split(c->d_chunks, n16, c->d_arena, static_cast<const uint16_t*>(q),
+                                        c->d_part_acc, c->d_part_ml, c->hq, c->hkv, st));
+    RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nq, c->d_arena, static_cast<const uint16_t*>(q), c->d_part_acc,
+                                 c->d_part_ml, c->hq, c->hkv, st));
   }
   RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
                                       static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));

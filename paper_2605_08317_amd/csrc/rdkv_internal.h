@@ -53,6 +53,9 @@ hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_m
                                       const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
                                       float* lse, hipStream_t st);
 
+hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
+                               float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
+
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);
 void timing_end(int kind, hipStream_t st);
@@ -79,6 +82,7 @@ struct rdkv_cache {
   std::vector<rdkv::Chunk> chunks;
   int64_t arena_bytes = 0;
   int64_t kept_total = 0;
+  int64_t n_chunks16 = 0;               // leading chunks of the 16-bit tier
   // device memory (owned)
   uint8_t* d_arena = nullptr;
   int32_t* d_tier_idx = nullptr;        // [kept_total]

@@ -612,3 +612,71 @@ def test_compress_tokenwise_end_to_end_small():
     q = rand_bf16(rng, (1, Hkv * g, d))
     out, lse = O.decode(cache, q)
     assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+
+
+# ----------------------------------------------------------------------------
+# tile layout of the quantized tiers (a documented bijection of the canonical record)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("which", ["k", "v"])
+def test_tile_positions_are_a_bijection_onto_the_tile(bits, which):
+    byte_off, shift = O.tile_code_positions(bits, which)
+    tb = O.tile_data_bytes(bits)
+    assert tb == 32 * 128 * bits // 8
+    pos = byte_off * 8 + shift
+    assert pos.min() == 0 and pos.max() == tb * 8 - bits
+    assert len(np.unique(pos)) == 32 * 128                      # no two codes share a field
+    assert np.all(shift % bits == 0)                            # App. B: fields at offsets 0,2,4,6 / 0,4 / 0
+    sc, of = O.tile_meta_positions(which)
+    both = np.concatenate([sc.reshape(-1), of.reshape(-1)])
+    assert sorted(both.tolist()) == list(range(256))            # 128 scales then 128 offsets, each slot used once
+    assert sc.max() < 128 <= of.min()
+
+
+def test_tile_positions_hand_checked():
+    # K, 8-bit: row 0, channel 0 -> lane 0, operand 0, slot 0 -> byte 0; channel 8 -> quad 1 -> lane 16 -> byte 256;
+    # channel 32 -> operand 1 -> byte 8 of lane 0; row 16 -> operand 4 -> B = 32 -> third 1 KiB chunk
+    bo, sh = O.tile_code_positions(8, "k")
+    assert (bo[0, 0], bo[0, 8], bo[0, 32], bo[16, 0], bo[1, 0], bo[0, 1]) == (0, 256, 8, 2048, 16, 1)
+    # K, 4-bit: slots pair up as (n0,n4),(n1,n5),..: channel 1 (slot 1) is nibble 4 -> byte 2 low nibble
+    bo, sh = O.tile_code_positions(4, "k")
+    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (0, 4)
+    assert (bo[0, 32], sh[0, 32]) == (4, 0)                     # group 1 -> next 32-bit word of lane 0
+    assert bo[16, 0] == 1024                                    # second m-block -> word 4 -> second chunk
+    # K, 2-bit: operand 1 (group 1) shares the word of operand 0 in fields 4..7 and 12..15
+    bo, sh = O.tile_code_positions(2, "k")
+    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (0, 2)
+    assert (bo[0, 32], sh[0, 32]) == (1, 0) and (bo[0, 33], sh[0, 33]) == (3, 0)
+    # V, 8-bit: the eight slots of a lane are tokens {0..3, 16..19} + 4*quad of one channel
+    bo, sh = O.tile_code_positions(8, "v")
+    assert [int(bo[r, 0]) for r in (0, 1, 2, 3, 16, 17, 18, 19)] == list(range(8))
+    assert bo[4, 0] == 16 * 16 and bo[0, 1] == 16 and bo[0, 16] == 8     # quad 1; channel 1 -> lane 1; n-tile 1
+    sc, of = O.tile_meta_positions("k")
+    assert sc[0].tolist() == [0, 4, 8, 12] and sc[1, 0] == 1 and sc[16, 0] == 16 and sc[4, 0] == 32
+    assert of[0].tolist() == [128, 129, 130, 131] and of[31, 3] == 255
+    sc, of = O.tile_meta_positions("v")
+    assert sc[0].tolist() == [0, 8, 16, 24] and sc[16, 0] == 4 and sc[4, 0] == 32 and of[0, 0] == 128
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_tile_pack_roundtrip_and_padding(bits):
+    rng = np.random.default_rng(30 + bits)
+    n = 75                                                       # two full tiles and a ragged third
+    codes = rng.integers(0, 1 << bits, (n, 128)).astype(np.uint8)
+    sc = rng.integers(0, 65536, (n, 4)).astype(np.uint16)
+    of = rng.integers(0, 65536, (n, 4)).astype(np.uint16)
+    for which in ("k", "v"):
+        data, meta = O.pack_tiles(codes, sc, of, bits, which)
+        assert data.size == 3 * O.tile_data_bytes(bits) and meta.size == 3 * 512
+        c2, s2, o2 = O.unpack_tiles(data, meta, n, bits, which)
+        np.testing.assert_array_equal(c2, codes)
+        np.testing.assert_array_equal(s2, sc)
+        np.testing.assert_array_equal(o2, of)
+        # rows beyond n are zero rows
+        c3, s3, o3 = O.unpack_tiles(data, meta, 96, bits, which)
+        assert not c3[n:].any() and not s3[n:].any() and not o3[n:].any()
+    # a single code lands in exactly one field
+    one = np.zeros((1, 128), np.uint8)
+    one[0, 5] = (1 << bits) - 1
+    data, _ = O.pack_tiles(one, np.zeros((1, 4), np.uint16), np.zeros((1, 4), np.uint16), bits, "k")
+    assert int(np.unpackbits(data).sum()) == bits

@@ -15,6 +15,8 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # the quantizer must be reproducible bit for bit: no implicit fused multiply-add
     "-ffp-contract=off",
+    # MFMA results stay in ordinary vector registers (no copies through the accumulation registers)
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]

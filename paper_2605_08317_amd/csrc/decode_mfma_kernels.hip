@@ -29,6 +29,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWG = 256;
 constexpr int kWaves = 4;
+constexpr int kQBytes = 5 * 64 * 16;   // LDS copy of the query operands
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLogitScale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 
@@ -44,7 +45,11 @@ union Pack8 {
 // fields of a word -> pair of exact fp16 integers: (w & mask) | 0x6400 is 1024 + code * 2^shift in each half
 template <int SHIFT>
 __device__ __forceinline__ uint32_t field_pair(uint32_t w, uint32_t mask) {
-  const uint32_t x = (w & mask) | 0x64006400u;
+  // one v_and_or_b32: the mask rides in a scalar register, the fp16 pattern in a vector register
+  // (a gfx9 VALU instruction may read only one scalar or literal operand)
+  uint32_t x;
+  const uint32_t magic = 0x64006400u;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(x) : "v"(w), "s"(mask), "v"(magic));
   const half2v v = __builtin_bit_cast(half2v, x);
   constexpr float inv = 1.0f / static_cast<float>(1 << SHIFT);
   const half2v scale = {static_cast<_Float16>(inv), static_cast<_Float16>(inv)};
@@ -90,27 +95,53 @@ __device__ __forceinline__ half8 unpack_operand(const uint4 (&raw)[TIER / 2], in
   return r.h;
 }
 
-template <int TIER>
-struct TileRaw {
-  uint4 k[TIER / 2];
-  uint4 v[TIER / 2];
-  uint4 meta;
+// Raw bytes of NT consecutive tiles held by one lane.  K and V registers are refilled right after their last
+// use (K after the logits, V after the second product), so loads of the next tiles overlap the rest of the
+// iteration without a second register buffer.
+template <int TIER, int NT>
+struct SuperRaw {
+  uint4 k[NT][TIER / 2];
+  uint4 v[NT][TIER / 2];
+  uint4 kmeta;   // NT == 2: K metadata of tile (lane / 32); NT == 1: K metadata (lanes 0..31) and V metadata (32..63)
+  uint4 vmeta;   // NT == 2 only
 };
 
-template <int TIER>
-__device__ __forceinline__ void load_tile(TileRaw<TIER>& t, const uint8_t* __restrict__ kd,
-                                          const uint8_t* __restrict__ km, const uint8_t* __restrict__ vd,
-                                          const uint8_t* __restrict__ vm, int tile, int lane) {
+template <int TIER, int NT>
+__device__ __forceinline__ void load_k(SuperRaw<TIER, NT>& r, const uint8_t* __restrict__ kd,
+                                       const uint8_t* __restrict__ km, const uint8_t* __restrict__ vm, int st,
+                                       int ntiles, int lane) {
   constexpr int kTileBytes = kRowPad * kHeadDim * TIER / 8;
-  const uint8_t* kp = kd + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
-  const uint8_t* vp = vd + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
 #pragma unroll
-  for (int i = 0; i < TIER / 2; ++i) {
-    t.k[i] = *reinterpret_cast<const uint4*>(kp + i * 1024);
-    t.v[i] = *reinterpret_cast<const uint4*>(vp + i * 1024);
+  for (int u = 0; u < NT; ++u) {
+    const int tile = min(st * NT + u, ntiles - 1);
+    const uint8_t* kp = kd + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
+#pragma unroll
+    for (int i = 0; i < TIER / 2; ++i) r.k[u][i] = *reinterpret_cast<const uint4*>(kp + i * 1024);
   }
-  const uint8_t* mp = (lane < 32 ? km : vm) + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16;
-  t.meta = *reinterpret_cast<const uint4*>(mp);
+  if constexpr (NT == 2) {
+    const int tile = min(st * 2 + (lane >> 5), ntiles - 1);
+    r.kmeta = *reinterpret_cast<const uint4*>(km + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16);
+  } else {
+    const int tile = min(st, ntiles - 1);
+    r.kmeta = *reinterpret_cast<const uint4*>((lane < 32 ? km : vm) + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16);
+  }
+}
+
+template <int TIER, int NT>
+__device__ __forceinline__ void load_v(SuperRaw<TIER, NT>& r, const uint8_t* __restrict__ vd,
+                                       const uint8_t* __restrict__ vm, int st, int ntiles, int lane) {
+  constexpr int kTileBytes = kRowPad * kHeadDim * TIER / 8;
+#pragma unroll
+  for (int u = 0; u < NT; ++u) {
+    const int tile = min(st * NT + u, ntiles - 1);
+    const uint8_t* vp = vd + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
+#pragma unroll
+    for (int i = 0; i < TIER / 2; ++i) r.v[u][i] = *reinterpret_cast<const uint4*>(vp + i * 1024);
+  }
+  if constexpr (NT == 2) {
+    const int tile = min(st * 2 + (lane >> 5), ntiles - 1);
+    r.vmeta = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16);
+  }
 }
 
 struct QOperands {
@@ -118,18 +149,28 @@ struct QOperands {
   half8 qsum;      // B operand of the K-offset product: slots 0..3 group sums (hi), 4..7 (lo); quad 0 only
 };
 
-template <int TIER>
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int TIER, int NT>
 __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ km,
                                               const uint8_t* __restrict__ vd, const uint8_t* __restrict__ vm,
-                                              int rows, const QOperands& qo, int g, float* __restrict__ part_acc,
+                                              int rows, int g, float* __restrict__ part_acc,
                                               float* __restrict__ part_ml, uint8_t* smem) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: tile indices and branches stay uniform
   const int quad = lane >> 4, l16 = lane & 15;
-  uint8_t* s_meta = smem + wave * 1024;                            // this wavefront's metadata staging
-  float* s_ml = reinterpret_cast<float*>(smem + kWaves * 1024);    // [4][16][2]
+  const uint8_t* s_q = smem + lane * 16;                           // query operands: [5][64 lanes][16 B]
+  uint8_t* s_meta_k = smem + kQBytes + wave * 2048;                // this wavefront's metadata staging
+  uint8_t* s_meta_v = s_meta_k + NT * 512;
+  float* s_ml = reinterpret_cast<float*>(smem + kQBytes + kWaves * 2048);    // [4][16][2]
   float* s_acc = s_ml + kWaves * 16 * 2;                           // [4][g][128]
 
   const int ntiles = (rows + kRowPad - 1) / kRowPad;
+  const int nsuper = (ntiles + NT - 1) / NT;
   float m_run = kNegBig, l_run = 0.f;
   floatx4 acc[8], acc_off;
 #pragma unroll
@@ -137,62 +178,72 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   acc_off = floatx4{0.f, 0.f, 0.f, 0.f};
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-  TileRaw<TIER> cur, nxt;
-  if (wave < ntiles) load_tile<TIER>(cur, kd, km, vd, vm, wave, lane);
-  for (int t = wave; t < ntiles; t += kWaves) {
-    const bool more = t + kWaves < ntiles;
-    if (more) load_tile<TIER>(nxt, kd, km, vd, vm, t + kWaves, lane);
+  SuperRaw<TIER, NT> raw;
+  if (wave < nsuper) {
+    load_k<TIER, NT>(raw, kd, km, vm, wave, ntiles, lane);
+    load_v<TIER, NT>(raw, vd, vm, wave, ntiles, lane);
+  }
+  for (int st = wave; st < nsuper; st += kWaves) {
+    const bool more = st + kWaves < nsuper;
 
-    // stage the tile's metadata (K: bytes 0..511, V: 512..1023) for broadcast reads
-    *reinterpret_cast<uint4*>(s_meta + lane * 16) = cur.meta;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // stage the metadata for broadcast reads (K tiles at s_meta_k + 512u, V tiles at s_meta_v + 512u)
+    *reinterpret_cast<uint4*>(s_meta_k + lane * 16) = raw.kmeta;
+    wave_lds_sync();
 
-    // ---- logits: x[mb][i] for token 16mb + 4quad + i, head l16 ------------------------------
-    float x[2][4];
-    {
+    // ---- logits: x[u][mb][i] for token 32(st NT + u) + 16mb + 4quad + i, head l16 -----------
+    float x[NT][2][4];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
       Pack8 ks[4];   // scales of (mb, grp, i): 32 fp16
 #pragma unroll
-      for (int j = 0; j < 4; ++j) ks[j].q = *reinterpret_cast<const uint4*>(s_meta + quad * 64 + j * 16);
+      for (int j = 0; j < 4; ++j) ks[j].q = *reinterpret_cast<const uint4*>(s_meta_k + u * 512 + quad * 64 + j * 16);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
         // offsets x group sums of q
-        const uint2 mo = *reinterpret_cast<const uint2*>(s_meta + 256 + (mb * 16 + l16) * 8);
+        const uint2 mo = *reinterpret_cast<const uint2*>(s_meta_k + u * 512 + 256 + (mb * 16 + l16) * 8);
         Pack8 a_off;
         a_off.u[0] = a_off.u[2] = quad == 0 ? mo.x : 0u;
         a_off.u[1] = a_off.u[3] = quad == 0 ? mo.y : 0u;
-        const floatx4 d_off = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_off.h, qo.qsum, zero4, 0, 0, 0);
+        const floatx4 d_off = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_off.h, *reinterpret_cast<const half8*>(s_q + 4 * 1024), zero4, 0, 0, 0);
         float sum[4] = {d_off[0], d_off[1], d_off[2], d_off[3]};
 #pragma unroll
         for (int grp = 0; grp < 4; ++grp) {
-          const half8 a = unpack_operand<TIER>(cur.k, mb * 4 + grp);
-          const floatx4 dd = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qo.q[grp], zero4, 0, 0, 0);
+          const half8 a = unpack_operand<TIER>(raw.k[u], mb * 4 + grp);
+          const floatx4 dd = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, *reinterpret_cast<const half8*>(s_q + grp * 1024), zero4, 0, 0, 0);
           const int e = (mb * 4 + grp) * 4;           // scale index of i = 0
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             sum[i] = __builtin_fmaf(static_cast<float>(ks[e >> 3].h[(e & 7) + i]), dd[i], sum[i]);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[mb][i] = sum[i] * kLogitScale;
+        for (int i = 0; i < 4; ++i) x[u][mb][i] = sum[i];   // raw q.k; the 1/sqrt(d) and log2(e) factors enter at the exp
       }
     }
-    if (t == ntiles - 1) {   // padded rows of the last tile
+    if (more) load_k<TIER, NT>(raw, kd, km, vm, st + kWaves, ntiles, lane);   // K registers are free again
+
+    if ((st + 1) * NT * kRowPad > rows) {   // padded rows (and a missing second tile) of the last super-tile
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+      for (int u = 0; u < NT; ++u)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (t * kRowPad + 16 * mb + 4 * quad + i >= rows) x[mb][i] = -INFINITY;
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if ((st * NT + u) * kRowPad + 16 * mb + 4 * quad + i >= rows) x[u][mb][i] = -INFINITY;
     }
 
     // ---- online softmax (head l16; the four quads hold different tokens) ----------------------
-    float mt = fmaxf(fmaxf(fmaxf(x[0][0], x[0][1]), fmaxf(x[0][2], x[0][3])),
-                     fmaxf(fmaxf(x[1][0], x[1][1]), fmaxf(x[1][2], x[1][3])));
+    float mt = kNegBig;
+#pragma unroll
+    for (int u = 0; u < NT; ++u)
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mt = fmaxf(mt, x[u][mb][i]);
     mt = fmaxf(mt, __shfl_xor(mt, 16));
     mt = fmaxf(mt, __shfl_xor(mt, 32));
     const float m_new = fmaxf(m_run, mt);
     if (__any(m_new != m_run)) {
-      const float alpha = fast_exp2(m_run - m_new);
+      const float alpha = fast_exp2((m_run - m_new) * kLogitScale);
       l_run *= alpha;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -203,49 +254,55 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
       }
       m_run = m_new;
     }
-    float p[8];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        p[mb * 4 + i] = fast_exp2(x[mb][i] - m_run);
-        l_run += p[mb * 4 + i];
-      }
 
-    // ---- P V: slot j = 4mb + i of this lane is token 16mb + 4quad + i --------------------------
-    {
+    if constexpr (NT == 2) {
+      *reinterpret_cast<uint4*>(s_meta_v + lane * 16) = raw.vmeta;
+      wave_lds_sync();
+    }
+    // ---- P V: slot j = 4mb + i of this lane is token 16mb + 4quad + i of tile u ----------------
+    const float neg_mc = -m_run * kLogitScale;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      float p[8];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          p[mb * 4 + i] = fast_exp2(__builtin_fmaf(x[u][mb][i], kLogitScale, neg_mc));
+          l_run += p[mb * 4 + i];
+        }
       Pack8 ph;
 #pragma unroll
       for (int j = 0; j < 4; ++j) ph.p[j] = half2v{static_cast<_Float16>(p[2 * j]), static_cast<_Float16>(p[2 * j + 1])};
       Pack8 voff;
-      voff.q = *reinterpret_cast<const uint4*>(s_meta + 512 + 256 + (quad * 4 + (l16 & 3)) * 16);
+      voff.q = *reinterpret_cast<const uint4*>(s_meta_v + u * 512 + 256 + (quad * 4 + (l16 & 3)) * 16);
       if (l16 >= 4) voff.q = make_uint4(0, 0, 0, 0);
       acc_off = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph.h, voff.h, acc_off, 0, 0, 0);
 #pragma unroll
       for (int grp = 0; grp < 4; ++grp) {
         Pack8 vs, pa;
-        vs.q = *reinterpret_cast<const uint4*>(s_meta + 512 + (quad * 4 + grp) * 16);
+        vs.q = *reinterpret_cast<const uint4*>(s_meta_v + u * 512 + (quad * 4 + grp) * 16);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          pa.p[j] = half2v{static_cast<_Float16>(p[2 * j] * static_cast<float>(vs.h[2 * j])),
-                           static_cast<_Float16>(p[2 * j + 1] * static_cast<float>(vs.h[2 * j + 1]))};
+          pa.p[j] = half2v{static_cast<_Float16>(__builtin_fmaf(static_cast<float>(vs.h[2 * j]), p[2 * j], 0.0f)),
+                           static_cast<_Float16>(__builtin_fmaf(static_cast<float>(vs.h[2 * j + 1]), p[2 * j + 1], 0.0f))};
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
           const int nt = grp * 2 + h2;
-          const half8 b = unpack_operand<TIER>(cur.v, nt);
+          const half8 b = unpack_operand<TIER>(raw.v[u], nt);
           acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa.h, b, acc[nt], 0, 0, 0);
         }
       }
     }
-    __builtin_amdgcn_wave_barrier();   // all reads of s_meta are issued before the next tile overwrites it
-    if (more) cur = nxt;
+    __builtin_amdgcn_wave_barrier();   // all reads of the staging area are issued before it is overwritten
+    if (more) load_v<TIER, NT>(raw, vd, vm, st + kWaves, ntiles, lane);       // V registers are free again
   }
 
   // ---- merge the 4 wavefronts; acc[nt][i] is head 4quad+i, channel 16nt + l16 -----------------
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (quad == 0) {
-    s_ml[(wave * 16 + l16) * 2] = m_run;
+    s_ml[(wave * 16 + l16) * 2] = m_run * kLogitScale;   // running maximum in the log2 domain from here on
     s_ml[(wave * 16 + l16) * 2 + 1] = l_run;
   }
   __syncthreads();
@@ -294,6 +351,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
 }
 
+template <int TIER_SEL>
 __global__ __launch_bounds__(kWG) void decode_tiles_kernel(const Chunk* __restrict__ chunks,
                                                            const uint8_t* __restrict__ arena,
                                                            const uint16_t* __restrict__ q, float* part_acc,
@@ -334,16 +392,25 @@ __global__ __launch_bounds__(kWG) void decode_tiles_kernel(const Chunk* __restri
     qo.qsum[4 + grp] = quad == 0 ? lo : static_cast<_Float16>(0.0f);
   }
 
+  if (threadIdx.x < 64) {
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) *reinterpret_cast<half8*>(smem + grp * 1024 + lane * 16) = qo.q[grp];
+    *reinterpret_cast<half8*>(smem + 4 * 1024 + lane * 16) = qo.qsum;
+  }
+  __syncthreads();
+
   float* pa = part_acc + static_cast<int64_t>(ch.slot) * g * kHeadDim;
   float* pm = part_ml + static_cast<int64_t>(ch.slot) * g * 2;
   const uint8_t* kd = arena + ch.k_data;
   const uint8_t* km = arena + ch.k_meta;
   const uint8_t* vd = arena + ch.v_data;
   const uint8_t* vm = arena + ch.v_meta;
-  switch (ch.tier) {
-    case 8: process_tiles<8>(kd, km, vd, vm, ch.rows, qo, g, pa, pm, smem); break;
-    case 4: process_tiles<4>(kd, km, vd, vm, ch.rows, qo, g, pa, pm, smem); break;
-    default: process_tiles<2>(kd, km, vd, vm, ch.rows, qo, g, pa, pm, smem); break;
+  // TIER_SEL == 0: any quantized tier in one launch; otherwise the launch holds chunks of one tier only
+  const int tier = TIER_SEL == 0 ? ch.tier : TIER_SEL;
+  switch (tier) {
+    case 8: process_tiles<8, 1>(kd, km, vd, vm, ch.rows, g, pa, pm, smem); break;
+    case 4: process_tiles<4, 1>(kd, km, vd, vm, ch.rows, g, pa, pm, smem); break;
+    default: process_tiles<2, 1>(kd, km, vd, vm, ch.rows, g, pa, pm, smem); break;
   }
 }
 
@@ -353,9 +420,14 @@ hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t*
                                float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   const int g = hq / hkv;
-  const size_t lds = kWaves * 1024 + kWaves * 16 * 2 * sizeof(float) + static_cast<size_t>(kWaves) * g * kHeadDim * sizeof(float);
-  hipLaunchKernelGGL(decode_tiles_kernel, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
+  const size_t lds = kQBytes + kWaves * 2048 + kWaves * 16 * 2 * sizeof(float) + static_cast<size_t>(kWaves) * g * kHeadDim * sizeof(float);
+  hipLaunchKernelGGL(decode_tiles_kernel<0>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
                      hq, hkv);
+  if (false) {
+    hipLaunchKernelGGL(decode_tiles_kernel<8>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml, hq, hkv);
+    hipLaunchKernelGGL(decode_tiles_kernel<4>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml, hq, hkv);
+    hipLaunchKernelGGL(decode_tiles_kernel<2>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml, hq, hkv);
+  }
   return hipGetLastError();
 }
 

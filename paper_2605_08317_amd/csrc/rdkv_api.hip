@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -466,8 +467,8 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   c->kept_total = kept;
 
   // byte-balanced chunks: every workgroup streams about the same number of stored bytes
-  const int64_t target_chunks = 2048;
-  const int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>(32 << 10, stored / target_chunks));
+  int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>(32 << 10, stored / 2048));
+  if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
   for (int64_t i = 0; i < n; ++i) {
     slot_begin[i] = static_cast<int32_t>(c->chunks.size());

@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--budget", type=float, default=None, help="override the average bits/element")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch the per-layer calls eagerly")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="counter-collection mode for `rocprofv3 --pmc`: build the caches, run --steps eager decode "
+                         "steps, the batched launch, the bf16 path and a 1 GiB device-to-device copy, then exit")
     return ap.parse_args()
 
 
@@ -48,6 +51,31 @@ def timed_ms(fn, steps, torch):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / steps
+
+
+def pmc_probe(args, torch, b, step_eager, K_all, V_all, Qobs_all, q_all, Ks, Vs, q_l, outs, lses,
+              T, hq, hkv, L, budgets, wl):
+    """The launches whose HBM counters are wanted, eagerly and nothing else.  The copy of known size calibrates
+    the counter's unit: hipMemcpyAsync device-to-device of 1 GiB reads 2^30 bytes and writes 2^30 bytes."""
+    for _ in range(args.steps):
+        step_eager()
+    cfg_b = b.Config([T] * L, hq, hkv, budget_bits=budgets * L, s_obs=wl.s_obs)
+    cache_b = b.rdkv_compress(cfg_b, K_all, V_all, Qobs_all)
+    out_b = torch.empty((L, hq, 128), dtype=torch.float32, device="cuda")
+    lse_b = torch.empty((L, hq), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        b.rdkv_decode_attn(cache_b, q_all, out_b, lse_b)
+    ws = torch.empty(b.rdkv_decode_bf16_workspace_bytes([T], hq, hkv), dtype=torch.uint8, device="cuda")
+    for l in range(L):
+        b.rdkv_decode_attn_bf16(Ks[l], Vs[l], [T], hq, hkv, q_l[l], out=outs[l], lse=lses[l], workspace=ws)
+    n = 1 << 30
+    src = K_all.view(torch.uint8)[:n]
+    dst = V_all.view(torch.uint8)[n:2 * n] if V_all.numel() * 2 >= 2 * n else torch.empty(n, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_probe": True, "per_layer_steps": args.steps, "layers": L, "copy_bytes": n,
+                      "stored_bytes_per_layer": sum(c_.stats()["stored_bytes"] for c_ in [cache_b]) / L}))
 
 
 def main():
@@ -123,6 +151,10 @@ def main():
     for _ in range(max(1, args.warmup)):
         step_eager()
     torch.cuda.synchronize()
+    if args.pmc_probe:
+        pmc_probe(args, torch, b, step_eager, K_all, V_all, Qobs_all, q_all, Ks, Vs, q_l, outs, lses,
+                  T, hq, hkv, L, budgets, wl)
+        return
     if args.no_graph:
         step = step_eager
     else:
@@ -188,12 +220,15 @@ def main():
         nb, msb = b.rdkv_kernel_timing_read(b.RDKV_TIME_DECODE_TIERED)
         b.rdkv_kernel_timing_enable(False)
         kb_ms = msb / max(nb, 1)
-        same = bool(torch.allclose(out_b.view(L, 1, hq, d), outs, rtol=1e-3, atol=1e-5))
+        # the two launches split the rows differently, so they agree to rounding, not bit for bit
+        ref_n = outs.view(L, hq, d).abs().amax(dim=-1)
+        diff = ((out_b - outs.view(L, hq, d)).abs().amax(dim=-1) / ref_n).max().item()
+        same = bool(diff <= 1e-3)
         bytes_b = st_b["stored_bytes"] + qo_bytes
         batched = {"launch": f"{L} sequences x {T} tokens in one launch", "ms": ms_b, "kernel_ms": kb_ms,
                    "bytes": bytes_b, "achieved_gbs": bytes_b / (kb_ms * 1e-3) / 1e9,
                    "frac": bytes_b / (kb_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "n_chunks": st_b["n_chunks"],
-                   "matches_per_layer_output": same}
+                   "matches_per_layer_output": same, "max_rel_diff_vs_per_layer": diff}
         cache_b.free()
     except Exception as e:  # reported, never hidden
         batched = {"error": repr(e)}
@@ -230,11 +265,15 @@ def main():
                "compress_ms_scaled": t_comp * scale * 1e3,
                "gpu_vs_oracle_sample_max_abs_diff": float(np.abs(got - o_ref[0]).max())}
 
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
+    # calibrated against a copy of known size); null when the summary is absent
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "decode_tiered_traffic.json")
-    if os.path.exists(tpath):
+    tpath = os.path.join(ROOT, "profiles", "decode_stack128k_pmc_traffic.txt")
+    if os.path.exists(tpath) and args.workload == "stack128k" and not (args.ctx or args.layers or args.budget):
         with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+            for line in f:
+                if line.startswith("hbm_bytes_per_launch"):
+                    traffic = float(line.split("=")[1])
 
     result = {
         "metric": "decode-attn step latency at 128K ctx (32-layer stack, compressed KV), 1 MI355X",

@@ -422,11 +422,17 @@ def tile_code_positions(bits, which):
       K: operand o = 4*(r // 16) + c // 32, lane = 16*((c // 8) % 4) + r % 16, slot s = c % 8
       V: operand o = c // 16,            lane = 16*((r % 16) // 4) + c % 16,
          slot s = 4*(r // 16) + r % 4
-    and the code of (lane, o, s) sits at
-      8-bit: byte B = 8*o + s of the lane's run, at 1024*(B // 16) + 16*lane + B % 16
-      4-bit: 32-bit word o at 1024*(o // 4) + 16*lane + 4*(o % 4), nibble s//2 + 4*(s%2)
-      2-bit: 32-bit word o//2 at 16*lane + 4*(o // 2), 2-bit field 4*(o%2) + s//2 + 8*(s%2)
-    (fields counted from the least significant bit of the little-endian word).
+    The lane's data is a run of 32-bit words; word W of the run is stored at byte
+    1024*(W // 4) + 16*lane + 4*(W % 4) of the tile (so a wavefront reads 1 KiB per
+    16-byte load).  Inside a word, slot s picks the 16-bit half (s % 2) and the word
+    (s // 2); the operand picks the field, so that one AND with a constant mask
+    isolates the same field of both halves and every slot of an operand carries the
+    same power-of-two factor:
+      8-bit: word W = 4*(o // 2) + s // 2, bit 16*(s % 2) + 8*(o % 2)
+      4-bit: word W = 4*(o // 4) + s // 2, bit 16*(s % 2) + 4*(o % 4)
+      2-bit: word W = s // 2,              bit 16*(s % 2) + 2*o
+    (bits counted from the least significant bit of the little-endian word; inside a
+    byte the fields sit at offsets 0,2,4,6 / 0,4 / 0 as in App. B).
     Returns (byte_offset [32,128] int64, bit_shift [32,128] int64) of each code's
     byte and its shift inside that byte.
     """
@@ -440,12 +446,12 @@ def tile_code_positions(bits, which):
             else:
                 o, lane, sl = c // 16, 16 * ((r % 16) // 4) + c % 16, 4 * (r // 16) + r % 4
             if bits == 8:
-                B = 8 * o + sl
-                bit = 8 * (1024 * (B // 16) + 16 * lane + B % 16)
+                W, wbit = 4 * (o // 2) + sl // 2, 16 * (sl % 2) + 8 * (o % 2)
             elif bits == 4:
-                bit = 8 * (1024 * (o // 4) + 16 * lane + 4 * (o % 4)) + 4 * (sl // 2 + 4 * (sl % 2))
+                W, wbit = 4 * (o // 4) + sl // 2, 16 * (sl % 2) + 4 * (o % 4)
             else:
-                bit = 8 * (16 * lane + 4 * (o // 2)) + 2 * (4 * (o % 2) + sl // 2 + 8 * (sl % 2))
+                W, wbit = sl // 2, 16 * (sl % 2) + 2 * o
+            bit = 8 * (1024 * (W // 4) + 16 * lane + 4 * (W % 4)) + wbit
             byte_off[r, c], shift[r, c] = bit // 8, bit % 8
     return byte_off, shift
 

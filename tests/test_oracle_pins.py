@@ -634,23 +634,33 @@ def test_tile_positions_are_a_bijection_onto_the_tile(bits, which):
 
 
 def test_tile_positions_hand_checked():
-    # K, 8-bit: row 0, channel 0 -> lane 0, operand 0, slot 0 -> byte 0; channel 8 -> quad 1 -> lane 16 -> byte 256;
-    # channel 32 -> operand 1 -> byte 8 of lane 0; row 16 -> operand 4 -> B = 32 -> third 1 KiB chunk
+    # positions worked out by hand from the layout rule (word W of a lane at 1024*(W//4) + 16*lane + 4*(W%4)):
+    # K, 8-bit: (row 0, ch 0) = lane 0, operand 0, slot 0 -> word 0 bit 0 -> byte 0.  ch 1 = slot 1 -> high half of
+    # word 0 -> byte 2.  ch 2 = slot 2 -> word 1 -> byte 4.  ch 8 = quad 1 -> lane 16 -> byte 256.  ch 32 = operand 1
+    # -> bit 8 of word 0 -> byte 1.  ch 64 = operand 2 -> word 4 -> second 1 KiB chunk.  row 16 = operand 4 -> word 8.
     bo, sh = O.tile_code_positions(8, "k")
-    assert (bo[0, 0], bo[0, 8], bo[0, 32], bo[16, 0], bo[1, 0], bo[0, 1]) == (0, 256, 8, 2048, 16, 1)
-    # K, 4-bit: slots pair up as (n0,n4),(n1,n5),..: channel 1 (slot 1) is nibble 4 -> byte 2 low nibble
+    assert (bo[0, 0], bo[0, 1], bo[0, 2], bo[0, 8], bo[0, 32], bo[0, 64], bo[16, 0], bo[1, 0]) == \
+        (0, 2, 4, 256, 1, 1024, 2048, 16)
+    assert not sh.any()
+    # K, 4-bit: operand -> nibble inside each 16-bit half; slots (0,1) are the two halves of word 0
     bo, sh = O.tile_code_positions(4, "k")
-    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (0, 4)
-    assert (bo[0, 32], sh[0, 32]) == (4, 0)                     # group 1 -> next 32-bit word of lane 0
-    assert bo[16, 0] == 1024                                    # second m-block -> word 4 -> second chunk
-    # K, 2-bit: operand 1 (group 1) shares the word of operand 0 in fields 4..7 and 12..15
+    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (4, 0)
+    assert (bo[0, 32], sh[0, 32]) == (0, 4)                     # group 1 = operand 1 -> bits 4..7 of the same half
+    assert (bo[0, 64], sh[0, 64]) == (1, 0) and (bo[0, 96], sh[0, 96]) == (1, 4)
+    assert bo[16, 0] == 1024                                    # second m-block = operand 4 -> word 4 -> second chunk
+    # K, 2-bit: all eight operands share the lane's four words, operand o in bits 2o, 2o+1 of each half
     bo, sh = O.tile_code_positions(2, "k")
-    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (0, 2)
-    assert (bo[0, 32], sh[0, 32]) == (1, 0) and (bo[0, 33], sh[0, 33]) == (3, 0)
-    # V, 8-bit: the eight slots of a lane are tokens {0..3, 16..19} + 4*quad of one channel
+    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (4, 0)
+    assert (bo[0, 32], sh[0, 32]) == (0, 2) and (bo[0, 33], sh[0, 33]) == (2, 2)
+    assert (bo[16, 0], sh[16, 0]) == (1, 0) and (bo[16, 96], sh[16, 96]) == (1, 6)   # operands 4 and 7: second byte
+    # V, 8-bit: the eight slots of a lane are tokens {0..3, 16..19} + 4*quad of one channel: bytes 0,2 of words 0..3
     bo, sh = O.tile_code_positions(8, "v")
-    assert [int(bo[r, 0]) for r in (0, 1, 2, 3, 16, 17, 18, 19)] == list(range(8))
-    assert bo[4, 0] == 16 * 16 and bo[0, 1] == 16 and bo[0, 16] == 8     # quad 1; channel 1 -> lane 1; n-tile 1
+    assert [int(bo[r, 0]) for r in (0, 1, 2, 3, 16, 17, 18, 19)] == [0, 2, 4, 6, 8, 10, 12, 14]
+    assert bo[4, 0] == 16 * 16 and bo[0, 1] == 16 and bo[0, 16] == 1 and bo[0, 32] == 1024   # quad 1; lane 1; operands 1, 2
+    # V, 2-bit: channel block c // 16 picks the field, token slots pick word and half
+    bo, sh = O.tile_code_positions(2, "v")
+    assert (bo[0, 16], sh[0, 16]) == (0, 2) and (bo[1, 0], sh[1, 0]) == (2, 0) and (bo[16, 0], sh[16, 0]) == (8, 0)
+    assert (bo[0, 112], sh[0, 112]) == (1, 6)
     sc, of = O.tile_meta_positions("k")
     assert sc[0].tolist() == [0, 4, 8, 12] and sc[1, 0] == 1 and sc[16, 0] == 16 and sc[4, 0] == 32
     assert of[0].tolist() == [128, 129, 130, 131] and of[31, 3] == 255

@@ -29,9 +29,17 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWG = 256;
 constexpr int kWaves = 4;
-constexpr int kQBytes = 5 * 64 * 16;   // LDS copy of the query operands
+constexpr int kQBytes = 9 * 64 * 16;   // LDS copy of the query operands: 8 x (m-block, group) and the group sums
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLogitScale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
+
+// Codes enter the matrix cores as fp16 subnormals: a 16-bit pattern with a zero exponent field and the code in
+// mantissa bits [fb, fb + b) is the number code * 2^fb * 2^-24 exactly, so one AND per pair of codes is the whole
+// conversion.  The layout gives all eight slots of an operand the same fb; the query operand of the K product is
+// pre-multiplied by 2^(kQExp - fb) and the V accumulators are rescaled once per chunk.
+constexpr int kQExp = 4;                                   // keeps the scaled query clear of fp16 underflow
+constexpr float kKUnit = 1.0f / static_cast<float>(1 << (24 - kQExp));   // K partial products come out times this
+constexpr float kXScale = kLogitScale * static_cast<float>(1 << (24 - kQExp));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -42,112 +50,75 @@ union Pack8 {
   uint4 q;
 };
 
-// fields of a word -> pair of exact fp16 integers: (w & mask) | 0x6400 is 1024 + code * 2^shift in each half
-template <int SHIFT>
-__device__ __forceinline__ uint32_t field_pair(uint32_t w, uint32_t mask) {
-  // one v_and_or_b32: the mask rides in a scalar register, the fp16 pattern in a vector register
-  // (a gfx9 VALU instruction may read only one scalar or literal operand)
-  uint32_t x;
-  const uint32_t magic = 0x64006400u;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(x) : "v"(w), "s"(mask), "v"(magic));
-  const half2v v = __builtin_bit_cast(half2v, x);
-  constexpr float inv = 1.0f / static_cast<float>(1 << SHIFT);
-  const half2v scale = {static_cast<_Float16>(inv), static_cast<_Float16>(inv)};
-  const half2v bias = {static_cast<_Float16>(-1024.0f * inv), static_cast<_Float16>(-1024.0f * inv)};
-  const half2v r = __builtin_elementwise_fma(v, scale, bias);
-  return __builtin_bit_cast(uint32_t, r);
+// bit offset (inside a 16-bit half, after the pre-shift) of the field that operand o reads
+template <int TIER>
+__host__ __device__ constexpr int field_bit(int o) {
+  return TIER == 8 ? 0 : TIER == 4 ? 4 * (o & 1) : (o < 5 ? 2 * o : 2 * (o - 5));
 }
 
-// operand o (0..7) of this lane out of the raw tile bytes it loaded
+// Raw bytes of one tile side held by a lane, plus the right-shifted copy that brings the fields lying in the exponent
+// bits of a half down into its mantissa bits (2-bit: fields 5..7, shift 10; 4-bit: nibbles 2 and 3, shift 8).
 template <int TIER>
-__device__ __forceinline__ half8 unpack_operand(const uint4 (&raw)[TIER / 2], int o) {
+struct Side {
+  uint4 raw[TIER / 2];
+};
+template <int TIER>
+struct Shifted {
+  uint4 s[TIER == 8 ? 1 : TIER / 2];
+};
+
+template <int TIER>
+__device__ __forceinline__ Shifted<TIER> pre_shift(const Side<TIER>& a) {
+  Shifted<TIER> r;
+  if constexpr (TIER != 8) {
+    constexpr int kSh = TIER == 2 ? 10 : 8;
+#pragma unroll
+    for (int i = 0; i < TIER / 2; ++i)
+      r.s[i] = make_uint4(a.raw[i].x >> kSh, a.raw[i].y >> kSh, a.raw[i].z >> kSh, a.raw[i].w >> kSh);
+  }
+  return r;
+}
+
+// operand o (0..7) of this lane: eight codes as fp16 subnormals
+template <int TIER>
+__device__ __forceinline__ half8 unpack_operand(const Side<TIER>& a, const Shifted<TIER>& sh, int o) {
   Pack8 r;
   if constexpr (TIER == 8) {
-    const uint4 c = raw[o >> 1];
-    const uint32_t w0 = (o & 1) ? c.z : c.x, w1 = (o & 1) ? c.w : c.y;
-    const half2v k1024 = {static_cast<_Float16>(1024.0f), static_cast<_Float16>(1024.0f)};
-    const uint32_t ws[2] = {w0, w1};
-#pragma unroll
-    for (int d = 0; d < 2; ++d) {
-      const uint32_t lo = __builtin_amdgcn_perm(0x64646464u, ws[d], 0x04010400u);   // bytes 0,1 -> 0x64bb 0x64bb
-      const uint32_t hi = __builtin_amdgcn_perm(0x64646464u, ws[d], 0x04030402u);   // bytes 2,3
-      r.p[2 * d] = __builtin_bit_cast(half2v, lo) - k1024;
-      r.p[2 * d + 1] = __builtin_bit_cast(half2v, hi) - k1024;
-    }
+    const uint4 c = a.raw[o >> 1];
+    // bytes (0, 2) of every word for an even operand, (1, 3) for an odd one, zero-extended to 16 bits each.
+    // Both go through the byte permute: mixing it with a plain AND of the same register was seen to be
+    // scheduled with the AND done in place before the permute read its source.
+    const uint32_t sel = (o & 1) ? 0x0C030C01u : 0x0C020C00u;
+    r.u[0] = __builtin_amdgcn_perm(0u, c.x, sel);
+    r.u[1] = __builtin_amdgcn_perm(0u, c.y, sel);
+    r.u[2] = __builtin_amdgcn_perm(0u, c.z, sel);
+    r.u[3] = __builtin_amdgcn_perm(0u, c.w, sel);
   } else if constexpr (TIER == 4) {
-    const uint4 c = raw[o >> 2];
-    const uint32_t w = (o & 3) == 0 ? c.x : (o & 3) == 1 ? c.y : (o & 3) == 2 ? c.z : c.w;
-    const uint32_t t = w >> 8;
-    r.u[0] = field_pair<0>(w, 0x000F000Fu);
-    r.u[1] = field_pair<4>(w, 0x00F000F0u);
-    r.u[2] = field_pair<0>(t, 0x000F000Fu);
-    r.u[3] = field_pair<4>(t, 0x00F000F0u);
+    const int n = o & 3;
+    const uint4 c = n < 2 ? a.raw[o >> 2] : sh.s[o >> 2];
+    const uint32_t mask = 0x000F000Fu << (4 * (n & 1));
+    r.q = make_uint4(c.x & mask, c.y & mask, c.z & mask, c.w & mask);
   } else {
-    const uint4 c = raw[0];
-    const int d = o >> 1;
-    uint32_t w = d == 0 ? c.x : d == 1 ? c.y : d == 2 ? c.z : c.w;
-    if (o & 1) w >>= 8;
-    r.u[0] = field_pair<0>(w, 0x00030003u);
-    r.u[1] = field_pair<2>(w, 0x000C000Cu);
-    r.u[2] = field_pair<4>(w, 0x00300030u);
-    r.u[3] = field_pair<6>(w, 0x00C000C0u);
+    const uint4 c = o < 5 ? a.raw[0] : sh.s[0];
+    const uint32_t mask = 0x00030003u << field_bit<2>(o);
+    r.q = make_uint4(c.x & mask, c.y & mask, c.z & mask, c.w & mask);
   }
   return r.h;
 }
 
-// Raw bytes of NT consecutive tiles held by one lane.  K and V registers are refilled right after their last
-// use (K after the logits, V after the second product), so loads of the next tiles overlap the rest of the
-// iteration without a second register buffer.
-template <int TIER, int NT>
-struct SuperRaw {
-  uint4 k[NT][TIER / 2];
-  uint4 v[NT][TIER / 2];
-  uint4 kmeta;   // NT == 2: K metadata of tile (lane / 32); NT == 1: K metadata (lanes 0..31) and V metadata (32..63)
-  uint4 vmeta;   // NT == 2 only
-};
-
-template <int TIER, int NT>
-__device__ __forceinline__ void load_k(SuperRaw<TIER, NT>& r, const uint8_t* __restrict__ kd,
-                                       const uint8_t* __restrict__ km, const uint8_t* __restrict__ vm, int st,
-                                       int ntiles, int lane) {
+template <int TIER>
+__device__ __forceinline__ void load_side(Side<TIER>& r, const uint8_t* __restrict__ data, int tile, int lane) {
   constexpr int kTileBytes = kRowPad * kHeadDim * TIER / 8;
+  const uint8_t* p = data + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
 #pragma unroll
-  for (int u = 0; u < NT; ++u) {
-    const int tile = min(st * NT + u, ntiles - 1);
-    const uint8_t* kp = kd + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
-#pragma unroll
-    for (int i = 0; i < TIER / 2; ++i) r.k[u][i] = *reinterpret_cast<const uint4*>(kp + i * 1024);
-  }
-  if constexpr (NT == 2) {
-    const int tile = min(st * 2 + (lane >> 5), ntiles - 1);
-    r.kmeta = *reinterpret_cast<const uint4*>(km + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16);
-  } else {
-    const int tile = min(st, ntiles - 1);
-    r.kmeta = *reinterpret_cast<const uint4*>((lane < 32 ? km : vm) + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16);
-  }
+  for (int i = 0; i < TIER / 2; ++i) r.raw[i] = *reinterpret_cast<const uint4*>(p + i * 1024);
 }
 
-template <int TIER, int NT>
-__device__ __forceinline__ void load_v(SuperRaw<TIER, NT>& r, const uint8_t* __restrict__ vd,
-                                       const uint8_t* __restrict__ vm, int st, int ntiles, int lane) {
-  constexpr int kTileBytes = kRowPad * kHeadDim * TIER / 8;
-#pragma unroll
-  for (int u = 0; u < NT; ++u) {
-    const int tile = min(st * NT + u, ntiles - 1);
-    const uint8_t* vp = vd + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
-#pragma unroll
-    for (int i = 0; i < TIER / 2; ++i) r.v[u][i] = *reinterpret_cast<const uint4*>(vp + i * 1024);
-  }
-  if constexpr (NT == 2) {
-    const int tile = min(st * 2 + (lane >> 5), ntiles - 1);
-    r.vmeta = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16);
-  }
+// K metadata (lanes 0..31) and V metadata (lanes 32..63) of a tile: 16 bytes per lane
+__device__ __forceinline__ uint4 load_meta(const uint8_t* __restrict__ km, const uint8_t* __restrict__ vm, int tile,
+                                           int lane) {
+  return *reinterpret_cast<const uint4*>((lane < 32 ? km : vm) + static_cast<int64_t>(tile) * 512 + (lane & 31) * 16);
 }
-
-struct QOperands {
-  half8 q[4];      // B operand per channel group: q[head l16][32 grp + 8 quad + 0..7]
-  half8 qsum;      // B operand of the K-offset product: slots 0..3 group sums (hi), 4..7 (lo); quad 0 only
-};
 
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -155,95 +126,154 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int TIER, int NT>
+// One workgroup streams the tiles of one chunk; a wavefront owns a tile and the four wavefronts interleave.
+// A wavefront keeps DEPTH tiles in registers; the K (and metadata) registers of a tile are refilled right after the
+// logits, the V registers right after the second product, with the tile DEPTH rounds ahead, so DEPTH - 1 to DEPTH
+// tiles per wavefront are in flight at any time (the low-bit tiers need two to cover the HBM latency).
+template <int TIER, int DEPTH>
 __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ km,
                                               const uint8_t* __restrict__ vd, const uint8_t* __restrict__ vm,
-                                              int rows, int g, float* __restrict__ part_acc,
-                                              float* __restrict__ part_ml, uint8_t* smem) {
+                                              int rows, int g, const uint16_t* __restrict__ q,
+                                              float* __restrict__ part_acc, float* __restrict__ part_ml,
+                                              uint8_t* smem) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: tile indices and branches stay uniform
   const int quad = lane >> 4, l16 = lane & 15;
-  const uint8_t* s_q = smem + lane * 16;                           // query operands: [5][64 lanes][16 B]
-  uint8_t* s_meta_k = smem + kQBytes + wave * 2048;                // this wavefront's metadata staging
-  uint8_t* s_meta_v = s_meta_k + NT * 512;
-  float* s_ml = reinterpret_cast<float*>(smem + kQBytes + kWaves * 2048);    // [4][16][2]
+  const uint8_t* s_q = smem + lane * 16;                           // query operands: [9][64 lanes][16 B]
+  uint8_t* s_meta_k = smem + kQBytes + wave * 1024;                // this wavefront's metadata staging
+  uint8_t* s_meta_v = s_meta_k + 512;
+  float* s_ml = reinterpret_cast<float*>(smem + kQBytes + kWaves * 1024);    // [4][16][2]
   float* s_acc = s_ml + kWaves * 16 * 2;                           // [4][g][128]
 
   const int ntiles = (rows + kRowPad - 1) / kRowPad;
-  const int nsuper = (ntiles + NT - 1) / NT;
-  float m_run = kNegBig, l_run = 0.f;
+
+  // ---- issue the query loads, then the first tile's loads, before anything waits ---------------------------
+  uint4 qraw[4];
+#pragma unroll
+  for (int grp = 0; grp < 4; ++grp) {
+    qraw[grp] = make_uint4(0, 0, 0, 0);
+    if (wave == 0 && l16 < g) qraw[grp] = *reinterpret_cast<const uint4*>(q + l16 * kHeadDim + grp * 32 + quad * 8);
+  }
+  Side<TIER> rk[DEPTH], rv[DEPTH];
+  uint4 rmeta[DEPTH];
+#pragma unroll
+  for (int dd = 0; dd < DEPTH; ++dd) {
+    const int t = wave + dd * kWaves;
+    rmeta[dd] = make_uint4(0, 0, 0, 0);
+    if (t < ntiles) {
+      load_side<TIER>(rk[dd], kd, t, lane);
+      rmeta[dd] = load_meta(km, vm, t, lane);
+      load_side<TIER>(rv[dd], vd, t, lane);
+    }
+  }
+
+  // ---- query operands: lane (head l16, quad) holds q[head][32 grp + 8 quad + 0..7]; B operand of (mb, grp) is
+  //      q * 2^(kQExp - fb(4 mb + grp)); the group sums go through one more product with the offsets -------------
+  if (wave == 0) {
+    float gsum[4];
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) {
+      const uint32_t w[4] = {qraw[grp].x, qraw[grp].y, qraw[grp].z, qraw[grp].w};
+      float v[8];
+      float s = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[2 * j] = __uint_as_float(w[j] << 16);
+        v[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+        s += v[2 * j] + v[2 * j + 1];
+      }
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      gsum[grp] = s;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        const float f = static_cast<float>(1 << kQExp) / static_cast<float>(1 << field_bit<TIER>(4 * mb + grp));
+        half8 qo;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) qo[j] = static_cast<_Float16>(v[j] * f);
+        *reinterpret_cast<half8*>(smem + (mb * 4 + grp) * 1024 + lane * 16) = qo;
+      }
+    }
+    half8 qsum;   // slots 0..3: high parts of the group sums, 4..7: low parts; quad 0 only
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) {
+      const _Float16 hi = static_cast<_Float16>(gsum[grp]);
+      const _Float16 lo = static_cast<_Float16>(gsum[grp] - static_cast<float>(hi));
+      qsum[grp] = quad == 0 ? hi : static_cast<_Float16>(0.0f);
+      qsum[4 + grp] = quad == 0 ? lo : static_cast<_Float16>(0.0f);
+    }
+    *reinterpret_cast<half8*>(smem + 8 * 1024 + lane * 16) = qsum;
+  }
+  __syncthreads();
+
+  float m_run = kNegBig, l_run = 0.f;     // running maximum in units of kKUnit * (raw q.k)
   floatx4 acc[8], acc_off;
 #pragma unroll
   for (int nt = 0; nt < 8; ++nt) acc[nt] = floatx4{0.f, 0.f, 0.f, 0.f};
   acc_off = floatx4{0.f, 0.f, 0.f, 0.f};
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-  SuperRaw<TIER, NT> raw;
-  if (wave < nsuper) {
-    load_k<TIER, NT>(raw, kd, km, vm, wave, ntiles, lane);
-    load_v<TIER, NT>(raw, vd, vm, wave, ntiles, lane);
-  }
-  for (int st = wave; st < nsuper; st += kWaves) {
-    const bool more = st + kWaves < nsuper;
+  auto step = [&](Side<TIER>& rk, Side<TIER>& rv, uint4& rmeta, const int tile) __attribute__((always_inline)) {
+    const int next = tile + DEPTH * kWaves;
+    const bool more = next < ntiles;
 
-    // stage the metadata for broadcast reads (K tiles at s_meta_k + 512u, V tiles at s_meta_v + 512u)
-    *reinterpret_cast<uint4*>(s_meta_k + lane * 16) = raw.kmeta;
+    // stage the metadata for broadcast reads (K at s_meta_k, V at s_meta_v = s_meta_k + 512)
+    *reinterpret_cast<uint4*>(s_meta_k + lane * 16) = rmeta;
+    uint4 rmeta_next = rmeta;
     wave_lds_sync();
 
-    // ---- logits: x[u][mb][i] for token 32(st NT + u) + 16mb + 4quad + i, head l16 -----------
-    float x[NT][2][4];
+    // ---- logits x[mb][i] of token 16 mb + 4 quad + i and head l16, times kKUnit ---------------------------
+    float x[2][4];
+    {
+      const Shifted<TIER> ks = pre_shift<TIER>(rk);
+      Pack8 sc[4];   // scales of (mb, grp, i): 32 fp16
 #pragma unroll
-    for (int u = 0; u < NT; ++u) {
-      Pack8 ks[4];   // scales of (mb, grp, i): 32 fp16
-#pragma unroll
-      for (int j = 0; j < 4; ++j) ks[j].q = *reinterpret_cast<const uint4*>(s_meta_k + u * 512 + quad * 64 + j * 16);
+      for (int j = 0; j < 4; ++j) sc[j].q = *reinterpret_cast<const uint4*>(s_meta_k + quad * 64 + j * 16);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
         // offsets x group sums of q
-        const uint2 mo = *reinterpret_cast<const uint2*>(s_meta_k + u * 512 + 256 + (mb * 16 + l16) * 8);
+        const uint2 mo = *reinterpret_cast<const uint2*>(s_meta_k + 256 + (mb * 16 + l16) * 8);
         Pack8 a_off;
         a_off.u[0] = a_off.u[2] = quad == 0 ? mo.x : 0u;
         a_off.u[1] = a_off.u[3] = quad == 0 ? mo.y : 0u;
-        const floatx4 d_off = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_off.h, *reinterpret_cast<const half8*>(s_q + 4 * 1024), zero4, 0, 0, 0);
-        float sum[4] = {d_off[0], d_off[1], d_off[2], d_off[3]};
+        const floatx4 d_off = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+            a_off.h, *reinterpret_cast<const half8*>(s_q + 8 * 1024), zero4, 0, 0, 0);
+        float sum[4] = {d_off[0] * kKUnit, d_off[1] * kKUnit, d_off[2] * kKUnit, d_off[3] * kKUnit};
 #pragma unroll
         for (int grp = 0; grp < 4; ++grp) {
-          const half8 a = unpack_operand<TIER>(raw.k[u], mb * 4 + grp);
-          const floatx4 dd = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, *reinterpret_cast<const half8*>(s_q + grp * 1024), zero4, 0, 0, 0);
+          const half8 a = unpack_operand<TIER>(rk, ks, mb * 4 + grp);
+          const floatx4 dd = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+              a, *reinterpret_cast<const half8*>(s_q + (mb * 4 + grp) * 1024), zero4, 0, 0, 0);
           const int e = (mb * 4 + grp) * 4;           // scale index of i = 0
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            sum[i] = __builtin_fmaf(static_cast<float>(ks[e >> 3].h[(e & 7) + i]), dd[i], sum[i]);
+            sum[i] = __builtin_fmaf(static_cast<float>(sc[e >> 3].h[(e & 7) + i]), dd[i], sum[i]);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[u][mb][i] = sum[i];   // raw q.k; the 1/sqrt(d) and log2(e) factors enter at the exp
+        for (int i = 0; i < 4; ++i) x[mb][i] = sum[i];
       }
     }
-    if (more) load_k<TIER, NT>(raw, kd, km, vm, st + kWaves, ntiles, lane);   // K registers are free again
-
-    if ((st + 1) * NT * kRowPad > rows) {   // padded rows (and a missing second tile) of the last super-tile
-#pragma unroll
-      for (int u = 0; u < NT; ++u)
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if ((st * NT + u) * kRowPad + 16 * mb + 4 * quad + i >= rows) x[u][mb][i] = -INFINITY;
+    if (more) {                        // K registers are free again
+      load_side<TIER>(rk, kd, next, lane);
+      rmeta_next = load_meta(km, vm, next, lane);
     }
 
-    // ---- online softmax (head l16; the four quads hold different tokens) ----------------------
-    float mt = kNegBig;
-#pragma unroll
-    for (int u = 0; u < NT; ++u)
+    if ((tile + 1) * kRowPad > rows) {   // padded rows of the last tile
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) mt = fmaxf(mt, x[u][mb][i]);
+        for (int i = 0; i < 4; ++i)
+          if (tile * kRowPad + 16 * mb + 4 * quad + i >= rows) x[mb][i] = -INFINITY;
+    }
+
+    // ---- online softmax (head l16; the four quads hold different tokens) ----------------------
+    float mt = fmaxf(fmaxf(fmaxf(x[0][0], x[0][1]), fmaxf(x[0][2], x[0][3])),
+                     fmaxf(fmaxf(x[1][0], x[1][1]), fmaxf(x[1][2], x[1][3])));
     mt = fmaxf(mt, __shfl_xor(mt, 16));
     mt = fmaxf(mt, __shfl_xor(mt, 32));
     const float m_new = fmaxf(m_run, mt);
     if (__any(m_new != m_run)) {
-      const float alpha = fast_exp2((m_run - m_new) * kLogitScale);
+      const float alpha = fast_exp2((m_run - m_new) * kXScale);
       l_run *= alpha;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -255,54 +285,53 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
       m_run = m_new;
     }
 
-    if constexpr (NT == 2) {
-      *reinterpret_cast<uint4*>(s_meta_v + lane * 16) = raw.vmeta;
-      wave_lds_sync();
-    }
-    // ---- P V: slot j = 4mb + i of this lane is token 16mb + 4quad + i of tile u ----------------
-    const float neg_mc = -m_run * kLogitScale;
-#pragma unroll
-    for (int u = 0; u < NT; ++u) {
-      float p[8];
+    // ---- P V: slot j = 4mb + i of this lane is token 16mb + 4quad + i ----------------
+    {
+      const float neg_mc = -m_run * kXScale;
+      Pack8 ph;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          p[mb * 4 + i] = fast_exp2(__builtin_fmaf(x[u][mb][i], kLogitScale, neg_mc));
-          l_run += p[mb * 4 + i];
+        for (int h2 = 0; h2 < 2; ++h2) {
+          const float p0 = fast_exp2(__builtin_fmaf(x[mb][2 * h2], kXScale, neg_mc));
+          const float p1 = fast_exp2(__builtin_fmaf(x[mb][2 * h2 + 1], kXScale, neg_mc));
+          l_run += p0 + p1;
+          ph.p[mb * 2 + h2] = half2v{static_cast<_Float16>(p0), static_cast<_Float16>(p1)};
         }
-      Pack8 ph;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) ph.p[j] = half2v{static_cast<_Float16>(p[2 * j]), static_cast<_Float16>(p[2 * j + 1])};
+      const Shifted<TIER> vs = pre_shift<TIER>(rv);
       Pack8 voff;
-      voff.q = *reinterpret_cast<const uint4*>(s_meta_v + u * 512 + 256 + (quad * 4 + (l16 & 3)) * 16);
+      voff.q = *reinterpret_cast<const uint4*>(s_meta_v + 256 + (quad * 4 + (l16 & 3)) * 16);
       if (l16 >= 4) voff.q = make_uint4(0, 0, 0, 0);
       acc_off = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph.h, voff.h, acc_off, 0, 0, 0);
 #pragma unroll
       for (int grp = 0; grp < 4; ++grp) {
-        Pack8 vs, pa;
-        vs.q = *reinterpret_cast<const uint4*>(s_meta_v + u * 512 + (quad * 4 + grp) * 16);
+        Pack8 sv, pa;
+        sv.q = *reinterpret_cast<const uint4*>(s_meta_v + (quad * 4 + grp) * 16);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          pa.p[j] = half2v{static_cast<_Float16>(__builtin_fmaf(static_cast<float>(vs.h[2 * j]), p[2 * j], 0.0f)),
-                           static_cast<_Float16>(__builtin_fmaf(static_cast<float>(vs.h[2 * j + 1]), p[2 * j + 1], 0.0f))};
+        for (int j = 0; j < 4; ++j) pa.p[j] = ph.p[j] * sv.p[j];      // p * scale in fp16
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
           const int nt = grp * 2 + h2;
-          const half8 b = unpack_operand<TIER>(raw.v[u], nt);
+          const half8 b = unpack_operand<TIER>(rv, vs, nt);
           acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa.h, b, acc[nt], 0, 0, 0);
         }
       }
     }
     __builtin_amdgcn_wave_barrier();   // all reads of the staging area are issued before it is overwritten
-    if (more) load_v<TIER, NT>(raw, vd, vm, st + kWaves, ntiles, lane);       // V registers are free again
+    if (more) load_side<TIER>(rv, vd, next, lane);       // V registers are free again
+    rmeta = rmeta_next;
+  };
+  for (int tile = wave; tile < ntiles; tile += DEPTH * kWaves) {
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd)
+      if (tile + dd * kWaves < ntiles) step(rk[dd], rv[dd], rmeta[dd], tile + dd * kWaves);
   }
 
   // ---- merge the 4 wavefronts; acc[nt][i] is head 4quad+i, channel 16nt + l16 -----------------
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (quad == 0) {
-    s_ml[(wave * 16 + l16) * 2] = m_run * kLogitScale;   // running maximum in the log2 domain from here on
+    s_ml[(wave * 16 + l16) * 2] = m_run * kXScale;   // running maximum in the log2 domain from here on
     s_ml[(wave * 16 + l16) * 2 + 1] = l_run;
   }
   __syncthreads();
@@ -315,14 +344,20 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
     for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[(w * 16 + h) * 2]);
     f_own[i] = fast_exp2(s_ml[(wave * 16 + h) * 2] - mm);
   }
-  // the V-offset product left sum_t p m_v[t][grp] in lane (quad, l16 = grp); bring it to every channel lane
+  // undo the subnormal unit of the V codes; the V-offset product left sum_t p m_v[t][grp] in lane
+  // (quad, l16 = grp): bring it to every channel lane
 #pragma unroll
   for (int grp = 0; grp < 4; ++grp)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float o = __shfl(acc_off[i], quad * 16 + grp);
-      acc[2 * grp][i] += o;
-      acc[2 * grp + 1][i] += o;
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const int nt = 2 * grp + h2;
+        constexpr float kBase = 16777216.0f;   // 2^24
+        const float unit = kBase / static_cast<float>(1 << field_bit<TIER>(nt));
+        acc[nt][i] = __builtin_fmaf(acc[nt][i], unit, o);
+      }
     }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -351,8 +386,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
 }
 
-template <int TIER_SEL>
-__global__ __launch_bounds__(kWG) void decode_tiles_kernel(const Chunk* __restrict__ chunks,
+__global__ __launch_bounds__(kWG, 3) void decode_tiles_kernel(const Chunk* __restrict__ chunks,
                                                            const uint8_t* __restrict__ arena,
                                                            const uint16_t* __restrict__ q, float* part_acc,
                                                            float* part_ml, int hq, int hkv) {
@@ -360,57 +394,17 @@ __global__ __launch_bounds__(kWG) void decode_tiles_kernel(const Chunk* __restri
   const Chunk ch = chunks[blockIdx.x];
   const int g = hq / hkv;
   const int seq = ch.item / hkv, head = ch.item % hkv;
-  const int lane = threadIdx.x & 63, quad = lane >> 4, l16 = lane & 15;
-
-  // query operands: lane (head l16, quad) holds q[head][32 grp + 8 quad + 0..7] as fp16
-  QOperands qo;
-  float gsum[4];
-#pragma unroll
-  for (int grp = 0; grp < 4; ++grp) {
-    uint4 raw = make_uint4(0, 0, 0, 0);
-    if (l16 < g)
-      raw = *reinterpret_cast<const uint4*>(q + (static_cast<int64_t>(seq) * hq + head * g + l16) * kHeadDim +
-                                             grp * 32 + quad * 8);
-    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-    float s = 0.f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float lo = __uint_as_float(w[j] << 16), hi = __uint_as_float(w[j] & 0xFFFF0000u);
-      qo.q[grp][2 * j] = static_cast<_Float16>(lo);
-      qo.q[grp][2 * j + 1] = static_cast<_Float16>(hi);
-      s += lo + hi;
-    }
-    s += __shfl_xor(s, 16);
-    s += __shfl_xor(s, 32);
-    gsum[grp] = s;
-  }
-#pragma unroll
-  for (int grp = 0; grp < 4; ++grp) {
-    const _Float16 hi = static_cast<_Float16>(gsum[grp]);
-    const _Float16 lo = static_cast<_Float16>(gsum[grp] - static_cast<float>(hi));
-    qo.qsum[grp] = quad == 0 ? hi : static_cast<_Float16>(0.0f);
-    qo.qsum[4 + grp] = quad == 0 ? lo : static_cast<_Float16>(0.0f);
-  }
-
-  if (threadIdx.x < 64) {
-#pragma unroll
-    for (int grp = 0; grp < 4; ++grp) *reinterpret_cast<half8*>(smem + grp * 1024 + lane * 16) = qo.q[grp];
-    *reinterpret_cast<half8*>(smem + 4 * 1024 + lane * 16) = qo.qsum;
-  }
-  __syncthreads();
-
+  const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * g) * kHeadDim;
   float* pa = part_acc + static_cast<int64_t>(ch.slot) * g * kHeadDim;
   float* pm = part_ml + static_cast<int64_t>(ch.slot) * g * 2;
   const uint8_t* kd = arena + ch.k_data;
   const uint8_t* km = arena + ch.k_meta;
   const uint8_t* vd = arena + ch.v_data;
   const uint8_t* vm = arena + ch.v_meta;
-  // TIER_SEL == 0: any quantized tier in one launch; otherwise the launch holds chunks of one tier only
-  const int tier = TIER_SEL == 0 ? ch.tier : TIER_SEL;
-  switch (tier) {
-    case 8: process_tiles<8, 1>(kd, km, vd, vm, ch.rows, g, pa, pm, smem); break;
-    case 4: process_tiles<4, 1>(kd, km, vd, vm, ch.rows, g, pa, pm, smem); break;
-    default: process_tiles<2, 1>(kd, km, vd, vm, ch.rows, g, pa, pm, smem); break;
+  switch (ch.tier) {
+    case 8: process_tiles<8, 1>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
+    case 4: process_tiles<4, 2>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
+    default: process_tiles<2, 2>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
   }
 }
 
@@ -420,14 +414,10 @@ hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t*
                                float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   const int g = hq / hkv;
-  const size_t lds = kQBytes + kWaves * 2048 + kWaves * 16 * 2 * sizeof(float) + static_cast<size_t>(kWaves) * g * kHeadDim * sizeof(float);
-  hipLaunchKernelGGL(decode_tiles_kernel<0>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
+  const size_t lds = kQBytes + kWaves * 1024 + kWaves * 16 * 2 * sizeof(float) +
+                     static_cast<size_t>(kWaves) * g * kHeadDim * sizeof(float);
+  hipLaunchKernelGGL(decode_tiles_kernel, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
                      hq, hkv);
-  if (false) {
-    hipLaunchKernelGGL(decode_tiles_kernel<8>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml, hq, hkv);
-    hipLaunchKernelGGL(decode_tiles_kernel<4>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml, hq, hkv);
-    hipLaunchKernelGGL(decode_tiles_kernel<2>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml, hq, hkv);
-  }
   return hipGetLastError();
 }
 

@@ -168,10 +168,11 @@ __device__ __forceinline__ void tile_rc(bool is_v, int lane, int o, int s, int* 
 // owns eight 8-slot operands:
 //   K: operand o = 4*(r/16) + c/32, lane = 16*((c/8)%4) + r%16, slot s = c%8
 //   V: operand o = c/16,            lane = 16*((r%16)/4) + c%16, slot s = 4*(r/16) + r%4
-// and the code of (lane, o, s) sits at
-//   8-bit: byte B = 8o+s of the lane's run, stored at 1024*(B/16) + 16*lane + B%16
-//   4-bit: word o at 1024*(o/4) + 16*lane + 4*(o%4), nibble s/2 + 4*(s%2)
-//   2-bit: word o/2 at 16*lane + 4*(o/2), field 4*(o%2) + s/2 + 8*(s%2)
+// The lane's data is a run of 32-bit words, word W stored at 1024*(W/4) + 16*lane + 4*(W%4); slot s picks the word
+// and its 16-bit half, the operand picks the field, so one AND isolates an operand's codes in both halves:
+//   8-bit: W = 4*(o/2) + s/2, bit 16*(s%2) + 8*(o%2)
+//   4-bit: W = 4*(o/4) + s/2, bit 16*(s%2) + 4*(o%4)
+//   2-bit: W = s/2,           bit 16*(s%2) + 2*o
 // Metadata tile = 128 fp16 scales then 128 fp16 offsets; with mb = r/16, quad = (r%16)/4, i = r%4, j = 4mb+i:
 //   K scale ((quad*2+mb)*4+grp)*4+i, K offset 128 + 4r + grp; V scale and offset (128 +) (quad*4+grp)*8 + j.
 template <int BITS>
@@ -263,16 +264,16 @@ __global__ __launch_bounds__(256) void quant_pack_tile_kernel(PackArgs a) {
 #pragma unroll
       for (int f = 0; f < kFields; ++f) {
         int o, sl;
+        const int W = 4 * chunk + dd;                       // word of the lane's run
         if constexpr (BITS == 8) {
-          const int B = 16 * chunk + 4 * dd + f;
-          o = B >> 3;
-          sl = B & 7;
+          o = 2 * (W >> 2) + (f & 1);
+          sl = 2 * (W & 3) + (f >> 1);
         } else if constexpr (BITS == 4) {
-          o = 4 * chunk + dd;
-          sl = (f < 4) ? 2 * f : 2 * (f - 4) + 1;
+          o = 4 * (W >> 2) + (f & 3);
+          sl = 2 * (W & 3) + (f >> 2);
         } else {
-          o = 2 * dd + ((f & 7) >> 2);
-          sl = 2 * (f & 3) + (f >> 3);
+          o = f & 7;
+          sl = 2 * W + (f >> 3);
         }
         int r, c;
         tile_rc(w == 1, lane, o, sl, &r, &c);

@@ -18,7 +18,7 @@ Conventions
 * Tiers (bit-widths) B = {0, 2, 4, 8, 16} (Sec. 3); tier 16 keeps the input
   16-bit pattern, tier 0 stores nothing.
 
-Parity pins for each function are listed in tests/test_oracle_*.py; every
+Parity pins for each function are in tests/test_oracle_pins.py; every
 function here has at least one pin that is not a retyping of its own formula.
 End-to-end accuracy on the paper's benchmarks is "parity unpinned" (the data
 sets and models are not available).
@@ -644,6 +644,343 @@ def unpack_item(cache, item):
 
 
 # --------------------------------------------------------------------------
+# Mixed mode (Sec. 3.2 Stages 2-3, the paper's own arrangement): V token-wise,
+# K channel-wise on the retained tokens
+# --------------------------------------------------------------------------
+def channel_slots(bits_ch):
+    """Sorted-channel order of one item's K rows (App. B: channels are sorted by
+    bit-width into segments along the channel axis and the query is permuted to
+    match).  Tiers in the order 16, 8, 4, 2, ascending channel index inside a tier;
+    every tier is padded to a whole number of 8-channel "quads" (the paper pads the
+    2-bit and 4-bit segments to whole bytes; padded channels carry s = m = 0 and
+    zero codes, so they contribute nothing).  Evicted channels (0 bits) get no slot.
+    Returns {'order': {b: channel indices}, 'nq': {b: quads}, 'slot_ch': int array,
+    one entry per slot, the channel it holds or -1 for padding,
+    'qslot': slot indices of the quantized tiers (8, 4, 2) in order}."""
+    bits_ch = np.asarray(bits_ch, dtype=np.uint8)
+    order, nq, slot_ch = {}, {}, []
+    for b in PACK_ORDER:
+        ch = np.nonzero(bits_ch == b)[0].astype(np.int64)
+        order[b] = ch
+        nq[b] = (len(ch) + 7) // 8
+        slot_ch += list(ch) + [-1] * (8 * nq[b] - len(ch))
+    slot_ch = np.asarray(slot_ch, dtype=np.int64)
+    return {"order": order, "nq": nq, "slot_ch": slot_ch, "n_q16": 8 * nq[16]}
+
+
+def k_tile_bytes_mixed(nq):
+    """Bytes of one 32-token K tile: a quad of tier b is 8 channels x 32 tokens x b bits."""
+    return sum(nq[b] * 32 * b for b in PACK_ORDER)
+
+
+def k_meta_bytes_mixed(nq):
+    """Per tile: one fp16 scale and one fp16 offset per slot of the quantized tiers."""
+    return 4 * 8 * (nq[8] + nq[4] + nq[2])
+
+
+def quantize_channelwise(Krows, bits_ch):
+    """Channel-wise K quantization of the retained rows of one tier segment.
+
+    The paper uses one scale and zero-point per channel (App. B); this build's
+    layout groups 32 consecutive retained tokens of a channel (one tile of the
+    segment; the last group may be short), with the same quantizer as elsewhere
+    (fp16 scale, fp16 offset = group minimum, fp32 arithmetic in a fixed order).
+    Krows: float32 [n, d] bf16-exact, in packed order.  Returns
+      codes  uint16 [n, d]: integer codes (tiers 8/4/2), bf16 bit patterns (tier 16), 0 (tier 0)
+      scale, off  uint16 [tiles, d]: fp16 bit patterns (0 for tiers 16 and 0)."""
+    Krows = _check_bf16_exact(Krows, "K")
+    n, d = Krows.shape
+    bits_ch = np.asarray(bits_ch, dtype=np.uint8)
+    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    codes = np.zeros((n, d), dtype=np.uint16)
+    scale = np.zeros((nt, d), dtype=np.uint16)
+    off = np.zeros((nt, d), dtype=np.uint16)
+    for c in range(d):
+        b = int(bits_ch[c])
+        if b == 16:
+            codes[:, c] = bf16_bits(Krows[:, c])
+        elif b in (2, 4, 8):
+            for t in range(nt):
+                rows = slice(t * TILE_ROWS, min(n, (t + 1) * TILE_ROWS))
+                cc, sc, mc = quantize_groups(Krows[rows, c][None, :], b)
+                codes[rows, c] = cc[0]
+                scale[t, c] = sc.view(np.uint16)[0]
+                off[t, c] = mc.view(np.uint16)[0]
+    return codes, scale, off
+
+
+def dequantize_channelwise(codes, scale, off, bits_ch):
+    """K_hat float64 [n, d]: s*code + m for tiers 8/4/2, the bf16 value for tier 16,
+    exactly zero for an evicted channel (Sec. 3.2: a 0-bit channel is removed)."""
+    n, d = codes.shape
+    out = np.zeros((n, d), dtype=np.float64)
+    for c in range(d):
+        b = int(bits_ch[c])
+        if b == 16:
+            out[:, c] = bf16_from_bits(codes[:, c]).astype(np.float64)
+        elif b in (2, 4, 8):
+            t = np.arange(n) // TILE_ROWS
+            s = scale[:, c].copy().view(np.float16).astype(np.float64)[t]
+            m = off[:, c].copy().view(np.float16).astype(np.float64)[t]
+            out[:, c] = s * codes[:, c].astype(np.float64) + m
+    return out
+
+
+def _k_field_position(b, slot, mb):
+    """(byte offset inside the lane's 2b bytes, bit shift) of the code of channel
+    slot `slot` (0..7 of the quad) and token half `mb` for a quantized tier b.
+    The lane's bytes are b/2 little-endian 32-bit words; a 16-bit half of a word holds
+    16/b fields; field f of half hh of word w is slot 2*(w*(8/b) + f//2) + hh of
+    token half f % 2."""
+    F = 16 // b
+    hh, pair = slot % 2, slot // 2
+    w, fpair = pair // (F // 2), pair % (F // 2)
+    f = 2 * fpair + mb
+    bit = 32 * w + 16 * hh + b * f
+    return bit // 8, bit % 8
+
+
+def pack_k_tiles_mixed(codes, scale, off, bits_ch):
+    """Physical K tiles of one tier segment in mixed mode.
+
+    Tile data = for tier b in 16, 8, 4, 2, for each quad of the tier (8 channel slots
+    x 32 tokens): 16 lanes x 2b bytes, lane l16 holding tokens l16 (half 0) and 16 + l16
+    (half 1) of the tile for the quad's 8 slots:
+      tier 16:    8 bf16 of half 0 (slot order) then 8 bf16 of half 1
+      tiers 8/4/2: bit fields per _k_field_position
+    Tile metadata = fp16 scales of all quantized slots (tiers 8, 4, 2 in order), then
+    their fp16 offsets.  Rows beyond n in the last tile and padding slots are zero.
+    Returns (data uint8, meta uint8)."""
+    n, d = codes.shape
+    sl = channel_slots(bits_ch)
+    nq, slot_ch = sl["nq"], sl["slot_ch"]
+    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    tb, mbytes = k_tile_bytes_mixed(nq), k_meta_bytes_mixed(nq)
+    data = np.zeros((nt, tb), dtype=np.uint8)
+    meta = np.zeros((nt, mbytes // 2), dtype="<u2")
+    nqs = mbytes // 4                                 # quantized slots
+    cp = np.zeros((nt * TILE_ROWS, d), dtype=np.uint16)
+    cp[:n] = codes
+    cp = cp.reshape(nt, TILE_ROWS, d)
+    base, slot0, qs = 0, 0, 0
+    for b in PACK_ORDER:
+        for Q in range(nq[b]):
+            for j in range(8):
+                ch = int(slot_ch[slot0 + 8 * Q + j])
+                if b != 16:
+                    if ch >= 0:
+                        meta[:, qs] = scale[:, ch]
+                        meta[:, nqs + qs] = off[:, ch]
+                    qs += 1
+                if ch < 0:
+                    continue
+                for mb in range(2):
+                    for l16 in range(16):
+                        vals = cp[:, 16 * mb + l16, ch]                      # one value per tile
+                        lane_base = base + Q * 32 * b + l16 * 2 * b
+                        if b == 16:
+                            o = lane_base + 16 * mb + 2 * j
+                            data[:, o] = (vals & 0xFF).astype(np.uint8)
+                            data[:, o + 1] = (vals >> 8).astype(np.uint8)
+                        else:
+                            bo, sh = _k_field_position(b, j, mb)
+                            data[:, lane_base + bo] |= (vals.astype(np.uint32) << sh).astype(np.uint8)
+        base += nq[b] * 32 * b
+        slot0 += 8 * nq[b]
+    return data.reshape(-1), meta.view(np.uint8).reshape(-1)
+
+
+def unpack_k_tiles_mixed(data, meta, n, bits_ch, d=128):
+    """Inverse of pack_k_tiles_mixed for the first n rows: (codes, scale, off)."""
+    sl = channel_slots(bits_ch)
+    nq, slot_ch = sl["nq"], sl["slot_ch"]
+    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    tb, mbytes = k_tile_bytes_mixed(nq), k_meta_bytes_mixed(nq)
+    data = np.asarray(data, dtype=np.uint8).reshape(nt, tb)
+    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape(nt, mbytes // 2)
+    nqs = mbytes // 4
+    codes = np.zeros((nt, TILE_ROWS, d), dtype=np.uint16)
+    scale = np.zeros((nt, d), dtype=np.uint16)
+    off = np.zeros((nt, d), dtype=np.uint16)
+    base, slot0, qs = 0, 0, 0
+    for b in PACK_ORDER:
+        for Q in range(nq[b]):
+            for j in range(8):
+                ch = int(slot_ch[slot0 + 8 * Q + j])
+                if b != 16:
+                    if ch >= 0:
+                        scale[:, ch] = meta[:, qs]
+                        off[:, ch] = meta[:, nqs + qs]
+                    qs += 1
+                if ch < 0:
+                    continue
+                for mb in range(2):
+                    for l16 in range(16):
+                        lane_base = base + Q * 32 * b + l16 * 2 * b
+                        if b == 16:
+                            o = lane_base + 16 * mb + 2 * j
+                            v = data[:, o].astype(np.uint16) | (data[:, o + 1].astype(np.uint16) << 8)
+                        else:
+                            bo, sh = _k_field_position(b, j, mb)
+                            v = (data[:, lane_base + bo] >> sh) & ((1 << b) - 1)
+                        codes[:, 16 * mb + l16, ch] = v
+        base += nq[b] * 32 * b
+        slot0 += 8 * nq[b]
+    return codes.reshape(nt * TILE_ROWS, d)[:n], scale, off
+
+
+def pack_v16_tiles(vbits):
+    """Mixed mode keeps 16-bit V rows (Zone B of Sec. 3.3) in 32-token tiles with the
+    same lane / operand / slot assignment as the quantized V tiers: the bf16 of
+    (lane, operand o, slot s) sits at byte 1024*o + 16*lane + 2*s of the 8 KiB tile.
+    vbits: uint16 [n, 128].  Returns uint8 [tiles * 8192]."""
+    n = vbits.shape[0]
+    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    vp = np.zeros((nt * TILE_ROWS, 128), dtype=np.uint16)
+    vp[:n] = vbits
+    vp = vp.reshape(nt, TILE_ROWS, 128)
+    out = np.zeros((nt, 4096), dtype="<u2")
+    for r in range(TILE_ROWS):
+        for c in range(128):
+            o, lane, sl = c // 16, 16 * ((r % 16) // 4) + c % 16, 4 * (r // 16) + r % 4
+            out[:, (1024 * o + 16 * lane) // 2 + sl] = vp[:, r, c]
+    return out.view(np.uint8).reshape(-1)
+
+
+def unpack_v16_tiles(data, n):
+    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    w = np.asarray(data, dtype=np.uint8).view("<u2").reshape(nt, 4096)
+    out = np.zeros((nt, TILE_ROWS, 128), dtype=np.uint16)
+    for r in range(TILE_ROWS):
+        for c in range(128):
+            o, lane, sl = c // 16, 16 * ((r % 16) // 4) + c % 16, 4 * (r // 16) + r % 4
+            out[:, r, c] = w[:, (1024 * o + 16 * lane) // 2 + sl]
+    return out.reshape(nt * TILE_ROWS, 128)[:n]
+
+
+def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list):
+    """Pack a ragged batch in mixed mode (Alg. 1 Stage 4 as printed: V rows sorted by
+    b_t^V into sub-segments, K rows of the retained tokens with channels sorted by
+    b_c^K).  bits_tok_list[s]: uint8 [Hkv, T_s] (V token map); bits_ch_list[s]: uint8
+    [Hkv, d] (K channel map).  Arena: per item and per V tier (16, 8, 4, 2) the four
+    segments K data, K meta, V data, V meta, each on a 256-byte boundary; the K
+    segments hold the channel-wise tiles of that tier's tokens.  Same keys as
+    build_cache_tokenwise plus 'bits_ch' [items, d] and 'mixed' = True."""
+    items = []
+    for Ks, Vs, bt, bc in zip(K_list, V_list, bits_tok_list, bits_ch_list):
+        for h in range(Ks.shape[0]):
+            items.append((Ks[h], Vs[h], bt[h], bc[h]))
+    d = K_list[0].shape[2]
+    n_items = len(items)
+    counts = np.zeros((n_items, 4), dtype=np.int32)
+    seg_off = np.zeros((n_items, 4, 4), dtype=np.int64)
+    chunks, tier_idx, canon = [], [], []
+    cur = 0
+    for i, (Kh, Vh, bt, bc) in enumerate(items):
+        Kh = _check_bf16_exact(Kh, "K")
+        Vh = _check_bf16_exact(Vh, "V")
+        idx = partition(bt)
+        rec = {}
+        for ti, b in enumerate(PACK_ORDER):
+            pos = idx[b]
+            n = len(pos)
+            counts[i, ti] = n
+            tier_idx.append(pos)
+            kc, ks, ko = quantize_channelwise(Kh[pos], bc)
+            kd, km = pack_k_tiles_mixed(kc, ks, ko, bc)
+            if b == 16:
+                vcodes = bf16_bits(Vh[pos]).reshape(n, d)
+                vd, vm = pack_v16_tiles(vcodes), np.zeros(0, dtype=np.uint8)
+                rec[b] = {"pos": pos, "k_codes": kc, "k_scale": ks, "k_off": ko, "v_codes": vcodes}
+            else:
+                c, sc, m = quantize_groups(Vh[pos].reshape(n, d // GROUP, GROUP), b)
+                vd, vm = pack_tiles(c.reshape(n, d), sc.view(np.uint16), m.view(np.uint16), b, "v")
+                rec[b] = {"pos": pos, "k_codes": kc, "k_scale": ks, "k_off": ko, "v_codes": c.reshape(n, d),
+                          "v_scale": sc.view(np.uint16), "v_off": m.view(np.uint16)}
+            for si, seg in enumerate((kd, km, vd, vm)):
+                cur = _round_up(cur, SEG_ALIGN)
+                seg_off[i, ti, si] = cur
+                if seg.size:
+                    chunks.append((cur, seg))
+                    cur += seg.size
+        canon.append(rec)
+    arena = np.zeros(_round_up(cur, SEG_ALIGN), dtype=np.uint8)
+    for o, flat in chunks:
+        arena[o:o + flat.size] = flat
+    return {
+        "counts": counts,
+        "tier_idx": np.concatenate(tier_idx).astype(np.int32) if tier_idx else np.zeros(0, np.int32),
+        "seg_off": seg_off, "arena": arena, "canon": canon, "d": d, "hkv": K_list[0].shape[0],
+        "seq_lens": [k.shape[1] for k in K_list], "mixed": True,
+        "bits_ch": np.stack([it[3] for it in items]).astype(np.uint8),
+    }
+
+
+def stored_bytes_mixed(counts, bits_ch, d=128):
+    """Bytes a decode step must read in mixed mode (unpadded): per item and V tier with n
+    rows, K codes n * sum_c b_c / 8, K metadata ceil(n / 32) * 4 per quantized channel, and
+    the V rows as in token-wise mode (n * (16 b + 16), or n * 256 at 16 bits)."""
+    counts = np.asarray(counts, dtype=np.int64).reshape(-1, 4)
+    total = 0
+    for i in range(counts.shape[0]):
+        bc = np.asarray(bits_ch[i], dtype=np.int64)
+        kbits = int(bc.sum())
+        nquant = int(((bc == 2) | (bc == 4) | (bc == 8)).sum())
+        for ti, b in enumerate(PACK_ORDER):
+            n = int(counts[i, ti])
+            total += n * kbits // 8 + ((n + TILE_ROWS - 1) // TILE_ROWS) * 4 * nquant
+            total += n * (row_bytes(b, d) + meta_bytes(b, d))
+    return total
+
+
+def unpack_item_mixed(cache, item):
+    """K_hat, V_hat (float64 [n_kept, d]) of one item of a mixed-mode cache, read back
+    from the physical arena."""
+    d = cache["d"]
+    arena, seg_off, counts = cache["arena"], cache["seg_off"], cache["counts"]
+    bc = cache["bits_ch"][item]
+    nq = channel_slots(bc)["nq"]
+    tb, mb_ = k_tile_bytes_mixed(nq), k_meta_bytes_mixed(nq)
+    ks, vs = [], []
+    for ti, b in enumerate(PACK_ORDER):
+        n = int(counts[item, ti])
+        if n == 0:
+            continue
+        nt = (n + TILE_ROWS - 1) // TILE_ROWS
+        o = [int(x) for x in seg_off[item, ti]]
+        kc, ksc, kof = unpack_k_tiles_mixed(arena[o[0]:o[0] + nt * tb], arena[o[1]:o[1] + nt * mb_], n, bc, d)
+        ks.append(dequantize_channelwise(kc, ksc, kof, bc))
+        if b == 16:
+            vbits = unpack_v16_tiles(arena[o[2]:o[2] + nt * 8192], n)
+            vs.append(bf16_from_bits(vbits).astype(np.float64))
+        else:
+            codes, sc, of = unpack_tiles(arena[o[2]:o[2] + nt * tile_data_bytes(b)],
+                                         arena[o[3]:o[3] + nt * TILE_META_BYTES], n, b, "v")
+            vs.append(dequantize_groups(codes.reshape(n, d // GROUP, GROUP), sc.copy().view(np.float16),
+                                        of.copy().view(np.float16)).reshape(n, d))
+    if not ks:
+        return np.zeros((0, d)), np.zeros((0, d))
+    return np.concatenate(ks), np.concatenate(vs)
+
+
+def allocate_mixed(w_tok, w_ch, avg_bits, r_k=np.float32(0.5), tiers=TIERS, eps_v=EPS_V_LLAMA31_8B,
+                   eps_k=EPS_K_LLAMA31_8B, rel_tol=np.float32(1e-2), max_iters=64):
+    """Stages 2 and 3 of Alg. 1 for one item: the V token map from the token weights
+    with average 2 (1 - r_K) avg_bits, then the K channel map from the channel weights
+    with the K budget spread over the retained tokens only.  w_tok: float32 [T];
+    w_ch: float32 [d].  Returns (bits_tok uint8 [T], bits_ch uint8 [d])."""
+    T, d = len(w_tok), len(w_ch)
+    v_avg, _ = mixed_budgets(avg_bits, r_k, T, None, d)
+    bits_tok = mckp_bisect(w_tok, np.float32(v_avg), tiers, eps_v, rel_tol, max_iters)
+    n_kept = int((bits_tok > 0).sum())
+    _, k_avg = mixed_budgets(avg_bits, r_k, T, n_kept, d)
+    if n_kept == 0:
+        return bits_tok, np.zeros(d, dtype=np.uint8)
+    bits_ch = mckp_bisect(w_ch, np.float32(k_avg), tiers, eps_k, rel_tol, max_iters)
+    return bits_tok, bits_ch
+
+
+# --------------------------------------------------------------------------
 # Decode (Sec. 3.3, Eq. 7): dense attention on the compressed cache (K_hat, V_hat)
 # --------------------------------------------------------------------------
 def attention_rows(q, Kh, Vh):
@@ -662,9 +999,10 @@ def attention_rows(q, Kh, Vh):
 
 
 def decode(cache, q):
-    """One decode step over a packed token-wise cache.  q: [batch, Hq, d] (bf16
-    exact).  Every retained token enters with its dequantised K row and V row;
-    evicted tokens (tier 0) are absent (Eq. 7 without the new-token zone).
+    """One decode step over a packed cache (token-wise or mixed).  q: [batch, Hq, d]
+    (bf16 exact).  Every retained token enters with its dequantised K row and V row;
+    evicted tokens (tier 0) are absent and evicted K channels are zero (Eq. 7 without
+    the new-token zone).
     Returns out float64 [batch, Hq, d], lse float64 [batch, Hq]."""
     q = np.asarray(q, dtype=np.float64)
     batch, Hq, d = q.shape
@@ -674,7 +1012,8 @@ def decode(cache, q):
     lse = np.zeros((batch, Hq))
     for s in range(batch):
         for h in range(hkv):
-            Kh, Vh = unpack_item(cache, s * hkv + h)
+            item = s * hkv + h
+            Kh, Vh = unpack_item_mixed(cache, item) if cache.get("mixed") else unpack_item(cache, item)
             o, l = attention_rows(q[s, h * g:(h + 1) * g], Kh, Vh)
             out[s, h * g:(h + 1) * g] = o
             lse[s, h * g:(h + 1) * g] = l

@@ -690,3 +690,225 @@ def test_tile_pack_roundtrip_and_padding(bits):
     one[0, 5] = (1 << bits) - 1
     data, _ = O.pack_tiles(one, np.zeros((1, 4), np.uint16), np.zeros((1, 4), np.uint16), bits, "k")
     assert int(np.unpackbits(data).sum()) == bits
+
+
+# ----------------------------------------------------------------------------
+# mixed mode: V token-wise, K channel-wise on the retained tokens (Sec. 3.2 Stages 2-3, App. B)
+# ----------------------------------------------------------------------------
+def _mixed_case(rng, T=150, hkv=2, p_tok=(.3, .3, .2, .1, .1), p_ch=(.1, .4, .3, .15, .05)):
+    K = rand_bf16(rng, (hkv, T, 128))
+    K[:, :, 7] *= 10.0
+    K = bf16_round(K)
+    V = rand_bf16(rng, (hkv, T, 128))
+    bt = rng.choice([0, 2, 4, 8, 16], (hkv, T), p=p_tok).astype(np.uint8)
+    bc = rng.choice([0, 2, 4, 8, 16], (hkv, 128), p=p_ch).astype(np.uint8)
+    return K, V, bt, bc
+
+
+def test_mixed_all_16_bit_reproduces_bruteforce_attention():
+    rng = np.random.default_rng(41)
+    K, V, _, _ = _mixed_case(rng, T=70)
+    bt = np.full((2, 70), 16, np.uint8)
+    bc = np.full((2, 128), 16, np.uint8)
+    cache = O.build_cache_mixed([K], [V], [bt], [bc])
+    q = rand_bf16(rng, (1, 8, 128))
+    out, lse = O.decode(cache, q)
+    for j in range(8):
+        o, l = _bruteforce_attention(q[0, j], K[j // 4], V[j // 4])
+        np.testing.assert_allclose(out[0, j], o, rtol=1e-12, atol=1e-13)
+        assert abs(lse[0, j] - l) < 1e-12
+
+
+def test_zero_bit_channel_is_a_zeroed_key_column_and_zero_bit_token_is_eviction():
+    # Sec. 3.2: a channel with b_c = 0 is removed (its K column contributes nothing to q.k);
+    # a token with b_t = 0 is evicted.  With every other unit at 16 bits the result is exact.
+    rng = np.random.default_rng(42)
+    K, V, _, _ = _mixed_case(rng, T=90)
+    bt = np.where(rng.random((2, 90)) < 0.4, 0, 16).astype(np.uint8)
+    bc = np.where(rng.random((2, 128)) < 0.3, 0, 16).astype(np.uint8)
+    cache = O.build_cache_mixed([K], [V], [bt], [bc])
+    q = rand_bf16(rng, (1, 8, 128))
+    out, lse = O.decode(cache, q)
+    for j in range(8):
+        h = j // 4
+        keep = np.nonzero(bt[h])[0]
+        Kz = K[h][keep].astype(np.float64) * (bc[h] > 0)[None, :]
+        o, l = _bruteforce_attention(q[0, j], Kz, V[h][keep])
+        np.testing.assert_allclose(out[0, j], o, rtol=1e-12, atol=1e-13)
+        assert abs(lse[0, j] - l) < 1e-12
+
+
+def test_channelwise_quantizer_groups_are_32_tokens_of_one_channel():
+    rng = np.random.default_rng(43)
+    n = 75
+    X = rand_bf16(rng, (n, 128), scale=2.0)
+    bc = np.tile(np.array([16, 8, 4, 2, 0, 8, 4, 2], np.uint8), 16)
+    codes, sc, of = O.quantize_channelwise(X, bc)
+    Xh = O.dequantize_channelwise(codes, sc, of, bc)
+    assert sc.shape == (3, 128) and of.shape == (3, 128)
+    for c in range(128):
+        b = int(bc[c])
+        if b == 16:
+            np.testing.assert_array_equal(Xh[:, c], X[:, c].astype(np.float64))      # input bits kept
+        elif b == 0:
+            assert not Xh[:, c].any() and not codes[:, c].any()
+        else:
+            assert codes[:, c].max() <= (1 << b) - 1
+            for t in range(3):
+                rows = slice(32 * t, min(n, 32 * t + 32))
+                s = float(sc[t, c:c + 1].view(np.float16)[0])
+                m = float(of[t, c:c + 1].view(np.float16)[0])
+                # offset = the group's minimum (bf16 values of this size are exact in fp16)
+                assert m == float(X[rows, c].min())
+                # error bound of a round-to-nearest uniform quantizer (fp16 rounding of s may clamp the top element)
+                assert np.abs(Xh[rows, c] - X[rows, c]).max() <= 0.5 * s * (1 + 2 ** -10) + 0.125 * s * (b == 8)
+    # a group is one tile of one channel: changing tile 1 of channel 1 leaves every other (tile, channel) alone
+    X2 = X.copy()
+    X2[40, 1] = np.float32(50.0)
+    c2, s2, o2 = O.quantize_channelwise(X2, bc)
+    same = np.ones((3, 128), bool)
+    same[1, 1] = False
+    assert np.array_equal(s2[same], sc[same]) and np.array_equal(o2[same], of[same]) and s2[1, 1] != sc[1, 1]
+    keep = np.ones((n, 128), bool)
+    keep[32:64, 1] = False
+    assert np.array_equal(c2[keep], codes[keep])
+
+
+def test_per_channel_dequantization_fusion_identity():
+    # App. B: q.k_hat = sum_c (s_c q_c) code_c - sum_c s_c z_c q_c with k_hat = s (code - z), here z = -m / s
+    rng = np.random.default_rng(44)
+    X = rand_bf16(rng, (32, 128))
+    bc = rng.choice([2, 4, 8], 128).astype(np.uint8)
+    codes, sc, of = O.quantize_channelwise(X, bc)
+    s = sc[0].copy().view(np.float16).astype(np.float64)
+    m = of[0].copy().view(np.float16).astype(np.float64)
+    q = rng.standard_normal(128)
+    fused = codes.astype(np.float64) @ (s * q) + np.dot(m, q)            # -s z = m
+    direct = O.dequantize_channelwise(codes, sc, of, bc) @ q
+    np.testing.assert_allclose(fused, direct, rtol=1e-12, atol=1e-12)
+
+
+def test_channel_slots_hand_worked():
+    bc = np.zeros(128, np.uint8)
+    bc[[5, 70, 100]] = 8
+    bc[[0, 1]] = 16
+    bc[10:21] = 4                      # 11 channels -> two quads, five padding slots
+    bc[[30, 31, 32]] = 2
+    sl = O.channel_slots(bc)
+    assert sl["nq"] == {16: 1, 8: 1, 4: 2, 2: 1}
+    assert sl["slot_ch"].tolist() == [0, 1] + [-1] * 6 + [5, 70, 100] + [-1] * 5 + list(range(10, 21)) + [-1] * 5 \
+        + [30, 31, 32] + [-1] * 5
+    assert O.k_tile_bytes_mixed(sl["nq"]) == 512 + 256 + 2 * 128 + 64
+    assert O.k_meta_bytes_mixed(sl["nq"]) == 4 * 8 * 4
+
+
+def test_mixed_k_tile_layout_hand_checked_and_roundtrip():
+    rng = np.random.default_rng(45)
+    bc = np.zeros(128, np.uint8)
+    bc[[5, 70, 100]] = 8
+    bc[[0, 1]] = 16
+    bc[10:21] = 4
+    bc[[30, 31, 32]] = 2
+    n = 40
+    X = rand_bf16(rng, (n, 128))
+    codes, sc, of = O.quantize_channelwise(X, bc)
+    data, meta = O.pack_k_tiles_mixed(codes, sc, of, bc)
+    tb = 512 + 256 + 256 + 64
+    assert data.size == 2 * tb and meta.size == 2 * 128
+    d16 = data.view("<u2")
+    # tier 16 quad at byte 0: lane l16 owns 32 bytes: 8 bf16 of token l16 then 8 bf16 of token 16 + l16
+    assert d16[0] == codes[0, 0] and d16[1] == codes[0, 1] and d16[8] == codes[16, 0] and d16[16] == codes[1, 0]
+    assert d16[2] == 0                                             # padding slot
+    # tier 8 quad at byte 512: lane l16 owns 16 bytes, word d = [half0 slot 2d, half1 slot 2d, half0 slot 2d+1, ...]
+    assert data[512 + 0] == codes[0, 5] and data[512 + 1] == codes[16, 5] and data[512 + 2] == codes[0, 70]
+    assert data[512 + 3] == codes[16, 70] and data[512 + 4] == codes[0, 100] and data[512 + 16] == codes[1, 5]
+    # tier 4 at byte 768: lane owns 8 bytes; nibbles of the first 16-bit half: slot 0 half 0, slot 0 half 1, slot 2 half 0, ...
+    b0 = int(data[768])
+    assert (b0 & 15, b0 >> 4) == (int(codes[0, 10]), int(codes[16, 10]))
+    b1 = int(data[769])
+    assert (b1 & 15, b1 >> 4) == (int(codes[0, 12]), int(codes[16, 12]))           # slot 2
+    b2 = int(data[770])
+    assert (b2 & 15, b2 >> 4) == (int(codes[0, 11]), int(codes[16, 11]))           # second half of word 0: slot 1
+    assert (int(data[772]) & 15) == int(codes[0, 14])                              # word 1: slot 4
+    assert (int(data[768 + 128]) & 15) == int(codes[0, 18])                        # second quad: channels 18..20
+    # tier 2 at byte 1024: lane owns one word; fields of the first half: slot 0 (half 0, half 1), slot 2, ...
+    w = int(data[1024:1028].view("<u4")[0])
+    assert (w & 3, (w >> 2) & 3, (w >> 4) & 3, (w >> 16) & 3) == \
+        (int(codes[0, 30]), int(codes[16, 30]), int(codes[0, 32]), int(codes[0, 31]))
+    # second tile starts at tb; it holds rows 32..39 and zero rows after them
+    assert data[tb + 512] == codes[32, 5] and data[tb + 512 + 1] == 0
+    # metadata: scales of the quantized slots (8-bit quad, two 4-bit quads, 2-bit quad), then offsets
+    m16 = meta.view("<u2")
+    assert m16[0] == sc[0, 5] and m16[2] == sc[0, 100] and m16[3] == 0 and m16[8] == sc[0, 10] and m16[24] == sc[0, 30]
+    assert m16[32] == of[0, 5] and m16[64 + 0] == sc[1, 5]
+    c2, s2, o2 = O.unpack_k_tiles_mixed(data, meta, n, bc)
+    np.testing.assert_array_equal(c2, codes)
+    np.testing.assert_array_equal(s2, sc)
+    np.testing.assert_array_equal(o2, of)
+
+
+def test_v16_tile_roundtrip_and_positions():
+    rng = np.random.default_rng(46)
+    vb = rng.integers(0, 65536, (45, 128)).astype(np.uint16)
+    data = O.pack_v16_tiles(vb)
+    assert data.size == 2 * 8192
+    w = data.view("<u2")
+    # operand 0 (channels 0..15), lane 0 (quad 0, channel 0): slots = tokens 0,1,2,3,16,17,18,19
+    assert [int(x) for x in w[:8]] == [int(vb[r, 0]) for r in (0, 1, 2, 3, 16, 17, 18, 19)]
+    assert w[8] == vb[0, 1] and w[16 * 8] == vb[4, 0] and w[512] == vb[0, 16]       # lane 1; quad 1; operand 1
+    np.testing.assert_array_equal(O.unpack_v16_tiles(data, 45), vb)
+
+
+def test_mixed_cache_bytes_and_decode_from_physical_bytes():
+    rng = np.random.default_rng(47)
+    K, V, bt, bc = _mixed_case(rng)
+    cache = O.build_cache_mixed([K], [V], [bt], [bc])
+    # closed-form segment sizes
+    for item in range(2):
+        nq = O.channel_slots(bc[item])["nq"]
+        for ti, b in enumerate(O.PACK_ORDER):
+            n = int((bt[item] == b).sum())
+            assert cache["counts"][item, ti] == n
+            nt = (n + 31) // 32
+            sizes = [nt * O.k_tile_bytes_mixed(nq), nt * O.k_meta_bytes_mixed(nq),
+                     nt * (8192 if b == 16 else 512 * b), 0 if b == 16 else nt * 512]
+            offs = cache["seg_off"][item, ti]
+            assert all(int(o) % 256 == 0 for o in offs)
+            nxt = list(offs[1:]) + [cache["seg_off"][item, ti + 1, 0] if ti < 3 else
+                                    (cache["seg_off"][item + 1, 0, 0] if item == 0 else cache["arena"].size)]
+            for o, sz, o2 in zip(offs, sizes, nxt):
+                assert int(o) + sz <= int(o2) < int(o) + sz + 256
+    # decoding the physical bytes equals attention over the canonical dequantized rows
+    q = rand_bf16(rng, (1, 8, 128))
+    out, lse = O.decode(cache, q)
+    for j in range(8):
+        h = j // 4
+        rec = cache["canon"][h]
+        Kh = np.concatenate([O.dequantize_channelwise(rec[b]["k_codes"], rec[b]["k_scale"], rec[b]["k_off"], bc[h])
+                             for b in O.PACK_ORDER])
+        Vh = np.concatenate([O.bf16_from_bits(rec[16]["v_codes"]).astype(np.float64)] +
+                            [O.dequantize_groups(rec[b]["v_codes"].reshape(-1, 4, 32), rec[b]["v_scale"].view(np.float16),
+                                                 rec[b]["v_off"].view(np.float16)).reshape(-1, 128) for b in (8, 4, 2)])
+        o, l = _bruteforce_attention(q[0, j], Kh, Vh)
+        np.testing.assert_allclose(out[0, j], o, rtol=1e-11, atol=1e-12)
+    assert O.stored_bytes_mixed(cache["counts"], cache["bits_ch"]) < cache["arena"].size
+
+
+def test_allocate_mixed_meets_both_budgets():
+    # Sec. 3.2: B_V = B_K = B_head / 2; the K budget is spread over the retained tokens only
+    rng = np.random.default_rng(48)
+    T, d = 3000, 128
+    w_tok = (1.0 + rng.pareto(1.2, T)).astype(np.float32)
+    w_ch = np.exp(rng.standard_normal(d)).astype(np.float32)
+    for avg in (0.5, 1.0, 2.0):
+        bt, bc = O.allocate_mixed(w_tok, w_ch, np.float32(avg))
+        n_kept = int((bt > 0).sum())
+        assert int(bt.astype(np.int64).sum()) <= math.floor(avg * T)                    # V: mean b_t <= avg
+        k_avg = min(16.0, avg * T / n_kept)
+        assert int(bc.astype(np.int64).sum()) <= math.floor(np.float32(k_avg) * d)      # K: mean b_c <= k_avg
+        # whole-cache budget: nominal bits of V plus K never exceed avg bits per cache scalar
+        total_bits = int(bt.astype(np.int64).sum()) * d + int(bc.astype(np.int64).sum()) * n_kept
+        assert total_bits <= avg * 2 * T * d
+        assert set(np.unique(bt)) <= {0, 2, 4, 8, 16} and set(np.unique(bc)) <= {0, 2, 4, 8, 16}
+    bt, bc = O.allocate_mixed(w_tok, w_ch, np.float32(0.0))
+    assert not bt.any() and not bc.any()

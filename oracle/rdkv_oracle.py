@@ -729,13 +729,14 @@ def dequantize_channelwise(codes, scale, off, bits_ch):
 def _k_field_position(b, slot, mb):
     """(byte offset inside the lane's 2b bytes, bit shift) of the code of channel
     slot `slot` (0..7 of the quad) and token half `mb` for a quantized tier b.
-    The lane's bytes are b/2 little-endian 32-bit words; a 16-bit half of a word holds
-    16/b fields; field f of half hh of word w is slot 2*(w*(8/b) + f//2) + hh of
-    token half f % 2."""
-    F = 16 // b
+    The lane's bytes are b/2 little-endian 32-bit words.  Slots pair up as (2p, 2p+1)
+    in the low and high 16-bit halves of a word; a half holds 16/b fields, the first
+    8/b of them token half 0 and the rest token half 1, so that shifting a word right
+    by 8 bits puts the half-1 codes where the half-0 codes were.  With P = 8/b pairs
+    per word: pair p lives in word p // P at field P*mb + p % P of each half."""
+    P = 8 // b
     hh, pair = slot % 2, slot // 2
-    w, fpair = pair // (F // 2), pair % (F // 2)
-    f = 2 * fpair + mb
+    w, f = pair // P, P * mb + pair % P
     bit = 32 * w + 16 * hh + b * f
     return bit // 8, bit % 8
 

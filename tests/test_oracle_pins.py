@@ -819,22 +819,23 @@ def test_mixed_k_tile_layout_hand_checked_and_roundtrip():
     # tier 16 quad at byte 0: lane l16 owns 32 bytes: 8 bf16 of token l16 then 8 bf16 of token 16 + l16
     assert d16[0] == codes[0, 0] and d16[1] == codes[0, 1] and d16[8] == codes[16, 0] and d16[16] == codes[1, 0]
     assert d16[2] == 0                                             # padding slot
-    # tier 8 quad at byte 512: lane l16 owns 16 bytes, word d = [half0 slot 2d, half1 slot 2d, half0 slot 2d+1, ...]
+    # tier 8 quad at byte 512: lane l16 owns 16 bytes = 4 words, word p = slots (2p, 2p+1):
+    # bytes [slot 2p half 0, slot 2p half 1, slot 2p+1 half 0, slot 2p+1 half 1]
     assert data[512 + 0] == codes[0, 5] and data[512 + 1] == codes[16, 5] and data[512 + 2] == codes[0, 70]
     assert data[512 + 3] == codes[16, 70] and data[512 + 4] == codes[0, 100] and data[512 + 16] == codes[1, 5]
-    # tier 4 at byte 768: lane owns 8 bytes; nibbles of the first 16-bit half: slot 0 half 0, slot 0 half 1, slot 2 half 0, ...
-    b0 = int(data[768])
-    assert (b0 & 15, b0 >> 4) == (int(codes[0, 10]), int(codes[16, 10]))
-    b1 = int(data[769])
-    assert (b1 & 15, b1 >> 4) == (int(codes[0, 12]), int(codes[16, 12]))           # slot 2
+    # tier 4 at byte 768: lane owns 8 bytes = 2 words, two slot pairs per word.  First 16-bit half of word 0:
+    # nibbles [slot 0 half 0, slot 2 half 0, slot 0 half 1, slot 2 half 1]; second half: slots 1 and 3
+    b0, b1 = int(data[768]), int(data[769])
+    assert (b0 & 15, b0 >> 4) == (int(codes[0, 10]), int(codes[0, 12]))
+    assert (b1 & 15, b1 >> 4) == (int(codes[16, 10]), int(codes[16, 12]))
     b2 = int(data[770])
-    assert (b2 & 15, b2 >> 4) == (int(codes[0, 11]), int(codes[16, 11]))           # second half of word 0: slot 1
+    assert (b2 & 15, b2 >> 4) == (int(codes[0, 11]), int(codes[0, 13]))
     assert (int(data[772]) & 15) == int(codes[0, 14])                              # word 1: slot 4
     assert (int(data[768 + 128]) & 15) == int(codes[0, 18])                        # second quad: channels 18..20
-    # tier 2 at byte 1024: lane owns one word; fields of the first half: slot 0 (half 0, half 1), slot 2, ...
+    # tier 2 at byte 1024: lane owns one word; fields of the first half: slots 0, 2, 4, 6 of half 0, then of half 1
     w = int(data[1024:1028].view("<u4")[0])
-    assert (w & 3, (w >> 2) & 3, (w >> 4) & 3, (w >> 16) & 3) == \
-        (int(codes[0, 30]), int(codes[16, 30]), int(codes[0, 32]), int(codes[0, 31]))
+    assert (w & 3, (w >> 2) & 3, (w >> 8) & 3, (w >> 10) & 3, (w >> 16) & 3) == \
+        (int(codes[0, 30]), int(codes[0, 32]), int(codes[16, 30]), int(codes[16, 32]), int(codes[0, 31]))
     # second tile starts at tb; it holds rows 32..39 and zero rows after them
     assert data[tb + 512] == codes[32, 5] and data[tb + 512 + 1] == 0
     # metadata: scales of the quantized slots (8-bit quad, two 4-bit quads, 2-bit quad), then offsets

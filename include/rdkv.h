@@ -87,7 +87,9 @@ typedef struct rdkv_stats {
   int64_t n_items;          /* batch * hkv */
   int64_t rows[4];          /* kept tokens per tier, order 16, 8, 4, 2, summed over items */
   int64_t evicted;          /* tokens at 0 bits, summed over items */
-  int64_t stored_bytes;     /* bytes a decode step must read: codes + scale/offset metadata, unpadded */
+  int64_t stored_bytes;     /* bytes a decode step must read: codes + scale/offset metadata, unpadded
+                               (channel-wise mode: K codes n * sum_c b_c / 8 and 4 bytes per quantized channel
+                               and 32-token tile, V rows as in token-wise mode) */
   int64_t arena_bytes;      /* bytes allocated for the packed arena (with padding and alignment) */
   int64_t index_bytes;      /* kept-position lists, segment tables, split schedule */
   int64_t n_chunks;         /* work items of one decode launch */
@@ -147,6 +149,12 @@ rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const floa
  *   bits_tok DEVICE uint8 ragged [hkv][T_s]
  *   bits_ch  DEVICE uint8 [items][d] (channel-wise mode) or NULL
  *   out      HOST: receives the cache handle (library-owned; rdkv_cache_free)
+ * Token-wise mode: a token's K row and V row are both stored at bits_tok (groups of 32
+ * channels of the row).  Channel-wise mode (Sec. 3.2 Stage 3, App. B): bits_tok is the V
+ * map and decides which tokens are retained; the K rows of the retained tokens are stored
+ * channel by channel at bits_ch, channels sorted by bit-width, one scale and offset per
+ * channel and per 32 consecutive retained tokens of a tier segment; a channel at 0 bits is
+ * dropped (it contributes nothing to q.k), a channel at 16 bits keeps its bf16 values.
  */
 rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V,
                       const uint8_t* bits_tok, const uint8_t* bits_ch, void* stream,
@@ -159,7 +167,8 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V,
 /*
  * One decode step over the packed cache (Sec. 3.3, Eq. 7 without the new-token
  * zone): for every sequence and query head, softmax(q K_hat^T / sqrt d) V_hat
- * over the retained tokens, dequantization fused into the attention kernel.
+ * over the retained tokens, dequantization fused into the attention kernel (in
+ * channel-wise mode the per-channel scales are folded into the query, App. B).
  *   q    DEVICE bf16 [batch][hq][d]
  *   out  DEVICE fp32 [batch][hq][d]
  *   lse  DEVICE fp32 [batch][hq] or NULL: natural-log sum of exp of the logits

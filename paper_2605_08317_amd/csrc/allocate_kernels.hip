@@ -116,7 +116,30 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   }
 }
 
+// retained units (bit-width above zero) of every item: Stage 3 spreads the K budget over them
+__global__ __launch_bounds__(256) void count_kept_kernel(const uint8_t* __restrict__ bits,
+                                                         const int64_t* __restrict__ item_off,
+                                                         const int32_t* __restrict__ item_U,
+                                                         int32_t* __restrict__ kept) {
+  __shared__ int sm[4];
+  const int item = blockIdx.x;
+  const uint8_t* b = bits + item_off[item];
+  int c = 0;
+  for (int u = threadIdx.x; u < item_U[item]; u += 256) c += b[u] != 0;
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) kept[item] = sm[0] + sm[1] + sm[2] + sm[3];
+}
+
 }  // namespace
+
+hipError_t launch_count_kept(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U, int n_items,
+                             int32_t* kept, hipStream_t st) {
+  if (n_items == 0) return hipSuccess;
+  hipLaunchKernelGGL(count_kept_kernel, dim3(n_items), dim3(256), 0, st, bits, d_item_off, d_item_U, kept);
+  return hipGetLastError();
+}
 
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,

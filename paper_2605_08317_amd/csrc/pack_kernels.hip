@@ -129,6 +129,9 @@ struct PackArgs {
   const int64_t* item_row_off; // [items]: first row of the item's [T][d] block in K / V
   uint8_t* arena;
   int32_t ti;                  // which stored tier this launch packs
+  int32_t v_only;              // mixed mode: K is packed channel-wise by pack_k_mixed_kernel
+  const ItemK* items_k;        // [items] (mixed mode)
+  const uint8_t* bits_ch;      // [items][128] (mixed mode)
 };
 
 // 16-bit tier: the kept bf16 rows are copied verbatim, row-major (one thread = 64 bytes of K and of V)
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(256) void quant_pack_tile_kernel(PackArgs a) {
       t = fminf(fmaxf(t, 0.0f), Q);
       s_codes[w][row][grp * 32 + i] = (s == 0.0f) ? uint8_t(0) : static_cast<uint8_t>(t);
     }
-    if (row < valid) {
+    if (row < valid && !(a.v_only && w == 0)) {
       const int mb = row >> 4, quad = (row & 15) >> 2, i = row & 3;
       int si, oi;
       if (w == 0) {
@@ -255,6 +258,7 @@ __global__ __launch_bounds__(256) void quant_pack_tile_kernel(PackArgs a) {
   constexpr int kWords = kRowPad * kHeadDim * BITS / 32;      // 1024 / 512 / 256
 #pragma unroll
   for (int w = 0; w < 2; ++w) {
+    if (a.v_only && w == 0) continue;
     uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[w * 2] +
                                                 static_cast<int64_t>(blockIdx.x) * (kRowPad * kHeadDim * BITS / 8));
     for (int word = tid; word < kWords; word += 256) {
@@ -281,6 +285,148 @@ __global__ __launch_bounds__(256) void quant_pack_tile_kernel(PackArgs a) {
       }
       dst[word] = out;
     }
+  }
+}
+
+
+// ---- mixed mode -------------------------------------------------------------------------------------------------
+// 16-bit V rows as 32-token tiles with the lane / operand / slot assignment of the quantized V tiers:
+// the bf16 of (lane, operand o, slot s) sits at byte 1024 o + 16 lane + 2 s of the 8 KiB tile.
+__global__ __launch_bounds__(256) void pack_v16_tile_kernel(PackArgs a) {
+  constexpr int kRowStride = kHeadDim + 8;
+  __shared__ __align__(16) uint16_t s_rows[kRowPad][kRowStride];
+  const int item = blockIdx.y;
+  const int n = a.counts[item * 4 + a.ti];
+  const int r0 = blockIdx.x * kRowPad;
+  if (r0 >= n) return;
+  const int valid = min(kRowPad, n - r0);
+  const int tid = threadIdx.x;
+  const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
+  {
+    const int row = tid >> 3, part = tid & 7;
+    uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+    if (row < valid) {
+      const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + r0 + row];
+      const uint4* p = reinterpret_cast<const uint4*>(a.V + (a.item_row_off[item] + pos) * kHeadDim + part * 16);
+      v0 = p[0];
+      v1 = p[1];
+    }
+    uint4* d = reinterpret_cast<uint4*>(&s_rows[row][part * 16]);
+    d[0] = v0;
+    d[1] = v1;
+  }
+  __syncthreads();
+  uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[2] + static_cast<int64_t>(blockIdx.x) * (kRowPad * kHeadDim * 2));
+  for (int word = tid; word < kRowPad * kHeadDim / 2; word += 256) {
+    const int o = word >> 8, lane = (word >> 2) & 63, sp = word & 3;
+    int r, c;
+    tile_rc(true, lane, o, 2 * sp, &r, &c);
+    const uint32_t lo = s_rows[r][c];
+    tile_rc(true, lane, o, 2 * sp + 1, &r, &c);
+    dst[word] = lo | (static_cast<uint32_t>(s_rows[r][c]) << 16);
+  }
+}
+
+// Channel-wise K of one 32-token tile (Sec. 3.2 Stage 3 on the retained tokens): every channel is quantized at
+// its own bit-width over the tile's valid rows (one group = 32 consecutive retained tokens of one channel) and the
+// codes are written in sorted-channel order.  Lane l16 of a quad owns 2b bytes: tokens l16 and 16 + l16 for the
+// quad's 8 slots.  Slots pair up in the two halves of a 32-bit word; with P = 8/b pairs per word, pair p sits in
+// word p / P at field P * mb + p % P of each half (mb = token half); tier 16 stores 8 bf16 per token half.
+__global__ __launch_bounds__(256) void pack_k_mixed_kernel(PackArgs a) {
+  constexpr int kRowStride = kHeadDim + 8;
+  __shared__ __align__(16) uint16_t s_rows[kRowPad][kRowStride];
+  __shared__ uint16_t s_codes[kRowPad][kHeadDim + 2];
+  __shared__ uint16_t s_sc[kHeadDim], s_of[kHeadDim];
+  __shared__ ItemK s_ik;
+  const int item = blockIdx.y;
+  const int n = a.counts[item * 4 + a.ti];
+  const int r0 = blockIdx.x * kRowPad;
+  if (r0 >= n) return;
+  const int valid = min(kRowPad, n - r0);
+  const int tid = threadIdx.x;
+  const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
+  for (int i = tid; i < static_cast<int>(sizeof(ItemK) / 4); i += 256)
+    reinterpret_cast<uint32_t*>(&s_ik)[i] = reinterpret_cast<const uint32_t*>(a.items_k + item)[i];
+  {
+    const int row = tid >> 3, part = tid & 7;
+    uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+    if (row < valid) {
+      const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + r0 + row];
+      const uint4* p = reinterpret_cast<const uint4*>(a.K + (a.item_row_off[item] + pos) * kHeadDim + part * 16);
+      v0 = p[0];
+      v1 = p[1];
+    }
+    uint4* d = reinterpret_cast<uint4*>(&s_rows[row][part * 16]);
+    d[0] = v0;
+    d[1] = v1;
+  }
+  __syncthreads();
+  if (tid < kHeadDim) {
+    const int c = tid;
+    const int b = a.bits_ch[item * kHeadDim + c];
+    uint16_t sc = 0, of = 0;
+    if (b == 16) {
+      for (int r = 0; r < kRowPad; ++r) s_codes[r][c] = s_rows[r][c];      // rows beyond `valid` are zero
+    } else if (b == 8 || b == 4 || b == 2) {
+      float mn = __uint_as_float(static_cast<uint32_t>(s_rows[0][c]) << 16), mx = mn;
+      for (int r = 1; r < valid; ++r) {
+        const float x = __uint_as_float(static_cast<uint32_t>(s_rows[r][c]) << 16);
+        mn = fminf(mn, x);
+        mx = fmaxf(mx, x);
+      }
+      mn = mn + 0.0f;
+      const float Q = static_cast<float>((1 << b) - 1);
+      const _Float16 sh = static_cast<_Float16>((mx - mn) / Q);
+      const _Float16 mh = static_cast<_Float16>(mn);
+      const float s = static_cast<float>(sh), m = static_cast<float>(mh);
+      for (int r = 0; r < kRowPad; ++r) {
+        const float x = __uint_as_float(static_cast<uint32_t>(s_rows[r][c]) << 16);
+        float t = rintf((x - m) / s);
+        t = fminf(fmaxf(t, 0.0f), Q);
+        s_codes[r][c] = (s == 0.0f || r >= valid) ? uint16_t(0) : static_cast<uint16_t>(t);
+      }
+      sc = __builtin_bit_cast(unsigned short, sh);
+      of = __builtin_bit_cast(unsigned short, mh);
+    } else {
+      for (int r = 0; r < kRowPad; ++r) s_codes[r][c] = 0;
+    }
+    s_sc[c] = sc;
+    s_of[c] = of;
+  }
+  __syncthreads();
+
+  uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[0] + static_cast<int64_t>(blockIdx.x) * s_ik.kt_bytes);
+  for (int word = tid; word < s_ik.kt_bytes / 4; word += 256) {
+    const int byte = word * 4;
+    int t = 3;
+    while (t > 0 && byte < s_ik.tier_base[t]) --t;
+    while (t < 3 && s_ik.nq[t] == 0) ++t;            // empty tiers share their base with the next one
+    const int b = 16 >> t;
+    const int off = byte - s_ik.tier_base[t];
+    const int quad = off / (32 * b), l16 = (off % (32 * b)) / (2 * b), wi = (off % (2 * b)) >> 2;
+    const int16_t* sl = s_ik.slot_ch + s_ik.slot_base[t] + 8 * quad;
+    uint32_t out = 0;
+    if (b == 16) {
+      const int mb = wi >> 2, j = 2 * (wi & 3);
+      const int c0 = sl[j], c1 = sl[j + 1];
+      if (c0 >= 0) out |= s_codes[16 * mb + l16][c0];
+      if (c1 >= 0) out |= static_cast<uint32_t>(s_codes[16 * mb + l16][c1]) << 16;
+    } else {
+      const int P = 8 / b;
+      for (int hh = 0; hh < 2; ++hh)
+        for (int f = 0; f < 2 * P; ++f) {
+          const int mb = f / P, slot = 2 * (wi * P + f % P) + hh;
+          const int c = sl[slot];
+          if (c >= 0) out |= static_cast<uint32_t>(s_codes[16 * mb + l16][c]) << (16 * hh + b * f);
+        }
+    }
+    dst[word] = out;
+  }
+  uint16_t* meta = reinterpret_cast<uint16_t*>(a.arena + so[1] + static_cast<int64_t>(blockIdx.x) * s_ik.km_bytes);
+  for (int j = tid; j < s_ik.n_qslots; j += 256) {
+    const int c = s_ik.slot_ch[s_ik.slot_base[1] + j];
+    meta[j] = c >= 0 ? s_sc[c] : uint16_t(0);
+    meta[s_ik.n_qslots + j] = c >= 0 ? s_of[c] : uint16_t(0);
   }
 }
 
@@ -311,14 +457,20 @@ hipError_t launch_tier_scatter(const uint8_t* bits, const int64_t* item_tok_off,
 hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t* tier_idx,
                              const int64_t* idx_base, const int32_t* counts, const int64_t* seg_off,
                              const int64_t* item_row_off, uint8_t* arena, int n_items,
-                             const int32_t max_count[4], hipStream_t st) {
+                             const int32_t max_count[4], const ItemK* items_k, const uint8_t* bits_ch,
+                             hipStream_t st) {
+  const bool mixed = items_k != nullptr;
   for (int ti = 0; ti < 4; ++ti) {
     if (max_count[ti] == 0) continue;
-    PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti};
+    PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti, mixed ? 1 : 0, items_k, bits_ch};
     dim3 grid_rows((max_count[ti] + 63) / 64, n_items), grid_tiles((max_count[ti] + kRowPad - 1) / kRowPad, n_items);
     dim3 block(256);
+    if (mixed) hipLaunchKernelGGL(pack_k_mixed_kernel, grid_tiles, block, 0, st, a);
     switch (ti) {
-      case 0: hipLaunchKernelGGL(copy_rows_kernel, grid_rows, block, 0, st, a); break;
+      case 0:
+        if (mixed) hipLaunchKernelGGL(pack_v16_tile_kernel, grid_tiles, block, 0, st, a);
+        else hipLaunchKernelGGL(copy_rows_kernel, grid_rows, block, 0, st, a);
+        break;
       case 1: hipLaunchKernelGGL(quant_pack_tile_kernel<8>, grid_tiles, block, 0, st, a); break;
       case 2: hipLaunchKernelGGL(quant_pack_tile_kernel<4>, grid_tiles, block, 0, st, a); break;
       default: hipLaunchKernelGGL(quant_pack_tile_kernel<2>, grid_tiles, block, 0, st, a); break;

@@ -22,7 +22,8 @@ hipError_t launch_tier_scatter(const uint8_t* bits, const int64_t* item_tok_off,
 hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t* tier_idx,
                              const int64_t* idx_base, const int32_t* counts, const int64_t* seg_off,
                              const int64_t* item_row_off, uint8_t* arena, int n_items,
-                             const int32_t max_count[4], hipStream_t st);
+                             const int32_t max_count[4], const ItemK* items_k, const uint8_t* bits_ch,
+                             hipStream_t st);
 int partition_block();
 int weights_block();
 size_t weights_scratch_floats(int64_t n_blocks, int64_t n_items, int64_t total_tokens, int R_pad, bool want_ch);
@@ -33,6 +34,8 @@ hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off,
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
                            const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, hipStream_t st);
+hipError_t launch_count_kept(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U, int n_items,
+                             int32_t* kept, hipStream_t st);
 }  // namespace rdkv
 
 using namespace rdkv;
@@ -213,6 +216,33 @@ void free_cache_buffers(rdkv_cache* c) {
   al.put(c->d_part_ml);
   al.put(c->d_bits_tok);
   al.put(c->d_bits_ch);
+  al.put(c->d_items_k);
+}
+
+// Sorted-channel layout of one item's K tiles from its channel bit map.
+ItemK make_item_k(const uint8_t* bits_ch) {
+  ItemK k;
+  std::memset(&k, 0, sizeof(k));
+  int slot = 0, byte = 0;
+  for (int ti = 0; ti < 4; ++ti) {
+    const int b = pack_tier_bits(ti);
+    k.slot_base[ti] = static_cast<int16_t>(slot);
+    k.tier_base[ti] = static_cast<int16_t>(byte);
+    int cnt = 0;
+    for (int c = 0; c < kHeadDim; ++c)
+      if (bits_ch[c] == b) k.slot_ch[slot + cnt++] = static_cast<int16_t>(c);
+    const int nq = (cnt + 7) / 8;
+    for (int j = cnt; j < 8 * nq; ++j) k.slot_ch[slot + j] = -1;
+    k.nq[ti] = static_cast<int16_t>(nq);
+    slot += 8 * nq;
+    byte += nq * 32 * b;
+  }
+  k.n_slots = static_cast<int16_t>(slot);
+  k.n_qslots = static_cast<int16_t>(slot - 8 * k.nq[0]);
+  k.kt_bytes = byte;
+  k.km_bytes = 4 * k.n_qslots;
+  for (int j = slot; j < kMaxSlots; ++j) k.slot_ch[j] = -1;
+  return k;
 }
 
 // Lower convex hull of (b_k, eps_k) and the threshold ratios r_k = db / (-d eps) of its edges.
@@ -356,34 +386,73 @@ rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const floa
   rdkv_status s = check_config(cfg, true, false);
   if (s != RDKV_OK) return s;
   if (!w_tok || !bits_tok) return fail(RDKV_ERR_INVALID_ARG, "w_tok and bits_tok must not be null");
-  if (cfg->k_mode == RDKV_K_CHANNELWISE)
-    return fail(RDKV_ERR_UNSUPPORTED, "channel-wise K allocation is not implemented yet");
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
+  if (mixed && (!w_ch || !bits_ch))
+    return fail(RDKV_ERR_INVALID_ARG, "w_ch and bits_ch must not be null in channel-wise mode");
   if (cfg->batch == 0) return RDKV_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
   Temp tmp(al);
   Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  const int64_t n = it.n_items;
   std::vector<int> ht;
   std::vector<double> hr;
   hull_thresholds(cfg, cfg->eps_v, &ht, &hr);
-  std::vector<double> budget(it.n_items);
-  for (int64_t i = 0; i < it.n_items; ++i) budget[i] = static_cast<double>(cfg->budget_bits[i / cfg->hkv]);
-  int64_t* d_off = tmp.get<int64_t>(it.n_items);
-  int32_t* d_T = tmp.get<int32_t>(it.n_items);
-  double* d_budget = tmp.get<double>(it.n_items);
+  // Stage 2.  Token-wise mode: the sequence's average serves K and V alike.  Channel-wise mode: V gets the share
+  // 1 - r_K of the head budget, i.e. 2 (1 - r_K) avg_bits per token unit (rounded to fp32 like every budget).
+  std::vector<double> budget(n);
+  for (int64_t i = 0; i < n; ++i) {
+    const double a = static_cast<double>(cfg->budget_bits[i / cfg->hkv]);
+    budget[i] = mixed ? static_cast<double>(static_cast<float>(2.0 * (1.0 - static_cast<double>(cfg->kv_split_rk)) * a))
+                      : a;
+  }
+  int64_t* d_off = tmp.get<int64_t>(n);
+  int32_t* d_T = tmp.get<int32_t>(n);
+  double* d_budget = tmp.get<double>(n);
   if (!d_off || !d_T || !d_budget) return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_budget, budget.data(), it.n_items * sizeof(double), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_budget, budget.data(), n * sizeof(double), hipMemcpyHostToDevice, st));
   {
   TimedScope ts(RDKV_TIME_ALLOCATE, st);
-  RDKV_HIP(launch_allocate(w_tok, d_off, d_T, d_budget, static_cast<int>(it.n_items), static_cast<int>(ht.size()),
+  RDKV_HIP(launch_allocate(w_tok, d_off, d_T, d_budget, static_cast<int>(n), static_cast<int>(ht.size()),
                            ht.data(), hr.data(), 1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters,
                            bits_tok, st));
   }
+  if (!mixed) {
+    RDKV_HIP(hipStreamSynchronize(st));
+    return RDKV_OK;
+  }
+  // Stage 3: the K budget r_K * B_head is spread over the retained tokens only:
+  // k_avg = min(16, 2 r_K avg_bits T / n_kept) average bits per channel unit.
+  int32_t* d_kept = tmp.get<int32_t>(n);
+  int64_t* d_ch_off = tmp.get<int64_t>(n);
+  int32_t* d_ch_U = tmp.get<int32_t>(n);
+  double* d_kbudget = tmp.get<double>(n);
+  if (!d_kept || !d_ch_off || !d_ch_U || !d_kbudget) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  std::vector<int32_t> kept(n);
+  RDKV_HIP(launch_count_kept(bits_tok, d_off, d_T, static_cast<int>(n), d_kept, st));
+  RDKV_HIP(hipMemcpyAsync(kept.data(), d_kept, n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
   RDKV_HIP(hipStreamSynchronize(st));
-  (void)w_ch;
-  (void)bits_ch;
+  std::vector<int64_t> ch_off(n);
+  std::vector<int32_t> ch_U(n, kHeadDim);
+  std::vector<double> kbudget(n);
+  for (int64_t i = 0; i < n; ++i) {
+    ch_off[i] = i * kHeadDim;
+    const double a = static_cast<double>(cfg->budget_bits[i / cfg->hkv]);
+    const double rk = static_cast<double>(cfg->kv_split_rk);
+    double k_avg = 0.0;    // nothing retained: no key is stored
+    if (kept[i] > 0) k_avg = std::min(16.0, 2.0 * rk * a * static_cast<double>(it.T[i]) / static_cast<double>(kept[i]));
+    kbudget[i] = static_cast<double>(static_cast<float>(k_avg));
+  }
+  hull_thresholds(cfg, cfg->eps_k, &ht, &hr);
+  RDKV_HIP(hipMemcpyAsync(d_ch_off, ch_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_ch_U, ch_U.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_kbudget, kbudget.data(), n * sizeof(double), hipMemcpyHostToDevice, st));
+  RDKV_HIP(launch_allocate(w_ch, d_ch_off, d_ch_U, d_kbudget, static_cast<int>(n), static_cast<int>(ht.size()),
+                           ht.data(), hr.data(), 1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_ch,
+                           st));
+  RDKV_HIP(hipStreamSynchronize(st));
   return RDKV_OK;
 }
 
@@ -393,14 +462,14 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   rdkv_status s = check_config(cfg, false, false);
   if (s != RDKV_OK) return s;
   if (!out) return fail(RDKV_ERR_INVALID_ARG, "out is null");
-  if (cfg->k_mode == RDKV_K_CHANNELWISE)
-    return fail(RDKV_ERR_UNSUPPORTED, "channel-wise K packing is not implemented yet");
-  (void)bits_ch;
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
   Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
   if (it.total_tokens > 0 && (!K || !V || !bits_tok))
     return fail(RDKV_ERR_INVALID_ARG, "K, V and bits_tok must not be null");
+  if (mixed && it.n_items > 0 && !bits_ch)
+    return fail(RDKV_ERR_INVALID_ARG, "bits_ch must not be null in channel-wise mode");
   const int g = cfg->hq / cfg->hkv;
 
   rdkv_cache* c = new (std::nothrow) rdkv_cache();
@@ -438,7 +507,23 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
                                it.max_T, st));
     if (it.max_T > 0)
       PACK_HIP(hipMemcpyAsync(c->counts.data(), d_counts, n * 4 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    std::vector<uint8_t> h_bits_ch;
+    if (mixed) {
+      h_bits_ch.resize(n * kHeadDim);
+      PACK_HIP(hipMemcpyAsync(h_bits_ch.data(), bits_ch, n * kHeadDim, hipMemcpyDeviceToHost, st));
+    }
     PACK_HIP(hipStreamSynchronize(st));
+    if (mixed) {
+      c->items_k.resize(n);
+      for (int64_t i = 0; i < n; ++i) {
+        for (int ch = 0; ch < kHeadDim; ++ch)
+          if (!valid_tier(h_bits_ch[i * kHeadDim + ch]))
+            return bail(fail(RDKV_ERR_INVALID_ARG, "bits_ch[%lld][%d] = %d is not a tier", static_cast<long long>(i),
+                             ch, h_bits_ch[i * kHeadDim + ch]));
+        c->items_k[i] = make_item_k(&h_bits_ch[i * kHeadDim]);
+        c->max_kt_bytes = std::max(c->max_kt_bytes, c->items_k[i].kt_bytes);
+      }
+    }
   }
 
   // ---- plan: kept-position lists, arena segments, split schedule -------------------------
@@ -453,18 +538,37 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
       kept += cnt;
       max_count[ti] = std::max<int32_t>(max_count[ti], static_cast<int32_t>(cnt));
       const int64_t npad = round_up(cnt, kRowPad);
-      const int64_t sizes[4] = {npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits),
-                                npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits)};
+      int64_t sizes[4] = {npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits),
+                          npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits)};
+      if (mixed) {   // the K segments hold the channel-wise tiles of this tier's tokens
+        sizes[0] = npad / kRowPad * c->items_k[i].kt_bytes;
+        sizes[1] = npad / kRowPad * c->items_k[i].km_bytes;
+      }
       for (int si = 0; si < 4; ++si) {
         cur = round_up(cur, kSegAlign);
         c->seg_off[(i * 4 + ti) * 4 + si] = cur;
         cur += sizes[si];
       }
-      stored += cnt * 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+      if (mixed) {
+        int64_t kbits = 0, nquant = 0;
+        const ItemK& ik = c->items_k[i];
+        for (int s2 = 0; s2 < ik.n_slots; ++s2)
+          if (ik.slot_ch[s2] >= 0) {
+            int t2 = 3;
+            while (t2 > 0 && s2 < ik.slot_base[t2]) --t2;
+            kbits += pack_tier_bits(t2);
+            nquant += t2 > 0;
+          }
+        stored += cnt * kbits / 8 + (cnt + kRowPad - 1) / kRowPad * 4 * nquant;
+        stored += cnt * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+      } else {
+        stored += cnt * 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+      }
     }
   }
   c->arena_bytes = round_up(cur, kSegAlign);
   c->kept_total = kept;
+  c->stored_bytes = stored;
 
   // byte-balanced chunks: every workgroup streams about the same number of stored bytes
   int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>(32 << 10, stored / 2048));
@@ -476,15 +580,18 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
       const int bits = pack_tier_bits(ti);
       const int64_t cnt = c->counts[i * 4 + ti];
       if (cnt == 0) continue;
-      const int64_t per_row = 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+      int64_t per_row = 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+      if (mixed)
+        per_row = tier_row_bytes(bits) + tier_meta_bytes(bits) +
+                  (c->items_k[i].kt_bytes + c->items_k[i].km_bytes + kRowPad - 1) / kRowPad;
       const int64_t want = std::max<int64_t>(64, chunk_bytes / per_row);
       const int64_t nch = (cnt + want - 1) / want;
       const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
       const int64_t* so = &c->seg_off[(i * 4 + ti) * 4];
       for (int64_t r0 = 0; r0 < cnt; r0 += rows_per) {
         Chunk ch;
-        ch.k_data = so[0] + r0 * tier_row_bytes(bits);
-        ch.k_meta = so[1] + r0 * tier_meta_bytes(bits);
+        ch.k_data = so[0] + (mixed ? r0 / kRowPad * c->items_k[i].kt_bytes : r0 * tier_row_bytes(bits));
+        ch.k_meta = so[1] + (mixed ? r0 / kRowPad * c->items_k[i].km_bytes : r0 * tier_meta_bytes(bits));
         ch.v_data = so[2] + r0 * tier_row_bytes(bits);
         ch.v_meta = so[3] + r0 * tier_meta_bytes(bits);
         ch.rows = static_cast<int32_t>(std::min<int64_t>(rows_per, cnt - r0));
@@ -515,6 +622,11 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   c->d_part_acc = static_cast<float*>(al.get(std::max<int64_t>(n_chunks, 1) * g * kHeadDim * sizeof(float)));
   c->d_part_ml = static_cast<float*>(al.get(std::max<int64_t>(n_chunks, 1) * g * 2 * sizeof(float)));
   c->d_bits_tok = static_cast<uint8_t*>(al.get(std::max<int64_t>(it.total_tokens, 1)));
+  if (mixed) {
+    c->d_bits_ch = static_cast<uint8_t*>(al.get(std::max<int64_t>(n, 1) * kHeadDim));
+    c->d_items_k = static_cast<ItemK*>(al.get(std::max<int64_t>(n, 1) * sizeof(ItemK)));
+    if (!c->d_bits_ch || !c->d_items_k) return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
+  }
   if (!c->d_arena || !c->d_tier_idx || !c->d_chunks || !c->d_slot_begin || !c->d_slot_count || !c->d_part_acc ||
       !c->d_part_ml || !c->d_bits_tok)
     return bail(fail(RDKV_ERR_ALLOC, "device allocation of the packed cache failed (%lld arena bytes)",
@@ -531,13 +643,17 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
     PACK_HIP(hipMemcpyAsync(c->d_slot_count, slot_count.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
     if (it.total_tokens > 0)
       PACK_HIP(hipMemcpyAsync(c->d_bits_tok, bits_tok, it.total_tokens, hipMemcpyDeviceToDevice, st));
+    if (mixed) {
+      PACK_HIP(hipMemcpyAsync(c->d_bits_ch, bits_ch, n * kHeadDim, hipMemcpyDeviceToDevice, st));
+      PACK_HIP(hipMemcpyAsync(c->d_items_k, c->items_k.data(), n * sizeof(ItemK), hipMemcpyHostToDevice, st));
+    }
     if (kept > 0) {
       PACK_HIP(launch_tier_scatter(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_idx_base, c->d_tier_idx,
                                    static_cast<int>(n), it.max_T, st));
       TimedScope ts(RDKV_TIME_PACK, st);
       PACK_HIP(launch_quant_pack(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), c->d_tier_idx,
                                  d_idx_base, d_counts, d_seg_off, d_tok_off, c->d_arena, static_cast<int>(n),
-                                 max_count, st));
+                                 max_count, mixed ? c->d_items_k : nullptr, mixed ? c->d_bits_ch : nullptr, st));
     }
     PACK_HIP(hipStreamSynchronize(st));   // host vectors and scratch go out of scope
   }
@@ -552,25 +668,37 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, 
   rdkv_status s = check_config(cfg, true, true);
   if (s != RDKV_OK) return s;
   if (!out) return fail(RDKV_ERR_INVALID_ARG, "out is null");
-  if (cfg->k_mode == RDKV_K_CHANNELWISE)
-    return fail(RDKV_ERR_UNSUPPORTED, "channel-wise K compression is not implemented yet");
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
   Temp tmp(al);
   Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
   float* w = tmp.get<float>(std::max<int64_t>(it.total_tokens, 1));
   uint8_t* bits = tmp.get<uint8_t>(std::max<int64_t>(it.total_tokens, 1));
-  if (!w || !bits) return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  s = rdkv_weights(cfg, K, Q_obs, w, nullptr, stream);
+  float* w_ch = mixed ? tmp.get<float>(std::max<int64_t>(it.n_items, 1) * kHeadDim) : nullptr;
+  uint8_t* bits_ch = mixed ? tmp.get<uint8_t>(std::max<int64_t>(it.n_items, 1) * kHeadDim) : nullptr;
+  if (!w || !bits || (mixed && (!w_ch || !bits_ch))) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  s = rdkv_weights(cfg, K, Q_obs, w, w_ch, stream);
   if (s != RDKV_OK) return s;
-  s = rdkv_allocate(cfg, w, nullptr, bits, nullptr, stream);
+  s = rdkv_allocate(cfg, w, w_ch, bits, bits_ch, stream);
   if (s != RDKV_OK) return s;
-  return rdkv_pack(cfg, K, V, bits, nullptr, stream, out);
+  return rdkv_pack(cfg, K, V, bits, bits_ch, stream, out);
 }
 
 rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, float* lse, void* stream) {
   if (!c || !q || !out) return fail(RDKV_ERR_INVALID_ARG, "cache, q and out must not be null");
   if (c->n_items == 0) return RDKV_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (c->k_mode == RDKV_K_CHANNELWISE) {
+    {
+      TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
+      RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->chunks.size()), c->d_arena, c->d_items_k,
+                                   c->max_kt_bytes, static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
+                                   c->hq, c->hkv, st));
+    }
+    RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
+                                        static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));
+    return RDKV_OK;
+  }
   {
     TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
     const int n16 = static_cast<int>(c->n_chunks16), nq = static_cast<int>(c->chunks.size()) - n16;
@@ -645,8 +773,9 @@ rdkv_status rdkv_cache_stats(const rdkv_cache* c, rdkv_stats* out) {
       const int64_t cnt = c->counts[i * 4 + ti];
       out->rows[ti] += cnt;
       kept += cnt;
-      out->stored_bytes += cnt * 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
+      (void)bits;
     }
+  out->stored_bytes = c->stored_bytes;
   out->evicted = c->total_tokens - kept;
   out->arena_bytes = c->arena_bytes;
   out->index_bytes = c->index_bytes;

@@ -31,6 +31,20 @@ struct Chunk {
   int32_t slot;                             // partial-result slot
 };
 
+// Channel-wise K (mixed mode): how one item's K tiles are laid out.  Channels are sorted by bit-width into
+// slots: tiers 16, 8, 4, 2 in this order, each padded to whole quads of 8 channels; a quad of tier b takes
+// 32 b bytes of a 32-token tile.
+constexpr int kMaxSlots = 160;   // 128 channels + up to 7 padding slots per tier
+struct ItemK {
+  int32_t kt_bytes;              // K tile data bytes
+  int32_t km_bytes;              // K tile metadata bytes: fp16 scales of the quantized slots, then their offsets
+  int16_t nq[4];                 // quads per tier (16, 8, 4, 2)
+  int16_t tier_base[4];          // byte offset of each tier inside a tile
+  int16_t slot_base[4];          // first slot of each tier
+  int16_t n_slots, n_qslots;     // all slots; slots of the quantized tiers
+  int16_t slot_ch[kMaxSlots];    // channel held by a slot, -1 for padding
+};
+
 struct DenseArgs {
   const uint16_t* K;
   const uint16_t* V;
@@ -55,6 +69,9 @@ hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_m
 
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
                                float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
+hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
+                               int max_kt_bytes, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv,
+                               hipStream_t st);
 
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);
@@ -92,7 +109,11 @@ struct rdkv_cache {
   float* d_part_acc = nullptr;
   float* d_part_ml = nullptr;
   uint8_t* d_bits_tok = nullptr;        // copy of the token bit map
-  uint8_t* d_bits_ch = nullptr;
+  uint8_t* d_bits_ch = nullptr;         // [items][128] K channel bit map (mixed mode)
+  rdkv::ItemK* d_items_k = nullptr;     // [items] (mixed mode)
+  std::vector<rdkv::ItemK> items_k;
+  int32_t max_kt_bytes = 0;
+  int64_t stored_bytes = 0;             // bytes a decode step must read (unpadded)
   int64_t index_bytes = 0;
   rdkv_alloc_fn alloc = nullptr;
   rdkv_free_fn free_ = nullptr;

@@ -192,7 +192,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
 
     // ---- P V: slot j = 4mb + i of this lane is token 16mb + 4quad + i ----------------
     {
-      const float neg_mc = -m_run * kXScale;
+      const float neg_mc = kPExp - m_run * kXScale;   // probabilities times 2^kPExp
       Pack8 ph;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
@@ -236,7 +236,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (quad == 0) {
-    s_ml[(wave * 16 + l16) * 2] = m_run * kXScale;   // running maximum in the log2 domain from here on
+    s_ml[(wave * 16 + l16) * 2] = m_run * kXScale - kPExp;   // running maximum in the log2 domain from here on
     s_ml[(wave * 16 + l16) * 2 + 1] = l_run;
   }
   __syncthreads();

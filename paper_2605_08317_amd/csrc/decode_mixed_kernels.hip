@@ -222,7 +222,7 @@ __device__ __forceinline__ void process_mixed(const ItemK& ik, const uint8_t* __
     }
 
     // ---- P V: slot j = 4mb + i of this lane is token 16mb + 4quad + i ----------------
-    const float neg_mc = -m_run * kXScale;
+    const float neg_mc = kPExp - m_run * kXScale;   // probabilities times 2^kPExp
     float p[8];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -279,7 +279,7 @@ __device__ __forceinline__ void process_mixed(const ItemK& ik, const uint8_t* __
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (quad == 0) {
-    s_ml[(wave * 16 + l16) * 2] = m_run * kXScale;   // log2 domain from here on
+    s_ml[(wave * 16 + l16) * 2] = m_run * kXScale - kPExp;   // log2 domain from here on
     s_ml[(wave * 16 + l16) * 2 + 1] = l_run;
   }
   __syncthreads();

@@ -24,6 +24,12 @@ constexpr int kQExp = 4;                                   // keeps the scaled q
 constexpr float kKUnit = 1.0f / static_cast<float>(1 << (24 - kQExp));   // K partial products come out times this
 constexpr float kXScale = kLogitScale * static_cast<float>(1 << (24 - kQExp));
 
+// The probabilities exp2(x - running maximum) are carried times 2^kPExp, so that after the multiplication by a
+// V scale they stay in fp16's normal range for flat attention over tens of thousands of tokens (p ~ 1e-5); the
+// factor is returned by reporting the running maximum kPExp lower to the merge.  2^kPExp * scale must stay below
+// 65504, which holds for V scales below 1023.
+constexpr float kPExp = 6.0f;
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 union Pack8 {

@@ -1,0 +1,135 @@
+"""GPU parity at the full sizes of the BASELINE configs, in the launch configuration bench.py times (one
+rdkv_compress and one rdkv_decode_attn call per layer / batch).  The oracle cannot redo a whole 128K-token layer in
+seconds, so it recomputes sampled items (sequence, KV head) one by one from the library's own fp32 weights: their
+bit maps, kept-position lists and packed bytes must match bit for bit, their decode outputs within 2e-3; the rest
+is covered by properties that hold at any size (budget met, counts consistent with the bit map)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rdkv_oracle as O
+from paper_2605_08317_amd import workloads as W
+from test_gpu_parity import B, _rel_err, DECODE_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _item_segments(arena, seg_off, item, sizes):
+    """The four segments of every tier of one item, cut out of an arena."""
+    out = []
+    for ti in range(4):
+        for si in range(4):
+            o = int(seg_off[item, ti, si])
+            out.append(arena[o:o + sizes[ti][si]])
+    return out
+
+
+def _seg_sizes_tokenwise(counts):
+    sizes = []
+    for ti, b in enumerate(O.PACK_ORDER):
+        npad = (int(counts[ti]) + 31) // 32 * 32
+        sizes.append([npad * O.row_bytes(b), npad * O.meta_bytes(b), npad * O.row_bytes(b), npad * O.meta_bytes(b)])
+    return sizes
+
+
+def _seg_sizes_mixed(counts, bits_ch):
+    nq = O.channel_slots(bits_ch)["nq"]
+    sizes = []
+    for ti, b in enumerate(O.PACK_ORDER):
+        nt = (int(counts[ti]) + 31) // 32
+        sizes.append([nt * O.k_tile_bytes_mixed(nq), nt * O.k_meta_bytes_mixed(nq),
+                      nt * (8192 if b == 16 else 512 * b), 0 if b == 16 else nt * 512])
+    return sizes
+
+
+def _check_sampled_items(b, wl, inp, cache, out, lse, w_tok, samples, mixed=False, w_ch=None):
+    hkv, d, g = wl.hkv, wl.d, wl.hq // wl.hkv
+    seq_lens = inp["seq_lens"]
+    counts = cache.export(b.RDKV_EXPORT_COUNTS, np.int32).reshape(-1, 4)
+    seg_off = cache.export(b.RDKV_EXPORT_SEG_OFF, np.int64).reshape(-1, 4, 4)
+    tier_idx = cache.export(b.RDKV_EXPORT_TIER_IDX, np.int32)
+    bits_all = cache.export(b.RDKV_EXPORT_BITS_TOK, np.uint8)
+    arena = cache.export(b.RDKV_EXPORT_ARENA, np.uint8)
+    bits_ch_all = cache.export(b.RDKV_EXPORT_BITS_CH, np.uint8).reshape(-1, d) if mixed else None
+    tok_off = np.concatenate([[0], np.cumsum([hkv * T for T in seq_lens])])
+    idx_off = np.concatenate([[0], np.cumsum(counts.sum(axis=1))])
+    # properties over every item: the bit map meets the budget and the tier counts are its histogram
+    for s, T in enumerate(seq_lens):
+        bt = bits_all[tok_off[s]:tok_off[s + 1]].reshape(hkv, T)
+        v_avg = inp["budgets"][s] if not mixed else O.mixed_budgets(np.float32(inp["budgets"][s]), np.float32(0.5), T, None, d)[0]
+        for h in range(hkv):
+            assert int(bt[h].astype(np.int64).sum()) <= int(np.floor(np.float64(np.float32(v_avg)) * T))
+            assert [int((bt[h] == t).sum()) for t in O.PACK_ORDER] == counts[s * hkv + h].tolist()
+    K_views = W.split_sequences(inp["K"], seq_lens, hkv, d)
+    V_views = W.split_sequences(inp["V"], seq_lens, hkv, d)
+    w_views = W.split_sequences(w_tok, seq_lens, hkv, None)
+    worst = 0.0
+    for (s, h) in samples:
+        item, T = s * hkv + h, seq_lens[s]
+        print(f"[sample] sequence {s} KV head {h} T={T}", flush=True)
+        Kh = K_views[s][h].float().cpu().numpy()[None]
+        Vh = V_views[s][h].float().cpu().numpy()[None]
+        wh = w_views[s][h].cpu().numpy()
+        if mixed:
+            bt, bc = O.allocate_mixed(wh, w_ch[item], np.float32(inp["budgets"][s]))
+            np.testing.assert_array_equal(bits_ch_all[item], bc)
+            ref = O.build_cache_mixed([Kh], [Vh], [bt[None]], [bc[None]])
+            sizes = _seg_sizes_mixed(counts[item], bc)
+        else:
+            bt = O.mckp_bisect(wh, np.float32(inp["budgets"][s]))
+            ref = O.build_cache_tokenwise([Kh], [Vh], [bt[None]])
+            sizes = _seg_sizes_tokenwise(counts[item])
+        np.testing.assert_array_equal(bits_all[tok_off[s] + h * T:tok_off[s] + (h + 1) * T], bt)
+        np.testing.assert_array_equal(counts[item], ref["counts"][0])
+        np.testing.assert_array_equal(tier_idx[idx_off[item]:idx_off[item + 1]], ref["tier_idx"])
+        for got, want in zip(_item_segments(arena, seg_off, item, sizes), _item_segments(ref["arena"], ref["seg_off"], 0, sizes)):
+            assert np.array_equal(got, want), "packed bytes of the sampled item differ"
+        q = inp["q"][s:s + 1, h * g:(h + 1) * g].float().cpu().numpy()
+        ro, rl = O.decode(ref, q)
+        go = out[s, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)[None]
+        gl = lse[s, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)[None]
+        err = _rel_err(go, ro)
+        worst = max(worst, err)
+        assert err <= DECODE_TOL
+        np.testing.assert_allclose(gl, rl, rtol=1e-4, atol=1e-4)
+    print(f"[full size] worst sampled decode error {worst:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("name,layer,samples", [
+    ("layer8b", 0, [(0, 0), (0, 5)]),
+    ("stack128k", 0, [(0, 3)]),
+    ("stack128k", 17, [(0, 6)]),
+    ("batch70b", 0, [(0, 1), (7, 4), (15, 7)]),
+])
+def test_tokenwise_configs_at_full_size(name, layer, samples):
+    b = B()
+    wl = W.CONFIGS[name]
+    print(f"[case] full-size {name} layer {layer}", flush=True)
+    inp = W.make_inputs(wl, device="cuda", layer=layer)
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs)
+    cache = b.rdkv_compress(cfg, inp["K"], inp["V"], inp["Q_obs"])
+    w_tok, _ = b.rdkv_weights(cfg, inp["K"], inp["Q_obs"])
+    out, lse = b.rdkv_decode_attn(cache, inp["q"])
+    torch.cuda.synchronize()
+    _check_sampled_items(b, wl, inp, cache, out, lse, w_tok, samples)
+    cache.free()
+
+
+def test_mixed_config_at_full_size():
+    b = B()
+    wl = W.CONFIGS["mixed"]
+    print("[case] full-size mixed", flush=True)
+    inp = W.make_inputs(wl, device="cuda")
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs,
+                   k_mode=b.RDKV_K_CHANNELWISE)
+    _, w_ch = b.rdkv_weights(cfg, inp["K"], inp["Q_obs"], want_channel=True)
+    bits_tok, bits_ch = b.rdkv_allocate(cfg, inp["w_tok"], w_ch)
+    cache = b.rdkv_pack(cfg, inp["K"], inp["V"], bits_tok, bits_ch)
+    out, lse = b.rdkv_decode_attn(cache, inp["q"])
+    torch.cuda.synchronize()
+    _check_sampled_items(b, wl, inp, cache, out, lse, inp["w_tok"], [(0, 2), (0, 7)], mixed=True,
+                         w_ch=w_ch.cpu().numpy().reshape(-1, wl.d))
+    st = cache.stats()
+    print(f"[mixed full] token rows(16,8,4,2)={st['rows']} evicted={st['evicted']} stored={st['stored_bytes']} "
+          f"dense={st['dense_bytes']}", flush=True)
+    cache.free()

@@ -297,60 +297,63 @@ __global__ __launch_bounds__(kWG) void decode_tiered_kernel(const Chunk* __restr
 }
 
 // Log-sum-exp merge of the partial results of one (item, query head).  512 threads: 4 slot groups x 128
-// channels; the slot loop of each group is unrolled so that its loads overlap; fixed summation order.
+// channels.  Every thread issues all the loads of its (up to kMergeBatch) slots before anything waits on them: the
+// running maxima, the sums and the accumulators of a batch arrive together, so a merge of a few dozen partials costs
+// two dependent memory round trips (slot range, then data) instead of one per pass.  Fixed summation order.
 constexpr int kMergeThreads = 512;
-
-__device__ __forceinline__ float merge_block_reduce(float v, bool is_max, float* sm) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float t = __shfl_xor(v, o);
-    v = is_max ? fmaxf(v, t) : v + t;
-  }
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float r = sm[0];
-#pragma unroll
-  for (int i = 1; i < kMergeThreads / 64; ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
-  return r;
-}
+constexpr int kMergeBatch = 16;   // slots per thread and round: 64 slots per (item, head) and round
 
 __device__ __forceinline__ void merge_slots(const float* __restrict__ part_acc, const float* __restrict__ part_ml,
                                             int64_t slot0, int n, int g, int h, float* __restrict__ out,
                                             float* __restrict__ lse) {
-  __shared__ float sm_red[kMergeThreads / 64];
+  __shared__ float sm_m[4], sm_l[4];
   __shared__ float sm_o[4][kHeadDim];
   const int tid = threadIdx.x, c = tid & (kHeadDim - 1), grp = tid >> 7;
-  float mx = kNegBig;
-  for (int i = tid; i < n; i += kMergeThreads) mx = fmaxf(mx, part_ml[((slot0 + i) * g + h) * 2]);
-  const float mstar = merge_block_reduce(mx, true, sm_red);
-  float lp = 0.f;
-  for (int i = tid; i < n; i += kMergeThreads) {
-    const float* ml = part_ml + ((slot0 + i) * g + h) * 2;
-    lp = __builtin_fmaf(ml[1], fast_exp2(ml[0] - mstar), lp);
-  }
-  const float l = merge_block_reduce(lp, false, sm_red);
-  float o = 0.f;
-  int i = grp;
-  for (; i + 12 < n; i += 16) {
-    float f[4], a[4];
+  float m_run = kNegBig, l_run = 0.f, o_run = 0.f;      // of this thread's slots: grp, grp + 4, ...
+  for (int base = grp; base < n; base += 4 * kMergeBatch) {
+    float2 ml[kMergeBatch];
+    float a[kMergeBatch];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t s = slot0 + i + 4 * u;
-      f[u] = part_ml[(s * g + h) * 2];
-      a[u] = part_acc[(s * g + h) * kHeadDim + c];
+    for (int u = 0; u < kMergeBatch; ++u) {
+      const int i = base + 4 * u;
+      ml[u] = make_float2(kNegBig, 0.f);
+      a[u] = 0.f;
+      if (i < n) {
+        const int64_t s = slot0 + i;
+        ml[u] = *reinterpret_cast<const float2*>(part_ml + (s * g + h) * 2);
+        a[u] = part_acc[(s * g + h) * kHeadDim + c];
+      }
     }
+    float mb = m_run;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) o = __builtin_fmaf(a[u], fast_exp2(f[u] - mstar), o);
+    for (int u = 0; u < kMergeBatch; ++u) mb = fmaxf(mb, ml[u].x);
+    const float f0 = fast_exp2(m_run - mb);
+    l_run *= f0;
+    o_run *= f0;
+#pragma unroll
+    for (int u = 0; u < kMergeBatch; ++u) {
+      const float f = fast_exp2(ml[u].x - mb);
+      l_run = __builtin_fmaf(ml[u].y, f, l_run);
+      o_run = __builtin_fmaf(a[u], f, o_run);
+    }
+    m_run = mb;
   }
-  for (; i < n; i += 4) {
-    const int64_t s = slot0 + i;
-    o = __builtin_fmaf(part_acc[(s * g + h) * kHeadDim + c], fast_exp2(part_ml[(s * g + h) * 2] - mstar), o);
+  // the four slot groups: every thread of a group holds the same (m, l)
+  if (c == 0) {
+    sm_m[grp] = m_run;
+    sm_l[grp] = l_run;
   }
-  sm_o[grp][c] = o;
+  sm_o[grp][c] = o_run;
   __syncthreads();
   if (grp == 0) {
-    const float t = (sm_o[0][c] + sm_o[1][c]) + (sm_o[2][c] + sm_o[3][c]);
+    const float mstar = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+    float l = 0.f, t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float f = fast_exp2(sm_m[k] - mstar);
+      l = __builtin_fmaf(sm_l[k], f, l);
+      t = __builtin_fmaf(sm_o[k][c], f, t);
+    }
     const bool empty = !(l > 0.f);
     out[c] = empty ? 0.f : t / l;
     if (lse != nullptr && c == 0) *lse = empty ? -INFINITY : (mstar + __log2f(l)) * 0.6931471805599453f;

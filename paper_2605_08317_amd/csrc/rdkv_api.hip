@@ -571,7 +571,7 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   c->stored_bytes = stored;
 
   // byte-balanced chunks: every workgroup streams about the same number of stored bytes
-  int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>(32 << 10, stored / 2048));
+  int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>(24 << 10, stored / 2048));
   if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
   for (int64_t i = 0; i < n; ++i) {

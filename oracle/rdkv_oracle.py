@@ -31,7 +31,8 @@ import numpy as np
 TIERS = (0, 2, 4, 8, 16)
 PACK_ORDER = (16, 8, 4, 2)          # order of tier segments inside an item
 GROUP = 32                          # quantization group size
-ROW_PAD = 32                        # tier segments are padded to whole 32-row tiles
+ROW_PAD = 32                        # mixed mode: tier segments are padded to whole 32-row tiles
+ROW_PAD_TOKENWISE = 64              # token-wise mode: whole 64-row tiles
 SEG_ALIGN = 256                     # byte alignment of every segment in the arena
 
 # Table 9 (App. I), LLaMA-3.1-8B row; eps(0) = 1 and eps(16) = 0 for every model.
@@ -414,7 +415,8 @@ TILE_META_BYTES = 512               # per tile: 128 fp16 scales then 128 fp16 of
 
 @functools.lru_cache(maxsize=None)
 def tile_code_positions(bits, which):
-    """Where the code of (row r of a 32-row tile, channel c) lives inside the tile's data block.
+    """Mixed mode (V side): where the code of (row r of a 32-row tile, channel c) lives inside the
+    tile's data block.  (The K variant of this layout is kept for the layout pins only.)
 
     Layout fixed by this build (the paper's own layout, App. B, is row-major per
     token; any documented bijection serves Eq. 7).  The 64 lanes of a wavefront
@@ -478,6 +480,104 @@ def tile_meta_positions(which):
     return sc, of
 
 
+TILE64_ROWS = 64                    # token-wise mode: tokens per tile of a quantized tier segment
+TILE64_META_BYTES = 1024            # per tile and side: 16 bytes per token
+
+
+@functools.lru_cache(maxsize=None)
+def tile64_code_positions(bits, which):
+    """Token-wise mode: where the code of (row r of a 64-row tile, channel c) lives inside
+    the tile's data block of 64 * 16 * bits bytes.
+
+    Layout fixed by this build (the paper's own layout, App. B, is row-major per token;
+    any documented bijection serves Eq. 7).  One wavefront lane owns a run of 4*bits
+    32-bit words; word W of lane L is stored at byte 1024*(W // 4) + 16*L + 4*(W % 4), so
+    a wavefront reads 1 KiB per 16-byte load.  The run holds four *groups* of `bits` words;
+    a group is unpacked in eight *steps* of four codes: with F = 16 / bits fields per 16-bit
+    half, step s reads field f = s % F of both halves of the word pair p = s // F of the
+    group, i.e. code k (0..3) of step s is at word 2p + k // 2, bit 16*(k % 2) + bits*f.
+      K: lane = token r; group = c // 32 (the quantization group); step, code: c % 32 = 4 s + k
+      V: lane = 32*(r // 32) + c % 32; group = c // 32; step, code: r % 32 = 4 s + k
+    (K: a lane holds one token's row; V: a lane holds one channel for 32 tokens.)
+    Returns (byte_offset [64,128] int64, bit_shift [64,128] int64)."""
+    assert bits in (2, 4, 8) and which in ("k", "v")
+    F = 16 // bits
+    byte_off = np.zeros((TILE64_ROWS, 128), dtype=np.int64)
+    shift = np.zeros((TILE64_ROWS, 128), dtype=np.int64)
+    for r in range(TILE64_ROWS):
+        for c in range(128):
+            if which == "k":
+                lane, grp, idx = r, c // 32, c % 32
+            else:
+                lane, grp, idx = 32 * (r // 32) + c % 32, c // 32, r % 32
+            st, k = idx // 4, idx % 4
+            W = grp * bits + 2 * (st // F) + k // 2
+            bit = 8 * (1024 * (W // 4) + 16 * lane + 4 * (W % 4)) + 16 * (k % 2) + bits * (st % F)
+            byte_off[r, c], shift[r, c] = bit // 8, bit % 8
+    return byte_off, shift
+
+
+@functools.lru_cache(maxsize=None)
+def tile64_meta_positions(which):
+    """fp16 element index (0..511) of the scale and of the offset of (row r, group)
+    inside the tile's 1024-byte metadata block.
+      K: row-major, 16 bytes per token: scales of the 4 groups, then their offsets
+      V: per block of 4 tokens 64 bytes: [group][token] scales (32 bytes), then offsets"""
+    sc = np.zeros((TILE64_ROWS, 4), dtype=np.int64)
+    of = np.zeros((TILE64_ROWS, 4), dtype=np.int64)
+    for r in range(TILE64_ROWS):
+        for grp in range(4):
+            if which == "k":
+                sc[r, grp], of[r, grp] = 8 * r + grp, 8 * r + 4 + grp
+            else:
+                sc[r, grp] = 32 * (r // 4) + 4 * grp + r % 4
+                of[r, grp] = 32 * (r // 4) + 16 + 4 * grp + r % 4
+    return sc, of
+
+
+def tile64_data_bytes(bits):
+    return TILE64_ROWS * 128 * bits // 8
+
+
+def pack_tiles64(codes, scale_bits, off_bits, bits, which):
+    """Physical 64-row tiles of n rows (zero-padded to whole tiles).  codes uint8 [n,128];
+    scale_bits, off_bits uint16 [n,4].  Returns (data uint8, meta uint8)."""
+    n = codes.shape[0]
+    R = TILE64_ROWS
+    nt = (n + R - 1) // R
+    cp = np.zeros((nt * R, 128), dtype=np.uint8)
+    cp[:n] = codes
+    sp = np.zeros((nt * R, 4), dtype=np.uint16)
+    op = np.zeros((nt * R, 4), dtype=np.uint16)
+    sp[:n], op[:n] = scale_bits, off_bits
+    byte_off, shift = tile64_code_positions(bits, which)
+    sc_idx, of_idx = tile64_meta_positions(which)
+    data = np.zeros((nt, tile64_data_bytes(bits)), dtype=np.uint8)
+    meta = np.zeros((nt, TILE64_META_BYTES // 2), dtype="<u2")
+    cp = cp.reshape(nt, R, 128)
+    for t in range(nt):
+        contrib = (cp[t].astype(np.uint32) << shift.astype(np.uint32)).astype(np.uint8)
+        np.bitwise_or.at(data[t], byte_off.reshape(-1), contrib.reshape(-1))
+        meta[t, sc_idx.reshape(-1)] = sp[t * R:(t + 1) * R].reshape(-1)
+        meta[t, of_idx.reshape(-1)] = op[t * R:(t + 1) * R].reshape(-1)
+    return data.reshape(-1), meta.view(np.uint8).reshape(-1)
+
+
+def unpack_tiles64(data, meta, n, bits, which):
+    """Inverse of pack_tiles64 for the first n rows."""
+    R = TILE64_ROWS
+    nt = (n + R - 1) // R
+    byte_off, shift = tile64_code_positions(bits, which)
+    sc_idx, of_idx = tile64_meta_positions(which)
+    data = np.asarray(data, dtype=np.uint8).reshape(nt, tile64_data_bytes(bits))
+    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape(nt, TILE64_META_BYTES // 2)
+    mask = (1 << bits) - 1
+    codes = ((data[:, byte_off] >> shift.astype(np.uint8)) & mask).astype(np.uint8)
+    sc = meta[:, sc_idx].astype(np.uint16)
+    of = meta[:, of_idx].astype(np.uint16)
+    return codes.reshape(nt * R, 128)[:n], sc.reshape(nt * R, 4)[:n], of.reshape(nt * R, 4)[:n]
+
+
 def tile_data_bytes(bits):
     return TILE_ROWS * 128 * bits // 8
 
@@ -525,10 +625,10 @@ def unpack_tiles(data, meta, n, bits, which):
 def physical_segments(rec, d=128):
     """Physical form of one item's canonical record.
 
-    Per tier b with n rows, padded with zero rows to whole 32-row tiles:
+    Per tier b with n rows, padded with zero rows to whole 64-row tiles:
       tier 16:      K data and V data are the bf16 rows, row-major; no metadata
-      tiers 8,4,2:  K data = tiles of 32*16*b bytes (tile_code_positions(b, 'k')),
-                    K meta = tiles of 512 bytes (tile_meta_positions('k')), same for V
+      tiers 8,4,2:  K data = tiles of 64*16*b bytes (tile64_code_positions(b, 'k')),
+                    K meta = tiles of 1024 bytes (tile64_meta_positions('k')), same for V
     Returns {b: (kd, km, vd, vm)} as flat uint8 arrays.
     """
     assert d == 128
@@ -536,7 +636,7 @@ def physical_segments(rec, d=128):
     for b in PACK_ORDER:
         ent = rec[b]
         n = len(ent["pos"])
-        npad = _round_up(n, ROW_PAD)
+        npad = _round_up(n, ROW_PAD_TOKENWISE)
         segs = []
         for name in ("k", "v"):
             if b == 16:
@@ -544,7 +644,7 @@ def physical_segments(rec, d=128):
                 data[:n] = ent[name + "_codes"].astype("<u2").view(np.uint8).reshape(n, 2 * d)
                 segs += [data.reshape(-1), np.zeros(0, dtype=np.uint8)]
             else:
-                data, meta = pack_tiles(ent[name + "_codes"], ent[name + "_scale"], ent[name + "_off"], b, name)
+                data, meta = pack_tiles64(ent[name + "_codes"], ent[name + "_scale"], ent[name + "_off"], b, name)
                 segs += [data, meta]
         out[b] = tuple(segs)
     return out
@@ -629,10 +729,10 @@ def unpack_item(cache, item):
                 raw = arena[d_off:d_off + n * 2 * d].reshape(n, 2 * d)
                 mats.append(bf16_from_bits(raw.view("<u2").astype(np.uint16)).astype(np.float64))
             else:
-                nt = (n + TILE_ROWS - 1) // TILE_ROWS
+                nt = (n + TILE64_ROWS - 1) // TILE64_ROWS
                 m_off = int(seg_off[item, ti, which + 1])
-                codes, sc, of = unpack_tiles(arena[d_off:d_off + nt * tile_data_bytes(b)],
-                                             arena[m_off:m_off + nt * TILE_META_BYTES], n, b, name)
+                codes, sc, of = unpack_tiles64(arena[d_off:d_off + nt * tile64_data_bytes(b)],
+                                               arena[m_off:m_off + nt * TILE64_META_BYTES], n, b, name)
                 s = sc.copy().view(np.float16)
                 m = of.copy().view(np.float16)
                 mats.append(dequantize_groups(codes.reshape(n, d // GROUP, GROUP), s, m).reshape(n, d))

@@ -470,7 +470,7 @@ def test_cache_layout_counts_offsets_and_bytes():
     spans = []
     for i in range(n_items):
         for ti, b in enumerate(O.PACK_ORDER):
-            npad = (int(cache["counts"][i, ti]) + 31) // 32 * 32
+            npad = (int(cache["counts"][i, ti]) + 63) // 64 * 64          # whole 64-row tiles
             sizes = [npad * O.row_bytes(b), npad * O.meta_bytes(b)] * 2
             for si in range(4):
                 if sizes[si]:
@@ -689,6 +689,77 @@ def test_tile_pack_roundtrip_and_padding(bits):
     one = np.zeros((1, 128), np.uint8)
     one[0, 5] = (1 << bits) - 1
     data, _ = O.pack_tiles(one, np.zeros((1, 4), np.uint16), np.zeros((1, 4), np.uint16), bits, "k")
+    assert int(np.unpackbits(data).sum()) == bits
+
+
+# ----------------------------------------------------------------------------
+# 64-row tiles of the token-wise mode
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("which", ["k", "v"])
+def test_tile64_positions_are_a_bijection_onto_the_tile(bits, which):
+    byte_off, shift = O.tile64_code_positions(bits, which)
+    tb = O.tile64_data_bytes(bits)
+    assert tb == 64 * 128 * bits // 8
+    pos = byte_off * 8 + shift
+    assert pos.min() == 0 and pos.max() == tb * 8 - bits
+    assert len(np.unique(pos)) == 64 * 128                      # no two codes share a field
+    assert np.all(shift % bits == 0)                            # App. B: fields at offsets 0,2,4,6 / 0,4 / 0
+    sc, of = O.tile64_meta_positions(which)
+    both = np.concatenate([sc.reshape(-1), of.reshape(-1)])
+    assert sorted(both.tolist()) == list(range(512))            # 16 bytes per token, each fp16 slot used once
+
+
+def test_tile64_positions_hand_checked():
+    # word W of lane L sits at 1024*(W//4) + 16*L + 4*(W%4); a lane owns 4*bits words, `bits` words per group.
+    # K, 2-bit (2 words per group, 8 fields per half): token r = lane r.  ch 0 = group 0, step 0, code 0 -> word 0 bit 0;
+    # ch 1 = code 1 -> high half of word 0 -> byte 2; ch 2 = code 2 -> word 1 -> byte 4; ch 4 = step 1 -> field 1 -> bit 2;
+    # ch 28 = step 7 -> field 7 -> bit 14 -> byte 1, shift 6; ch 32 = group 1 -> word 2 -> byte 8; ch 96 -> word 6 ->
+    # second 16-byte chunk -> byte 1024 + 8; token 1 -> lane 1 -> byte 16
+    bo, sh = O.tile64_code_positions(2, "k")
+    assert [(int(bo[0, c]), int(sh[0, c])) for c in (0, 1, 2, 4, 28, 32, 96)] == \
+        [(0, 0), (2, 0), (4, 0), (0, 2), (1, 6), (8, 0), (1032, 0)]
+    assert bo[1, 0] == 16 and bo[63, 0] == 16 * 63
+    # K, 4-bit (4 words per group, 4 fields per half): steps 0..3 use the word pair (0, 1), steps 4..7 the pair (2, 3)
+    bo, sh = O.tile64_code_positions(4, "k")
+    assert [(int(bo[0, c]), int(sh[0, c])) for c in (0, 4, 12, 16, 18, 32)] == \
+        [(0, 0), (0, 4), (1, 4), (8, 0), (12, 0), (1024, 0)]
+    # K, 8-bit (8 words per group, 2 fields per half): step s uses the pair s // 2, byte s % 2 of each half
+    bo, sh = O.tile64_code_positions(8, "k")
+    assert [int(bo[0, c]) for c in (0, 1, 2, 3, 4, 8, 32)] == [0, 2, 4, 6, 1, 8, 2048]
+    assert not sh.any()
+    # V, 2-bit: lane = 32*(r // 32) + c % 32 holds one channel for 32 tokens; the token index plays the role the
+    # channel index plays for K: token 1 = code 1 -> byte 2; token 4 = step 1 -> bit 2; token 32 -> lane 32 -> byte 512;
+    # channel 1 -> lane 1 -> byte 16; channel 32 = group 1 -> word 2 -> byte 8
+    bo, sh = O.tile64_code_positions(2, "v")
+    assert [(int(bo[r, c]), int(sh[r, c])) for r, c in ((0, 0), (1, 0), (4, 0), (32, 0), (0, 1), (0, 32), (33, 33))] == \
+        [(0, 0), (2, 0), (0, 2), (512, 0), (16, 0), (8, 0), (512 + 16 + 8 + 2, 0)]
+    # metadata: K row-major [4 scales][4 offsets] per token; V per 4-token block [group][token] scales, then offsets
+    sc, of = O.tile64_meta_positions("k")
+    assert sc[0].tolist() == [0, 1, 2, 3] and of[0].tolist() == [4, 5, 6, 7] and sc[5, 2] == 42 and of[63, 3] == 511
+    sc, of = O.tile64_meta_positions("v")
+    assert sc[0].tolist() == [0, 4, 8, 12] and sc[1, 0] == 1 and of[0, 0] == 16 and sc[4, 0] == 32 and of[63, 3] == 511
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_tile64_pack_roundtrip_and_padding(bits):
+    rng = np.random.default_rng(60 + bits)
+    n = 150                                                      # two full tiles and a ragged third
+    codes = rng.integers(0, 1 << bits, (n, 128)).astype(np.uint8)
+    sc = rng.integers(0, 65536, (n, 4)).astype(np.uint16)
+    of = rng.integers(0, 65536, (n, 4)).astype(np.uint16)
+    for which in ("k", "v"):
+        data, meta = O.pack_tiles64(codes, sc, of, bits, which)
+        assert data.size == 3 * O.tile64_data_bytes(bits) and meta.size == 3 * 1024
+        c2, s2, o2 = O.unpack_tiles64(data, meta, n, bits, which)
+        np.testing.assert_array_equal(c2, codes)
+        np.testing.assert_array_equal(s2, sc)
+        np.testing.assert_array_equal(o2, of)
+        c3, s3, o3 = O.unpack_tiles64(data, meta, 192, bits, which)
+        assert not c3[n:].any() and not s3[n:].any() and not o3[n:].any()
+    one = np.zeros((1, 128), np.uint8)
+    one[0, 77] = (1 << bits) - 1
+    data, _ = O.pack_tiles64(one, np.zeros((1, 4), np.uint16), np.zeros((1, 4), np.uint16), bits, "v")
     assert int(np.unpackbits(data).sum()) == bits
 
 

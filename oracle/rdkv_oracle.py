@@ -522,7 +522,8 @@ def tile64_meta_positions(which):
     """fp16 element index (0..511) of the scale and of the offset of (row r, group)
     inside the tile's 1024-byte metadata block.
       K: row-major, 16 bytes per token: scales of the 4 groups, then their offsets
-      V: per block of 4 tokens 64 bytes: [group][token] scales (32 bytes), then offsets"""
+      V: per block of 4 tokens 64 bytes = 4 groups x 16 bytes: the group's scales of the 4 tokens,
+         then its offsets of the 4 tokens"""
     sc = np.zeros((TILE64_ROWS, 4), dtype=np.int64)
     of = np.zeros((TILE64_ROWS, 4), dtype=np.int64)
     for r in range(TILE64_ROWS):
@@ -530,8 +531,8 @@ def tile64_meta_positions(which):
             if which == "k":
                 sc[r, grp], of[r, grp] = 8 * r + grp, 8 * r + 4 + grp
             else:
-                sc[r, grp] = 32 * (r // 4) + 4 * grp + r % 4
-                of[r, grp] = 32 * (r // 4) + 16 + 4 * grp + r % 4
+                sc[r, grp] = 32 * (r // 4) + 8 * grp + r % 4
+                of[r, grp] = 32 * (r // 4) + 8 * grp + 4 + r % 4
     return sc, of
 
 

@@ -1,5 +1,6 @@
 // Stage 4 of Alg. 1 on the GPU: stable per-tier partition of the token bit map and
-// group-wise quantize-and-pack into tier segments (16-bit rows row-major, quantized tiers in 32-row tiles).
+// group-wise quantize-and-pack into tier segments (16-bit rows row-major, quantized tiers in 64-row tiles in
+// token-wise mode and 32-row tiles in mixed mode).
 //
 // The quantizer is fp32 in a fixed operation order (this file is compiled with
 // floating-point contraction off) so that codes, scales and offsets are
@@ -289,6 +290,128 @@ __global__ __launch_bounds__(256) void quant_pack_tile_kernel(PackArgs a) {
 }
 
 
+// Token-wise tiers 8/4/2: one workgroup = one tile of 64 kept rows, K and V.
+//
+// Tile layout (what the decode kernel's 4x4x4 MFMA steps want).  A wavefront lane owns a run of 4*BITS 32-bit words,
+// word W of lane L stored at byte 1024*(W/4) + 16*L + 4*(W%4).  The run holds four groups of BITS words; a group is
+// read in eight steps of four codes: with F = 16/BITS fields per 16-bit half, step s reads field s % F of both
+// halves of the word pair s / F, i.e. code k of step s sits at word 2*(s/F) + k/2, bit 16*(k%2) + BITS*(s%F).
+//   K: lane = token r; group = c / 32; c % 32 = 4*step + k        (a lane holds one token's row)
+//   V: lane = 32*(r/32) + c % 32; group = c / 32; r % 32 = 4*step + k   (a lane holds one channel for 32 tokens)
+// Metadata tile = 1024 bytes: K row-major per token [4 scales][4 offsets]; V per block of 4 tokens 4 groups x 16
+// bytes: the group's scales of the 4 tokens, then its offsets.
+template <int BITS>
+__global__ __launch_bounds__(256) void quant_pack_tile64_kernel(PackArgs a) {
+  constexpr int kRows = 64;
+  constexpr int kRowStride = kHeadDim + 8;                 // bf16 elements; 272-byte rows
+  __shared__ __align__(16) uint16_t s_rows[2][kRows][kRowStride];
+  __shared__ __align__(16) uint8_t s_codes[2][kRows][kHeadDim];
+  const int item = blockIdx.y;
+  const int n = a.counts[item * 4 + a.ti];
+  const int r0 = blockIdx.x * kRows;
+  if (r0 >= n) return;
+  const int valid = min(kRows, n - r0);
+  const int tid = threadIdx.x;
+  const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
+
+  {  // gather the tile's rows: 4 threads per row, 64 bytes of K and of V each
+    const int row = tid >> 2, part = tid & 3;
+    uint4 kv[2][4];
+#pragma unroll
+    for (int w = 0; w < 2; ++w)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) kv[w][i] = make_uint4(0, 0, 0, 0);
+    if (row < valid) {
+      const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + r0 + row];
+      const int64_t src = (a.item_row_off[item] + pos) * kHeadDim + part * 32;
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const uint4* p = reinterpret_cast<const uint4*>((w == 0 ? a.K : a.V) + src);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kv[w][i] = p[i];
+      }
+    }
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      uint4* d = reinterpret_cast<uint4*>(&s_rows[w][row][part * 32]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) d[i] = kv[w][i];
+    }
+  }
+  __syncthreads();
+
+  // quantize: one task = one group of 32 channels of one row of K or V (fixed-order fp32); 512 tasks
+  for (int task = tid; task < 2 * kRows * 4; task += 256) {
+    const int w = task >> 8, row = (task >> 2) & 63, grp = task & 3;
+    float x[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) x[i] = __uint_as_float(static_cast<uint32_t>(s_rows[w][row][grp * 32 + i]) << 16);
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int i = 1; i < 32; ++i) {
+      mn = fminf(mn, x[i]);
+      mx = fmaxf(mx, x[i]);
+    }
+    mn = mn + 0.0f;   // canonical +0
+    constexpr float Q = static_cast<float>((1 << BITS) - 1);
+    const _Float16 sh = static_cast<_Float16>((mx - mn) / Q);   // round to nearest even
+    const _Float16 mh = static_cast<_Float16>(mn);
+    const float s = static_cast<float>(sh), m = static_cast<float>(mh);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      float t = rintf((x[i] - m) / s);
+      t = fminf(fmaxf(t, 0.0f), Q);
+      s_codes[w][row][grp * 32 + i] = (s == 0.0f) ? uint8_t(0) : static_cast<uint8_t>(t);
+    }
+    if (row < valid) {
+      int si, oi;
+      if (w == 0) {
+        si = 8 * row + grp;
+        oi = si + 4;
+      } else {
+        si = 32 * (row >> 2) + 8 * grp + (row & 3);
+        oi = si + 4;
+      }
+      uint16_t* meta = reinterpret_cast<uint16_t*>(a.arena + so[w * 2 + 1] + static_cast<int64_t>(blockIdx.x) * 1024);
+      meta[si] = __builtin_bit_cast(unsigned short, sh);
+      meta[oi] = __builtin_bit_cast(unsigned short, mh);
+    }
+  }
+  __syncthreads();
+
+  // emit the tile's data words in their physical order (coalesced 32-bit stores)
+  constexpr int kWords = kRows * kHeadDim * BITS / 32;      // 2048 / 1024 / 512
+  constexpr int F = 16 / BITS;
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[w * 2] +
+                                                static_cast<int64_t>(blockIdx.x) * (kRows * kHeadDim * BITS / 8));
+    for (int word = tid; word < kWords; word += 256) {
+      const int chunk = word >> 8, lane = (word >> 2) & 63, dd = word & 3;
+      const int W = 4 * chunk + dd;
+      const int grp = W / BITS, wl = W % BITS;
+      const int pair = wl >> 1, kw = wl & 1;
+      uint32_t out = 0;
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int f = 0; f < F; ++f) {
+          const int idx = 4 * (pair * F + f) + 2 * kw + half;      // position inside the group: 4*step + k
+          int r, c;
+          if (w == 0) {
+            r = lane;
+            c = 32 * grp + idx;
+          } else {
+            r = 32 * (lane >> 5) + idx;
+            c = 32 * grp + (lane & 31);
+          }
+          out |= static_cast<uint32_t>(s_codes[w][r][c]) << (16 * half + BITS * f);
+        }
+      dst[word] = out;
+    }
+  }
+}
+
 // ---- mixed mode -------------------------------------------------------------------------------------------------
 // 16-bit V rows as 32-token tiles with the lane / operand / slot assignment of the quantized V tiers:
 // the bf16 of (lane, operand o, slot s) sits at byte 1024 o + 16 lane + 2 s of the 8 KiB tile.
@@ -464,6 +587,7 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
     if (max_count[ti] == 0) continue;
     PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti, mixed ? 1 : 0, items_k, bits_ch};
     dim3 grid_rows((max_count[ti] + 63) / 64, n_items), grid_tiles((max_count[ti] + kRowPad - 1) / kRowPad, n_items);
+    dim3 grid_tiles64((max_count[ti] + 63) / 64, n_items);
     dim3 block(256);
     if (mixed) hipLaunchKernelGGL(pack_k_mixed_kernel, grid_tiles, block, 0, st, a);
     switch (ti) {
@@ -471,9 +595,18 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
         if (mixed) hipLaunchKernelGGL(pack_v16_tile_kernel, grid_tiles, block, 0, st, a);
         else hipLaunchKernelGGL(copy_rows_kernel, grid_rows, block, 0, st, a);
         break;
-      case 1: hipLaunchKernelGGL(quant_pack_tile_kernel<8>, grid_tiles, block, 0, st, a); break;
-      case 2: hipLaunchKernelGGL(quant_pack_tile_kernel<4>, grid_tiles, block, 0, st, a); break;
-      default: hipLaunchKernelGGL(quant_pack_tile_kernel<2>, grid_tiles, block, 0, st, a); break;
+      case 1:
+        if (mixed) hipLaunchKernelGGL(quant_pack_tile_kernel<8>, grid_tiles, block, 0, st, a);
+        else hipLaunchKernelGGL(quant_pack_tile64_kernel<8>, grid_tiles64, block, 0, st, a);
+        break;
+      case 2:
+        if (mixed) hipLaunchKernelGGL(quant_pack_tile_kernel<4>, grid_tiles, block, 0, st, a);
+        else hipLaunchKernelGGL(quant_pack_tile64_kernel<4>, grid_tiles64, block, 0, st, a);
+        break;
+      default:
+        if (mixed) hipLaunchKernelGGL(quant_pack_tile_kernel<2>, grid_tiles, block, 0, st, a);
+        else hipLaunchKernelGGL(quant_pack_tile64_kernel<2>, grid_tiles64, block, 0, st, a);
+        break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -537,7 +537,7 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
       idx_base[i * 4 + ti] = kept;
       kept += cnt;
       max_count[ti] = std::max<int32_t>(max_count[ti], static_cast<int32_t>(cnt));
-      const int64_t npad = round_up(cnt, kRowPad);
+      const int64_t npad = round_up(cnt, mixed ? kRowPad : kTile64);
       int64_t sizes[4] = {npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits),
                           npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits)};
       if (mixed) {   // the K segments hold the channel-wise tiles of this tier's tokens

@@ -13,7 +13,8 @@ namespace rdkv {
 constexpr int kHeadDim = 128;
 constexpr int kGroup = 32;             // quantization group (channels)
 constexpr int kGroupsPerRow = kHeadDim / kGroup;
-constexpr int kRowPad = 32;            // tier segments are padded to whole 32-row tiles
+constexpr int kRowPad = 32;            // mixed mode: tier segments are padded to whole 32-row tiles
+constexpr int kTile64 = 64;            // token-wise mode: whole 64-row tiles
 constexpr int kSegAlign = 256;         // byte alignment of arena segments
 constexpr int kNumPackTiers = 4;       // stored tiers, order 16, 8, 4, 2
 constexpr int kDenseMaxSeqs = 64;      // sequences per dense-decode launch (kernel-argument table)

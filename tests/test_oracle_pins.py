@@ -734,11 +734,11 @@ def test_tile64_positions_hand_checked():
     bo, sh = O.tile64_code_positions(2, "v")
     assert [(int(bo[r, c]), int(sh[r, c])) for r, c in ((0, 0), (1, 0), (4, 0), (32, 0), (0, 1), (0, 32), (33, 33))] == \
         [(0, 0), (2, 0), (0, 2), (512, 0), (16, 0), (8, 0), (512 + 16 + 8 + 2, 0)]
-    # metadata: K row-major [4 scales][4 offsets] per token; V per 4-token block [group][token] scales, then offsets
+    # metadata: K row-major [4 scales][4 offsets] per token; V per 4-token block, per group: 4 scales then 4 offsets
     sc, of = O.tile64_meta_positions("k")
     assert sc[0].tolist() == [0, 1, 2, 3] and of[0].tolist() == [4, 5, 6, 7] and sc[5, 2] == 42 and of[63, 3] == 511
     sc, of = O.tile64_meta_positions("v")
-    assert sc[0].tolist() == [0, 4, 8, 12] and sc[1, 0] == 1 and of[0, 0] == 16 and sc[4, 0] == 32 and of[63, 3] == 511
+    assert sc[0].tolist() == [0, 8, 16, 24] and sc[1, 0] == 1 and of[0, 0] == 4 and sc[4, 0] == 32 and of[63, 3] == 511
 
 
 @pytest.mark.parametrize("bits", [2, 4, 8])

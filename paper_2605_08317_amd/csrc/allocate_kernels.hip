@@ -40,6 +40,29 @@ __device__ __forceinline__ long long block_sum(long long v, long long* sm) {
   return t;
 }
 
+// Sum of a small int over the workgroup with one barrier: DPP row rotations inside a row of 16 lanes, four lane
+// reads for the rows, one LDS slot per wavefront.  `sm` holds two sets of slots used alternately (parity), so that a
+// call never overwrites slots another wavefront may still be reading from the previous call.
+template <int CTRL>
+__device__ __forceinline__ int dpp_add(int v) {
+  return v + __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ int block_sum_small(int v, int* sm, int parity) {
+  v = dpp_add<0x128>(v);   // row_ror:8
+  v = dpp_add<0x124>(v);   // row_ror:4
+  v = dpp_add<0x122>(v);   // row_ror:2
+  v = dpp_add<0x121>(v);   // row_ror:1
+  const int ws = __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+                 __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+  int* slots = sm + parity * (kThreads / 64);
+  if ((threadIdx.x & 63) == 0) slots[threadIdx.x >> 6] = ws;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int i = 0; i < kThreads / 64; ++i) t += slots[i];
+  return t;
+}
+
 __device__ __forceinline__ float block_max(float v, float* sm) {
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
   const int wave = threadIdx.x >> 6;
@@ -51,9 +74,53 @@ __device__ __forceinline__ float block_max(float v, float* sm) {
   return t;
 }
 
+// Bit sum of one unit at thresholds thr: tiers[#thresholds strictly below w].
+__device__ __forceinline__ int classify_tier(double wu, const double (&thr)[kMaxHull - 1], const int32_t (&tiers)[kMaxHull]) {
+  int idx = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxHull - 1; ++k) idx += (wu > thr[k]) ? 1 : 0;
+  return tiers[idx];
+}
+
+// A unit is decided on the multiplier bracket [lo, hi] when no threshold lam * r_k, lam in [lo, hi], can change its
+// tier: for every k either w > hi * r_k (above for all lam) or not w > lo * r_k (below for all lam).  Rounded fp64
+// products are monotone in lam, so the test is exact.
+__device__ __forceinline__ bool undecided(double wu, const double (&thr_lo)[kMaxHull - 1],
+                                          const double (&thr_hi)[kMaxHull - 1]) {
+  bool u = false;
+#pragma unroll
+  for (int k = 0; k < kMaxHull - 1; ++k) u |= (wu > thr_lo[k]) && !(wu > thr_hi[k]);
+  return u;
+}
+
+constexpr int kMlp = 16;          // independent loads per thread in a streaming pass
+constexpr int kListCap = 6144;    // undecided units kept in LDS (24 KiB)
+constexpr int kBuckets = 8192;    // histogram over the top 13 bits of the positive fp32 pattern (32 KiB)
+constexpr int kBucketShift = 18;
+
+__device__ __forceinline__ int bucket_of(float w) {
+  const uint32_t u = __float_as_uint(w);
+  return (w > 0.0f) ? static_cast<int>(min(u, 0x7F7FFFFFu) >> kBucketShift) : 0;   // w <= 0 is never above a threshold
+}
+
+// Units with w > thr: at least those in buckets above thr's bucket, at most those plus thr's own bucket.
+// suffix[b] = number of units in buckets >= b (suffix[kBuckets] = 0).
+__device__ __forceinline__ void count_bounds(double thr, const int* __restrict__ suffix, int* lo_cnt, int* hi_cnt) {
+  // largest finite float <= thr (thr > 0): every float in a higher bucket exceeds thr, none in a lower bucket does
+  float tf = static_cast<float>(fmin(thr, 3.4028234663852886e38));
+  if (static_cast<double>(tf) > thr) tf = __uint_as_float(__float_as_uint(tf) - 1u);
+  const int bt = static_cast<int>(__float_as_uint(tf) >> kBucketShift);
+  *lo_cnt = suffix[bt + 1];
+  *hi_cnt = suffix[bt];
+}
+
 __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   __shared__ long long sm_sum[kThreads / 64];
   __shared__ float sm_max[kThreads / 64];
+  __shared__ int s_hist[kBuckets + 1];
+  __shared__ float s_list[kListCap];
+  __shared__ int s_count;
+  __shared__ int sm_small[2 * (kThreads / 64)];
   const int item = blockIdx.x;
   const int U = a.item_U[item];
   if (U == 0) return;
@@ -70,49 +137,149 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
     return;
   }
   const long long need = static_cast<long long>(ceil(a.need_frac * static_cast<double>(B_int)));
+  int32_t tiers[kMaxHull];
+  double r[kMaxHull - 1];
+#pragma unroll
+  for (int k = 0; k < kMaxHull; ++k) tiers[k] = a.tiers[k];
+#pragma unroll
+  for (int k = 0; k < kMaxHull - 1; ++k) r[k] = a.r[k];
 
+  // ---- one pass: maximum and histogram ------------------------------------------------------------------
+  for (int i = threadIdx.x; i <= kBuckets; i += kThreads) s_hist[i] = 0;
+  __syncthreads();
   float mx = 0.f;
-  for (int u = threadIdx.x; u < U; u += kThreads) mx = fmaxf(mx, w[u]);
+  for (int u0 = threadIdx.x; u0 < U; u0 += kMlp * kThreads) {
+    float wv[kMlp];
+#pragma unroll
+    for (int j = 0; j < kMlp; ++j) wv[j] = (u0 + j * kThreads < U) ? w[u0 + j * kThreads] : 0.0f;
+#pragma unroll
+    for (int j = 0; j < kMlp; ++j)
+      if (u0 + j * kThreads < U) {
+        mx = fmaxf(mx, wv[j]);
+        atomicAdd(&s_hist[bucket_of(wv[j])], 1);
+      }
+  }
   mx = block_max(mx, sm_max);
+  // suffix sums in place: s_hist[b] = units in buckets >= b (each thread owns 8 consecutive buckets)
+  {
+    const int b0 = threadIdx.x * (kBuckets / kThreads);
+    int local = 0;
+#pragma unroll
+    for (int i = 0; i < kBuckets / kThreads; ++i) local += s_hist[b0 + i];
+    __shared__ int s_part[kThreads];
+    s_part[threadIdx.x] = local;
+    __syncthreads();
+    for (int off = 1; off < kThreads; off <<= 1) {   // inclusive suffix scan (Hillis-Steele)
+      const int v = (threadIdx.x + off < kThreads) ? s_part[threadIdx.x + off] : 0;
+      __syncthreads();
+      s_part[threadIdx.x] += v;
+      __syncthreads();
+    }
+    int run = s_part[threadIdx.x] - local;           // units in buckets above this thread's range
+#pragma unroll
+    for (int i = kBuckets / kThreads - 1; i >= 0; --i) {
+      run += s_hist[b0 + i];
+      s_hist[b0 + i] = run;
+    }
+    __syncthreads();
+  }
 
   double lo = 0.0, hi = static_cast<double>(mx);
   double best = 0.0;
   bool have = false;
-  // per-step increments of the bit sum when a threshold is passed: tiers[k] - tiers[k-1]
+  // Every step decides exactly as Alg. 2 does at lam = (lo + hi) / 2.  While the histogram bounds on the bit sum
+  // settle the comparisons, no unit is read.  At the first step they cannot, the units whose tier can still change
+  // inside the bracket are moved to LDS (the others add a constant) and the remaining steps evaluate those exactly;
+  // the same pass gives this step's exact sum, so if the units do not fit the search goes on with the bounds.
+  int mode = 0;   // 0: histogram bounds, 1: list in LDS
+  int n_list = 0;
+  long long s_fixed = 0;
   for (int it = 0; it < a.max_iters; ++it) {
     const double lam = (lo + hi) * 0.5;
     double thr[kMaxHull - 1];
 #pragma unroll
-    for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? lam * a.r[k] : INFINITY;
+    for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? lam * r[k] : INFINITY;
     long long s = 0;
-    for (int u = threadIdx.x; u < U; u += kThreads) {
-      const double wu = static_cast<double>(w[u]);
-      int idx = 0;
+    int verdict = -1;   // 0: over budget, 1: feasible (continue), 2: feasible and inside the band (stop)
+    if (mode == 0) {
+      long long s_min = static_cast<long long>(tiers[0]) * U, s_max = s_min;
 #pragma unroll
-      for (int k = 0; k < kMaxHull - 1; ++k) idx += (wu > thr[k]) ? 1 : 0;
-      s += a.tiers[idx];
+      for (int k = 0; k < kMaxHull - 1; ++k) {
+        if (k < nh - 1) {
+          int c_lo, c_hi;
+          count_bounds(thr[k], s_hist, &c_lo, &c_hi);
+          s_min += static_cast<long long>(tiers[k + 1] - tiers[k]) * c_lo;
+          s_max += static_cast<long long>(tiers[k + 1] - tiers[k]) * c_hi;
+        }
+      }
+      if (s_min > B_int) verdict = 0;
+      else if (s_max <= B_int && s_min >= need) verdict = 2;
+      else if (s_max < need) verdict = 1;
+      if (verdict < 0) {
+        // ambiguous: collect the units still undecided on [lo, hi]
+        double t_lo[kMaxHull - 1], t_hi[kMaxHull - 1];
+#pragma unroll
+        for (int k = 0; k < kMaxHull - 1; ++k) {
+          t_lo[k] = (k < nh - 1) ? lo * r[k] : INFINITY;
+          t_hi[k] = (k < nh - 1) ? hi * r[k] : INFINITY;
+        }
+        if (threadIdx.x == 0) s_count = 0;
+        __syncthreads();
+        long long sf = 0;
+        for (int u0 = threadIdx.x; u0 < U; u0 += kMlp * kThreads) {
+          float wv[kMlp];
+#pragma unroll
+          for (int j = 0; j < kMlp; ++j) wv[j] = (u0 + j * kThreads < U) ? w[u0 + j * kThreads] : 0.0f;
+#pragma unroll
+          for (int j = 0; j < kMlp; ++j)
+            if (u0 + j * kThreads < U) {
+              const double wu = static_cast<double>(wv[j]);
+              s += classify_tier(wu, thr, tiers);                 // this step's exact bit sum
+              if (undecided(wu, t_lo, t_hi)) {
+                const int pos = atomicAdd(&s_count, 1);
+                if (pos < kListCap) s_list[pos] = wv[j];
+              } else {
+                sf += classify_tier(wu, t_hi, tiers);
+              }
+            }
+        }
+        s = block_sum(s, sm_sum);
+        s_fixed = block_sum(sf, sm_sum);
+        __syncthreads();
+        n_list = s_count;
+        __syncthreads();                      // everyone has read the count before a later step resets it
+        if (n_list <= kListCap) mode = 1;     // else: too many for LDS; try again at the next unsettled step
+        verdict = s > B_int ? 0 : (s >= need ? 2 : 1);
+      }
+    } else if (mode == 1) {
+      int sl = 0;   // at most kListCap * 16: fits an int
+      for (int i = threadIdx.x; i < n_list; i += kThreads) sl += classify_tier(static_cast<double>(s_list[i]), thr, tiers);
+      s = block_sum_small(sl, sm_small, it & 1) + s_fixed;
     }
-    s = block_sum(s, sm_sum);
-    if (s <= B_int) {
+    if (verdict < 0) verdict = s > B_int ? 0 : (s >= need ? 2 : 1);
+    if (verdict == 0) {
+      lo = lam;
+    } else {
       best = lam;
       have = true;
       hi = lam;
-      if (s >= need) break;
-    } else {
-      lo = lam;
+      if (verdict == 2) break;
     }
   }
   double thr[kMaxHull - 1];
 #pragma unroll
-  for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? best * a.r[k] : INFINITY;
-  for (int u = threadIdx.x; u < U; u += kThreads) {
-    int idx = 0;
-    if (have) {
-      const double wu = static_cast<double>(w[u]);
+  for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? best * r[k] : INFINITY;
+  for (int u0 = threadIdx.x; u0 < U; u0 += kMlp * kThreads) {
+    float wv[kMlp];
 #pragma unroll
-      for (int k = 0; k < kMaxHull - 1; ++k) idx += (wu > thr[k]) ? 1 : 0;
-    }
-    bits[u] = static_cast<uint8_t>(a.tiers[idx]);
+    for (int j = 0; j < kMlp; ++j) wv[j] = (u0 + j * kThreads < U) ? w[u0 + j * kThreads] : 0.0f;
+#pragma unroll
+    for (int j = 0; j < kMlp; ++j)
+      if (u0 + j * kThreads < U) {
+        int t = tiers[0];
+        if (have) t = classify_tier(static_cast<double>(wv[j]), thr, tiers);
+        bits[u0 + j * kThreads] = static_cast<uint8_t>(t);
+      }
   }
 }
 

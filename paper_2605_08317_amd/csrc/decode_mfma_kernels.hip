@@ -155,20 +155,27 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   // so a wavefront always has its next tile in flight.  An 8-bit tile is 18 KiB: there the K and V codes take turns
   // in one register set (the other wavefronts of the SIMD cover the wait) and the kernel stays within 128 registers.
   constexpr bool kShare = TIER == 8;
-  uint4 kraw[TIER], vraw_[kShare ? 1 : TIER], kmeta = make_uint4(0, 0, 0, 0), vmeta = make_uint4(0, 0, 0, 0);
-  auto& vraw = [&]() -> auto& { if constexpr (kShare) return kraw; else return vraw_; }();
-  auto load_k = [&](int t) __attribute__((always_inline)) {
-    load_tile_side<TIER>(kraw, kd, t, lane);
-    kmeta = *reinterpret_cast<const uint4*>(km + static_cast<int64_t>(t) * 1024 + lane * 16);
+  constexpr int kDepth = TIER == 2 ? 2 : 1;   // a 2-bit tile is only 6 KiB: two per wavefront in flight
+  struct Regs {
+    uint4 k[TIER], v[kShare ? 1 : TIER], kmeta, vmeta;
   };
-  auto load_v = [&](int t) __attribute__((always_inline)) {
-    load_tile_side<TIER>(vraw, vd, t, lane);
+  Regs regs[kDepth];
+  auto load_k = [&](Regs& r, int t) __attribute__((always_inline)) {
+    load_tile_side<TIER>(r.k, kd, t, lane);
+    r.kmeta = *reinterpret_cast<const uint4*>(km + static_cast<int64_t>(t) * 1024 + lane * 16);
+  };
+  auto load_v = [&](Regs& r, int t) __attribute__((always_inline)) {
+    if constexpr (kShare) load_tile_side<TIER>(r.k, vd, t, lane); else load_tile_side<TIER>(r.v, vd, t, lane);
     // lane (block, j) fetches group j's scales and offsets of tokens 4 blk + 0..3; the quad shares them below
-    vmeta = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(t) * 1024 + lane * 16);
+    r.vmeta = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(t) * 1024 + lane * 16);
   };
-  if (wave < ntiles) {
-    load_k(wave);
-    if constexpr (!kShare) load_v(wave);
+#pragma unroll
+  for (int dd = 0; dd < kDepth; ++dd) {
+    regs[dd].kmeta = regs[dd].vmeta = make_uint4(0, 0, 0, 0);
+    if (wave + dd * kWaves < ntiles) {
+      load_k(regs[dd], wave + dd * kWaves);
+      if constexpr (!kShare) load_v(regs[dd], wave + dd * kWaves);
+    }
   }
 
   // ---- query operands (once per workgroup) ------------------------------------------------------------------
@@ -227,9 +234,13 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-  for (int tile = wave; tile < ntiles; tile += kWaves) {
-    const int next = tile + kWaves;
+  auto do_tile = [&](Regs& r, const int tile) __attribute__((always_inline)) {
+    const int next = tile + kDepth * kWaves;
     const bool more = next < ntiles;
+    auto& kraw = r.k;
+    auto& vraw = [&]() -> auto& { if constexpr (kShare) return r.k; else return r.v; }();
+    const uint4& kmeta = r.kmeta;
+    const uint4& vmeta = r.vmeta;
 
     // ---- logits x[hs][i] of token 4 blk + i and head 4 hs + j, in units of kKUnit --------------------------
     float x[HS][4];
@@ -282,8 +293,8 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
         }
       }
     }
-    if constexpr (kShare) load_v(tile);   // the K codes are used up: their registers take this tile's V codes
-    else if (more) load_k(next);          // K registers are free again
+    if constexpr (kShare) load_v(r, tile);   // the K codes are used up: their registers take this tile's V codes
+    else if (more) load_k(r, next);          // K registers are free again
 
     if ((tile + 1) * kTile > rows) {   // padded rows of the last tile
 #pragma unroll
@@ -359,8 +370,13 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
 #undef RDKV_PV_GROUP
     }
     if (more) {               // V registers are free again
-      if constexpr (kShare) load_k(next); else load_v(next);
+      if constexpr (kShare) load_k(r, next); else load_v(r, next);
     }
+  };
+  for (int tile = wave; tile < ntiles; tile += kDepth * kWaves) {
+#pragma unroll
+    for (int dd = 0; dd < kDepth; ++dd)
+      if (tile + dd * kWaves < ntiles) do_tile(regs[dd], tile + dd * kWaves);
   }
 
   // ---- end of the chunk: undo the subnormal unit, add the offsets, merge the 4 wavefronts --------------------

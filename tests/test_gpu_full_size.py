@@ -27,7 +27,7 @@ def _item_segments(arena, seg_off, item, sizes):
 def _seg_sizes_tokenwise(counts):
     sizes = []
     for ti, b in enumerate(O.PACK_ORDER):
-        npad = (int(counts[ti]) + 31) // 32 * 32
+        npad = (int(counts[ti]) + O.ROW_PAD_TOKENWISE - 1) // O.ROW_PAD_TOKENWISE * O.ROW_PAD_TOKENWISE
         sizes.append([npad * O.row_bytes(b), npad * O.meta_bytes(b), npad * O.row_bytes(b), npad * O.meta_bytes(b)])
     return sizes
 

@@ -31,8 +31,8 @@ import numpy as np
 TIERS = (0, 2, 4, 8, 16)
 PACK_ORDER = (16, 8, 4, 2)          # order of tier segments inside an item
 GROUP = 32                          # quantization group size
-ROW_PAD = 32                        # mixed mode: tier segments are padded to whole 32-row tiles
-ROW_PAD_TOKENWISE = 64              # token-wise mode: whole 64-row tiles
+ROW_PAD_TOKENWISE = 64              # tier segments are padded to whole 64-row tiles (both modes)
+K_TOKEN_GROUP = 32                  # mixed mode: a K channel's group = 32 consecutive retained tokens of a segment
 SEG_ALIGN = 256                     # byte alignment of every segment in the arena
 
 # Table 9 (App. I), LLaMA-3.1-8B row; eps(0) = 1 and eps(16) = 0 for every model.
@@ -409,78 +409,7 @@ def canonical_item(Kh, Vh, bits_tok):
     return rec
 
 
-TILE_ROWS = 32                      # tokens per tile of a quantized tier segment
-TILE_META_BYTES = 512               # per tile: 128 fp16 scales then 128 fp16 offsets
-
-
-@functools.lru_cache(maxsize=None)
-def tile_code_positions(bits, which):
-    """Mixed mode (V side): where the code of (row r of a 32-row tile, channel c) lives inside the
-    tile's data block.  (The K variant of this layout is kept for the layout pins only.)
-
-    Layout fixed by this build (the paper's own layout, App. B, is row-major per
-    token; any documented bijection serves Eq. 7).  The 64 lanes of a wavefront
-    are indexed lane = 16*quad + l16; every lane owns eight 8-slot "operands":
-      K: operand o = 4*(r // 16) + c // 32, lane = 16*((c // 8) % 4) + r % 16, slot s = c % 8
-      V: operand o = c // 16,            lane = 16*((r % 16) // 4) + c % 16,
-         slot s = 4*(r // 16) + r % 4
-    The lane's data is a run of 32-bit words; word W of the run is stored at byte
-    1024*(W // 4) + 16*lane + 4*(W % 4) of the tile (so a wavefront reads 1 KiB per
-    16-byte load).  Inside a word, slot s picks the 16-bit half (s % 2) and the word
-    (s // 2); the operand picks the field, so that one AND with a constant mask
-    isolates the same field of both halves and every slot of an operand carries the
-    same power-of-two factor:
-      8-bit: word W = 4*(o // 2) + s // 2, bit 16*(s % 2) + 8*(o % 2)
-      4-bit: word W = 4*(o // 4) + s // 2, bit 16*(s % 2) + 4*(o % 4)
-      2-bit: word W = s // 2,              bit 16*(s % 2) + 2*o
-    (bits counted from the least significant bit of the little-endian word; inside a
-    byte the fields sit at offsets 0,2,4,6 / 0,4 / 0 as in App. B).
-    Returns (byte_offset [32,128] int64, bit_shift [32,128] int64) of each code's
-    byte and its shift inside that byte.
-    """
-    assert bits in (2, 4, 8) and which in ("k", "v")
-    byte_off = np.zeros((TILE_ROWS, 128), dtype=np.int64)
-    shift = np.zeros((TILE_ROWS, 128), dtype=np.int64)
-    for r in range(TILE_ROWS):
-        for c in range(128):
-            if which == "k":
-                o, lane, sl = 4 * (r // 16) + c // 32, 16 * ((c // 8) % 4) + r % 16, c % 8
-            else:
-                o, lane, sl = c // 16, 16 * ((r % 16) // 4) + c % 16, 4 * (r // 16) + r % 4
-            if bits == 8:
-                W, wbit = 4 * (o // 2) + sl // 2, 16 * (sl % 2) + 8 * (o % 2)
-            elif bits == 4:
-                W, wbit = 4 * (o // 4) + sl // 2, 16 * (sl % 2) + 4 * (o % 4)
-            else:
-                W, wbit = sl // 2, 16 * (sl % 2) + 2 * o
-            bit = 8 * (1024 * (W // 4) + 16 * lane + 4 * (W % 4)) + wbit
-            byte_off[r, c], shift[r, c] = bit // 8, bit % 8
-    return byte_off, shift
-
-
-@functools.lru_cache(maxsize=None)
-def tile_meta_positions(which):
-    """fp16 element index (0..255) of the scale and of the offset of (row r, group)
-    inside the tile's 512-byte metadata block (scales in elements 0..127, offsets in
-    128..255).  With mb = r // 16, quad = (r % 16) // 4, i = r % 4, j = 4*mb + i:
-      K scales  ((quad*2 + mb)*4 + grp)*4 + i        K offsets 128 + r*4 + grp
-      V scales  (quad*4 + grp)*8 + j                 V offsets 128 + (quad*4 + grp)*8 + j
-    """
-    sc = np.zeros((TILE_ROWS, 4), dtype=np.int64)
-    of = np.zeros((TILE_ROWS, 4), dtype=np.int64)
-    for r in range(TILE_ROWS):
-        mb, quad, i = r // 16, (r % 16) // 4, r % 4
-        for grp in range(4):
-            if which == "k":
-                sc[r, grp] = ((quad * 2 + mb) * 4 + grp) * 4 + i
-                of[r, grp] = 128 + r * 4 + grp
-            else:
-                sc[r, grp] = (quad * 4 + grp) * 8 + 4 * mb + i
-                of[r, grp] = 128 + (quad * 4 + grp) * 8 + 4 * mb + i
-    return sc, of
-
-
-TILE64_ROWS = 64                    # token-wise mode: tokens per tile of a quantized tier segment
+TILE64_ROWS = 64                    # tokens per tile of a quantized tier segment
 TILE64_META_BYTES = 1024            # per tile and side: 16 bytes per token
 
 
@@ -577,50 +506,6 @@ def unpack_tiles64(data, meta, n, bits, which):
     sc = meta[:, sc_idx].astype(np.uint16)
     of = meta[:, of_idx].astype(np.uint16)
     return codes.reshape(nt * R, 128)[:n], sc.reshape(nt * R, 4)[:n], of.reshape(nt * R, 4)[:n]
-
-
-def tile_data_bytes(bits):
-    return TILE_ROWS * 128 * bits // 8
-
-
-def pack_tiles(codes, scale_bits, off_bits, bits, which):
-    """Physical tiles of n rows (zero-padded to whole tiles).  codes uint8 [n,128];
-    scale_bits, off_bits uint16 [n,4].  Returns (data uint8 [tiles*tile_bytes],
-    meta uint8 [tiles*512])."""
-    n = codes.shape[0]
-    nt = (n + TILE_ROWS - 1) // TILE_ROWS
-    cp = np.zeros((nt * TILE_ROWS, 128), dtype=np.uint8)
-    cp[:n] = codes
-    sp = np.zeros((nt * TILE_ROWS, 4), dtype=np.uint16)
-    op = np.zeros((nt * TILE_ROWS, 4), dtype=np.uint16)
-    sp[:n], op[:n] = scale_bits, off_bits
-    byte_off, shift = tile_code_positions(bits, which)
-    sc_idx, of_idx = tile_meta_positions(which)
-    tb = tile_data_bytes(bits)
-    data = np.zeros((nt, tb), dtype=np.uint8)
-    meta = np.zeros((nt, TILE_META_BYTES // 2), dtype="<u2")
-    cp = cp.reshape(nt, TILE_ROWS, 128)
-    for t in range(nt):
-        contrib = (cp[t].astype(np.uint32) << shift.astype(np.uint32)).astype(np.uint8)
-        np.bitwise_or.at(data[t], byte_off.reshape(-1), contrib.reshape(-1))
-        meta[t, sc_idx.reshape(-1)] = sp[t * TILE_ROWS:(t + 1) * TILE_ROWS].reshape(-1)
-        meta[t, of_idx.reshape(-1)] = op[t * TILE_ROWS:(t + 1) * TILE_ROWS].reshape(-1)
-    return data.reshape(-1), meta.view(np.uint8).reshape(-1)
-
-
-def unpack_tiles(data, meta, n, bits, which):
-    """Inverse of pack_tiles for the first n rows."""
-    nt = (n + TILE_ROWS - 1) // TILE_ROWS
-    byte_off, shift = tile_code_positions(bits, which)
-    sc_idx, of_idx = tile_meta_positions(which)
-    data = np.asarray(data, dtype=np.uint8).reshape(nt, tile_data_bytes(bits))
-    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape(nt, TILE_META_BYTES // 2)
-    mask = (1 << bits) - 1
-    codes = ((data[:, byte_off] >> shift.astype(np.uint8)) & mask).astype(np.uint8)      # [nt,32,128]
-    sc = meta[:, sc_idx].astype(np.uint16)
-    of = meta[:, of_idx].astype(np.uint16)
-    return (codes.reshape(nt * TILE_ROWS, 128)[:n], sc.reshape(nt * TILE_ROWS, 4)[:n],
-            of.reshape(nt * TILE_ROWS, 4)[:n])
 
 
 def physical_segments(rec, d=128):
@@ -748,61 +633,71 @@ def unpack_item(cache, item):
 # Mixed mode (Sec. 3.2 Stages 2-3, the paper's own arrangement): V token-wise,
 # K channel-wise on the retained tokens
 # --------------------------------------------------------------------------
+SLOT_PAD = {16: 4, 8: 4, 4: 8, 2: 16}   # channel slots of a K tier are padded to whole steps / whole 32-bit words
+
+
 def channel_slots(bits_ch):
     """Sorted-channel order of one item's K rows (App. B: channels are sorted by
     bit-width into segments along the channel axis and the query is permuted to
-    match).  Tiers in the order 16, 8, 4, 2, ascending channel index inside a tier;
-    every tier is padded to a whole number of 8-channel "quads" (the paper pads the
-    2-bit and 4-bit segments to whole bytes; padded channels carry s = m = 0 and
-    zero codes, so they contribute nothing).  Evicted channels (0 bits) get no slot.
-    Returns {'order': {b: channel indices}, 'nq': {b: quads}, 'slot_ch': int array,
-    one entry per slot, the channel it holds or -1 for padding,
-    'qslot': slot indices of the quantized tiers (8, 4, 2) in order}."""
+    match).  Tiers in the order 16, 8, 4, 2, ascending channel index inside a tier.
+    A retained token's K row is a run of 32-bit words: a 16-bit word holds 2 channels,
+    an 8-bit word 4, a 4-bit word 8, a 2-bit word 16; every tier is padded to whole
+    words (the 16-bit tier to whole word pairs = 4 channels) -- the paper pads its 2-
+    and 4-bit segments to whole bytes the same way; padded channels carry zero codes
+    and s = m = 0, so they contribute nothing.  Evicted channels (0 bits) get no slot.
+    A *step* is 4 consecutive slots (one matrix-core operand in the decode kernel).
+    Returns {'order': {b: channel indices}, 'npad': {b: padded slot count},
+    'nw': {b: words per token}, 'slot_ch': one entry per slot, the channel it holds or
+    -1 for padding, 'n_words', 'n_words_padded' (even), 'n_steps16', 'n_qsteps'}."""
     bits_ch = np.asarray(bits_ch, dtype=np.uint8)
-    order, nq, slot_ch = {}, {}, []
+    order, npad, nw, slot_ch = {}, {}, {}, []
     for b in PACK_ORDER:
         ch = np.nonzero(bits_ch == b)[0].astype(np.int64)
         order[b] = ch
-        nq[b] = (len(ch) + 7) // 8
-        slot_ch += list(ch) + [-1] * (8 * nq[b] - len(ch))
-    slot_ch = np.asarray(slot_ch, dtype=np.int64)
-    return {"order": order, "nq": nq, "slot_ch": slot_ch, "n_q16": 8 * nq[16]}
+        npad[b] = _round_up(len(ch), SLOT_PAD[b])
+        nw[b] = npad[b] * b // 32
+        slot_ch += list(ch) + [-1] * (npad[b] - len(ch))
+    n_words = sum(nw.values())
+    return {"order": order, "npad": npad, "nw": nw, "slot_ch": np.asarray(slot_ch, dtype=np.int64),
+            "n_words": n_words, "n_words_padded": _round_up(n_words, 2),
+            "n_steps16": npad[16] // 4, "n_qsteps": (npad[8] + npad[4] + npad[2]) // 4}
 
 
-def k_tile_bytes_mixed(nq):
-    """Bytes of one 32-token K tile: a quad of tier b is 8 channels x 32 tokens x b bits."""
-    return sum(nq[b] * 32 * b for b in PACK_ORDER)
+def k_tile_bytes_mixed(sl):
+    """Bytes of one 64-token K tile: 64 tokens x an even number of 32-bit words."""
+    return 256 * sl["n_words_padded"]
 
 
-def k_meta_bytes_mixed(nq):
-    """Per tile: one fp16 scale and one fp16 offset per slot of the quantized tiers."""
-    return 4 * 8 * (nq[8] + nq[4] + nq[2])
+def k_meta_bytes_mixed(sl):
+    """Per tile: for each of the two 32-token groups and each quantized step (4 slots),
+    4 fp16 scales then 4 fp16 offsets."""
+    return 32 * sl["n_qsteps"]
 
 
 def quantize_channelwise(Krows, bits_ch):
     """Channel-wise K quantization of the retained rows of one tier segment.
 
     The paper uses one scale and zero-point per channel (App. B); this build's
-    layout groups 32 consecutive retained tokens of a channel (one tile of the
+    layout groups 32 consecutive retained tokens of a channel (half a tile of the
     segment; the last group may be short), with the same quantizer as elsewhere
     (fp16 scale, fp16 offset = group minimum, fp32 arithmetic in a fixed order).
     Krows: float32 [n, d] bf16-exact, in packed order.  Returns
       codes  uint16 [n, d]: integer codes (tiers 8/4/2), bf16 bit patterns (tier 16), 0 (tier 0)
-      scale, off  uint16 [tiles, d]: fp16 bit patterns (0 for tiers 16 and 0)."""
+      scale, off  uint16 [groups, d]: fp16 bit patterns (0 for tiers 16 and 0)."""
     Krows = _check_bf16_exact(Krows, "K")
     n, d = Krows.shape
     bits_ch = np.asarray(bits_ch, dtype=np.uint8)
-    nt = (n + TILE_ROWS - 1) // TILE_ROWS
+    ng = (n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP
     codes = np.zeros((n, d), dtype=np.uint16)
-    scale = np.zeros((nt, d), dtype=np.uint16)
-    off = np.zeros((nt, d), dtype=np.uint16)
+    scale = np.zeros((ng, d), dtype=np.uint16)
+    off = np.zeros((ng, d), dtype=np.uint16)
     for c in range(d):
         b = int(bits_ch[c])
         if b == 16:
             codes[:, c] = bf16_bits(Krows[:, c])
         elif b in (2, 4, 8):
-            for t in range(nt):
-                rows = slice(t * TILE_ROWS, min(n, (t + 1) * TILE_ROWS))
+            for t in range(ng):
+                rows = slice(t * K_TOKEN_GROUP, min(n, (t + 1) * K_TOKEN_GROUP))
                 cc, sc, mc = quantize_groups(Krows[rows, c][None, :], b)
                 codes[rows, c] = cc[0]
                 scale[t, c] = sc.view(np.uint16)[0]
@@ -820,144 +715,151 @@ def dequantize_channelwise(codes, scale, off, bits_ch):
         if b == 16:
             out[:, c] = bf16_from_bits(codes[:, c]).astype(np.float64)
         elif b in (2, 4, 8):
-            t = np.arange(n) // TILE_ROWS
+            t = np.arange(n) // K_TOKEN_GROUP
             s = scale[:, c].copy().view(np.float16).astype(np.float64)[t]
             m = off[:, c].copy().view(np.float16).astype(np.float64)[t]
             out[:, c] = s * codes[:, c].astype(np.float64) + m
     return out
 
 
-def _k_field_position(b, slot, mb):
-    """(byte offset inside the lane's 2b bytes, bit shift) of the code of channel
-    slot `slot` (0..7 of the quad) and token half `mb` for a quantized tier b.
-    The lane's bytes are b/2 little-endian 32-bit words.  Slots pair up as (2p, 2p+1)
-    in the low and high 16-bit halves of a word; a half holds 16/b fields, the first
-    8/b of them token half 0 and the rest token half 1, so that shifting a word right
-    by 8 bits puts the half-1 codes where the half-0 codes were.  With P = 8/b pairs
-    per word: pair p lives in word p // P at field P*mb + p % P of each half."""
-    P = 8 // b
-    hh, pair = slot % 2, slot // 2
-    w, f = pair // P, P * mb + pair % P
-    bit = 32 * w + 16 * hh + b * f
-    return bit // 8, bit % 8
+def _k_word_offset(W, r, nwp):
+    """Byte offset, inside a K tile of nwp words per token, of word W of token r (0..63).
+    Words go out in runs of four (a wavefront reads 1 KiB per 16-byte load, lane = token);
+    if nwp is not a multiple of four the last two words form a run of their own."""
+    full = 4 * (nwp // 4)
+    if W < full:
+        return 1024 * (W // 4) + 16 * r + 4 * (W % 4)
+    return 256 * full + 8 * r + 4 * (W - full)
+
+
+def _k_code_bit(b, j):
+    """Bit position inside its 32-bit word of slot j of the word (a b-bit word holds
+    32/b slots).  Slot j = 4k + e is element e of the word's step k; elements (0, 1)
+    sit at one bit field of the low and high 16-bit half, elements (2, 3) at the next
+    field: bit 16 (e % 2) + b (e // 2) + 2 b k.  A 16-bit word holds its two slots in
+    its two halves."""
+    if b == 16:
+        return 16 * j
+    k, e = j // 4, j % 4
+    return 16 * (e % 2) + b * (e // 2) + 2 * b * k
+
+
+def _k_slot_words(sl):
+    """(tier b, slot index inside the tier, word index inside the row, slot inside the
+    word) for every slot of the sorted-channel order."""
+    out, word0 = [], 0
+    for b in PACK_ORDER:
+        per_word = 32 // b
+        for s in range(sl["npad"][b]):
+            out.append((b, s, word0 + s // per_word, s % per_word))
+        word0 += sl["nw"][b]
+    return out
 
 
 def pack_k_tiles_mixed(codes, scale, off, bits_ch):
-    """Physical K tiles of one tier segment in mixed mode.
+    """Physical K tiles (64 tokens) of one tier segment in mixed mode.
 
-    Tile data = for tier b in 16, 8, 4, 2, for each quad of the tier (8 channel slots
-    x 32 tokens): 16 lanes x 2b bytes, lane l16 holding tokens l16 (half 0) and 16 + l16
-    (half 1) of the tile for the quad's 8 slots:
-      tier 16:    8 bf16 of half 0 (slot order) then 8 bf16 of half 1
-      tiers 8/4/2: bit fields per _k_field_position
-    Tile metadata = fp16 scales of all quantized slots (tiers 8, 4, 2 in order), then
-    their fp16 offsets.  Rows beyond n in the last tile and padding slots are zero.
+    Tile data: token r of the tile owns n_words_padded 32-bit words (_k_word_offset);
+    the words of the 16-bit channels come first, then the 8-, 4- and 2-bit words, slots
+    in sorted-channel order inside a tier (_k_code_bit).
+    Tile metadata: for token group G (rows 32G..32G+31 of the tile) and quantized step
+    sq (4 consecutive slots of the 8/4/2-bit tiers): fp16 element 8 (G n_qsteps + sq) + e
+    is the scale of the step's slot e, element + 4 its offset.
+    Rows beyond n in the last tile and padding slots are zero.
     Returns (data uint8, meta uint8)."""
     n, d = codes.shape
     sl = channel_slots(bits_ch)
-    nq, slot_ch = sl["nq"], sl["slot_ch"]
-    nt = (n + TILE_ROWS - 1) // TILE_ROWS
-    tb, mbytes = k_tile_bytes_mixed(nq), k_meta_bytes_mixed(nq)
-    data = np.zeros((nt, tb), dtype=np.uint8)
-    meta = np.zeros((nt, mbytes // 2), dtype="<u2")
-    nqs = mbytes // 4                                 # quantized slots
-    cp = np.zeros((nt * TILE_ROWS, d), dtype=np.uint16)
+    R = TILE64_ROWS
+    nt = (n + R - 1) // R
+    nwp, nqs = sl["n_words_padded"], sl["n_qsteps"]
+    data = np.zeros((nt, 64 * nwp), dtype="<u4")
+    meta = np.zeros((nt, 16 * nqs), dtype="<u2")
+    cp = np.zeros((nt * R, d), dtype=np.uint32)
     cp[:n] = codes
-    cp = cp.reshape(nt, TILE_ROWS, d)
-    base, slot0, qs = 0, 0, 0
-    for b in PACK_ORDER:
-        for Q in range(nq[b]):
-            for j in range(8):
-                ch = int(slot_ch[slot0 + 8 * Q + j])
-                if b != 16:
-                    if ch >= 0:
-                        meta[:, qs] = scale[:, ch]
-                        meta[:, nqs + qs] = off[:, ch]
-                    qs += 1
-                if ch < 0:
-                    continue
-                for mb in range(2):
-                    for l16 in range(16):
-                        vals = cp[:, 16 * mb + l16, ch]                      # one value per tile
-                        lane_base = base + Q * 32 * b + l16 * 2 * b
-                        if b == 16:
-                            o = lane_base + 16 * mb + 2 * j
-                            data[:, o] = (vals & 0xFF).astype(np.uint8)
-                            data[:, o + 1] = (vals >> 8).astype(np.uint8)
-                        else:
-                            bo, sh = _k_field_position(b, j, mb)
-                            data[:, lane_base + bo] |= (vals.astype(np.uint32) << sh).astype(np.uint8)
-        base += nq[b] * 32 * b
-        slot0 += 8 * nq[b]
-    return data.reshape(-1), meta.view(np.uint8).reshape(-1)
+    cp = cp.reshape(nt, R, d)
+    ng = scale.shape[0]
+    sg = np.zeros((2 * nt, d), dtype=np.uint16)
+    og = np.zeros((2 * nt, d), dtype=np.uint16)
+    sg[:ng], og[:ng] = scale, off
+    sg, og = sg.reshape(nt, 2, d), og.reshape(nt, 2, d)
+    rows = np.arange(R)
+    qs = 0
+    for (b, s, W, j), ch in zip(_k_slot_words(sl), sl["slot_ch"]):
+        if b != 16:
+            if ch >= 0:
+                for G in range(2):
+                    meta[:, 8 * (G * nqs + qs // 4) + qs % 4] = sg[:, G, ch]
+                    meta[:, 8 * (G * nqs + qs // 4) + 4 + qs % 4] = og[:, G, ch]
+            qs += 1
+        if ch < 0:
+            continue
+        widx = np.array([_k_word_offset(W, r, nwp) // 4 for r in rows])
+        data[:, widx] |= cp[:, :, ch] << np.uint32(_k_code_bit(b, j))
+    return data.view(np.uint8).reshape(-1), meta.view(np.uint8).reshape(-1)
 
 
 def unpack_k_tiles_mixed(data, meta, n, bits_ch, d=128):
     """Inverse of pack_k_tiles_mixed for the first n rows: (codes, scale, off)."""
     sl = channel_slots(bits_ch)
-    nq, slot_ch = sl["nq"], sl["slot_ch"]
-    nt = (n + TILE_ROWS - 1) // TILE_ROWS
-    tb, mbytes = k_tile_bytes_mixed(nq), k_meta_bytes_mixed(nq)
-    data = np.asarray(data, dtype=np.uint8).reshape(nt, tb)
-    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape(nt, mbytes // 2)
-    nqs = mbytes // 4
-    codes = np.zeros((nt, TILE_ROWS, d), dtype=np.uint16)
-    scale = np.zeros((nt, d), dtype=np.uint16)
-    off = np.zeros((nt, d), dtype=np.uint16)
-    base, slot0, qs = 0, 0, 0
-    for b in PACK_ORDER:
-        for Q in range(nq[b]):
-            for j in range(8):
-                ch = int(slot_ch[slot0 + 8 * Q + j])
-                if b != 16:
-                    if ch >= 0:
-                        scale[:, ch] = meta[:, qs]
-                        off[:, ch] = meta[:, nqs + qs]
-                    qs += 1
-                if ch < 0:
-                    continue
-                for mb in range(2):
-                    for l16 in range(16):
-                        lane_base = base + Q * 32 * b + l16 * 2 * b
-                        if b == 16:
-                            o = lane_base + 16 * mb + 2 * j
-                            v = data[:, o].astype(np.uint16) | (data[:, o + 1].astype(np.uint16) << 8)
-                        else:
-                            bo, sh = _k_field_position(b, j, mb)
-                            v = (data[:, lane_base + bo] >> sh) & ((1 << b) - 1)
-                        codes[:, 16 * mb + l16, ch] = v
-        base += nq[b] * 32 * b
-        slot0 += 8 * nq[b]
-    return codes.reshape(nt * TILE_ROWS, d)[:n], scale, off
+    R = TILE64_ROWS
+    nt = (n + R - 1) // R
+    ng = (n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP
+    nwp, nqs = sl["n_words_padded"], sl["n_qsteps"]
+    data = np.asarray(data, dtype=np.uint8).view("<u4").reshape(nt, 64 * nwp)
+    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape(nt, 16 * nqs)
+    codes = np.zeros((nt, R, d), dtype=np.uint16)
+    scale = np.zeros((2 * nt, d), dtype=np.uint16)
+    off = np.zeros((2 * nt, d), dtype=np.uint16)
+    rows = np.arange(R)
+    qs = 0
+    for (b, s, W, j), ch in zip(_k_slot_words(sl), sl["slot_ch"]):
+        if b != 16:
+            if ch >= 0:
+                for G in range(2):
+                    scale[G::2, ch] = meta[:, 8 * (G * nqs + qs // 4) + qs % 4]
+                    off[G::2, ch] = meta[:, 8 * (G * nqs + qs // 4) + 4 + qs % 4]
+            qs += 1
+        if ch < 0:
+            continue
+        widx = np.array([_k_word_offset(W, r, nwp) // 4 for r in rows])
+        codes[:, :, ch] = (data[:, widx] >> np.uint32(_k_code_bit(b, j))) & np.uint32((1 << b) - 1)
+    return codes.reshape(nt * R, d)[:n], scale[:ng], off[:ng]
+
+
+def _v16_position(r, c):
+    """16-bit element index, inside a 16 KiB tile of 64 bf16 V rows, of (row r, channel c):
+    lane 32 (r // 32) + c % 32 holds channel c for the 32 tokens of its tile half, eight
+    tokens per 16-byte unit; unit u = 4 (c // 32) + (r % 32) // 8 sits at byte 1024 u + 16 lane."""
+    lane, u = 32 * (r // 32) + c % 32, 4 * (c // 32) + (r % 32) // 8
+    return (1024 * u + 16 * lane) // 2 + r % 8
 
 
 def pack_v16_tiles(vbits):
-    """Mixed mode keeps 16-bit V rows (Zone B of Sec. 3.3) in 32-token tiles with the
-    same lane / operand / slot assignment as the quantized V tiers: the bf16 of
-    (lane, operand o, slot s) sits at byte 1024*o + 16*lane + 2*s of the 8 KiB tile.
-    vbits: uint16 [n, 128].  Returns uint8 [tiles * 8192]."""
+    """Mixed mode keeps 16-bit V rows (Zone B of Sec. 3.3) in 64-token tiles with the
+    lane assignment of the quantized V tiers (a lane holds one channel for 32 tokens).
+    vbits: uint16 [n, 128].  Returns uint8 [tiles * 16384]."""
     n = vbits.shape[0]
-    nt = (n + TILE_ROWS - 1) // TILE_ROWS
-    vp = np.zeros((nt * TILE_ROWS, 128), dtype=np.uint16)
+    R = TILE64_ROWS
+    nt = (n + R - 1) // R
+    vp = np.zeros((nt * R, 128), dtype=np.uint16)
     vp[:n] = vbits
-    vp = vp.reshape(nt, TILE_ROWS, 128)
-    out = np.zeros((nt, 4096), dtype="<u2")
-    for r in range(TILE_ROWS):
+    vp = vp.reshape(nt, R, 128)
+    out = np.zeros((nt, R * 128), dtype="<u2")
+    for r in range(R):
         for c in range(128):
-            o, lane, sl = c // 16, 16 * ((r % 16) // 4) + c % 16, 4 * (r // 16) + r % 4
-            out[:, (1024 * o + 16 * lane) // 2 + sl] = vp[:, r, c]
+            out[:, _v16_position(r, c)] = vp[:, r, c]
     return out.view(np.uint8).reshape(-1)
 
 
 def unpack_v16_tiles(data, n):
-    nt = (n + TILE_ROWS - 1) // TILE_ROWS
-    w = np.asarray(data, dtype=np.uint8).view("<u2").reshape(nt, 4096)
-    out = np.zeros((nt, TILE_ROWS, 128), dtype=np.uint16)
-    for r in range(TILE_ROWS):
+    R = TILE64_ROWS
+    nt = (n + R - 1) // R
+    w = np.asarray(data, dtype=np.uint8).view("<u2").reshape(nt, R * 128)
+    out = np.zeros((nt, R, 128), dtype=np.uint16)
+    for r in range(R):
         for c in range(128):
-            o, lane, sl = c // 16, 16 * ((r % 16) // 4) + c % 16, 4 * (r // 16) + r % 4
-            out[:, r, c] = w[:, (1024 * o + 16 * lane) // 2 + sl]
-    return out.reshape(nt * TILE_ROWS, 128)[:n]
+            out[:, r, c] = w[:, _v16_position(r, c)]
+    return out.reshape(nt * R, 128)[:n]
 
 
 def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list):
@@ -996,7 +898,7 @@ def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list):
                 rec[b] = {"pos": pos, "k_codes": kc, "k_scale": ks, "k_off": ko, "v_codes": vcodes}
             else:
                 c, sc, m = quantize_groups(Vh[pos].reshape(n, d // GROUP, GROUP), b)
-                vd, vm = pack_tiles(c.reshape(n, d), sc.view(np.uint16), m.view(np.uint16), b, "v")
+                vd, vm = pack_tiles64(c.reshape(n, d), sc.view(np.uint16), m.view(np.uint16), b, "v")
                 rec[b] = {"pos": pos, "k_codes": kc, "k_scale": ks, "k_off": ko, "v_codes": c.reshape(n, d),
                           "v_scale": sc.view(np.uint16), "v_off": m.view(np.uint16)}
             for si, seg in enumerate((kd, km, vd, vm)):
@@ -1020,7 +922,8 @@ def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list):
 
 def stored_bytes_mixed(counts, bits_ch, d=128):
     """Bytes a decode step must read in mixed mode (unpadded): per item and V tier with n
-    rows, K codes n * sum_c b_c / 8, K metadata ceil(n / 32) * 4 per quantized channel, and
+    rows, K codes n * sum_c b_c / 8, K metadata ceil(n / 32) * 4 per quantized channel (one fp16
+    scale and offset per channel and group of 32 retained tokens), and
     the V rows as in token-wise mode (n * (16 b + 16), or n * 256 at 16 bits)."""
     counts = np.asarray(counts, dtype=np.int64).reshape(-1, 4)
     total = 0
@@ -1030,7 +933,7 @@ def stored_bytes_mixed(counts, bits_ch, d=128):
         nquant = int(((bc == 2) | (bc == 4) | (bc == 8)).sum())
         for ti, b in enumerate(PACK_ORDER):
             n = int(counts[i, ti])
-            total += n * kbits // 8 + ((n + TILE_ROWS - 1) // TILE_ROWS) * 4 * nquant
+            total += n * kbits // 8 + ((n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP) * 4 * nquant
             total += n * (row_bytes(b, d) + meta_bytes(b, d))
     return total
 
@@ -1041,23 +944,23 @@ def unpack_item_mixed(cache, item):
     d = cache["d"]
     arena, seg_off, counts = cache["arena"], cache["seg_off"], cache["counts"]
     bc = cache["bits_ch"][item]
-    nq = channel_slots(bc)["nq"]
-    tb, mb_ = k_tile_bytes_mixed(nq), k_meta_bytes_mixed(nq)
+    sl = channel_slots(bc)
+    tb, mb_ = k_tile_bytes_mixed(sl), k_meta_bytes_mixed(sl)
     ks, vs = [], []
     for ti, b in enumerate(PACK_ORDER):
         n = int(counts[item, ti])
         if n == 0:
             continue
-        nt = (n + TILE_ROWS - 1) // TILE_ROWS
+        nt = (n + TILE64_ROWS - 1) // TILE64_ROWS
         o = [int(x) for x in seg_off[item, ti]]
         kc, ksc, kof = unpack_k_tiles_mixed(arena[o[0]:o[0] + nt * tb], arena[o[1]:o[1] + nt * mb_], n, bc, d)
         ks.append(dequantize_channelwise(kc, ksc, kof, bc))
         if b == 16:
-            vbits = unpack_v16_tiles(arena[o[2]:o[2] + nt * 8192], n)
+            vbits = unpack_v16_tiles(arena[o[2]:o[2] + nt * 16384], n)
             vs.append(bf16_from_bits(vbits).astype(np.float64))
         else:
-            codes, sc, of = unpack_tiles(arena[o[2]:o[2] + nt * tile_data_bytes(b)],
-                                         arena[o[3]:o[3] + nt * TILE_META_BYTES], n, b, "v")
+            codes, sc, of = unpack_tiles64(arena[o[2]:o[2] + nt * tile64_data_bytes(b)],
+                                           arena[o[3]:o[3] + nt * TILE64_META_BYTES], n, b, "v")
             vs.append(dequantize_groups(codes.reshape(n, d // GROUP, GROUP), sc.copy().view(np.float16),
                                         of.copy().view(np.float16)).reshape(n, d))
     if not ks:

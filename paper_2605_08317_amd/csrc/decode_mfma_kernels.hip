@@ -29,101 +29,6 @@ namespace {
 
 using namespace tile;
 
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-
-constexpr int kTile = 64;   // tokens per tile
-
-union Pack4 {
-  half4 h;
-  half2v p[2];
-  uint32_t u[2];
-};
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
-  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v) {
-  return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
-}
-// reduction over the 16 lanes that hold the same head (lane % 4): lanes 4 apart inside a row of 16, then the rows
-__device__ __forceinline__ float head_max(float v) {
-  v = fmaxf(v, dpp_f32<0x124>(v));   // row_ror:4
-  v = fmaxf(v, dpp_f32<0x128>(v));   // row_ror:8
-  v = fmaxf(v, __shfl_xor(v, 16));
-  v = fmaxf(v, __shfl_xor(v, 32));
-  return v;
-}
-__device__ __forceinline__ float head_sum(float v) {
-  v += dpp_f32<0x124>(v);
-  v += dpp_f32<0x128>(v);
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
-  return v;
-}
-// value held by lane i of this lane's quad
-template <int I>
-__device__ __forceinline__ uint32_t quad_bcast(uint32_t v) { return dpp_u32<I * 0x55>(v); }
-
-// Field position of step s inside a 16-bit half, which right-shifted copy of the word it is read from, and the bit
-// offset that remains after that shift (the code then reads as code * 2^fb * 2^-24).
-template <int TIER>
-struct Step {
-  static constexpr int F = 16 / TIER;                                     // fields per half
-  __host__ __device__ static constexpr int pair(int s) { return s / F; }
-  __host__ __device__ static constexpr int field(int s) { return s % F; }
-  __host__ __device__ static constexpr int copy(int s) {
-    return TIER == 8 ? 0 : TIER == 4 ? field(s) / 2 : field(s) / 3;
-  }
-  __host__ __device__ static constexpr int fb(int s) {
-    return TIER == 8 ? 0 : TIER == 4 ? 4 * (field(s) % 2) : 2 * (field(s) % 3);
-  }
-  static constexpr int kCopies = TIER == 8 ? 1 : TIER == 4 ? 2 : 3;
-  static constexpr int kShift = TIER == 4 ? 8 : 6;                        // right shift between copies
-};
-
-// The 4 codes of step s of a group whose words are gw[0..TIER): two words, fp16 subnormals in both halves.
-template <int TIER>
-__device__ __forceinline__ half4 step_operand(const uint32_t (&gw)[Step<TIER>::kCopies][TIER], int s) {
-  using S = Step<TIER>;
-  Pack4 r;
-  const int p = S::pair(s);
-  if constexpr (TIER == 8) {
-    // byte f of each half, zero-extended: both selections go through the byte permute (mixing it with a plain
-    // AND of the same register was seen to be scheduled with the AND done in place before the permute read it)
-    const uint32_t sel = S::field(s) ? 0x0C030C01u : 0x0C020C00u;
-    r.u[0] = __builtin_amdgcn_perm(0u, gw[0][2 * p], sel);
-    r.u[1] = __builtin_amdgcn_perm(0u, gw[0][2 * p + 1], sel);
-  } else {
-    const uint32_t mask = (TIER == 4 ? 0x000F000Fu : 0x00030003u) << S::fb(s);
-    r.u[0] = gw[S::copy(s)][2 * p] & mask;
-    r.u[1] = gw[S::copy(s)][2 * p + 1] & mask;
-  }
-  return r.h;
-}
-
-template <int TIER>
-__device__ __forceinline__ void group_words(const uint4 (&raw)[TIER], int grp, uint32_t (&gw)[Step<TIER>::kCopies][TIER]) {
-  using S = Step<TIER>;
-#pragma unroll
-  for (int w = 0; w < TIER; ++w) {
-    const int W = grp * TIER + w;
-    const uint4 c = raw[W >> 2];
-    const uint32_t v = (W & 3) == 0 ? c.x : (W & 3) == 1 ? c.y : (W & 3) == 2 ? c.z : c.w;
-    gw[0][w] = v;
-#pragma unroll
-    for (int k = 1; k < S::kCopies; ++k) gw[k][w] = v >> (k * S::kShift);
-  }
-}
-
-template <int TIER>
-__device__ __forceinline__ void load_tile_side(uint4 (&raw)[TIER], const uint8_t* __restrict__ data, int tile, int lane) {
-  const uint8_t* p = data + static_cast<int64_t>(tile) * (kTile * 16 * TIER) + lane * 16;
-#pragma unroll
-  for (int i = 0; i < TIER; ++i) raw[i] = *reinterpret_cast<const uint4*>(p + i * 1024);
-}
-
 // LDS: query operands [HS][4 groups][8 steps][4 heads] x 8 bytes, group sums [HS][hi, lo][4 heads] x 8 bytes,
 // then the merge area
 template <int HS>
@@ -213,25 +118,9 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
   __syncthreads();
 
-  // 2^-fb of the field this lane's block is read from on the V side (block a = blk % 8 feeds step a)
-  float kappa = 1.0f;
-#pragma unroll
-  for (int a = 0; a < 8; ++a)
-    if ((blk & 7) == a) kappa = 1.0f / static_cast<float>(1 << S::fb(a));
-
-  float m_run[HS], l_run[HS];
-  floatx4 acc[HS][4];
-  float off[HS][4];
-#pragma unroll
-  for (int hs = 0; hs < HS; ++hs) {
-    m_run[hs] = kNegBig;
-    l_run[hs] = 0.f;
-#pragma unroll
-    for (int grp = 0; grp < 4; ++grp) {
-      acc[hs][grp] = floatx4{0.f, 0.f, 0.f, 0.f};
-      off[hs][grp] = 0.f;
-    }
-  }
+  const float kappa = v_kappa<TIER>(blk);
+  Run<HS> run;
+  run.init();
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
   auto do_tile = [&](Regs& r, const int tile) __attribute__((always_inline)) {
@@ -296,79 +185,10 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
     if constexpr (kShare) load_v(r, tile);   // the K codes are used up: their registers take this tile's V codes
     else if (more) load_k(r, next);          // K registers are free again
 
-    if ((tile + 1) * kTile > rows) {   // padded rows of the last tile
-#pragma unroll
-      for (int hs = 0; hs < HS; ++hs)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (tile * kTile + 4 * blk + i >= rows) x[hs][i] = -INFINITY;
-    }
-
-    // ---- online softmax per head; probabilities carried times 2^kPExp ----------------------------------
+    mask_rows<HS>(x, tile, rows, blk);
     float p[HS][4];
-#pragma unroll
-    for (int hs = 0; hs < HS; ++hs) {
-      const float mt = head_max(fmaxf(fmaxf(x[hs][0], x[hs][1]), fmaxf(x[hs][2], x[hs][3])));
-      const float m_new = fmaxf(m_run[hs], mt);
-      if (__any(m_new != m_run[hs])) {
-        const float alpha = fast_exp2((m_run[hs] - m_new) * kXScale);
-        l_run[hs] *= alpha;
-        const uint32_t au = __builtin_bit_cast(uint32_t, alpha);
-        const float ah[4] = {__builtin_bit_cast(float, quad_bcast<0>(au)), __builtin_bit_cast(float, quad_bcast<1>(au)),
-                             __builtin_bit_cast(float, quad_bcast<2>(au)), __builtin_bit_cast(float, quad_bcast<3>(au))};
-#pragma unroll
-        for (int grp = 0; grp < 4; ++grp) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) acc[hs][grp][i] *= ah[i];   // acc row i is head i
-          off[hs][grp] *= alpha;
-        }
-        m_run[hs] = m_new;
-      }
-      const float neg_mc = kPExp - m_run[hs] * kXScale;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        p[hs][i] = fast_exp2(__builtin_fmaf(x[hs][i], kXScale, neg_mc));
-        l_run[hs] += p[hs][i];
-      }
-    }
-
-    // ---- P V ------------------------------------------------------------------------------------------------
-    {
-      Pack4 ph[HS];
-#pragma unroll
-      for (int hs = 0; hs < HS; ++hs) {
-        ph[hs].p[0] = half2v{static_cast<_Float16>(p[hs][0] * kappa), static_cast<_Float16>(p[hs][1] * kappa)};
-        ph[hs].p[1] = half2v{static_cast<_Float16>(p[hs][2] * kappa), static_cast<_Float16>(p[hs][3] * kappa)};
-      }
-#define RDKV_PV_GROUP(G_)                                                                                      \
-  {                                                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                         \
-    /* V metadata of tokens 4 blk + 0..3: lane G_ of the quad holds group G_'s scales (x, y), offsets (z, w) */ \
-    Pack4 sv, ov, pa[HS];                                                                                      \
-    sv.u[0] = quad_bcast<G_>(vmeta.x); sv.u[1] = quad_bcast<G_>(vmeta.y);                                      \
-    ov.u[0] = quad_bcast<G_>(vmeta.z); ov.u[1] = quad_bcast<G_>(vmeta.w);                                      \
-    _Pragma("unroll") for (int hs = 0; hs < HS; ++hs) {                                                        \
-      pa[hs].p[0] = ph[hs].p[0] * sv.p[0];                                                                     \
-      pa[hs].p[1] = ph[hs].p[1] * sv.p[1];                                                                     \
-      float o = off[hs][G_];                                                                                   \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i) o = __builtin_fmaf(p[hs][i], static_cast<float>(ov.h[i]), o); \
-      off[hs][G_] = o;                                                                                         \
-    }                                                                                                          \
-    uint32_t gw[S::kCopies][TIER];                                                                             \
-    group_words<TIER>(vraw, G_, gw);                                                                           \
-    RDKV_PV_STEP(G_, 0) RDKV_PV_STEP(G_, 1) RDKV_PV_STEP(G_, 2) RDKV_PV_STEP(G_, 3)                            \
-    RDKV_PV_STEP(G_, 4) RDKV_PV_STEP(G_, 5) RDKV_PV_STEP(G_, 6) RDKV_PV_STEP(G_, 7)                            \
-  }
-#define RDKV_PV_STEP(G_, A_)                                                                                   \
-  {                                                                                                            \
-    const half4 b = step_operand<TIER>(gw, A_);                                                                \
-    _Pragma("unroll") for (int hs = 0; hs < HS; ++hs)                                                          \
-        acc[hs][G_] = __builtin_amdgcn_mfma_f32_4x4x4f16(pa[hs].h, b, acc[hs][G_], 3, A_, 0);                  \
-  }
-      RDKV_PV_GROUP(0) RDKV_PV_GROUP(1) RDKV_PV_GROUP(2) RDKV_PV_GROUP(3)
-#undef RDKV_PV_STEP
-#undef RDKV_PV_GROUP
-    }
+    softmax_tile<HS>(x, run, p);
+    pv_tile<TIER, HS>(vraw, vmeta, p, kappa, run);
     if (more) {               // V registers are free again
       if constexpr (kShare) load_k(r, next); else load_v(r, next);
     }
@@ -380,60 +200,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
 
   // ---- end of the chunk: undo the subnormal unit, add the offsets, merge the 4 wavefronts --------------------
-  // acc[hs][grp][i]: head 4 hs + i, channel 32 grp + lane % 32, summed over this lane's token half
-  const int th = lane >> 5, cl = lane & 31;
-#pragma unroll
-  for (int hs = 0; hs < HS; ++hs) {
-    l_run[hs] = head_sum(l_run[hs]);
-#pragma unroll
-    for (int grp = 0; grp < 4; ++grp) {
-      const uint32_t ou = __builtin_bit_cast(uint32_t, head_sum(off[hs][grp]));   // lanes of head j hold sum_t p m
-      const float oh[4] = {__builtin_bit_cast(float, quad_bcast<0>(ou)), __builtin_bit_cast(float, quad_bcast<1>(ou)),
-                           __builtin_bit_cast(float, quad_bcast<2>(ou)), __builtin_bit_cast(float, quad_bcast<3>(ou))};
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        acc[hs][grp][i] = __builtin_fmaf(acc[hs][grp][i], 16777216.0f, th == 0 ? oh[i] : 0.f);
-    }
-    if (lane < 4) {
-      s_ml[((wave * HS + hs) * 4 + lane) * 2] = m_run[hs] * kXScale - kPExp;   // log2 domain from here on
-      s_ml[((wave * HS + hs) * 4 + lane) * 2 + 1] = l_run[hs];
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int hs = 0; hs < HS; ++hs)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int head = 4 * hs + i;
-      float mm = kNegBig;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
-      const float f = fast_exp2(s_ml[((wave * HS + hs) * 4 + i) * 2] - mm);
-      if (head < g) {
-#pragma unroll
-        for (int grp = 0; grp < 4; ++grp)
-          s_acc[((wave * 2 + th) * g + head) * kHeadDim + 32 * grp + cl] = acc[hs][grp][i] * f;
-      }
-    }
-  __syncthreads();
-  for (int idx = tid; idx < g * kHeadDim; idx += kWG) {
-    float v = 0.f;
-#pragma unroll
-    for (int w = 0; w < 2 * kWaves; ++w) v += s_acc[w * g * kHeadDim + idx];
-    part_acc[idx] = v;
-  }
-  if (tid < g) {
-    const int hs = tid >> 2, i = tid & 3;
-    float mm = kNegBig;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
-    float ll = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w)
-      ll += s_ml[((w * HS + hs) * 4 + i) * 2 + 1] * fast_exp2(s_ml[((w * HS + hs) * 4 + i) * 2] - mm);
-    part_ml[tid * 2] = mm;
-    part_ml[tid * 2 + 1] = ll;
-  }
+  finish_chunk<HS, false>(run, 16777216.0f, g, s_ml, s_acc, part_acc, part_ml);
 }
 
 template <int HS>

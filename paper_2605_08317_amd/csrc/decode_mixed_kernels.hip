@@ -1,17 +1,20 @@
-// Split-K flash-decode over a mixed-mode cache (Sec. 3.2 Stages 2-3, Sec. 3.3, Eq. 7): V token-wise in tiers,
-// K of the retained tokens channel-wise, on the gfx950 matrix cores.
+// Split-K flash-decode over a mixed-mode cache (Sec. 3.2 Stages 2-3, Sec. 3.3): V token-wise, K channel-wise on
+// the retained tokens, on the gfx950 matrix cores (v_mfma_f32_4x4x4_16B, sixteen independent 4x4x4 blocks).
 //
-// Per-channel quantization k_hat[t][c] = s_c code[t][c] + m_c (one scale and offset per channel and 32-token
-// tile) turns the logits into  sum_c (s_c q_c) code[t][c] + sum_c m_c q_c  (the dequantization fusion of App. B):
-// the query operand is scaled by the tile's channel scales (two fp16 terms whose sum is the exact product), the raw
-// codes are the other MFMA operand, and the offsets go through one more MFMA whose rows are all equal.  Channels are stored
-// sorted by bit-width (App. B: "the query is permuted to the same sorted order"): the permuted query operands are
-// built once per workgroup.  Channels kept at 16 bits go through the bf16 MFMA with the bf16 query (exact products).
+// K side.  A retained token's K row is a run of 32-bit words in sorted-channel order (16-bit words first, then
+// 8-, 4- and 2-bit words); a lane of the wavefront is a token of the 64-token tile and holds its row in registers.
+// With per-channel quantization the logit is sum_c (s_c q_c) code_c + sum_c m_c q_c (fusion identity of App. B).
+// Here a channel's scale belongs to a group of 32 retained tokens (half a tile), so the scaled query is rebuilt
+// per tile: lane i of a token group multiplies the four query heads of step i (4 channel slots) by the step's four
+// scales, keeps the product as an exact sum of two fp16 terms (a single rounded term costs ~2.5e-3 of output error
+// with x10 outlier channels), parks both in the wavefront's LDS table, and adds its share of sum_c m_c q_c, which
+// a lane-transposing reduction turns into one bias per (token group, head).  The main loop then walks the row's
+// words -- word index static, tier boundaries run-time but uniform -- turning each word into one, two or four
+// steps of fp16-subnormal codes (one AND per pair of codes) times the step's scaled query from LDS.  16-bit
+// channels go through the bf16 instruction with the raw bf16 query (exact products).
 //
-// A K tile has a run-time shape (it depends on the item's channel bit map), so a wavefront prefetches the next
-// tile's bytes into registers as a flat run of 1 KiB pieces, parks them in its own LDS buffer, and picks operands
-// out of LDS by address.  The V side is the tile layout of the token-wise tiers; 16-bit V rows (Zone B) are 32-token
-// tiles of bf16 multiplied by the probabilities split into two bf16 terms.
+// V side, softmax and the end-of-chunk merge are the stages shared with the token-wise kernel; 16-bit V rows are
+// 64-token tiles of bf16 with the same lane assignment, multiplied by the probabilities as two bf16 terms.
 #include "decode_tile_common.h"
 
 namespace rdkv {
@@ -20,422 +23,414 @@ namespace {
 
 using namespace tile;
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
 
-constexpr int kMaxOps = 8;                  // K operands of a tile: at most 7 (4 full + 3 partial tiers)
-constexpr int kItemKBytes = (sizeof(ItemK) + 15) / 16 * 16;
-constexpr int kKMetaBytes = 1024;           // per wavefront: K metadata of a tile (at most 4 * 152 bytes)
-constexpr int kVMetaBytes = 512;
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 
-union PackB8 {
-  bf16x8 h;
-  uint32_t u[4];
-  uint4 q;
-};
+// four bf16 of an operand from two 32-bit words (a bit cast: a union of the two types is left in scratch memory)
+__device__ __forceinline__ short4v bf4(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(short4v, uint2v{lo, hi}); }
 
-// V side registers of one tile
-template <int VT>
-struct VRegs {
-  Side<VT> s;
-};
-template <>
-struct VRegs<16> {
-  uint4 o[8];   // operand nt: 8 bf16 (tokens) of channel 16 nt + l16
-};
-
-template <int VT>
-__device__ __forceinline__ void load_v(VRegs<VT>& r, const uint8_t* __restrict__ vd, int tile, int lane) {
-  if constexpr (VT == 16) {
-    const uint8_t* p = vd + static_cast<int64_t>(tile) * (kRowPad * kHeadDim * 2) + lane * 16;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) r.o[i] = *reinterpret_cast<const uint4*>(p + i * 1024);
-  } else {
-    load_side<VT>(r.s, vd, tile, lane);
+// LDS: query operands per step [steps][HS][4 heads] x 8 bytes (raw bf16 for 16-bit steps, fp16 q * 2^(kQExp - fb)
+// for quantized ones), fp16 q * 2^kQExp per quantized step (for the offsets), then per wavefront the scaled-query
+// table [2 token groups][quantized steps][HS][4 heads] x 16 bytes (high terms, low terms).  The merge area of the
+// chunk's end reuses the same memory.
+struct LdsPlan {
+  int qpre, qraw, wtab, wtab_wave, total;
+  __host__ __device__ LdsPlan(int n_steps, int n_qsteps, int hs, int g) {
+    qpre = 0;
+    qraw = qpre + n_steps * hs * 32;
+    wtab = qraw + n_qsteps * hs * 32;
+    wtab_wave = 2 * n_qsteps * hs * 64;
+    const int tables = wtab + kWaves * wtab_wave;
+    const int merge = kWaves * 4 * hs * 2 * 4 + 2 * kWaves * g * kHeadDim * 4;
+    total = tables > merge ? tables : merge;
   }
-}
+};
 
-template <int VT, int NK>
-__device__ __forceinline__ void process_mixed(const ItemK& ik, const uint8_t* __restrict__ kd,
-                                              const uint8_t* __restrict__ km, const uint8_t* __restrict__ vd,
-                                              const uint8_t* __restrict__ vm, int rows, int g,
+// bit offset left after the copy shift of field f of a 16-bit half (tier b): the code reads as code * 2^fb * 2^-24
+__device__ __forceinline__ int field_fb(int b, int f) { return b == 2 ? 2 * (f % 3) : b == 4 ? 4 * (f % 2) : 0; }
+
+template <int VT, int NW, int HS>
+__device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __restrict__ arena,
+                                              const ItemK* __restrict__ ikp, int g, const uint16_t* __restrict__ q,
                                               float* __restrict__ part_acc, float* __restrict__ part_ml,
-                                              const uint8_t* s_qop, uint8_t* s_wave, float* s_ml, float* s_acc) {
+                                              uint8_t* smem, int lds_steps, int lds_qsteps) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int quad = lane >> 4, l16 = lane & 15;
-  uint8_t* s_kbuf = s_wave;                        // [NK KiB] this wavefront's K tile
-  uint8_t* s_kmeta = s_wave + NK * 1024;           // scales then offsets of the quantized slots
-  uint8_t* s_vmeta = s_kmeta + kKMetaBytes;
+  const int blk = lane >> 2, j = lane & 3, G = lane >> 5;
+  const int rows = ch.rows;
+  const int ntiles = (rows + kTile - 1) / kTile;
 
-  const int kt_bytes = ik.kt_bytes, km_bytes = ik.km_bytes;
-  const int ntiles = (rows + kRowPad - 1) / kRowPad;
+  // per-item layout, uniform over the workgroup
+  const int e16 = __builtin_amdgcn_readfirstlane(ikp->word_end[0]);
+  const int e8 = __builtin_amdgcn_readfirstlane(ikp->word_end[1]);
+  const int e4 = __builtin_amdgcn_readfirstlane(ikp->word_end[2]);
+  const int e2 = __builtin_amdgcn_readfirstlane(ikp->word_end[3]);
+  const int nwp = __builtin_amdgcn_readfirstlane(ikp->n_words_padded);
+  const int ns16 = __builtin_amdgcn_readfirstlane(ikp->n_steps16);
+  const int nqs = __builtin_amdgcn_readfirstlane(ikp->n_qsteps);
+  const int n_steps = ns16 + nqs;
+  const int kt_bytes = 256 * nwp, km_bytes = 32 * nqs;
+  const LdsPlan plan(lds_steps, lds_qsteps, HS, g);   // the launch sized LDS for the largest item of the cache
+  const uint8_t* s_qpre = smem + plan.qpre;
+  const uint8_t* s_qraw = smem + plan.qraw;
+  uint8_t* s_wtab = smem + plan.wtab + wave * plan.wtab_wave;
 
-  uint4 kraw[NK], kmeta_r = make_uint4(0, 0, 0, 0), vmeta_r = make_uint4(0, 0, 0, 0);
-  VRegs<VT> rv;
+  const uint8_t* kd = arena + ch.k_data;
+  const uint8_t* km = arena + ch.k_meta;
+  const uint8_t* vd = arena + ch.v_data;
+  const uint8_t* vm = arena + ch.v_meta;
+
+  // ---- registers of a tile and their loads ------------------------------------------------------------------
+  uint32_t kw[NW];      // the lane's token: its K row
+  uint4 kmeta[2];       // scales (x, y), offsets (z, w) of quantized step lane % 32 (+ 32) of this lane's token group
+  // V codes: 4- and 2-bit tiles sit whole in registers; 8- and 16-bit tiles stream through two 32-byte buffers
+  // (an 8-bit channel group, half a 16-bit one), the next piece in flight while the current one is multiplied
+  constexpr bool kStream = VT >= 8;
+  constexpr int kVRegs = kStream ? 2 : VT;
+  constexpr int kPieces = VT == 16 ? 8 : 4;          // pieces of a streamed tile
+  uint4 vraw[kStream ? 2 : 1][kVRegs], vmeta;
   auto load_k = [&](int t) __attribute__((always_inline)) {
-    const uint8_t* p = kd + static_cast<int64_t>(t) * kt_bytes + lane * 16;
+    const uint8_t* p = kd + static_cast<int64_t>(t) * kt_bytes;
 #pragma unroll
-    for (int i = 0; i < NK; ++i) {
-      kraw[i] = make_uint4(0, 0, 0, 0);
-      if (i * 1024 + lane * 16 < kt_bytes) kraw[i] = *reinterpret_cast<const uint4*>(p + i * 1024);
+    for (int u = 0; u < NW / 4; ++u) {
+      // every word is assigned on every path (stores under the branches get merged into stores through a selected
+      // pointer, which keeps the array out of registers)
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (4 * u + 3 < nwp) {
+        v = *reinterpret_cast<const uint4*>(p + 1024 * u + 16 * lane);
+      } else if (4 * u + 1 < nwp) {   // the row's last two words
+        const uint2 t2 = *reinterpret_cast<const uint2*>(p + 1024 * u + 8 * lane);
+        v.x = t2.x;
+        v.y = t2.y;
+      }
+      kw[4 * u] = v.x; kw[4 * u + 1] = v.y; kw[4 * u + 2] = v.z; kw[4 * u + 3] = v.w;
     }
-    if (lane * 16 < km_bytes) kmeta_r = *reinterpret_cast<const uint4*>(km + static_cast<int64_t>(t) * km_bytes + lane * 16);
-    if constexpr (VT != 16) {
-      if (lane < 32) vmeta_r = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(t) * 512 + lane * 16);
+    const uint8_t* pm = km + static_cast<int64_t>(t) * km_bytes;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int sq = (lane & 31) + 32 * it;
+      kmeta[it] = make_uint4(0, 0, 0, 0);
+      if (sq < nqs) kmeta[it] = *reinterpret_cast<const uint4*>(pm + (G * nqs + sq) * 16);
     }
   };
+  auto load_v_piece = [&](int t, int piece, uint4 (&dst)[kVRegs]) __attribute__((always_inline)) {
+    const uint8_t* p = vd + static_cast<int64_t>(t) * (kTile * 16 * VT) + 2048 * piece + 16 * lane;
+    dst[0] = *reinterpret_cast<const uint4*>(p);
+    dst[1] = *reinterpret_cast<const uint4*>(p + 1024);
+  };
+  auto load_v = [&](int t) __attribute__((always_inline)) {
+    if constexpr (kStream) load_v_piece(t, 0, vraw[0]);
+    else load_tile_side<VT>(vraw[0], vd, t, lane);
+    if constexpr (VT != 16) vmeta = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(t) * 1024 + lane * 16);
+  };
+#pragma unroll
+  for (int w = 0; w < NW; ++w) kw[w] = 0;
+  kmeta[0] = kmeta[1] = vmeta = make_uint4(0, 0, 0, 0);
   if (wave < ntiles) {
     load_k(wave);
-    load_v<VT>(rv, vd, wave, lane);
+    load_v(wave);
   }
 
-  float m_run = kNegBig, l_run = 0.f;     // running maximum in units of kKUnit * (raw q.k)
-  floatx4 acc[8], acc_off;
+  // ---- query operands per step (once per workgroup) ---------------------------------------------------------
+  for (int e = tid; e < n_steps * HS * 4; e += kWG) {
+    const int s = e / (HS * 4), hs = (e >> 2) % HS, hj = e & 3;
+    const int head = 4 * hs + hj;
+    float v[4];
 #pragma unroll
-  for (int nt = 0; nt < 8; ++nt) acc[nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-  acc_off = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < 4; ++k) {
+      const int c = ikp->slot_ch[4 * s + k];
+      v[k] = (c >= 0 && head < g) ? __uint_as_float(static_cast<uint32_t>(q[head * kHeadDim + c]) << 16) : 0.f;
+    }
+    uint2 out;
+    if (s < ns16) {   // raw bf16
+      out.x = (__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xFFFF0000u);
+      out.y = (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xFFFF0000u);
+    } else {
+      const int sq = s - ns16;
+      int b, k;   // tier of the step and its position inside its word
+      if (sq < e8 - e16) { b = 8; k = 0; }
+      else if (sq < (e8 - e16) + 2 * (e4 - e8)) { b = 4; k = (sq - (e8 - e16)) & 1; }
+      else { b = 2; k = (sq - (e8 - e16) - 2 * (e4 - e8)) & 3; }
+      const float f0 = ldexpf(1.0f, kQExp - field_fb(b, 2 * k)), f1 = ldexpf(1.0f, kQExp - field_fb(b, 2 * k + 1));
+      Pack4 o, r;
+      o.h[0] = static_cast<_Float16>(v[0] * f0); o.h[1] = static_cast<_Float16>(v[1] * f0);
+      o.h[2] = static_cast<_Float16>(v[2] * f1); o.h[3] = static_cast<_Float16>(v[3] * f1);
+      const float fr = static_cast<float>(1 << kQExp);
+#pragma unroll
+      for (int k2 = 0; k2 < 4; ++k2) r.h[k2] = static_cast<_Float16>(v[k2] * fr);
+      out = make_uint2(o.u[0], o.u[1]);
+      *reinterpret_cast<uint2*>(smem + plan.qraw + ((sq * HS + hs) * 4 + hj) * 8) = make_uint2(r.u[0], r.u[1]);
+    }
+    *reinterpret_cast<uint2*>(smem + plan.qpre + ((s * HS + hs) * 4 + hj) * 8) = out;
+  }
+  __syncthreads();
+
+  const float kappa = VT == 16 ? 1.0f : v_kappa<(VT == 16 ? 8 : VT)>(blk);
+  Run<HS> run;
+  run.init();
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
   for (int tile = wave; tile < ntiles; tile += kWaves) {
     const int next = tile + kWaves;
     const bool more = next < ntiles;
 
-    // ---- park the K tile and the metadata in LDS, then start the loads of the next tile ------------
+    // ---- scaled query of this tile's two token groups, and the bias sum_c m_c q_c --------------------------
+    float bias[HS];
+    {
+      float bp[HS][4];
 #pragma unroll
-    for (int i = 0; i < NK; ++i)
-      if (i * 1024 < kt_bytes) *reinterpret_cast<uint4*>(s_kbuf + i * 1024 + lane * 16) = kraw[i];
-    *reinterpret_cast<uint4*>(s_kmeta + lane * 16) = kmeta_r;
-    if constexpr (VT != 16) {
-      if (lane < 32) *reinterpret_cast<uint4*>(s_vmeta + lane * 16) = vmeta_r;
+      for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+        for (int h = 0; h < 4; ++h) bp[hs][h] = 0.f;
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        if (32 * it < nqs) {   // uniform
+          const int sq = (lane & 31) + 32 * it;
+          Pack4 sc, mo;
+          sc.u[0] = kmeta[it].x; sc.u[1] = kmeta[it].y;
+          mo.u[0] = kmeta[it].z; mo.u[1] = kmeta[it].w;
+          if (sq < nqs) {
+#pragma unroll
+            for (int hs = 0; hs < HS; ++hs) {
+              const uint4* qp = reinterpret_cast<const uint4*>(s_qpre + ((ns16 + sq) * HS + hs) * 32);
+              const uint4* qr = reinterpret_cast<const uint4*>(s_qraw + (sq * HS + hs) * 32);
+              const uint4 qa = qp[0], qb = qp[1], ra = qr[0], rb = qr[1];
+              const uint32_t qw[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
+              const uint32_t rw[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+              uint4* dst = reinterpret_cast<uint4*>(s_wtab + ((G * nqs + sq) * HS + hs) * 64);
+#pragma unroll
+              for (int h = 0; h < 4; ++h) {
+                Pack4 qv, rv, hi, lo;
+                qv.u[0] = qw[2 * h]; qv.u[1] = qw[2 * h + 1];
+                rv.u[0] = rw[2 * h]; rv.u[1] = rw[2 * h + 1];
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr) {
+                  hi.p[pr] = qv.p[pr] * sc.p[pr];
+                  lo.p[pr] = __builtin_elementwise_fma(qv.p[pr], sc.p[pr], -hi.p[pr]);
+                }
+                dst[h] = make_uint4(hi.u[0], hi.u[1], lo.u[0], lo.u[1]);
+                bp[hs][h] = __builtin_amdgcn_fdot2(rv.p[0], mo.p[0], bp[hs][h], false);
+                bp[hs][h] = __builtin_amdgcn_fdot2(rv.p[1], mo.p[1], bp[hs][h], false);
+              }
+            }
+          }
+        }
+      }
+      // lane (block, head j) ends with the sum over its token group's 32 lanes of bp[.][j]
+#pragma unroll
+      for (int hs = 0; hs < HS; ++hs) {
+        const bool o1 = (j & 1) != 0, o2 = (j & 2) != 0;
+        float k0 = o1 ? bp[hs][1] : bp[hs][0], s0 = o1 ? bp[hs][0] : bp[hs][1];
+        float k1 = o1 ? bp[hs][3] : bp[hs][2], s1 = o1 ? bp[hs][2] : bp[hs][3];
+        k0 += dpp_f32<0xB1>(s0);   // quad_perm [1, 0, 3, 2]
+        k1 += dpp_f32<0xB1>(s1);
+        float kk = o2 ? k1 : k0, ss = o2 ? k0 : k1;
+        kk += dpp_f32<0x4E>(ss);   // quad_perm [2, 3, 0, 1]
+        kk += dpp_f32<0x124>(kk);  // row_ror:4
+        kk += dpp_f32<0x128>(kk);  // row_ror:8
+        kk += __shfl_xor(kk, 16);
+        bias[hs] = kk;
+      }
     }
     wave_lds_sync();
-    if (more) load_k(next);
 
-    // ---- logits: x[mb][i] of token 16 mb + 4 quad + i and head l16, times kKUnit ---------------------
-    floatx4 xq0 = zero4, xq1 = zero4;       // quantized channels, in units of kKUnit
-    floatx4 xt0 = zero4, xt1 = zero4;       // 16-bit channels, true scale
-    floatx4 xb = zero4;                     // sum_c m_c q_c: the same in every row
-    int e = 0;
-#pragma unroll 1
-    for (int t = 0; t < 4; ++t) {
-      const int nq = ik.nq[t];
-      const int b = 16 >> t;
-      const int qslot0 = ik.slot_base[t] - ik.slot_base[1];
-#pragma unroll 1
-      for (int o = 0; 4 * o < nq; ++o, ++e) {
-        const int Q = 4 * o + quad;
-        const bool have = Q < nq;
-        const uint8_t* src = s_kbuf + ik.tier_base[t] + (have ? Q : 0) * 32 * b + l16 * 2 * b;
-        const uint8_t* qop = s_qop + e * 2048 + lane * 16;
-        if (t == 0) {
-          PackB8 a0, a1, bq;
-          a0.q = *reinterpret_cast<const uint4*>(src);
-          a1.q = *reinterpret_cast<const uint4*>(src + 16);
-          if (!have) a0.q = a1.q = make_uint4(0, 0, 0, 0);
-          bq.q = *reinterpret_cast<const uint4*>(qop);
-          xt0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0.h, bq.h, xt0, 0, 0, 0);
-          xt1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1.h, bq.h, xt1, 0, 0, 0);
-        } else {
-          Pack8 sc, of, qpre, qpl, bq, bql, a0, a1;
-          const int moff = (qslot0 + 8 * (have ? Q : 0)) * 2;
-          sc.q = *reinterpret_cast<const uint4*>(s_kmeta + moff);
-          of.q = *reinterpret_cast<const uint4*>(s_kmeta + (km_bytes >> 1) + moff);
-          if (!have) sc.q = of.q = make_uint4(0, 0, 0, 0);
-          qpre.q = *reinterpret_cast<const uint4*>(qop);
-          qpl.q = *reinterpret_cast<const uint4*>(qop + 1024);
-          // s_c q_c as an exact sum of two fp16 terms: the product of an 8-bit and an 11-bit significand
-          // is the rounded product plus a remainder that the fused multiply-add returns exactly
+    // ---- logits x[hs][i] of token 4 blk + i and head 4 hs + j, in units of kKUnit ----------------------------
+    float x[HS][4];
+    {
+      floatx4 a16[HS], aqh[HS], aql[HS];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            bq.p[j] = qpre.p[j] * sc.p[j];
-            bql.p[j] = __builtin_elementwise_fma(qpre.p[j], sc.p[j], -bq.p[j]);
-          }
-          if (t == 1) {
-            uint4 w = *reinterpret_cast<const uint4*>(src);
-            if (!have) w = make_uint4(0, 0, 0, 0);
-            const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+      for (int hs = 0; hs < HS; ++hs) a16[hs] = aqh[hs] = aql[hs] = zero4;
+      // The tier boundaries are laundered once per tile: as loop invariants the sixty-odd comparisons below would
+      // be evaluated ahead of the tile loop and kept in scalar registers (thousands of spills).
+      int t16 = e16, t8 = e8, t4 = e4, t2 = e2;
+      asm volatile("" : "+s"(t16), "+s"(t8), "+s"(t4), "+s"(t2));
+      // table address of word w's first step = tier base + w * (steps per word) * HS * 64
+      const uint8_t* wt = s_wtab + G * nqs * HS * 64 + j * 16;
+      const uint8_t* wt8 = wt - t16 * (HS * 64);
+      const uint8_t* wt4 = wt + ((t8 - t16) - 2 * t8) * (HS * 64);
+      const uint8_t* wt2 = wt + ((t8 - t16) + 2 * (t4 - t8) - 4 * t4) * (HS * 64);
+      auto qstep = [&](const Pack4& a, const uint8_t* o) __attribute__((always_inline)) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-              a0.u[p] = __builtin_amdgcn_perm(0u, ws[p], 0x0C020C00u);
-              a1.u[p] = __builtin_amdgcn_perm(0u, ws[p], 0x0C030C01u);
-            }
-          } else if (t == 2) {
-            uint2 w = *reinterpret_cast<const uint2*>(src);
-            if (!have) w = make_uint2(0, 0);
-            const uint32_t ws[2] = {w.x, w.y}, wh[2] = {w.x >> 8, w.y >> 8};
+        for (int hs = 0; hs < HS; ++hs) {
+          const uint4 b = *reinterpret_cast<const uint4*>(o + hs * 64);
+          Pack4 bh, bl;
+          bh.u[0] = b.x; bh.u[1] = b.y;
+          bl.u[0] = b.z; bl.u[1] = b.w;
+          aqh[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(a.h, bh.h, aqh[hs], 0, 0, 0);
+          aql[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(a.h, bl.h, aql[hs], 0, 0, 0);
+        }
+      };
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-              const uint32_t mask = 0x000F000Fu << (4 * (p & 1));
-              a0.u[p] = ws[p >> 1] & mask;
-              a1.u[p] = wh[p >> 1] & mask;
-            }
-          } else {
-            uint32_t w = *reinterpret_cast<const uint32_t*>(src);
-            if (!have) w = 0;
-            const uint32_t wh = w >> 8;
+      for (int w = 0; w < NW; ++w) {
+        if ((w & 1) == 0) __builtin_amdgcn_sched_barrier(0);   // keep the unpacking next to its use
+        if (w < t16) {
+          if ((w & 1) == 0) {   // a 16-bit step = two words = four bf16 (the 16-bit tier has an even word count)
+            // the two words pass through an empty asm: read as one 8-byte vector straight from kw[], the pair would
+            // keep the whole array out of registers (scalar replacement gives up on mixed-width accesses)
+            uint32_t lo = kw[w], hi = kw[w + 1 < NW ? w + 1 : w];
+            asm("" : "+v"(lo), "+v"(hi));
+            const short4v a = bf4(lo, hi);
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-              const uint32_t mask = 0x00030003u << (2 * p);
-              a0.u[p] = w & mask;
-              a1.u[p] = wh & mask;
+            for (int hs = 0; hs < HS; ++hs) {
+              const uint2 braw = *reinterpret_cast<const uint2*>(s_qpre + (((w >> 1) * HS + hs) * 4 + j) * 8);
+              a16[hs] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, bf4(braw.x, braw.y), a16[hs], 0, 0, 0);
             }
           }
-          xq0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, bq.h, xq0, 0, 0, 0);
-          xq1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, bq.h, xq1, 0, 0, 0);
-          xq0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, bql.h, xq0, 0, 0, 0);
-          xq1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, bql.h, xq1, 0, 0, 0);
-          xb = __builtin_amdgcn_mfma_f32_16x16x32_f16(of.h, qpl.h, xb, 0, 0, 0);
+        } else if (w < t8) {
+          Pack4 a;
+          a.u[0] = __builtin_amdgcn_perm(0u, kw[w], 0x0C020C00u);
+          a.u[1] = __builtin_amdgcn_perm(0u, kw[w], 0x0C030C01u);
+          qstep(a, wt8 + w * (HS * 64));
+        } else if (w < t4) {
+          const uint32_t c0 = kw[w], c1 = c0 >> 8;
+          const uint8_t* o = wt4 + 2 * w * (HS * 64);
+          Pack4 a;
+          a.u[0] = c0 & 0x000F000Fu; a.u[1] = c0 & 0x00F000F0u;
+          qstep(a, o);
+          a.u[0] = c1 & 0x000F000Fu; a.u[1] = c1 & 0x00F000F0u;
+          qstep(a, o + HS * 64);
+        } else if (w < t2) {
+          const uint32_t c0 = kw[w], c1 = c0 >> 6, c2 = c0 >> 12;
+          const uint8_t* o = wt2 + 4 * w * (HS * 64);
+          Pack4 a;
+          a.u[0] = c0 & 0x00030003u; a.u[1] = c0 & 0x000C000Cu;     // fields 0, 1
+          qstep(a, o);
+          a.u[0] = c0 & 0x00300030u; a.u[1] = c1 & 0x00030003u;     // fields 2, 3
+          qstep(a, o + HS * 64);
+          a.u[0] = c1 & 0x000C000Cu; a.u[1] = c1 & 0x00300030u;     // fields 4, 5
+          qstep(a, o + 2 * HS * 64);
+          a.u[0] = c2 & 0x00030003u; a.u[1] = c2 & 0x000C000Cu;     // fields 6, 7
+          qstep(a, o + 3 * HS * 64);
         }
       }
-    }
-    float x[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      x[0][i] = __builtin_fmaf(xt0[i] + xb[i], kKUnit, xq0[i]);
-      x[1][i] = __builtin_fmaf(xt1[i] + xb[i], kKUnit, xq1[i]);
-    }
-    if ((tile + 1) * kRowPad > rows) {   // padded rows of the last tile
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+      for (int hs = 0; hs < HS; ++hs)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (tile * kRowPad + 16 * mb + 4 * quad + i >= rows) x[mb][i] = -INFINITY;
+          x[hs][i] = __builtin_fmaf(a16[hs][i], kKUnit, aqh[hs][i] + aql[hs][i]) + bias[hs] * (1.0f / 16777216.0f);
     }
+    if (more) load_k(next);   // K registers are free again
 
-    // ---- online softmax (head l16; the four quads hold different tokens) ----------------------
-    float mt = fmaxf(fmaxf(fmaxf(x[0][0], x[0][1]), fmaxf(x[0][2], x[0][3])),
-                     fmaxf(fmaxf(x[1][0], x[1][1]), fmaxf(x[1][2], x[1][3])));
-    mt = fmaxf(mt, __shfl_xor(mt, 16));
-    mt = fmaxf(mt, __shfl_xor(mt, 32));
-    const float m_new = fmaxf(m_run, mt);
-    if (__any(m_new != m_run)) {
-      const float alpha = fast_exp2((m_run - m_new) * kXScale);
-      l_run *= alpha;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float ah = __shfl(alpha, 4 * quad + i);
-#pragma unroll
-        for (int nt = 0; nt < 8; ++nt) acc[nt][i] *= ah;
-        acc_off[i] *= ah;
-      }
-      m_run = m_new;
-    }
+    mask_rows<HS>(x, tile, rows, blk);
+    float p[HS][4];
+    softmax_tile<HS>(x, run, p);
 
-    // ---- P V: slot j = 4mb + i of this lane is token 16mb + 4quad + i ----------------
-    const float neg_mc = kPExp - m_run * kXScale;   // probabilities times 2^kPExp
-    float p[8];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        p[4 * mb + i] = fast_exp2(__builtin_fmaf(x[mb][i], kXScale, neg_mc));
-        l_run += p[4 * mb + i];
-      }
+    // ---- P V ------------------------------------------------------------------------------------------------
     if constexpr (VT == 16) {
-      PackB8 phi, plo;
-      union { bf16x8 h; __bf16 e[8]; } hi, lo;
+      // bf16 rows: p as two truncated bf16 terms (the remainder of the first is exact in fp32)
+      short4v phi[HS], plo[HS];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        hi.e[j] = static_cast<__bf16>(p[j]);
-        lo.e[j] = static_cast<__bf16>(p[j] - static_cast<float>(hi.e[j]));
-      }
-      phi.h = hi.h;
-      plo.h = lo.h;
+      for (int hs = 0; hs < HS; ++hs) {
+        uint32_t hb[4], lb[4];
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt) {
-        PackB8 bv;
-        bv.q = rv.o[nt];
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.h, bv.h, acc[nt], 0, 0, 0);
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.h, bv.h, acc[nt], 0, 0, 0);
-      }
-    } else {
-      Pack8 ph;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) ph.p[j] = half2v{static_cast<_Float16>(p[2 * j]), static_cast<_Float16>(p[2 * j + 1])};
-      const Shifted<VT> vs = pre_shift<VT>(rv.s);
-      Pack8 voff;
-      voff.q = *reinterpret_cast<const uint4*>(s_vmeta + 256 + (quad * 4 + (l16 & 3)) * 16);
-      if (l16 >= 4) voff.q = make_uint4(0, 0, 0, 0);
-      acc_off = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph.h, voff.h, acc_off, 0, 0, 0);
-#pragma unroll
-      for (int grp = 0; grp < 4; ++grp) {
-        Pack8 sv, pa;
-        sv.q = *reinterpret_cast<const uint4*>(s_vmeta + (quad * 4 + grp) * 16);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) pa.p[j] = ph.p[j] * sv.p[j];
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          const int nt = grp * 2 + h2;
-          const half8 bv = unpack_operand<VT>(rv.s, vs, nt);
-          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa.h, bv, acc[nt], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+          hb[i] = __float_as_uint(p[hs][i]) & 0xFFFF0000u;
+          lb[i] = __float_as_uint(p[hs][i] - __uint_as_float(hb[i]));
         }
+        phi[hs] = bf4((hb[0] >> 16) | hb[1], (hb[2] >> 16) | hb[3]);
+        plo[hs] = bf4((lb[0] >> 16) | (lb[1] & 0xFFFF0000u), (lb[2] >> 16) | (lb[3] & 0xFFFF0000u));
       }
+#define RDKV_PV16_STEP(G_, A_, X_, Y_)                                                                          \
+  {                                                                                                            \
+    const short4v b = bf4(X_, Y_);                                                                             \
+    _Pragma("unroll") for (int hs = 0; hs < HS; ++hs) {                                                        \
+      run.acc[hs][G_] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(phi[hs], b, run.acc[hs][G_], 3, A_, 0);         \
+      run.acc[hs][G_] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(plo[hs], b, run.acc[hs][G_], 3, A_, 0);         \
+    }                                                                                                          \
+  }
+      // piece P_ = half H_ of channel group G_: tokens 16 H_ .. 16 H_ + 15 of this lane's token half
+#define RDKV_PV16_PIECE(G_, H_)                                                                                \
+  {                                                                                                            \
+    constexpr int P_ = 2 * G_ + H_;                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                         \
+    if (P_ + 1 < kPieces) load_v_piece(tile, P_ + 1, vraw[(P_ + 1) & 1]);                                      \
+    else if (more) load_v_piece(next, 0, vraw[0]);                                                             \
+    const uint4(&v)[kVRegs] = vraw[P_ & 1];                                                                    \
+    RDKV_PV16_STEP(G_, 4 * H_ + 0, v[0].x, v[0].y) RDKV_PV16_STEP(G_, 4 * H_ + 1, v[0].z, v[0].w)              \
+    RDKV_PV16_STEP(G_, 4 * H_ + 2, v[1].x, v[1].y) RDKV_PV16_STEP(G_, 4 * H_ + 3, v[1].z, v[1].w)              \
+  }
+      RDKV_PV16_PIECE(0, 0) RDKV_PV16_PIECE(0, 1) RDKV_PV16_PIECE(1, 0) RDKV_PV16_PIECE(1, 1)
+      RDKV_PV16_PIECE(2, 0) RDKV_PV16_PIECE(2, 1) RDKV_PV16_PIECE(3, 0) RDKV_PV16_PIECE(3, 1)
+#undef RDKV_PV16_PIECE
+#undef RDKV_PV16_STEP
+    } else if constexpr (VT == 8) {
+      pv_tile_groups<8, HS>(
+          [&](auto gi, uint32_t (&gw)[1][8]) __attribute__((always_inline)) {
+            constexpr int P = decltype(gi)::value;
+            if (P + 1 < kPieces) load_v_piece(tile, P + 1, vraw[(P + 1) & 1]);
+            else if (more) load_v_piece(next, 0, vraw[0]);
+            const uint4(&v)[kVRegs] = vraw[P & 1];
+            gw[0][0] = v[0].x; gw[0][1] = v[0].y; gw[0][2] = v[0].z; gw[0][3] = v[0].w;
+            gw[0][4] = v[1].x; gw[0][5] = v[1].y; gw[0][6] = v[1].z; gw[0][7] = v[1].w;
+          },
+          vmeta, p, kappa, run);
+      if (more) vmeta = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(next) * 1024 + lane * 16);
+    } else {
+      pv_tile<VT, HS>(vraw[0], vmeta, p, kappa, run);
+      if (more) load_v(next);   // V registers are free again
     }
-    __builtin_amdgcn_wave_barrier();   // all reads of the LDS buffers are issued before they are overwritten
-    if (more) load_v<VT>(rv, vd, next, lane);
   }
 
-  // ---- merge the 4 wavefronts; acc[nt][i] is head 4quad+i, channel 16nt + l16 -----------------
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  if (quad == 0) {
-    s_ml[(wave * 16 + l16) * 2] = m_run * kXScale - kPExp;   // log2 domain from here on
-    s_ml[(wave * 16 + l16) * 2 + 1] = l_run;
-  }
-  __syncthreads();
-  float f_own[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int h = 4 * quad + i;
-    float mm = kNegBig;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[(w * 16 + h) * 2]);
-    f_own[i] = fast_exp2(s_ml[(wave * 16 + h) * 2] - mm);
-  }
-  if constexpr (VT != 16) {
-#pragma unroll
-    for (int grp = 0; grp < 4; ++grp)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float o = __shfl(acc_off[i], quad * 16 + grp);
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          const int nt = 2 * grp + h2;
-          const float unit = 16777216.0f / static_cast<float>(1 << field_bit<VT == 16 ? 8 : VT>(nt));
-          acc[nt][i] = __builtin_fmaf(acc[nt][i], unit, o);
-        }
-      }
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int h = 4 * quad + i;
-    if (h < g) {
-#pragma unroll
-      for (int nt = 0; nt < 8; ++nt) s_acc[(wave * g + h) * kHeadDim + nt * 16 + l16] = acc[nt][i] * f_own[i];
-    }
-  }
-  __syncthreads();
-  for (int idx = tid; idx < g * kHeadDim; idx += kWG) {
-    float v = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) v += s_acc[w * g * kHeadDim + idx];
-    part_acc[idx] = v;
-  }
-  if (tid < g) {
-    float mm = kNegBig;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[(w * 16 + tid) * 2]);
-    float ll = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) ll += s_ml[(w * 16 + tid) * 2 + 1] * fast_exp2(s_ml[(w * 16 + tid) * 2] - mm);
-    part_ml[tid * 2] = mm;
-    part_ml[tid * 2 + 1] = ll;
-  }
+  finish_chunk<HS, true>(run, VT == 16 ? 1.0f : 16777216.0f, g, reinterpret_cast<float*>(smem),
+                         reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2, part_acc, part_ml);
 }
 
-template <int NK>
-__global__ __launch_bounds__(kWG, 2) void decode_mixed_kernel(const Chunk* __restrict__ chunks,
-                                                             const uint8_t* __restrict__ arena,
-                                                             const ItemK* __restrict__ items_k,
-                                                             const uint16_t* __restrict__ q, float* part_acc,
-                                                             float* part_ml, int hq, int hkv) {
+template <int NW, int HS>
+__global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mixed_kernel(
+    const Chunk* __restrict__ chunks, const uint8_t* __restrict__ arena, const ItemK* __restrict__ items_k,
+    const uint16_t* __restrict__ q, float* part_acc, float* part_ml, int hq, int hkv, int lds_steps,
+    int lds_qsteps) {
   extern __shared__ __align__(16) uint8_t smem[];
-  // LDS: item layout | query rows (g x 128 bf16) | query operands (kMaxOps x 2 KiB) | per wavefront K tile, K and
-  // V metadata | running maxima and sums | accumulators of the 4 wavefronts
   const Chunk ch = chunks[blockIdx.x];
   const int g = hq / hkv;
   const int seq = ch.item / hkv, head = ch.item % hkv;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int quad = lane >> 4, l16 = lane & 15;
-  ItemK& ik = *reinterpret_cast<ItemK*>(smem);
-  uint16_t* s_qrow = reinterpret_cast<uint16_t*>(smem + kItemKBytes);
-  uint8_t* s_qop = smem + kItemKBytes + 8 * kHeadDim * 2;
-  uint8_t* s_waves = s_qop + kMaxOps * 2048;
-  constexpr int kWaveBytes = NK * 1024 + kKMetaBytes + kVMetaBytes;
-  float* s_ml = reinterpret_cast<float*>(s_waves + kWaves * kWaveBytes);
-  float* s_acc = s_ml + kWaves * 16 * 2;
-
-  for (int i = tid; i < static_cast<int>(sizeof(ItemK) / 4); i += kWG)
-    reinterpret_cast<uint32_t*>(smem)[i] = reinterpret_cast<const uint32_t*>(items_k + ch.item)[i];
   const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * g) * kHeadDim;
-  for (int i = tid; i < g * kHeadDim; i += kWG) s_qrow[i] = qp[i];
-  __syncthreads();
-
-  // query operands in sorted-channel order: lane (head l16, quad) of operand e holds the 8 slots of its quad.
-  // Quantized tiers: slot pair p carries 2^(b (p % (8/b))) from its field position, undone here (times 2^kQExp).
-  {
-    int e = 0;
-    for (int t = 0; t < 4; ++t) {
-      const int nq = ik.nq[t], b = 16 >> t;
-      for (int o = 0; 4 * o < nq; ++o, ++e) {
-        if ((e & 3) != wave) continue;
-        const int Q = 4 * o + quad;
-        uint16_t raw[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int c = Q < nq ? ik.slot_ch[ik.slot_base[t] + 8 * Q + j] : -1;
-          raw[j] = (c >= 0 && l16 < g) ? s_qrow[l16 * kHeadDim + c] : uint16_t(0);
-        }
-        uint8_t* dst = s_qop + e * 2048 + lane * 16;
-        if (t == 0) {
-          uint4 v;
-          v.x = raw[0] | (static_cast<uint32_t>(raw[1]) << 16);
-          v.y = raw[2] | (static_cast<uint32_t>(raw[3]) << 16);
-          v.z = raw[4] | (static_cast<uint32_t>(raw[5]) << 16);
-          v.w = raw[6] | (static_cast<uint32_t>(raw[7]) << 16);
-          *reinterpret_cast<uint4*>(dst) = v;
-        } else {
-          half8 pre, plain;
-          const int P = 8 / b;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float v = __uint_as_float(static_cast<uint32_t>(raw[j]) << 16);
-            const int ex = kQExp - b * ((j >> 1) % P);
-            plain[j] = static_cast<_Float16>(v);
-            pre[j] = static_cast<_Float16>(ldexpf(v, ex));
-          }
-          *reinterpret_cast<half8*>(dst) = pre;
-          *reinterpret_cast<half8*>(dst + 1024) = plain;
-        }
-      }
-    }
-  }
-  __syncthreads();
-
   float* pa = part_acc + static_cast<int64_t>(ch.slot) * g * kHeadDim;
   float* pm = part_ml + static_cast<int64_t>(ch.slot) * g * 2;
-  const uint8_t* kd = arena + ch.k_data;
-  const uint8_t* km = arena + ch.k_meta;
-  const uint8_t* vd = arena + ch.v_data;
-  const uint8_t* vm = arena + ch.v_meta;
-  uint8_t* s_wave = s_waves + wave * kWaveBytes;
+  const ItemK* ikp = items_k + ch.item;
   switch (ch.tier) {
-    case 16: process_mixed<16, NK>(ik, kd, km, vd, vm, ch.rows, g, pa, pm, s_qop, s_wave, s_ml, s_acc); break;
-    case 8: process_mixed<8, NK>(ik, kd, km, vd, vm, ch.rows, g, pa, pm, s_qop, s_wave, s_ml, s_acc); break;
-    case 4: process_mixed<4, NK>(ik, kd, km, vd, vm, ch.rows, g, pa, pm, s_qop, s_wave, s_ml, s_acc); break;
-    default: process_mixed<2, NK>(ik, kd, km, vd, vm, ch.rows, g, pa, pm, s_qop, s_wave, s_ml, s_acc); break;
+    case 16: process_mixed<16, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
+    case 8: process_mixed<8, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
+    case 4: process_mixed<4, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
+    default: process_mixed<2, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
   }
+}
+
+template <int NW, int HS>
+hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int lds_steps,
+                      int lds_qsteps, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv,
+                      hipStream_t st) {
+  const size_t lds = static_cast<size_t>(LdsPlan(lds_steps, lds_qsteps, HS, hq / hkv).total);
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_mixed_kernel<NW, HS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((decode_mixed_kernel<NW, HS>), dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, items_k, q,
+                     part_acc, part_ml, hq, hkv, lds_steps, lds_qsteps);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                               int max_kt_bytes, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv,
-                               hipStream_t st) {
+                               int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
+                               float* part_ml, int hq, int hkv, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
-  const int g = hq / hkv;
-  const int nk = max_kt_bytes <= 2048 ? 2 : max_kt_bytes <= 4096 ? 4 : 8;
-  if (max_kt_bytes > 8192) return hipErrorInvalidValue;
-  const size_t lds = kItemKBytes + 8 * kHeadDim * 2 + kMaxOps * 2048 +
-                     static_cast<size_t>(kWaves) * (nk * 1024 + kKMetaBytes + kVMetaBytes) +
-                     kWaves * 16 * 2 * sizeof(float) + static_cast<size_t>(kWaves) * g * kHeadDim * sizeof(float);
-  dim3 grid(n_chunks), block(kWG);
-  switch (nk) {
-    case 2: hipLaunchKernelGGL(decode_mixed_kernel<2>, grid, block, lds, st, chunks, arena, items_k, q, part_acc, part_ml, hq, hkv); break;
-    case 4: hipLaunchKernelGGL(decode_mixed_kernel<4>, grid, block, lds, st, chunks, arena, items_k, q, part_acc, part_ml, hq, hkv); break;
-    default: hipLaunchKernelGGL(decode_mixed_kernel<8>, grid, block, lds, st, chunks, arena, items_k, q, part_acc, part_ml, hq, hkv); break;
+  const int hs = hq / hkv > 4 ? 2 : 1;
+#define RDKV_MIXED_LAUNCH(NW_, HS_)                                                                           \
+  return launch_one<NW_, HS_>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, part_acc, part_ml, hq, \
+                              hkv, st)
+  if (hs == 1) {
+    if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 1);
+    if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 1);
+    RDKV_MIXED_LAUNCH(64, 1);
   }
-  return hipGetLastError();
+  if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 2);
+  if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 2);
+  RDKV_MIXED_LAUNCH(64, 2);
+#undef RDKV_MIXED_LAUNCH
 }
 
 }  // namespace rdkv

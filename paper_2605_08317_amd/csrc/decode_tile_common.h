@@ -1,25 +1,32 @@
-// Device helpers shared by the tile decode kernels: operand types, the subnormal-fp16 unpack of packed codes,
-// tile loads and the wavefront-level LDS fence.
+// Device helpers shared by the tile decode kernels (token-wise and mixed mode): operand types, the subnormal-fp16
+// unpack of packed codes, tile loads, and the stages both kernels run after the logits of a 64-token tile are
+// known: online softmax, P V over a token-wise V tile, and the end-of-chunk merge of a workgroup's wavefronts.
+//
+// Lane roles (v_mfma_f32_4x4x4_16B_f16, sixteen independent 4x4x4 blocks, lane = 4 * block + x):
+//   logits    lane (block b, x = head j) holds tokens 4b..4b+3 of the tile in its four result registers
+//   P V       A = p * scale of lane (b, head j) for its tokens, broadcast from block a to blocks 0..7 and from
+//             block 8 + a to blocks 8..15 (cbsz = 3);  B = V codes: lane = (token half, channel of the group),
+//             4 tokens per step;  D: lane holds 4 heads of one channel, summed over its token half.
 #pragma once
 #include "rdkv_internal.h"
 
 namespace rdkv {
 namespace tile {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWG = 256;
 constexpr int kWaves = 4;
-constexpr int kQBytes = 9 * 64 * 16;   // LDS copy of the query operands: 8 x (m-block, group) and the group sums
+constexpr int kTile = 64;   // tokens per tile
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLogitScale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 
 // Codes enter the matrix cores as fp16 subnormals: a 16-bit pattern with a zero exponent field and the code in
 // mantissa bits [fb, fb + b) is the number code * 2^fb * 2^-24 exactly, so one AND per pair of codes is the whole
-// conversion.  The layout gives all eight slots of an operand the same fb; the query operand of the K product is
-// pre-multiplied by 2^(kQExp - fb) and the V accumulators are rescaled once per chunk.
+// conversion.  The query operand of the K product is pre-multiplied by 2^(kQExp - fb); on the V side the power of
+// two goes into p (per lane) and the accumulators are rescaled once per chunk.
 constexpr int kQExp = 4;                                   // keeps the scaled query clear of fp16 underflow
 constexpr float kKUnit = 1.0f / static_cast<float>(1 << (24 - kQExp));   // K partial products come out times this
 constexpr float kXScale = kLogitScale * static_cast<float>(1 << (24 - kQExp));
@@ -32,81 +39,301 @@ constexpr float kPExp = 6.0f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-union Pack8 {
-  half8 h;
-  half2v p[4];
-  uint32_t u[4];
-  uint4 q;
+union Pack4 {
+  half4 h;
+  half2v p[2];
+  uint32_t u[2];
 };
 
-// bit offset (inside a 16-bit half, after the pre-shift) of the field that operand o reads
-template <int TIER>
-__host__ __device__ constexpr int field_bit(int o) {
-  return TIER == 8 ? 0 : TIER == 4 ? 4 * (o & 1) : (o < 5 ? 2 * o : 2 * (o - 5));
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
 }
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
+}
+// reduction over the 16 lanes that hold the same head (lane % 4): lanes 4 apart inside a row of 16, then the rows
+__device__ __forceinline__ float head_max(float v) {
+  v = fmaxf(v, dpp_f32<0x124>(v));   // row_ror:4
+  v = fmaxf(v, dpp_f32<0x128>(v));   // row_ror:8
+  v = fmaxf(v, __shfl_xor(v, 16));
+  v = fmaxf(v, __shfl_xor(v, 32));
+  return v;
+}
+__device__ __forceinline__ float head_sum(float v) {
+  v += dpp_f32<0x124>(v);
+  v += dpp_f32<0x128>(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+// value held by lane i of this lane's quad
+template <int I>
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t v) { return dpp_u32<I * 0x55>(v); }
 
-// Raw bytes of one tile side held by a lane, plus the right-shifted copy that brings the fields lying in the exponent
-// bits of a half down into its mantissa bits (2-bit: fields 5..7, shift 10; 4-bit: nibbles 2 and 3, shift 8).
+// Field position of step s inside a 16-bit half, which right-shifted copy of the word it is read from, and the bit
+// offset that remains after that shift (the code then reads as code * 2^fb * 2^-24).
 template <int TIER>
-struct Side {
-  uint4 raw[TIER / 2];
-};
-template <int TIER>
-struct Shifted {
-  uint4 s[TIER == 8 ? 1 : TIER / 2];
-};
-
-template <int TIER>
-__device__ __forceinline__ Shifted<TIER> pre_shift(const Side<TIER>& a) {
-  Shifted<TIER> r;
-  if constexpr (TIER != 8) {
-    constexpr int kSh = TIER == 2 ? 10 : 8;
-#pragma unroll
-    for (int i = 0; i < TIER / 2; ++i)
-      r.s[i] = make_uint4(a.raw[i].x >> kSh, a.raw[i].y >> kSh, a.raw[i].z >> kSh, a.raw[i].w >> kSh);
+struct Step {
+  static constexpr int F = 16 / TIER;                                     // fields per half
+  __host__ __device__ static constexpr int pair(int s) { return s / F; }
+  __host__ __device__ static constexpr int field(int s) { return s % F; }
+  __host__ __device__ static constexpr int copy(int s) {
+    return TIER == 8 ? 0 : TIER == 4 ? field(s) / 2 : field(s) / 3;
   }
-  return r;
-}
+  __host__ __device__ static constexpr int fb(int s) {
+    return TIER == 8 ? 0 : TIER == 4 ? 4 * (field(s) % 2) : 2 * (field(s) % 3);
+  }
+  static constexpr int kCopies = TIER == 8 ? 1 : TIER == 4 ? 2 : 3;
+  static constexpr int kShift = TIER == 4 ? 8 : 6;                        // right shift between copies
+};
 
-// operand o (0..7) of this lane: eight codes as fp16 subnormals
+// The 4 codes of step s of a group whose words are gw[0..TIER): two words, fp16 subnormals in both halves.
 template <int TIER>
-__device__ __forceinline__ half8 unpack_operand(const Side<TIER>& a, const Shifted<TIER>& sh, int o) {
-  Pack8 r;
+__device__ __forceinline__ half4 step_operand(const uint32_t (&gw)[Step<TIER>::kCopies][TIER], int s) {
+  using S = Step<TIER>;
+  Pack4 r;
+  const int p = S::pair(s);
   if constexpr (TIER == 8) {
-    const uint4 c = a.raw[o >> 1];
-    // bytes (0, 2) of every word for an even operand, (1, 3) for an odd one, zero-extended to 16 bits each.
-    // Both go through the byte permute: mixing it with a plain AND of the same register was seen to be
-    // scheduled with the AND done in place before the permute read its source.
-    const uint32_t sel = (o & 1) ? 0x0C030C01u : 0x0C020C00u;
-    r.u[0] = __builtin_amdgcn_perm(0u, c.x, sel);
-    r.u[1] = __builtin_amdgcn_perm(0u, c.y, sel);
-    r.u[2] = __builtin_amdgcn_perm(0u, c.z, sel);
-    r.u[3] = __builtin_amdgcn_perm(0u, c.w, sel);
-  } else if constexpr (TIER == 4) {
-    const int n = o & 3;
-    const uint4 c = n < 2 ? a.raw[o >> 2] : sh.s[o >> 2];
-    const uint32_t mask = 0x000F000Fu << (4 * (n & 1));
-    r.q = make_uint4(c.x & mask, c.y & mask, c.z & mask, c.w & mask);
+    // byte f of each half, zero-extended: both selections go through the byte permute (mixing it with a plain
+    // AND of the same register was seen to be scheduled with the AND done in place before the permute read it)
+    const uint32_t sel = S::field(s) ? 0x0C030C01u : 0x0C020C00u;
+    r.u[0] = __builtin_amdgcn_perm(0u, gw[0][2 * p], sel);
+    r.u[1] = __builtin_amdgcn_perm(0u, gw[0][2 * p + 1], sel);
   } else {
-    const uint4 c = o < 5 ? a.raw[0] : sh.s[0];
-    const uint32_t mask = 0x00030003u << field_bit<2>(o);
-    r.q = make_uint4(c.x & mask, c.y & mask, c.z & mask, c.w & mask);
+    const uint32_t mask = (TIER == 4 ? 0x000F000Fu : 0x00030003u) << S::fb(s);
+    r.u[0] = gw[S::copy(s)][2 * p] & mask;
+    r.u[1] = gw[S::copy(s)][2 * p + 1] & mask;
   }
   return r.h;
 }
 
 template <int TIER>
-__device__ __forceinline__ void load_side(Side<TIER>& r, const uint8_t* __restrict__ data, int tile, int lane) {
-  constexpr int kTileBytes = kRowPad * kHeadDim * TIER / 8;
-  const uint8_t* p = data + static_cast<int64_t>(tile) * kTileBytes + lane * 16;
+__device__ __forceinline__ void group_words(const uint4 (&raw)[TIER], int grp, uint32_t (&gw)[Step<TIER>::kCopies][TIER]) {
+  using S = Step<TIER>;
 #pragma unroll
-  for (int i = 0; i < TIER / 2; ++i) r.raw[i] = *reinterpret_cast<const uint4*>(p + i * 1024);
+  for (int w = 0; w < TIER; ++w) {
+    const int W = grp * TIER + w;
+    const uint4 c = raw[W >> 2];
+    const uint32_t v = (W & 3) == 0 ? c.x : (W & 3) == 1 ? c.y : (W & 3) == 2 ? c.z : c.w;
+    gw[0][w] = v;
+#pragma unroll
+    for (int k = 1; k < S::kCopies; ++k) gw[k][w] = v >> (k * S::kShift);
+  }
+}
+
+template <int TIER>
+__device__ __forceinline__ void load_tile_side(uint4 (&raw)[TIER], const uint8_t* __restrict__ data, int tile, int lane) {
+  const uint8_t* p = data + static_cast<int64_t>(tile) * (kTile * 16 * TIER) + lane * 16;
+#pragma unroll
+  for (int i = 0; i < TIER; ++i) raw[i] = *reinterpret_cast<const uint4*>(p + i * 1024);
 }
 
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Running state of one wavefront over its tiles of a chunk: per head set the running maximum and sum of the
+// online softmax (lanes of head j), and the output accumulators acc[hs][grp][i] (head 4 hs + i, channel
+// 32 grp + lane % 32, summed over this lane's token half) with the offset sums off[hs][grp] = sum_t p m.
+template <int HS>
+struct Run {
+  float m[HS], l[HS];
+  floatx4 acc[HS][4];
+  float off[HS][4];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs) {
+      m[hs] = kNegBig;
+      l[hs] = 0.f;
+#pragma unroll
+      for (int grp = 0; grp < 4; ++grp) {
+        acc[hs][grp] = floatx4{0.f, 0.f, 0.f, 0.f};
+        off[hs][grp] = 0.f;
+      }
+    }
+  }
+};
+
+// Padded rows of a chunk's last tile take no part in the softmax.
+template <int HS>
+__device__ __forceinline__ void mask_rows(float (&x)[HS][4], int tile, int rows, int blk) {
+  if ((tile + 1) * kTile > rows) {
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (tile * kTile + 4 * blk + i >= rows) x[hs][i] = -INFINITY;
+  }
+}
+
+// Online softmax per head over the logits x (in units of 1 / kXScale) of a tile; probabilities carried times 2^kPExp.
+template <int HS>
+__device__ __forceinline__ void softmax_tile(const float (&x)[HS][4], Run<HS>& run, float (&p)[HS][4]) {
+#pragma unroll
+  for (int hs = 0; hs < HS; ++hs) {
+    const float mt = head_max(fmaxf(fmaxf(x[hs][0], x[hs][1]), fmaxf(x[hs][2], x[hs][3])));
+    const float m_new = fmaxf(run.m[hs], mt);
+    if (__any(m_new != run.m[hs])) {
+      const float alpha = fast_exp2((run.m[hs] - m_new) * kXScale);
+      run.l[hs] *= alpha;
+      const uint32_t au = __builtin_bit_cast(uint32_t, alpha);
+      const float ah[4] = {__builtin_bit_cast(float, quad_bcast<0>(au)), __builtin_bit_cast(float, quad_bcast<1>(au)),
+                           __builtin_bit_cast(float, quad_bcast<2>(au)), __builtin_bit_cast(float, quad_bcast<3>(au))};
+#pragma unroll
+      for (int grp = 0; grp < 4; ++grp) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) run.acc[hs][grp][i] *= ah[i];   // acc row i is head i
+        run.off[hs][grp] *= alpha;
+      }
+      run.m[hs] = m_new;
+    }
+    const float neg_mc = kPExp - run.m[hs] * kXScale;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[hs][i] = fast_exp2(__builtin_fmaf(x[hs][i], kXScale, neg_mc));
+      run.l[hs] += p[hs][i];
+    }
+  }
+}
+
+// 2^-fb of the field this lane's block is read from on the V side (block a = blk % 8 feeds step a)
+template <int TIER>
+__device__ __forceinline__ float v_kappa(int blk) {
+  float kappa = 1.0f;
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+    if ((blk & 7) == a) kappa = 1.0f / static_cast<float>(1 << Step<TIER>::fb(a));
+  return kappa;
+}
+
+template <int G>
+struct GroupIndex {
+  static constexpr int value = G;
+};
+
+// P V over a token-wise V tile of tier TIER (8, 4, 2).  fill_gw(GroupIndex<G>, gw) delivers the code words of
+// channel group G (and their shifted copies); vmeta = group (lane % 4)'s scales (x, y) and offsets (z, w) of
+// tokens 4 blk + 0..3.
+template <int TIER, int HS, class FillGw>
+__device__ __forceinline__ void pv_tile_groups(FillGw&& fill_gw, const uint4& vmeta, const float (&p)[HS][4],
+                                               float kappa, Run<HS>& run) {
+  using S = Step<TIER>;
+  Pack4 ph[HS];
+#pragma unroll
+  for (int hs = 0; hs < HS; ++hs) {
+    ph[hs].p[0] = half2v{static_cast<_Float16>(p[hs][0] * kappa), static_cast<_Float16>(p[hs][1] * kappa)};
+    ph[hs].p[1] = half2v{static_cast<_Float16>(p[hs][2] * kappa), static_cast<_Float16>(p[hs][3] * kappa)};
+  }
+#define RDKV_PV_GROUP(G_)                                                                                      \
+  {                                                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                         \
+    /* V metadata of tokens 4 blk + 0..3: lane G_ of the quad holds group G_'s scales (x, y), offsets (z, w) */ \
+    Pack4 sv, ov, pa[HS];                                                                                      \
+    sv.u[0] = quad_bcast<G_>(vmeta.x); sv.u[1] = quad_bcast<G_>(vmeta.y);                                      \
+    ov.u[0] = quad_bcast<G_>(vmeta.z); ov.u[1] = quad_bcast<G_>(vmeta.w);                                      \
+    _Pragma("unroll") for (int hs = 0; hs < HS; ++hs) {                                                        \
+      pa[hs].p[0] = ph[hs].p[0] * sv.p[0];                                                                     \
+      pa[hs].p[1] = ph[hs].p[1] * sv.p[1];                                                                     \
+      float o = run.off[hs][G_];                                                                               \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) o = __builtin_fmaf(p[hs][i], static_cast<float>(ov.h[i]), o); \
+      run.off[hs][G_] = o;                                                                                     \
+    }                                                                                                          \
+    uint32_t gw[S::kCopies][TIER];                                                                             \
+    fill_gw(GroupIndex<G_>{}, gw);                                                                             \
+    RDKV_PV_STEP(G_, 0) RDKV_PV_STEP(G_, 1) RDKV_PV_STEP(G_, 2) RDKV_PV_STEP(G_, 3)                            \
+    RDKV_PV_STEP(G_, 4) RDKV_PV_STEP(G_, 5) RDKV_PV_STEP(G_, 6) RDKV_PV_STEP(G_, 7)                            \
+  }
+#define RDKV_PV_STEP(G_, A_)                                                                                   \
+  {                                                                                                            \
+    const half4 b = step_operand<TIER>(gw, A_);                                                                \
+    _Pragma("unroll") for (int hs = 0; hs < HS; ++hs)                                                          \
+        run.acc[hs][G_] = __builtin_amdgcn_mfma_f32_4x4x4f16(pa[hs].h, b, run.acc[hs][G_], 3, A_, 0);          \
+  }
+  RDKV_PV_GROUP(0) RDKV_PV_GROUP(1) RDKV_PV_GROUP(2) RDKV_PV_GROUP(3)
+#undef RDKV_PV_STEP
+#undef RDKV_PV_GROUP
+}
+
+// the same with the whole tile's code words in registers
+template <int TIER, int HS>
+__device__ __forceinline__ void pv_tile(const uint4 (&vraw)[TIER], const uint4& vmeta, const float (&p)[HS][4],
+                                        float kappa, Run<HS>& run) {
+  pv_tile_groups<TIER, HS>(
+      [&](auto gi, uint32_t (&gw)[Step<TIER>::kCopies][TIER]) __attribute__((always_inline)) {
+        group_words<TIER>(vraw, decltype(gi)::value, gw);
+      },
+      vmeta, p, kappa, run);
+}
+
+// End of a chunk: scale the accumulators back (acc_scale = 2^24 where the V codes entered as fp16 subnormals),
+// add the offset sums, merge the workgroup's four wavefronts through LDS and write the chunk's partial result.
+// s_ml: [kWaves][4 HS heads][m, l] floats; s_acc: [2 kWaves streams][g][128] floats.  ALIAS: the two areas overlap
+// LDS that the tile loop used, so a barrier separates the two uses.
+template <int HS, bool ALIAS>
+__device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, int g, float* s_ml, float* s_acc,
+                                             float* __restrict__ part_acc, float* __restrict__ part_ml) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int th = lane >> 5, cl = lane & 31;
+#pragma unroll
+  for (int hs = 0; hs < HS; ++hs) {
+    run.l[hs] = head_sum(run.l[hs]);
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) {
+      const uint32_t ou = __builtin_bit_cast(uint32_t, head_sum(run.off[hs][grp]));   // lanes of head j hold sum_t p m
+      const float oh[4] = {__builtin_bit_cast(float, quad_bcast<0>(ou)), __builtin_bit_cast(float, quad_bcast<1>(ou)),
+                           __builtin_bit_cast(float, quad_bcast<2>(ou)), __builtin_bit_cast(float, quad_bcast<3>(ou))};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        run.acc[hs][grp][i] = __builtin_fmaf(run.acc[hs][grp][i], acc_scale, th == 0 ? oh[i] : 0.f);
+    }
+  }
+  if constexpr (ALIAS) __syncthreads();
+#pragma unroll
+  for (int hs = 0; hs < HS; ++hs)
+    if (lane < 4) {
+      s_ml[((wave * HS + hs) * 4 + lane) * 2] = run.m[hs] * kXScale - kPExp;   // log2 domain from here on
+      s_ml[((wave * HS + hs) * 4 + lane) * 2 + 1] = run.l[hs];
+    }
+  __syncthreads();
+#pragma unroll
+  for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int head = 4 * hs + i;
+      float mm = kNegBig;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
+      const float f = fast_exp2(s_ml[((wave * HS + hs) * 4 + i) * 2] - mm);
+      if (head < g) {
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp)
+          s_acc[((wave * 2 + th) * g + head) * kHeadDim + 32 * grp + cl] = run.acc[hs][grp][i] * f;
+      }
+    }
+  __syncthreads();
+  for (int idx = tid; idx < g * kHeadDim; idx += kWG) {
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < 2 * kWaves; ++w) v += s_acc[w * g * kHeadDim + idx];
+    part_acc[idx] = v;
+  }
+  if (tid < g) {
+    const int hs = tid >> 2, i = tid & 3;
+    float mm = kNegBig;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
+    float ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+      ll += s_ml[((w * HS + hs) * 4 + i) * 2 + 1] * fast_exp2(s_ml[((w * HS + hs) * 4 + i) * 2] - mm);
+    part_ml[tid * 2] = mm;
+    part_ml[tid * 2 + 1] = ll;
+  }
 }
 
 }  // namespace tile

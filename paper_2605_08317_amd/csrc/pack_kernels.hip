@@ -154,143 +154,7 @@ __global__ __launch_bounds__(256) void copy_rows_kernel(PackArgs a) {
   }
 }
 
-// (row, channel) of the code held by (lane, operand o, slot s) of a tile; see the layout notes below
-__device__ __forceinline__ void tile_rc(bool is_v, int lane, int o, int s, int* r, int* c) {
-  const int quad = lane >> 4, l16 = lane & 15;
-  if (!is_v) {
-    *r = 16 * (o >> 2) + l16;
-    *c = 32 * (o & 3) + 8 * quad + s;
-  } else {
-    *r = 16 * (s >> 2) + 4 * quad + (s & 3);
-    *c = 16 * o + l16;
-  }
-}
-
-// Quantized tiers: one workgroup = one tile of 32 kept rows, K and V.
-//
-// Tile layout (what the decode kernel's MFMA operands want).  Lanes are indexed lane = 16*quad + l16; every lane
-// owns eight 8-slot operands:
-//   K: operand o = 4*(r/16) + c/32, lane = 16*((c/8)%4) + r%16, slot s = c%8
-//   V: operand o = c/16,            lane = 16*((r%16)/4) + c%16, slot s = 4*(r/16) + r%4
-// The lane's data is a run of 32-bit words, word W stored at 1024*(W/4) + 16*lane + 4*(W%4); slot s picks the word
-// and its 16-bit half, the operand picks the field, so one AND isolates an operand's codes in both halves:
-//   8-bit: W = 4*(o/2) + s/2, bit 16*(s%2) + 8*(o%2)
-//   4-bit: W = 4*(o/4) + s/2, bit 16*(s%2) + 4*(o%4)
-//   2-bit: W = s/2,           bit 16*(s%2) + 2*o
-// Metadata tile = 128 fp16 scales then 128 fp16 offsets; with mb = r/16, quad = (r%16)/4, i = r%4, j = 4mb+i:
-//   K scale ((quad*2+mb)*4+grp)*4+i, K offset 128 + 4r + grp; V scale and offset (128 +) (quad*4+grp)*8 + j.
-template <int BITS>
-__global__ __launch_bounds__(256) void quant_pack_tile_kernel(PackArgs a) {
-  constexpr int kRowStride = kHeadDim + 8;                 // bf16 elements; 272-byte rows
-  __shared__ __align__(16) uint16_t s_rows[2][kRowPad][kRowStride];
-  __shared__ __align__(16) uint8_t s_codes[2][kRowPad][kHeadDim];
-  const int item = blockIdx.y;
-  const int n = a.counts[item * 4 + a.ti];
-  const int r0 = blockIdx.x * kRowPad;
-  if (r0 >= n) return;
-  const int valid = min(kRowPad, n - r0);
-  const int tid = threadIdx.x;
-  const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
-
-  {  // gather the tile's rows: 8 threads per row, 32 bytes of K and of V each
-    const int row = tid >> 3, part = tid & 7;
-    uint4 kv[2][2];
-#pragma unroll
-    for (int w = 0; w < 2; ++w) kv[w][0] = kv[w][1] = make_uint4(0, 0, 0, 0);
-    if (row < valid) {
-      const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + r0 + row];
-      const int64_t src = (a.item_row_off[item] + pos) * kHeadDim + part * 16;
-#pragma unroll
-      for (int w = 0; w < 2; ++w) {
-        const uint4* p = reinterpret_cast<const uint4*>((w == 0 ? a.K : a.V) + src);
-        kv[w][0] = p[0];
-        kv[w][1] = p[1];
-      }
-    }
-#pragma unroll
-    for (int w = 0; w < 2; ++w) {
-      uint4* d = reinterpret_cast<uint4*>(&s_rows[w][row][part * 16]);
-      d[0] = kv[w][0];
-      d[1] = kv[w][1];
-    }
-  }
-  __syncthreads();
-
-  {  // quantize: one thread = one group of 32 channels of one row of K or V (fixed-order fp32)
-    const int w = tid >> 7, row = (tid >> 2) & 31, grp = tid & 3;
-    float x[32];
-#pragma unroll
-    for (int i = 0; i < 32; ++i) x[i] = __uint_as_float(static_cast<uint32_t>(s_rows[w][row][grp * 32 + i]) << 16);
-    float mn = x[0], mx = x[0];
-#pragma unroll
-    for (int i = 1; i < 32; ++i) {
-      mn = fminf(mn, x[i]);
-      mx = fmaxf(mx, x[i]);
-    }
-    mn = mn + 0.0f;   // canonical +0
-    constexpr float Q = static_cast<float>((1 << BITS) - 1);
-    const _Float16 sh = static_cast<_Float16>((mx - mn) / Q);   // round to nearest even
-    const _Float16 mh = static_cast<_Float16>(mn);
-    const float s = static_cast<float>(sh), m = static_cast<float>(mh);
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      float t = rintf((x[i] - m) / s);
-      t = fminf(fmaxf(t, 0.0f), Q);
-      s_codes[w][row][grp * 32 + i] = (s == 0.0f) ? uint8_t(0) : static_cast<uint8_t>(t);
-    }
-    if (row < valid && !(a.v_only && w == 0)) {
-      const int mb = row >> 4, quad = (row & 15) >> 2, i = row & 3;
-      int si, oi;
-      if (w == 0) {
-        si = ((quad * 2 + mb) * 4 + grp) * 4 + i;
-        oi = 128 + row * 4 + grp;
-      } else {
-        si = (quad * 4 + grp) * 8 + 4 * mb + i;
-        oi = 128 + si;
-      }
-      uint16_t* meta = reinterpret_cast<uint16_t*>(a.arena + so[w * 2 + 1] + static_cast<int64_t>(blockIdx.x) * 512);
-      meta[si] = __builtin_bit_cast(unsigned short, sh);
-      meta[oi] = __builtin_bit_cast(unsigned short, mh);
-    }
-  }
-  __syncthreads();
-
-  // emit the tile's data words in their physical order (coalesced 32-bit stores)
-  constexpr int kWords = kRowPad * kHeadDim * BITS / 32;      // 1024 / 512 / 256
-#pragma unroll
-  for (int w = 0; w < 2; ++w) {
-    if (a.v_only && w == 0) continue;
-    uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[w * 2] +
-                                                static_cast<int64_t>(blockIdx.x) * (kRowPad * kHeadDim * BITS / 8));
-    for (int word = tid; word < kWords; word += 256) {
-      const int chunk = word >> 8, lane = (word >> 2) & 63, dd = word & 3;
-      uint32_t out = 0;
-      constexpr int kFields = 32 / BITS;
-#pragma unroll
-      for (int f = 0; f < kFields; ++f) {
-        int o, sl;
-        const int W = 4 * chunk + dd;                       // word of the lane's run
-        if constexpr (BITS == 8) {
-          o = 2 * (W >> 2) + (f & 1);
-          sl = 2 * (W & 3) + (f >> 1);
-        } else if constexpr (BITS == 4) {
-          o = 4 * (W >> 2) + (f & 3);
-          sl = 2 * (W & 3) + (f >> 2);
-        } else {
-          o = f & 7;
-          sl = 2 * W + (f >> 3);
-        }
-        int r, c;
-        tile_rc(w == 1, lane, o, sl, &r, &c);
-        out |= static_cast<uint32_t>(s_codes[w][r][c]) << (f * BITS);
-      }
-      dst[word] = out;
-    }
-  }
-}
-
-
-// Token-wise tiers 8/4/2: one workgroup = one tile of 64 kept rows, K and V.
+// Tiers 8/4/2: one workgroup = one tile of 64 kept rows, K and V (mixed mode: V only, v_only set).
 //
 // Tile layout (what the decode kernel's 4x4x4 MFMA steps want).  A wavefront lane owns a run of 4*BITS 32-bit words,
 // word W of lane L stored at byte 1024*(W/4) + 16*L + 4*(W%4).  The run holds four groups of BITS words; a group is
@@ -363,7 +227,7 @@ __global__ __launch_bounds__(256) void quant_pack_tile64_kernel(PackArgs a) {
       t = fminf(fmaxf(t, 0.0f), Q);
       s_codes[w][row][grp * 32 + i] = (s == 0.0f) ? uint8_t(0) : static_cast<uint8_t>(t);
     }
-    if (row < valid) {
+    if (row < valid && !(a.v_only && w == 0)) {
       int si, oi;
       if (w == 0) {
         si = 8 * row + grp;
@@ -384,6 +248,7 @@ __global__ __launch_bounds__(256) void quant_pack_tile64_kernel(PackArgs a) {
   constexpr int F = 16 / BITS;
 #pragma unroll
   for (int w = 0; w < 2; ++w) {
+    if (a.v_only && w == 0) continue;
     uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[w * 2] +
                                                 static_cast<int64_t>(blockIdx.x) * (kRows * kHeadDim * BITS / 8));
     for (int word = tid; word < kWords; word += 256) {
@@ -413,87 +278,95 @@ __global__ __launch_bounds__(256) void quant_pack_tile64_kernel(PackArgs a) {
 }
 
 // ---- mixed mode -------------------------------------------------------------------------------------------------
-// 16-bit V rows as 32-token tiles with the lane / operand / slot assignment of the quantized V tiers:
-// the bf16 of (lane, operand o, slot s) sits at byte 1024 o + 16 lane + 2 s of the 8 KiB tile.
-__global__ __launch_bounds__(256) void pack_v16_tile_kernel(PackArgs a) {
+// 16-bit V rows as 64-token tiles with the lane assignment of the quantized V tiers: lane 32 (r / 32) + c % 32 holds
+// channel c for the 32 tokens of its tile half, eight tokens per 16-byte unit; unit u = 4 (c / 32) + (r % 32) / 8
+// sits at byte 1024 u + 16 lane of the 16 KiB tile.
+__global__ __launch_bounds__(256) void pack_v16_tile64_kernel(PackArgs a) {
+  constexpr int kRows = 64;
   constexpr int kRowStride = kHeadDim + 8;
-  __shared__ __align__(16) uint16_t s_rows[kRowPad][kRowStride];
+  __shared__ __align__(16) uint16_t s_rows[kRows][kRowStride];
   const int item = blockIdx.y;
   const int n = a.counts[item * 4 + a.ti];
-  const int r0 = blockIdx.x * kRowPad;
+  const int r0 = blockIdx.x * kRows;
   if (r0 >= n) return;
-  const int valid = min(kRowPad, n - r0);
+  const int valid = min(kRows, n - r0);
   const int tid = threadIdx.x;
   const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
   {
-    const int row = tid >> 3, part = tid & 7;
-    uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+    const int row = tid >> 2, part = tid & 3;
+    uint4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = make_uint4(0, 0, 0, 0);
     if (row < valid) {
       const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + r0 + row];
-      const uint4* p = reinterpret_cast<const uint4*>(a.V + (a.item_row_off[item] + pos) * kHeadDim + part * 16);
-      v0 = p[0];
-      v1 = p[1];
+      const uint4* p = reinterpret_cast<const uint4*>(a.V + (a.item_row_off[item] + pos) * kHeadDim + part * 32);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = p[i];
     }
-    uint4* d = reinterpret_cast<uint4*>(&s_rows[row][part * 16]);
-    d[0] = v0;
-    d[1] = v1;
+    uint4* d = reinterpret_cast<uint4*>(&s_rows[row][part * 32]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) d[i] = v[i];
   }
   __syncthreads();
-  uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[2] + static_cast<int64_t>(blockIdx.x) * (kRowPad * kHeadDim * 2));
-  for (int word = tid; word < kRowPad * kHeadDim / 2; word += 256) {
-    const int o = word >> 8, lane = (word >> 2) & 63, sp = word & 3;
-    int r, c;
-    tile_rc(true, lane, o, 2 * sp, &r, &c);
-    const uint32_t lo = s_rows[r][c];
-    tile_rc(true, lane, o, 2 * sp + 1, &r, &c);
-    dst[word] = lo | (static_cast<uint32_t>(s_rows[r][c]) << 16);
+  uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[2] + static_cast<int64_t>(blockIdx.x) * (kRows * kHeadDim * 2));
+  for (int word = tid; word < kRows * kHeadDim / 2; word += 256) {
+    const int u = word >> 8, lane = (word >> 2) & 63, t8 = 2 * (word & 3);
+    const int r = 32 * (lane >> 5) + 8 * (u & 3) + t8, c = 32 * (u >> 2) + (lane & 31);
+    dst[word] = s_rows[r][c] | (static_cast<uint32_t>(s_rows[r + 1][c]) << 16);
   }
 }
 
-// Channel-wise K of one 32-token tile (Sec. 3.2 Stage 3 on the retained tokens): every channel is quantized at
-// its own bit-width over the tile's valid rows (one group = 32 consecutive retained tokens of one channel) and the
-// codes are written in sorted-channel order.  Lane l16 of a quad owns 2b bytes: tokens l16 and 16 + l16 for the
-// quad's 8 slots.  Slots pair up in the two halves of a 32-bit word; with P = 8/b pairs per word, pair p sits in
-// word p / P at field P * mb + p % P of each half (mb = token half); tier 16 stores 8 bf16 per token half.
+// Channel-wise K of one 64-token tile (Sec. 3.2 Stage 3 on the retained tokens): every channel is quantized at
+// its own bit-width over each half of the tile (one group = 32 consecutive retained tokens of one channel) and the
+// codes are written in sorted-channel order.  Token r of the tile owns n_words_padded 32-bit words: word W at byte
+// 1024 (W / 4) + 16 r + 4 (W % 4), the last two words of a row whose word count is not a multiple of four at
+// 1024 (n / 4) + 8 r + 4 (W % 2).  Inside a word, slot 4k + e of a b-bit tier sits at bit
+// 16 (e % 2) + b (e / 2) + 2 b k; a 16-bit word holds its two slots in its halves.
+// Metadata: per token group G and quantized step sq (4 slots) 4 fp16 scales then 4 fp16 offsets at fp16 index
+// 8 (G n_qsteps + sq).
 __global__ __launch_bounds__(256) void pack_k_mixed_kernel(PackArgs a) {
+  constexpr int kRows = 64;
   constexpr int kRowStride = kHeadDim + 8;
-  __shared__ __align__(16) uint16_t s_rows[kRowPad][kRowStride];
-  __shared__ uint16_t s_codes[kRowPad][kHeadDim + 2];
-  __shared__ uint16_t s_sc[kHeadDim], s_of[kHeadDim];
+  __shared__ __align__(16) uint16_t s_rows[kRows][kRowStride];
+  __shared__ uint16_t s_codes[kRows][kHeadDim + 2];
+  __shared__ uint16_t s_sc[2][kHeadDim], s_of[2][kHeadDim];
   __shared__ ItemK s_ik;
   const int item = blockIdx.y;
   const int n = a.counts[item * 4 + a.ti];
-  const int r0 = blockIdx.x * kRowPad;
+  const int r0 = blockIdx.x * kRows;
   if (r0 >= n) return;
-  const int valid = min(kRowPad, n - r0);
+  const int valid = min(kRows, n - r0);
   const int tid = threadIdx.x;
   const int64_t* so = a.seg_off + (static_cast<int64_t>(item) * 4 + a.ti) * 4;
   for (int i = tid; i < static_cast<int>(sizeof(ItemK) / 4); i += 256)
     reinterpret_cast<uint32_t*>(&s_ik)[i] = reinterpret_cast<const uint32_t*>(a.items_k + item)[i];
   {
-    const int row = tid >> 3, part = tid & 7;
-    uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+    const int row = tid >> 2, part = tid & 3;
+    uint4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = make_uint4(0, 0, 0, 0);
     if (row < valid) {
       const int pos = a.tier_idx[a.idx_base[item * 4 + a.ti] + r0 + row];
-      const uint4* p = reinterpret_cast<const uint4*>(a.K + (a.item_row_off[item] + pos) * kHeadDim + part * 16);
-      v0 = p[0];
-      v1 = p[1];
+      const uint4* p = reinterpret_cast<const uint4*>(a.K + (a.item_row_off[item] + pos) * kHeadDim + part * 32);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = p[i];
     }
-    uint4* d = reinterpret_cast<uint4*>(&s_rows[row][part * 16]);
-    d[0] = v0;
-    d[1] = v1;
+    uint4* d = reinterpret_cast<uint4*>(&s_rows[row][part * 32]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) d[i] = v[i];
   }
   __syncthreads();
-  if (tid < kHeadDim) {
-    const int c = tid;
+  {  // one thread = one (token group, channel)
+    const int G = tid >> 7, c = tid & 127;
+    const int rb = kKTokenGroup * G, vg = min(max(valid - rb, 0), kKTokenGroup);
     const int b = a.bits_ch[item * kHeadDim + c];
     uint16_t sc = 0, of = 0;
     if (b == 16) {
-      for (int r = 0; r < kRowPad; ++r) s_codes[r][c] = s_rows[r][c];      // rows beyond `valid` are zero
-    } else if (b == 8 || b == 4 || b == 2) {
-      float mn = __uint_as_float(static_cast<uint32_t>(s_rows[0][c]) << 16), mx = mn;
-      for (int r = 1; r < valid; ++r) {
-        const float x = __uint_as_float(static_cast<uint32_t>(s_rows[r][c]) << 16);
+      for (int r = 0; r < kKTokenGroup; ++r) s_codes[rb + r][c] = s_rows[rb + r][c];   // rows beyond `valid` are zero
+    } else if ((b == 8 || b == 4 || b == 2) && vg > 0) {
+      float mn = __uint_as_float(static_cast<uint32_t>(s_rows[rb][c]) << 16), mx = mn;
+      for (int r = 1; r < vg; ++r) {
+        const float x = __uint_as_float(static_cast<uint32_t>(s_rows[rb + r][c]) << 16);
         mn = fminf(mn, x);
         mx = fmaxf(mx, x);
       }
@@ -502,54 +375,57 @@ __global__ __launch_bounds__(256) void pack_k_mixed_kernel(PackArgs a) {
       const _Float16 sh = static_cast<_Float16>((mx - mn) / Q);
       const _Float16 mh = static_cast<_Float16>(mn);
       const float s = static_cast<float>(sh), m = static_cast<float>(mh);
-      for (int r = 0; r < kRowPad; ++r) {
-        const float x = __uint_as_float(static_cast<uint32_t>(s_rows[r][c]) << 16);
+      for (int r = 0; r < kKTokenGroup; ++r) {
+        const float x = __uint_as_float(static_cast<uint32_t>(s_rows[rb + r][c]) << 16);
         float t = rintf((x - m) / s);
         t = fminf(fmaxf(t, 0.0f), Q);
-        s_codes[r][c] = (s == 0.0f || r >= valid) ? uint16_t(0) : static_cast<uint16_t>(t);
+        s_codes[rb + r][c] = (s == 0.0f || r >= vg) ? uint16_t(0) : static_cast<uint16_t>(t);
       }
       sc = __builtin_bit_cast(unsigned short, sh);
       of = __builtin_bit_cast(unsigned short, mh);
     } else {
-      for (int r = 0; r < kRowPad; ++r) s_codes[r][c] = 0;
+      for (int r = 0; r < kKTokenGroup; ++r) s_codes[rb + r][c] = 0;
     }
-    s_sc[c] = sc;
-    s_of[c] = of;
+    s_sc[G][c] = sc;
+    s_of[G][c] = of;
   }
   __syncthreads();
 
+  const int nwp = s_ik.n_words_padded, full = nwp & ~3;
   uint32_t* dst = reinterpret_cast<uint32_t*>(a.arena + so[0] + static_cast<int64_t>(blockIdx.x) * s_ik.kt_bytes);
-  for (int word = tid; word < s_ik.kt_bytes / 4; word += 256) {
-    const int byte = word * 4;
-    int t = 3;
-    while (t > 0 && byte < s_ik.tier_base[t]) --t;
-    while (t < 3 && s_ik.nq[t] == 0) ++t;            // empty tiers share their base with the next one
-    const int b = 16 >> t;
-    const int off = byte - s_ik.tier_base[t];
-    const int quad = off / (32 * b), l16 = (off % (32 * b)) / (2 * b), wi = (off % (2 * b)) >> 2;
-    const int16_t* sl = s_ik.slot_ch + s_ik.slot_base[t] + 8 * quad;
-    uint32_t out = 0;
-    if (b == 16) {
-      const int mb = wi >> 2, j = 2 * (wi & 3);
-      const int c0 = sl[j], c1 = sl[j + 1];
-      if (c0 >= 0) out |= s_codes[16 * mb + l16][c0];
-      if (c1 >= 0) out |= static_cast<uint32_t>(s_codes[16 * mb + l16][c1]) << 16;
+  for (int idx = tid; idx < kRows * nwp; idx += 256) {
+    int W, r;
+    if (idx < kRows * full) {
+      W = 4 * (idx >> 8) + (idx & 3);
+      r = (idx >> 2) & 63;
     } else {
-      const int P = 8 / b;
-      for (int hh = 0; hh < 2; ++hh)
-        for (int f = 0; f < 2 * P; ++f) {
-          const int mb = f / P, slot = 2 * (wi * P + f % P) + hh;
-          const int c = sl[slot];
-          if (c >= 0) out |= static_cast<uint32_t>(s_codes[16 * mb + l16][c]) << (16 * hh + b * f);
-        }
+      W = full + (idx & 1);
+      r = (idx - kRows * full) >> 1;
     }
-    dst[word] = out;
+    uint32_t out = 0;
+    if (W < s_ik.n_words) {
+      int t = 0;
+      while (W >= s_ik.word_end[t]) ++t;
+      const int b = 16 >> t, per_word = 32 / b;
+      const int lw = W - (t > 0 ? s_ik.word_end[t - 1] : 0);
+      const int16_t* sl = s_ik.slot_ch + s_ik.slot_base[t] + lw * per_word;
+      for (int jj = 0; jj < per_word; ++jj) {
+        const int c = sl[jj];
+        if (c < 0) continue;
+        const int k = jj >> 2, e = jj & 3;
+        const int bit = b == 16 ? 16 * jj : 16 * (e & 1) + b * (e >> 1) + 2 * b * k;
+        out |= static_cast<uint32_t>(s_codes[r][c]) << bit;
+      }
+    }
+    dst[idx] = out;
   }
+  const int nqs = s_ik.n_qsteps;
   uint16_t* meta = reinterpret_cast<uint16_t*>(a.arena + so[1] + static_cast<int64_t>(blockIdx.x) * s_ik.km_bytes);
-  for (int j = tid; j < s_ik.n_qslots; j += 256) {
-    const int c = s_ik.slot_ch[s_ik.slot_base[1] + j];
-    meta[j] = c >= 0 ? s_sc[c] : uint16_t(0);
-    meta[s_ik.n_qslots + j] = c >= 0 ? s_of[c] : uint16_t(0);
+  for (int idx = tid; idx < 16 * nqs; idx += 256) {
+    const int G = idx / (8 * nqs), rem = idx - G * 8 * nqs;
+    const int sq = rem >> 3, e = rem & 3, is_off = (rem >> 2) & 1;
+    const int c = s_ik.slot_ch[s_ik.slot_base[1] + 4 * sq + e];
+    meta[idx] = c >= 0 ? (is_off ? s_of[G][c] : s_sc[G][c]) : uint16_t(0);
   }
 }
 
@@ -586,27 +462,17 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
   for (int ti = 0; ti < 4; ++ti) {
     if (max_count[ti] == 0) continue;
     PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti, mixed ? 1 : 0, items_k, bits_ch};
-    dim3 grid_rows((max_count[ti] + 63) / 64, n_items), grid_tiles((max_count[ti] + kRowPad - 1) / kRowPad, n_items);
-    dim3 grid_tiles64((max_count[ti] + 63) / 64, n_items);
+    dim3 grid64((max_count[ti] + 63) / 64, n_items);   // 64 rows per workgroup in every kernel below
     dim3 block(256);
-    if (mixed) hipLaunchKernelGGL(pack_k_mixed_kernel, grid_tiles, block, 0, st, a);
+    if (mixed) hipLaunchKernelGGL(pack_k_mixed_kernel, grid64, block, 0, st, a);
     switch (ti) {
       case 0:
-        if (mixed) hipLaunchKernelGGL(pack_v16_tile_kernel, grid_tiles, block, 0, st, a);
-        else hipLaunchKernelGGL(copy_rows_kernel, grid_rows, block, 0, st, a);
+        if (mixed) hipLaunchKernelGGL(pack_v16_tile64_kernel, grid64, block, 0, st, a);
+        else hipLaunchKernelGGL(copy_rows_kernel, grid64, block, 0, st, a);
         break;
-      case 1:
-        if (mixed) hipLaunchKernelGGL(quant_pack_tile_kernel<8>, grid_tiles, block, 0, st, a);
-        else hipLaunchKernelGGL(quant_pack_tile64_kernel<8>, grid_tiles64, block, 0, st, a);
-        break;
-      case 2:
-        if (mixed) hipLaunchKernelGGL(quant_pack_tile_kernel<4>, grid_tiles, block, 0, st, a);
-        else hipLaunchKernelGGL(quant_pack_tile64_kernel<4>, grid_tiles64, block, 0, st, a);
-        break;
-      default:
-        if (mixed) hipLaunchKernelGGL(quant_pack_tile_kernel<2>, grid_tiles, block, 0, st, a);
-        else hipLaunchKernelGGL(quant_pack_tile64_kernel<2>, grid_tiles64, block, 0, st, a);
-        break;
+      case 1: hipLaunchKernelGGL(quant_pack_tile64_kernel<8>, grid64, block, 0, st, a); break;
+      case 2: hipLaunchKernelGGL(quant_pack_tile64_kernel<4>, grid64, block, 0, st, a); break;
+      default: hipLaunchKernelGGL(quant_pack_tile64_kernel<2>, grid64, block, 0, st, a); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -223,24 +223,27 @@ void free_cache_buffers(rdkv_cache* c) {
 ItemK make_item_k(const uint8_t* bits_ch) {
   ItemK k;
   std::memset(&k, 0, sizeof(k));
-  int slot = 0, byte = 0;
+  int slot = 0, words = 0, qsteps = 0;
   for (int ti = 0; ti < 4; ++ti) {
     const int b = pack_tier_bits(ti);
+    const int pad = ti == 0 ? 4 : 32 / b;            // whole word pairs (16-bit) / whole words
     k.slot_base[ti] = static_cast<int16_t>(slot);
-    k.tier_base[ti] = static_cast<int16_t>(byte);
     int cnt = 0;
     for (int c = 0; c < kHeadDim; ++c)
       if (bits_ch[c] == b) k.slot_ch[slot + cnt++] = static_cast<int16_t>(c);
-    const int nq = (cnt + 7) / 8;
-    for (int j = cnt; j < 8 * nq; ++j) k.slot_ch[slot + j] = -1;
-    k.nq[ti] = static_cast<int16_t>(nq);
-    slot += 8 * nq;
-    byte += nq * 32 * b;
+    const int npad = (cnt + pad - 1) / pad * pad;
+    for (int j = cnt; j < npad; ++j) k.slot_ch[slot + j] = -1;
+    slot += npad;
+    words += npad * b / 32;
+    k.word_end[ti] = static_cast<int16_t>(words);
+    if (ti == 0) k.n_steps16 = static_cast<int16_t>(npad / 4); else qsteps += npad / 4;
   }
   k.n_slots = static_cast<int16_t>(slot);
-  k.n_qslots = static_cast<int16_t>(slot - 8 * k.nq[0]);
-  k.kt_bytes = byte;
-  k.km_bytes = 4 * k.n_qslots;
+  k.n_qsteps = static_cast<int16_t>(qsteps);
+  k.n_words = static_cast<int16_t>(words);
+  k.n_words_padded = static_cast<int16_t>((words + 1) / 2 * 2);
+  k.kt_bytes = 256 * k.n_words_padded;
+  k.km_bytes = 32 * k.n_qsteps;
   for (int j = slot; j < kMaxSlots; ++j) k.slot_ch[j] = -1;
   return k;
 }
@@ -521,7 +524,10 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
             return bail(fail(RDKV_ERR_INVALID_ARG, "bits_ch[%lld][%d] = %d is not a tier", static_cast<long long>(i),
                              ch, h_bits_ch[i * kHeadDim + ch]));
         c->items_k[i] = make_item_k(&h_bits_ch[i * kHeadDim]);
-        c->max_kt_bytes = std::max(c->max_kt_bytes, c->items_k[i].kt_bytes);
+        const ItemK& ik = c->items_k[i];
+        c->max_k_words = std::max<int32_t>(c->max_k_words, ik.n_words_padded);
+        c->max_k_steps = std::max<int32_t>(c->max_k_steps, ik.n_steps16 + ik.n_qsteps);
+        c->max_k_qsteps = std::max<int32_t>(c->max_k_qsteps, ik.n_qsteps);
       }
     }
   }
@@ -537,12 +543,12 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
       idx_base[i * 4 + ti] = kept;
       kept += cnt;
       max_count[ti] = std::max<int32_t>(max_count[ti], static_cast<int32_t>(cnt));
-      const int64_t npad = round_up(cnt, mixed ? kRowPad : kTile64);
+      const int64_t npad = round_up(cnt, kTile64);
       int64_t sizes[4] = {npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits),
                           npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits)};
       if (mixed) {   // the K segments hold the channel-wise tiles of this tier's tokens
-        sizes[0] = npad / kRowPad * c->items_k[i].kt_bytes;
-        sizes[1] = npad / kRowPad * c->items_k[i].km_bytes;
+        sizes[0] = npad / kTile64 * c->items_k[i].kt_bytes;
+        sizes[1] = npad / kTile64 * c->items_k[i].km_bytes;
       }
       for (int si = 0; si < 4; ++si) {
         cur = round_up(cur, kSegAlign);
@@ -559,7 +565,7 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
             kbits += pack_tier_bits(t2);
             nquant += t2 > 0;
           }
-        stored += cnt * kbits / 8 + (cnt + kRowPad - 1) / kRowPad * 4 * nquant;
+        stored += cnt * kbits / 8 + (cnt + kKTokenGroup - 1) / kKTokenGroup * 4 * nquant;
         stored += cnt * (tier_row_bytes(bits) + tier_meta_bytes(bits));
       } else {
         stored += cnt * 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
@@ -583,15 +589,15 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
       int64_t per_row = 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
       if (mixed)
         per_row = tier_row_bytes(bits) + tier_meta_bytes(bits) +
-                  (c->items_k[i].kt_bytes + c->items_k[i].km_bytes + kRowPad - 1) / kRowPad;
+                  (c->items_k[i].kt_bytes + c->items_k[i].km_bytes + kTile64 - 1) / kTile64;
       const int64_t want = std::max<int64_t>(64, chunk_bytes / per_row);
       const int64_t nch = (cnt + want - 1) / want;
       const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
       const int64_t* so = &c->seg_off[(i * 4 + ti) * 4];
       for (int64_t r0 = 0; r0 < cnt; r0 += rows_per) {
         Chunk ch;
-        ch.k_data = so[0] + (mixed ? r0 / kRowPad * c->items_k[i].kt_bytes : r0 * tier_row_bytes(bits));
-        ch.k_meta = so[1] + (mixed ? r0 / kRowPad * c->items_k[i].km_bytes : r0 * tier_meta_bytes(bits));
+        ch.k_data = so[0] + (mixed ? r0 / kTile64 * c->items_k[i].kt_bytes : r0 * tier_row_bytes(bits));
+        ch.k_meta = so[1] + (mixed ? r0 / kTile64 * c->items_k[i].km_bytes : r0 * tier_meta_bytes(bits));
         ch.v_data = so[2] + r0 * tier_row_bytes(bits);
         ch.v_meta = so[3] + r0 * tier_meta_bytes(bits);
         ch.rows = static_cast<int32_t>(std::min<int64_t>(rows_per, cnt - r0));
@@ -695,7 +701,8 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
     {
       TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
       RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->chunks.size()), c->d_arena, c->d_items_k,
-                                   c->max_kt_bytes, static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
+                                   c->max_k_words, c->max_k_steps, c->max_k_qsteps,
+                                   static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
                                    c->hq, c->hkv, st));
     }
     RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,

@@ -13,8 +13,8 @@ namespace rdkv {
 constexpr int kHeadDim = 128;
 constexpr int kGroup = 32;             // quantization group (channels)
 constexpr int kGroupsPerRow = kHeadDim / kGroup;
-constexpr int kRowPad = 32;            // mixed mode: tier segments are padded to whole 32-row tiles
-constexpr int kTile64 = 64;            // token-wise mode: whole 64-row tiles
+constexpr int kTile64 = 64;            // tier segments are padded to whole 64-row tiles
+constexpr int kKTokenGroup = 32;       // mixed mode: a K channel's group = 32 consecutive retained tokens of a segment
 constexpr int kSegAlign = 256;         // byte alignment of arena segments
 constexpr int kNumPackTiers = 4;       // stored tiers, order 16, 8, 4, 2
 constexpr int kDenseMaxSeqs = 64;      // sequences per dense-decode launch (kernel-argument table)
@@ -33,16 +33,17 @@ struct Chunk {
 };
 
 // Channel-wise K (mixed mode): how one item's K tiles are laid out.  Channels are sorted by bit-width into
-// slots: tiers 16, 8, 4, 2 in this order, each padded to whole quads of 8 channels; a quad of tier b takes
-// 32 b bytes of a 32-token tile.
-constexpr int kMaxSlots = 160;   // 128 channels + up to 7 padding slots per tier
+// slots: tiers 16, 8, 4, 2 in this order.  A retained token's K row is a run of 32-bit words (a 16-bit word holds
+// 2 slots, an 8-bit word 4, a 4-bit word 8, a 2-bit word 16); every tier is padded to whole words, the 16-bit tier
+// to whole word pairs, the row to an even number of words.  A step is 4 consecutive slots.
+constexpr int kMaxSlots = 160;   // 128 channels + up to 3 + 3 + 7 + 15 padding slots
 struct ItemK {
-  int32_t kt_bytes;              // K tile data bytes
-  int32_t km_bytes;              // K tile metadata bytes: fp16 scales of the quantized slots, then their offsets
-  int16_t nq[4];                 // quads per tier (16, 8, 4, 2)
-  int16_t tier_base[4];          // byte offset of each tier inside a tile
+  int32_t kt_bytes;              // K tile (64 tokens) data bytes = 256 * n_words_padded
+  int32_t km_bytes;              // K tile metadata bytes = 32 * n_qsteps (2 token groups x 16 bytes per quantized step)
+  int16_t word_end[4];           // words per token up to and including tier 16, 8, 4, 2
   int16_t slot_base[4];          // first slot of each tier
-  int16_t n_slots, n_qslots;     // all slots; slots of the quantized tiers
+  int16_t n_slots, n_words, n_words_padded;
+  int16_t n_steps16, n_qsteps;   // steps of the 16-bit tier; steps of the quantized tiers
   int16_t slot_ch[kMaxSlots];    // channel held by a slot, -1 for padding
 };
 
@@ -71,8 +72,8 @@ hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_m
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
                                float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
 hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                               int max_kt_bytes, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv,
-                               hipStream_t st);
+                               int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
+                               float* part_ml, int hq, int hkv, hipStream_t st);
 
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);
@@ -113,7 +114,7 @@ struct rdkv_cache {
   uint8_t* d_bits_ch = nullptr;         // [items][128] K channel bit map (mixed mode)
   rdkv::ItemK* d_items_k = nullptr;     // [items] (mixed mode)
   std::vector<rdkv::ItemK> items_k;
-  int32_t max_kt_bytes = 0;
+  int32_t max_k_words = 0, max_k_steps = 0, max_k_qsteps = 0;   // largest K row shape over the items (mixed mode)
   int64_t stored_bytes = 0;             // bytes a decode step must read (unpadded)
   int64_t index_bytes = 0;
   rdkv_alloc_fn alloc = nullptr;

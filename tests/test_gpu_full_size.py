@@ -33,12 +33,12 @@ def _seg_sizes_tokenwise(counts):
 
 
 def _seg_sizes_mixed(counts, bits_ch):
-    nq = O.channel_slots(bits_ch)["nq"]
+    sl = O.channel_slots(bits_ch)
     sizes = []
     for ti, b in enumerate(O.PACK_ORDER):
-        nt = (int(counts[ti]) + 31) // 32
-        sizes.append([nt * O.k_tile_bytes_mixed(nq), nt * O.k_meta_bytes_mixed(nq),
-                      nt * (8192 if b == 16 else 512 * b), 0 if b == 16 else nt * 512])
+        nt = (int(counts[ti]) + 63) // 64
+        sizes.append([nt * O.k_tile_bytes_mixed(sl), nt * O.k_meta_bytes_mixed(sl),
+                      nt * (16384 if b == 16 else 1024 * b), 0 if b == 16 else nt * 1024])
     return sizes
 
 

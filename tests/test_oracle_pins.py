@@ -615,84 +615,6 @@ def test_compress_tokenwise_end_to_end_small():
 
 
 # ----------------------------------------------------------------------------
-# tile layout of the quantized tiers (a documented bijection of the canonical record)
-# ----------------------------------------------------------------------------
-@pytest.mark.parametrize("bits", [2, 4, 8])
-@pytest.mark.parametrize("which", ["k", "v"])
-def test_tile_positions_are_a_bijection_onto_the_tile(bits, which):
-    byte_off, shift = O.tile_code_positions(bits, which)
-    tb = O.tile_data_bytes(bits)
-    assert tb == 32 * 128 * bits // 8
-    pos = byte_off * 8 + shift
-    assert pos.min() == 0 and pos.max() == tb * 8 - bits
-    assert len(np.unique(pos)) == 32 * 128                      # no two codes share a field
-    assert np.all(shift % bits == 0)                            # App. B: fields at offsets 0,2,4,6 / 0,4 / 0
-    sc, of = O.tile_meta_positions(which)
-    both = np.concatenate([sc.reshape(-1), of.reshape(-1)])
-    assert sorted(both.tolist()) == list(range(256))            # 128 scales then 128 offsets, each slot used once
-    assert sc.max() < 128 <= of.min()
-
-
-def test_tile_positions_hand_checked():
-    # positions worked out by hand from the layout rule (word W of a lane at 1024*(W//4) + 16*lane + 4*(W%4)):
-    # K, 8-bit: (row 0, ch 0) = lane 0, operand 0, slot 0 -> word 0 bit 0 -> byte 0.  ch 1 = slot 1 -> high half of
-    # word 0 -> byte 2.  ch 2 = slot 2 -> word 1 -> byte 4.  ch 8 = quad 1 -> lane 16 -> byte 256.  ch 32 = operand 1
-    # -> bit 8 of word 0 -> byte 1.  ch 64 = operand 2 -> word 4 -> second 1 KiB chunk.  row 16 = operand 4 -> word 8.
-    bo, sh = O.tile_code_positions(8, "k")
-    assert (bo[0, 0], bo[0, 1], bo[0, 2], bo[0, 8], bo[0, 32], bo[0, 64], bo[16, 0], bo[1, 0]) == \
-        (0, 2, 4, 256, 1, 1024, 2048, 16)
-    assert not sh.any()
-    # K, 4-bit: operand -> nibble inside each 16-bit half; slots (0,1) are the two halves of word 0
-    bo, sh = O.tile_code_positions(4, "k")
-    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (4, 0)
-    assert (bo[0, 32], sh[0, 32]) == (0, 4)                     # group 1 = operand 1 -> bits 4..7 of the same half
-    assert (bo[0, 64], sh[0, 64]) == (1, 0) and (bo[0, 96], sh[0, 96]) == (1, 4)
-    assert bo[16, 0] == 1024                                    # second m-block = operand 4 -> word 4 -> second chunk
-    # K, 2-bit: all eight operands share the lane's four words, operand o in bits 2o, 2o+1 of each half
-    bo, sh = O.tile_code_positions(2, "k")
-    assert (bo[0, 0], sh[0, 0]) == (0, 0) and (bo[0, 1], sh[0, 1]) == (2, 0) and (bo[0, 2], sh[0, 2]) == (4, 0)
-    assert (bo[0, 32], sh[0, 32]) == (0, 2) and (bo[0, 33], sh[0, 33]) == (2, 2)
-    assert (bo[16, 0], sh[16, 0]) == (1, 0) and (bo[16, 96], sh[16, 96]) == (1, 6)   # operands 4 and 7: second byte
-    # V, 8-bit: the eight slots of a lane are tokens {0..3, 16..19} + 4*quad of one channel: bytes 0,2 of words 0..3
-    bo, sh = O.tile_code_positions(8, "v")
-    assert [int(bo[r, 0]) for r in (0, 1, 2, 3, 16, 17, 18, 19)] == [0, 2, 4, 6, 8, 10, 12, 14]
-    assert bo[4, 0] == 16 * 16 and bo[0, 1] == 16 and bo[0, 16] == 1 and bo[0, 32] == 1024   # quad 1; lane 1; operands 1, 2
-    # V, 2-bit: channel block c // 16 picks the field, token slots pick word and half
-    bo, sh = O.tile_code_positions(2, "v")
-    assert (bo[0, 16], sh[0, 16]) == (0, 2) and (bo[1, 0], sh[1, 0]) == (2, 0) and (bo[16, 0], sh[16, 0]) == (8, 0)
-    assert (bo[0, 112], sh[0, 112]) == (1, 6)
-    sc, of = O.tile_meta_positions("k")
-    assert sc[0].tolist() == [0, 4, 8, 12] and sc[1, 0] == 1 and sc[16, 0] == 16 and sc[4, 0] == 32
-    assert of[0].tolist() == [128, 129, 130, 131] and of[31, 3] == 255
-    sc, of = O.tile_meta_positions("v")
-    assert sc[0].tolist() == [0, 8, 16, 24] and sc[16, 0] == 4 and sc[4, 0] == 32 and of[0, 0] == 128
-
-
-@pytest.mark.parametrize("bits", [2, 4, 8])
-def test_tile_pack_roundtrip_and_padding(bits):
-    rng = np.random.default_rng(30 + bits)
-    n = 75                                                       # two full tiles and a ragged third
-    codes = rng.integers(0, 1 << bits, (n, 128)).astype(np.uint8)
-    sc = rng.integers(0, 65536, (n, 4)).astype(np.uint16)
-    of = rng.integers(0, 65536, (n, 4)).astype(np.uint16)
-    for which in ("k", "v"):
-        data, meta = O.pack_tiles(codes, sc, of, bits, which)
-        assert data.size == 3 * O.tile_data_bytes(bits) and meta.size == 3 * 512
-        c2, s2, o2 = O.unpack_tiles(data, meta, n, bits, which)
-        np.testing.assert_array_equal(c2, codes)
-        np.testing.assert_array_equal(s2, sc)
-        np.testing.assert_array_equal(o2, of)
-        # rows beyond n are zero rows
-        c3, s3, o3 = O.unpack_tiles(data, meta, 96, bits, which)
-        assert not c3[n:].any() and not s3[n:].any() and not o3[n:].any()
-    # a single code lands in exactly one field
-    one = np.zeros((1, 128), np.uint8)
-    one[0, 5] = (1 << bits) - 1
-    data, _ = O.pack_tiles(one, np.zeros((1, 4), np.uint16), np.zeros((1, 4), np.uint16), bits, "k")
-    assert int(np.unpackbits(data).sum()) == bits
-
-
-# ----------------------------------------------------------------------------
 # 64-row tiles of the token-wise mode
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("bits", [2, 4, 8])
@@ -859,76 +781,111 @@ def test_per_channel_dequantization_fusion_identity():
     np.testing.assert_allclose(fused, direct, rtol=1e-12, atol=1e-12)
 
 
-def test_channel_slots_hand_worked():
+def _hand_bits_ch():
     bc = np.zeros(128, np.uint8)
     bc[[5, 70, 100]] = 8
     bc[[0, 1]] = 16
-    bc[10:21] = 4                      # 11 channels -> two quads, five padding slots
+    bc[10:21] = 4                      # 11 channels -> two words of 8 slots, five padding slots
     bc[[30, 31, 32]] = 2
+    return bc
+
+
+def test_channel_slots_hand_worked():
+    sl = O.channel_slots(_hand_bits_ch())
+    assert sl["npad"] == {16: 4, 8: 4, 4: 16, 2: 16} and sl["nw"] == {16: 2, 8: 1, 4: 2, 2: 1}
+    assert sl["slot_ch"].tolist() == [0, 1, -1, -1] + [5, 70, 100, -1] + list(range(10, 21)) + [-1] * 5 \
+        + [30, 31, 32] + [-1] * 13
+    assert (sl["n_words"], sl["n_words_padded"], sl["n_steps16"], sl["n_qsteps"]) == (6, 6, 1, 9)
+    assert O.k_tile_bytes_mixed(sl) == 64 * 6 * 4 and O.k_meta_bytes_mixed(sl) == 2 * 9 * 16
+    # an odd word count is padded to an even one; no channels at all -> no bytes
+    bc = np.zeros(128, np.uint8)
+    bc[:4] = 8
     sl = O.channel_slots(bc)
-    assert sl["nq"] == {16: 1, 8: 1, 4: 2, 2: 1}
-    assert sl["slot_ch"].tolist() == [0, 1] + [-1] * 6 + [5, 70, 100] + [-1] * 5 + list(range(10, 21)) + [-1] * 5 \
-        + [30, 31, 32] + [-1] * 5
-    assert O.k_tile_bytes_mixed(sl["nq"]) == 512 + 256 + 2 * 128 + 64
-    assert O.k_meta_bytes_mixed(sl["nq"]) == 4 * 8 * 4
+    assert (sl["n_words"], sl["n_words_padded"]) == (1, 2)
+    sl = O.channel_slots(np.zeros(128, np.uint8))
+    assert O.k_tile_bytes_mixed(sl) == 0 and O.k_meta_bytes_mixed(sl) == 0 and sl["slot_ch"].size == 0
+    # every channel at 16 bits: 64 words per token, 32 steps, no padding
+    sl = O.channel_slots(np.full(128, 16, np.uint8))
+    assert (sl["n_words"], sl["n_steps16"], sl["n_qsteps"]) == (64, 32, 0) and (sl["slot_ch"] >= 0).all()
 
 
 def test_mixed_k_tile_layout_hand_checked_and_roundtrip():
     rng = np.random.default_rng(45)
-    bc = np.zeros(128, np.uint8)
-    bc[[5, 70, 100]] = 8
-    bc[[0, 1]] = 16
-    bc[10:21] = 4
-    bc[[30, 31, 32]] = 2
-    n = 40
+    bc = _hand_bits_ch()
+    n = 75
     X = rand_bf16(rng, (n, 128))
     codes, sc, of = O.quantize_channelwise(X, bc)
     data, meta = O.pack_k_tiles_mixed(codes, sc, of, bc)
-    tb = 512 + 256 + 256 + 64
-    assert data.size == 2 * tb and meta.size == 2 * 128
+    tb = 1536
+    assert data.size == 2 * tb and meta.size == 2 * 288
     d16 = data.view("<u2")
-    # tier 16 quad at byte 0: lane l16 owns 32 bytes: 8 bf16 of token l16 then 8 bf16 of token 16 + l16
-    assert d16[0] == codes[0, 0] and d16[1] == codes[0, 1] and d16[8] == codes[16, 0] and d16[16] == codes[1, 0]
-    assert d16[2] == 0                                             # padding slot
-    # tier 8 quad at byte 512: lane l16 owns 16 bytes = 4 words, word p = slots (2p, 2p+1):
-    # bytes [slot 2p half 0, slot 2p half 1, slot 2p+1 half 0, slot 2p+1 half 1]
-    assert data[512 + 0] == codes[0, 5] and data[512 + 1] == codes[16, 5] and data[512 + 2] == codes[0, 70]
-    assert data[512 + 3] == codes[16, 70] and data[512 + 4] == codes[0, 100] and data[512 + 16] == codes[1, 5]
-    # tier 4 at byte 768: lane owns 8 bytes = 2 words, two slot pairs per word.  First 16-bit half of word 0:
-    # nibbles [slot 0 half 0, slot 2 half 0, slot 0 half 1, slot 2 half 1]; second half: slots 1 and 3
-    b0, b1 = int(data[768]), int(data[769])
-    assert (b0 & 15, b0 >> 4) == (int(codes[0, 10]), int(codes[0, 12]))
-    assert (b1 & 15, b1 >> 4) == (int(codes[16, 10]), int(codes[16, 12]))
-    b2 = int(data[770])
-    assert (b2 & 15, b2 >> 4) == (int(codes[0, 11]), int(codes[0, 13]))
-    assert (int(data[772]) & 15) == int(codes[0, 14])                              # word 1: slot 4
-    assert (int(data[768 + 128]) & 15) == int(codes[0, 18])                        # second quad: channels 18..20
-    # tier 2 at byte 1024: lane owns one word; fields of the first half: slots 0, 2, 4, 6 of half 0, then of half 1
-    w = int(data[1024:1028].view("<u4")[0])
-    assert (w & 3, (w >> 2) & 3, (w >> 8) & 3, (w >> 10) & 3, (w >> 16) & 3) == \
-        (int(codes[0, 30]), int(codes[0, 32]), int(codes[16, 30]), int(codes[16, 32]), int(codes[0, 31]))
-    # second tile starts at tb; it holds rows 32..39 and zero rows after them
-    assert data[tb + 512] == codes[32, 5] and data[tb + 512 + 1] == 0
-    # metadata: scales of the quantized slots (8-bit quad, two 4-bit quads, 2-bit quad), then offsets
+    # six words per token: words 0..3 of token r at byte 16 r, words 4, 5 at byte 1024 + 8 r.
+    # words 0, 1 = the 16-bit step: channels 0, 1 in the halves of word 0, two padding slots in word 1
+    assert d16[0] == codes[0, 0] and d16[1] == codes[0, 1] and d16[2] == 0 and d16[3] == 0 and d16[8] == codes[1, 0]
+    # word 2 = the 8-bit step (channels 5, 70, 100, padding): elements 0, 1 in the low bytes of the halves,
+    # elements 2, 3 in their high bytes
+    assert data[8] == codes[0, 5] and data[10] == codes[0, 70] and data[9] == codes[0, 100] and data[11] == 0
+    assert data[16 + 8] == codes[1, 5]
+    # word 3 = 4-bit channels 10..17: step 0 = (10, 11, 12, 13) in the low byte of each half, step 1 in the high byte;
+    # inside a byte the low nibble is element 0 / 1, the high nibble element 2 / 3
+    assert (int(data[12]) & 15, int(data[12]) >> 4) == (int(codes[0, 10]), int(codes[0, 12]))
+    assert (int(data[14]) & 15, int(data[14]) >> 4) == (int(codes[0, 11]), int(codes[0, 13]))
+    assert (int(data[13]) & 15, int(data[13]) >> 4) == (int(codes[0, 14]), int(codes[0, 16]))
+    assert (int(data[15]) & 15, int(data[15]) >> 4) == (int(codes[0, 15]), int(codes[0, 17]))
+    # word 4 (second run) = 4-bit channels 18, 19, 20 and five padding slots
+    assert (int(data[1024]) & 15, int(data[1024]) >> 4) == (int(codes[0, 18]), int(codes[0, 20]))
+    assert int(data[1026]) == int(codes[0, 19]) and data[1025] == 0 and data[1027] == 0
+    # word 5 = 2-bit channels 30, 31, 32: elements 0, 1 at bits 0-1 of the halves, element 2 at bits 2-3
+    w = int(data[1028:1032].view("<u4")[0])
+    assert (w & 3, (w >> 16) & 3, (w >> 2) & 3, w >> 18, (w >> 4) & 0xFFF) == \
+        (int(codes[0, 30]), int(codes[0, 31]), int(codes[0, 32]), 0, 0)
+    assert (int(data[1024 + 8 + 4]) & 3) == int(codes[1, 30])
+    # second tile: rows 64..74, zero rows after them
+    assert data[tb + 8] == codes[64, 5] and data[tb + 16 * 10 + 8] == codes[74, 5] and data[tb + 16 * 11 + 8] == 0
+    # metadata: per token group and quantized step 4 scales then 4 offsets; 9 steps = 1 (8-bit) + 4 + 4
     m16 = meta.view("<u2")
-    assert m16[0] == sc[0, 5] and m16[2] == sc[0, 100] and m16[3] == 0 and m16[8] == sc[0, 10] and m16[24] == sc[0, 30]
-    assert m16[32] == of[0, 5] and m16[64 + 0] == sc[1, 5]
+    assert m16[:8].tolist() == [sc[0, 5], sc[0, 70], sc[0, 100], 0, of[0, 5], of[0, 70], of[0, 100], 0]
+    assert m16[8:12].tolist() == [sc[0, c] for c in (10, 11, 12, 13)] and m16[12] == of[0, 10]
+    assert m16[40:44].tolist() == [sc[0, 30], sc[0, 31], sc[0, 32], 0]
+    assert m16[72] == sc[1, 5] and m16[144] == sc[2, 5] and m16[144 + 72] == 0       # group 1; tile 1; no rows in group 3
     c2, s2, o2 = O.unpack_k_tiles_mixed(data, meta, n, bc)
     np.testing.assert_array_equal(c2, codes)
     np.testing.assert_array_equal(s2, sc)
     np.testing.assert_array_equal(o2, of)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_mixed_k_tile_fields_are_disjoint_and_cover_the_tile(seed):
+    rng = np.random.default_rng(seed)
+    bc = rng.choice([0, 2, 4, 8, 16], 128, p=[.1, .4, .3, .15, .05]).astype(np.uint8)
+    sl = O.channel_slots(bc)
+    # all-ones codes of every real slot: set bits = sum of widths x 64 tokens, so no two fields overlap
+    codes = np.zeros((64, 128), np.uint16)
+    for c in range(128):
+        codes[:, c] = (1 << int(bc[c])) - 1 if bc[c] else 0
+    ng = 2
+    data, _ = O.pack_k_tiles_mixed(codes, np.zeros((ng, 128), np.uint16), np.zeros((ng, 128), np.uint16), bc)
+    assert data.size == O.k_tile_bytes_mixed(sl)
+    assert int(np.unpackbits(data).sum()) == 64 * int(bc.astype(np.int64).sum())
+    # a quantized code never reaches the exponent bits of its 16-bit half once its step's shift is applied:
+    # fields of one half are 2b apart per step and b apart inside a step
+    for b in (2, 4, 8):
+        bits = sorted(O._k_code_bit(b, j) % 16 for j in range(0, 32 // b, 2))
+        assert bits == list(range(0, 16, b))
+
+
 def test_v16_tile_roundtrip_and_positions():
     rng = np.random.default_rng(46)
-    vb = rng.integers(0, 65536, (45, 128)).astype(np.uint16)
+    vb = rng.integers(0, 65536, (70, 128)).astype(np.uint16)
     data = O.pack_v16_tiles(vb)
-    assert data.size == 2 * 8192
+    assert data.size == 2 * 16384
     w = data.view("<u2")
-    # operand 0 (channels 0..15), lane 0 (quad 0, channel 0): slots = tokens 0,1,2,3,16,17,18,19
-    assert [int(x) for x in w[:8]] == [int(vb[r, 0]) for r in (0, 1, 2, 3, 16, 17, 18, 19)]
-    assert w[8] == vb[0, 1] and w[16 * 8] == vb[4, 0] and w[512] == vb[0, 16]       # lane 1; quad 1; operand 1
-    np.testing.assert_array_equal(O.unpack_v16_tiles(data, 45), vb)
+    # lane 0 = (token half 0, channel 0): its first 16-byte unit holds tokens 0..7, the next unit (1 KiB on) 8..15
+    assert [int(x) for x in w[:8]] == [int(vb[r, 0]) for r in range(8)] and w[512] == vb[8, 0]
+    # lane 1 = channel 1; lane 32 = token half 1; channel 32 = group 1 = unit 4
+    assert w[8] == vb[0, 1] and w[256] == vb[32, 0] and w[2048] == vb[0, 32]
+    assert w[8192] == vb[64, 0] and w[8192 + 6] == 0                                # second tile: rows 64..69, then zeros
+    np.testing.assert_array_equal(O.unpack_v16_tiles(data, 70), vb)
 
 
 def test_mixed_cache_bytes_and_decode_from_physical_bytes():
@@ -937,13 +894,13 @@ def test_mixed_cache_bytes_and_decode_from_physical_bytes():
     cache = O.build_cache_mixed([K], [V], [bt], [bc])
     # closed-form segment sizes
     for item in range(2):
-        nq = O.channel_slots(bc[item])["nq"]
+        sl = O.channel_slots(bc[item])
         for ti, b in enumerate(O.PACK_ORDER):
             n = int((bt[item] == b).sum())
             assert cache["counts"][item, ti] == n
-            nt = (n + 31) // 32
-            sizes = [nt * O.k_tile_bytes_mixed(nq), nt * O.k_meta_bytes_mixed(nq),
-                     nt * (8192 if b == 16 else 512 * b), 0 if b == 16 else nt * 512]
+            nt = (n + 63) // 64
+            sizes = [nt * O.k_tile_bytes_mixed(sl), nt * O.k_meta_bytes_mixed(sl),
+                     nt * (16384 if b == 16 else 1024 * b), 0 if b == 16 else nt * 1024]
             offs = cache["seg_off"][item, ti]
             assert all(int(o) % 256 == 0 for o in offs)
             nxt = list(offs[1:]) + [cache["seg_off"][item, ti + 1, 0] if ti < 3 else

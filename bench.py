@@ -8,9 +8,9 @@ bits/element, synthetic bf16 tensors (see paper_2605_08317_amd/workloads.py).
 A step is one decode-attention step of the whole stack over the compressed
 caches: 32 dependent per-layer calls of rdkv_decode_attn, replayed from a HIP
 graph.  `value` is its latency.  The one-shot compression pass that produced the
-caches, the library's own bf16 path on the same tensors, and the same 32 caches
-submitted as one 32-sequence batch are timed beside it and reported in the same
-JSON line.
+caches, the library's own bf16 path on the same tensors, the same 32 caches
+submitted as one 32-sequence batch, and the mixed-mode config (V token-wise, K
+channel-wise) are timed beside it and reported in the same JSON line.
 """
 import argparse
 import json
@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--budget", type=float, default=None, help="override the average bits/element")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch the per-layer calls eagerly")
+    ap.add_argument("--per-layer-only", action="store_true",
+                    help="skip the bf16, batched and mixed-mode legs (kernel traces of the per-layer launches alone)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter-collection mode for `rocprofv3 --pmc`: build the caches, run --steps eager decode "
                          "steps, the batched launch, the bf16 path and a 1 GiB device-to-device copy, then exit")
@@ -178,6 +180,11 @@ def main():
     kern_ms = ms_k / max(n_k, 1)
     achieved = alg_bytes_layer / (kern_ms * 1e-3) / 1e9
 
+    if args.per_layer_only:
+        print(json.dumps({"per_layer_only": True, "ms_per_step": ms_step, "kernel_ms": kern_ms,
+                          "bytes_per_launch": alg_bytes_layer, "achieved_gbs": achieved}))
+        return
+
     # ---- the library's bf16 path on the same tensors (D0) ----------------------------------------------
     ws_bytes = b.rdkv_decode_bf16_workspace_bytes([T], hq, hkv)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
@@ -233,6 +240,47 @@ def main():
     except Exception as e:  # reported, never hidden
         batched = {"error": repr(e)}
 
+    # ---- mixed mode (BASELINE configs[4]): V token-wise, K channel-wise, one 64K-token sequence ---------
+    mixed = None
+    try:
+        wm = W.CONFIGS["mixed"]
+        im = W.make_inputs(wm, device="cuda")
+        cfg_m = b.Config(im["seq_lens"], wm.hq, wm.hkv, budget_bits=im["budgets"], s_obs=wm.s_obs,
+                         k_mode=b.RDKV_K_CHANNELWISE)
+        _, w_ch = b.rdkv_weights(cfg_m, im["K"], im["Q_obs"], want_channel=True)
+        bt_m, bc_m = b.rdkv_allocate(cfg_m, im["w_tok"], w_ch)       # Pareto token weights are supplied
+        cache_m = b.rdkv_pack(cfg_m, im["K"], im["V"], bt_m, bc_m)
+        st_m = cache_m.stats()
+        out_m = torch.empty((1, wm.hq, d), dtype=torch.float32, device="cuda")
+        lse_m = torch.empty((1, wm.hq), dtype=torch.float32, device="cuda")
+        fn_m = lambda: b.rdkv_decode_attn(cache_m, im["q"], out_m, lse_m)
+        for _ in range(3):
+            fn_m()
+        torch.cuda.synchronize()
+        gm = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gm):
+            for _ in range(8):
+                fn_m()
+        gm.replay()
+        ms_m = timed_ms(gm.replay, args.steps, torch) / 8
+        b.rdkv_kernel_timing_enable(True)
+        for _ in range(args.steps):
+            fn_m()
+        torch.cuda.synchronize()
+        nm, msm = b.rdkv_kernel_timing_read(b.RDKV_TIME_DECODE_TIERED)
+        b.rdkv_kernel_timing_enable(False)
+        km_ms = msm / max(nm, 1)
+        bytes_m = st_m["stored_bytes"] + wm.hq * d * (2 + 4)
+        mixed = {"workload": f"mixed: Hq={wm.hq}, Hkv={wm.hkv}, T={im['seq_lens'][0]}, avg budget {im['budgets'][0]} "
+                             "bit/elt, V token-wise, K channel-wise", "ms_decode_and_merge": ms_m,
+                 "kernel_ms": km_ms, "bytes": bytes_m, "achieved_gbs": bytes_m / (km_ms * 1e-3) / 1e9,
+                 "frac": bytes_m / (km_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "rows_16_8_4_2": st_m["rows"],
+                 "n_chunks": st_m["n_chunks"], "memory_ratio": st_m["dense_bytes"] / max(st_m["stored_bytes"], 1)}
+        cache_m.free()
+        del im
+    except Exception as e:  # reported, never hidden
+        mixed = {"error": repr(e)}
+
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample ----------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -284,7 +332,7 @@ def main():
                                f"avg budget {budgets[0]} bit/elt, token-wise tiers {{16,8,4,2,0}}, group 32",
                    "launch": "one rdkv_decode_attn call per layer, " + ("eager" if args.no_graph else "HIP graph replay"),
                    "tokens_per_s": 1e3 / ms_step},
-        "roofline": {"bound": "hbm", "kernel": "decode_tiered_kernel (per-layer launch)",
+        "roofline": {"bound": "hbm", "kernel": "decode_tiles_kernel (per-layer launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "bytes_per_launch": alg_bytes_layer, "kernel_ms": kern_ms,
                      "launches_timed": n_k},
@@ -297,6 +345,7 @@ def main():
                       "frac": bf16_bytes_layer / (k16_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "speedup_compressed_vs_bf16": ms_bf16 / ms_step},
         "batched_launch": batched,
+        "mixed_path": mixed,
         "compress": {"wall_ms_all_layers": compress_wall_ms,
                      "kernel_ms": {k: v[1] for k, v in kt.items()},
                      "launches": {k: v[0] for k, v in kt.items()}},

@@ -61,14 +61,12 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
   const int rows = ch.rows;
   const int ntiles = (rows + kTile - 1) / kTile;
 
-  // per-item layout, uniform over the workgroup
-  const int e16 = __builtin_amdgcn_readfirstlane(ikp->word_end[0]);
-  const int e8 = __builtin_amdgcn_readfirstlane(ikp->word_end[1]);
-  const int e4 = __builtin_amdgcn_readfirstlane(ikp->word_end[2]);
-  const int e2 = __builtin_amdgcn_readfirstlane(ikp->word_end[3]);
-  const int nwp = __builtin_amdgcn_readfirstlane(ikp->n_words_padded);
-  const int ns16 = __builtin_amdgcn_readfirstlane(ikp->n_steps16);
-  const int nqs = __builtin_amdgcn_readfirstlane(ikp->n_qsteps);
+  // shape of the item's K rows (uniform over the workgroup; it travels with the chunk so that the first loads
+  // need not wait for a second dependent fetch)
+  const int e16 = ch.k_word_end[0], e8 = ch.k_word_end[1], e4 = ch.k_word_end[2], e2 = ch.k_word_end[3];
+  const int nwp = (e2 + 1) & ~1;
+  const int ns16 = e16 >> 1;
+  const int nqs = (e8 - e16) + 2 * (e4 - e8) + 4 * (e2 - e4);
   const int n_steps = ns16 + nqs;
   const int kt_bytes = 256 * nwp, km_bytes = 32 * nqs;
   const LdsPlan plan(lds_steps, lds_qsteps, HS, g);   // the launch sized LDS for the largest item of the cache
@@ -241,8 +239,8 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
       floatx4 a16[HS], aqh[HS], aql[HS];
 #pragma unroll
       for (int hs = 0; hs < HS; ++hs) a16[hs] = aqh[hs] = aql[hs] = zero4;
-      // The tier boundaries are laundered once per tile: as loop invariants the sixty-odd comparisons below would
-      // be evaluated ahead of the tile loop and kept in scalar registers (thousands of spills).
+      // The tier boundaries are laundered once per tile: as loop invariants the comparisons below would be
+      // evaluated ahead of the tile loop and kept in scalar registers (thousands of spills).
       int t16 = e16, t8 = e8, t4 = e4, t2 = e2;
       asm volatile("" : "+s"(t16), "+s"(t8), "+s"(t4), "+s"(t2));
       // table address of word w's first step = tier base + w * (steps per word) * HS * 64
@@ -261,49 +259,81 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
           aql[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(a.h, bl.h, aql[hs], 0, 0, 0);
         }
       };
+      // one word of each tier; the word index is a compile-time constant (registers cannot be indexed at run time)
+      auto body16 = [&](auto wc) __attribute__((always_inline)) {   // a 16-bit step = two words = four bf16
+        constexpr int w = decltype(wc)::value;
+        if constexpr ((w & 1) == 0 && w + 1 < NW) {
+          // the two words pass through an empty asm: read as one 8-byte vector straight from kw[], the pair would
+          // keep the whole array out of registers (scalar replacement gives up on mixed-width accesses)
+          uint32_t lo = kw[w], hi = kw[w + 1];
+          asm("" : "+v"(lo), "+v"(hi));
+          const short4v a = bf4(lo, hi);
 #pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        if ((w & 1) == 0) __builtin_amdgcn_sched_barrier(0);   // keep the unpacking next to its use
-        if (w < t16) {
-          if ((w & 1) == 0) {   // a 16-bit step = two words = four bf16 (the 16-bit tier has an even word count)
-            // the two words pass through an empty asm: read as one 8-byte vector straight from kw[], the pair would
-            // keep the whole array out of registers (scalar replacement gives up on mixed-width accesses)
-            uint32_t lo = kw[w], hi = kw[w + 1 < NW ? w + 1 : w];
-            asm("" : "+v"(lo), "+v"(hi));
-            const short4v a = bf4(lo, hi);
-#pragma unroll
-            for (int hs = 0; hs < HS; ++hs) {
-              const uint2 braw = *reinterpret_cast<const uint2*>(s_qpre + (((w >> 1) * HS + hs) * 4 + j) * 8);
-              a16[hs] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, bf4(braw.x, braw.y), a16[hs], 0, 0, 0);
-            }
+          for (int hs = 0; hs < HS; ++hs) {
+            const uint2 braw = *reinterpret_cast<const uint2*>(s_qpre + (((w >> 1) * HS + hs) * 4 + j) * 8);
+            a16[hs] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, bf4(braw.x, braw.y), a16[hs], 0, 0, 0);
           }
-        } else if (w < t8) {
-          Pack4 a;
-          a.u[0] = __builtin_amdgcn_perm(0u, kw[w], 0x0C020C00u);
-          a.u[1] = __builtin_amdgcn_perm(0u, kw[w], 0x0C030C01u);
-          qstep(a, wt8 + w * (HS * 64));
-        } else if (w < t4) {
-          const uint32_t c0 = kw[w], c1 = c0 >> 8;
-          const uint8_t* o = wt4 + 2 * w * (HS * 64);
-          Pack4 a;
-          a.u[0] = c0 & 0x000F000Fu; a.u[1] = c0 & 0x00F000F0u;
-          qstep(a, o);
-          a.u[0] = c1 & 0x000F000Fu; a.u[1] = c1 & 0x00F000F0u;
-          qstep(a, o + HS * 64);
-        } else if (w < t2) {
-          const uint32_t c0 = kw[w], c1 = c0 >> 6, c2 = c0 >> 12;
-          const uint8_t* o = wt2 + 4 * w * (HS * 64);
-          Pack4 a;
-          a.u[0] = c0 & 0x00030003u; a.u[1] = c0 & 0x000C000Cu;     // fields 0, 1
-          qstep(a, o);
-          a.u[0] = c0 & 0x00300030u; a.u[1] = c1 & 0x00030003u;     // fields 2, 3
-          qstep(a, o + HS * 64);
-          a.u[0] = c1 & 0x000C000Cu; a.u[1] = c1 & 0x00300030u;     // fields 4, 5
-          qstep(a, o + 2 * HS * 64);
-          a.u[0] = c2 & 0x00030003u; a.u[1] = c2 & 0x000C000Cu;     // fields 6, 7
-          qstep(a, o + 3 * HS * 64);
         }
-      }
+      };
+      auto body8 = [&](auto wc) __attribute__((always_inline)) {
+        constexpr int w = decltype(wc)::value;
+        Pack4 a;
+        a.u[0] = __builtin_amdgcn_perm(0u, kw[w], 0x0C020C00u);
+        a.u[1] = __builtin_amdgcn_perm(0u, kw[w], 0x0C030C01u);
+        qstep(a, wt8 + w * (HS * 64));
+      };
+      auto body4 = [&](auto wc) __attribute__((always_inline)) {
+        constexpr int w = decltype(wc)::value;
+        const uint32_t c0 = kw[w], c1 = c0 >> 8;
+        const uint8_t* o = wt4 + 2 * w * (HS * 64);
+        Pack4 a;
+        a.u[0] = c0 & 0x000F000Fu; a.u[1] = c0 & 0x00F000F0u;
+        qstep(a, o);
+        a.u[0] = c1 & 0x000F000Fu; a.u[1] = c1 & 0x00F000F0u;
+        qstep(a, o + HS * 64);
+      };
+      auto body2 = [&](auto wc) __attribute__((always_inline)) {
+        constexpr int w = decltype(wc)::value;
+        const uint32_t c0 = kw[w], c1 = c0 >> 6, c2 = c0 >> 12;
+        const uint8_t* o = wt2 + 4 * w * (HS * 64);
+        Pack4 a;
+        a.u[0] = c0 & 0x00030003u; a.u[1] = c0 & 0x000C000Cu;     // fields 0, 1
+        qstep(a, o);
+        a.u[0] = c0 & 0x00300030u; a.u[1] = c1 & 0x00030003u;     // fields 2, 3
+        qstep(a, o + HS * 64);
+        a.u[0] = c1 & 0x000C000Cu; a.u[1] = c1 & 0x00300030u;     // fields 4, 5
+        qstep(a, o + 2 * HS * 64);
+        a.u[0] = c2 & 0x00030003u; a.u[1] = c2 & 0x000C000Cu;     // fields 6, 7
+        qstep(a, o + 3 * HS * 64);
+      };
+      // A tier is a run of consecutive words [first, end): jump to its first word and fall through word by word
+      // until the end (one uniform comparison per word; a test of every word against every tier costs several
+      // times the branches and leaves accumulator copies at every merge).
+#define RDKV_K_CASE(BODY_, END_, W_)                \
+  case (W_):                                        \
+    if constexpr ((W_) < NW) {                      \
+      if ((W_) >= (END_)) break;                    \
+      BODY_(GroupIndex<(W_)>{});                    \
+    }                                               \
+    [[fallthrough]];
+#define RDKV_K_CASE4(BODY_, END_, W_) \
+  RDKV_K_CASE(BODY_, END_, W_) RDKV_K_CASE(BODY_, END_, W_ + 1) RDKV_K_CASE(BODY_, END_, W_ + 2) RDKV_K_CASE(BODY_, END_, W_ + 3)
+#define RDKV_K_CASE16(BODY_, END_, W_) \
+  RDKV_K_CASE4(BODY_, END_, W_) RDKV_K_CASE4(BODY_, END_, W_ + 4) RDKV_K_CASE4(BODY_, END_, W_ + 8) RDKV_K_CASE4(BODY_, END_, W_ + 12)
+#define RDKV_K_TIER(BODY_, FIRST_, END_)                                                                      \
+  switch (FIRST_) {                                                                                           \
+    RDKV_K_CASE16(BODY_, END_, 0) RDKV_K_CASE16(BODY_, END_, 16) RDKV_K_CASE16(BODY_, END_, 32)               \
+    RDKV_K_CASE16(BODY_, END_, 48)                                                                            \
+    default: break;                                                                                           \
+  }
+      RDKV_K_TIER(body16, 0, t16)
+      RDKV_K_TIER(body8, t16, t8)
+      RDKV_K_TIER(body4, t8, t4)
+      RDKV_K_TIER(body2, t4, t2)
+#undef RDKV_K_TIER
+#undef RDKV_K_CASE16
+#undef RDKV_K_CASE4
+#undef RDKV_K_CASE
 #pragma unroll
       for (int hs = 0; hs < HS; ++hs)
 #pragma unroll

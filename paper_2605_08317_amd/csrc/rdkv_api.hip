@@ -577,7 +577,9 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   c->stored_bytes = stored;
 
   // byte-balanced chunks: every workgroup streams about the same number of stored bytes
-  int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>(24 << 10, stored / 2048));
+  // (a mixed-mode chunk has more set-up per workgroup, and its kernel keeps 3 workgroups per CU resident:
+  // 40 KB chunks keep a single 64K-token sequence within one round of workgroups)
+  int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>((mixed ? 40 : 24) << 10, stored / 2048));
   if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
   for (int64_t i = 0; i < n; ++i) {
@@ -604,6 +606,7 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
         ch.tier = bits;
         ch.item = static_cast<int32_t>(i);
         ch.slot = static_cast<int32_t>(c->chunks.size());
+        for (int t2 = 0; t2 < 4; ++t2) ch.k_word_end[t2] = mixed ? c->items_k[i].word_end[t2] : int16_t(0);
         c->chunks.push_back(ch);
       }
     }

@@ -30,6 +30,7 @@ struct Chunk {
   int32_t tier;                             // 16, 8, 4, 2
   int32_t item;                             // sequence * hkv + kv head
   int32_t slot;                             // partial-result slot
+  int16_t k_word_end[4];                    // mixed mode: ItemK::word_end of the item (the shape of its K rows)
 };
 
 // Channel-wise K (mixed mode): how one item's K tiles are laid out.  Channels are sorted by bit-width into

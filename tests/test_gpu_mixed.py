@@ -51,6 +51,9 @@ CASES = [
     ("tiny", {"seq_lens": (500,)}, [.2, .2, .2, .2, .2], [1., .0, .0, .0, .0]),            # every channel evicted
     ("tiny", {"seq_lens": (900,), "hq": 2, "hkv": 2}, [.5, .2, .2, .1, .0], [.2, .2, .2, .2, .2]),
     ("batch70b", {"batch": 3, "len_range": (100, 1300)}, [.5, .2, .2, .05, .05], [.05, .45, .35, .1, .05]),
+    # 8 query heads per KV head with short K rows (2- and 4-bit channels only) and with the longest ones (all 16-bit)
+    ("batch70b", {"batch": 2, "len_range": (300, 900)}, [.3, .3, .2, .1, .1], [.2, .6, .2, .0, .0]),
+    ("batch70b", {"batch": 2, "len_range": (200, 500)}, [.3, .3, .2, .1, .1], [.0, .0, .0, .1, .9]),
 ]
 
 

@@ -19,6 +19,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 constexpr int kTokPerWG = 256;
+constexpr int kRowsPerStage = 128;          // window rows staged in LDS at a time (39 KB per workgroup: 4 per CU)
 constexpr int kQStride = kHeadDim + 8;      // bf16 elements per LDS row (272 B: conflict-free 16-byte reads)
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLogitScale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
@@ -53,8 +54,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 template <int PASS>
 __global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t* sQ = reinterpret_cast<uint16_t*>(smem_raw);                        // [R_pad][kQStride]
-  float* sStat = reinterpret_cast<float*>(smem_raw + a.R_pad * kQStride * 2);   // [4 waves][R_pad][2] / [4][128]
+  uint16_t* sQ = reinterpret_cast<uint16_t*>(smem_raw);                              // [kRowsPerStage][kQStride]
+  float* sStat = reinterpret_cast<float*>(smem_raw + kRowsPerStage * kQStride * 2);   // [4 waves][kRowsPerStage][2]
 
   const int item = blockIdx.y;
   const int T = a.item_T[item];
@@ -65,14 +66,7 @@ __global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
   const int seq = item / a.hkv, head = item % a.hkv;
   const int64_t blk = a.item_blk_off[item] + blockIdx.x;
 
-  // stage the R window rows of this KV head (contiguous in Q_obs) into LDS; pad rows are zero
   const uint16_t* Qg = a.Q + (static_cast<int64_t>(seq) * a.hq + head * a.g) * a.s_obs * kHeadDim;
-  for (int i = tid; i < a.R_pad * (kHeadDim / 8); i += 256) {
-    const int r = i >> 4, c8 = i & 15;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < a.R) v = *reinterpret_cast<const uint4*>(Qg + r * kHeadDim + c8 * 8);
-    *reinterpret_cast<uint4*>(sQ + r * kQStride + c8 * 8) = v;
-  }
 
   // this wavefront's 64 keys as A operands: a_op[tt][kb] = key (tt*16 + l16), channels kb*32 + quad*8 .. +7
   const uint16_t* Kh = a.K + a.item_row_off[item] * kHeadDim;
@@ -111,26 +105,73 @@ __global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
 
   // does any row of this block need the causal mask?  keys <= T - s_obs are visible to every row
   const bool need_mask = a.causal && (tok0 + kTokPerWG > T - a.s_obs + 1);
-  const int n_rt = a.R_pad / 16;
+  // nearly every block of a long context has 256 valid keys, all visible to every row: no masks, and the logit
+  // scale goes into the fused multiply-add that feeds exp2 (4 plain-ALU instructions per logit instead of 9)
+  const bool fast = !need_mask && (tok0 + kTokPerWG <= T) && (a.R == a.R_pad);
   float colsum[4][4];
 #pragma unroll
   for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
     for (int i = 0; i < 4; ++i) colsum[tt][i] = 0.f;
 
-  for (int rt = 0; rt < n_rt; ++rt) {
+  // The window rows pass through LDS kRowsPerStage at a time (the keys stay in registers): a workgroup then needs
+  // 39 KB instead of 78 KB for 256 rows and four of them fit a CU.
+  for (int r0 = 0; r0 < a.R_pad; r0 += kRowsPerStage) {
+  const int nrows = min(kRowsPerStage, a.R_pad - r0);
+  __syncthreads();   // the previous stage's readers are done
+  // stage rows r0 .. r0 + nrows of this KV head (contiguous in Q_obs) into LDS; pad rows are zero
+  for (int i = tid; i < nrows * (kHeadDim / 8); i += 256) {
+    const int r = i >> 4, c8 = i & 15;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r0 + r < a.R) v = *reinterpret_cast<const uint4*>(Qg + (r0 + r) * kHeadDim + c8 * 8);
+    *reinterpret_cast<uint4*>(sQ + r * kQStride + c8 * 8) = v;
+  }
+  if (PASS == 2)   // the rows' log-sum-exp, read once per row tile below
+    for (int r = tid; r < nrows; r += 256) sStat[r] = a.lse[static_cast<int64_t>(item) * a.R_pad + r0 + r];
+  __syncthreads();
+  for (int rt = 0; rt < nrows / 16; ++rt) {
     floatx4 acc[4];
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) acc[tt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const int row = rt * 16 + l16;
+    const int lrow = rt * 16 + l16, row = r0 + lrow;   // row inside the stage / of the window
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) {
-      const bf16x8 b_op = *reinterpret_cast<const bf16x8*>(sQ + row * kQStride + kb * 32 + quad * 8);
+      const bf16x8 b_op = *reinterpret_cast<const bf16x8*>(sQ + lrow * kQStride + kb * 32 + quad * 8);
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt)
         acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_op[tt][kb], b_op, acc[tt], 0, 0, 0);
     }
     // acc[tt][i] = q_row . k_tok with tok = wtok0 + tt*16 + quad*4 + i, row = rt*16 + l16
+    if (fast) {
+      if (PASS == 1) {
+        float mx = acc[0][0];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) mx = fmaxf(mx, acc[tt][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx *= kLogitScale;                       // the scale is positive: the maximum of the scaled logits
+        float ls = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) ls += fast_exp2(__builtin_fmaf(acc[tt][i], kLogitScale, -mx));
+        ls += __shfl_xor(ls, 16);
+        ls += __shfl_xor(ls, 32);
+        if (quad == 0) {
+          sStat[(wave * kRowsPerStage + lrow) * 2] = mx;
+          sStat[(wave * kRowsPerStage + lrow) * 2 + 1] = ls;
+        }
+      } else {
+        const float nlse = -sStat[lrow];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) colsum[tt][i] += fast_exp2(__builtin_fmaf(acc[tt][i], kLogitScale, nlse));
+      }
+      continue;
+    }
     const int limit = a.causal ? (T - a.s_obs + (row % a.s_obs)) : (T - 1);   // last visible key of this row
     const bool row_ok = row < a.R;
     float x[4][4];
@@ -159,11 +200,11 @@ __global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
       ls += __shfl_xor(ls, 16);
       ls += __shfl_xor(ls, 32);
       if (quad == 0) {
-        sStat[(wave * a.R_pad + row) * 2] = mx;
-        sStat[(wave * a.R_pad + row) * 2 + 1] = ls;
+        sStat[(wave * kRowsPerStage + lrow) * 2] = mx;
+        sStat[(wave * kRowsPerStage + lrow) * 2 + 1] = ls;
       }
     } else {
-      const float lse = a.lse[static_cast<int64_t>(item) * a.R_pad + row];
+      const float lse = sStat[lrow];
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
@@ -171,19 +212,23 @@ __global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
     }
   }
 
-  if (PASS == 1) {
+  if (PASS == 1) {   // this block's (maximum, sum) of the stage's rows: merge the four wavefronts
     __syncthreads();
-    for (int r = tid; r < a.R_pad; r += 256) {
+    for (int r = tid; r < nrows; r += 256) {
       float m = kNegBig;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) m = fmaxf(m, sStat[(w * a.R_pad + r) * 2]);
+      for (int w = 0; w < 4; ++w) m = fmaxf(m, sStat[(w * kRowsPerStage + r) * 2]);
       float l = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) l += sStat[(w * a.R_pad + r) * 2 + 1] * fast_exp2(sStat[(w * a.R_pad + r) * 2] - m);
-      a.row_part[(blk * a.R_pad + r) * 2] = m;
-      a.row_part[(blk * a.R_pad + r) * 2 + 1] = l;
+      for (int w = 0; w < 4; ++w)
+        l += sStat[(w * kRowsPerStage + r) * 2 + 1] * fast_exp2(sStat[(w * kRowsPerStage + r) * 2] - m);
+      a.row_part[(blk * a.R_pad + r0 + r) * 2] = m;
+      a.row_part[(blk * a.R_pad + r0 + r) * 2 + 1] = l;
     }
-  } else {
+  }
+  }   // stages
+
+  if (PASS == 2) {
     float* w_out = a.w_raw + a.item_row_off[item];
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt)
@@ -277,8 +322,7 @@ hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off,
   a.w_raw = a.lse + n_items * a.R_pad;
   a.ksq_part = w_ch ? a.w_raw + total_tokens : nullptr;
   const int max_blk = (max_T + kTokPerWG - 1) / kTokPerWG;
-  const size_t lds = static_cast<size_t>(a.R_pad) * kQStride * 2 +
-                     std::max<size_t>(4 * static_cast<size_t>(a.R_pad) * 2 * sizeof(float), 4 * kHeadDim * sizeof(float));
+  const size_t lds = static_cast<size_t>(kRowsPerStage) * kQStride * 2 + 4 * kRowsPerStage * 2 * sizeof(float);
   hipError_t e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(weights_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize,
                           static_cast<int>(lds));

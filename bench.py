@@ -38,6 +38,11 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch the per-layer calls eagerly")
     ap.add_argument("--per-layer-only", action="store_true",
                     help="skip the bf16, batched and mixed-mode legs (kernel traces of the per-layer launches alone)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="per-tier roofline points on the stack128k layer shape: explicit all-16/8/4/2 bit maps and "
+                         "budgets 0.4..8 bit/elt, --sweep-batch sequences of 128K tokens per launch; prints one JSON line")
+    ap.add_argument("--sweep-batch", type=int, default=4)
+    ap.add_argument("--sweep-only", default="", help="comma list of sweep points to run (e.g. all-2,b0.4)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter-collection mode for `rocprofv3 --pmc`: build the caches, run --steps eager decode "
                          "steps, the batched launch, the bf16 path and a 1 GiB device-to-device copy, then exit")
@@ -80,6 +85,60 @@ def pmc_probe(args, torch, b, step_eager, K_all, V_all, Qobs_all, q_all, Ks, Vs,
                       "stored_bytes_per_layer": sum(c_.stats()["stored_bytes"] for c_ in [cache_b]) / L}))
 
 
+def sweep(args, torch, b, W):
+    """Decode bandwidth tier by tier: one launch over --sweep-batch sequences of the stack128k layer shape (distinct
+    synthetic data per sequence, more bytes than the 256 MB last-level cache for every point but the sparsest)."""
+    wl = W.CONFIGS["stack128k"]
+    B, T, hq, hkv, d = args.sweep_batch, wl.seq_lens[0], wl.hq, wl.hkv, wl.d
+    per_seq = hkv * T * d
+    K = torch.empty(B * per_seq, dtype=torch.bfloat16, device="cuda")
+    V = torch.empty(B * per_seq, dtype=torch.bfloat16, device="cuda")
+    Qobs = torch.empty((B, hq, wl.s_obs, d), dtype=torch.bfloat16, device="cuda")
+    q = torch.empty((B, hq, d), dtype=torch.bfloat16, device="cuda")
+    for s_ in range(B):
+        inp = W.make_inputs(wl, device="cuda", layer=s_)
+        K[s_ * per_seq:(s_ + 1) * per_seq] = inp["K"]
+        V[s_ * per_seq:(s_ + 1) * per_seq] = inp["V"]
+        Qobs[s_] = inp["Q_obs"][0]
+        q[s_] = inp["q"][0]
+        del inp
+    out = torch.empty((B, hq, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, hq), dtype=torch.float32, device="cuda")
+    points = [("all-16", 16), ("all-8", 8), ("all-4", 4), ("all-2", 2)] + [(f"b{x}", float(x)) for x in (0.4, 1, 2, 4, 8)]
+    only = [x for x in args.sweep_only.split(",") if x]
+    res = []
+    for name, val in points:
+        if only and name not in only:
+            continue
+        if name.startswith("all-"):
+            cfg = b.Config([T] * B, hq, hkv, s_obs=wl.s_obs)
+            bits = torch.full((B * hkv * T,), int(val), dtype=torch.uint8, device="cuda")
+            cache = b.rdkv_pack(cfg, K, V, bits)
+            del bits
+        else:
+            cfg = b.Config([T] * B, hq, hkv, budget_bits=[val] * B, s_obs=wl.s_obs)
+            cache = b.rdkv_compress(cfg, K, V, Qobs)
+        st = cache.stats()
+        fn = lambda: b.rdkv_decode_attn(cache, q, out, lse)
+        for _ in range(3):
+            fn()
+        ms = timed_ms(fn, args.steps, torch)
+        b.rdkv_kernel_timing_enable(True)
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        n_k, ms_k = b.rdkv_kernel_timing_read(b.RDKV_TIME_DECODE_TIERED)
+        b.rdkv_kernel_timing_enable(False)
+        k_ms = ms_k / max(n_k, 1)
+        nbytes = st["stored_bytes"] + B * hq * d * (2 + 4)
+        res.append({"point": name, "rows_16_8_4_2": st["rows"], "bytes": nbytes, "n_chunks": st["n_chunks"],
+                    "ms_decode_and_merge": ms, "kernel_ms": k_ms, "achieved_gbs": nbytes / (k_ms * 1e-3) / 1e9,
+                    "frac": nbytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        cache.free()
+    print(json.dumps({"sweep": res, "launch": f"{B} sequences x {T} tokens, Hq={hq}, Hkv={hkv}",
+                      "kernel_ms": "HIP events around the decode kernels of a launch (the merge is in ms_decode_and_merge)"}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -92,6 +151,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.sweep:
+        sweep(args, torch, b, W)
+        return
     wl = W.CONFIGS[args.workload]
     if args.ctx:
         wl = W.scaled(wl, seq_lens=(args.ctx,))

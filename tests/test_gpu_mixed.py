@@ -164,3 +164,27 @@ def test_mixed_workload_staged_pass_and_fused_compress():
     np.testing.assert_array_equal(cache2.export(b.RDKV_EXPORT_BITS_TOK, np.uint8).reshape(wl.hkv, -1), bt)
     _assert_cache_equal_mixed(b, cache2, O.build_cache_mixed(Ks, Vs, [bt], [bc]))
     cache2.free()
+
+
+@pytest.mark.parametrize("r_k", [0.4, 0.6])
+def test_allocate_mixed_with_other_kv_splits(r_k):
+    """B_K = r_K B_head (Sec. 3.2; Table 8 varies r_K): the V map takes 2 (1 - r_K) of the average budget, the K
+    channels the rest spread over the retained tokens."""
+    b = B()
+    hkv, hq, T = 2, 8, 6000
+    rng = np.random.default_rng(11)
+    w_tok = (1.0 + rng.pareto(1.2, (hkv, T))).astype(np.float32)
+    w_ch = np.exp(rng.normal(0, 1.0, (hkv, 128))).astype(np.float32)
+    cfg = b.Config([T], hq, hkv, budget_bits=[1.5], k_mode=b.RDKV_K_CHANNELWISE, kv_split_rk=r_k)
+    print(f"[case] allocate mixed r_K={r_k}", flush=True)
+    bits_tok, bits_ch = b.rdkv_allocate(cfg, torch.from_numpy(w_tok.reshape(-1)).cuda(),
+                                        torch.from_numpy(w_ch.reshape(-1)).cuda())
+    torch.cuda.synchronize()
+    got_t, got_c = bits_tok.cpu().numpy().reshape(hkv, T), bits_ch.cpu().numpy().reshape(hkv, 128)
+    for h in range(hkv):
+        rt, rc = O.allocate_mixed(w_tok[h], w_ch[h], np.float32(1.5), r_k=np.float32(r_k))
+        np.testing.assert_array_equal(got_t[h], rt)
+        np.testing.assert_array_equal(got_c[h], rc)
+        n_kept = int((rt > 0).sum())
+        total_bits = int(rt.astype(np.int64).sum()) * 128 + int(rc.astype(np.int64).sum()) * n_kept
+        assert total_bits <= 1.5 * 2 * T * 128                    # whole-cache budget

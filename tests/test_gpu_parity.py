@@ -284,3 +284,45 @@ def test_compress_then_decode(name, kw):
     total = sum(a.size for a in ref["bits"])
     assert differ <= max(2, 2e-3 * total)
     cache.free()
+
+
+# ----------------------------------------------------------------------------
+# allocator variants as parameters (Table 4's ablation shapes): tier subsets with their own distortion table
+# ----------------------------------------------------------------------------
+def _eps_for(tiers):
+    table = dict(zip(O.TIERS, O.EPS_V_LLAMA31_8B))
+    return [np.float32(table[t]) for t in tiers]
+
+
+@pytest.mark.parametrize("label,tiers,budget", [
+    ("quant-only", (2, 4, 8, 16), 4.0),      # no eviction: every token keeps at least 2 bits
+    ("evict-only", (0, 16), 3.0),            # bi-state
+    ("tri-state", (0, 4, 16), 2.0),
+])
+def test_tier_subsets_compress_then_decode(label, tiers, budget):
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(1500,), budgets=(budget,))
+    eps = _eps_for(tiers)
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs,
+                   tiers=list(tiers), eps_v=eps)
+    print(f"[case] tier subset {label}: tiers={tiers} budget={budget}", flush=True)
+    cache = b.rdkv_compress(cfg, dev["K"], dev["V"], dev["Q_obs"])
+    w_tok, _ = b.rdkv_weights(cfg, dev["K"], dev["Q_obs"])
+    torch.cuda.synchronize()
+    w_list = [x.cpu().numpy() for x in W.split_sequences(w_tok, inp["seq_lens"], wl.hkv, None)]
+    Ks = _split(inp["K"], inp["seq_lens"], wl.hkv, wl.d)
+    Vs = _split(inp["V"], inp["seq_lens"], wl.hkv, wl.d)
+    Qs = [_np(inp["Q_obs"][s]) for s in range(len(inp["seq_lens"]))]
+    ref = O.compress_tokenwise(Ks, Vs, Qs, [np.float32(budget)], tiers=tiers, eps=tuple(float(e) for e in eps),
+                               weights_override=w_list)
+    bits = cache.export(b.RDKV_EXPORT_BITS_TOK, np.uint8)
+    np.testing.assert_array_equal(bits, np.concatenate([x.reshape(-1) for x in ref["bits"]]))
+    assert set(np.unique(bits).tolist()) <= set(tiers)
+    if 0 not in tiers:
+        assert bits.min() >= 2                                   # a token always costs at least the lowest tier
+    _assert_cache_equal(b, cache, ref)
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    ref_out, ref_lse = O.decode(ref, _np(inp["q"]))
+    _check_decode(out, lse, ref_out, ref_lse)
+    cache.free()

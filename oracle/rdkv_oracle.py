@@ -1003,11 +1003,30 @@ def attention_rows(q, Kh, Vh):
     return (e / l) @ Vh, (zmax + np.log(l))[:, 0]
 
 
+def append_tokens(cache, k_new, v_new):
+    """Zone C of Sec. 3.3 (third term of Eq. 7): tokens generated after the compression
+    pass are kept uncompressed and attended to like any other row.  The paper keeps them
+    in FP16; here the bf16 input values are kept verbatim (as for the 16-bit tier).
+    k_new, v_new: float32 [batch, Hkv, d], bf16-exact: one new token per sequence.
+    The rows are appended to cache['tail'][item] = (K rows, V rows)."""
+    k_new = _check_bf16_exact(k_new, "k_new")
+    v_new = _check_bf16_exact(v_new, "v_new")
+    hkv, d = cache["hkv"], cache["d"]
+    batch = len(cache["seq_lens"])
+    assert k_new.shape == (batch, hkv, d) and v_new.shape == (batch, hkv, d)
+    tail = cache.setdefault("tail", [(np.zeros((0, d)), np.zeros((0, d))) for _ in range(batch * hkv)])
+    for s in range(batch):
+        for h in range(hkv):
+            tk, tv = tail[s * hkv + h]
+            tail[s * hkv + h] = (np.concatenate([tk, k_new[s, h][None].astype(np.float64)]),
+                                 np.concatenate([tv, v_new[s, h][None].astype(np.float64)]))
+
+
 def decode(cache, q):
     """One decode step over a packed cache (token-wise or mixed).  q: [batch, Hq, d]
     (bf16 exact).  Every retained token enters with its dequantised K row and V row;
-    evicted tokens (tier 0) are absent and evicted K channels are zero (Eq. 7 without
-    the new-token zone).
+    evicted tokens (tier 0) are absent and evicted K channels are zero; appended tokens
+    (append_tokens) enter with their bf16 rows (Eq. 7).
     Returns out float64 [batch, Hq, d], lse float64 [batch, Hq]."""
     q = np.asarray(q, dtype=np.float64)
     batch, Hq, d = q.shape
@@ -1019,6 +1038,8 @@ def decode(cache, q):
         for h in range(hkv):
             item = s * hkv + h
             Kh, Vh = unpack_item_mixed(cache, item) if cache.get("mixed") else unpack_item(cache, item)
+            if "tail" in cache:
+                Kh, Vh = np.concatenate([Kh, cache["tail"][item][0]]), np.concatenate([Vh, cache["tail"][item][1]])
             o, l = attention_rows(q[s, h * g:(h + 1) * g], Kh, Vh)
             out[s, h * g:(h + 1) * g] = o
             lse[s, h * g:(h + 1) * g] = l

@@ -1,13 +1,10 @@
-// Split-K flash-decode over row-major tier segments (Sec. 3.3, Eq. 7) for gfx950.
+// Split-K flash-decode over row-major bf16 rows (Sec. 3.3, Eq. 7) for gfx950: the uncompressed path and the
+// 16-bit tier of a token-wise cache, and the log-sum-exp merge of split partials.
 //
-// One workgroup (4 wavefronts) streams one chunk of rows of one tier of one
-// (sequence, KV head).  Sixteen lanes share a token: each lane owns 8 of the 128
-// channels, so a wavefront covers 4 tokens per load and a K/V byte is read once
-// for all g query heads of the group.  Low-bit codes are unpacked in registers;
-// the K product uses the fusion identity of App. B (scale and offset applied to
-// the per-group partial sums, not to every element).  Online softmax runs per
-// 16-lane row with DPP reductions; rows, wavefronts and chunks are merged by
-// log-sum-exp weights (rows and wavefronts in LDS, chunks by merge_kernel).
+// One workgroup (4 wavefronts) streams one chunk of rows of one (sequence, KV head).  Sixteen lanes share a token:
+// each lane owns 8 of the 128 channels, so a wavefront covers 4 tokens per load and a K/V byte is read once for
+// all g query heads of the group.  Online softmax runs per 16-lane row with DPP reductions; rows, wavefronts and
+// chunks are merged by log-sum-exp weights (rows and wavefronts in LDS, chunks by the merge kernels).
 #include "rdkv_internal.h"
 
 namespace rdkv {
@@ -35,61 +32,23 @@ __device__ __forceinline__ float row16_sum(float v) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
-  return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<unsigned short>(h & 0xFFFFu)));
-}
-
-// Raw bytes one lane holds for one row: 8 channels at TIER bits each.
-template <int TIER>
-struct LaneRaw;
-template <>
-struct LaneRaw<16> { uint4 v; };
-template <>
-struct LaneRaw<8> { uint2 v; };
-template <>
-struct LaneRaw<4> { uint32_t v; };
-template <>
-struct LaneRaw<2> { uint16_t v; };
-
-template <int TIER>
-__device__ __forceinline__ LaneRaw<TIER> load_lane(const uint8_t* __restrict__ base, int row, int c16) {
-  LaneRaw<TIER> r;
-  const uint8_t* p = base + static_cast<int64_t>(row) * (TIER * 16) + c16 * TIER;
-  if constexpr (TIER == 16) r.v = *reinterpret_cast<const uint4*>(p);
-  if constexpr (TIER == 8) r.v = *reinterpret_cast<const uint2*>(p);
-  if constexpr (TIER == 4) r.v = *reinterpret_cast<const uint32_t*>(p);
-  if constexpr (TIER == 2) r.v = *reinterpret_cast<const uint16_t*>(p);
-  return r;
-}
-
-// 8 channel values as floats: bf16 values for tier 16, integer codes otherwise.
-template <int TIER>
-__device__ __forceinline__ void unpack8(const LaneRaw<TIER>& r, float (&x)[8]) {
-  if constexpr (TIER == 16) {
-    const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
+// 8 bf16 channel values of one row held by a lane, as floats
+__device__ __forceinline__ void unpack8(const uint4& r, float (&x)[8]) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      x[2 * i] = __uint_as_float(w[i] << 16);
-      x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-    }
-  } else if constexpr (TIER == 8) {
-    const uint32_t w[2] = {r.v.x, r.v.y};
-#pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = static_cast<float>((w[i >> 2] >> (8 * (i & 3))) & 0xFFu);
-  } else if constexpr (TIER == 4) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = static_cast<float>((r.v >> (4 * i)) & 0xFu);
-  } else {
-    const uint32_t w = r.v;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = static_cast<float>((w >> (2 * i)) & 0x3u);
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = __uint_as_float(w[i] << 16);
+    x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
   }
 }
 
+__device__ __forceinline__ uint4 load_lane(const uint8_t* __restrict__ base, int row, int c16) {
+  return *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(row) * (kHeadDim * 2) + c16 * 16);
+}
+
 // Streams `rows` rows and leaves the chunk's unnormalised result in part_acc / part_ml.
-template <int TIER, int G>
-__device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ km,
-                                             const uint8_t* __restrict__ vd, const uint8_t* __restrict__ vm,
+template <int G>
+__device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ vd,
                                              int rows, const uint16_t* __restrict__ q,
                                              float* __restrict__ part_acc, float* __restrict__ part_ml,
                                              float* smem) {
@@ -98,19 +57,12 @@ __device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, con
   // logits are kept in the log2 domain: q is scaled by log2(e) / sqrt(d)
   const float qscale = 1.4426950408889634f * 0.08838834764831845f;
 
-  float qv[G][8], qsum[G];
+  float qv[G][8];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    LaneRaw<16> raw;
-    raw.v = *reinterpret_cast<const uint4*>(q + h * kHeadDim + c16 * 8);
-    unpack8<16>(raw, qv[h]);
-    float s = 0.f;
+    unpack8(*reinterpret_cast<const uint4*>(q + h * kHeadDim + c16 * 8), qv[h]);
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      qv[h][c] *= qscale;
-      s += qv[h][c];
-    }
-    qsum[h] = s;
+    for (int c = 0; c < 8; ++c) qv[h][c] *= qscale;
   }
 
   float m[G], l[G], acc[G][8];
@@ -124,40 +76,23 @@ __device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, con
 
   const int last = rows - 1;
   for (int base = wave * 16; base < rows; base += kWaves * 16) {
-    LaneRaw<TIER> kr[4], vr[4];
-    uint32_t kmeta[4], vmeta[4];
+    uint4 kr[4], vr[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = min(base + u * 4 + r, last);
-      kr[u] = load_lane<TIER>(kd, row, c16);
-      if constexpr (TIER != 16)
-        kmeta[u] = *reinterpret_cast<const uint32_t*>(km + static_cast<int64_t>(row) * 16 + (c16 >> 2) * 4);
-    }
+    for (int u = 0; u < 4; ++u) kr[u] = load_lane(kd, min(base + u * 4 + r, last), c16);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = min(base + u * 4 + r, last);
-      vr[u] = load_lane<TIER>(vd, row, c16);
-      if constexpr (TIER != 16)
-        vmeta[u] = *reinterpret_cast<const uint32_t*>(vm + static_cast<int64_t>(row) * 16 + (c16 >> 2) * 4);
-    }
+    for (int u = 0; u < 4; ++u) vr[u] = load_lane(vd, min(base + u * 4 + r, last), c16);
 
     float s[4][G];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float kx[8];
-      unpack8<TIER>(kr[u], kx);
-      float sc = 1.f, off = 0.f;
-      if constexpr (TIER != 16) {
-        sc = half_bits_to_float(kmeta[u]);
-        off = half_bits_to_float(kmeta[u] >> 16);
-      }
+      unpack8(kr[u], kx);
       const bool valid = (base + u * 4 + r) < rows;
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         float dot = 0.f;
 #pragma unroll
         for (int c = 0; c < 8; ++c) dot = __builtin_fmaf(qv[h][c], kx[c], dot);
-        if constexpr (TIER != 16) dot = __builtin_fmaf(dot, sc, off * qsum[h]);
         dot = row16_sum(dot);
         s[u][h] = valid ? dot : -INFINITY;
       }
@@ -192,13 +127,7 @@ __device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, con
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float vx[8];
-      unpack8<TIER>(vr[u], vx);
-      if constexpr (TIER != 16) {
-        const float sc = half_bits_to_float(vmeta[u]);
-        const float off = half_bits_to_float(vmeta[u] >> 16);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) vx[c] = __builtin_fmaf(vx[c], sc, off);
-      }
+      unpack8(vr[u], vx);
 #pragma unroll
       for (int h = 0; h < G; ++h)
 #pragma unroll
@@ -269,8 +198,7 @@ __global__ __launch_bounds__(kWG) void decode_dense_kernel(DenseArgs a) {
   const int seq = a.seq_base + sl;
   const uint16_t* q = a.q + (static_cast<int64_t>(seq) * a.hq + head * G) * kHeadDim;
   const int64_t slot = (static_cast<int64_t>(sl) * a.hkv + head) * a.max_splits + split;
-  process_rows<16, G>(kd, nullptr, vd, nullptr, rows, q, a.part_acc + slot * G * kHeadDim,
-                      a.part_ml + slot * G * 2, smem);
+  process_rows<G>(kd, vd, rows, q, a.part_acc + slot * G * kHeadDim, a.part_ml + slot * G * 2, smem);
 }
 
 template <int G>
@@ -284,16 +212,8 @@ __global__ __launch_bounds__(kWG) void decode_tiered_kernel(const Chunk* __restr
   const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * G) * kHeadDim;
   float* pa = part_acc + static_cast<int64_t>(ch.slot) * G * kHeadDim;
   float* pm = part_ml + static_cast<int64_t>(ch.slot) * G * 2;
-  const uint8_t* kd = arena + ch.k_data;
-  const uint8_t* km = arena + ch.k_meta;
-  const uint8_t* vd = arena + ch.v_data;
-  const uint8_t* vm = arena + ch.v_meta;
-  switch (ch.tier) {
-    case 16: process_rows<16, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
-    case 8: process_rows<8, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
-    case 4: process_rows<4, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
-    default: process_rows<2, G>(kd, km, vd, vm, ch.rows, qp, pa, pm, smem); break;
-  }
+  // row-major bf16 rows: the 16-bit tier of a token-wise cache
+  process_rows<G>(arena + ch.k_data, arena + ch.v_data, ch.rows, qp, pa, pm, smem);
 }
 
 // Log-sum-exp merge of the partial results of one (item, query head).  512 threads: 4 slot groups x 128

@@ -941,3 +941,55 @@ def test_allocate_mixed_meets_both_budgets():
         assert set(np.unique(bt)) <= {0, 2, 4, 8, 16} and set(np.unique(bc)) <= {0, 2, 4, 8, 16}
     bt, bc = O.allocate_mixed(w_tok, w_ch, np.float32(0.0))
     assert not bt.any() and not bc.any()
+
+
+# ----------------------------------------------------------------------------
+# Zone C: tokens appended after the compression pass (third term of Eq. 7)
+# ----------------------------------------------------------------------------
+def test_appended_tokens_on_an_all_16_bit_cache_reproduce_bruteforce_attention():
+    rng = np.random.default_rng(61)
+    Hkv, g, T, n_new = 2, 4, 150, 5
+    Ks, Vs = _small_case(rng, Hkv=Hkv, T=T)
+    cache = O.build_cache_tokenwise(Ks, Vs, [np.full((Hkv, T), 16, np.uint8)])
+    kn = rand_bf16(rng, (n_new, 1, Hkv, 128))
+    vn = rand_bf16(rng, (n_new, 1, Hkv, 128))
+    for i in range(n_new):
+        O.append_tokens(cache, kn[i], vn[i])
+    q = rand_bf16(rng, (1, Hkv * g, 128))
+    out, lse = O.decode(cache, q)
+    for j in range(Hkv * g):
+        h = j // g
+        Kall = np.concatenate([Ks[0][h], kn[:, 0, h]])
+        Vall = np.concatenate([Vs[0][h], vn[:, 0, h]])
+        o, l = _bruteforce_attention(q[0, j], Kall, Vall)
+        np.testing.assert_allclose(out[0, j], o, rtol=1e-12, atol=1e-13)
+        assert abs(lse[0, j] - l) < 1e-12
+
+
+def test_appended_zone_is_the_lse_merge_of_the_two_zones_and_survives_full_eviction():
+    # Eq. 7: the output over (compressed rows, new rows) is the softmax-weighted merge of the two zones
+    rng = np.random.default_rng(62)
+    Hkv, g, T = 2, 2, 200
+    Ks, Vs = _small_case(rng, Hkv=Hkv, T=T)
+    bits = rng.choice([0, 2, 4, 8, 16], (Hkv, T)).astype(np.uint8)
+    bits[1, :] = 0                                                 # head 1 keeps nothing of the prompt
+    cache = O.build_cache_tokenwise(Ks, Vs, [bits])
+    q = rand_bf16(rng, (1, Hkv * g, 128))
+    out_a, lse_a = O.decode(cache, q)
+    kn = rand_bf16(rng, (3, 1, Hkv, 128))
+    vn = rand_bf16(rng, (3, 1, Hkv, 128))
+    for i in range(3):
+        O.append_tokens(cache, kn[i], vn[i])
+    out, lse = O.decode(cache, q)
+    for j in range(Hkv * g):
+        h = j // g
+        o_c, l_c = _bruteforce_attention(q[0, j], kn[:, 0, h], vn[:, 0, h])
+        o_c = np.asarray(o_c)
+        if h == 1:                                                 # only the new tokens are left
+            np.testing.assert_allclose(out[0, j], o_c, rtol=1e-12, atol=1e-13)
+            assert abs(lse[0, j] - l_c) < 1e-12 and np.isneginf(lse_a[0, j])
+        else:
+            m = max(lse_a[0, j], l_c)
+            wa, wc = np.exp(lse_a[0, j] - m), np.exp(l_c - m)
+            np.testing.assert_allclose(out[0, j], (wa * out_a[0, j] + wc * o_c) / (wa + wc), rtol=1e-11, atol=1e-12)
+            assert abs(lse[0, j] - (m + np.log(wa + wc))) < 1e-11

@@ -270,6 +270,33 @@ def main():
     k16_ms = ms16 / max(n16, 1)
     bf16_bytes_layer = dense / L + qo_bytes / L
 
+    # ---- generation loop (Zone C): append one token per layer, then decode over compressed rows + tail ----
+    gen = None
+    try:
+        n_gen = 16
+        for c_ in caches:
+            b.rdkv_cache_reserve_tail(c_, 256)
+        k_new = torch.randn((n_gen, L, 1, hkv, d), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        v_new = torch.randn((n_gen, L, 1, hkv, d), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for i in range(n_gen):
+            for l in range(L):
+                b.rdkv_cache_append(caches[l], k_new[i, l], v_new[i, l])
+                b.rdkv_decode_attn(caches[l], q_l[l], outs[l], lses[l])
+        torch.cuda.synchronize()
+        ms_gen = (time.time() - t0) * 1e3 / n_gen
+        g2 = torch.cuda.CUDAGraph()            # decode alone at the reached tail length, replayed like the main step
+        with torch.cuda.graph(g2):
+            step_eager()
+        g2.replay()
+        ms_tail = timed_ms(g2.replay, args.steps, torch)
+        gen = {"appended_tokens_per_layer": n_gen, "ms_per_step_eager_append_and_decode": ms_gen,
+               "ms_per_step_decode_with_tail_graph": ms_tail,
+               "note": "eager: 2 library calls per layer from Python; the tail adds one kernel launch per layer"}
+    except Exception as e:  # reported, never hidden
+        gen = {"error": repr(e)}
+
     # ---- the same L caches as one batch of L sequences: a single launch with enough bytes in flight ------
     batched = None
     try:
@@ -290,8 +317,8 @@ def main():
         b.rdkv_kernel_timing_enable(False)
         kb_ms = msb / max(nb, 1)
         # the two launches split the rows differently, so they agree to rounding, not bit for bit
-        ref_n = outs.view(L, hq, d).abs().amax(dim=-1)
-        diff = ((out_b - outs.view(L, hq, d)).abs().amax(dim=-1) / ref_n).max().item()
+        ref_n = ref_out.view(L, hq, d).abs().amax(dim=-1)
+        diff = ((out_b - ref_out.view(L, hq, d)).abs().amax(dim=-1) / ref_n).max().item()
         same = bool(diff <= 1e-3)
         bytes_b = st_b["stored_bytes"] + qo_bytes
         batched = {"launch": f"{L} sequences x {T} tokens in one launch", "ms": ms_b, "kernel_ms": kb_ms,
@@ -368,7 +395,7 @@ def main():
             o_ref, _ = O.decode(ref, qc)
         t_dec = (time.time() - t0) / reps
         scale = (hkv / n_heads) * L
-        got = outs[0, 0, :n_heads * g].cpu().numpy().astype(np.float64)
+        got = ref_out[0, 0, :n_heads * g].cpu().numpy().astype(np.float64)
         cpu = {"value": t_dec * scale * 1e3, "unit": "ms", "cores": int(threads), "kind": "oracle",
                "sample": f"{n_heads} of {hkv} KV heads of layer 0 (1/{int(scale)} of the step), "
                          f"decode timed {reps}x and scaled; oracle compress of the sample took {t_comp:.1f} s",
@@ -408,6 +435,7 @@ def main():
                       "speedup_compressed_vs_bf16": ms_bf16 / ms_step},
         "batched_launch": batched,
         "mixed_path": mixed,
+        "generation_loop": gen,
         "compress": {"wall_ms_all_layers": compress_wall_ms,
                      "kernel_ms": {k: v[1] for k, v in kt.items()},
                      "launches": {k: v[0] for k, v in kt.items()}},

@@ -89,7 +89,7 @@ typedef struct rdkv_stats {
   int64_t evicted;          /* tokens at 0 bits, summed over items */
   int64_t stored_bytes;     /* bytes a decode step must read: codes + scale/offset metadata, unpadded
                                (channel-wise mode: K codes n * sum_c b_c / 8 and 4 bytes per quantized channel
-                               and 32-token tile, V rows as in token-wise mode) */
+                               and group of 32 retained tokens, V rows as in token-wise mode) */
   int64_t arena_bytes;      /* bytes allocated for the packed arena (with padding and alignment) */
   int64_t index_bytes;      /* kept-position lists, segment tables, split schedule */
   int64_t n_chunks;         /* work items of one decode launch */
@@ -211,6 +211,20 @@ enum {
 };
 rdkv_status rdkv_kernel_timing_enable(int32_t enable);
 rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* total_ms);
+
+/* Zone C of Sec. 3.3 (third term of Eq. 7): tokens generated after the compression pass stay uncompressed (the
+ * paper keeps them in FP16; here their bf16 rows are kept verbatim) and rdkv_decode_attn attends to them together
+ * with the compressed rows.
+ *   rdkv_cache_reserve_tail  once per cache, before the first append: room for max_new_tokens rows per (sequence,
+ *                            KV head), 512 bytes per row and item, owned by the cache; synchronises `stream`.
+ *                            Error if max_new_tokens <= 0 or the tail is already reserved.
+ *   rdkv_cache_append        one new token per sequence: k_new, v_new are DEVICE bf16 [batch][hkv][head_dim]; the
+ *                            copy is enqueued on `stream` (decode calls on the same stream see it).  Error if no
+ *                            tail is reserved or it is full; the cache is unchanged then.
+ *   rdkv_cache_tail_len      tokens appended so far (0 for a null cache). */
+rdkv_status rdkv_cache_reserve_tail(rdkv_cache* cache, int32_t max_new_tokens, void* stream);
+rdkv_status rdkv_cache_append(rdkv_cache* cache, const void* k_new, const void* v_new, void* stream);
+int32_t rdkv_cache_tail_len(const rdkv_cache* cache);
 
 /* Introspection (tests, benchmarks). */
 rdkv_status rdkv_cache_stats(const rdkv_cache* cache, rdkv_stats* out);

@@ -24,6 +24,7 @@ STATUS_NAMES = {0: "RDKV_OK", 1: "RDKV_ERR_INVALID_ARG", 2: "RDKV_ERR_SHAPE", 3:
 EXPORTED_SYMBOLS = [
     "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_pack",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
+    "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len",
     "rdkv_cache_stats", "rdkv_cache_export_bytes", "rdkv_cache_export", "rdkv_cache_free",
     "rdkv_kernel_timing_enable", "rdkv_kernel_timing_read",
 ]
@@ -79,6 +80,10 @@ def _load():
     lib.rdkv_decode_bf16_workspace_bytes.argtypes = [ctypes.POINTER(i32), i32, i32, i32, i32]
     lib.rdkv_decode_bf16_workspace_bytes.restype = sz
     lib.rdkv_decode_attn_bf16.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.rdkv_cache_reserve_tail.argtypes = [vp, i32, vp]
+    lib.rdkv_cache_append.argtypes = [vp, vp, vp, vp]
+    lib.rdkv_cache_tail_len.argtypes = [vp]
+    lib.rdkv_cache_tail_len.restype = i32
     lib.rdkv_cache_stats.argtypes = [vp, ctypes.POINTER(rdkv_stats)]
     lib.rdkv_cache_export_bytes.argtypes = [vp, i32]
     lib.rdkv_cache_export_bytes.restype = sz
@@ -214,6 +219,18 @@ def rdkv_decode_attn(cache, q, out=None, lse=None):
         lse = torch.empty((len(cfg.seq_lens), cfg.hq), dtype=torch.float32, device=q.device)
     _check(lib.rdkv_decode_attn(cache.h, _ptr(q), _ptr(out), _ptr(lse), _stream()))
     return out, lse
+
+
+def rdkv_cache_reserve_tail(cache, max_new_tokens):
+    _check(lib.rdkv_cache_reserve_tail(cache.h, int(max_new_tokens), _stream()))
+
+
+def rdkv_cache_append(cache, k_new, v_new):
+    _check(lib.rdkv_cache_append(cache.h, _ptr(k_new), _ptr(v_new), _stream()))
+
+
+def rdkv_cache_tail_len(cache):
+    return int(lib.rdkv_cache_tail_len(cache.h))
 
 
 def rdkv_decode_bf16_workspace_bytes(seq_lens, hq, hkv, head_dim=128):

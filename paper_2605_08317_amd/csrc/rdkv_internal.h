@@ -31,7 +31,10 @@ struct Chunk {
   int32_t item;                             // sequence * hkv + kv head
   int32_t slot;                             // partial-result slot
   int16_t k_word_end[4];                    // mixed mode: ItemK::word_end of the item (the shape of its K rows)
+  int32_t row0;                             // appended-token zone: first row of the chunk inside the item's tail
+  int32_t reserved;
 };
+constexpr int kTailChunkRows = 256;         // appended tokens per decode work item
 
 // Channel-wise K (mixed mode): how one item's K tiles are laid out.  Channels are sorted by bit-width into
 // slots: tiers 16, 8, 4, 2 in this order.  A retained token's K row is a run of 32-bit words (a 16-bit word holds
@@ -64,8 +67,12 @@ struct DenseArgs {
 // ---- launchers implemented in the .hip files ------------------------------
 hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
 hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
+// row_limit: rows of an item's segment that exist so far; a chunk covers rows [row0, row0 + rows) below that limit
 hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                      float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
+                                      float* part_acc, float* part_ml, int hq, int hkv, int row_limit,
+                                      hipStream_t st);
+hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint8_t* tail, int64_t n_items,
+                              int32_t tail_cap, int32_t row, hipStream_t st);
 hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
                                       const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
                                       float* lse, hipStream_t st);
@@ -116,6 +123,11 @@ struct rdkv_cache {
   rdkv::ItemK* d_items_k = nullptr;     // [items] (mixed mode)
   std::vector<rdkv::ItemK> items_k;
   int32_t max_k_words = 0, max_k_steps = 0, max_k_qsteps = 0;   // largest K row shape over the items (mixed mode)
+  // appended-token zone (Zone C): per item [tail_cap][128] bf16 K rows, then the same for V, in one allocation
+  std::vector<int32_t> slot_begin, slot_count;   // host copies of the partial-slot tables
+  uint8_t* d_tail = nullptr;
+  rdkv::Chunk* d_tail_chunks = nullptr; // [chunk index][item]: the first ceil(tail_len / 256) * items are live
+  int32_t tail_cap = 0, tail_len = 0;
   int64_t stored_bytes = 0;             // bytes a decode step must read (unpadded)
   int64_t index_bytes = 0;
   rdkv_alloc_fn alloc = nullptr;

@@ -293,7 +293,7 @@ def main():
         ms_tail = timed_ms(g2.replay, args.steps, torch)
         gen = {"appended_tokens_per_layer": n_gen, "ms_per_step_eager_append_and_decode": ms_gen,
                "ms_per_step_decode_with_tail_graph": ms_tail,
-               "note": "eager: 2 library calls per layer from Python; the tail adds one kernel launch per layer"}
+               "note": "eager: 2 library calls per layer from Python; the tail's chunks ride in the decode kernel's launch"}
     except Exception as e:  # reported, never hidden
         gen = {"error": repr(e)}
 

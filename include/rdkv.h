@@ -216,7 +216,8 @@ rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* tot
  * paper keeps them in FP16; here their bf16 rows are kept verbatim) and rdkv_decode_attn attends to them together
  * with the compressed rows.
  *   rdkv_cache_reserve_tail  once per cache, before the first append: room for max_new_tokens rows per (sequence,
- *                            KV head), 512 bytes per row and item, owned by the cache; synchronises `stream`.
+ *                            KV head), 512 bytes per row and item (in whole 64-token tiles), owned by the cache;
+ *                            synchronises `stream`.
  *                            Error if max_new_tokens <= 0 or the tail is already reserved.
  *   rdkv_cache_append        one new token per sequence: k_new, v_new are DEVICE bf16 [batch][hkv][head_dim]; the
  *                            copy is enqueued on `stream` (decode calls on the same stream see it).  Error if no

@@ -205,17 +205,15 @@ template <int G>
 __global__ __launch_bounds__(kWG) void decode_tiered_kernel(const Chunk* __restrict__ chunks,
                                                             const uint8_t* __restrict__ arena,
                                                             const uint16_t* __restrict__ q, float* part_acc,
-                                                            float* part_ml, int hq, int hkv, int row_limit) {
+                                                            float* part_ml, int hq, int hkv) {
   __shared__ float smem[16 * G * 2 + kWaves * G * kHeadDim];
   const Chunk ch = chunks[blockIdx.x];
   const int seq = ch.item / hkv, head = ch.item % hkv;
   const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * G) * kHeadDim;
   float* pa = part_acc + static_cast<int64_t>(ch.slot) * G * kHeadDim;
   float* pm = part_ml + static_cast<int64_t>(ch.slot) * G * 2;
-  // row-major bf16 rows: the 16-bit tier of a token-wise cache, or a chunk of the appended-token zone (whose last
-  // chunk ends where the tokens appended so far end; the host launches no chunk that starts beyond them)
-  const int rows = min(ch.rows, row_limit - ch.row0);
-  process_rows<G>(arena + ch.k_data, arena + ch.v_data, rows, qp, pa, pm, smem);
+  // row-major bf16 rows: the 16-bit tier of a token-wise cache
+  process_rows<G>(arena + ch.k_data, arena + ch.v_data, ch.rows, qp, pa, pm, smem);
 }
 
 // Log-sum-exp merge of the partial results of one (item, query head).  512 threads: 4 slot groups x 128
@@ -327,39 +325,48 @@ hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipS
 }
 
 hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                      float* part_acc, float* part_ml, int hq, int hkv, int row_limit,
-                                      hipStream_t st) {
+                                      float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st) {
   const int g = hq / hkv;
   if (n_chunks == 0) return hipSuccess;
   dim3 grid(n_chunks), block(kWG);
   switch (g) {
-    case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv, row_limit); break;
-    case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv, row_limit); break;
-    case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv, row_limit); break;
-    case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv, row_limit); break;
+    case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
-// Zone C: one new bf16 K row and V row per item, written at row `row` of the item's tail
-__global__ __launch_bounds__(64) void append_rows_kernel(const uint16_t* __restrict__ k_new,
-                                                         const uint16_t* __restrict__ v_new, uint8_t* __restrict__ tail,
-                                                         int64_t n_items, int32_t tail_cap, int32_t row) {
+// Zone C: one new bf16 K row and V row per item, scattered into the item's tail at token index `row`.  The tail
+// is kept in the 64-token tiles the decode kernels read (see process_tail_tiles): per item tail_tiles tiles of
+// 16 KiB for K, then (after the K tiles of all items) the same for V.
+__global__ __launch_bounds__(256) void append_rows_kernel(const uint16_t* __restrict__ k_new,
+                                                          const uint16_t* __restrict__ v_new, uint8_t* __restrict__ tail,
+                                                          int64_t n_items, int32_t tail_tiles, int32_t row) {
   const int64_t item = blockIdx.x;
   const int t = threadIdx.x;
-  if (t >= 32) return;
-  const int which = t >> 4, part = t & 15;   // K rows of all items first, then V rows
-  const uint4 v = *reinterpret_cast<const uint4*>((which ? v_new : k_new) + item * kHeadDim + part * 8);
-  uint8_t* dst = tail + ((which * n_items + item) * tail_cap + row) * (kHeadDim * 2) + part * 16;
-  *reinterpret_cast<uint4*>(dst) = v;
+  const int tile = row >> 6, r = row & 63;
+  constexpr int kTileBytes = 64 * kHeadDim * 2;
+  if (t < 16) {          // K: words 4t .. 4t+3 of the token's row = 16 bytes at 1024 t + 16 r
+    const uint4 v = *reinterpret_cast<const uint4*>(k_new + item * kHeadDim + t * 8);
+    uint8_t* dst = tail + (item * tail_tiles + tile) * static_cast<int64_t>(kTileBytes) + 1024 * t + 16 * r;
+    *reinterpret_cast<uint4*>(dst) = v;
+  } else if (t >= 128) {  // V: channel c of the token: unit u = 4 (c / 32) + (r % 32) / 8, lane 32 (r / 32) + c % 32
+    const int c = t - 128;
+    const int lane = 32 * (r >> 5) + (c & 31), u = 4 * (c >> 5) + ((r & 31) >> 3);
+    uint8_t* dst = tail + ((n_items + item) * tail_tiles + tile) * static_cast<int64_t>(kTileBytes) + 1024 * u +
+                   16 * lane + 2 * (r & 7);
+    *reinterpret_cast<uint16_t*>(dst) = v_new[item * kHeadDim + c];
+  }
 }
 
 hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint8_t* tail, int64_t n_items,
-                              int32_t tail_cap, int32_t row, hipStream_t st) {
+                              int32_t tail_tiles, int32_t row, hipStream_t st) {
   if (n_items == 0) return hipSuccess;
-  hipLaunchKernelGGL(append_rows_kernel, dim3(static_cast<unsigned>(n_items)), dim3(64), 0, st, k_new, v_new, tail,
-                     n_items, tail_cap, row);
+  hipLaunchKernelGGL(append_rows_kernel, dim3(static_cast<unsigned>(n_items)), dim3(256), 0, st, k_new, v_new, tail,
+                     n_items, tail_tiles, row);
   return hipGetLastError();
 }
 

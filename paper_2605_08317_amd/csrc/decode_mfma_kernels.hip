@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kWG, HS == 1 ? 4 : 3) void decode_tiles_kernel(cons
                                                                            const uint8_t* __restrict__ arena,
                                                                            const uint16_t* __restrict__ q,
                                                                            float* part_acc, float* part_ml, int hq,
-                                                                           int hkv) {
+                                                                           int hkv, int row_limit) {
   extern __shared__ __align__(16) uint8_t smem[];
   const Chunk ch = chunks[blockIdx.x];
   const int g = hq / hkv;
@@ -221,6 +221,12 @@ __global__ __launch_bounds__(kWG, HS == 1 ? 4 : 3) void decode_tiles_kernel(cons
   const uint8_t* vd = arena + ch.v_data;
   const uint8_t* vm = arena + ch.v_meta;
   switch (ch.tier) {
+    case kTierTail: {   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
+      float* s_ml = reinterpret_cast<float*>(smem + Lds<HS>::kQop + Lds<HS>::kQsum);
+      process_tail_tiles<HS, false>(kd, vd, min(ch.rows, row_limit - ch.row0), g, qp, smem, s_ml,
+                                   s_ml + kWaves * 4 * HS * 2, pa, pm);
+      break;
+    }
     case 8: process_tiles<8, HS>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
     case 4: process_tiles<4, HS>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
     default: process_tiles<2, HS>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
@@ -230,7 +236,7 @@ __global__ __launch_bounds__(kWG, HS == 1 ? 4 : 3) void decode_tiles_kernel(cons
 }  // namespace
 
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st) {
+                               float* part_acc, float* part_ml, int hq, int hkv, int row_limit, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   const int g = hq / hkv;
   const int hs = g > 4 ? 2 : 1;
@@ -238,10 +244,10 @@ hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t*
                      kWaves * 4 * hs * 2 * sizeof(float) + static_cast<size_t>(2 * kWaves) * g * kHeadDim * sizeof(float);
   if (hs == 1)
     hipLaunchKernelGGL(decode_tiles_kernel<1>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
-                       hq, hkv);
+                       hq, hkv, row_limit);
   else
     hipLaunchKernelGGL(decode_tiles_kernel<2>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
-                       hq, hkv);
+                       hq, hkv, row_limit);
   return hipGetLastError();
 }
 

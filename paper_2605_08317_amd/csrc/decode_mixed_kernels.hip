@@ -23,13 +23,6 @@ namespace {
 
 using namespace tile;
 
-typedef short short4v __attribute__((ext_vector_type(4)));
-
-typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
-
-// four bf16 of an operand from two 32-bit words (a bit cast: a union of the two types is left in scratch memory)
-__device__ __forceinline__ short4v bf4(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(short4v, uint2v{lo, hi}); }
-
 // LDS: query operands per step [steps][HS][4 heads] x 8 bytes (raw bf16 for 16-bit steps, fp16 q * 2^(kQExp - fb)
 // for quantized ones), fp16 q * 2^kQExp per quantized step (for the offsets), then per wavefront the scaled-query
 // table [2 token groups][quantized steps][HS][4 heads] x 16 bytes (high terms, low terms).  The merge area of the
@@ -351,16 +344,7 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
       // bf16 rows: p as two truncated bf16 terms (the remainder of the first is exact in fp32)
       short4v phi[HS], plo[HS];
 #pragma unroll
-      for (int hs = 0; hs < HS; ++hs) {
-        uint32_t hb[4], lb[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          hb[i] = __float_as_uint(p[hs][i]) & 0xFFFF0000u;
-          lb[i] = __float_as_uint(p[hs][i] - __uint_as_float(hb[i]));
-        }
-        phi[hs] = bf4((hb[0] >> 16) | hb[1], (hb[2] >> 16) | hb[3]);
-        plo[hs] = bf4((lb[0] >> 16) | (lb[1] & 0xFFFF0000u), (lb[2] >> 16) | (lb[3] & 0xFFFF0000u));
-      }
+      for (int hs = 0; hs < HS; ++hs) split_bf16(p[hs], phi[hs], plo[hs]);
 #define RDKV_PV16_STEP(G_, A_, X_, Y_)                                                                          \
   {                                                                                                            \
     const short4v b = bf4(X_, Y_);                                                                             \
@@ -410,7 +394,7 @@ template <int NW, int HS>
 __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mixed_kernel(
     const Chunk* __restrict__ chunks, const uint8_t* __restrict__ arena, const ItemK* __restrict__ items_k,
     const uint16_t* __restrict__ q, float* part_acc, float* part_ml, int hq, int hkv, int lds_steps,
-    int lds_qsteps) {
+    int lds_qsteps, int row_limit) {
   extern __shared__ __align__(16) uint8_t smem[];
   const Chunk ch = chunks[blockIdx.x];
   const int g = hq / hkv;
@@ -420,6 +404,11 @@ __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mix
   float* pm = part_ml + static_cast<int64_t>(ch.slot) * g * 2;
   const ItemK* ikp = items_k + ch.item;
   switch (ch.tier) {
+    case kTierTail:   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
+      process_tail_tiles<HS, true>(arena + ch.k_data, arena + ch.v_data, min(ch.rows, row_limit - ch.row0), g, qp, smem,
+                                  reinterpret_cast<float*>(smem), reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2,
+                                  pa, pm);
+      break;
     case 16: process_mixed<16, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
     case 8: process_mixed<8, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
     case 4: process_mixed<4, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
@@ -430,7 +419,7 @@ __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mix
 template <int NW, int HS>
 hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int lds_steps,
                       int lds_qsteps, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv,
-                      hipStream_t st) {
+                      int row_limit, hipStream_t st) {
   const size_t lds = static_cast<size_t>(LdsPlan(lds_steps, lds_qsteps, HS, hq / hkv).total);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_mixed_kernel<NW, HS>),
@@ -438,7 +427,7 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((decode_mixed_kernel<NW, HS>), dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, items_k, q,
-                     part_acc, part_ml, hq, hkv, lds_steps, lds_qsteps);
+                     part_acc, part_ml, hq, hkv, lds_steps, lds_qsteps, row_limit);
   return hipGetLastError();
 }
 
@@ -446,12 +435,12 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
 
 hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                               float* part_ml, int hq, int hkv, hipStream_t st) {
+                               float* part_ml, int hq, int hkv, int row_limit, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   const int hs = hq / hkv > 4 ? 2 : 1;
 #define RDKV_MIXED_LAUNCH(NW_, HS_)                                                                           \
   return launch_one<NW_, HS_>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, part_acc, part_ml, hq, \
-                              hkv, st)
+                              hkv, row_limit, st)
   if (hs == 1) {
     if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 1);
     if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 1);

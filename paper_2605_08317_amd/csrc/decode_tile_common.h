@@ -39,6 +39,24 @@ constexpr float kPExp = 6.0f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+
+// four bf16 of an operand from two 32-bit words (a bit cast: a union of the two types is left in scratch memory)
+__device__ __forceinline__ short4v bf4(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(short4v, uint2v{lo, hi}); }
+
+// the probabilities of a lane's four tokens as two truncated bf16 terms (the remainder of the first is exact in fp32)
+__device__ __forceinline__ void split_bf16(const float (&p)[4], short4v& hi, short4v& lo) {
+  uint32_t hb[4], lb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hb[i] = __float_as_uint(p[i]) & 0xFFFF0000u;
+    lb[i] = __float_as_uint(p[i] - __uint_as_float(hb[i]));
+  }
+  hi = bf4((hb[0] >> 16) | hb[1], (hb[2] >> 16) | hb[3]);
+  lo = bf4((lb[0] >> 16) | (lb[1] & 0xFFFF0000u), (lb[2] >> 16) | (lb[3] & 0xFFFF0000u));
+}
+
 union Pack4 {
   half4 h;
   half2v p[2];
@@ -334,6 +352,100 @@ __device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, int 
     part_ml[tid * 2] = mm;
     part_ml[tid * 2 + 1] = ll;
   }
+}
+
+// A chunk of appended tokens (Sec. 3.3 Zone C: bf16 rows kept after the compression pass) on the same instruction
+// and lane roles.  The tail is stored in 64-token tiles written by the append kernel: K tile = 16 KiB, word W (two
+// bf16 channels 2W, 2W+1) of token r at byte 1024 (W / 4) + 16 r + 4 (W % 4), so a lane (= token) reads its row
+// with sixteen coalesced 16-byte loads; V tile = 16 KiB in the layout of the 16-bit V tiles of mixed mode (lane
+// 32 (r / 32) + c % 32 holds channel c, eight tokens per 16-byte unit u = 4 (c / 32) + (r % 32) / 8 at 1024 u).
+// s_q: LDS for the query operands, [32 steps][HS][4 heads] x 8 bytes (raw bf16; the products are exact).
+template <int HS, bool ALIAS>
+__device__ __forceinline__ void process_tail_tiles(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ vd,
+                                                   int rows, int g, const uint16_t* __restrict__ q, uint8_t* s_q,
+                                                   float* s_ml, float* s_acc, float* __restrict__ part_acc,
+                                                   float* __restrict__ part_ml) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int blk = lane >> 2, j = lane & 3;
+  const int ntiles = (rows + kTile - 1) / kTile;
+  constexpr int kTileBytes = kTile * kHeadDim * 2;
+  for (int e = tid; e < 32 * HS * 4; e += kWG) {
+    const int s = e / (HS * 4), hs = (e >> 2) % HS, hj = e & 3;
+    const int head = 4 * hs + hj;
+    uint2 v = make_uint2(0, 0);
+    if (head < g) v = *reinterpret_cast<const uint2*>(q + head * kHeadDim + 4 * s);
+    *reinterpret_cast<uint2*>(s_q + ((s * HS + hs) * 4 + hj) * 8) = v;
+  }
+  __syncthreads();
+  Run<HS> run;
+  run.init();
+  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  for (int tile = wave; tile < ntiles; tile += kWaves) {
+    const uint8_t* kp = kd + static_cast<int64_t>(tile) * kTileBytes + 16 * lane;
+    const uint8_t* vp = vd + static_cast<int64_t>(tile) * kTileBytes + 16 * lane;
+    uint4 kq[16], vq[3][4];   // the K row and the first channel group of V in one round trip
+#pragma unroll
+    for (int i = 0; i < 16; ++i) kq[i] = *reinterpret_cast<const uint4*>(kp + 1024 * i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) vq[0][i] = *reinterpret_cast<const uint4*>(vp + 1024 * i);
+    floatx4 a16[HS];
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs) a16[hs] = zero4;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int s = 2 * i + half;   // step s = channels 4s .. 4s+3 = words 2s, 2s+1
+        const short4v a = half ? bf4(kq[i].z, kq[i].w) : bf4(kq[i].x, kq[i].y);
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) {
+          const uint2 braw = *reinterpret_cast<const uint2*>(s_q + ((s * HS + hs) * 4 + j) * 8);
+          a16[hs] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, bf4(braw.x, braw.y), a16[hs], 0, 0, 0);
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);   // the K registers are free: the other three channel groups of V
+#pragma unroll
+    for (int i = 0; i < 4; ++i) vq[1][i] = *reinterpret_cast<const uint4*>(vp + 1024 * (4 + i));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) vq[2][i] = *reinterpret_cast<const uint4*>(vp + 1024 * (8 + i));
+    float x[HS][4];
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[hs][i] = a16[hs][i] * kKUnit;
+    mask_rows<HS>(x, tile, rows, blk);
+    float p[HS][4];
+    softmax_tile<HS>(x, run, p);
+    short4v phi[HS], plo[HS];
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs) split_bf16(p[hs], phi[hs], plo[hs]);
+    // P V: step a of a channel group = tokens 4a..4a+3 of this lane's token half (rows past the end are zero in the
+    // tile and carry p = 0)
+#define RDKV_TAIL_STEP(G_, A_, X_, Y_)                                                                          \
+  {                                                                                                            \
+    const short4v b = bf4(X_, Y_);                                                                             \
+    _Pragma("unroll") for (int hs = 0; hs < HS; ++hs) {                                                        \
+      run.acc[hs][G_] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(phi[hs], b, run.acc[hs][G_], 3, A_, 0);         \
+      run.acc[hs][G_] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(plo[hs], b, run.acc[hs][G_], 3, A_, 0);         \
+    }                                                                                                          \
+  }
+#define RDKV_TAIL_GROUP(G_, V_)                                                                                \
+  RDKV_TAIL_STEP(G_, 0, V_[0].x, V_[0].y) RDKV_TAIL_STEP(G_, 1, V_[0].z, V_[0].w)                              \
+  RDKV_TAIL_STEP(G_, 2, V_[1].x, V_[1].y) RDKV_TAIL_STEP(G_, 3, V_[1].z, V_[1].w)                              \
+  RDKV_TAIL_STEP(G_, 4, V_[2].x, V_[2].y) RDKV_TAIL_STEP(G_, 5, V_[2].z, V_[2].w)                              \
+  RDKV_TAIL_STEP(G_, 6, V_[3].x, V_[3].y) RDKV_TAIL_STEP(G_, 7, V_[3].z, V_[3].w)
+    RDKV_TAIL_GROUP(0, vq[0])
+#pragma unroll
+    for (int i = 0; i < 4; ++i) vq[0][i] = *reinterpret_cast<const uint4*>(vp + 1024 * (12 + i));   // group 3
+    RDKV_TAIL_GROUP(1, vq[1])
+    RDKV_TAIL_GROUP(2, vq[2])
+    RDKV_TAIL_GROUP(3, vq[0])
+#undef RDKV_TAIL_GROUP
+#undef RDKV_TAIL_STEP
+  }
+  finish_chunk<HS, ALIAS>(run, 1.0f, g, s_ml, s_acc, part_acc, part_ml);
 }
 
 }  // namespace tile

@@ -218,7 +218,6 @@ void free_cache_buffers(rdkv_cache* c) {
   al.put(c->d_bits_ch);
   al.put(c->d_items_k);
   al.put(c->d_tail);
-  al.put(c->d_tail_chunks);
 }
 
 // Sorted-channel layout of one item's K tiles from its channel bit map.
@@ -702,12 +701,9 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, 
   return rdkv_pack(cfg, K, V, bits, bits_ch, stream, out);
 }
 
-// Zone C: the chunks of the appended tokens that exist so far, on the kernel of the bf16 rows
-static hipError_t launch_tail(const rdkv_cache* c, const void* q, hipStream_t st) {
-  if (c->tail_len == 0) return hipSuccess;
-  const int live = (c->tail_len + kTailChunkRows - 1) / kTailChunkRows * static_cast<int>(c->n_items);
-  return launch_decode_tiered_split(c->d_tail_chunks, live, c->d_tail, static_cast<const uint16_t*>(q), c->d_part_acc,
-                                    c->d_part_ml, c->hq, c->hkv, c->tail_len, st);
+// Zone C: chunks of appended tokens that exist so far (they follow the other chunks in the chunk table)
+static int live_tail_chunks(const rdkv_cache* c) {
+  return (c->tail_len + kTailChunkRows - 1) / kTailChunkRows * static_cast<int>(c->n_items);
 }
 
 rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, float* lse, void* stream) {
@@ -717,11 +713,10 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
   if (c->k_mode == RDKV_K_CHANNELWISE) {
     {
       TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
-      RDKV_HIP(launch_tail(c, q, st));
-      RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->chunks.size()), c->d_arena, c->d_items_k,
-                                   c->max_k_words, c->max_k_steps, c->max_k_qsteps,
+      RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->chunks.size()) + live_tail_chunks(c), c->d_arena,
+                                   c->d_items_k, c->max_k_words, c->max_k_steps, c->max_k_qsteps,
                                    static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
-                                   c->hq, c->hkv, st));
+                                   c->hq, c->hkv, c->tail_len, st));
     }
     RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
                                         static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));
@@ -731,10 +726,10 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
     TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
     const int n16 = static_cast<int>(c->n_chunks16), nq = static_cast<int>(c->chunks.size()) - n16;
     RDKV_HIP(launch_decode_tiered_split(c->d_chunks, n16, c->d_arena, static_cast<const uint16_t*>(q),
-                                        c->d_part_acc, c->d_part_ml, c->hq, c->hkv, INT32_MAX, st));
-    RDKV_HIP(launch_tail(c, q, st));
-    RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nq, c->d_arena, static_cast<const uint16_t*>(q), c->d_part_acc,
-                                 c->d_part_ml, c->hq, c->hkv, st));
+                                        c->d_part_acc, c->d_part_ml, c->hq, c->hkv, st));
+    RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nq + live_tail_chunks(c), c->d_arena,
+                                 static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml, c->hq, c->hkv,
+                                 c->tail_len, st));
   }
   RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
                                       static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));
@@ -752,7 +747,8 @@ rdkv_status rdkv_cache_reserve_tail(rdkv_cache* c, int32_t max_new_tokens, void*
   const int g = c->hq / c->hkv;
   const int npi = (max_new_tokens + kTailChunkRows - 1) / kTailChunkRows;     // tail chunks per item
   const int64_t n_old = static_cast<int64_t>(c->chunks.size()), n_slots = n_old + n * npi;
-  const int64_t row_bytes = kHeadDim * 2, side = n * max_new_tokens * row_bytes;
+  const int64_t tail_tiles = (max_new_tokens + kTile64 - 1) / kTile64, tile_bytes = kTile64 * kHeadDim * 2;
+  const int64_t side = n * tail_tiles * tile_bytes;     // K tiles of all items, then V tiles
   // partial slots: every item keeps its slots contiguous, the tail's after the compressed tiers'
   std::vector<int32_t> nb(n), nc(n);
   for (int64_t i = 0; i < n; ++i) {
@@ -761,48 +757,53 @@ rdkv_status rdkv_cache_reserve_tail(rdkv_cache* c, int32_t max_new_tokens, void*
   }
   std::vector<Chunk> chunks = c->chunks;
   for (Chunk& ch : chunks) ch.slot += ch.item * npi;
-  std::vector<Chunk> tail(static_cast<size_t>(n) * npi);
+  uint8_t* d_tail = static_cast<uint8_t*>(al.get(2 * side));
+  Chunk* d_chunks = static_cast<Chunk*>(al.get((n_old + n * npi) * sizeof(Chunk)));
+  float* d_acc = static_cast<float*>(al.get(n_slots * g * kHeadDim * sizeof(float)));
+  float* d_ml = static_cast<float*>(al.get(n_slots * g * 2 * sizeof(float)));
+  if (!d_tail || !d_chunks || !d_acc || !d_ml) {
+    al.put(d_tail); al.put(d_chunks); al.put(d_acc); al.put(d_ml);
+    return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  }
+  // the tail's chunks follow the others in the table, ordered (chunk index, item): the live ones are a prefix.
+  // The decode kernels address everything relative to the arena, so the tail's offsets are pointer differences.
+  const int64_t base = reinterpret_cast<intptr_t>(d_tail) - reinterpret_cast<intptr_t>(c->d_arena);
+  std::vector<Chunk> table = chunks;
+  table.resize(static_cast<size_t>(n_old + n * npi));
   for (int j = 0; j < npi; ++j)
     for (int64_t i = 0; i < n; ++i) {
-      Chunk& ch = tail[static_cast<size_t>(j) * n + i];
+      Chunk& ch = table[static_cast<size_t>(n_old + static_cast<int64_t>(j) * n + i)];
       std::memset(&ch, 0, sizeof(ch));
-      ch.k_data = (i * max_new_tokens + static_cast<int64_t>(j) * kTailChunkRows) * row_bytes;
-      ch.v_data = side + ch.k_data;
+      ch.k_data = base + (i * tail_tiles + static_cast<int64_t>(j) * (kTailChunkRows / kTile64)) * tile_bytes;
+      ch.v_data = ch.k_data + side;
       ch.rows = std::min<int32_t>(kTailChunkRows, max_new_tokens - j * kTailChunkRows);
-      ch.tier = 16;
+      ch.tier = kTierTail;
       ch.item = static_cast<int32_t>(i);
       ch.slot = nb[i] + c->slot_count[i] + j;
       ch.row0 = j * kTailChunkRows;
     }
-  uint8_t* d_tail = static_cast<uint8_t*>(al.get(2 * side));
-  Chunk* d_tail_chunks = static_cast<Chunk*>(al.get(tail.size() * sizeof(Chunk)));
-  float* d_acc = static_cast<float*>(al.get(n_slots * g * kHeadDim * sizeof(float)));
-  float* d_ml = static_cast<float*>(al.get(n_slots * g * 2 * sizeof(float)));
-  if (!d_tail || !d_tail_chunks || !d_acc || !d_ml) {
-    al.put(d_tail); al.put(d_tail_chunks); al.put(d_acc); al.put(d_ml);
-    return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  }
   // slots of tail chunks that no launch has reached yet must read as empty partials: m = -1e30, l = 0, acc = 0
   std::vector<float> ml(static_cast<size_t>(n_slots) * g * 2, 0.f);
   for (size_t k = 0; k < ml.size(); k += 2) ml[k] = -1.0e30f;
   hipError_t e = hipMemsetAsync(d_acc, 0, n_slots * g * kHeadDim * sizeof(float), st);
+  if (e == hipSuccess) e = hipMemsetAsync(d_tail, 0, 2 * side, st);   // rows not yet appended must read as zeros
   if (e == hipSuccess) e = hipMemcpyAsync(d_ml, ml.data(), ml.size() * sizeof(float), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipMemcpyAsync(d_tail_chunks, tail.data(), tail.size() * sizeof(Chunk), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess && n_old > 0)
-    e = hipMemcpyAsync(c->d_chunks, chunks.data(), n_old * sizeof(Chunk), hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(d_chunks, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_begin, nb.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_count, nc.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);     // the host vectors above go out of scope
   if (e != hipSuccess) {
-    al.put(d_tail); al.put(d_tail_chunks); al.put(d_acc); al.put(d_ml);
+    al.put(d_tail); al.put(d_chunks); al.put(d_acc); al.put(d_ml);
     return fail(RDKV_ERR_HIP, "rdkv_cache_reserve_tail: %s", hipGetErrorString(e));
   }
   al.put(c->d_part_acc);
   al.put(c->d_part_ml);
+  al.put(c->d_chunks);
   c->d_part_acc = d_acc;
   c->d_part_ml = d_ml;
+  c->d_chunks = d_chunks;
   c->d_tail = d_tail;
-  c->d_tail_chunks = d_tail_chunks;
+  c->n_tail_chunks = n * npi;
   c->chunks.swap(chunks);
   c->slot_begin.swap(nb);
   c->slot_count.swap(nc);
@@ -817,7 +818,8 @@ rdkv_status rdkv_cache_append(rdkv_cache* c, const void* k_new, const void* v_ne
   if (c->tail_len >= c->tail_cap)
     return fail(RDKV_ERR_INVALID_ARG, "the tail is full (%d tokens reserved)", c->tail_cap);
   RDKV_HIP(launch_append_rows(static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), c->d_tail,
-                              c->n_items, c->tail_cap, c->tail_len, static_cast<hipStream_t>(stream)));
+                              c->n_items, (c->tail_cap + kTile64 - 1) / kTile64, c->tail_len,
+                              static_cast<hipStream_t>(stream)));
   c->tail_len += 1;
   return RDKV_OK;
 }

@@ -35,6 +35,7 @@ struct Chunk {
   int32_t reserved;
 };
 constexpr int kTailChunkRows = 256;         // appended tokens per decode work item
+constexpr int kTierTail = 17;               // Chunk::tier of a chunk of appended tokens (64-token tiles of bf16 rows)
 
 // Channel-wise K (mixed mode): how one item's K tiles are laid out.  Channels are sorted by bit-width into
 // slots: tiers 16, 8, 4, 2 in this order.  A retained token's K row is a run of 32-bit words (a 16-bit word holds
@@ -67,21 +68,20 @@ struct DenseArgs {
 // ---- launchers implemented in the .hip files ------------------------------
 hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
 hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
-// row_limit: rows of an item's segment that exist so far; a chunk covers rows [row0, row0 + rows) below that limit
 hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                      float* part_acc, float* part_ml, int hq, int hkv, int row_limit,
-                                      hipStream_t st);
+                                      float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
 hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint8_t* tail, int64_t n_items,
-                              int32_t tail_cap, int32_t row, hipStream_t st);
+                              int32_t tail_tiles, int32_t row, hipStream_t st);
 hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
                                       const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
                                       float* lse, hipStream_t st);
 
+// row_limit: appended tokens that exist so far (chunks of tier kTierTail end there)
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
+                               float* part_acc, float* part_ml, int hq, int hkv, int row_limit, hipStream_t st);
 hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                               float* part_ml, int hq, int hkv, hipStream_t st);
+                               float* part_ml, int hq, int hkv, int row_limit, hipStream_t st);
 
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);
@@ -123,10 +123,12 @@ struct rdkv_cache {
   rdkv::ItemK* d_items_k = nullptr;     // [items] (mixed mode)
   std::vector<rdkv::ItemK> items_k;
   int32_t max_k_words = 0, max_k_steps = 0, max_k_qsteps = 0;   // largest K row shape over the items (mixed mode)
-  // appended-token zone (Zone C): per item [tail_cap][128] bf16 K rows, then the same for V, in one allocation
+  // appended-token zone (Zone C): per item ceil(tail_cap / 64) tiles of 64 bf16 K rows (16 KiB each), then the same
+  // for V, in one allocation (zero-filled: rows not yet appended read as zeros)
   std::vector<int32_t> slot_begin, slot_count;   // host copies of the partial-slot tables
   uint8_t* d_tail = nullptr;
-  rdkv::Chunk* d_tail_chunks = nullptr; // [chunk index][item]: the first ceil(tail_len / 256) * items are live
+  int64_t n_tail_chunks = 0;            // chunks of the tail, appended to d_chunks in (chunk index, item) order:
+                                        // the first ceil(tail_len / 256) * items of them are live
   int32_t tail_cap = 0, tail_len = 0;
   int64_t stored_bytes = 0;             // bytes a decode step must read (unpadded)
   int64_t index_bytes = 0;

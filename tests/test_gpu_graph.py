@@ -1,0 +1,77 @@
+"""The decode entry points under HIP graph capture (the launch configuration bench.py times): a captured decode is
+replayed several times with eager work and synchronisations in between, and every replay must reproduce the eager
+result bit for bit (the kernels are deterministic: fixed summation orders, no atomics)."""
+import numpy as np
+import pytest
+import torch
+
+from test_gpu_parity import B, _inputs, _pack_both
+from test_gpu_mixed import _pack_both_mixed, _random_maps
+
+pytestmark = pytest.mark.gpu
+
+
+def _replay_equals_eager(b, cache, q, other_cache=None):
+    out_e, lse_e = b.rdkv_decode_attn(cache, q)
+    torch.cuda.synchronize()
+    out_g, lse_g = torch.empty_like(out_e), torch.empty_like(lse_e)
+    b.rdkv_decode_attn(cache, q, out_g, lse_g)              # warm-up on the capture stream's allocator state
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        b.rdkv_decode_attn(cache, q, out_g, lse_g)
+    for i in range(4):
+        out_g.fill_(float("nan"))
+        lse_g.fill_(float("nan"))
+        if other_cache is not None:                           # eager work of the same library between the replays
+            b.rdkv_decode_attn(other_cache, q)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), f"replay {i} differs from the eager result"
+        assert torch.equal(lse_g, lse_e)
+
+
+def test_graph_replay_tokenwise_with_16_bit_rows_and_a_tail():
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(2500,))
+    rng = np.random.default_rng(31)
+    bits = [rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(wl.hkv, T), p=[.3, .25, .2, .15, .1])
+            for T in inp["seq_lens"]]
+    cache, _ = _pack_both(b, wl, inp, dev, bits)
+    other, _ = _pack_both(b, wl, inp, dev, [np.full_like(bits[0], 4)])
+    b.rdkv_cache_reserve_tail(cache, 64)
+    kn = torch.randn((1, wl.hkv, 128), device="cuda").to(torch.bfloat16)
+    for _ in range(5):
+        b.rdkv_cache_append(cache, kn, kn)
+    _replay_equals_eager(b, cache, dev["q"], other)
+    cache.free()
+    other.free()
+
+
+def test_graph_replay_mixed():
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(1800,))
+    bt, bc = _random_maps(np.random.default_rng(32), inp["seq_lens"], wl.hkv, [.3, .3, .2, .1, .1], [.1, .4, .3, .15, .05])
+    cache, _ = _pack_both_mixed(b, wl, inp, dev, bt, bc)
+    _replay_equals_eager(b, cache, dev["q"])
+    cache.free()
+
+
+def test_graph_replay_bf16_path():
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(3000,))
+    ws = torch.empty(b.rdkv_decode_bf16_workspace_bytes(inp["seq_lens"], wl.hq, wl.hkv), dtype=torch.uint8, device="cuda")
+    out_e, lse_e = b.rdkv_decode_attn_bf16(dev["K"], dev["V"], inp["seq_lens"], wl.hq, wl.hkv, dev["q"], workspace=ws)
+    torch.cuda.synchronize()
+    out_g, lse_g = torch.empty_like(out_e), torch.empty_like(lse_e)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        b.rdkv_decode_attn_bf16(dev["K"], dev["V"], inp["seq_lens"], wl.hq, wl.hkv, dev["q"], out=out_g, lse=lse_g,
+                                workspace=ws)
+    for i in range(3):
+        out_g.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e) and torch.equal(lse_g, lse_e), f"replay {i} differs"

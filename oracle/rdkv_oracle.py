@@ -674,20 +674,23 @@ def k_meta_bytes_mixed(sl):
     return 32 * sl["n_qsteps"]
 
 
-def quantize_channelwise(Krows, bits_ch):
-    """Channel-wise K quantization of the retained rows of one tier segment.
+def quantize_channelwise(Krows, bits_ch, group_tokens=K_TOKEN_GROUP):
+    """Channel-wise K quantization of retained rows.
 
-    The paper uses one scale and zero-point per channel (App. B); this build's
-    layout groups 32 consecutive retained tokens of a channel (half a tile of the
-    segment; the last group may be short), with the same quantizer as elsewhere
-    (fp16 scale, fp16 offset = group minimum, fp32 arithmetic in a fixed order).
+    group_tokens = None: one scale and zero-point per channel over all the rows given --
+    the paper's own format (App. B: s_c, z_c per channel; the rows are then all the
+    retained tokens of a (sequence, KV head)).  group_tokens = 32 (this build's default
+    layout): groups of 32 consecutive rows of a channel (half a tile of a tier segment;
+    the last group may be short).  Same quantizer as elsewhere (fp16 scale, fp16 offset =
+    group minimum, fp32 arithmetic in a fixed order).
     Krows: float32 [n, d] bf16-exact, in packed order.  Returns
       codes  uint16 [n, d]: integer codes (tiers 8/4/2), bf16 bit patterns (tier 16), 0 (tier 0)
       scale, off  uint16 [groups, d]: fp16 bit patterns (0 for tiers 16 and 0)."""
     Krows = _check_bf16_exact(Krows, "K")
     n, d = Krows.shape
     bits_ch = np.asarray(bits_ch, dtype=np.uint8)
-    ng = (n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP
+    gt = max(n, 1) if group_tokens is None else group_tokens
+    ng = (n + gt - 1) // gt
     codes = np.zeros((n, d), dtype=np.uint16)
     scale = np.zeros((ng, d), dtype=np.uint16)
     off = np.zeros((ng, d), dtype=np.uint16)
@@ -697,7 +700,7 @@ def quantize_channelwise(Krows, bits_ch):
             codes[:, c] = bf16_bits(Krows[:, c])
         elif b in (2, 4, 8):
             for t in range(ng):
-                rows = slice(t * K_TOKEN_GROUP, min(n, (t + 1) * K_TOKEN_GROUP))
+                rows = slice(t * gt, min(n, (t + 1) * gt))
                 cc, sc, mc = quantize_groups(Krows[rows, c][None, :], b)
                 codes[rows, c] = cc[0]
                 scale[t, c] = sc.view(np.uint16)[0]
@@ -705,9 +708,10 @@ def quantize_channelwise(Krows, bits_ch):
     return codes, scale, off
 
 
-def dequantize_channelwise(codes, scale, off, bits_ch):
+def dequantize_channelwise(codes, scale, off, bits_ch, group_tokens=K_TOKEN_GROUP):
     """K_hat float64 [n, d]: s*code + m for tiers 8/4/2, the bf16 value for tier 16,
-    exactly zero for an evicted channel (Sec. 3.2: a 0-bit channel is removed)."""
+    exactly zero for an evicted channel (Sec. 3.2: a 0-bit channel is removed).
+    group_tokens = None: scale and off hold one row that serves every token."""
     n, d = codes.shape
     out = np.zeros((n, d), dtype=np.float64)
     for c in range(d):
@@ -715,7 +719,7 @@ def dequantize_channelwise(codes, scale, off, bits_ch):
         if b == 16:
             out[:, c] = bf16_from_bits(codes[:, c]).astype(np.float64)
         elif b in (2, 4, 8):
-            t = np.arange(n) // K_TOKEN_GROUP
+            t = np.zeros(n, dtype=np.int64) if group_tokens is None else np.arange(n) // group_tokens
             s = scale[:, c].copy().view(np.float16).astype(np.float64)[t]
             m = off[:, c].copy().view(np.float16).astype(np.float64)[t]
             out[:, c] = s * codes[:, c].astype(np.float64) + m
@@ -756,7 +760,7 @@ def _k_slot_words(sl):
     return out
 
 
-def pack_k_tiles_mixed(codes, scale, off, bits_ch):
+def pack_k_tiles_mixed(codes, scale, off, bits_ch, per_unit=False):
     """Physical K tiles (64 tokens) of one tier segment in mixed mode.
 
     Tile data: token r of the tile owns n_words_padded 32-bit words (_k_word_offset);
@@ -765,6 +769,8 @@ def pack_k_tiles_mixed(codes, scale, off, bits_ch):
     Tile metadata: for token group G (rows 32G..32G+31 of the tile) and quantized step
     sq (4 consecutive slots of the 8/4/2-bit tiers): fp16 element 8 (G n_qsteps + sq) + e
     is the scale of the step's slot e, element + 4 its offset.
+    per_unit (one scale per channel over all retained tokens, App. B): the metadata is a
+    single record of that form for the whole segment (scale and off have one row).
     Rows beyond n in the last tile and padding slots are zero.
     Returns (data uint8, meta uint8)."""
     n, d = codes.shape
@@ -773,20 +779,24 @@ def pack_k_tiles_mixed(codes, scale, off, bits_ch):
     nt = (n + R - 1) // R
     nwp, nqs = sl["n_words_padded"], sl["n_qsteps"]
     data = np.zeros((nt, 64 * nwp), dtype="<u4")
-    meta = np.zeros((nt, 16 * nqs), dtype="<u2")
+    meta = np.zeros((min(nt, 1), 8 * nqs) if per_unit else (nt, 16 * nqs), dtype="<u2")
     cp = np.zeros((nt * R, d), dtype=np.uint32)
     cp[:n] = codes
     cp = cp.reshape(nt, R, d)
-    ng = scale.shape[0]
-    sg = np.zeros((2 * nt, d), dtype=np.uint16)
-    og = np.zeros((2 * nt, d), dtype=np.uint16)
-    sg[:ng], og[:ng] = scale, off
-    sg, og = sg.reshape(nt, 2, d), og.reshape(nt, 2, d)
+    if not per_unit:
+        ng = scale.shape[0]
+        sg = np.zeros((2 * nt, d), dtype=np.uint16)
+        og = np.zeros((2 * nt, d), dtype=np.uint16)
+        sg[:ng], og[:ng] = scale, off
+        sg, og = sg.reshape(nt, 2, d), og.reshape(nt, 2, d)
     rows = np.arange(R)
     qs = 0
     for (b, s, W, j), ch in zip(_k_slot_words(sl), sl["slot_ch"]):
         if b != 16:
-            if ch >= 0:
+            if ch >= 0 and per_unit and nt > 0:
+                meta[0, 8 * (qs // 4) + qs % 4] = scale[0, ch]
+                meta[0, 8 * (qs // 4) + 4 + qs % 4] = off[0, ch]
+            elif ch >= 0:
                 for G in range(2):
                     meta[:, 8 * (G * nqs + qs // 4) + qs % 4] = sg[:, G, ch]
                     meta[:, 8 * (G * nqs + qs // 4) + 4 + qs % 4] = og[:, G, ch]
@@ -798,23 +808,26 @@ def pack_k_tiles_mixed(codes, scale, off, bits_ch):
     return data.view(np.uint8).reshape(-1), meta.view(np.uint8).reshape(-1)
 
 
-def unpack_k_tiles_mixed(data, meta, n, bits_ch, d=128):
+def unpack_k_tiles_mixed(data, meta, n, bits_ch, d=128, per_unit=False):
     """Inverse of pack_k_tiles_mixed for the first n rows: (codes, scale, off)."""
     sl = channel_slots(bits_ch)
     R = TILE64_ROWS
     nt = (n + R - 1) // R
-    ng = (n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP
+    ng = 1 if per_unit else (n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP
     nwp, nqs = sl["n_words_padded"], sl["n_qsteps"]
     data = np.asarray(data, dtype=np.uint8).view("<u4").reshape(nt, 64 * nwp)
-    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape(nt, 16 * nqs)
+    meta = np.asarray(meta, dtype=np.uint8).view("<u2").reshape((1, 8 * nqs) if per_unit else (nt, 16 * nqs))
     codes = np.zeros((nt, R, d), dtype=np.uint16)
-    scale = np.zeros((2 * nt, d), dtype=np.uint16)
-    off = np.zeros((2 * nt, d), dtype=np.uint16)
+    scale = np.zeros((max(2 * nt, 1), d), dtype=np.uint16)
+    off = np.zeros((max(2 * nt, 1), d), dtype=np.uint16)
     rows = np.arange(R)
     qs = 0
     for (b, s, W, j), ch in zip(_k_slot_words(sl), sl["slot_ch"]):
         if b != 16:
-            if ch >= 0:
+            if ch >= 0 and per_unit:
+                scale[0, ch] = meta[0, 8 * (qs // 4) + qs % 4]
+                off[0, ch] = meta[0, 8 * (qs // 4) + 4 + qs % 4]
+            elif ch >= 0:
                 for G in range(2):
                     scale[G::2, ch] = meta[:, 8 * (G * nqs + qs // 4) + qs % 4]
                     off[G::2, ch] = meta[:, 8 * (G * nqs + qs // 4) + 4 + qs % 4]
@@ -862,14 +875,18 @@ def unpack_v16_tiles(data, n):
     return out.reshape(nt * R, 128)[:n]
 
 
-def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list):
+def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list, k_per_channel_scale=False):
     """Pack a ragged batch in mixed mode (Alg. 1 Stage 4 as printed: V rows sorted by
     b_t^V into sub-segments, K rows of the retained tokens with channels sorted by
     b_c^K).  bits_tok_list[s]: uint8 [Hkv, T_s] (V token map); bits_ch_list[s]: uint8
     [Hkv, d] (K channel map).  Arena: per item and per V tier (16, 8, 4, 2) the four
     segments K data, K meta, V data, V meta, each on a 256-byte boundary; the K
-    segments hold the channel-wise tiles of that tier's tokens.  Same keys as
-    build_cache_tokenwise plus 'bits_ch' [items, d] and 'mixed' = True."""
+    segments hold the channel-wise tiles of that tier's tokens.
+    k_per_channel_scale: the paper's own K format (App. B): one scale and zero-point per
+    channel over all retained tokens of the item (instead of groups of 32 tokens); every
+    non-empty tier segment then carries the same single metadata record.
+    Same keys as build_cache_tokenwise plus 'bits_ch' [items, d], 'mixed' = True and
+    'k_per_unit'."""
     items = []
     for Ks, Vs, bt, bc in zip(K_list, V_list, bits_tok_list, bits_ch_list):
         for h in range(Ks.shape[0]):
@@ -885,13 +902,22 @@ def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list):
         Vh = _check_bf16_exact(Vh, "V")
         idx = partition(bt)
         rec = {}
+        if k_per_channel_scale:          # the unit is the channel over every retained token, whatever its V tier
+            all_pos = np.concatenate([idx[b] for b in PACK_ORDER])
+            kc_all, ks_all, ko_all = quantize_channelwise(Kh[all_pos], bc, None)
+            row0 = 0
         for ti, b in enumerate(PACK_ORDER):
             pos = idx[b]
             n = len(pos)
             counts[i, ti] = n
             tier_idx.append(pos)
-            kc, ks, ko = quantize_channelwise(Kh[pos], bc)
-            kd, km = pack_k_tiles_mixed(kc, ks, ko, bc)
+            if k_per_channel_scale:
+                kc, ks, ko = kc_all[row0:row0 + n], ks_all, ko_all
+                row0 += n
+                kd, km = pack_k_tiles_mixed(kc, ks, ko, bc, per_unit=True)
+            else:
+                kc, ks, ko = quantize_channelwise(Kh[pos], bc)
+                kd, km = pack_k_tiles_mixed(kc, ks, ko, bc)
             if b == 16:
                 vcodes = bf16_bits(Vh[pos]).reshape(n, d)
                 vd, vm = pack_v16_tiles(vcodes), np.zeros(0, dtype=np.uint8)
@@ -917,13 +943,15 @@ def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list):
         "seg_off": seg_off, "arena": arena, "canon": canon, "d": d, "hkv": K_list[0].shape[0],
         "seq_lens": [k.shape[1] for k in K_list], "mixed": True,
         "bits_ch": np.stack([it[3] for it in items]).astype(np.uint8),
+        "k_per_unit": bool(k_per_channel_scale),
     }
 
 
-def stored_bytes_mixed(counts, bits_ch, d=128):
+def stored_bytes_mixed(counts, bits_ch, d=128, k_per_channel_scale=False):
     """Bytes a decode step must read in mixed mode (unpadded): per item and V tier with n
     rows, K codes n * sum_c b_c / 8, K metadata ceil(n / 32) * 4 per quantized channel (one fp16
-    scale and offset per channel and group of 32 retained tokens), and
+    scale and offset per channel and group of 32 retained tokens; with one scale per channel
+    the record is stored once per non-empty tier segment), and
     the V rows as in token-wise mode (n * (16 b + 16), or n * 256 at 16 bits)."""
     counts = np.asarray(counts, dtype=np.int64).reshape(-1, 4)
     total = 0
@@ -933,7 +961,8 @@ def stored_bytes_mixed(counts, bits_ch, d=128):
         nquant = int(((bc == 2) | (bc == 4) | (bc == 8)).sum())
         for ti, b in enumerate(PACK_ORDER):
             n = int(counts[i, ti])
-            total += n * kbits // 8 + ((n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP) * 4 * nquant
+            ngroups = (1 if n else 0) if k_per_channel_scale else (n + K_TOKEN_GROUP - 1) // K_TOKEN_GROUP
+            total += n * kbits // 8 + ngroups * 4 * nquant
             total += n * (row_bytes(b, d) + meta_bytes(b, d))
     return total
 
@@ -953,8 +982,10 @@ def unpack_item_mixed(cache, item):
             continue
         nt = (n + TILE64_ROWS - 1) // TILE64_ROWS
         o = [int(x) for x in seg_off[item, ti]]
-        kc, ksc, kof = unpack_k_tiles_mixed(arena[o[0]:o[0] + nt * tb], arena[o[1]:o[1] + nt * mb_], n, bc, d)
-        ks.append(dequantize_channelwise(kc, ksc, kof, bc))
+        pu = cache.get("k_per_unit", False)
+        kc, ksc, kof = unpack_k_tiles_mixed(arena[o[0]:o[0] + nt * tb], arena[o[1]:o[1] + (mb_ // 2 if pu else nt * mb_)],
+                                            n, bc, d, per_unit=pu)
+        ks.append(dequantize_channelwise(kc, ksc, kof, bc, None if pu else K_TOKEN_GROUP))
         if b == 16:
             vbits = unpack_v16_tiles(arena[o[2]:o[2] + nt * 16384], n)
             vs.append(bf16_from_bits(vbits).astype(np.float64))

@@ -993,3 +993,72 @@ def test_appended_zone_is_the_lse_merge_of_the_two_zones_and_survives_full_evict
             wa, wc = np.exp(lse_a[0, j] - m), np.exp(l_c - m)
             np.testing.assert_allclose(out[0, j], (wa * out_a[0, j] + wc * o_c) / (wa + wc), rtol=1e-11, atol=1e-12)
             assert abs(lse[0, j] - (m + np.log(wa + wc))) < 1e-11
+
+
+# ----------------------------------------------------------------------------
+# the paper's own K format: one scale and zero-point per channel over all retained tokens (App. B)
+# ----------------------------------------------------------------------------
+def test_per_channel_scale_is_one_group_over_the_whole_unit():
+    rng = np.random.default_rng(71)
+    n = 100
+    X = rand_bf16(rng, (n, 128), scale=2.0)
+    bc = rng.choice([0, 2, 4, 8, 16], 128).astype(np.uint8)
+    codes, sc, of = O.quantize_channelwise(X, bc, None)
+    assert sc.shape == (1, 128) and of.shape == (1, 128)
+    Xh = O.dequantize_channelwise(codes, sc, of, bc, None)
+    q = rng.standard_normal(128)
+    s = sc[0].copy().view(np.float16).astype(np.float64)
+    m = of[0].copy().view(np.float16).astype(np.float64)
+    for c in range(128):
+        b = int(bc[c])
+        if b in (2, 4, 8):
+            assert m[c] == float(X[:, c].min())                           # offset = minimum of the whole unit
+            assert np.abs(Xh[:, c] - X[:, c]).max() <= 0.5 * s[c] * (1 + 2 ** -10) + 0.125 * s[c] * (b == 8)
+            assert codes[:, c].max() <= (1 << b) - 1 and codes[:, c].min() == 0
+    # fusion identity with a single scaled query for every token (App. B): q.k_hat = sum (s q) code + sum m q
+    quant = np.isin(bc, (2, 4, 8))
+    raw16 = np.where(bc == 16)[0]
+    fused = codes[:, quant].astype(np.float64) @ (s[quant] * q[quant]) + np.dot(m[quant], q[quant]) \
+        + X[:, raw16].astype(np.float64) @ q[raw16]
+    np.testing.assert_allclose(fused, Xh @ q, rtol=1e-12, atol=1e-12)
+    # a unit of at most 32 tokens is the same thing in both formats
+    c32, s32, o32 = O.quantize_channelwise(X[:32], bc)
+    c1, s1, o1 = O.quantize_channelwise(X[:32], bc, None)
+    assert np.array_equal(c32, c1) and np.array_equal(s32, s1) and np.array_equal(o32, o1)
+
+
+def test_mixed_cache_with_per_channel_scale_bytes_and_decode():
+    rng = np.random.default_rng(72)
+    K, V, bt, bc = _mixed_case(rng)
+    cache = O.build_cache_mixed([K], [V], [bt], [bc], k_per_channel_scale=True)
+    for item in range(2):
+        sl = O.channel_slots(bc[item])
+        keep = np.concatenate([np.nonzero(bt[item] == b)[0] for b in O.PACK_ORDER])
+        codes, sc, of = O.quantize_channelwise(K[item][keep], bc[item], None)
+        for ti, b in enumerate(O.PACK_ORDER):
+            n = int((bt[item] == b).sum())
+            offs = cache["seg_off"][item, ti]
+            # the metadata segment of a non-empty tier is one record: 16 bytes per quantized step
+            nxt = int(offs[2])
+            assert int(offs[1]) + (16 * sl["n_qsteps"] if n else 0) <= nxt < int(offs[1]) + 16 * sl["n_qsteps"] + 256
+            if n:
+                m16 = cache["arena"][int(offs[1]):int(offs[1]) + 16 * sl["n_qsteps"]].view("<u2")
+                q0 = int(np.nonzero(sl["slot_ch"][sl["npad"][16]:] >= 0)[0][0])          # first real quantized slot
+                ch = int(sl["slot_ch"][sl["npad"][16] + q0])
+                assert m16[8 * (q0 // 4) + q0 % 4] == sc[0, ch] and m16[8 * (q0 // 4) + 4 + q0 % 4] == of[0, ch]
+    q = rand_bf16(rng, (1, 8, 128))
+    out, lse = O.decode(cache, q)
+    for j in range(8):
+        h = j // 4
+        keep = np.concatenate([np.nonzero(bt[h] == b)[0] for b in O.PACK_ORDER])
+        codes, sc, of = O.quantize_channelwise(K[h][keep], bc[h], None)
+        Kh = O.dequantize_channelwise(codes, sc, of, bc[h], None)
+        rec = cache["canon"][h]
+        Vh = np.concatenate([O.bf16_from_bits(rec[16]["v_codes"]).astype(np.float64)] +
+                            [O.dequantize_groups(rec[b]["v_codes"].reshape(-1, 4, 32), rec[b]["v_scale"].view(np.float16),
+                                                 rec[b]["v_off"].view(np.float16)).reshape(-1, 128) for b in (8, 4, 2)])
+        o, l = _bruteforce_attention(q[0, j], Kh, Vh)
+        np.testing.assert_allclose(out[0, j], o, rtol=1e-11, atol=1e-12)
+    full = O.build_cache_mixed([K], [V], [bt], [bc])
+    assert O.stored_bytes_mixed(cache["counts"], cache["bits_ch"], k_per_channel_scale=True) < \
+        O.stored_bytes_mixed(full["counts"], full["bits_ch"])

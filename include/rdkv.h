@@ -71,6 +71,9 @@ typedef struct rdkv_config {
   int32_t group_size;       /* quantization group; must be 32 */
   const float* budget_bits; /* HOST [batch]: average bits per cache element for each sequence */
   float kv_split_rk;        /* r_K: share of the bit budget given to K in channel-wise mode (0.5) */
+  int32_t k_scale_per_channel; /* channel-wise mode: 0 (default) = a scale and zero-point per channel and group of 32
+                               retained tokens; 1 = one per channel over all retained tokens of the (sequence, KV
+                               head), the format of App. B (the scaled query is then formed once per decode step) */
   int32_t n_tiers;          /* number of entries of tiers[] (<= 5) */
   int32_t tiers[RDKV_MAX_TIERS];   /* ascending bit-widths out of {0,2,4,8,16} (Sec. 3: B) */
   float eps_v[RDKV_MAX_TIERS];     /* distortion table eps_V(b) aligned with tiers[] (Eq. 6, App. I) */

@@ -793,9 +793,10 @@ def pack_k_tiles_mixed(codes, scale, off, bits_ch, per_unit=False):
     qs = 0
     for (b, s, W, j), ch in zip(_k_slot_words(sl), sl["slot_ch"]):
         if b != 16:
-            if ch >= 0 and per_unit and nt > 0:
-                meta[0, 8 * (qs // 4) + qs % 4] = scale[0, ch]
-                meta[0, 8 * (qs // 4) + 4 + qs % 4] = off[0, ch]
+            if ch >= 0 and per_unit:
+                if nt > 0:
+                    meta[0, 8 * (qs // 4) + qs % 4] = scale[0, ch]
+                    meta[0, 8 * (qs // 4) + 4 + qs % 4] = off[0, ch]
             elif ch >= 0:
                 for G in range(2):
                     meta[:, 8 * (G * nqs + qs // 4) + qs % 4] = sg[:, G, ch]

@@ -41,7 +41,7 @@ class rdkv_config(ctypes.Structure):
         ("s_obs", ctypes.c_int32), ("pool_kernel", ctypes.c_int32), ("causal", ctypes.c_int32),
         ("k_mode", ctypes.c_int32), ("group_size", ctypes.c_int32),
         ("budget_bits", ctypes.POINTER(ctypes.c_float)),
-        ("kv_split_rk", ctypes.c_float),
+        ("kv_split_rk", ctypes.c_float), ("k_scale_per_channel", ctypes.c_int32),
         ("n_tiers", ctypes.c_int32), ("tiers", ctypes.c_int32 * 5),
         ("eps_v", ctypes.c_float * 5), ("eps_k", ctypes.c_float * 5),
         ("rel_tol", ctypes.c_float), ("max_iters", ctypes.c_int32),

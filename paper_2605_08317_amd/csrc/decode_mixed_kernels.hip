@@ -47,7 +47,7 @@ template <int VT, int NW, int HS>
 __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __restrict__ arena,
                                               const ItemK* __restrict__ ikp, int g, const uint16_t* __restrict__ q,
                                               float* __restrict__ part_acc, float* __restrict__ part_ml,
-                                              uint8_t* smem, int lds_steps, int lds_qsteps) {
+                                              uint8_t* smem, int lds_steps, int lds_qsteps, bool per_unit) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int blk = lane >> 2, j = lane & 3, G = lane >> 5;
@@ -97,12 +97,14 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
       }
       kw[4 * u] = v.x; kw[4 * u + 1] = v.y; kw[4 * u + 2] = v.z; kw[4 * u + 3] = v.w;
     }
-    const uint8_t* pm = km + static_cast<int64_t>(t) * km_bytes;
+    if (!per_unit) {   // scales per group of 32 tokens: a record per tile and token group
+      const uint8_t* pm = km + static_cast<int64_t>(t) * km_bytes;
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int sq = (lane & 31) + 32 * it;
-      kmeta[it] = make_uint4(0, 0, 0, 0);
-      if (sq < nqs) kmeta[it] = *reinterpret_cast<const uint4*>(pm + (G * nqs + sq) * 16);
+      for (int it = 0; it < 2; ++it) {
+        const int sq = (lane & 31) + 32 * it;
+        kmeta[it] = make_uint4(0, 0, 0, 0);
+        if (sq < nqs) kmeta[it] = *reinterpret_cast<const uint4*>(pm + (G * nqs + sq) * 16);
+      }
     }
   };
   auto load_v_piece = [&](int t, int piece, uint4 (&dst)[kVRegs]) __attribute__((always_inline)) {
@@ -118,6 +120,13 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
 #pragma unroll
   for (int w = 0; w < NW; ++w) kw[w] = 0;
   kmeta[0] = kmeta[1] = vmeta = make_uint4(0, 0, 0, 0);
+  if (per_unit) {      // one scale per channel over all retained tokens (App. B): a single record per segment
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int sq = (lane & 31) + 32 * it;
+      if (sq < nqs) kmeta[it] = *reinterpret_cast<const uint4*>(km + sq * 16);
+    }
+  }
   if (wave < ntiles) {
     load_k(wave);
     load_v(wave);
@@ -162,12 +171,11 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
   run.init();
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-  for (int tile = wave; tile < ntiles; tile += kWaves) {
-    const int next = tile + kWaves;
-    const bool more = next < ntiles;
-
-    // ---- scaled query of this tile's two token groups, and the bias sum_c m_c q_c --------------------------
-    float bias[HS];
+  // ---- scaled query of a tile's two token groups, and the bias sum_c m_c q_c ------------------------------------
+  // (per tile with 32-token groups; once per wavefront when a channel has one scale for all its tokens -- the
+  // paper's "scaled query computed once per decode step")
+  float bias[HS];
+  auto prep = [&]() __attribute__((always_inline)) {
     {
       float bp[HS][4];
 #pragma unroll
@@ -225,6 +233,13 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
       }
     }
     wave_lds_sync();
+  };
+  if (per_unit) prep();
+
+  for (int tile = wave; tile < ntiles; tile += kWaves) {
+    const int next = tile + kWaves;
+    const bool more = next < ntiles;
+    if (!per_unit) prep();
 
     // ---- logits x[hs][i] of token 4 blk + i and head 4 hs + j, in units of kKUnit ----------------------------
     float x[HS][4];
@@ -394,7 +409,7 @@ template <int NW, int HS>
 __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mixed_kernel(
     const Chunk* __restrict__ chunks, const uint8_t* __restrict__ arena, const ItemK* __restrict__ items_k,
     const uint16_t* __restrict__ q, float* part_acc, float* part_ml, int hq, int hkv, int lds_steps,
-    int lds_qsteps, int row_limit) {
+    int lds_qsteps, int row_limit, int per_unit) {
   extern __shared__ __align__(16) uint8_t smem[];
   const Chunk ch = chunks[blockIdx.x];
   const int g = hq / hkv;
@@ -409,17 +424,17 @@ __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mix
                                   reinterpret_cast<float*>(smem), reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2,
                                   pa, pm);
       break;
-    case 16: process_mixed<16, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
-    case 8: process_mixed<8, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
-    case 4: process_mixed<4, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
-    default: process_mixed<2, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps); break;
+    case 16: process_mixed<16, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    case 8: process_mixed<8, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    case 4: process_mixed<4, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    default: process_mixed<2, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
   }
 }
 
 template <int NW, int HS>
 hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int lds_steps,
                       int lds_qsteps, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv,
-                      int row_limit, hipStream_t st) {
+                      int row_limit, int per_unit, hipStream_t st) {
   const size_t lds = static_cast<size_t>(LdsPlan(lds_steps, lds_qsteps, HS, hq / hkv).total);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_mixed_kernel<NW, HS>),
@@ -427,7 +442,7 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((decode_mixed_kernel<NW, HS>), dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, items_k, q,
-                     part_acc, part_ml, hq, hkv, lds_steps, lds_qsteps, row_limit);
+                     part_acc, part_ml, hq, hkv, lds_steps, lds_qsteps, row_limit, per_unit);
   return hipGetLastError();
 }
 
@@ -435,12 +450,12 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
 
 hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                               float* part_ml, int hq, int hkv, int row_limit, hipStream_t st) {
+                               float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   const int hs = hq / hkv > 4 ? 2 : 1;
 #define RDKV_MIXED_LAUNCH(NW_, HS_)                                                                           \
   return launch_one<NW_, HS_>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, part_acc, part_ml, hq, \
-                              hkv, row_limit, st)
+                              hkv, row_limit, per_unit, st)
   if (hs == 1) {
     if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 1);
     if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 1);

@@ -133,7 +133,18 @@ struct PackArgs {
   int32_t v_only;              // mixed mode: K is packed channel-wise by pack_k_mixed_kernel
   const ItemK* items_k;        // [items] (mixed mode)
   const uint8_t* bits_ch;      // [items][128] (mixed mode)
+  uint32_t* k_range;           // [items][128][2]: ordered-integer images of a channel's minimum and maximum over all
+                               // retained tokens (one scale per channel, App. B), or null (groups of 32 tokens)
 };
+
+// monotone map float -> uint32 (and back), so that integer atomic min / max order floats
+__device__ __forceinline__ uint32_t float_to_ordered(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
 
 // 16-bit tier: the kept bf16 rows are copied verbatim, row-major (one thread = 64 bytes of K and of V)
 __global__ __launch_bounds__(256) void copy_rows_kernel(PackArgs a) {
@@ -316,6 +327,31 @@ __global__ __launch_bounds__(256) void pack_v16_tile64_kernel(PackArgs a) {
   }
 }
 
+// One scale per channel over all retained tokens (App. B): the channel's minimum and maximum over the kept rows of
+// all four tiers of the item.  k_range starts at (0xFFFFFFFF, 0).
+__global__ __launch_bounds__(256) void k_channel_range_kernel(PackArgs a) {
+  __shared__ uint32_t s_mn[2][kHeadDim], s_mx[2][kHeadDim];
+  const int item = blockIdx.y;
+  const int64_t first = a.idx_base[item * 4];
+  const int kept = a.counts[item * 4] + a.counts[item * 4 + 1] + a.counts[item * 4 + 2] + a.counts[item * 4 + 3];
+  const int c = threadIdx.x & (kHeadDim - 1), sub = threadIdx.x >> 7;
+  uint32_t mn = 0xFFFFFFFFu, mx = 0u;
+  for (int r = blockIdx.x * 2 + sub; r < kept; r += gridDim.x * 2) {
+    const int pos = a.tier_idx[first + r];
+    const float x = __uint_as_float(static_cast<uint32_t>(a.K[(a.item_row_off[item] + pos) * kHeadDim + c]) << 16);
+    const uint32_t k = float_to_ordered(x);
+    mn = min(mn, k);
+    mx = max(mx, k);
+  }
+  s_mn[sub][c] = mn;
+  s_mx[sub][c] = mx;
+  __syncthreads();
+  if (sub == 0 && kept > 0) {
+    atomicMin(&a.k_range[(static_cast<int64_t>(item) * kHeadDim + c) * 2], min(s_mn[0][c], s_mn[1][c]));
+    atomicMax(&a.k_range[(static_cast<int64_t>(item) * kHeadDim + c) * 2 + 1], max(s_mx[0][c], s_mx[1][c]));
+  }
+}
+
 // Channel-wise K of one 64-token tile (Sec. 3.2 Stage 3 on the retained tokens): every channel is quantized at
 // its own bit-width over each half of the tile (one group = 32 consecutive retained tokens of one channel) and the
 // codes are written in sorted-channel order.  Token r of the tile owns n_words_padded 32-bit words: word W at byte
@@ -364,11 +400,18 @@ __global__ __launch_bounds__(256) void pack_k_mixed_kernel(PackArgs a) {
     if (b == 16) {
       for (int r = 0; r < kKTokenGroup; ++r) s_codes[rb + r][c] = s_rows[rb + r][c];   // rows beyond `valid` are zero
     } else if ((b == 8 || b == 4 || b == 2) && vg > 0) {
-      float mn = __uint_as_float(static_cast<uint32_t>(s_rows[rb][c]) << 16), mx = mn;
-      for (int r = 1; r < vg; ++r) {
-        const float x = __uint_as_float(static_cast<uint32_t>(s_rows[rb + r][c]) << 16);
-        mn = fminf(mn, x);
-        mx = fmaxf(mx, x);
+      float mn, mx;
+      if (a.k_range) {   // the range of the whole unit
+        mn = ordered_to_float(a.k_range[(static_cast<int64_t>(item) * kHeadDim + c) * 2]);
+        mx = ordered_to_float(a.k_range[(static_cast<int64_t>(item) * kHeadDim + c) * 2 + 1]);
+      } else {
+        mn = __uint_as_float(static_cast<uint32_t>(s_rows[rb][c]) << 16);
+        mx = mn;
+        for (int r = 1; r < vg; ++r) {
+          const float x = __uint_as_float(static_cast<uint32_t>(s_rows[rb + r][c]) << 16);
+          mn = fminf(mn, x);
+          mx = fmaxf(mx, x);
+        }
       }
       mn = mn + 0.0f;
       const float Q = static_cast<float>((1 << b) - 1);
@@ -420,6 +463,17 @@ __global__ __launch_bounds__(256) void pack_k_mixed_kernel(PackArgs a) {
     dst[idx] = out;
   }
   const int nqs = s_ik.n_qsteps;
+  if (a.k_range) {   // one record for the whole segment, written by its first tile
+    if (blockIdx.x == 0) {
+      uint16_t* meta1 = reinterpret_cast<uint16_t*>(a.arena + so[1]);
+      for (int idx = tid; idx < 8 * nqs; idx += 256) {
+        const int sq = idx >> 3, e = idx & 3, is_off = (idx >> 2) & 1;
+        const int c = s_ik.slot_ch[s_ik.slot_base[1] + 4 * sq + e];
+        meta1[idx] = c >= 0 ? (is_off ? s_of[0][c] : s_sc[0][c]) : uint16_t(0);
+      }
+    }
+    return;
+  }
   uint16_t* meta = reinterpret_cast<uint16_t*>(a.arena + so[1] + static_cast<int64_t>(blockIdx.x) * s_ik.km_bytes);
   for (int idx = tid; idx < 16 * nqs; idx += 256) {
     const int G = idx / (8 * nqs), rem = idx - G * 8 * nqs;
@@ -457,11 +511,16 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
                              const int64_t* idx_base, const int32_t* counts, const int64_t* seg_off,
                              const int64_t* item_row_off, uint8_t* arena, int n_items,
                              const int32_t max_count[4], const ItemK* items_k, const uint8_t* bits_ch,
-                             hipStream_t st) {
+                             uint32_t* k_range, hipStream_t st) {
   const bool mixed = items_k != nullptr;
+  if (k_range) {   // k_range must hold (0xFFFFFFFF, 0) pairs on entry
+    PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, 0, 1, items_k, bits_ch, k_range};
+    hipLaunchKernelGGL(k_channel_range_kernel, dim3(64, n_items), dim3(256), 0, st, a);
+  }
   for (int ti = 0; ti < 4; ++ti) {
     if (max_count[ti] == 0) continue;
-    PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti, mixed ? 1 : 0, items_k, bits_ch};
+    PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti, mixed ? 1 : 0, items_k, bits_ch,
+               k_range};
     dim3 grid64((max_count[ti] + 63) / 64, n_items);   // 64 rows per workgroup in every kernel below
     dim3 block(256);
     if (mixed) hipLaunchKernelGGL(pack_k_mixed_kernel, grid64, block, 0, st, a);

@@ -23,7 +23,7 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
                              const int64_t* idx_base, const int32_t* counts, const int64_t* seg_off,
                              const int64_t* item_row_off, uint8_t* arena, int n_items,
                              const int32_t max_count[4], const ItemK* items_k, const uint8_t* bits_ch,
-                             hipStream_t st);
+                             uint32_t* k_range, hipStream_t st);
 int partition_block();
 int weights_block();
 size_t weights_scratch_floats(int64_t n_blocks, int64_t n_items, int64_t total_tokens, int R_pad, bool want_ch);
@@ -334,6 +334,7 @@ rdkv_status rdkv_config_default(rdkv_config* cfg) {
   cfg->k_mode = RDKV_K_TOKENWISE;
   cfg->group_size = kGroup;
   cfg->kv_split_rk = 0.5f;
+  cfg->k_scale_per_channel = 0;
   cfg->n_tiers = 5;
   const int t[5] = {0, 2, 4, 8, 16};
   const float ev[5] = {1.0f, 0.313f, 0.0140f, 4.9e-5f, 0.0f};
@@ -479,6 +480,7 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   rdkv_cache* c = new (std::nothrow) rdkv_cache();
   if (!c) return fail(RDKV_ERR_ALLOC, "host allocation failed");
   c->batch = cfg->batch; c->hq = cfg->hq; c->hkv = cfg->hkv; c->d = cfg->head_dim; c->k_mode = cfg->k_mode;
+  c->k_per_unit = (cfg->k_mode == RDKV_K_CHANNELWISE && cfg->k_scale_per_channel) ? 1 : 0;
   c->seq_lens.assign(cfg->seq_lens, cfg->seq_lens + cfg->batch);
   c->n_items = it.n_items; c->total_tokens = it.total_tokens;
   c->alloc = cfg->alloc; c->free_ = cfg->free_; c->alloc_user = cfg->alloc_user;
@@ -549,7 +551,8 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
                           npad * tier_row_bytes(bits), npad * tier_meta_bytes(bits)};
       if (mixed) {   // the K segments hold the channel-wise tiles of this tier's tokens
         sizes[0] = npad / kTile64 * c->items_k[i].kt_bytes;
-        sizes[1] = npad / kTile64 * c->items_k[i].km_bytes;
+        sizes[1] = c->k_per_unit ? (cnt > 0 ? c->items_k[i].km_bytes / 2 : 0)      // one record per segment
+                                 : npad / kTile64 * c->items_k[i].km_bytes;
       }
       for (int si = 0; si < 4; ++si) {
         cur = round_up(cur, kSegAlign);
@@ -566,7 +569,8 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
             kbits += pack_tier_bits(t2);
             nquant += t2 > 0;
           }
-        stored += cnt * kbits / 8 + (cnt + kKTokenGroup - 1) / kKTokenGroup * 4 * nquant;
+        const int64_t groups = c->k_per_unit ? (cnt > 0 ? 1 : 0) : (cnt + kKTokenGroup - 1) / kKTokenGroup;
+        stored += cnt * kbits / 8 + groups * 4 * nquant;
         stored += cnt * (tier_row_bytes(bits) + tier_meta_bytes(bits));
       } else {
         stored += cnt * 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
@@ -600,7 +604,8 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
       for (int64_t r0 = 0; r0 < cnt; r0 += rows_per) {
         Chunk ch;
         ch.k_data = so[0] + (mixed ? r0 / kTile64 * c->items_k[i].kt_bytes : r0 * tier_row_bytes(bits));
-        ch.k_meta = so[1] + (mixed ? r0 / kTile64 * c->items_k[i].km_bytes : r0 * tier_meta_bytes(bits));
+        ch.k_meta = so[1] + (mixed ? (c->k_per_unit ? 0 : r0 / kTile64 * c->items_k[i].km_bytes)
+                                   : r0 * tier_meta_bytes(bits));
         ch.v_data = so[2] + r0 * tier_row_bytes(bits);
         ch.v_meta = so[3] + r0 * tier_meta_bytes(bits);
         ch.rows = static_cast<int32_t>(std::min<int64_t>(rows_per, cnt - r0));
@@ -667,10 +672,20 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
     if (kept > 0) {
       PACK_HIP(launch_tier_scatter(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_idx_base, c->d_tier_idx,
                                    static_cast<int>(n), it.max_T, st));
+      uint32_t* d_krange = nullptr;
+      std::vector<uint32_t> h_krange;
+      if (c->k_per_unit) {   // per-channel (minimum, maximum) over all retained tokens, as ordered integers
+        d_krange = tmp.get<uint32_t>(n * kHeadDim * 2);
+        if (!d_krange) return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
+        h_krange.resize(static_cast<size_t>(n) * kHeadDim * 2);
+        for (size_t k = 0; k < h_krange.size(); k += 2) { h_krange[k] = 0xFFFFFFFFu; h_krange[k + 1] = 0u; }
+        PACK_HIP(hipMemcpyAsync(d_krange, h_krange.data(), h_krange.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+      }
       TimedScope ts(RDKV_TIME_PACK, st);
       PACK_HIP(launch_quant_pack(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), c->d_tier_idx,
                                  d_idx_base, d_counts, d_seg_off, d_tok_off, c->d_arena, static_cast<int>(n),
-                                 max_count, mixed ? c->d_items_k : nullptr, mixed ? c->d_bits_ch : nullptr, st));
+                                 max_count, mixed ? c->d_items_k : nullptr, mixed ? c->d_bits_ch : nullptr, d_krange, st));
+      PACK_HIP(hipStreamSynchronize(st));   // h_krange goes out of scope
     }
     PACK_HIP(hipStreamSynchronize(st));   // host vectors and scratch go out of scope
   }
@@ -716,7 +731,7 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
       RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->chunks.size()) + live_tail_chunks(c), c->d_arena,
                                    c->d_items_k, c->max_k_words, c->max_k_steps, c->max_k_qsteps,
                                    static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
-                                   c->hq, c->hkv, c->tail_len, st));
+                                   c->hq, c->hkv, c->tail_len, c->k_per_unit, st));
     }
     RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
                                         static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));

@@ -81,7 +81,7 @@ hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t*
                                float* part_acc, float* part_ml, int hq, int hkv, int row_limit, hipStream_t st);
 hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                               float* part_ml, int hq, int hkv, int row_limit, hipStream_t st);
+                               float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st);
 
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);
@@ -100,6 +100,7 @@ struct PackItemDesc;   // compress_kernels
 // The opaque handle of the C ABI.
 struct rdkv_cache {
   int32_t batch = 0, hq = 0, hkv = 0, d = 0, k_mode = 0;
+  int32_t k_per_unit = 0;               // mixed mode: one K scale per channel over all retained tokens (App. B)
   std::vector<int32_t> seq_lens;
   int64_t n_items = 0;
   int64_t total_tokens = 0;             // sum_s hkv * T_s

@@ -19,14 +19,15 @@ def _random_maps(rng, seq_lens, hkv, p_tok, p_ch):
     return bt, bc
 
 
-def _pack_both_mixed(b, wl, inp, dev, bt, bc):
-    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, k_mode=b.RDKV_K_CHANNELWISE)
+def _pack_both_mixed(b, wl, inp, dev, bt, bc, per_channel_scale=False):
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, k_mode=b.RDKV_K_CHANNELWISE,
+                   k_scale_per_channel=int(per_channel_scale))
     bt_flat = torch.from_numpy(np.concatenate([x.reshape(-1) for x in bt])).cuda()
     bc_flat = torch.from_numpy(np.concatenate([x.reshape(-1) for x in bc])).cuda()
     cache = b.rdkv_pack(cfg, dev["K"], dev["V"], bt_flat, bc_flat)
     Ks = _split(inp["K"], inp["seq_lens"], wl.hkv, wl.d)
     Vs = _split(inp["V"], inp["seq_lens"], wl.hkv, wl.d)
-    ref = O.build_cache_mixed(Ks, Vs, bt, bc)
+    ref = O.build_cache_mixed(Ks, Vs, bt, bc, k_per_channel_scale=per_channel_scale)
     return cache, ref
 
 
@@ -40,7 +41,8 @@ def _assert_cache_equal_mixed(b, cache, ref):
     if not np.array_equal(arena, ref["arena"]):
         bad = np.nonzero(arena != ref["arena"])[0]
         raise AssertionError(f"arena differs at {len(bad)} bytes, first at {bad[:8]}")
-    assert cache.stats()["stored_bytes"] == O.stored_bytes_mixed(ref["counts"], ref["bits_ch"])
+    assert cache.stats()["stored_bytes"] == O.stored_bytes_mixed(ref["counts"], ref["bits_ch"],
+                                                                 k_per_channel_scale=ref["k_per_unit"])
 
 
 CASES = [
@@ -188,3 +190,19 @@ def test_allocate_mixed_with_other_kv_splits(r_k):
         n_kept = int((rt > 0).sum())
         total_bits = int(rt.astype(np.int64).sum()) * 128 + int(rc.astype(np.int64).sum()) * n_kept
         assert total_bits <= 1.5 * 2 * T * 128                    # whole-cache budget
+
+
+# the paper's own K format (App. B): one scale and zero-point per channel over all retained tokens
+@pytest.mark.parametrize("name,kw,p_tok,p_ch", [CASES[0], CASES[1], CASES[3], CASES[5], CASES[6]])
+def test_per_channel_scale_pack_and_decode(name, kw, p_tok, p_ch):
+    b = B()
+    wl, inp, dev = _inputs(name, **kw)
+    bt, bc = _random_maps(np.random.default_rng(12), inp["seq_lens"], wl.hkv, p_tok, p_ch)
+    bt[0][0, :] = 0                                    # one head with nothing retained
+    cache, ref = _pack_both_mixed(b, wl, inp, dev, bt, bc, per_channel_scale=True)
+    _assert_cache_equal_mixed(b, cache, ref)
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    ref_out, ref_lse = O.decode(ref, _np(inp["q"]))
+    _check_decode(out, lse, ref_out, ref_lse)
+    cache.free()

@@ -1097,6 +1097,59 @@ def decode_dense(K_list, V_list, q):
 
 
 # --------------------------------------------------------------------------
+# Distortion-table calibration (App. B "Calibration"; App. I, Table 9)
+# --------------------------------------------------------------------------
+CALIB_BITS = (2, 4, 8)
+
+
+def _nmse(x, x_hat):
+    """Normalized squared error of one (sequence, KV head) slice: sum (x - x_hat)^2 / sum x^2
+    in fp64; a slice that is all zero reports 0."""
+    x = np.asarray(x, dtype=np.float64)
+    den = float((x * x).sum())
+    if den == 0.0:
+        return 0.0
+    e = x - np.asarray(x_hat, dtype=np.float64)
+    return float((e * e).sum()) / den
+
+
+def calibrate_eps(K_list, V_list, k_channelwise=False, k_per_channel_scale=False):
+    """eps(b) of this build's quantizer on supplied K and V, b in (2, 4, 8): the normalized
+    distortion the knapsack of Eq. 6 consumes (App. I: per-token NMSE for V, per-channel NMSE
+    for K; eps(0) = 1 and eps(16) = 0 hold by definition and are not computed).  The paper
+    estimates the table once per (layer, head) slice and averages; the slice values are
+    returned here and averaging is left to the caller.
+
+    Every token is retained (calibration sees the uncompressed prefix).  V: every token row in
+    groups of 32 channels.  K: as V when k_channelwise is false (K rows share the token map);
+    else per channel in groups of 32 consecutive tokens starting at token 0 (the last group may
+    be short), or one scale per channel over all tokens with k_per_channel_scale (App. B).
+    Returns (eps_k, eps_v): float64 [items, 3], item = s * Hkv + h."""
+    rows_k, rows_v = [], []
+    for Ks, Vs in zip(K_list, V_list):
+        Ks = _check_bf16_exact(Ks, "K")
+        Vs = _check_bf16_exact(Vs, "V")
+        hkv, T, d = Ks.shape
+        for h in range(hkv):
+            ek, ev = [], []
+            for b in CALIB_BITS:
+                cv, sv, mv = quantize_groups(Vs[h].reshape(T, d // GROUP, GROUP), b)
+                ev.append(_nmse(Vs[h], dequantize_groups(cv, sv, mv).reshape(T, d)))
+                if not k_channelwise:
+                    ck, sk, mk = quantize_groups(Ks[h].reshape(T, d // GROUP, GROUP), b)
+                    ek.append(_nmse(Ks[h], dequantize_groups(ck, sk, mk).reshape(T, d)))
+                else:
+                    gt = None if k_per_channel_scale else K_TOKEN_GROUP
+                    bc = np.full(d, b, dtype=np.uint8)
+                    ck, sk, mk = quantize_channelwise(Ks[h], bc, group_tokens=gt)
+                    ek.append(_nmse(Ks[h], dequantize_channelwise(ck, sk, mk, bc, group_tokens=gt)))
+            rows_k.append(ek)
+            rows_v.append(ev)
+    return (np.asarray(rows_k, dtype=np.float64).reshape(-1, 3),
+            np.asarray(rows_v, dtype=np.float64).reshape(-1, 3))
+
+
+# --------------------------------------------------------------------------
 # Whole compression pass, token-wise mode (Alg. 1 with K sharing the token map)
 # --------------------------------------------------------------------------
 def compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B,

@@ -1062,3 +1062,94 @@ def test_mixed_cache_with_per_channel_scale_bytes_and_decode():
     full = O.build_cache_mixed([K], [V], [bt], [bc])
     assert O.stored_bytes_mixed(cache["counts"], cache["bits_ch"], k_per_channel_scale=True) < \
         O.stored_bytes_mixed(full["counts"], full["bits_ch"])
+
+
+# ---- distortion-table calibration (App. B "Calibration", App. I) --------------------------------------------------
+def _grid_group(bits, rng):
+    """32 values m + s (code + delta), s a power of two, delta = +-1/4 except on the two end points: the quantizer
+    must find exactly these codes, and every inner element is off by exactly s/4.  All values are bf16-exact."""
+    Q = (1 << bits) - 1
+    s = 2.0 ** -7
+    pool = list(range(1, min(Q, 64)))               # codes whose 4 code +- 1 still fits 8 significant bits
+    inner = rng.choice(pool, size=30, replace=True)
+    delta = rng.choice([-0.25, 0.25], size=30)
+    x = np.concatenate([[0.0], s * (inner + delta), [s * Q]]).astype(np.float32)
+    rng.shuffle(x)
+    return x, 30 * (s / 4) ** 2
+
+
+@pytest.mark.parametrize("channelwise", [False, True])
+def test_calibration_closed_form_on_grid_data(channelwise):
+    rng = np.random.default_rng(11)
+    T, d = 64, 128
+    for bi, bits in enumerate(O.CALIB_BITS):
+        X = np.zeros((T, d), dtype=np.float32)
+        err = 0.0
+        for a in range(T):                            # row a, group grp (token-wise view)
+            for grp in range(4):
+                X[a, 32 * grp:32 * grp + 32], e = _grid_group(bits, rng)
+                err += e
+        want = err / float((X.astype(np.float64) ** 2).sum())
+        assert np.array_equal(bf16_round(X), X)
+        if channelwise:                               # the same groups laid along the token axis of a channel
+            Kc = X.reshape(T, 4, 32).transpose(1, 2, 0).reshape(128, T)          # token = 32 grp + i, channel = a
+            Kc = np.concatenate([Kc, Kc], axis=1)                               # d = 128 channels
+            want = 2 * err / float((Kc.astype(np.float64) ** 2).sum())
+            ek, _ = O.calibrate_eps([Kc[None]], [Kc[None]], k_channelwise=True)
+        else:
+            ek, ev = O.calibrate_eps([X[None]], [X[None]])
+            assert ev[0, bi] == pytest.approx(want, rel=1e-12)
+        assert ek[0, bi] == pytest.approx(want, rel=1e-12)
+
+
+def test_calibration_axes_transposition_and_unit_scale():
+    # channel-wise K in groups of 32 tokens is token-wise quantization of the transposed matrix
+    rng = np.random.default_rng(12)
+    X = bf16_round(rng.standard_normal((128, 128)).astype(np.float32) * np.float32(3.0))
+    ek_ch, ev = O.calibrate_eps([X[None]], [X[None]], k_channelwise=True)
+    ek_tr, _ = O.calibrate_eps([X.T.copy()[None]], [X[None]])
+    np.testing.assert_allclose(ek_ch, ek_tr, rtol=1e-13)
+    # with at most 32 tokens a channel's only group is the whole unit: both K formats agree
+    Y = X[:29]
+    a, _ = O.calibrate_eps([Y[None]], [Y[None]], k_channelwise=True)
+    b_, _ = O.calibrate_eps([Y[None]], [Y[None]], k_channelwise=True, k_per_channel_scale=True)
+    np.testing.assert_array_equal(a, b_)
+    # one scale over a long unit is coarser than one per 32 tokens
+    c, _ = O.calibrate_eps([X[None]], [X[None]], k_channelwise=True, k_per_channel_scale=True)
+    assert (c > ek_ch).all()
+    # powers of two scale the data, the scales and the errors alike
+    e1 = O.calibrate_eps([X[None]], [X[None]])
+    e2 = O.calibrate_eps([(X * np.float32(0.25))[None]], [(X * np.float32(0.25))[None]])
+    np.testing.assert_allclose(e1[0], e2[0], rtol=1e-12)
+    np.testing.assert_allclose(e1[1], e2[1], rtol=1e-12)
+
+
+def test_calibration_on_gaussian_data_has_the_printed_order_of_magnitude():
+    # uniform quantization noise: a step of range / Q gives a mean squared error of step^2 / 12; Table 9's entries
+    # (five models) span 0.149-0.347, 0.0062-0.0164 and 2.2e-5-1.5e-4 (one outlier at 4.4e-3)
+    tab = _read_table9()
+    lo = [min(min(ek[i], ev[i]) for ek, ev in tab.values()) for i in (1, 2, 3)]
+    hi = [max(max(ek[i], ev[i]) for ek, ev in tab.values()) for i in (1, 2, 3)]
+    rng = np.random.default_rng(13)
+    K = bf16_round(rng.standard_normal((2, 512, 128)).astype(np.float32))
+    V = bf16_round(rng.standard_normal((2, 512, 128)).astype(np.float32))
+    ek, ev = O.calibrate_eps([K], [V])
+    assert ek.shape == (2, 3) and ev.shape == (2, 3)
+    for e in (ek, ev):
+        assert (e[:, 0] > e[:, 1]).all() and (e[:, 1] > e[:, 2]).all()
+        for i in range(3):
+            assert (e[:, i] > 0.5 * lo[i]).all() and (e[:, i] < 2.0 * hi[i]).all()
+    # and against the noise model itself: E[step^2] / 12 with the measured group ranges
+    x = V[0].reshape(512, 4, 32)
+    rng_g = x.max(-1).astype(np.float64) - x.min(-1).astype(np.float64)
+    for i, b in enumerate(O.CALIB_BITS[1:], start=1):     # 2-bit noise is far from uniform; 4- and 8-bit are close
+        model = float((32 * (rng_g / ((1 << b) - 1)) ** 2 / 12).sum() / (V[0].astype(np.float64) ** 2).sum())
+        assert ev[0, i] == pytest.approx(model, rel=0.1)
+
+
+def test_calibration_degenerate_slices():
+    Z = np.zeros((1, 40, 128), dtype=np.float32)
+    C = np.full((1, 40, 128), 1.5, dtype=np.float32)      # constant groups: scale 0, offset = the value: exact
+    for kw in ({}, {"k_channelwise": True}, {"k_channelwise": True, "k_per_channel_scale": True}):
+        ek, ev = O.calibrate_eps([Z, C], [Z, C], **kw)
+        assert not ek.any() and not ev.any()

@@ -194,6 +194,18 @@ def main():
     compress_wall_ms = (time.time() - t0) * 1e3
     kt = {name: b.rdkv_kernel_timing_read(kind) for name, kind in
           (("weights", b.RDKV_TIME_WEIGHTS), ("allocate", b.RDKV_TIME_ALLOCATE), ("pack", b.RDKV_TIME_PACK))}
+    # distortion-table calibration on layer 0 (App. I): K and V read once each, three quantizers per element
+    calib = {}
+    for name, kw in (("token_rows", {}), ("k_channels_32_tokens", {"k_mode": b.RDKV_K_CHANNELWISE}),
+                     ("k_whole_channel", {"k_mode": b.RDKV_K_CHANNELWISE, "k_scale_per_channel": 1})):
+        ccfg = b.Config([T], hq, hkv, **kw)
+        b.rdkv_calibrate_eps(ccfg, Ks[0], Vs[0])
+        b.rdkv_kernel_timing_read(b.RDKV_TIME_CALIBRATE)
+        ek, ev = b.rdkv_calibrate_eps(ccfg, Ks[0], Vs[0])
+        _, ms_c = b.rdkv_kernel_timing_read(b.RDKV_TIME_CALIBRATE)
+        c_bytes = (3 if name == "k_whole_channel" else 2) * per_layer_elems * 2
+        calib[name] = {"eps_k_2_4_8": [float(x) for x in ek.mean(axis=0)], "eps_v_2_4_8": [float(x) for x in ev.mean(axis=0)],
+                       "kernel_ms": ms_c, "achieved_gbs": c_bytes / (ms_c * 1e-3) / 1e9}
     b.rdkv_kernel_timing_enable(False)
     stats = [c.stats() for c in caches]
     stored = sum(s["stored_bytes"] for s in stats)
@@ -439,6 +451,7 @@ def main():
         "compress": {"wall_ms_all_layers": compress_wall_ms,
                      "kernel_ms": {k: v[1] for k, v in kt.items()},
                      "launches": {k: v[0] for k, v in kt.items()}},
+        "calibration": calib,
         "paper_context": "paper: 4.5x decode speedup, 1.9x peak memory vs full-cache FlashAttention-2 at 128K on an "
                          "A100 64GB (whole model); not comparable, context only",
         "setup_s": time.time() - t_setup,

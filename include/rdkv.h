@@ -210,7 +210,8 @@ enum {
   RDKV_TIME_WEIGHTS = 2,
   RDKV_TIME_ALLOCATE = 3,
   RDKV_TIME_PACK = 4,
-  RDKV_TIME_KINDS = 5
+  RDKV_TIME_CALIBRATE = 5,
+  RDKV_TIME_KINDS = 6
 };
 rdkv_status rdkv_kernel_timing_enable(int32_t enable);
 rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* total_ms);
@@ -229,6 +230,24 @@ rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* tot
 rdkv_status rdkv_cache_reserve_tail(rdkv_cache* cache, int32_t max_new_tokens, void* stream);
 rdkv_status rdkv_cache_append(rdkv_cache* cache, const void* k_new, const void* v_new, void* stream);
 int32_t rdkv_cache_tail_len(const rdkv_cache* cache);
+
+/*
+ * Calibration of the distortion table (App. B "Calibration"; App. I, Table 9) on the library's own quantizer: for
+ * every (sequence, KV head) slice and b in {2, 4, 8} the normalized squared error
+ *     eps(b) = sum (x - x_hat_b)^2 / sum x^2
+ * over all tokens of the slice (every token retained; 0 for a slice that is all zero).  eps(0) = 1 (removal) and
+ * eps(16) = 0 (bits kept verbatim) hold by definition and are not returned.  The paper averages the slice values over
+ * layers, heads and calibration sequences; that average is left to the caller.
+ *   K, V    DEVICE bf16, ragged [hkv][T_s][d] blocks (cfg: batch, hq, hkv, head_dim, seq_lens, k_mode,
+ *           k_scale_per_channel; budgets, tiers and the probe fields are not read; T_s >= 1)
+ *   eps_v   HOST double out [items][3] (b = 2, 4, 8): V quantized per token, groups of 32 channels
+ *   eps_k   HOST double out [items][3]: K at the granularity cfg selects -- token-wise: as V; channel-wise: groups of
+ *           32 consecutive tokens of a channel starting at token 0 (last group may be short), or one scale per
+ *           channel over all tokens when k_scale_per_channel is set
+ * Codes are those rdkv_pack would store; errors and sums are fp64.  Synchronises `stream` (host results).
+ */
+rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void* V, double* eps_k, double* eps_v,
+                               void* stream);
 
 /* Introspection (tests, benchmarks). */
 rdkv_status rdkv_cache_stats(const rdkv_cache* cache, rdkv_stats* out);

@@ -24,11 +24,12 @@ STATUS_NAMES = {0: "RDKV_OK", 1: "RDKV_ERR_INVALID_ARG", 2: "RDKV_ERR_SHAPE", 3:
 EXPORTED_SYMBOLS = [
     "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_pack",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
-    "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len",
+    "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_calibrate_eps",
     "rdkv_cache_stats", "rdkv_cache_export_bytes", "rdkv_cache_export", "rdkv_cache_free",
     "rdkv_kernel_timing_enable", "rdkv_kernel_timing_read",
 ]
-(RDKV_TIME_DECODE_TIERED, RDKV_TIME_DECODE_BF16, RDKV_TIME_WEIGHTS, RDKV_TIME_ALLOCATE, RDKV_TIME_PACK) = range(5)
+(RDKV_TIME_DECODE_TIERED, RDKV_TIME_DECODE_BF16, RDKV_TIME_WEIGHTS, RDKV_TIME_ALLOCATE, RDKV_TIME_PACK,
+ RDKV_TIME_CALIBRATE) = range(6)
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -84,6 +85,7 @@ def _load():
     lib.rdkv_cache_append.argtypes = [vp, vp, vp, vp]
     lib.rdkv_cache_tail_len.argtypes = [vp]
     lib.rdkv_cache_tail_len.restype = i32
+    lib.rdkv_calibrate_eps.argtypes = [cfgp, vp, vp, vp, vp, vp]
     lib.rdkv_cache_stats.argtypes = [vp, ctypes.POINTER(rdkv_stats)]
     lib.rdkv_cache_export_bytes.argtypes = [vp, i32]
     lib.rdkv_cache_export_bytes.restype = sz
@@ -231,6 +233,16 @@ def rdkv_cache_append(cache, k_new, v_new):
 
 def rdkv_cache_tail_len(cache):
     return int(lib.rdkv_cache_tail_len(cache.h))
+
+
+def rdkv_calibrate_eps(cfg, K, V):
+    """(eps_k, eps_v): float64 [items, 3] for b = 2, 4, 8."""
+    n = len(cfg.seq_lens) * cfg.hkv
+    eps_k = np.zeros((n, 3), dtype=np.float64)
+    eps_v = np.zeros((n, 3), dtype=np.float64)
+    _check(lib.rdkv_calibrate_eps(cfg.ref(), _ptr(K), _ptr(V), eps_k.ctypes.data_as(ctypes.c_void_p),
+                                  eps_v.ctypes.data_as(ctypes.c_void_p), _stream()))
+    return eps_k, eps_v
 
 
 def rdkv_decode_bf16_workspace_bytes(seq_lens, hq, hkv, head_dim=128):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librdkv.so")
-SOURCES = ["rdkv_api.hip", "decode_kernels.hip", "decode_mfma_kernels.hip", "decode_mixed_kernels.hip", "pack_kernels.hip", "allocate_kernels.hip", "weights_kernels.hip"]
+SOURCES = ["rdkv_api.hip", "decode_kernels.hip", "decode_mfma_kernels.hip", "decode_mixed_kernels.hip", "pack_kernels.hip", "allocate_kernels.hip", "weights_kernels.hip", "calib_kernels.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

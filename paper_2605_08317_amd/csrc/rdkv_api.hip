@@ -34,6 +34,9 @@ hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off,
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
                            const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, hipStream_t st);
+hipError_t launch_calibrate(const uint16_t* K, const uint16_t* V, const int64_t* item_row_off, const int32_t* item_T,
+                            int n_items, int max_T, bool k_channelwise, bool k_whole_channel, double* acc_k,
+                            double* acc_v, uint32_t* range, hipStream_t st);
 hipError_t launch_count_kept(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U, int n_items,
                              int32_t* kept, hipStream_t st);
 }  // namespace rdkv
@@ -383,6 +386,56 @@ rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_ob
                           scratch, st));
   }
   RDKV_HIP(hipStreamSynchronize(st));   // scratch is released on return
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void* V, double* eps_k, double* eps_v,
+                               void* stream) {
+  if (!cfg) return fail(RDKV_ERR_INVALID_ARG, "cfg must not be null");
+  rdkv_status s = check_shape(cfg->batch, cfg->hq, cfg->hkv, cfg->head_dim, cfg->seq_lens);
+  if (s != RDKV_OK) return s;
+  if (cfg->k_mode != RDKV_K_TOKENWISE && cfg->k_mode != RDKV_K_CHANNELWISE)
+    return fail(RDKV_ERR_INVALID_ARG, "k_mode must be RDKV_K_TOKENWISE or RDKV_K_CHANNELWISE");
+  if (cfg->group_size != kGroup) return fail(RDKV_ERR_UNSUPPORTED, "group_size must be 32");
+  if (!K || !V || !eps_k || !eps_v) return fail(RDKV_ERR_INVALID_ARG, "K, V, eps_k and eps_v must not be null");
+  if (cfg->batch == 0) return RDKV_OK;
+  for (int b = 0; b < cfg->batch; ++b)
+    if (cfg->seq_lens[b] < 1) return fail(RDKV_ERR_SHAPE, "seq_lens[%d] = %d: calibration needs at least one token", b, cfg->seq_lens[b]);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al);
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  const size_t n = static_cast<size_t>(it.n_items);
+  const bool channelwise = cfg->k_mode == RDKV_K_CHANNELWISE;
+  const bool whole = channelwise && cfg->k_scale_per_channel != 0;
+  int64_t* d_off = tmp.get<int64_t>(n);
+  int32_t* d_T = tmp.get<int32_t>(n);
+  double* d_acc = tmp.get<double>(n * 8);                       // [K | V][items][4]
+  uint32_t* d_range = whole ? tmp.get<uint32_t>(n * kHeadDim * 2) : nullptr;
+  if (!d_off || !d_T || !d_acc || (whole && !d_range)) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  std::vector<double> h_acc(n * 8, 0.0);
+  std::vector<uint32_t> h_range;
+  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  RDKV_HIP(hipMemcpyAsync(d_acc, h_acc.data(), h_acc.size() * sizeof(double), hipMemcpyHostToDevice, st));
+  if (whole) {
+    h_range.resize(n * kHeadDim * 2);
+    for (size_t k = 0; k < h_range.size(); k += 2) { h_range[k] = 0xFFFFFFFFu; h_range[k + 1] = 0u; }
+    RDKV_HIP(hipMemcpyAsync(d_range, h_range.data(), h_range.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+  }
+  {
+    TimedScope ts(RDKV_TIME_CALIBRATE, st);
+    RDKV_HIP(launch_calibrate(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), d_off, d_T,
+                              static_cast<int>(n), it.max_T, channelwise, whole, d_acc, d_acc + n * 4, d_range, st));
+  }
+  RDKV_HIP(hipMemcpyAsync(h_acc.data(), d_acc, h_acc.size() * sizeof(double), hipMemcpyDeviceToHost, st));
+  RDKV_HIP(hipStreamSynchronize(st));
+  for (size_t i = 0; i < n; ++i)
+    for (int side = 0; side < 2; ++side) {
+      const double* a = h_acc.data() + (side * n + i) * 4;
+      double* dst = (side == 0 ? eps_k : eps_v) + i * 3;
+      for (int k = 0; k < 3; ++k) dst[k] = a[3] > 0.0 ? a[k] / a[3] : 0.0;
+    }
   return RDKV_OK;
 }
 

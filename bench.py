@@ -194,7 +194,7 @@ def main():
     compress_wall_ms = (time.time() - t0) * 1e3
     kt = {name: b.rdkv_kernel_timing_read(kind) for name, kind in
           (("weights", b.RDKV_TIME_WEIGHTS), ("allocate", b.RDKV_TIME_ALLOCATE), ("pack", b.RDKV_TIME_PACK))}
-    # distortion-table calibration on layer 0 (App. I): K and V read once each, three quantizers per element
+    # distortion-table calibration on layer 0 (Table 9's quantity): K and V read once each, three quantizers per element
     calib = {}
     for name, kw in (("token_rows", {}), ("k_channels_32_tokens", {"k_mode": b.RDKV_K_CHANNELWISE}),
                      ("k_whole_channel", {"k_mode": b.RDKV_K_CHANNELWISE, "k_scale_per_channel": 1})):

@@ -76,7 +76,7 @@ typedef struct rdkv_config {
                                head), the format of App. B (the scaled query is then formed once per decode step) */
   int32_t n_tiers;          /* number of entries of tiers[] (<= 5) */
   int32_t tiers[RDKV_MAX_TIERS];   /* ascending bit-widths out of {0,2,4,8,16} (Sec. 3: B) */
-  float eps_v[RDKV_MAX_TIERS];     /* distortion table eps_V(b) aligned with tiers[] (Eq. 6, App. I) */
+  float eps_v[RDKV_MAX_TIERS];     /* distortion table eps_V(b) aligned with tiers[] (Eq. 6, Table 9) */
   float eps_k[RDKV_MAX_TIERS];     /* distortion table eps_K(b) */
   float rel_tol;            /* bisection tolerance delta (App. B: 1e-2) */
   int32_t max_iters;        /* bisection steps I (App. B: 64) */
@@ -232,8 +232,8 @@ rdkv_status rdkv_cache_append(rdkv_cache* cache, const void* k_new, const void* 
 int32_t rdkv_cache_tail_len(const rdkv_cache* cache);
 
 /*
- * Calibration of the distortion table (App. B "Calibration"; App. I, Table 9) on the library's own quantizer: for
- * every (sequence, KV head) slice and b in {2, 4, 8} the normalized squared error
+ * Calibration of the distortion table (App. B "Calibration"; App. "Calibrated Distortion Tables", Table 9) on the
+ * library's own quantizer: for every (sequence, KV head) slice and b in {2, 4, 8} the normalized squared error
  *     eps(b) = sum (x - x_hat_b)^2 / sum x^2
  * over all tokens of the slice (every token retained; 0 for a slice that is all zero).  eps(0) = 1 (removal) and
  * eps(16) = 0 (bits kept verbatim) hold by definition and are not returned.  The paper averages the slice values over

@@ -35,7 +35,7 @@ ROW_PAD_TOKENWISE = 64              # tier segments are padded to whole 64-row t
 K_TOKEN_GROUP = 32                  # mixed mode: a K channel's group = 32 consecutive retained tokens of a segment
 SEG_ALIGN = 256                     # byte alignment of every segment in the arena
 
-# Table 9 (App. I), LLaMA-3.1-8B row; eps(0) = 1 and eps(16) = 0 for every model.
+# Table 9 (App. "Calibrated Distortion Tables"), LLaMA-3.1-8B row; eps(0) = 1 and eps(16) = 0 for every model.
 EPS_V_LLAMA31_8B = (1.0, 0.313, 0.0140, 4.9e-5, 0.0)
 EPS_K_LLAMA31_8B = (1.0, 0.149, 0.0062, 2.2e-5, 0.0)
 # Bennett-style table: per-coordinate RMSE proportional to 2^-b (Eq. 5).
@@ -1058,7 +1058,8 @@ def decode(cache, q):
     """One decode step over a packed cache (token-wise or mixed).  q: [batch, Hq, d]
     (bf16 exact).  Every retained token enters with its dequantised K row and V row;
     evicted tokens (tier 0) are absent and evicted K channels are zero; appended tokens
-    (append_tokens) enter with their bf16 rows (Eq. 7).
+    (append_tokens) enter with their bf16 rows (Eq. 7), appended tokens that were
+    compressed later (rebudget_tail) with their dequantised rows.
     Returns out float64 [batch, Hq, d], lse float64 [batch, Hq]."""
     q = np.asarray(q, dtype=np.float64)
     batch, Hq, d = q.shape
@@ -1070,6 +1071,9 @@ def decode(cache, q):
         for h in range(hkv):
             item = s * hkv + h
             Kh, Vh = unpack_item_mixed(cache, item) if cache.get("mixed") else unpack_item(cache, item)
+            for child in cache.get("absorbed", []):
+                Kc, Vc = unpack_item(child, item)
+                Kh, Vh = np.concatenate([Kh, Kc]), np.concatenate([Vh, Vc])
             if "tail" in cache:
                 Kh, Vh = np.concatenate([Kh, cache["tail"][item][0]]), np.concatenate([Vh, cache["tail"][item][1]])
             o, l = attention_rows(q[s, h * g:(h + 1) * g], Kh, Vh)
@@ -1097,7 +1101,37 @@ def decode_dense(K_list, V_list, q):
 
 
 # --------------------------------------------------------------------------
-# Distortion-table calibration (App. B "Calibration"; App. I, Table 9)
+# Streaming re-budgeting (App. "Limitations and Future Work": the extension to the decode phase)
+# --------------------------------------------------------------------------
+def rebudget_tail(cache, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B, pool_kernel=5, causal=True,
+                  rel_tol=np.float32(1e-2), max_iters=64, weights_override=None):
+    """The paper sketches the extension in one sentence: attention weights are gathered over a
+    buffer of recent decode tokens and the same knapsack allocation is applied to compress
+    them.  Reading taken here: the buffer is the whole appended-token zone; its n tokens are
+    treated as a sequence of their own and go through Alg. 1 unchanged (token-wise mode) --
+    the probe queries are the decode queries of the last S_w appended tokens, window row i at
+    tail position n - S_w + i, softmax over the tail's keys only -- with a budget of their own.
+    The compressed rows join the cache as one more generation (cache['absorbed']); the tail is
+    empty afterwards and can take new tokens.
+    Qobs_list[s]: [Hq, S_w, d]; budgets[s]: average bits per element of the tail of sequence s.
+    Returns the child cache (also appended to cache['absorbed'])."""
+    assert not cache.get("mixed"), "token-wise caches only"
+    hkv, d = cache["hkv"], cache["d"]
+    batch = len(cache["seq_lens"])
+    tail = cache["tail"]
+    n = tail[0][0].shape[0]
+    assert n > 0 and all(t[0].shape[0] == n for t in tail)
+    K_list = [np.stack([tail[s * hkv + h][0] for h in range(hkv)]).astype(np.float32) for s in range(batch)]
+    V_list = [np.stack([tail[s * hkv + h][1] for h in range(hkv)]).astype(np.float32) for s in range(batch)]
+    child = compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers, eps, pool_kernel, causal, rel_tol,
+                               max_iters, weights_override)
+    cache.setdefault("absorbed", []).append(child)
+    cache["tail"] = [(np.zeros((0, d)), np.zeros((0, d))) for _ in range(batch * hkv)]
+    return child
+
+
+# --------------------------------------------------------------------------
+# Distortion-table calibration (App. B "Calibration"; App. "Calibrated Distortion Tables", Table 9)
 # --------------------------------------------------------------------------
 CALIB_BITS = (2, 4, 8)
 
@@ -1115,7 +1149,7 @@ def _nmse(x, x_hat):
 
 def calibrate_eps(K_list, V_list, k_channelwise=False, k_per_channel_scale=False):
     """eps(b) of this build's quantizer on supplied K and V, b in (2, 4, 8): the normalized
-    distortion the knapsack of Eq. 6 consumes (App. I: per-token NMSE for V, per-channel NMSE
+    distortion the knapsack of Eq. 6 consumes (App. "Calibrated Distortion Tables": per-token NMSE for V, per-channel NMSE
     for K; eps(0) = 1 and eps(16) = 0 hold by definition and are not computed).  The paper
     estimates the table once per (layer, head) slice and averages; the slice values are
     returned here and averaging is left to the caller.

@@ -1,10 +1,12 @@
-// Distortion-table calibration (App. B "Calibration"; App. I, Table 9): the normalized squared error of the library's
-// own quantizer at 2, 4 and 8 bits on supplied K and V, per (sequence, KV head) slice.  Every token is retained.
+// Distortion-table calibration (App. B "Calibration"; App. "Calibrated Distortion Tables", Table 9): the normalized
+// squared error of the library's own quantizer at 2, 4 and 8 bits on supplied K and V, per (sequence, KV head)
+// slice.  Every token is retained.
 //   rows     : groups of 32 channels of a token row (V always; K when it shares the token map)
 //   channels : groups of 32 consecutive tokens of a channel starting at token 0, or the whole channel (App. B)
 // The codes are those of the pack kernels (same fp32 operations in the same order); the error of an element,
 // x - (s code + m), and all sums are taken in fp64, so the result differs from an fp64 reference only by the order
-// of the additions.  Both kernels read every byte once (the whole-channel format reads K twice) and are HBM-bound.
+// of the additions.  Every byte is read once (the whole-channel format reads K twice); three IEEE divisions and three
+// fp64 error terms per element make the kernels bound by the plain ALUs, not by HBM.
 #include "rdkv_internal.h"
 
 namespace rdkv {
@@ -52,7 +54,8 @@ __device__ __forceinline__ double group_error(const float (&x)[N], const bool (&
     float t = rintf((x[i] - m) / s);
     t = fminf(fmaxf(t, 0.0f), Q);
     if (s == 0.0f) t = 0.0f;
-    const double e = static_cast<double>(x[i]) - (static_cast<double>(s) * static_cast<double>(t) + static_cast<double>(m));
+    const double xh = static_cast<double>(s) * static_cast<double>(t) + static_cast<double>(m);
+    const double e = static_cast<double>(x[i]) - xh;
     if (ok[i]) err += e * e;
   }
   return err;

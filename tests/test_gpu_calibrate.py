@@ -1,4 +1,4 @@
-"""GPU parity of the distortion-table calibration (App. B "Calibration", App. I): the library's per-slice eps(b),
+"""GPU parity of the distortion-table calibration (App. B "Calibration", App. "Calibrated Distortion Tables"): the library's per-slice eps(b),
 b = 2, 4, 8, against the fp64 oracle on the same K and V.  Both sides take every rounding decision (codes, fp16 scale
 and offset) in the same fp32 operations, and errors are summed in fp64 on both, so the only difference is the order of
 the additions: relative tolerance 1e-10."""

@@ -1064,7 +1064,7 @@ def test_mixed_cache_with_per_channel_scale_bytes_and_decode():
         O.stored_bytes_mixed(full["counts"], full["bits_ch"])
 
 
-# ---- distortion-table calibration (App. B "Calibration", App. I) --------------------------------------------------
+# ---- distortion-table calibration (App. B "Calibration", App. "Calibrated Distortion Tables") --------------------------------------------------
 def _grid_group(bits, rng):
     """32 values m + s (code + delta), s a power of two, delta = +-1/4 except on the two end points: the quantizer
     must find exactly these codes, and every inner element is off by exactly s/4.  All values are bf16-exact."""
@@ -1153,3 +1153,75 @@ def test_calibration_degenerate_slices():
     for kw in ({}, {"k_channelwise": True}, {"k_channelwise": True, "k_per_channel_scale": True}):
         ek, ev = O.calibrate_eps([Z, C], [Z, C], **kw)
         assert not ek.any() and not ev.any()
+
+
+# ----------------------------------------------------------------------------
+# streaming re-budgeting: the appended tokens go through the same pass (App. "Limitations and Future Work")
+# ----------------------------------------------------------------------------
+def _cache_with_tail(rng, Hkv, g, T, n_new):
+    Ks, Vs = _small_case(rng, Hkv=Hkv, T=T)
+    bits = rng.choice([0, 2, 4, 8, 16], (Hkv, T)).astype(np.uint8)
+    cache = O.build_cache_tokenwise(Ks, Vs, [bits])
+    kn = rand_bf16(rng, (n_new, 1, Hkv, 128))
+    vn = rand_bf16(rng, (n_new, 1, Hkv, 128))
+    for i in range(n_new):
+        O.append_tokens(cache, kn[i], vn[i])
+    return cache, kn, vn
+
+
+def test_rebudget_at_16_bits_changes_nothing_and_at_0_bits_forgets_the_tail():
+    rng = np.random.default_rng(81)
+    Hkv, g, T, n_new, S_w = 2, 2, 120, 70, 8
+    q = rand_bf16(rng, (1, Hkv * g, 128))
+    Qobs = [rand_bf16(rng, (Hkv * g, S_w, 128))]
+    cache, kn, vn = _cache_with_tail(rng, Hkv, g, T, n_new)
+    before, lse_before = O.decode(cache, q)
+    child = O.rebudget_tail(cache, Qobs, [np.float32(16.0)])
+    assert (np.concatenate([b.ravel() for b in child["bits"]]) == 16).all()      # every row kept verbatim
+    assert all(t[0].shape[0] == 0 for t in cache["tail"])                       # the tail is empty again
+    after, lse_after = O.decode(cache, q)
+    np.testing.assert_allclose(after, before, rtol=1e-12, atol=1e-13)            # same rows, other order
+    np.testing.assert_allclose(lse_after, lse_before, rtol=0, atol=1e-12)
+
+    cache2, _, _ = _cache_with_tail(np.random.default_rng(83), Hkv, g, T, n_new)
+    # a zero budget evicts the whole tail: what is left is the prefix alone
+    prefix_only = {k: v for k, v in cache2.items() if k != "tail"}
+    want, lse_want = O.decode(prefix_only, q)
+    O.rebudget_tail(cache2, Qobs, [np.float32(0.0)])
+    got, lse_got = O.decode(cache2, q)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse_got, lse_want, rtol=0, atol=1e-12)
+
+
+def test_rebudget_is_the_compression_pass_on_the_tail_and_decode_merges_the_generations():
+    rng = np.random.default_rng(82)
+    Hkv, g, T, n_new, S_w = 2, 2, 150, 96, 16
+    q = rand_bf16(rng, (1, Hkv * g, 128))
+    Qobs = [rand_bf16(rng, (Hkv * g, S_w, 128))]
+    cache, kn, vn = _cache_with_tail(rng, Hkv, g, T, n_new)
+    prefix_only = {k: v for k, v in cache.items() if k != "tail"}
+    out_p, lse_p = O.decode(prefix_only, q)
+    child = O.rebudget_tail(cache, Qobs, [np.float32(3.0)])
+    # the child is what the one-shot pass makes of the appended rows taken as a sequence of their own
+    K_tail = np.ascontiguousarray(kn[:, 0].transpose(1, 0, 2))
+    V_tail = np.ascontiguousarray(vn[:, 0].transpose(1, 0, 2))
+    alone = O.compress_tokenwise([K_tail], [V_tail], Qobs, [np.float32(3.0)])
+    assert np.array_equal(child["arena"], alone["arena"]) and np.array_equal(child["tier_idx"], alone["tier_idx"])
+    for h in range(Hkv):
+        assert int(child["bits"][0][h].astype(np.int64).sum()) <= math.floor(3.0 * n_new)      # its own budget (Eq. 6)
+        assert 0 < int((child["bits"][0][h] > 0).sum()) <= n_new
+    # three more tokens arrive; the output is the log-sum-exp merge of prefix, absorbed generation and new tail
+    k3, v3 = rand_bf16(rng, (3, 1, Hkv, 128)), rand_bf16(rng, (3, 1, Hkv, 128))
+    for i in range(3):
+        O.append_tokens(cache, k3[i], v3[i])
+    out, lse = O.decode(cache, q)
+    out_c, lse_c = O.decode(alone, q)
+    for j in range(Hkv * g):
+        h = j // g
+        o_t, l_t = _bruteforce_attention(q[0, j], k3[:, 0, h], v3[:, 0, h])
+        ls = np.array([lse_p[0, j], lse_c[0, j], l_t])
+        m = ls.max()
+        w = np.exp(ls - m)
+        want = (w[0] * out_p[0, j] + w[1] * out_c[0, j] + w[2] * np.asarray(o_t)) / w.sum()
+        np.testing.assert_allclose(out[0, j], want, rtol=1e-11, atol=1e-12)
+        assert abs(lse[0, j] - (m + np.log(w.sum()))) < 1e-11

@@ -306,6 +306,36 @@ def main():
         gen = {"appended_tokens_per_layer": n_gen, "ms_per_step_eager_append_and_decode": ms_gen,
                "ms_per_step_decode_with_tail_graph": ms_tail,
                "note": "eager: 2 library calls per layer from Python; the tail's chunks ride in the decode kernel's launch"}
+        # streaming re-budgeting: fill the tail to 256 tokens, compress it at 2 bits per element, decode again
+        n_fill = 256 - n_gen
+        kf = torch.randn((n_fill, 1, hkv, d), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        for i in range(n_fill):
+            for l in range(L):
+                b.rdkv_cache_append(caches[l], kf[i], kf[(i + 1) % n_fill])
+        g3 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g3):
+            step_eager()
+        g3.replay()
+        ms_full_tail = timed_ms(g3.replay, args.steps, torch)
+        cfg_t = b.Config([256], hq, hkv, budget_bits=[2.0], s_obs=wl.s_obs)
+        q_recent = torch.randn((1, hq, wl.s_obs, d), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for l in range(L):
+            b.rdkv_cache_rebudget_tail(caches[l], cfg_t, q_recent)
+        torch.cuda.synchronize()
+        ms_rebudget = (time.time() - t0) * 1e3
+        g4 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g4):
+            step_eager()
+        g4.replay()
+        ms_after = timed_ms(g4.replay, args.steps, torch)
+        st_after = [c.stats() for c in caches]
+        gen["rebudget"] = {"tail_tokens": 256, "budget_bits": 2.0, "wall_ms_all_layers": ms_rebudget,
+                           "ms_per_step_decode_tail_256_bf16": ms_full_tail,
+                           "ms_per_step_decode_after_rebudget": ms_after,
+                           "tail_bytes_bf16": L * hkv * 256 * 512,
+                           "tail_bytes_after": sum(s_["stored_bytes"] for s_ in st_after) - stored}
     except Exception as e:  # reported, never hidden
         gen = {"error": repr(e)}
 

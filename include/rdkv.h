@@ -232,6 +232,27 @@ rdkv_status rdkv_cache_append(rdkv_cache* cache, const void* k_new, const void* 
 int32_t rdkv_cache_tail_len(const rdkv_cache* cache);
 
 /*
+ * Streaming re-budgeting (the extension sketched in App. "Limitations and Future Work"): the appended tokens are
+ * compressed by the same pass (Alg. 1) as a sequence of their own and join the compressed zones as one more
+ * generation; the tail is empty afterwards and keeps its capacity.  Token-wise caches only (RDKV_ERR_UNSUPPORTED
+ * otherwise).
+ *   cfg     the pass's parameters for the tail: batch, hq, hkv, head_dim as the cache; seq_lens[s] =
+ *           rdkv_cache_tail_len(cache) for every s; budget_bits[s] = average bits per element of the tail of
+ *           sequence s; s_obs <= tail length; tiers, distortion tables, tolerance as for rdkv_compress
+ *   Q_obs   DEVICE bf16 [batch][hq][s_obs][d]: the decode queries of the last s_obs appended tokens (window row i
+ *           sits at tail position n - s_obs + i; the probe's softmax runs over the tail's keys only)
+ * Synchronises `stream`.  Replaces the decode schedule: HIP graphs that captured rdkv_decode_attn on this cache must
+ * be captured again.  On error the cache is unchanged.
+ *   rdkv_cache_generations   number of absorbed generations (0 for a null cache)
+ *   rdkv_cache_generation    borrowed handle of generation `index` for rdkv_cache_stats / rdkv_cache_export (owned by
+ *                            the cache; never free it); NULL if out of range
+ * rdkv_cache_stats of the cache sums over its generations; rdkv_cache_export describes the prompt's zones only.
+ */
+rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* cache, const rdkv_config* cfg, const void* Q_obs, void* stream);
+int32_t rdkv_cache_generations(const rdkv_cache* cache);
+const rdkv_cache* rdkv_cache_generation(const rdkv_cache* cache, int32_t index);
+
+/*
  * Calibration of the distortion table (App. B "Calibration"; App. "Calibrated Distortion Tables", Table 9) on the
  * library's own quantizer: for every (sequence, KV head) slice and b in {2, 4, 8} the normalized squared error
  *     eps(b) = sum (x - x_hat_b)^2 / sum x^2

@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = [
     "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_pack",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
     "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_calibrate_eps",
+    "rdkv_cache_rebudget_tail", "rdkv_cache_generations", "rdkv_cache_generation",
     "rdkv_cache_stats", "rdkv_cache_export_bytes", "rdkv_cache_export", "rdkv_cache_free",
     "rdkv_kernel_timing_enable", "rdkv_kernel_timing_read",
 ]
@@ -86,6 +87,11 @@ def _load():
     lib.rdkv_cache_tail_len.argtypes = [vp]
     lib.rdkv_cache_tail_len.restype = i32
     lib.rdkv_calibrate_eps.argtypes = [cfgp, vp, vp, vp, vp, vp]
+    lib.rdkv_cache_rebudget_tail.argtypes = [vp, cfgp, vp, vp]
+    lib.rdkv_cache_generations.argtypes = [vp]
+    lib.rdkv_cache_generations.restype = i32
+    lib.rdkv_cache_generation.argtypes = [vp, i32]
+    lib.rdkv_cache_generation.restype = vp
     lib.rdkv_cache_stats.argtypes = [vp, ctypes.POINTER(rdkv_stats)]
     lib.rdkv_cache_export_bytes.argtypes = [vp, i32]
     lib.rdkv_cache_export_bytes.restype = sz
@@ -233,6 +239,32 @@ def rdkv_cache_append(cache, k_new, v_new):
 
 def rdkv_cache_tail_len(cache):
     return int(lib.rdkv_cache_tail_len(cache.h))
+
+
+class _Borrowed(Cache):
+    """A generation of another cache: never freed from here."""
+
+    def __init__(self, handle, cfg, owner):
+        super().__init__(handle, cfg)
+        self._owner = owner
+
+    def free(self):
+        self.h = None
+
+
+def rdkv_cache_rebudget_tail(cache, cfg, Q_obs):
+    _check(lib.rdkv_cache_rebudget_tail(cache.h, cfg.ref(), _ptr(Q_obs), _stream()))
+
+
+def rdkv_cache_generations(cache):
+    return int(lib.rdkv_cache_generations(cache.h))
+
+
+def rdkv_cache_generation(cache, index, cfg):
+    h = lib.rdkv_cache_generation(cache.h, int(index))
+    if not h:
+        raise IndexError(f"generation {index} does not exist")
+    return _Borrowed(ctypes.c_void_p(h), cfg, cache)
 
 
 def rdkv_calibrate_eps(cfg, K, V):

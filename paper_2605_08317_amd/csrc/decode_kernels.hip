@@ -370,6 +370,45 @@ hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint
   return hipGetLastError();
 }
 
+// Inverse of append_rows_kernel: the first n tokens of every item's tail, as row-major bf16 [items][n][128] K and V
+// (the input format of the compression pass).  One workgroup = one 64-token tile of one item.
+__global__ __launch_bounds__(256) void gather_tail_rows_kernel(const uint8_t* __restrict__ tail, int64_t n_items,
+                                                               int32_t tail_tiles, int32_t n,
+                                                               uint16_t* __restrict__ k_rows, uint16_t* __restrict__ v_rows) {
+  const int64_t item = blockIdx.y;
+  const int tile = blockIdx.x, t = threadIdx.x;
+  constexpr int kTileBytes = 64 * kHeadDim * 2;
+  const uint8_t* kt = tail + (item * tail_tiles + tile) * static_cast<int64_t>(kTileBytes);
+  const uint8_t* vt = tail + ((n_items + item) * tail_tiles + tile) * static_cast<int64_t>(kTileBytes);
+  const int64_t row_base = item * n + static_cast<int64_t>(tile) * 64;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {   // K: 16-byte unit (w, r) at 1024 w + 16 r holds channels 8w .. 8w+7 of token r
+    const int idx = j * 256 + t, w = idx >> 6, r = idx & 63;
+    if (tile * 64 + r < n)
+      *reinterpret_cast<uint4*>(k_rows + (row_base + r) * kHeadDim + 8 * w) =
+          *reinterpret_cast<const uint4*>(kt + 1024 * w + 16 * r);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {   // V: unit (u, lane) holds channel 32 (u / 4) + lane % 32 of 8 consecutive tokens
+    const int idx = j * 256 + t, u = idx >> 6, lane = idx & 63;
+    const uint4 v = *reinterpret_cast<const uint4*>(vt + 1024 * u + 16 * lane);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const int c = 32 * (u >> 2) + (lane & 31), r0 = 32 * (lane >> 5) + 8 * (u & 3);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (tile * 64 + r0 + k < n)
+        v_rows[(row_base + r0 + k) * kHeadDim + c] = static_cast<uint16_t>(w[k >> 1] >> (16 * (k & 1)));
+  }
+}
+
+hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t tail_tiles, int32_t n,
+                                   uint16_t* k_rows, uint16_t* v_rows, hipStream_t st) {
+  if (n_items == 0 || n == 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_tail_rows_kernel, dim3((n + 63) / 64, static_cast<unsigned>(n_items)), dim3(256), 0, st,
+                     tail, n_items, tail_tiles, n, k_rows, v_rows);
+  return hipGetLastError();
+}
+
 hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
                                       const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
                                       float* lse, hipStream_t st) {

@@ -221,6 +221,11 @@ void free_cache_buffers(rdkv_cache* c) {
   al.put(c->d_bits_ch);
   al.put(c->d_items_k);
   al.put(c->d_tail);
+  for (rdkv_cache* child : c->absorbed) {
+    free_cache_buffers(child);
+    delete child;
+  }
+  c->absorbed.clear();
 }
 
 // Sorted-channel layout of one item's K tiles from its channel bit map.
@@ -685,6 +690,9 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   });
   c->n_chunks16 = 0;
   for (const Chunk& ch : c->chunks) c->n_chunks16 += ch.tier == 16;
+  c->sched16 = c->n_chunks16;
+  c->schedq = static_cast<int64_t>(c->chunks.size()) - c->n_chunks16;
+  c->own_slot_count.assign(slot_count.begin(), slot_count.begin() + n);
 
   // ---- allocate what the cache owns ------------------------------------------------------
   c->d_arena = static_cast<uint8_t*>(al.get(c->arena_bytes));
@@ -781,7 +789,7 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
   if (c->k_mode == RDKV_K_CHANNELWISE) {
     {
       TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
-      RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->chunks.size()) + live_tail_chunks(c), c->d_arena,
+      RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->sched16 + c->schedq) + live_tail_chunks(c), c->d_arena,
                                    c->d_items_k, c->max_k_words, c->max_k_steps, c->max_k_qsteps,
                                    static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
                                    c->hq, c->hkv, c->tail_len, c->k_per_unit, st));
@@ -792,7 +800,7 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
   }
   {
     TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
-    const int n16 = static_cast<int>(c->n_chunks16), nq = static_cast<int>(c->chunks.size()) - n16;
+    const int n16 = static_cast<int>(c->sched16), nq = static_cast<int>(c->schedq);
     RDKV_HIP(launch_decode_tiered_split(c->d_chunks, n16, c->d_arena, static_cast<const uint16_t*>(q),
                                         c->d_part_acc, c->d_part_ml, c->hq, c->hkv, st));
     RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nq + live_tail_chunks(c), c->d_arena,
@@ -804,65 +812,93 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
   return RDKV_OK;
 }
 
-rdkv_status rdkv_cache_reserve_tail(rdkv_cache* c, int32_t max_new_tokens, void* stream) {
-  if (!c) return fail(RDKV_ERR_INVALID_ARG, "cache is null");
-  if (max_new_tokens <= 0) return fail(RDKV_ERR_INVALID_ARG, "max_new_tokens = %d must be positive", max_new_tokens);
-  if (c->tail_cap != 0) return fail(RDKV_ERR_INVALID_ARG, "the tail of this cache is already reserved (%d tokens)", c->tail_cap);
-  if (c->n_items == 0) { c->tail_cap = max_new_tokens; return RDKV_OK; }
-  hipStream_t st = static_cast<hipStream_t>(stream);
+// Rebuilds the decode schedule of a cache: the chunks of the cache itself and of every absorbed generation (all
+// 16-bit chunks first, then the quantized ones), then the tail's chunks in (chunk index, item) order so that the
+// live ones are a prefix.  Every item keeps its partial slots contiguous: own chunks, generation by generation,
+// then the tail.  The decode kernels address everything relative to d_arena, so the offsets of the other
+// allocations are pointer differences.  Synchronises the stream; on failure the cache is unchanged.
+static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
   Allocator al{c->alloc, c->free_, c->alloc_user};
   const int64_t n = c->n_items;
   const int g = c->hq / c->hkv;
-  const int npi = (max_new_tokens + kTailChunkRows - 1) / kTailChunkRows;     // tail chunks per item
-  const int64_t n_old = static_cast<int64_t>(c->chunks.size()), n_slots = n_old + n * npi;
-  const int64_t tail_tiles = (max_new_tokens + kTile64 - 1) / kTile64, tile_bytes = kTile64 * kHeadDim * 2;
-  const int64_t side = n * tail_tiles * tile_bytes;     // K tiles of all items, then V tiles
-  // partial slots: every item keeps its slots contiguous, the tail's after the compressed tiers'
+  const int npi = (c->tail_cap + kTailChunkRows - 1) / kTailChunkRows;     // tail chunks per item
+  std::vector<const rdkv_cache*> gens{c};
+  gens.insert(gens.end(), c->absorbed.begin(), c->absorbed.end());
   std::vector<int32_t> nb(n), nc(n);
+  std::vector<std::vector<int32_t>> gen_off(gens.size(), std::vector<int32_t>(n));
+  int64_t n_slots = 0, n_gen_chunks = 0;
   for (int64_t i = 0; i < n; ++i) {
-    nb[i] = c->slot_begin[i] + static_cast<int32_t>(i) * npi;
-    nc[i] = c->slot_count[i] + npi;
+    nb[i] = static_cast<int32_t>(n_slots);
+    int32_t off = 0;
+    for (size_t k = 0; k < gens.size(); ++k) {
+      gen_off[k][i] = off;
+      off += gens[k]->own_slot_count[i];
+    }
+    nc[i] = off + npi;
+    n_slots += nc[i];
   }
-  std::vector<Chunk> chunks = c->chunks;
-  for (Chunk& ch : chunks) ch.slot += ch.item * npi;
-  uint8_t* d_tail = static_cast<uint8_t*>(al.get(2 * side));
-  Chunk* d_chunks = static_cast<Chunk*>(al.get((n_old + n * npi) * sizeof(Chunk)));
-  float* d_acc = static_cast<float*>(al.get(n_slots * g * kHeadDim * sizeof(float)));
-  float* d_ml = static_cast<float*>(al.get(n_slots * g * 2 * sizeof(float)));
-  if (!d_tail || !d_chunks || !d_acc || !d_ml) {
-    al.put(d_tail); al.put(d_chunks); al.put(d_acc); al.put(d_ml);
-    return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  }
-  // the tail's chunks follow the others in the table, ordered (chunk index, item): the live ones are a prefix.
-  // The decode kernels address everything relative to the arena, so the tail's offsets are pointer differences.
-  const int64_t base = reinterpret_cast<intptr_t>(d_tail) - reinterpret_cast<intptr_t>(c->d_arena);
-  std::vector<Chunk> table = chunks;
-  table.resize(static_cast<size_t>(n_old + n * npi));
+  for (const rdkv_cache* gcache : gens) n_gen_chunks += static_cast<int64_t>(gcache->chunks.size());
+  std::vector<Chunk> table;
+  table.reserve(static_cast<size_t>(n_gen_chunks + n * npi));
+  std::vector<Chunk> own = c->chunks;   // this cache's chunks with their new slot numbers
+  int64_t n16 = 0;
+  for (int pass = 0; pass < 2; ++pass)
+    for (size_t k = 0; k < gens.size(); ++k) {
+      const rdkv_cache* gc = gens[k];
+      const int64_t base = reinterpret_cast<intptr_t>(gc->d_arena) - reinterpret_cast<intptr_t>(c->d_arena);
+      for (size_t j = 0; j < gc->chunks.size(); ++j) {
+        Chunk ch = gc->chunks[j];
+        if ((ch.tier == 16) != (pass == 0)) continue;
+        ch.slot = nb[ch.item] + gen_off[k][ch.item] + (ch.slot - gc->slot_begin[ch.item]);
+        if (k == 0) own[j].slot = ch.slot;
+        ch.k_data += base;
+        ch.k_meta += base;
+        ch.v_data += base;
+        ch.v_meta += base;
+        table.push_back(ch);
+        n16 += pass == 0;
+      }
+    }
+  const int64_t tail_tiles = (c->tail_cap + kTile64 - 1) / kTile64, tile_bytes = kTile64 * kHeadDim * 2;
+  const int64_t side = n * tail_tiles * tile_bytes;     // K tiles of all items, then V tiles
+  const int64_t tail_base = reinterpret_cast<intptr_t>(c->d_tail) - reinterpret_cast<intptr_t>(c->d_arena);
   for (int j = 0; j < npi; ++j)
     for (int64_t i = 0; i < n; ++i) {
-      Chunk& ch = table[static_cast<size_t>(n_old + static_cast<int64_t>(j) * n + i)];
+      Chunk ch;
       std::memset(&ch, 0, sizeof(ch));
-      ch.k_data = base + (i * tail_tiles + static_cast<int64_t>(j) * (kTailChunkRows / kTile64)) * tile_bytes;
+      ch.k_data = tail_base + (i * tail_tiles + static_cast<int64_t>(j) * (kTailChunkRows / kTile64)) * tile_bytes;
       ch.v_data = ch.k_data + side;
-      ch.rows = std::min<int32_t>(kTailChunkRows, max_new_tokens - j * kTailChunkRows);
+      ch.rows = std::min<int32_t>(kTailChunkRows, c->tail_cap - j * kTailChunkRows);
       ch.tier = kTierTail;
       ch.item = static_cast<int32_t>(i);
-      ch.slot = nb[i] + c->slot_count[i] + j;
+      ch.slot = nb[i] + nc[i] - npi + j;
       ch.row0 = j * kTailChunkRows;
+      table.push_back(ch);
     }
+  const int64_t n_table = static_cast<int64_t>(table.size());
+  Chunk* d_chunks = static_cast<Chunk*>(al.get(std::max<int64_t>(n_table, 1) * sizeof(Chunk)));
+  float* d_acc = static_cast<float*>(al.get(std::max<int64_t>(n_slots, 1) * g * kHeadDim * sizeof(float)));
+  float* d_ml = static_cast<float*>(al.get(std::max<int64_t>(n_slots, 1) * g * 2 * sizeof(float)));
+  if (!d_chunks || !d_acc || !d_ml) {
+    al.put(d_chunks); al.put(d_acc); al.put(d_ml);
+    return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  }
   // slots of tail chunks that no launch has reached yet must read as empty partials: m = -1e30, l = 0, acc = 0
   std::vector<float> ml(static_cast<size_t>(n_slots) * g * 2, 0.f);
   for (size_t k = 0; k < ml.size(); k += 2) ml[k] = -1.0e30f;
-  hipError_t e = hipMemsetAsync(d_acc, 0, n_slots * g * kHeadDim * sizeof(float), st);
-  if (e == hipSuccess) e = hipMemsetAsync(d_tail, 0, 2 * side, st);   // rows not yet appended must read as zeros
-  if (e == hipSuccess) e = hipMemcpyAsync(d_ml, ml.data(), ml.size() * sizeof(float), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipMemcpyAsync(d_chunks, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice, st);
+  hipError_t e = hipSuccess;
+  if (n_slots > 0) {
+    e = hipMemsetAsync(d_acc, 0, n_slots * g * kHeadDim * sizeof(float), st);
+    if (e == hipSuccess) e = hipMemcpyAsync(d_ml, ml.data(), ml.size() * sizeof(float), hipMemcpyHostToDevice, st);
+  }
+  if (e == hipSuccess && n_table > 0)
+    e = hipMemcpyAsync(d_chunks, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_begin, nb.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_count, nc.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);     // the host vectors above go out of scope
   if (e != hipSuccess) {
-    al.put(d_tail); al.put(d_chunks); al.put(d_acc); al.put(d_ml);
-    return fail(RDKV_ERR_HIP, "rdkv_cache_reserve_tail: %s", hipGetErrorString(e));
+    al.put(d_chunks); al.put(d_acc); al.put(d_ml);
+    return fail(RDKV_ERR_HIP, "rebuilding the decode schedule: %s", hipGetErrorString(e));
   }
   al.put(c->d_part_acc);
   al.put(c->d_part_ml);
@@ -870,14 +906,41 @@ rdkv_status rdkv_cache_reserve_tail(rdkv_cache* c, int32_t max_new_tokens, void*
   c->d_part_acc = d_acc;
   c->d_part_ml = d_ml;
   c->d_chunks = d_chunks;
-  c->d_tail = d_tail;
+  c->sched16 = n16;
+  c->schedq = n_gen_chunks - n16;
   c->n_tail_chunks = n * npi;
-  c->chunks.swap(chunks);
+  c->chunks.swap(own);
   c->slot_begin.swap(nb);
   c->slot_count.swap(nc);
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_cache_reserve_tail(rdkv_cache* c, int32_t max_new_tokens, void* stream) {
+  if (!c) return fail(RDKV_ERR_INVALID_ARG, "cache is null");
+  if (max_new_tokens <= 0) return fail(RDKV_ERR_INVALID_ARG, "max_new_tokens = %d must be positive", max_new_tokens);
+  if (c->tail_cap != 0) return fail(RDKV_ERR_INVALID_ARG, "the tail of this cache is already reserved (%d tokens)", c->tail_cap);
+  if (c->n_items == 0) { c->tail_cap = max_new_tokens; return RDKV_OK; }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{c->alloc, c->free_, c->alloc_user};
+  const int64_t tail_tiles = (max_new_tokens + kTile64 - 1) / kTile64, tile_bytes = kTile64 * kHeadDim * 2;
+  const int64_t side = c->n_items * tail_tiles * tile_bytes;     // K tiles of all items, then V tiles
+  uint8_t* d_tail = static_cast<uint8_t*>(al.get(2 * side));
+  if (!d_tail) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  hipError_t e = hipMemsetAsync(d_tail, 0, 2 * side, st);   // rows not yet appended must read as zeros
+  if (e != hipSuccess) {
+    al.put(d_tail);
+    return fail(RDKV_ERR_HIP, "rdkv_cache_reserve_tail: %s", hipGetErrorString(e));
+  }
+  c->d_tail = d_tail;
   c->tail_cap = max_new_tokens;
   c->tail_len = 0;
-  return RDKV_OK;
+  const rdkv_status s = rebuild_schedule(c, st);
+  if (s != RDKV_OK) {
+    c->d_tail = nullptr;
+    c->tail_cap = 0;
+    al.put(d_tail);
+  }
+  return s;
 }
 
 rdkv_status rdkv_cache_append(rdkv_cache* c, const void* k_new, const void* v_new, void* stream) {
@@ -893,6 +956,53 @@ rdkv_status rdkv_cache_append(rdkv_cache* c, const void* k_new, const void* v_ne
 }
 
 int32_t rdkv_cache_tail_len(const rdkv_cache* c) { return c ? c->tail_len : 0; }
+
+rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, const void* Q_obs, void* stream) {
+  if (!c || !cfg || !Q_obs) return fail(RDKV_ERR_INVALID_ARG, "cache, cfg and Q_obs must not be null");
+  if (c->k_mode != RDKV_K_TOKENWISE || cfg->k_mode != RDKV_K_TOKENWISE)
+    return fail(RDKV_ERR_UNSUPPORTED, "re-budgeting of appended tokens is built for token-wise caches only");
+  if (c->tail_len <= 0) return fail(RDKV_ERR_INVALID_ARG, "no appended tokens to compress");
+  if (cfg->batch != c->batch || cfg->hq != c->hq || cfg->hkv != c->hkv || cfg->head_dim != c->d)
+    return fail(RDKV_ERR_SHAPE, "cfg (batch %d, hq %d, hkv %d, d %d) does not match the cache (%d, %d, %d, %d)",
+                cfg->batch, cfg->hq, cfg->hkv, cfg->head_dim, c->batch, c->hq, c->hkv, c->d);
+  if (!cfg->seq_lens) return fail(RDKV_ERR_INVALID_ARG, "seq_lens is null");
+  for (int s = 0; s < cfg->batch; ++s)
+    if (cfg->seq_lens[s] != c->tail_len)
+      return fail(RDKV_ERR_SHAPE, "seq_lens[%d] = %d: every sequence has %d appended tokens", s, cfg->seq_lens[s], c->tail_len);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al);
+  const int32_t n_tail = c->tail_len;
+  const size_t elems = static_cast<size_t>(c->n_items) * n_tail * kHeadDim;
+  uint16_t* k_rows = tmp.get<uint16_t>(elems);
+  uint16_t* v_rows = tmp.get<uint16_t>(elems);
+  if (!k_rows || !v_rows) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  RDKV_HIP(launch_gather_tail_rows(c->d_tail, c->n_items, (c->tail_cap + kTile64 - 1) / kTile64, n_tail, k_rows, v_rows, st));
+  rdkv_cache* child = nullptr;
+  rdkv_status s = rdkv_compress(cfg, k_rows, v_rows, Q_obs, stream, &child);   // synchronises the stream
+  if (s != RDKV_OK) return s;
+  {  // rows not yet appended must read as zeros again
+    const int64_t tail_tiles = (c->tail_cap + kTile64 - 1) / kTile64;
+    RDKV_HIP(hipMemsetAsync(c->d_tail, 0, 2 * c->n_items * tail_tiles * kTile64 * kHeadDim * 2, st));
+  }
+  c->absorbed.push_back(child);
+  c->tail_len = 0;
+  s = rebuild_schedule(c, st);
+  if (s != RDKV_OK) {
+    c->absorbed.pop_back();
+    c->tail_len = n_tail;
+    rdkv_cache_free(child);
+    return s;
+  }
+  return RDKV_OK;
+}
+
+int32_t rdkv_cache_generations(const rdkv_cache* c) { return c ? static_cast<int32_t>(c->absorbed.size()) : 0; }
+
+const rdkv_cache* rdkv_cache_generation(const rdkv_cache* c, int32_t index) {
+  if (!c || index < 0 || index >= static_cast<int32_t>(c->absorbed.size())) return nullptr;
+  return c->absorbed[index];
+}
 
 size_t rdkv_decode_bf16_workspace_bytes(const int32_t* seq_lens, int32_t batch, int32_t hq, int32_t hkv,
                                         int32_t head_dim) {
@@ -963,6 +1073,17 @@ rdkv_status rdkv_cache_stats(const rdkv_cache* c, rdkv_stats* out) {
   out->index_bytes = c->index_bytes;
   out->n_chunks = static_cast<int64_t>(c->chunks.size());
   out->dense_bytes = c->total_tokens * kHeadDim * 2 * 2;
+  for (const rdkv_cache* child : c->absorbed) {   // appended tokens compressed later count like the prompt's
+    rdkv_stats cs;
+    rdkv_cache_stats(child, &cs);
+    for (int ti = 0; ti < 4; ++ti) out->rows[ti] += cs.rows[ti];
+    out->evicted += cs.evicted;
+    out->stored_bytes += cs.stored_bytes;
+    out->arena_bytes += cs.arena_bytes;
+    out->index_bytes += cs.index_bytes;
+    out->n_chunks += cs.n_chunks;
+    out->dense_bytes += cs.dense_bytes;
+  }
   return RDKV_OK;
 }
 

@@ -72,6 +72,8 @@ hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const u
                                       float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
 hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint8_t* tail, int64_t n_items,
                               int32_t tail_tiles, int32_t row, hipStream_t st);
+hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t tail_tiles, int32_t n,
+                                   uint16_t* k_rows, uint16_t* v_rows, hipStream_t st);
 hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
                                       const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
                                       float* lse, hipStream_t st);
@@ -131,6 +133,11 @@ struct rdkv_cache {
   int64_t n_tail_chunks = 0;            // chunks of the tail, appended to d_chunks in (chunk index, item) order:
                                         // the first ceil(tail_len / 256) * items of them are live
   int32_t tail_cap = 0, tail_len = 0;
+  // streaming re-budgeting: appended tokens that were compressed later, one packed cache per call (owned); their
+  // chunks are part of this cache's decode schedule (d_chunks), with offsets relative to d_arena
+  std::vector<rdkv_cache*> absorbed;
+  std::vector<int32_t> own_slot_count;  // [items]: partial slots of this cache's own chunks (no tail, no absorbed)
+  int64_t sched16 = 0, schedq = 0;      // chunks of the schedule: 16-bit tier, then the quantized tiers (all generations)
   int64_t stored_bytes = 0;             // bytes a decode step must read (unpadded)
   int64_t index_bytes = 0;
   rdkv_alloc_fn alloc = nullptr;

@@ -1,0 +1,136 @@
+"""GPU parity of streaming re-budgeting (the extension sketched in App. "Limitations and Future Work"): appended tokens
+are compressed by the same pass and join the cache as a further generation.  The absorbed generation must equal the
+oracle's bit for bit (bit map, kept positions, packed bytes) when both allocate from the library's own fp32 weights;
+decode over prompt zones, generations and the new tail within 2e-3 of the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rdkv_oracle as O
+from test_gpu_parity import B, _np, _check_decode, _inputs, _pack_both, _assert_cache_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def _append(b, cache, ref, rng, n_new, batch, hkv):
+    """n_new tokens per sequence into both caches; returns their rows as [batch][hkv][n_new][128] bf16 tensors."""
+    kn = torch.from_numpy(rng.standard_normal((n_new, batch, hkv, 128)).astype(np.float32)).to(torch.bfloat16)
+    vn = torch.from_numpy(rng.standard_normal((n_new, batch, hkv, 128)).astype(np.float32)).to(torch.bfloat16)
+    kn[:, :, :, 5] *= 8.0                                        # a heavy key channel
+    kd, vd = kn.cuda(), vn.cuda()
+    for i in range(n_new):
+        b.rdkv_cache_append(cache, kd[i], vd[i])
+        O.append_tokens(ref, kn[i].float().numpy(), vn[i].float().numpy())
+    return kn.permute(1, 2, 0, 3).contiguous(), vn.permute(1, 2, 0, 3).contiguous()
+
+
+def _rebudget_both(b, cache, ref, wl, batch, k_rows, n_tail, budgets, s_obs, rng, **cfg_kw):
+    """Runs the library's and the oracle's re-budgeting on the same tail; the oracle allocates from the weights the
+    library computes for the same rows.  Returns the oracle's child."""
+    Q_obs = torch.from_numpy(rng.standard_normal((batch, wl.hq, s_obs, 128)).astype(np.float32)).to(torch.bfloat16)
+    cfg = b.Config([n_tail] * batch, wl.hq, wl.hkv, budget_bits=budgets, s_obs=s_obs, **cfg_kw)
+    print(f"[step] rebudget tail of {n_tail} tokens, budgets {budgets}", flush=True)
+    b.rdkv_cache_rebudget_tail(cache, cfg, Q_obs.cuda())
+    assert b.rdkv_cache_tail_len(cache) == 0
+    w_tok, _ = b.rdkv_weights(cfg, k_rows.reshape(-1).cuda(), Q_obs.cuda())
+    torch.cuda.synchronize()
+    w_list = [w.cpu().numpy() for w in w_tok.view(batch, wl.hkv, n_tail)]
+    kw = {}
+    if "tiers" in cfg_kw:
+        kw = {"tiers": tuple(cfg_kw["tiers"]), "eps": tuple(cfg_kw["eps_v"])}
+    child = O.rebudget_tail(ref, [_np(Q_obs[s]) for s in range(batch)], [np.float32(x) for x in budgets],
+                            weights_override=w_list, **kw)
+    return child, cfg
+
+
+@pytest.mark.parametrize("name,kw,n_new,budgets", [
+    ("tiny", {"seq_lens": (900,)}, 200, [3.0]),
+    ("tiny", {"seq_lens": (500,)}, 64, [16.0]),                  # everything kept verbatim
+    ("batch70b", {"batch": 3, "len_range": (100, 700)}, 300, [0.5, 2.0, 6.0]),   # 8 query heads per KV head
+])
+def test_rebudget_matches_oracle(name, kw, n_new, budgets):
+    b = B()
+    wl, inp, dev = _inputs(name, **kw)
+    batch = len(inp["seq_lens"])
+    rng = np.random.default_rng(91)
+    bits = [rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(wl.hkv, T), p=[.4, .25, .2, .1, .05])
+            for T in inp["seq_lens"]]
+    cache, ref = _pack_both(b, wl, inp, dev, bits)
+    b.rdkv_cache_reserve_tail(cache, 320)
+    k_rows, _ = _append(b, cache, ref, rng, n_new, batch, wl.hkv)
+    st0 = cache.stats()
+    child, cfg = _rebudget_both(b, cache, ref, wl, batch, k_rows, n_new, budgets, 32, rng)
+    # the absorbed generation, bit for bit
+    assert b.rdkv_cache_generations(cache) == 1
+    gen = b.rdkv_cache_generation(cache, 0, cfg)
+    np.testing.assert_array_equal(gen.export(b.RDKV_EXPORT_BITS_TOK, np.uint8),
+                                  np.concatenate([x.reshape(-1) for x in child["bits"]]))
+    _assert_cache_equal(b, gen, child)
+    st1 = cache.stats()
+    assert st1["stored_bytes"] == st0["stored_bytes"] + O.stored_bytes(child["counts"])
+    assert st1["rows"] == [a + c for a, c in zip(st0["rows"], child["counts"].sum(axis=0).tolist())]
+    for s in range(batch):
+        for h in range(wl.hkv):
+            assert int(child["bits"][s][h].astype(np.int64).sum()) <= int(np.floor(np.float64(np.float32(budgets[s])) * n_new))
+    # decode right after, then with new tokens in the emptied tail
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
+    _append(b, cache, ref, rng, 7, batch, wl.hkv)
+    assert b.rdkv_cache_tail_len(cache) == 7
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
+    cache.free()
+
+
+def test_rebudget_twice_and_prompt_fully_evicted():
+    """Two generations on a cache whose first KV head kept nothing of the prompt."""
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(700,))
+    rng = np.random.default_rng(92)
+    bits = [rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(wl.hkv, T), p=[.4, .25, .2, .1, .05])
+            for T in inp["seq_lens"]]
+    bits[0][0, :] = 0
+    cache, ref = _pack_both(b, wl, inp, dev, bits)
+    b.rdkv_cache_reserve_tail(cache, 128)
+    for gen_i, (n_new, budget) in enumerate(((128, 4.0), (40, 1.0))):
+        k_rows, _ = _append(b, cache, ref, rng, n_new, 1, wl.hkv)
+        child, cfg = _rebudget_both(b, cache, ref, wl, 1, k_rows, n_new, [budget], 16, rng)
+        assert b.rdkv_cache_generations(cache) == gen_i + 1
+        _assert_cache_equal(b, b.rdkv_cache_generation(cache, gen_i, cfg), child)
+        out, lse = b.rdkv_decode_attn(cache, dev["q"])
+        torch.cuda.synchronize()
+        _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
+    _append(b, cache, ref, rng, 3, 1, wl.hkv)
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
+    cache.free()
+
+
+def test_rebudget_argument_errors():
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(300,))
+    rng = np.random.default_rng(93)
+    bits = [np.full((wl.hkv, 300), 4, np.uint8)]
+    cache, ref = _pack_both(b, wl, inp, dev, bits)
+    Q = torch.zeros((1, wl.hq, 8, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(RuntimeError):                                        # nothing appended (no tail at all)
+        b.rdkv_cache_rebudget_tail(cache, b.Config([8], wl.hq, wl.hkv, budget_bits=[2.0], s_obs=8), Q)
+    b.rdkv_cache_reserve_tail(cache, 64)
+    _append(b, cache, ref, rng, 10, 1, wl.hkv)
+    with pytest.raises(RuntimeError):                                        # wrong tail length
+        b.rdkv_cache_rebudget_tail(cache, b.Config([9], wl.hq, wl.hkv, budget_bits=[2.0], s_obs=8), Q)
+    with pytest.raises(RuntimeError):                                        # other head counts than the cache
+        b.rdkv_cache_rebudget_tail(cache, b.Config([10], wl.hq * 2, wl.hkv, budget_bits=[2.0], s_obs=8), Q)
+    with pytest.raises(RuntimeError):                                        # window longer than the tail
+        b.rdkv_cache_rebudget_tail(cache, b.Config([10], wl.hq, wl.hkv, budget_bits=[2.0], s_obs=32), Q)
+    with pytest.raises(RuntimeError):                                        # channel-wise K: not built
+        b.rdkv_cache_rebudget_tail(cache, b.Config([10], wl.hq, wl.hkv, budget_bits=[2.0], s_obs=8,
+                                                   k_mode=b.RDKV_K_CHANNELWISE), Q)
+    assert b.rdkv_cache_tail_len(cache) == 10 and b.rdkv_cache_generations(cache) == 0   # unchanged after errors
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
+    cache.free()

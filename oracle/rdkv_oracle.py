@@ -1072,7 +1072,7 @@ def decode(cache, q):
             item = s * hkv + h
             Kh, Vh = unpack_item_mixed(cache, item) if cache.get("mixed") else unpack_item(cache, item)
             for child in cache.get("absorbed", []):
-                Kc, Vc = unpack_item(child, item)
+                Kc, Vc = unpack_item_mixed(child, item) if child.get("mixed") else unpack_item(child, item)
                 Kh, Vh = np.concatenate([Kh, Kc]), np.concatenate([Vh, Vc])
             if "tail" in cache:
                 Kh, Vh = np.concatenate([Kh, cache["tail"][item][0]]), np.concatenate([Vh, cache["tail"][item][1]])
@@ -1104,18 +1104,21 @@ def decode_dense(K_list, V_list, q):
 # Streaming re-budgeting (App. "Limitations and Future Work": the extension to the decode phase)
 # --------------------------------------------------------------------------
 def rebudget_tail(cache, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B, pool_kernel=5, causal=True,
-                  rel_tol=np.float32(1e-2), max_iters=64, weights_override=None):
+                  rel_tol=np.float32(1e-2), max_iters=64, weights_override=None, eps_k=EPS_K_LLAMA31_8B,
+                  r_k=np.float32(0.5)):
     """The paper sketches the extension in one sentence: attention weights are gathered over a
     buffer of recent decode tokens and the same knapsack allocation is applied to compress
     them.  Reading taken here: the buffer is the whole appended-token zone; its n tokens are
-    treated as a sequence of their own and go through Alg. 1 unchanged (token-wise mode) --
-    the probe queries are the decode queries of the last S_w appended tokens, window row i at
-    tail position n - S_w + i, softmax over the tail's keys only -- with a budget of their own.
+    treated as a sequence of their own and go through Alg. 1 unchanged, in the mode of the
+    cache (token-wise, or V token-wise and K channel-wise on the kept tokens) -- the probe
+    queries are the decode queries of the last S_w appended tokens, window row i at tail
+    position n - S_w + i, softmax over the tail's keys only -- with a budget of their own.
     The compressed rows join the cache as one more generation (cache['absorbed']); the tail is
     empty afterwards and can take new tokens.
     Qobs_list[s]: [Hq, S_w, d]; budgets[s]: average bits per element of the tail of sequence s.
+    weights_override: token-wise caches: list of float32 [Hkv, n] token weights; mixed caches:
+    (list of [Hkv, n] token weights, list of [Hkv, d] channel weights).
     Returns the child cache (also appended to cache['absorbed'])."""
-    assert not cache.get("mixed"), "token-wise caches only"
     hkv, d = cache["hkv"], cache["d"]
     batch = len(cache["seq_lens"])
     tail = cache["tail"]
@@ -1123,8 +1126,26 @@ def rebudget_tail(cache, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B, 
     assert n > 0 and all(t[0].shape[0] == n for t in tail)
     K_list = [np.stack([tail[s * hkv + h][0] for h in range(hkv)]).astype(np.float32) for s in range(batch)]
     V_list = [np.stack([tail[s * hkv + h][1] for h in range(hkv)]).astype(np.float32) for s in range(batch)]
-    child = compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers, eps, pool_kernel, causal, rel_tol,
-                               max_iters, weights_override)
+    if cache.get("mixed"):
+        bt_list, bc_list = [], []
+        for s in range(batch):
+            if weights_override is not None:
+                w_tok = np.asarray(weights_override[0][s], dtype=np.float32)
+                w_ch = np.asarray(weights_override[1][s], dtype=np.float32)
+            else:
+                w_tok = avg_pool(token_weights(K_list[s], Qobs_list[s], causal), pool_kernel).astype(np.float32)
+                w_ch = channel_weights(K_list[s], Qobs_list[s]).astype(np.float32)
+            bt = np.zeros((hkv, n), dtype=np.uint8)
+            bc = np.zeros((hkv, d), dtype=np.uint8)
+            for h in range(hkv):
+                bt[h], bc[h] = allocate_mixed(w_tok[h], w_ch[h], budgets[s], r_k, tiers, eps, eps_k, rel_tol, max_iters)
+            bt_list.append(bt)
+            bc_list.append(bc)
+        child = build_cache_mixed(K_list, V_list, bt_list, bc_list, k_per_channel_scale=cache["k_per_unit"])
+        child["bits"] = bt_list
+    else:
+        child = compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers, eps, pool_kernel, causal, rel_tol,
+                                   max_iters, weights_override)
     cache.setdefault("absorbed", []).append(child)
     cache["tail"] = [(np.zeros((0, d)), np.zeros((0, d))) for _ in range(batch * hkv)]
     return child

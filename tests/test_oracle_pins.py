@@ -1158,10 +1158,13 @@ def test_calibration_degenerate_slices():
 # ----------------------------------------------------------------------------
 # streaming re-budgeting: the appended tokens go through the same pass (App. "Limitations and Future Work")
 # ----------------------------------------------------------------------------
-def _cache_with_tail(rng, Hkv, g, T, n_new):
+def _cache_with_tail(rng, Hkv, g, T, n_new, mixed=False):
     Ks, Vs = _small_case(rng, Hkv=Hkv, T=T)
     bits = rng.choice([0, 2, 4, 8, 16], (Hkv, T)).astype(np.uint8)
-    cache = O.build_cache_tokenwise(Ks, Vs, [bits])
+    if mixed:
+        cache = O.build_cache_mixed(Ks, Vs, [bits], [rng.choice([0, 2, 4, 8, 16], (Hkv, 128)).astype(np.uint8)])
+    else:
+        cache = O.build_cache_tokenwise(Ks, Vs, [bits])
     kn = rand_bf16(rng, (n_new, 1, Hkv, 128))
     vn = rand_bf16(rng, (n_new, 1, Hkv, 128))
     for i in range(n_new):
@@ -1169,21 +1172,23 @@ def _cache_with_tail(rng, Hkv, g, T, n_new):
     return cache, kn, vn
 
 
-def test_rebudget_at_16_bits_changes_nothing_and_at_0_bits_forgets_the_tail():
+@pytest.mark.parametrize("mixed", [False, True])
+def test_rebudget_at_16_bits_changes_nothing_and_at_0_bits_forgets_the_tail(mixed):
     rng = np.random.default_rng(81)
     Hkv, g, T, n_new, S_w = 2, 2, 120, 70, 8
     q = rand_bf16(rng, (1, Hkv * g, 128))
     Qobs = [rand_bf16(rng, (Hkv * g, S_w, 128))]
-    cache, kn, vn = _cache_with_tail(rng, Hkv, g, T, n_new)
+    cache, kn, vn = _cache_with_tail(rng, Hkv, g, T, n_new, mixed)
     before, lse_before = O.decode(cache, q)
     child = O.rebudget_tail(cache, Qobs, [np.float32(16.0)])
     assert (np.concatenate([b.ravel() for b in child["bits"]]) == 16).all()      # every row kept verbatim
+    assert not mixed or (child["bits_ch"] == 16).all()
     assert all(t[0].shape[0] == 0 for t in cache["tail"])                       # the tail is empty again
     after, lse_after = O.decode(cache, q)
     np.testing.assert_allclose(after, before, rtol=1e-12, atol=1e-13)            # same rows, other order
     np.testing.assert_allclose(lse_after, lse_before, rtol=0, atol=1e-12)
 
-    cache2, _, _ = _cache_with_tail(np.random.default_rng(83), Hkv, g, T, n_new)
+    cache2, _, _ = _cache_with_tail(np.random.default_rng(83), Hkv, g, T, n_new, mixed)
     # a zero budget evicts the whole tail: what is left is the prefix alone
     prefix_only = {k: v for k, v in cache2.items() if k != "tail"}
     want, lse_want = O.decode(prefix_only, q)
@@ -1224,4 +1229,34 @@ def test_rebudget_is_the_compression_pass_on_the_tail_and_decode_merges_the_gene
         w = np.exp(ls - m)
         want = (w[0] * out_p[0, j] + w[1] * out_c[0, j] + w[2] * np.asarray(o_t)) / w.sum()
         np.testing.assert_allclose(out[0, j], want, rtol=1e-11, atol=1e-12)
+        assert abs(lse[0, j] - (m + np.log(w.sum()))) < 1e-11
+
+
+def test_rebudget_of_a_mixed_cache_is_the_mixed_pass_on_the_tail():
+    rng = np.random.default_rng(84)
+    Hkv, g, T, n_new, S_w = 2, 2, 150, 96, 16
+    q = rand_bf16(rng, (1, Hkv * g, 128))
+    Qobs = [rand_bf16(rng, (Hkv * g, S_w, 128))]
+    cache, kn, vn = _cache_with_tail(rng, Hkv, g, T, n_new, mixed=True)
+    out_p, lse_p = O.decode({k: v for k, v in cache.items() if k != "tail"}, q)
+    child = O.rebudget_tail(cache, Qobs, [np.float32(2.0)])
+    # the same maps as the stages called one by one on the appended rows (Alg. 1, Sec. 3.2)
+    K_tail = np.ascontiguousarray(kn[:, 0].transpose(1, 0, 2))
+    V_tail = np.ascontiguousarray(vn[:, 0].transpose(1, 0, 2))
+    w_tok = O.avg_pool(O.token_weights(K_tail, Qobs[0]), 5).astype(np.float32)
+    w_ch = O.channel_weights(K_tail, Qobs[0]).astype(np.float32)
+    for h in range(Hkv):
+        bt, bc = O.allocate_mixed(w_tok[h], w_ch[h], np.float32(2.0))
+        assert np.array_equal(child["bits"][0][h], bt) and np.array_equal(child["bits_ch"][h], bc)
+        n_kept = int((bt > 0).sum())
+        assert 0 < n_kept < n_new and 0 < int((bc > 0).sum())
+    alone = O.build_cache_mixed([K_tail], [V_tail], child["bits"], [child["bits_ch"].reshape(Hkv, 128)])
+    assert np.array_equal(child["arena"], alone["arena"])
+    out, lse = O.decode(cache, q)
+    out_c, lse_c = O.decode(alone, q)
+    for j in range(Hkv * g):
+        ls = np.array([lse_p[0, j], lse_c[0, j]])
+        m = ls.max()
+        w = np.exp(ls - m)
+        np.testing.assert_allclose(out[0, j], (w[0] * out_p[0, j] + w[1] * out_c[0, j]) / w.sum(), rtol=1e-11, atol=1e-12)
         assert abs(lse[0, j] - (m + np.log(w.sum()))) < 1e-11

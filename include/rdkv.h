@@ -234,9 +234,10 @@ int32_t rdkv_cache_tail_len(const rdkv_cache* cache);
 /*
  * Streaming re-budgeting (the extension sketched in App. "Limitations and Future Work"): the appended tokens are
  * compressed by the same pass (Alg. 1) as a sequence of their own and join the compressed zones as one more
- * generation; the tail is empty afterwards and keeps its capacity.  Token-wise caches only (RDKV_ERR_UNSUPPORTED
- * otherwise).
- *   cfg     the pass's parameters for the tail: batch, hq, hkv, head_dim as the cache; seq_lens[s] =
+ * generation; the tail is empty afterwards and keeps its capacity.  Both cache modes; in channel-wise mode the
+ * generation gets its own channel bit map and sorted-channel layout per (sequence, KV head).
+ *   cfg     the pass's parameters for the tail: batch, hq, hkv, head_dim, k_mode and k_scale_per_channel as the
+ *           cache; seq_lens[s] =
  *           rdkv_cache_tail_len(cache) for every s; budget_bits[s] = average bits per element of the tail of
  *           sequence s; s_obs <= tail length; tiers, distortion tables, tolerance as for rdkv_compress
  *   Q_obs   DEVICE bf16 [batch][hq][s_obs][d]: the decode queries of the last s_obs appended tokens (window row i

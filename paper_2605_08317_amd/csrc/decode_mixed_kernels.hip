@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mix
   const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * g) * kHeadDim;
   float* pa = part_acc + static_cast<int64_t>(ch.slot) * g * kHeadDim;
   float* pm = part_ml + static_cast<int64_t>(ch.slot) * g * 2;
-  const ItemK* ikp = items_k + ch.item;
+  const ItemK* ikp = items_k + ch.reserved;   // the K row layout of this chunk's (generation, item)
   switch (ch.tier) {
     case kTierTail:   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
       process_tail_tiles<HS, true>(arena + ch.k_data, arena + ch.v_data, min(ch.rows, row_limit - ch.row0), g, qp, smem,

@@ -220,6 +220,7 @@ void free_cache_buffers(rdkv_cache* c) {
   al.put(c->d_bits_tok);
   al.put(c->d_bits_ch);
   al.put(c->d_items_k);
+  al.put(c->d_items_sched);
   al.put(c->d_tail);
   for (rdkv_cache* child : c->absorbed) {
     free_cache_buffers(child);
@@ -672,7 +673,7 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
         ch.slot = static_cast<int32_t>(c->chunks.size());
         for (int t2 = 0; t2 < 4; ++t2) ch.k_word_end[t2] = mixed ? c->items_k[i].word_end[t2] : int16_t(0);
         ch.row0 = 0;
-        ch.reserved = 0;
+        ch.reserved = static_cast<int32_t>(i);
         c->chunks.push_back(ch);
       }
     }
@@ -790,7 +791,9 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
     {
       TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
       RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->sched16 + c->schedq) + live_tail_chunks(c), c->d_arena,
-                                   c->d_items_k, c->max_k_words, c->max_k_steps, c->max_k_qsteps,
+                                   c->d_items_sched ? c->d_items_sched : c->d_items_k,
+                                   std::max(c->max_k_words, c->sched_k_words), std::max(c->max_k_steps, c->sched_k_steps),
+                                   std::max(c->max_k_qsteps, c->sched_k_qsteps),
                                    static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
                                    c->hq, c->hkv, c->tail_len, c->k_per_unit, st));
     }
@@ -850,6 +853,7 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
         Chunk ch = gc->chunks[j];
         if ((ch.tier == 16) != (pass == 0)) continue;
         ch.slot = nb[ch.item] + gen_off[k][ch.item] + (ch.slot - gc->slot_begin[ch.item]);
+        ch.reserved = static_cast<int32_t>(k * n + ch.item);
         if (k == 0) own[j].slot = ch.slot;
         ch.k_data += base;
         ch.k_meta += base;
@@ -876,11 +880,26 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
       table.push_back(ch);
     }
   const int64_t n_table = static_cast<int64_t>(table.size());
+  // channel-wise K: every (generation, item) has its own sorted-channel row layout
+  const bool mixed = c->k_mode == RDKV_K_CHANNELWISE;
+  std::vector<ItemK> items_sched;
+  ItemK* d_items_sched = nullptr;
+  int32_t kw = 0, ks = 0, kq = 0;
+  if (mixed && gens.size() > 1) {
+    for (const rdkv_cache* gc : gens) {
+      items_sched.insert(items_sched.end(), gc->items_k.begin(), gc->items_k.end());
+      kw = std::max(kw, gc->max_k_words);
+      ks = std::max(ks, gc->max_k_steps);
+      kq = std::max(kq, gc->max_k_qsteps);
+    }
+    d_items_sched = static_cast<ItemK*>(al.get(items_sched.size() * sizeof(ItemK)));
+    if (!d_items_sched) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  }
   Chunk* d_chunks = static_cast<Chunk*>(al.get(std::max<int64_t>(n_table, 1) * sizeof(Chunk)));
   float* d_acc = static_cast<float*>(al.get(std::max<int64_t>(n_slots, 1) * g * kHeadDim * sizeof(float)));
   float* d_ml = static_cast<float*>(al.get(std::max<int64_t>(n_slots, 1) * g * 2 * sizeof(float)));
   if (!d_chunks || !d_acc || !d_ml) {
-    al.put(d_chunks); al.put(d_acc); al.put(d_ml);
+    al.put(d_chunks); al.put(d_acc); al.put(d_ml); al.put(d_items_sched);
     return fail(RDKV_ERR_ALLOC, "device allocation failed");
   }
   // slots of tail chunks that no launch has reached yet must read as empty partials: m = -1e30, l = 0, acc = 0
@@ -893,16 +912,23 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
   }
   if (e == hipSuccess && n_table > 0)
     e = hipMemcpyAsync(d_chunks, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && d_items_sched)
+    e = hipMemcpyAsync(d_items_sched, items_sched.data(), items_sched.size() * sizeof(ItemK), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_begin, nb.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_count, nc.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);     // the host vectors above go out of scope
   if (e != hipSuccess) {
-    al.put(d_chunks); al.put(d_acc); al.put(d_ml);
+    al.put(d_chunks); al.put(d_acc); al.put(d_ml); al.put(d_items_sched);
     return fail(RDKV_ERR_HIP, "rebuilding the decode schedule: %s", hipGetErrorString(e));
   }
   al.put(c->d_part_acc);
   al.put(c->d_part_ml);
   al.put(c->d_chunks);
+  al.put(c->d_items_sched);
+  c->d_items_sched = d_items_sched;
+  c->sched_k_words = kw;
+  c->sched_k_steps = ks;
+  c->sched_k_qsteps = kq;
   c->d_part_acc = d_acc;
   c->d_part_ml = d_ml;
   c->d_chunks = d_chunks;
@@ -959,8 +985,9 @@ int32_t rdkv_cache_tail_len(const rdkv_cache* c) { return c ? c->tail_len : 0; }
 
 rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, const void* Q_obs, void* stream) {
   if (!c || !cfg || !Q_obs) return fail(RDKV_ERR_INVALID_ARG, "cache, cfg and Q_obs must not be null");
-  if (c->k_mode != RDKV_K_TOKENWISE || cfg->k_mode != RDKV_K_TOKENWISE)
-    return fail(RDKV_ERR_UNSUPPORTED, "re-budgeting of appended tokens is built for token-wise caches only");
+  if (cfg->k_mode != c->k_mode || (c->k_mode == RDKV_K_CHANNELWISE && (cfg->k_scale_per_channel != 0) != (c->k_per_unit != 0)))
+    return fail(RDKV_ERR_INVALID_ARG, "cfg must name the cache's own K format (k_mode %d, k_scale_per_channel %d)",
+                c->k_mode, c->k_per_unit);
   if (c->tail_len <= 0) return fail(RDKV_ERR_INVALID_ARG, "no appended tokens to compress");
   if (cfg->batch != c->batch || cfg->hq != c->hq || cfg->hkv != c->hkv || cfg->head_dim != c->d)
     return fail(RDKV_ERR_SHAPE, "cfg (batch %d, hq %d, hkv %d, d %d) does not match the cache (%d, %d, %d, %d)",

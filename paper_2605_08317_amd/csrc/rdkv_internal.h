@@ -32,7 +32,8 @@ struct Chunk {
   int32_t slot;                             // partial-result slot
   int16_t k_word_end[4];                    // mixed mode: ItemK::word_end of the item (the shape of its K rows)
   int32_t row0;                             // appended-token zone: first row of the chunk inside the item's tail
-  int32_t reserved;
+  int32_t reserved;                         // mixed mode: index of the chunk's ItemK in the schedule's table
+                                            // (generation * items + item)
 };
 constexpr int kTailChunkRows = 256;         // appended tokens per decode work item
 constexpr int kTierTail = 17;               // Chunk::tier of a chunk of appended tokens (64-token tiles of bf16 rows)
@@ -138,6 +139,8 @@ struct rdkv_cache {
   std::vector<rdkv_cache*> absorbed;
   std::vector<int32_t> own_slot_count;  // [items]: partial slots of this cache's own chunks (no tail, no absorbed)
   int64_t sched16 = 0, schedq = 0;      // chunks of the schedule: 16-bit tier, then the quantized tiers (all generations)
+  rdkv::ItemK* d_items_sched = nullptr; // mixed mode with absorbed generations: [generations][items] K row layouts
+  int32_t sched_k_words = 0, sched_k_steps = 0, sched_k_qsteps = 0;   // largest K row shape over all generations
   int64_t stored_bytes = 0;             // bytes a decode step must read (unpadded)
   int64_t index_bytes = 0;
   rdkv_alloc_fn alloc = nullptr;

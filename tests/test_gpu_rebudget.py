@@ -8,6 +8,7 @@ import torch
 
 from oracle import rdkv_oracle as O
 from test_gpu_parity import B, _np, _check_decode, _inputs, _pack_both, _assert_cache_equal
+from test_gpu_mixed import _pack_both_mixed, _random_maps, _assert_cache_equal_mixed
 
 pytestmark = pytest.mark.gpu
 
@@ -126,10 +127,50 @@ def test_rebudget_argument_errors():
         b.rdkv_cache_rebudget_tail(cache, b.Config([10], wl.hq * 2, wl.hkv, budget_bits=[2.0], s_obs=8), Q)
     with pytest.raises(RuntimeError):                                        # window longer than the tail
         b.rdkv_cache_rebudget_tail(cache, b.Config([10], wl.hq, wl.hkv, budget_bits=[2.0], s_obs=32), Q)
-    with pytest.raises(RuntimeError):                                        # channel-wise K: not built
+    with pytest.raises(RuntimeError):                                        # not the cache's own K format
         b.rdkv_cache_rebudget_tail(cache, b.Config([10], wl.hq, wl.hkv, budget_bits=[2.0], s_obs=8,
                                                    k_mode=b.RDKV_K_CHANNELWISE), Q)
     assert b.rdkv_cache_tail_len(cache) == 10 and b.rdkv_cache_generations(cache) == 0   # unchanged after errors
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
+    cache.free()
+
+
+@pytest.mark.parametrize("name,kw,n_new,budgets,per_channel_scale", [
+    ("tiny", {"seq_lens": (900,)}, 200, [3.0], False),
+    ("tiny", {"seq_lens": (600,)}, 160, [1.5], True),            # one K scale per channel over the unit (App. B)
+    ("batch70b", {"batch": 2, "len_range": (100, 700)}, 300, [1.0, 6.0], False),   # 8 query heads per KV head
+])
+def test_rebudget_mixed_matches_oracle(name, kw, n_new, budgets, per_channel_scale):
+    """Channel-wise caches: the generation has its own channel bit map and K row layout per (sequence, KV head)."""
+    b = B()
+    wl, inp, dev = _inputs(name, **kw)
+    batch = len(inp["seq_lens"])
+    rng = np.random.default_rng(94)
+    bt, bc = _random_maps(rng, inp["seq_lens"], wl.hkv, [.3, .3, .2, .1, .1], [.1, .4, .3, .15, .05])
+    cache, ref = _pack_both_mixed(b, wl, inp, dev, bt, bc, per_channel_scale)
+    b.rdkv_cache_reserve_tail(cache, 320)
+    k_rows, _ = _append(b, cache, ref, rng, n_new, batch, wl.hkv)
+    Q_obs = torch.from_numpy(rng.standard_normal((batch, wl.hq, 32, 128)).astype(np.float32)).to(torch.bfloat16)
+    cfg = b.Config([n_new] * batch, wl.hq, wl.hkv, budget_bits=budgets, s_obs=32, k_mode=b.RDKV_K_CHANNELWISE,
+                   k_scale_per_channel=int(per_channel_scale))
+    print(f"[step] rebudget mixed tail of {n_new} tokens, budgets {budgets}", flush=True)
+    b.rdkv_cache_rebudget_tail(cache, cfg, Q_obs.cuda())
+    w_tok, w_ch = b.rdkv_weights(cfg, k_rows.reshape(-1).cuda(), Q_obs.cuda(), want_channel=True)
+    torch.cuda.synchronize()
+    wt = [w.cpu().numpy() for w in w_tok.view(batch, wl.hkv, n_new)]
+    wc = [w.cpu().numpy() for w in w_ch.view(batch, wl.hkv, 128)]
+    child = O.rebudget_tail(ref, [_np(Q_obs[s]) for s in range(batch)], [np.float32(x) for x in budgets],
+                            weights_override=(wt, wc))
+    gen = b.rdkv_cache_generation(cache, 0, cfg)
+    np.testing.assert_array_equal(gen.export(b.RDKV_EXPORT_BITS_TOK, np.uint8),
+                                  np.concatenate([x.reshape(-1) for x in child["bits"]]))
+    _assert_cache_equal_mixed(b, gen, child)
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
+    _append(b, cache, ref, rng, 5, batch, wl.hkv)
     out, lse = b.rdkv_decode_attn(cache, dev["q"])
     torch.cuda.synchronize()
     _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))

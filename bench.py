@@ -254,6 +254,34 @@ def main():
     kern_ms = ms_k / max(n_k, 1)
     achieved = alg_bytes_layer / (kern_ms * 1e-3) / 1e9
 
+    # where a per-layer launch spends its time: the same two kernels over a cache of 256 tokens (launch and latency
+    # floor), and over one layer's cache again and again (its 16 MB stay in the L2 caches: no HBM wait)
+    floor = None
+    try:
+        wl_t = W.scaled(wl, seq_lens=(256,))
+        in_t = W.make_inputs(wl_t, device="cuda")
+        c_t = b.rdkv_compress(b.Config([256], hq, hkv, budget_bits=budgets, s_obs=wl.s_obs), in_t["K"], in_t["V"],
+                              in_t["Q_obs"])
+        g_t, g_h = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        for _ in range(2):
+            b.rdkv_decode_attn(c_t, in_t["q"], outs[0], lses[0])
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g_t):
+            for l in range(L):
+                b.rdkv_decode_attn(c_t, in_t["q"], outs[0], lses[0])
+        with torch.cuda.graph(g_h):
+            for l in range(L):
+                b.rdkv_decode_attn(caches[0], q_l[0], outs[0], lses[0])
+        g_t.replay(); g_h.replay()
+        floor = {"us_per_layer_256_token_cache": timed_ms(g_t.replay, args.steps, torch) * 1e3 / L,
+                 "us_per_layer_same_layer_repeated": timed_ms(g_h.replay, args.steps, torch) * 1e3 / L,
+                 "us_per_layer": ms_step * 1e3 / L}
+        c_t.free()
+        step()                                     # outs[0] again holds layer 0's result
+        torch.cuda.synchronize()
+    except Exception as e:  # reported, never hidden
+        floor = {"error": repr(e)}
+
     if args.per_layer_only:
         print(json.dumps({"per_layer_only": True, "ms_per_step": ms_step, "kernel_ms": kern_ms,
                           "bytes_per_launch": alg_bytes_layer, "achieved_gbs": achieved}))
@@ -475,6 +503,7 @@ def main():
                       "achieved_gbs": bf16_bytes_layer / (k16_ms * 1e-3) / 1e9,
                       "frac": bf16_bytes_layer / (k16_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "speedup_compressed_vs_bf16": ms_bf16 / ms_step},
+        "per_layer_launch_breakdown": floor,
         "batched_launch": batched,
         "mixed_path": mixed,
         "generation_loop": gen,

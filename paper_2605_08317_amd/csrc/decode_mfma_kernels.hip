@@ -150,24 +150,59 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
 #pragma unroll
         for (int i = 0; i < 4; ++i) x[hs][i] = d[i] * kKUnit;
       }
+      // The query operands come from LDS two steps at a time.  With one head set the read of the next pair of steps
+      // is issued before the products of the current pair, so that they cover the LDS latency; with two head sets
+      // the extra operand registers would spill, and the pair is read where it is used.
+      constexpr bool kAhead = HS == 1;
+      auto qread = [&](int hs, int grp, int st) __attribute__((always_inline)) {
+        return *reinterpret_cast<const uint2*>(s_qop + (((hs * 4 + grp) * 8 + st) * 4 + j) * 8);
+      };
+      uint2 bq[kAhead ? 2 : 1][HS][2];
+      if constexpr (kAhead) {
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) {
+          bq[0][hs][0] = qread(hs, 0, 0);
+          bq[0][hs][1] = qread(hs, 0, 1);
+        }
+      }
 #pragma unroll
       for (int grp = 0; grp < 4; ++grp) {
-        __builtin_amdgcn_sched_barrier(0);   // keep a group's operand reads next to their use (register pressure)
+        __builtin_amdgcn_sched_barrier(0);   // keep a group's unpacked words next to their use (register pressure)
         uint32_t gw[S::kCopies][TIER];
         group_words<TIER>(kraw, grp, gw);
         floatx4 dg[HS];
 #pragma unroll
         for (int hs = 0; hs < HS; ++hs) dg[hs] = zero4;
 #pragma unroll
-        for (int st = 0; st < 8; ++st) {
-          const half4 a = step_operand<TIER>(gw, st);
+        for (int sp = 0; sp < 4; ++sp) {
+          const int cur = kAhead ? (grp * 4 + sp) & 1 : 0;
+          if constexpr (kAhead) {
+            if (!(grp == 3 && sp == 3)) {
+              const int ngrp = sp == 3 ? grp + 1 : grp, nst = sp == 3 ? 0 : 2 * (sp + 1);
 #pragma unroll
-          for (int hs = 0; hs < HS; ++hs) {
-            Pack4 b;
-            const uint2 braw = *reinterpret_cast<const uint2*>(s_qop + (((hs * 4 + grp) * 8 + st) * 4 + j) * 8);
-            b.u[0] = braw.x;
-            b.u[1] = braw.y;
-            dg[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, b.h, dg[hs], 0, 0, 0);
+              for (int hs = 0; hs < HS; ++hs) {
+                bq[cur ^ 1][hs][0] = qread(hs, ngrp, nst);
+                bq[cur ^ 1][hs][1] = qread(hs, ngrp, nst + 1);
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          } else {
+#pragma unroll
+            for (int hs = 0; hs < HS; ++hs) {
+              bq[0][hs][0] = qread(hs, grp, 2 * sp);
+              bq[0][hs][1] = qread(hs, grp, 2 * sp + 1);
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const half4 a = step_operand<TIER>(gw, 2 * sp + e);
+#pragma unroll
+            for (int hs = 0; hs < HS; ++hs) {
+              Pack4 b;
+              b.u[0] = bq[cur][hs][e].x;
+              b.u[1] = bq[cur][hs][e].y;
+              dg[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, b.h, dg[hs], 0, 0, 0);
+            }
           }
         }
         // scale of (token 4 blk + i, group): held by lane i of this quad in half grp of its (x, y)

@@ -196,9 +196,11 @@ rdkv_status check_config(const rdkv_config* cfg, bool need_budget, bool need_pro
 }
 
 // chunk size policy of the dense path; used by the workspace query and the launch alike.  The split kernel keeps
-// 4 / 4 / 2 / 1 workgroups per compute unit resident at g = 1 / 2 / 4 / 8 (its register count), and a launch is
-// fastest when its workgroups fill the 256 compute units exactly once (measured at g = 4 on 8 x 128K tokens: 512
-// chunks 101 us, 1024 chunks 107 us, 640 chunks 126 us): aim for that many chunks of at least 256 rows.
+// 4 / 4 / 2 / 1 workgroups per compute unit resident at g = 1 / 2 / 4 / 8 (its register count).  Up to g = 4 a launch
+// is fastest when its workgroups fill the 256 compute units exactly once (measured at g = 4 on 8 x 128K tokens: 512
+// chunks 101 us, 1024 chunks 107 us, 640 chunks 126 us).  At g = 8 one workgroup per compute unit leaves nothing to
+// even out ragged sequence lengths, and four rounds are faster (16 sequences of 8K-32K tokens: 1024 chunks 539 us,
+// 256 chunks 760 us).  Chunks have at least 256 rows.
 void dense_plan(const int32_t* seq_lens, int batch, int hkv, int g, int* chunk_rows, int* max_splits) {
   int64_t total = 0;
   int max_T = 0;
@@ -206,7 +208,7 @@ void dense_plan(const int32_t* seq_lens, int batch, int hkv, int g, int* chunk_r
     total += static_cast<int64_t>(seq_lens[s]) * hkv;
     max_T = std::max(max_T, seq_lens[s]);
   }
-  const int64_t resident = 256 * (g <= 2 ? 4 : g <= 4 ? 2 : 1);
+  const int64_t resident = g <= 2 ? 1024 : g <= 4 ? 512 : 1024;
   int64_t cr = round_up(std::max<int64_t>(256, (total + resident - 1) / resident), 64);
   *chunk_rows = static_cast<int>(cr);
   *max_splits = std::max(1, static_cast<int>((max_T + cr - 1) / cr));

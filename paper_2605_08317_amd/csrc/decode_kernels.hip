@@ -305,6 +305,25 @@ __global__ __launch_bounds__(kMergeThreads) void merge_tiered_kernel(const float
               lse ? lse + qh : nullptr);
 }
 
+// The same merge for launches of few items: the slot tables travel in the kernel arguments, so the kernel's first
+// loads are the partials themselves (one dependent memory round trip less on a latency-bound per-layer decode).
+constexpr int kSmallMergeItems = 16;
+struct SmallSlots {
+  int32_t begin[kSmallMergeItems], count[kSmallMergeItems];
+};
+__global__ __launch_bounds__(kMergeThreads) void merge_tiered_small_kernel(const float* __restrict__ part_acc,
+                                                                      const float* __restrict__ part_ml,
+                                                                      SmallSlots slots, int g, int hq, int hkv,
+                                                                      float* __restrict__ out,
+                                                                      float* __restrict__ lse) {
+  const int h = blockIdx.x % g;
+  const int item = blockIdx.x / g;
+  const int seq = item / hkv, head = item % hkv;
+  const int64_t qh = static_cast<int64_t>(seq) * hq + head * g + h;
+  merge_slots(part_acc, part_ml, slots.begin[item], slots.count[item], g, h, out + qh * kHeadDim,
+              lse ? lse + qh : nullptr);
+}
+
 }  // namespace
 
 hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
@@ -410,9 +429,20 @@ hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t
 }
 
 hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
-                                      const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
+                                      const int32_t* slot_count, const int32_t* h_slot_begin,
+                                      const int32_t* h_slot_count, int n_items, int hq, int hkv, float* out,
                                       float* lse, hipStream_t st) {
   const int g = hq / hkv;
+  if (n_items <= kSmallMergeItems && h_slot_begin && h_slot_count) {
+    SmallSlots s{};
+    for (int i = 0; i < n_items; ++i) {
+      s.begin[i] = h_slot_begin[i];
+      s.count[i] = h_slot_count[i];
+    }
+    hipLaunchKernelGGL(merge_tiered_small_kernel, dim3(n_items * g), dim3(kMergeThreads), 0, st, part_acc, part_ml,
+                       s, g, hq, hkv, out, lse);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(merge_tiered_kernel, dim3(n_items * g), dim3(kMergeThreads), 0, st, part_acc, part_ml,
                      slot_begin, slot_count, g, hq, hkv, out, lse);
   return hipGetLastError();

@@ -804,7 +804,8 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
                                    c->hq, c->hkv, c->tail_len, c->k_per_unit, st));
     }
     RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
-                                        static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));
+                                        c->slot_begin.data(), c->slot_count.data(), static_cast<int>(c->n_items),
+                                        c->hq, c->hkv, out, lse, st));
     return RDKV_OK;
   }
   {
@@ -817,7 +818,8 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
                                  c->tail_len, st));
   }
   RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
-                                      static_cast<int>(c->n_items), c->hq, c->hkv, out, lse, st));
+                                      c->slot_begin.data(), c->slot_count.data(), static_cast<int>(c->n_items),
+                                      c->hq, c->hkv, out, lse, st));
   return RDKV_OK;
 }
 

@@ -75,8 +75,10 @@ hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint
                               int32_t tail_tiles, int32_t row, hipStream_t st);
 hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t tail_tiles, int32_t n,
                                    uint16_t* k_rows, uint16_t* v_rows, hipStream_t st);
+// h_slot_begin / h_slot_count: host copies of the two tables (used for launches of few items), or null
 hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
-                                      const int32_t* slot_count, int n_items, int hq, int hkv, float* out,
+                                      const int32_t* slot_count, const int32_t* h_slot_begin,
+                                      const int32_t* h_slot_count, int n_items, int hq, int hkv, float* out,
                                       float* lse, hipStream_t st);
 
 // row_limit: appended tokens that exist so far (chunks of tier kTierTail end there)

@@ -241,6 +241,23 @@ def rdkv_cache_tail_len(cache):
     return int(lib.rdkv_cache_tail_len(cache.h))
 
 
+@_ALLOC_FN
+def _torch_alloc(nbytes, user):
+    return torch.cuda.caching_allocator_alloc(nbytes)
+
+
+@_FREE_FN
+def _torch_free(ptr, user):
+    torch.cuda.caching_allocator_delete(ptr)
+
+
+def torch_allocator_hooks():
+    """Config overrides that route the library's device allocations through PyTorch's caching allocator
+    (`Config(..., **torch_allocator_hooks())`): hipMalloc / hipFree of the large scratch and arena buffers cost more
+    than the kernels of a compression pass over one 128K-token layer."""
+    return {"alloc": _torch_alloc, "free_": _torch_free}
+
+
 class _Borrowed(Cache):
     """A generation of another cache: never freed from here."""
 

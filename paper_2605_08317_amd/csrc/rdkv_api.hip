@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <initializer_list>
 #include <mutex>
 #include <new>
 #include <utility>
@@ -96,14 +97,34 @@ struct Allocator {
   }
 };
 
-// Device scratch that is released when the call returns.
+// Device scratch that is released when the call returns.  reserve() takes one allocation up front that the
+// following get() calls are carved from (an allocation and its release cost tens of microseconds each and the
+// release synchronises the device); requests that do not fit fall back to allocations of their own.
 struct Temp {
   const Allocator& al;
   std::vector<void*> ptrs;
+  uint8_t* slab = nullptr;
+  size_t slab_bytes = 0, used = 0;
   explicit Temp(const Allocator& a) : al(a) {}
   ~Temp() { for (void* p : ptrs) al.put(p); }
+  static size_t padded(size_t bytes) { return (std::max<size_t>(bytes, 16) + 255) / 256 * 256; }
+  void reserve(std::initializer_list<size_t> sizes) {
+    size_t total = 0;
+    for (size_t b : sizes) total += padded(b);
+    slab = static_cast<uint8_t*>(al.get(total));
+    if (slab) {
+      ptrs.push_back(slab);
+      slab_bytes = total;
+    }
+  }
   template <typename T>
   T* get(size_t n) {
+    const size_t b = padded(n * sizeof(T));
+    if (slab && used + b <= slab_bytes) {
+      T* p = reinterpret_cast<T*>(slab + used);
+      used += b;
+      return p;
+    }
     void* p = al.get(n * sizeof(T));
     if (p) ptrs.push_back(p);
     return static_cast<T*>(p);
@@ -382,10 +403,12 @@ rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_ob
     n_wblk += (it.T[i] + wb - 1) / wb;
   }
   const int R_pad = (cfg->hq / cfg->hkv * cfg->s_obs + 15) / 16 * 16;
+  const size_t nscr = weights_scratch_floats(n_wblk, it.n_items, it.total_tokens, R_pad, w_ch != nullptr);
+  tmp.reserve({it.n_items * sizeof(int64_t), it.n_items * sizeof(int32_t), it.n_items * sizeof(int32_t),
+               nscr * sizeof(float)});
   int64_t* d_off = tmp.get<int64_t>(it.n_items);
   int32_t* d_T = tmp.get<int32_t>(it.n_items);
   int32_t* d_wblk = tmp.get<int32_t>(it.n_items);
-  const size_t nscr = weights_scratch_floats(n_wblk, it.n_items, it.total_tokens, R_pad, w_ch != nullptr);
   float* scratch = tmp.get<float>(nscr);
   if (!d_off || !d_T || !d_wblk || !scratch) return fail(RDKV_ERR_ALLOC, "device allocation failed");
   RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
@@ -420,6 +443,8 @@ rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void
   const size_t n = static_cast<size_t>(it.n_items);
   const bool channelwise = cfg->k_mode == RDKV_K_CHANNELWISE;
   const bool whole = channelwise && cfg->k_scale_per_channel != 0;
+  tmp.reserve({n * sizeof(int64_t), n * sizeof(int32_t), n * 8 * sizeof(double),
+               whole ? n * kHeadDim * 2 * sizeof(uint32_t) : 0});
   int64_t* d_off = tmp.get<int64_t>(n);
   int32_t* d_T = tmp.get<int32_t>(n);
   double* d_acc = tmp.get<double>(n * 8);                       // [K | V][items][4]
@@ -476,6 +501,8 @@ rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const floa
     budget[i] = mixed ? static_cast<double>(static_cast<float>(2.0 * (1.0 - static_cast<double>(cfg->kv_split_rk)) * a))
                       : a;
   }
+  tmp.reserve({n * sizeof(int64_t), n * sizeof(int32_t), n * sizeof(double), n * sizeof(int32_t),
+               n * sizeof(int64_t), n * sizeof(int32_t), n * sizeof(double)});
   int64_t* d_off = tmp.get<int64_t>(n);
   int32_t* d_T = tmp.get<int32_t>(n);
   double* d_budget = tmp.get<double>(n);
@@ -560,6 +587,13 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   c->counts.assign(n * 4, 0);
   c->seg_off.assign(n * 16, 0);
   Temp tmp(al);
+  {
+    const size_t n1 = static_cast<size_t>(std::max<int64_t>(n, 1));
+    tmp.reserve({n1 * sizeof(int64_t), n1 * sizeof(int32_t), n1 * sizeof(int32_t),
+                 static_cast<size_t>(std::max<int64_t>(it.n_blocks * 4, 1)) * sizeof(int32_t),
+                 n1 * 4 * sizeof(int32_t), n1 * 4 * sizeof(int64_t), n1 * 16 * sizeof(int64_t),
+                 cfg->k_mode == RDKV_K_CHANNELWISE && cfg->k_scale_per_channel ? n1 * kHeadDim * 2 * sizeof(uint32_t) : 0});
+  }
   int64_t* d_tok_off = tmp.get<int64_t>(std::max<int64_t>(n, 1));
   int32_t* d_T = tmp.get<int32_t>(std::max<int64_t>(n, 1));
   int32_t* d_blk_off = tmp.get<int32_t>(std::max<int64_t>(n, 1));
@@ -772,6 +806,11 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, 
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
   Temp tmp(al);
   Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  {
+    const size_t nt = static_cast<size_t>(std::max<int64_t>(it.total_tokens, 1));
+    const size_t nc = static_cast<size_t>(std::max<int64_t>(it.n_items, 1)) * kHeadDim;
+    tmp.reserve({nt * sizeof(float), nt, mixed ? nc * sizeof(float) : 0, mixed ? nc : 0});
+  }
   float* w = tmp.get<float>(std::max<int64_t>(it.total_tokens, 1));
   uint8_t* bits = tmp.get<uint8_t>(std::max<int64_t>(it.total_tokens, 1));
   float* w_ch = mixed ? tmp.get<float>(std::max<int64_t>(it.n_items, 1) * kHeadDim) : nullptr;
@@ -1009,6 +1048,7 @@ rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, cons
   Temp tmp(al);
   const int32_t n_tail = c->tail_len;
   const size_t elems = static_cast<size_t>(c->n_items) * n_tail * kHeadDim;
+  tmp.reserve({elems * sizeof(uint16_t), elems * sizeof(uint16_t)});
   uint16_t* k_rows = tmp.get<uint16_t>(elems);
   uint16_t* v_rows = tmp.get<uint16_t>(elems);
   if (!k_rows || !v_rows) return fail(RDKV_ERR_ALLOC, "device allocation failed");

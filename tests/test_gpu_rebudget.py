@@ -175,3 +175,63 @@ def test_rebudget_mixed_matches_oracle(name, kw, n_new, budgets, per_channel_sca
     torch.cuda.synchronize()
     _check_decode(out, lse, *O.decode(ref, _np(inp["q"])))
     cache.free()
+
+
+def test_rebudget_at_full_size():
+    """One layer of the 128K-token stack, in the launch configuration the benchmark times: compress, append 256
+    tokens, re-budget them at 2 bits, append 9 more, decode.  The oracle redoes one sampled KV head end to end from the
+    library's fp32 weights (prompt and tail): bit maps and the generation's bytes bit for bit, output within 2e-3."""
+    from paper_2605_08317_amd import workloads as W
+    b = B()
+    wl = W.CONFIGS["stack128k"]
+    T, n_new, h, g = wl.seq_lens[0], 256, 5, wl.hq // wl.hkv
+    print("[case] full-size stack128k layer 3 with re-budgeting", flush=True)
+    inp = W.make_inputs(wl, device="cuda", layer=3)
+    cfg = b.Config([T], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs)
+    cache = b.rdkv_compress(cfg, inp["K"], inp["V"], inp["Q_obs"])
+    w_tok, _ = b.rdkv_weights(cfg, inp["K"], inp["Q_obs"])
+    torch.cuda.synchronize()
+    # the oracle's copy of head h: prompt zones from the library's weights
+    Kh = inp["K"].view(wl.hkv, T, 128)[h].float().cpu().numpy()[None]
+    Vh = inp["V"].view(wl.hkv, T, 128)[h].float().cpu().numpy()[None]
+    bt = O.mckp_bisect(w_tok.view(wl.hkv, T)[h].cpu().numpy(), np.float32(inp["budgets"][0]))
+    np.testing.assert_array_equal(cache.export(b.RDKV_EXPORT_BITS_TOK, np.uint8).reshape(wl.hkv, T)[h], bt)
+    ref = O.build_cache_tokenwise([Kh], [Vh], [bt[None]])
+    # 256 appended tokens
+    rng = np.random.default_rng(95)
+    kn = torch.from_numpy(rng.standard_normal((n_new + 9, 1, wl.hkv, 128)).astype(np.float32)).to(torch.bfloat16)
+    vn = torch.from_numpy(rng.standard_normal((n_new + 9, 1, wl.hkv, 128)).astype(np.float32)).to(torch.bfloat16)
+    kd, vd = kn.cuda(), vn.cuda()
+    b.rdkv_cache_reserve_tail(cache, n_new)
+    for i in range(n_new):
+        b.rdkv_cache_append(cache, kd[i], vd[i])
+        O.append_tokens(ref, kn[i, :, h:h + 1].float().numpy(), vn[i, :, h:h + 1].float().numpy())
+    Q_obs = torch.from_numpy(rng.standard_normal((1, wl.hq, wl.s_obs, 128)).astype(np.float32)).to(torch.bfloat16)
+    cfg_t = b.Config([n_new], wl.hq, wl.hkv, budget_bits=[2.0], s_obs=wl.s_obs)
+    b.rdkv_cache_rebudget_tail(cache, cfg_t, Q_obs.cuda())
+    k_rows = kn[:n_new, 0].permute(1, 0, 2).contiguous()                          # [hkv][n][128]
+    w_tail, _ = b.rdkv_weights(cfg_t, k_rows.reshape(-1).cuda(), Q_obs.cuda())
+    torch.cuda.synchronize()
+    child = O.rebudget_tail(ref, [Q_obs[0, h * g:(h + 1) * g].float().numpy()], [np.float32(2.0)],
+                            weights_override=[w_tail.view(wl.hkv, n_new)[h:h + 1].cpu().numpy()])
+    gen = b.rdkv_cache_generation(cache, 0, cfg_t)
+    np.testing.assert_array_equal(gen.export(b.RDKV_EXPORT_BITS_TOK, np.uint8).reshape(wl.hkv, n_new)[h], child["bits"][0][0])
+    # the generation's segments of item h against the oracle's single-item child
+    counts = gen.export(b.RDKV_EXPORT_COUNTS, np.int32).reshape(-1, 4)
+    seg_off = gen.export(b.RDKV_EXPORT_SEG_OFF, np.int64).reshape(-1, 4, 4)
+    arena = gen.export(b.RDKV_EXPORT_ARENA, np.uint8)
+    np.testing.assert_array_equal(counts[h], child["counts"][0])
+    for ti, bits in enumerate(O.PACK_ORDER):
+        npad = (int(counts[h, ti]) + 63) // 64 * 64
+        for si, nbytes in enumerate([npad * O.row_bytes(bits), npad * O.meta_bytes(bits)] * 2):
+            got = arena[int(seg_off[h, ti, si]):int(seg_off[h, ti, si]) + nbytes]
+            want = child["arena"][int(child["seg_off"][0, ti, si]):int(child["seg_off"][0, ti, si]) + nbytes]
+            assert np.array_equal(got, want), f"generation bytes differ in tier {bits}, segment {si}"
+    for i in range(n_new, n_new + 9):
+        b.rdkv_cache_append(cache, kd[i], vd[i])
+        O.append_tokens(ref, kn[i, :, h:h + 1].float().numpy(), vn[i, :, h:h + 1].float().numpy())
+    out, lse = b.rdkv_decode_attn(cache, inp["q"])
+    torch.cuda.synchronize()
+    ref_out, ref_lse = O.decode(ref, inp["q"][:, h * g:(h + 1) * g].float().cpu().numpy())
+    _check_decode(out[:, h * g:(h + 1) * g], lse[:, h * g:(h + 1) * g], ref_out, ref_lse)
+    cache.free()

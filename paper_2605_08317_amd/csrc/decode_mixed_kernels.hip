@@ -33,7 +33,7 @@ struct LdsPlan {
     qpre = 0;
     qraw = qpre + n_steps * hs * 32;
     wtab = qraw + n_qsteps * hs * 32;
-    wtab_wave = 2 * n_qsteps * hs * 64;
+    wtab_wave = (2 * n_qsteps + 1) * hs * 64;   // one entry of padding: the step loop reads one entry ahead
     const int tables = wtab + kWaves * wtab_wave;
     const int merge = kWaves * 4 * hs * 2 * 4 + 2 * kWaves * g * kHeadDim * 4;
     total = tables > merge ? tables : merge;
@@ -256,15 +256,33 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
       const uint8_t* wt8 = wt - t16 * (HS * 64);
       const uint8_t* wt4 = wt + ((t8 - t16) - 2 * t8) * (HS * 64);
       const uint8_t* wt2 = wt + ((t8 - t16) + 2 * (t4 - t8) - 4 * t4) * (HS * 64);
+      // The quantized steps of a row (8-, 4-, then 2-bit words) are consecutive entries of the table.  With one
+      // head set every step asks for the next entry before its own products, so that they cover the LDS latency
+      // (the entry after the last step is padding); with two head sets those registers would spill.
+      constexpr bool kAhead = HS == 1;
+      uint4 bq[HS];
+      if constexpr (kAhead) {
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) bq[hs] = *reinterpret_cast<const uint4*>(wt + hs * 64);
+      }
       auto qstep = [&](const Pack4& a, const uint8_t* o) __attribute__((always_inline)) {
+        uint4 nx[HS];
 #pragma unroll
         for (int hs = 0; hs < HS; ++hs) {
-          const uint4 b = *reinterpret_cast<const uint4*>(o + hs * 64);
+          if constexpr (kAhead) nx[hs] = *reinterpret_cast<const uint4*>(o + (HS + hs) * 64);
+          else bq[hs] = *reinterpret_cast<const uint4*>(o + hs * 64);
+        }
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) {
           Pack4 bh, bl;
-          bh.u[0] = b.x; bh.u[1] = b.y;
-          bl.u[0] = b.z; bl.u[1] = b.w;
+          bh.u[0] = bq[hs].x; bh.u[1] = bq[hs].y;
+          bl.u[0] = bq[hs].z; bl.u[1] = bq[hs].w;
           aqh[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(a.h, bh.h, aqh[hs], 0, 0, 0);
           aql[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(a.h, bl.h, aql[hs], 0, 0, 0);
+        }
+        if constexpr (kAhead) {
+#pragma unroll
+          for (int hs = 0; hs < HS; ++hs) bq[hs] = nx[hs];
         }
       };
       // one word of each tier; the word index is a compile-time constant (registers cannot be indexed at run time)

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the RDKV hot path on one MI355X.
 
-Workload (BASELINE.json configs[2], "stack128k"): 32 layers of an 8B-shaped model
+Workload ("stack128k", the configuration the headline metric is quoted on): 32 layers of an 8B-shaped model
 (Hq=32, Hkv=8, d=128), one sequence of 131072 tokens, average budget 0.4
 bits/element, synthetic bf16 tensors (see paper_2605_08317_amd/workloads.py).
 
@@ -403,7 +403,7 @@ def main():
     except Exception as e:  # reported, never hidden
         batched = {"error": repr(e)}
 
-    # ---- mixed mode (BASELINE configs[4]): V token-wise, K channel-wise, one 64K-token sequence ---------
+    # ---- mixed mode (the mixed-granularity configuration): V token-wise, K channel-wise, one 64K-token sequence ---------
     mixed = None
     try:
         wm = W.CONFIGS["mixed"]

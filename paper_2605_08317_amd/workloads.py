@@ -37,7 +37,7 @@ class Workload:
 
 
 CONFIGS = {
-    # benchmark configs[0..4]; seed = 1000 * config number + layer
+    # the five benchmark configurations; seed = 1000 * config number + layer
     "tiny": Workload("tiny", 1, 8, 2, 128, (4096,), None, 32, 4, 0.0, 9.5, (2.0,), seed_base=1000),
     "layer8b": Workload("layer8b", 1, 32, 8, 128, (32768,), None, 32, 3, 0.0, 9.5, (1.0,), seed_base=2000),
     "stack128k": Workload("stack128k", 1, 32, 8, 128, (131072,), None, 64, 0, 0.01, 9.5, (0.4,),

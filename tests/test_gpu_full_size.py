@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the BASELINE configs, in the launch configuration bench.py times (one
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times (one
 rdkv_compress and one rdkv_decode_attn call per layer / batch).  The oracle cannot redo a whole 128K-token layer in
 seconds, so it recomputes sampled items (sequence, KV head) one by one from the library's own fp32 weights: their
 bit maps, kept-position lists and packed bytes must match bit for bit, their decode outputs within 2e-3; the rest

@@ -124,7 +124,8 @@ def test_allocate_mixed_is_bit_exact(seq_lens, budgets):
 
 
 def test_mixed_workload_staged_pass_and_fused_compress():
-    """BASELINE config 5 at a shorter context: supplied Pareto token weights, channel weights from the probe."""
+    """The mixed-granularity benchmark configuration at a shorter context: supplied Pareto token weights, channel
+    weights from the probe."""
     b = B()
     wl, inp, dev = _inputs("mixed", seq_lens=(6000,))
     cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs,

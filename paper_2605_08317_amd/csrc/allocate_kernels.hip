@@ -93,7 +93,6 @@ __device__ __forceinline__ bool undecided(double wu, const double (&thr_lo)[kMax
   return u;
 }
 
-constexpr int kMlp = 16;          // independent loads per thread in a streaming pass
 constexpr int kListCap = 6144;    // undecided units kept in LDS (24 KiB)
 constexpr int kBuckets = 8192;    // histogram over the top 13 bits of the positive fp32 pattern (32 KiB)
 constexpr int kBucketShift = 18;
@@ -102,6 +101,32 @@ __device__ __forceinline__ int bucket_of(float w) {
   const uint32_t u = __float_as_uint(w);
   return (w > 0.0f) ? static_cast<int>(min(u, 0x7F7FFFFFu) >> kBucketShift) : 0;   // w <= 0 is never above a threshold
 }
+
+// An item's weights read as aligned 16-byte quads (one workgroup streams half a megabyte three times: with 4-byte
+// loads the passes are bound by the number of load instructions in flight).  Quad q covers units 4 q - a .. 4 q - a + 3,
+// a = how many floats the item's first weight sits past a 16-byte boundary; units outside [0, U) read as 0 and are
+// skipped by the caller.  The first and the last quad are read element by element (their neighbours may lie outside
+// the array).
+struct Quads {
+  const float* w;
+  int a, U, nq;
+  __device__ Quads(const float* w_, int U_) : w(w_), U(U_) {
+    a = static_cast<int>((reinterpret_cast<uintptr_t>(w_) >> 2) & 3);
+    nq = (U_ + a + 3) >> 2;
+  }
+  __device__ __forceinline__ int first_unit(int q) const { return 4 * q - a; }
+  __device__ __forceinline__ void load(int q, float (&v)[4]) const {
+    const int u0 = 4 * q - a;
+    if (q > 0 && q + 1 < nq) {
+      const float4 t = *reinterpret_cast<const float4*>(w + u0);
+      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = (q < nq && u0 + j >= 0 && u0 + j < U) ? w[u0 + j] : 0.0f;
+    }
+  }
+};
+constexpr int kQlp = 8;           // independent quad loads per thread in a streaming pass
 
 // Units with w > thr: at least those in buckets above thr's bucket, at most those plus thr's own bucket.
 // suffix[b] = number of units in buckets >= b (suffix[kBuckets] = 0).
@@ -148,16 +173,21 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   for (int i = threadIdx.x; i <= kBuckets; i += kThreads) s_hist[i] = 0;
   __syncthreads();
   float mx = 0.f;
-  for (int u0 = threadIdx.x; u0 < U; u0 += kMlp * kThreads) {
-    float wv[kMlp];
+  const Quads quads(w, U);
+  for (int q0 = threadIdx.x; q0 < quads.nq; q0 += kQlp * kThreads) {
+    float wv[kQlp][4];
 #pragma unroll
-    for (int j = 0; j < kMlp; ++j) wv[j] = (u0 + j * kThreads < U) ? w[u0 + j * kThreads] : 0.0f;
+    for (int j = 0; j < kQlp; ++j) quads.load(q0 + j * kThreads, wv[j]);
 #pragma unroll
-    for (int j = 0; j < kMlp; ++j)
-      if (u0 + j * kThreads < U) {
-        mx = fmaxf(mx, wv[j]);
-        atomicAdd(&s_hist[bucket_of(wv[j])], 1);
-      }
+    for (int j = 0; j < kQlp; ++j) {
+      const int u0 = quads.first_unit(q0 + j * kThreads);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (u0 + e >= 0 && u0 + e < U) {
+          mx = fmaxf(mx, wv[j][e]);
+          atomicAdd(&s_hist[bucket_of(wv[j][e])], 1);
+        }
+    }
   }
   mx = block_max(mx, sm_max);
   // suffix sums in place: s_hist[b] = units in buckets >= b (each thread owns 8 consecutive buckets)
@@ -226,22 +256,26 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
         if (threadIdx.x == 0) s_count = 0;
         __syncthreads();
         long long sf = 0;
-        for (int u0 = threadIdx.x; u0 < U; u0 += kMlp * kThreads) {
-          float wv[kMlp];
+        for (int q0 = threadIdx.x; q0 < quads.nq; q0 += kQlp * kThreads) {
+          float wv[kQlp][4];
 #pragma unroll
-          for (int j = 0; j < kMlp; ++j) wv[j] = (u0 + j * kThreads < U) ? w[u0 + j * kThreads] : 0.0f;
+          for (int j = 0; j < kQlp; ++j) quads.load(q0 + j * kThreads, wv[j]);
 #pragma unroll
-          for (int j = 0; j < kMlp; ++j)
-            if (u0 + j * kThreads < U) {
-              const double wu = static_cast<double>(wv[j]);
-              s += classify_tier(wu, thr, tiers);                 // this step's exact bit sum
-              if (undecided(wu, t_lo, t_hi)) {
-                const int pos = atomicAdd(&s_count, 1);
-                if (pos < kListCap) s_list[pos] = wv[j];
-              } else {
-                sf += classify_tier(wu, t_hi, tiers);
+          for (int j = 0; j < kQlp; ++j) {
+            const int u0 = quads.first_unit(q0 + j * kThreads);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (u0 + e >= 0 && u0 + e < U) {
+                const double wu = static_cast<double>(wv[j][e]);
+                s += classify_tier(wu, thr, tiers);                 // this step's exact bit sum
+                if (undecided(wu, t_lo, t_hi)) {
+                  const int pos = atomicAdd(&s_count, 1);
+                  if (pos < kListCap) s_list[pos] = wv[j][e];
+                } else {
+                  sf += classify_tier(wu, t_hi, tiers);
+                }
               }
-            }
+          }
         }
         s = block_sum(s, sm_sum);
         s_fixed = block_sum(sf, sm_sum);
@@ -269,17 +303,28 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   double thr[kMaxHull - 1];
 #pragma unroll
   for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? best * r[k] : INFINITY;
-  for (int u0 = threadIdx.x; u0 < U; u0 += kMlp * kThreads) {
-    float wv[kMlp];
+  for (int q0 = threadIdx.x; q0 < quads.nq; q0 += kQlp * kThreads) {
+    float wv[kQlp][4];
 #pragma unroll
-    for (int j = 0; j < kMlp; ++j) wv[j] = (u0 + j * kThreads < U) ? w[u0 + j * kThreads] : 0.0f;
+    for (int j = 0; j < kQlp; ++j) quads.load(q0 + j * kThreads, wv[j]);
 #pragma unroll
-    for (int j = 0; j < kMlp; ++j)
-      if (u0 + j * kThreads < U) {
+    for (int j = 0; j < kQlp; ++j) {
+      const int u0 = quads.first_unit(q0 + j * kThreads);
+      uint32_t packed = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
         int t = tiers[0];
-        if (have) t = classify_tier(static_cast<double>(wv[j]), thr, tiers);
-        bits[u0 + j * kThreads] = static_cast<uint8_t>(t);
+        if (have) t = classify_tier(static_cast<double>(wv[j][e]), thr, tiers);
+        packed |= static_cast<uint32_t>(t) << (8 * e);
       }
+      if (u0 >= 0 && u0 + 3 < U && (reinterpret_cast<uintptr_t>(bits + u0) & 3) == 0) {
+        *reinterpret_cast<uint32_t*>(bits + u0) = packed;          // four units' bytes at once
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (u0 + e >= 0 && u0 + e < U) bits[u0 + e] = static_cast<uint8_t>(packed >> (8 * e));
+      }
+    }
   }
 }
 

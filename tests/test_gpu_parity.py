@@ -181,6 +181,7 @@ def test_mixed_tier_decode(name, kw, probs):
     ((4096, 777, 12000), (0.4, 1.0, 4.0), "v"),
     ((3000, 3000), (8.0, 15.9), "bennett"),
     ((64, 2000), (0.0, 16.0), "v"),
+    ((1, 2, 3, 5, 7, 9, 130), (4.0, 4.0, 2.0, 8.0, 1.0, 3.0, 2.0), "v"),   # items shorter than, and askew to, a 16-byte quad
 ])
 def test_allocate_is_bit_exact(seq_lens, budgets, eps):
     b = B()

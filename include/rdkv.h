@@ -156,7 +156,8 @@ rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const floa
  * channels of the row).  Channel-wise mode (Sec. 3.2 Stage 3, App. B): bits_tok is the V
  * map and decides which tokens are retained; the K rows of the retained tokens are stored
  * channel by channel at bits_ch, channels sorted by bit-width, one scale and offset per
- * channel and per 32 consecutive retained tokens of a tier segment; a channel at 0 bits is
+ * channel and per 32 consecutive retained tokens of a tier segment (per channel over all
+ * retained tokens of the item when cfg->k_scale_per_channel is set); a channel at 0 bits is
  * dropped (it contributes nothing to q.k), a channel at 16 bits keeps its bf16 values.
  */
 rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V,
@@ -168,10 +169,11 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V,
                           const void* Q_obs, void* stream, rdkv_cache** out);
 
 /*
- * One decode step over the packed cache (Sec. 3.3, Eq. 7 without the new-token
- * zone): for every sequence and query head, softmax(q K_hat^T / sqrt d) V_hat
- * over the retained tokens, dequantization fused into the attention kernel (in
- * channel-wise mode the per-channel scales are folded into the query, App. B).
+ * One decode step over the packed cache (Sec. 3.3, Eq. 7): for every sequence
+ * and query head, softmax(q K_hat^T / sqrt d) V_hat over the retained tokens, the
+ * tokens appended since (rdkv_cache_append) and the appended tokens compressed
+ * later (rdkv_cache_rebudget_tail), dequantization fused into the attention kernel
+ * (in channel-wise mode the per-channel scales are folded into the query, App. B).
  *   q    DEVICE bf16 [batch][hq][d]
  *   out  DEVICE fp32 [batch][hq][d]
  *   lse  DEVICE fp32 [batch][hq] or NULL: natural-log sum of exp of the logits

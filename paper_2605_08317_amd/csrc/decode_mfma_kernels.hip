@@ -60,7 +60,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   // so a wavefront always has its next tile in flight.  An 8-bit tile is 18 KiB: there the K and V codes take turns
   // in one register set (the other wavefronts of the SIMD cover the wait) and the kernel stays within 128 registers.
   constexpr bool kShare = TIER == 8;
-  constexpr int kDepth = TIER == 2 ? 2 : 1;   // a 2-bit tile is only 6 KiB: two per wavefront in flight
+  constexpr int kDepth = (TIER == 2 && HS == 1) ? 2 : 1;   // a 2-bit tile is only 6 KiB: two per wavefront in flight
   struct Regs {
     uint4 k[TIER], v[kShare ? 1 : TIER], kmeta, vmeta;
   };

@@ -114,3 +114,19 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert p.returncode != 0 and "one GPU" in p.stderr
+
+
+def test_calibration_and_rebudget_argument_checks(b):
+    null = None
+    cfg = b.Config([100], 8, 2)
+    assert b.lib.rdkv_calibrate_eps(None, null, null, null, null, null) == 1           # no config
+    assert b.lib.rdkv_calibrate_eps(cfg.ref(), null, null, null, null, null) == 1      # null K / V / outputs
+    assert b.lib.rdkv_calibrate_eps(b.Config([100], 8, 2, head_dim=64).ref(), null, null, null, null, null) == 2
+    assert b.lib.rdkv_calibrate_eps(b.Config([100], 8, 2, k_mode=7).ref(), null, null, null, null, null) == 1
+    assert b.lib.rdkv_cache_rebudget_tail(None, cfg.ref(), null, null) == 1            # no cache
+    assert b.lib.rdkv_cache_generations(None) == 0
+    assert b.lib.rdkv_cache_generation(None, 0) is None
+    assert b.lib.rdkv_cache_tail_len(None) == 0
+    assert b.lib.rdkv_cache_reserve_tail(None, 16, null) == 1
+    assert b.lib.rdkv_cache_append(None, null, null, null) == 1
+    assert "null" in b.lib.rdkv_last_error().decode() or b.lib.rdkv_last_error().decode() != ""

@@ -32,17 +32,20 @@ def _seg_sizes_tokenwise(counts):
     return sizes
 
 
-def _seg_sizes_mixed(counts, bits_ch):
+def _seg_sizes_mixed(counts, bits_ch, per_channel_scale=False):
     sl = O.channel_slots(bits_ch)
     sizes = []
     for ti, b in enumerate(O.PACK_ORDER):
         nt = (int(counts[ti]) + 63) // 64
-        sizes.append([nt * O.k_tile_bytes_mixed(sl), nt * O.k_meta_bytes_mixed(sl),
+        k_meta = nt * O.k_meta_bytes_mixed(sl)
+        if per_channel_scale:                      # one record per non-empty tier segment: half a tile's metadata
+            k_meta = O.k_meta_bytes_mixed(sl) // 2 if nt else 0
+        sizes.append([nt * O.k_tile_bytes_mixed(sl), k_meta,
                       nt * (16384 if b == 16 else 1024 * b), 0 if b == 16 else nt * 1024])
     return sizes
 
 
-def _check_sampled_items(b, wl, inp, cache, out, lse, w_tok, samples, mixed=False, w_ch=None):
+def _check_sampled_items(b, wl, inp, cache, out, lse, w_tok, samples, mixed=False, w_ch=None, per_channel_scale=False):
     hkv, d, g = wl.hkv, wl.d, wl.hq // wl.hkv
     seq_lens = inp["seq_lens"]
     counts = cache.export(b.RDKV_EXPORT_COUNTS, np.int32).reshape(-1, 4)
@@ -73,8 +76,8 @@ def _check_sampled_items(b, wl, inp, cache, out, lse, w_tok, samples, mixed=Fals
         if mixed:
             bt, bc = O.allocate_mixed(wh, w_ch[item], np.float32(inp["budgets"][s]))
             np.testing.assert_array_equal(bits_ch_all[item], bc)
-            ref = O.build_cache_mixed([Kh], [Vh], [bt[None]], [bc[None]])
-            sizes = _seg_sizes_mixed(counts[item], bc)
+            ref = O.build_cache_mixed([Kh], [Vh], [bt[None]], [bc[None]], k_per_channel_scale=per_channel_scale)
+            sizes = _seg_sizes_mixed(counts[item], bc, per_channel_scale)
         else:
             bt = O.mckp_bisect(wh, np.float32(inp["budgets"][s]))
             ref = O.build_cache_tokenwise([Kh], [Vh], [bt[None]])
@@ -115,20 +118,21 @@ def test_tokenwise_configs_at_full_size(name, layer, samples):
     cache.free()
 
 
-def test_mixed_config_at_full_size():
+@pytest.mark.parametrize("per_channel_scale", [False, True])
+def test_mixed_config_at_full_size(per_channel_scale):
     b = B()
     wl = W.CONFIGS["mixed"]
-    print("[case] full-size mixed", flush=True)
+    print(f"[case] full-size mixed, one K scale per channel: {per_channel_scale}", flush=True)
     inp = W.make_inputs(wl, device="cuda")
     cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs,
-                   k_mode=b.RDKV_K_CHANNELWISE)
+                   k_mode=b.RDKV_K_CHANNELWISE, k_scale_per_channel=int(per_channel_scale))
     _, w_ch = b.rdkv_weights(cfg, inp["K"], inp["Q_obs"], want_channel=True)
     bits_tok, bits_ch = b.rdkv_allocate(cfg, inp["w_tok"], w_ch)
     cache = b.rdkv_pack(cfg, inp["K"], inp["V"], bits_tok, bits_ch)
     out, lse = b.rdkv_decode_attn(cache, inp["q"])
     torch.cuda.synchronize()
     _check_sampled_items(b, wl, inp, cache, out, lse, inp["w_tok"], [(0, 2), (0, 7)], mixed=True,
-                         w_ch=w_ch.cpu().numpy().reshape(-1, wl.d))
+                         w_ch=w_ch.cpu().numpy().reshape(-1, wl.d), per_channel_scale=per_channel_scale)
     st = cache.stats()
     print(f"[mixed full] token rows(16,8,4,2)={st['rows']} evicted={st['evicted']} stored={st['stored_bytes']} "
           f"dense={st['dense_bytes']}", flush=True)

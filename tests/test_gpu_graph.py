@@ -75,3 +75,26 @@ def test_graph_replay_bf16_path():
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(out_g, out_e) and torch.equal(lse_g, lse_e), f"replay {i} differs"
+
+
+def test_graph_recaptured_after_rebudget():
+    """Re-budgeting replaces the decode schedule: a graph captured afterwards must replay the new schedule (prompt
+    zones, the absorbed generation and the tokens appended since)."""
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(1500,))
+    rng = np.random.default_rng(33)
+    bits = [rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(wl.hkv, T), p=[.4, .25, .2, .15, .0])
+            for T in inp["seq_lens"]]
+    cache, _ = _pack_both(b, wl, inp, dev, bits)
+    other, _ = _pack_both(b, wl, inp, dev, [np.full_like(bits[0], 2)])
+    b.rdkv_cache_reserve_tail(cache, 128)
+    kn = torch.randn((100, 1, wl.hkv, 128), device="cuda").to(torch.bfloat16)
+    for i in range(96):
+        b.rdkv_cache_append(cache, kn[i], kn[99 - i])
+    Q = torch.randn((1, wl.hq, 32, 128), device="cuda").to(torch.bfloat16)
+    b.rdkv_cache_rebudget_tail(cache, b.Config([96], wl.hq, wl.hkv, budget_bits=[3.0], s_obs=32), Q)
+    for i in range(96, 100):
+        b.rdkv_cache_append(cache, kn[i], kn[99 - i])
+    _replay_equals_eager(b, cache, dev["q"], other)
+    cache.free()
+    other.free()

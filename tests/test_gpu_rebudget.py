@@ -47,6 +47,7 @@ def _rebudget_both(b, cache, ref, wl, batch, k_rows, n_tail, budgets, s_obs, rng
 @pytest.mark.parametrize("name,kw,n_new,budgets", [
     ("tiny", {"seq_lens": (900,)}, 200, [3.0]),
     ("tiny", {"seq_lens": (500,)}, 64, [16.0]),                  # everything kept verbatim
+    ("tiny", {"seq_lens": (400,)}, 64, [0.0]),                   # nothing kept: an empty generation
     ("batch70b", {"batch": 3, "len_range": (100, 700)}, 300, [0.5, 2.0, 6.0]),   # 8 query heads per KV head
 ])
 def test_rebudget_matches_oracle(name, kw, n_new, budgets):

@@ -1056,10 +1056,8 @@ rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, cons
   rdkv_cache* child = nullptr;
   rdkv_status s = rdkv_compress(cfg, k_rows, v_rows, Q_obs, stream, &child);   // synchronises the stream
   if (s != RDKV_OK) return s;
-  {  // rows not yet appended must read as zeros again
-    const int64_t tail_tiles = (c->tail_cap + kTile64 - 1) / kTile64;
-    RDKV_HIP(hipMemsetAsync(c->d_tail, 0, 2 * c->n_items * tail_tiles * kTile64 * kHeadDim * 2, st));
-  }
+  // The tail's tiles keep the rows just compressed: rows at or past tail_len are masked out of the softmax (their
+  // values are finite, so a zero probability times a stale V row adds nothing), and later appends overwrite them.
   c->absorbed.push_back(child);
   c->tail_len = 0;
   s = rebuild_schedule(c, st);

@@ -130,3 +130,23 @@ def test_calibration_and_rebudget_argument_checks(b):
     assert b.lib.rdkv_cache_reserve_tail(None, 16, null) == 1
     assert b.lib.rdkv_cache_append(None, null, null, null) == 1
     assert "null" in b.lib.rdkv_last_error().decode() or b.lib.rdkv_last_error().decode() != ""
+
+
+def test_ctypes_structs_match_the_c_header(b, tmp_path):
+    """The binding's ctypes mirror of rdkv_config / rdkv_stats against the header compiled as plain C."""
+    import subprocess
+    cfg_fields = [f[0] for f in b.rdkv_config._fields_]
+    st_fields = [f[0] for f in b.rdkv_stats._fields_]
+    src = tmp_path / "layout.c"
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "rdkv.h"', 'int main(void) {',
+             '  printf("%zu %zu\\n", sizeof(rdkv_config), sizeof(rdkv_stats));']
+    lines += [f'  printf("%zu\\n", offsetof(rdkv_config, {f}));' for f in cfg_fields]
+    lines += [f'  printf("%zu\\n", offsetof(rdkv_stats, {f}));' for f in st_fields]
+    lines += ['  return 0;', '}']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(out[0]), int(out[1])] == [ctypes.sizeof(b.rdkv_config), ctypes.sizeof(b.rdkv_stats)]
+    want = [getattr(b.rdkv_config, f).offset for f in cfg_fields] + [getattr(b.rdkv_stats, f).offset for f in st_fields]
+    assert [int(x) for x in out[2:]] == want

@@ -198,6 +198,21 @@ rdkv_status rdkv_decode_attn_bf16(const void* K, const void* V, const int32_t* s
                                   size_t workspace_bytes, void* stream);
 
 /*
+ * rdkv_decode_attn_bf16 for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same step with the same kernels and arguments, minus the workspace.
+ * The split partials live in a device array built into the library (rdkv_decode_bf16_noalloc_max_bytes() = 8 MiB on
+ * every GPU the library runs on, held until the process ends).  The call allocates nothing.  A batch whose
+ * rdkv_decode_bf16_workspace_bytes() exceeds that size is rejected with RDKV_ERR_UNSUPPORTED before anything is
+ * launched.  All calls on one GPU share the one array: calls that overlap in time on the same GPU (different
+ * streams, or threads) race on it -- issue them on one stream or serialise them.  Every partial slot the merge
+ * reads is written by the split kernel of the same call, so the array needs no clearing between calls.
+ */
+size_t rdkv_decode_bf16_noalloc_max_bytes(void);
+rdkv_status rdkv_decode_attn_bf16_noalloc(const void* K, const void* V, const int32_t* seq_lens, int32_t batch,
+                                          int32_t hq, int32_t hkv, int32_t head_dim, const void* q, float* out,
+                                          float* lse, void* stream);
+
+/*
  * Measurement aid (benchmarks).  While enabled, the calls above bracket their
  * main kernel with HIP events on the call's own stream: the split-K decode
  * kernel of rdkv_decode_attn / rdkv_decode_attn_bf16, the two MFMA passes of

@@ -24,6 +24,7 @@ STATUS_NAMES = {0: "RDKV_OK", 1: "RDKV_ERR_INVALID_ARG", 2: "RDKV_ERR_SHAPE", 3:
 EXPORTED_SYMBOLS = [
     "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_pack",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
+    "rdkv_decode_bf16_noalloc_max_bytes", "rdkv_decode_attn_bf16_noalloc",
     "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_calibrate_eps",
     "rdkv_cache_rebudget_tail", "rdkv_cache_generations", "rdkv_cache_generation",
     "rdkv_cache_stats", "rdkv_cache_export_bytes", "rdkv_cache_export", "rdkv_cache_free",
@@ -82,6 +83,9 @@ def _load():
     lib.rdkv_decode_bf16_workspace_bytes.argtypes = [ctypes.POINTER(i32), i32, i32, i32, i32]
     lib.rdkv_decode_bf16_workspace_bytes.restype = sz
     lib.rdkv_decode_attn_bf16.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.rdkv_decode_bf16_noalloc_max_bytes.argtypes = []
+    lib.rdkv_decode_bf16_noalloc_max_bytes.restype = sz
+    lib.rdkv_decode_attn_bf16_noalloc.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, i32, i32, vp, vp, vp, vp]
     lib.rdkv_cache_reserve_tail.argtypes = [vp, i32, vp]
     lib.rdkv_cache_append.argtypes = [vp, vp, vp, vp]
     lib.rdkv_cache_tail_len.argtypes = [vp]
@@ -310,6 +314,14 @@ def rdkv_decode_attn_bf16(K, V, seq_lens, hq, hkv, q, head_dim=128, out=None, ls
         lse = torch.empty((len(seq_lens), hq), dtype=torch.float32, device=q.device)
     _check(lib.rdkv_decode_attn_bf16(_ptr(K), _ptr(V), arr, len(seq_lens), hq, hkv, head_dim, _ptr(q), _ptr(out),
                                      _ptr(lse), _ptr(workspace), workspace.numel(), _stream()))
+    return out, lse
+
+
+def rdkv_decode_attn_bf16_noalloc(K, V, seq_lens, hq, hkv, q, out, lse=None, head_dim=128):
+    """The caller passes every buffer; nothing is allocated here or in the library."""
+    arr = (ctypes.c_int32 * len(seq_lens))(*[int(x) for x in seq_lens])
+    _check(lib.rdkv_decode_attn_bf16_noalloc(_ptr(K), _ptr(V), arr, len(seq_lens), hq, hkv, head_dim, _ptr(q),
+                                             _ptr(out), _ptr(lse), _stream()))
     return out, lse
 
 

@@ -1127,6 +1127,59 @@ rdkv_status rdkv_decode_attn_bf16(const void* K, const void* V, const int32_t* s
   return RDKV_OK;
 }
 
+}  // extern "C"
+
+// ---- the bf16 decode step for callers that cannot allocate ---------------------------------------------------------
+// Its split partials live in a file-scope device array instead of a caller workspace.  In host code the array's name
+// is only a stand-in for the symbol: the device address is looked up once per device and used from then on.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(8) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+rdkv_status static_scratch(void** out) {
+  int dev = -1;
+  RDKV_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(RDKV_ERR_UNSUPPORTED, "device index %d out of range", dev);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    RDKV_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(RDKV_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return RDKV_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t rdkv_decode_bf16_noalloc_max_bytes(void) { return kStaticScratchBytes; }
+
+rdkv_status rdkv_decode_attn_bf16_noalloc(const void* K, const void* V, const int32_t* seq_lens, int32_t batch,
+                                          int32_t hq, int32_t hkv, int32_t head_dim, const void* q, float* out,
+                                          float* lse, void* stream) {
+  rdkv_status s = check_shape(batch, hq, hkv, head_dim, seq_lens);
+  if (s != RDKV_OK) return s;
+  if (batch == 0) return RDKV_OK;
+  const size_t need = rdkv_decode_bf16_workspace_bytes(seq_lens, batch, hq, hkv, head_dim);
+  if (need > kStaticScratchBytes)
+    return fail(RDKV_ERR_UNSUPPORTED,
+                "this batch needs %zu bytes of split partials, more than the %zu bytes of the built-in scratch area; "
+                "use rdkv_decode_attn_bf16 with a workspace",
+                need, kStaticScratchBytes);
+  void* ws = nullptr;
+  s = static_scratch(&ws);
+  if (s != RDKV_OK) return s;
+  // every partial slot the merge reads is written by the split kernel of the same call: nothing to clear
+  return rdkv_decode_attn_bf16(K, V, seq_lens, batch, hq, hkv, head_dim, q, out, lse, ws, kStaticScratchBytes, stream);
+}
+
 rdkv_status rdkv_cache_stats(const rdkv_cache* c, rdkv_stats* out) {
   if (!c || !out) return fail(RDKV_ERR_INVALID_ARG, "cache and out must not be null");
   std::memset(out, 0, sizeof(*out));

@@ -288,6 +288,17 @@ const rdkv_cache* rdkv_cache_generation(const rdkv_cache* cache, int32_t index);
 rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void* V, double* eps_k, double* eps_v,
                                void* stream);
 
+/*
+ * Shape of a channel-wise K row (Sec. 3.2 Stage 3; App. B: channels sorted into bit-width segments): the number of
+ * 32-bit words a retained token's K row takes under the channel bit map bits_ch (HOST uint8 [128], values out of
+ * {0,2,4,8,16}) -- every bit-width segment padded to whole words, the 16-bit one to whole word pairs, the row to an
+ * even count; a K tile of 64 tokens takes 256 bytes per word.  Host computation, nothing is launched.  Returns -1 for
+ * a null pointer or a value that is no tier.  rdkv_k_row_words_max(): the longest row the decode kernel holds (every
+ * valid map fits).
+ */
+int32_t rdkv_k_row_words(const uint8_t* bits_ch);
+int32_t rdkv_k_row_words_max(void);
+
 /* Introspection (tests, benchmarks). */
 rdkv_status rdkv_cache_stats(const rdkv_cache* cache, rdkv_stats* out);
 /* Size in bytes of an export; 0 for an unknown `what`. */

@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = [
     "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_calibrate_eps",
     "rdkv_cache_rebudget_tail", "rdkv_cache_generations", "rdkv_cache_generation",
     "rdkv_cache_stats", "rdkv_cache_export_bytes", "rdkv_cache_export", "rdkv_cache_free",
-    "rdkv_kernel_timing_enable", "rdkv_kernel_timing_read",
+    "rdkv_kernel_timing_enable", "rdkv_kernel_timing_read", "rdkv_k_row_words", "rdkv_k_row_words_max",
 ]
 (RDKV_TIME_DECODE_TIERED, RDKV_TIME_DECODE_BF16, RDKV_TIME_WEIGHTS, RDKV_TIME_ALLOCATE, RDKV_TIME_PACK,
  RDKV_TIME_CALIBRATE) = range(6)
@@ -102,6 +102,10 @@ def _load():
     lib.rdkv_cache_export.argtypes = [vp, i32, vp, sz]
     lib.rdkv_cache_free.argtypes = [vp]
     lib.rdkv_cache_free.restype = None
+    lib.rdkv_k_row_words.argtypes = [vp]
+    lib.rdkv_k_row_words.restype = i32
+    lib.rdkv_k_row_words_max.argtypes = []
+    lib.rdkv_k_row_words_max.restype = i32
     lib.rdkv_kernel_timing_enable.argtypes = [i32]
     lib.rdkv_kernel_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
     return lib

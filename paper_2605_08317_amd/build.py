@@ -7,7 +7,19 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librdkv.so")
-SOURCES = ["rdkv_api.hip", "decode_kernels.hip", "decode_mfma_kernels.hip", "decode_mixed_kernels.hip", "pack_kernels.hip", "allocate_kernels.hip", "weights_kernels.hip", "calib_kernels.hip"]
+# (source, object, extra flags); the mixed-mode decode kernels are compiled once per head-set count so that their
+# many instantiations build in parallel; the slowest objects come first
+SOURCES = [
+    ("decode_mixed_kernels.hip", "decode_mixed_hs2.o", ["-DRDKV_MIXED_HS=2"]),
+    ("decode_mixed_kernels.hip", "decode_mixed_hs1.o", ["-DRDKV_MIXED_HS=1"]),
+    ("decode_mfma_kernels.hip", "decode_mfma_kernels.o", []),
+    ("rdkv_api.hip", "rdkv_api.o", []),
+    ("decode_kernels.hip", "decode_kernels.o", []),
+    ("pack_kernels.hip", "pack_kernels.o", []),
+    ("allocate_kernels.hip", "allocate_kernels.o", []),
+    ("weights_kernels.hip", "weights_kernels.o", []),
+    ("calib_kernels.hip", "calib_kernels.o", []),
+]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -22,16 +34,16 @@ FLAGS = [
 ]
 
 
-def build(verbose=True, jobs=4):
+def build(verbose=True, jobs=6):
     objs, procs = [], []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
-    for src in SOURCES:
-        obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
+    for src, obj_name, extra in SOURCES:
+        obj = os.path.join(HERE, "_build", obj_name)
         objs.append(obj)
-        cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj] + FLAGS
+        cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj] + FLAGS + extra
         if verbose:
             print(" ".join(cmd), flush=True)
-        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        procs.append((obj_name, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         if len(procs) >= jobs:
             _drain(procs)
     _drain(procs)

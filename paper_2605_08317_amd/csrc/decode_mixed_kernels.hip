@@ -15,7 +15,14 @@
 //
 // V side, softmax and the end-of-chunk merge are the stages shared with the token-wise kernel; 16-bit V rows are
 // 64-token tiles of bf16 with the same lane assignment, multiplied by the probabilities as two bf16 terms.
+//
+// This file is compiled once per head-set count (-DRDKV_MIXED_HS=1: up to 4 query heads per KV head, =2: 8), each
+// into an object of its own, so that the many instantiations build in parallel.
 #include "decode_tile_common.h"
+
+#ifndef RDKV_MIXED_HS
+#error "compile with -DRDKV_MIXED_HS=1 or -DRDKV_MIXED_HS=2"
+#endif
 
 namespace rdkv {
 
@@ -349,7 +356,7 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
 #define RDKV_K_TIER(BODY_, FIRST_, END_)                                                                      \
   switch (FIRST_) {                                                                                           \
     RDKV_K_CASE16(BODY_, END_, 0) RDKV_K_CASE16(BODY_, END_, 16) RDKV_K_CASE16(BODY_, END_, 32)               \
-    RDKV_K_CASE16(BODY_, END_, 48)                                                                            \
+    RDKV_K_CASE16(BODY_, END_, 48) RDKV_K_CASE4(BODY_, END_, 64)                                              \
     default: break;                                                                                           \
   }
       RDKV_K_TIER(body16, 0, t16)
@@ -466,22 +473,24 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
 
 }  // namespace
 
-hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                               int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                               float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st) {
+#define RDKV_MIXED_NAME2(a_, b_) a_##b_
+#define RDKV_MIXED_NAME(a_, b_) RDKV_MIXED_NAME2(a_, b_)
+hipError_t RDKV_MIXED_NAME(launch_decode_mixed_hs, RDKV_MIXED_HS)(
+    const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int max_words, int max_steps,
+    int max_qsteps, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv, int row_limit, int per_unit,
+    hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
-  const int hs = hq / hkv > 4 ? 2 : 1;
-#define RDKV_MIXED_LAUNCH(NW_, HS_)                                                                           \
-  return launch_one<NW_, HS_>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, part_acc, part_ml, hq, \
-                              hkv, row_limit, per_unit, st)
-  if (hs == 1) {
-    if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 1);
-    if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 1);
-    RDKV_MIXED_LAUNCH(64, 1);
-  }
-  if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 2);
-  if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 2);
-  RDKV_MIXED_LAUNCH(64, 2);
+#define RDKV_MIXED_LAUNCH(NW_)                                                                                \
+  return launch_one<NW_, RDKV_MIXED_HS>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, part_acc, \
+                                        part_ml, hq, hkv, row_limit, per_unit, st)
+  // kMaxKRowWords = 68 is the longest row a channel bit map can give (125 channels at 16 bits and one each at 8, 4
+  // and 2 bits: 64 + 1 + 1 + 1 words, padded to an even count); the host refuses anything longer
+  static_assert(kMaxKRowWords == 68, "the widest instantiation below must hold the longest K row");
+  if (max_words > kMaxKRowWords) return hipErrorInvalidValue;
+  if (max_words <= 16) RDKV_MIXED_LAUNCH(16);
+  if (max_words <= 32) RDKV_MIXED_LAUNCH(32);
+  if (max_words <= 64) RDKV_MIXED_LAUNCH(64);
+  RDKV_MIXED_LAUNCH(68);
 #undef RDKV_MIXED_LAUNCH
 }
 

@@ -627,6 +627,9 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
                              ch, h_bits_ch[i * kHeadDim + ch]));
         c->items_k[i] = make_item_k(&h_bits_ch[i * kHeadDim]);
         const ItemK& ik = c->items_k[i];
+        if (ik.n_words_padded > kMaxKRowWords)
+          return bail(fail(RDKV_ERR_INTERNAL, "K row of item %lld has %d words, more than the decode kernel holds (%d)",
+                           static_cast<long long>(i), ik.n_words_padded, kMaxKRowWords));
         c->max_k_words = std::max<int32_t>(c->max_k_words, ik.n_words_padded);
         c->max_k_steps = std::max<int32_t>(c->max_k_steps, ik.n_steps16 + ik.n_qsteps);
         c->max_k_qsteps = std::max<int32_t>(c->max_k_qsteps, ik.n_qsteps);
@@ -1212,6 +1215,15 @@ rdkv_status rdkv_cache_stats(const rdkv_cache* c, rdkv_stats* out) {
   }
   return RDKV_OK;
 }
+
+int32_t rdkv_k_row_words(const uint8_t* bits_ch) {
+  if (!bits_ch) return -1;
+  for (int ch = 0; ch < kHeadDim; ++ch)
+    if (!valid_tier(bits_ch[ch])) return -1;
+  return make_item_k(bits_ch).n_words_padded;
+}
+
+int32_t rdkv_k_row_words_max(void) { return kMaxKRowWords; }
 
 size_t rdkv_cache_export_bytes(const rdkv_cache* c, int what) {
   if (!c) return 0;

@@ -43,6 +43,7 @@ constexpr int kTierTail = 17;               // Chunk::tier of a chunk of appende
 // 2 slots, an 8-bit word 4, a 4-bit word 8, a 2-bit word 16); every tier is padded to whole words, the 16-bit tier
 // to whole word pairs, the row to an even number of words.  A step is 4 consecutive slots.
 constexpr int kMaxSlots = 160;   // 128 channels + up to 3 + 3 + 7 + 15 padding slots
+constexpr int kMaxKRowWords = 68;  // longest row: 125 channels at 16 bits, one each at 8, 4, 2 -> 64 + 1 + 1 + 1, evened
 struct ItemK {
   int32_t kt_bytes;              // K tile (64 tokens) data bytes = 256 * n_words_padded
   int32_t km_bytes;              // K tile metadata bytes = 32 * n_qsteps (2 token groups x 16 bytes per quantized step)
@@ -84,9 +85,20 @@ hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_m
 // row_limit: appended tokens that exist so far (chunks of tier kTierTail end there)
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
                                float* part_acc, float* part_ml, int hq, int hkv, int row_limit, hipStream_t st);
-hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                               int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                               float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st);
+// one object per head-set count (hs1: up to 4 query heads per KV head, hs2: 8)
+hipError_t launch_decode_mixed_hs1(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
+                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
+                                   float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st);
+hipError_t launch_decode_mixed_hs2(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
+                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
+                                   float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st);
+inline hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
+                                      int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
+                                      float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st) {
+  return (hq / hkv > 4 ? launch_decode_mixed_hs2 : launch_decode_mixed_hs1)(
+      chunks, n_chunks, arena, items_k, max_words, max_steps, max_qsteps, q, part_acc, part_ml, hq, hkv, row_limit,
+      per_unit, st);
+}
 
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);

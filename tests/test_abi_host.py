@@ -150,3 +150,39 @@ def test_ctypes_structs_match_the_c_header(b, tmp_path):
     assert [int(out[0]), int(out[1])] == [ctypes.sizeof(b.rdkv_config), ctypes.sizeof(b.rdkv_stats)]
     want = [getattr(b.rdkv_config, f).offset for f in cfg_fields] + [getattr(b.rdkv_stats, f).offset for f in st_fields]
     assert [int(x) for x in out[2:]] == want
+
+
+def test_every_channel_bit_map_fits_the_widest_k_row_kernel(b):
+    """A channel-wise K row is longest with 125 channels at 16 bits and one each at 8, 4 and 2 (every segment pays its
+    padding): 64 + 1 + 1 + 1 words, evened to 68.  The decode kernel's widest instantiation must hold it; the
+    library's own row-shape function is swept over every combination of tier counts."""
+    import numpy as np
+    widest = b.lib.rdkv_k_row_words_max()
+
+    def words(n16, n8, n4, n2):
+        m = np.zeros(128, np.uint8)
+        m[:n16] = 16
+        m[n16:n16 + n8] = 8
+        m[n16 + n8:n16 + n8 + n4] = 4
+        m[n16 + n8 + n4:n16 + n8 + n4 + n2] = 2
+        return b.lib.rdkv_k_row_words(m.ctypes.data_as(ctypes.c_void_p))
+
+    # hand-computed shapes: ceil4(n16)/2 + ceil(n8/4) + ceil(n4/8) + ceil(n2/16), evened
+    assert words(128, 0, 0, 0) == 64
+    assert words(125, 1, 1, 1) == 68
+    assert words(126, 2, 0, 0) == 66
+    assert words(0, 0, 0, 128) == 8
+    assert words(0, 0, 0, 0) == 0
+    assert words(1, 0, 0, 0) == 2
+    assert words(0, 37, 0, 91) == 10 + 6
+    worst = 0
+    for n16 in range(0, 129):
+        for n8 in range(0, 129 - n16, 1 if n16 > 100 else 7):
+            for n4 in range(0, 129 - n16 - n8, 1 if n16 > 100 else 5):
+                rest = 128 - n16 - n8 - n4
+                for n2 in {rest, max(rest - 1, 0), min(rest, 1)}:
+                    worst = max(worst, words(n16, n8, n4, n2))
+    assert worst == 68 and worst <= widest
+    bad = np.full(128, 3, np.uint8)
+    assert b.lib.rdkv_k_row_words(bad.ctypes.data_as(ctypes.c_void_p)) == -1
+    assert b.lib.rdkv_k_row_words(None) == -1

@@ -207,3 +207,30 @@ def test_per_channel_scale_pack_and_decode(name, kw, p_tok, p_ch):
     ref_out, ref_lse = O.decode(ref, _np(inp["q"]))
     _check_decode(out, lse, ref_out, ref_lse)
     cache.free()
+
+
+@pytest.mark.parametrize("counts", [(125, 1, 1, 1), (126, 2, 0, 0), (121, 3, 2, 2), (124, 0, 4, 0)])
+@pytest.mark.parametrize("name,kw", [("tiny", {"seq_lens": (700,)}), ("batch70b", {"batch": 2, "len_range": (200, 500)})])
+def test_k_rows_longer_than_64_words(name, kw, counts):
+    """Channel maps whose sorted-channel row exceeds 64 words (the 16-bit segment nearly full and every other segment
+    paying its padding: up to 68 words): Stage 3 of Alg. 1 produces them when the K average lies just under 16 bits."""
+    b = B()
+    wl, inp, dev = _inputs(name, **kw)
+    rng = np.random.default_rng(21)
+    n16, n8, n4, n2 = counts
+    bt, _ = _random_maps(rng, inp["seq_lens"], wl.hkv, [.2, .2, .2, .2, .2], [.2, .2, .2, .2, .2])
+    bc = []
+    for _ in inp["seq_lens"]:
+        m = np.zeros((wl.hkv, 128), np.uint8)
+        for h in range(wl.hkv):
+            row = np.array([16] * n16 + [8] * n8 + [4] * n4 + [2] * n2 + [0] * (128 - sum(counts)), np.uint8)
+            m[h] = rng.permutation(row)
+        bc.append(m)
+    print(f"[case] wide K rows {name} {kw} counts={counts}", flush=True)
+    cache, ref = _pack_both_mixed(b, wl, inp, dev, bt, bc)
+    _assert_cache_equal_mixed(b, cache, ref)
+    out, lse = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    ref_out, ref_lse = O.decode(ref, _np(inp["q"]))
+    _check_decode(out, lse, ref_out, ref_lse)
+    cache.free()

@@ -215,7 +215,7 @@ def classify(w, lam, hull_tiers, r):
 
 def argmin_bits(w, lam, tiers, eps):
     """Alg. 2 per-unit step in its printed form: argmin_b w_u eps(b) + lam b
-    (lowest b on ties).  Used to pin `classify`."""
+    (lowest b on ties), fp64.  This is what `mckp_bisect` runs."""
     w64 = np.asarray(w, dtype=np.float32).astype(np.float64)
     tiers = np.asarray(tiers, dtype=np.float64)
     e = np.asarray([np.float64(np.float32(x)) for x in eps])
@@ -239,6 +239,10 @@ def mckp_bisect(w, avg_bits, tiers=TIERS, eps=EPS_V_LLAMA31_8B, rel_tol=np.float
     first feasible iterate within the tolerance band below the budget, and
     otherwise returns the feasible iterate with the smallest multiplier seen.
     Integer comparisons on the summed bits avoid dividing by a zero budget.
+    Every step evaluates the per-unit rule in its printed form, argmin_b w eps(b) +
+    lam b with the lowest b on ties (`argmin_bits`); the convex hull only supplies
+    the shortcuts (highest and lowest useful tier).  `classify` is the equivalent
+    threshold form and is pinned against it separately.
 
     w: float32 [U].  avg_bits: float32 target average bits per unit.
     """
@@ -260,7 +264,7 @@ def mckp_bisect(w, avg_bits, tiers=TIERS, eps=EPS_V_LLAMA31_8B, rel_tol=np.float
         best = None
         for it in range(max_iters):
             lam = (lo + hi) * 0.5
-            cand = classify(w, lam, hull_tiers, r)
+            cand = argmin_bits(w, lam, tiers, eps)        # the per-unit step as Alg. 2 prints it
             S = int(cand.astype(np.int64).sum())
             info["iters"] = it + 1
             if S <= B_int:

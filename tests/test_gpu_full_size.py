@@ -9,7 +9,7 @@ import torch
 
 from oracle import rdkv_oracle as O
 from paper_2605_08317_amd import workloads as W
-from test_gpu_parity import B, _rel_err, DECODE_TOL
+from test_gpu_parity import B, _rel_err, _elementwise_err, DECODE_TOL, WEIGHT_RTOL
 
 pytestmark = pytest.mark.gpu
 
@@ -93,6 +93,7 @@ def _check_sampled_items(b, wl, inp, cache, out, lse, w_tok, samples, mixed=Fals
         gl = lse[s, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)[None]
         err = _rel_err(go, ro)
         worst = max(worst, err)
+        print(f"[sample] decode error {err:.2e}; element-wise with floor {_elementwise_err(go, ro):.2e}", flush=True)
         assert err <= DECODE_TOL
         np.testing.assert_allclose(gl, rl, rtol=1e-4, atol=1e-4)
     print(f"[full size] worst sampled decode error {worst:.2e}", flush=True)
@@ -137,3 +138,27 @@ def test_mixed_config_at_full_size(per_channel_scale):
     print(f"[mixed full] token rows(16,8,4,2)={st['rows']} evicted={st['evicted']} stored={st['stored_bytes']} "
           f"dense={st['dense_bytes']}", flush=True)
     cache.free()
+
+
+@pytest.mark.parametrize("layer,head", [(0, 3), (11, 6)])
+def test_token_weights_of_a_128k_layer_against_the_oracle(layer, head):
+    """Alg. 1 Stage 1 (Eq. 2) at the benchmark's full shape: T = 131072, S_w = 64, g = 4.  The library computes the
+    whole layer; the oracle redoes one sampled KV head (its 256 window rows over all keys) in fp64, pooling included."""
+    b = B()
+    wl = W.CONFIGS["stack128k"]
+    print(f"[case] full-size weights stack128k layer {layer} KV head {head}", flush=True)
+    inp = W.make_inputs(wl, device="cuda", layer=layer)
+    T, g = inp["seq_lens"][0], wl.hq // wl.hkv
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, s_obs=wl.s_obs)
+    w_tok, w_ch = b.rdkv_weights(cfg, inp["K"], inp["Q_obs"], want_channel=True)
+    torch.cuda.synchronize()
+    got = w_tok.view(wl.hkv, T)[head].cpu().numpy().astype(np.float64)
+    Kh = inp["K"].view(wl.hkv, T, wl.d)[head].float().cpu().numpy()[None]
+    Qh = inp["Q_obs"][0, head * g:(head + 1) * g].float().cpu().numpy()
+    ref = O.avg_pool(O.token_weights(Kh, Qh), 5)[0]
+    err = np.abs(got - ref) / (np.abs(ref) + 1e-6 * ref.max())
+    print(f"[weights full size] max rel err {err.max():.3e} at t={int(err.argmax())}, total mass {got.sum():.6f} "
+          f"(oracle {ref.sum():.6f})", flush=True)
+    assert err.max() <= WEIGHT_RTOL
+    ref_c = O.channel_weights(Kh, Qh)[0]
+    np.testing.assert_allclose(w_ch.view(wl.hkv, wl.d)[head].cpu().numpy(), ref_c, rtol=1e-5)

@@ -35,13 +35,24 @@ def _rel_err(out, ref):
     return float((num / den).max())
 
 
+def _elementwise_err(out, ref, floor=1e-3):
+    """max over elements of |o - ref| / max(|ref|, floor * max|ref| of the head): the element-wise relative error,
+    with components below a thousandth of the head's largest one measured against that floor."""
+    den = np.maximum(np.abs(ref), floor * np.abs(ref).max(axis=-1, keepdims=True))
+    return float((np.abs(out - ref) / np.maximum(den, 1e-30)).max())
+
+
 def _check_decode(out, lse, ref_out, ref_lse, tol=DECODE_TOL):
     out, lse = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
     empty = np.isneginf(ref_lse)
     assert np.array_equal(np.isneginf(lse), empty)
     assert not out[empty].any()
     if (~empty).any():
-        assert _rel_err(out[~empty], ref_out[~empty]) <= tol
+        err = _rel_err(out[~empty], ref_out[~empty])
+        # reported beside the gate: the same error element by element (floor 1e-3 of the head's largest component)
+        print(f"[decode] error relative to the head's largest component {err:.2e} (gate {tol:g}); "
+              f"element-wise with floor {_elementwise_err(out[~empty], ref_out[~empty]):.2e}", flush=True)
+        assert err <= tol
         np.testing.assert_allclose(lse[~empty], ref_lse[~empty], rtol=1e-4, atol=1e-4)
 
 
@@ -208,8 +219,11 @@ def test_allocate_is_bit_exact(seq_lens, budgets, eps):
 # ----------------------------------------------------------------------------
 # C1-C3: weights (fp32 on the GPU, bf16 MFMA products are exact; fp64 in the oracle)
 # ----------------------------------------------------------------------------
-WEIGHT_RTOL = 5e-4   # fp32 logits of magnitude <= ~100 in the log2 domain carry ~1e-5 absolute error -> ~1e-5
-                     # relative in each exp; the hardware exp2 adds a few ulp; sums over <= 512 rows
+# |w - w_ref| <= 1e-5 (|w_ref| + 1e-6 max w_ref).  The bf16 x bf16 products are exact in the matrix cores and the 128
+# of a logit are summed in fp32: a logit of magnitude <= ~30 in the log2 domain carries ~1e-6 absolute error, i.e.
+# ~1e-6 relative in its exponential; the hardware exp2 adds an ulp or two; the sums over <= 512 window rows have equal
+# signs.  Observed worst case over all the cases below and the full-size test: 1.1e-6.
+WEIGHT_RTOL = 1e-5
 
 
 @pytest.mark.parametrize("name,kw,pool,causal", [

@@ -258,6 +258,49 @@ def test_threshold_form_equals_printed_argmin_form(eps):
         assert np.array_equal(a[~near_tie], b[~near_tie])
 
 
+def test_exact_ties_take_the_lower_bit_width_in_both_forms():
+    """Alg. 2's per-unit step at an exact tie.  With the dyadic table eps = (1, 1/2, 1/4, 1/8, 0) every quantity is
+    exact in fp64: the hull ratios are r = (4, 8, 32, 64), and at lam = 1 a unit of weight r_k pays the same cost at
+    tiers k-1 and k (w = 4: 4*1 + 0 = 4*1/2 + 2; w = 8: 8/2 + 2 = 8/4 + 4; w = 32: 32/4 + 4 = 32/8 + 8;
+    w = 64: 64/8 + 8 = 0 + 16).  The printed argmin keeps the lower bit-width there, and so must the threshold form
+    (strict '>'); one ulp above the tie both move up."""
+    eps = (1.0, 0.5, 0.25, 0.125, 0.0)
+    hb, r = O.hull_thresholds(O.TIERS, eps)
+    assert hb == [0, 2, 4, 8, 16] and r == [4.0, 8.0, 32.0, 64.0]
+    ties = np.array([4.0, 8.0, 32.0, 64.0], np.float32)
+    above = np.nextafter(ties, np.float32(np.inf))
+    below = np.nextafter(ties, np.float32(0))
+    for lam, scale in ((1.0, 1.0), (0.25, 0.25), (8.0, 8.0)):            # powers of two keep the ties exact
+        for form in (lambda w: O.argmin_bits(w, lam, O.TIERS, eps), lambda w: O.classify(w, lam, hb, r)):
+            assert form(ties * np.float32(scale)).tolist() == [0, 2, 4, 8]
+            assert form(above * np.float32(scale)).tolist() == [2, 4, 8, 16]
+            assert form(below * np.float32(scale)).tolist() == [0, 2, 4, 8]
+    # inside the bisection: weights sitting exactly on the thresholds of the multiplier the search visits.
+    # 12 units, budget 2 bits per unit = 24 bits.  lam runs 32, 16, 8, 4, ...; at lam = 8 the units of weight 32 and
+    # 64 tie between 0 and 2 bits (r_1 lam = 32) resp. 2 and 4 bits (r_2 lam = 64) and must take the lower one.
+    w = np.array([64.0] * 4 + [32.0] * 4 + [1.0] * 4, np.float32)
+    bits, info = O.mckp_bisect(w, np.float32(2.0), O.TIERS, eps, rel_tol=np.float32(0.0), max_iters=3, return_info=True)
+    assert info["lam"] == 8.0 and bits.tolist() == [2] * 4 + [0] * 8
+    bits, info = O.mckp_bisect(w, np.float32(2.0), O.TIERS, eps, rel_tol=np.float32(0.0), max_iters=4, return_info=True)
+    # lam = 4: weight 64 ties between 4 and 8 bits (r_3 lam = 128 not reached; r_2 lam = 32 < 64 -> 4 bits), weight 32
+    # ties between 2 and 4 bits -> 2 bits: 4*4 + 4*2 = 24 = the budget
+    assert info["lam"] == 4.0 and bits.tolist() == [4] * 4 + [2] * 4 + [0] * 4
+
+
+def test_bisection_runs_the_printed_per_unit_step():
+    """mckp_bisect must return, for the multiplier it reports, exactly the printed argmin of every unit -- and the
+    threshold form must reproduce the whole search on ordinary (tie-free) weights."""
+    rng = np.random.default_rng(77)
+    for eps in (O.EPS_V_LLAMA31_8B, O.EPS_K_LLAMA31_8B, O.EPS_BENNETT):
+        w = np.exp(rng.normal(0, 2, 3000)).astype(np.float32)
+        for avg in (0.4, 1.0, 3.0, 7.5):
+            bits, info = O.mckp_bisect(w, np.float32(avg), O.TIERS, eps, return_info=True)
+            assert np.array_equal(bits, O.argmin_bits(w, info["lam"], O.TIERS, eps))
+            hb, r = O.hull_thresholds(O.TIERS, eps)
+            assert np.array_equal(bits, O.classify(w, info["lam"], hb, r))
+            assert int(bits.astype(np.int64).sum()) <= info["B_int"]
+
+
 def test_mckp_bruteforce_optimality_and_weak_duality():
     # tiny instances: enumerate all 5^U allocations (Eq. 6) and check
     #   g(lam) <= OPT(B) <= primal(returned)                       (Prop. A.3)
@@ -600,6 +643,57 @@ def test_k_dequant_fusion_identity():
         np.testing.assert_allclose(lhs, rhs, rtol=1e-12, atol=1e-12)
 
 
+def test_compress_tokenwise_equals_its_stages_and_brute_force_attention():
+    """The whole token-wise pass (Alg. 1 with K sharing the token map) against its stages called one by one, and the
+    decode of its result against brute-force attention over rows dequantized straight from the canonical records."""
+    rng = np.random.default_rng(29)
+    Hkv, g, d, Sw = 2, 2, 128, 16
+    seq = [300, 131]
+    Ks = [rand_bf16(rng, (Hkv, T, d)) for T in seq]
+    Vs = [rand_bf16(rng, (Hkv, T, d)) for T in seq]
+    for K in Ks:
+        K[:, :, 7] *= np.float32(8.0)                          # an outlier channel
+    Qo = [rand_bf16(rng, (Hkv * g, Sw, d)) for _ in seq]
+    budgets = [np.float32(7.0), np.float32(1.5)]
+    cache = O.compress_tokenwise(Ks, Vs, Qo, budgets, eps=O.EPS_BENNETT)
+    bits_list = []
+    for s_, T in enumerate(seq):
+        w = O.avg_pool(O.token_weights(Ks[s_], Qo[s_]), 5).astype(np.float32)      # Stage 1
+        assert np.array_equal(cache["weights"][s_], w)
+        # before pooling every window row is a probability vector: total mass g * S_w per KV head
+        np.testing.assert_allclose(O.token_weights(Ks[s_], Qo[s_]).sum(axis=1), g * Sw, rtol=1e-12)
+        bits = np.stack([O.mckp_bisect(w[h], budgets[s_], O.TIERS, O.EPS_BENNETT) for h in range(Hkv)])   # Stage 2
+        assert np.array_equal(cache["bits"][s_], bits)
+        for h in range(Hkv):
+            assert int(bits[h].astype(np.int64).sum()) <= int(np.floor(float(budgets[s_]) * T))
+        bits_list.append(bits)
+    assert len({int(b) for bb in bits_list for b in np.unique(bb)}) >= 4         # the case spans the tiers
+    staged = O.build_cache_tokenwise(Ks, Vs, bits_list)                          # Stage 4
+    assert np.array_equal(cache["arena"], staged["arena"]) and np.array_equal(cache["counts"], staged["counts"])
+    assert np.array_equal(cache["tier_idx"], staged["tier_idx"])
+    assert O.stored_bytes(cache["counts"]) == sum(
+        int((bb == b).sum()) * 2 * (16 * b + (16 if b < 16 else 0)) for bb in bits_list for b in (2, 4, 8, 16))
+    # decode = softmax attention over the retained rows, dequantized here from a quantizer call of this test's own
+    q = rand_bf16(rng, (len(seq), Hkv * g, d))
+    out, lse = O.decode(cache, q)
+    for s_, T in enumerate(seq):
+        for h in range(Hkv):
+            Kh, Vh = [], []
+            for b in (16, 8, 4, 2):
+                idx = np.nonzero(bits_list[s_][h] == b)[0]
+                for X, dst in ((Ks[s_][h][idx], Kh), (Vs[s_][h][idx], Vh)):
+                    if b == 16:
+                        dst.append(X.astype(np.float64))
+                    else:
+                        c, sc, m = O.quantize_groups(X.reshape(-1, 4, 32), b)
+                        dst.append(O.dequantize_groups(c, sc, m).reshape(-1, d))
+            Kh, Vh = np.concatenate(Kh), np.concatenate(Vh)
+            for j in range(g):
+                o, l = _bruteforce_attention(q[s_, h * g + j], Kh, Vh)
+                np.testing.assert_allclose(out[s_, h * g + j], o, rtol=1e-11, atol=1e-12)
+                assert abs(lse[s_, h * g + j] - l) < 1e-10
+
+
 def test_compress_tokenwise_end_to_end_small():
     rng = np.random.default_rng(23)
     Hkv, g, T, d, Sw = 2, 2, 400, 128, 32
@@ -921,6 +1015,39 @@ def test_mixed_cache_bytes_and_decode_from_physical_bytes():
         o, l = _bruteforce_attention(q[0, j], Kh, Vh)
         np.testing.assert_allclose(out[0, j], o, rtol=1e-11, atol=1e-12)
     assert O.stored_bytes_mixed(cache["counts"], cache["bits_ch"]) < cache["arena"].size
+
+
+def test_stored_bytes_mixed_hand_computed():
+    """Bytes a mixed-mode decode step reads, worked by hand for the channel map of _hand_bits_ch(): 2 channels at 16
+    bits, 3 at 8, 11 at 4, 3 at 2 -> 32 + 24 + 44 + 6 = 106 bits = 13.25 bytes of K codes per retained token, 17
+    quantized channels of 4 metadata bytes (fp16 scale + fp16 offset) per group of 32 retained tokens; V rows as in
+    token-wise mode (256 / 144 / 80 / 48 bytes at 16 / 8 / 4 / 2 bits)."""
+    bc = _hand_bits_ch()
+    counts = np.array([[3, 40, 65, 0]])                # rows per V tier 16, 8, 4, 2
+    # tier 16:  3 rows: K floor(3 * 13.25) = 39,  1 group -> 68;   V 3 * 256  = 768   -> 875
+    # tier  8: 40 rows: K 530,                    2 groups -> 136; V 40 * 144 = 5760  -> 6426
+    # tier  4: 65 rows: K floor(861.25) = 861,    3 groups -> 204; V 65 * 80  = 5200  -> 6265
+    assert O.stored_bytes_mixed(counts, [bc]) == 875 + 6426 + 6265 == 13566
+    # one scale per channel over all retained tokens: one 68-byte record per non-empty tier segment
+    assert O.stored_bytes_mixed(counts, [bc], k_per_channel_scale=True) == (39 + 68 + 768) + (530 + 68 + 5760) + (861 + 68 + 5200) == 13362
+    # second item with no quantized channel (all 16-bit: 256 bytes per K row, no metadata) and 2-bit V rows only
+    bc16 = np.full(128, 16, np.uint8)
+    two = np.array([[3, 40, 65, 0], [0, 0, 0, 10]])
+    assert O.stored_bytes_mixed(two, [bc, bc16]) == 13566 + 10 * 256 + 10 * 48
+    # every channel evicted: only the V rows remain
+    assert O.stored_bytes_mixed(np.array([[1, 1, 1, 1]]), [np.zeros(128, np.uint8)]) == 256 + 144 + 80 + 48
+    # cross-check against the packed form on real data: the arena of a cache whose segments are all whole tiles and
+    # 256-byte multiples holds exactly the stored bytes plus the zero padding of the sorted-channel rows
+    rng = np.random.default_rng(91)
+    T = 64 * 4
+    K, V = rand_bf16(rng, (1, T, 128)), rand_bf16(rng, (1, T, 128))
+    bt = np.repeat(np.array([16, 8, 4, 2], np.uint8), 64)[None]
+    cache = O.build_cache_mixed([K], [V], [bt], [bc[None]])
+    sl = O.channel_slots(bc)
+    pad_k = 4 * (O.k_tile_bytes_mixed(sl) - 64 * 106 // 8)            # padding slots inside the four K tiles
+    pad_meta = 4 * 2 * (4 * 9 - 17) * 4                               # 9 quantized steps = 36 slots for 17 channels
+    align = 4 * (512 - O.k_meta_bytes_mixed(sl))                      # each tile's 288 metadata bytes end a 256-byte unit
+    assert cache["arena"].size - pad_k - pad_meta - align == O.stored_bytes_mixed(cache["counts"], cache["bits_ch"])
 
 
 def test_allocate_mixed_meets_both_budgets():

@@ -12,12 +12,25 @@
  *    buffers are owned by the caller unless stated otherwise and must stay valid
  *    until the stream has executed the call's work.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Calls enqueue their kernels on it.  Calls that return a cache
- *    (rdkv_pack, rdkv_compress) read tier counts back and therefore synchronise
- *    the stream once; all other calls are asynchronous.
+ *    Calls enqueue their work on it and return without waiting for it, with these
+ *    exceptions, each stated again at its declaration: rdkv_pack and rdkv_compress
+ *    wait once (the tier counts size the arena and the split schedule, so they are
+ *    read back); rdkv_cache_reserve_tail and rdkv_cache_rebudget_tail (they replace
+ *    the schedule), rdkv_calibrate_eps, rdkv_cache_stats and rdkv_cache_export
+ *    (host results) wait for the stream.  rdkv_weights, rdkv_allocate,
+ *    rdkv_decode_attn, rdkv_decode_attn_bf16 and rdkv_cache_append never wait.
  *  - Every function returns an rdkv_status and never throws or aborts; host-side
- *    arguments are validated before anything is launched; on failure `*out`
- *    handles are left NULL and rdkv_last_error() holds a message (thread local).
+ *    arguments are validated before anything is launched (what only the device can
+ *    see -- the values inside a device bit map -- is reported after the one wait of
+ *    rdkv_pack, before anything is packed); on failure `*out` handles are left NULL
+ *    and rdkv_last_error() holds a message (thread local).
+ *  - Scratch memory of a call is released when the call returns, while its kernels
+ *    may still be queued.  The allocator hooks of rdkv_config must therefore behave
+ *    like a stream-ordered caching allocator used on the call's stream (memory
+ *    given back may be handed out again only to work enqueued later on that stream,
+ *    or after that stream has drained; PyTorch's caching allocator does this).
+ *    Without hooks, scratch comes from hipMallocAsync / hipFreeAsync on the call's
+ *    stream and what a cache owns from hipMalloc / hipFree.
  *  - Shapes: head_dim must be 128, hq a multiple of hkv with hq/hkv in
  *    {1,2,4,8}, quantization group size 32.
  *  - Ragged batch layout: K, V (and per-token arrays) hold, per sequence s in
@@ -97,6 +110,10 @@ typedef struct rdkv_stats {
   int64_t index_bytes;      /* kept-position lists, segment tables, split schedule */
   int64_t n_chunks;         /* work items of one decode launch */
   int64_t dense_bytes;      /* 2 * sum_s hkv*T_s*head_dim*2: the uncompressed bf16 K+V */
+  int64_t alloc_info;       /* 1 if the cache came from rdkv_compress, so that the fields below are known; else 0 */
+  int64_t iterations_max;   /* Alg. 2: most bisection steps any item's token-map search took */
+  double lambda_min;        /* Alg. 2: smallest and largest multiplier lambda* of the token-map searches that ran */
+  double lambda_max;        /*   (NaN if none ran: budget shortcuts, or alloc_info == 0); per item: rdkv_cache_export */
 } rdkv_stats;
 
 /* What rdkv_cache_export copies out (all to HOST memory). */
@@ -106,7 +123,12 @@ enum {
   RDKV_EXPORT_SEG_OFF = 2,  /* int64 [items][4 tiers][4]: arena byte offsets of K data, K meta, V data, V meta */
   RDKV_EXPORT_ARENA = 3,    /* uint8 [arena_bytes]: the physical packed buffers */
   RDKV_EXPORT_BITS_TOK = 4, /* uint8 [sum_s hkv*T_s]: token bit map */
-  RDKV_EXPORT_BITS_CH = 5   /* uint8 [items][head_dim]: K channel bit map (channel-wise mode) */
+  RDKV_EXPORT_BITS_CH = 5,  /* uint8 [items][head_dim]: K channel bit map (channel-wise mode) */
+  RDKV_EXPORT_LAMBDA = 6,   /* double [items], channel-wise mode [2][items] (token maps, then channel maps): the
+                               multiplier lambda of the allocation Alg. 2 returned; NaN where no search ran (the
+                               all-16 / all-0 shortcuts, no feasible step).  Caches built by rdkv_compress only:
+                               size 0 otherwise */
+  RDKV_EXPORT_ITERATIONS = 7 /* int32, same shape: bisection steps taken (0 where no search ran) */
 };
 
 const char* rdkv_version(void);
@@ -143,6 +165,12 @@ rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_ob
  */
 rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const float* w_ch,
                           uint8_t* bits_tok, uint8_t* bits_ch, void* stream);
+/* The same, also returning what Alg. 2 found per item: lambda_out DEVICE double [items] (channel-wise mode:
+ * [2][items], token maps then channel maps): the multiplier of the returned allocation, NaN where no search ran;
+ * iterations_out DEVICE int32, same shape: bisection steps taken.  Either may be NULL. */
+rdkv_status rdkv_allocate_info(const rdkv_config* cfg, const float* w_tok, const float* w_ch,
+                               uint8_t* bits_tok, uint8_t* bits_ch, double* lambda_out,
+                               int32_t* iterations_out, void* stream);
 
 /*
  * Stage 4 of Alg. 1: partition kept tokens by tier, quantize groups of 32 with an
@@ -159,14 +187,27 @@ rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const floa
  * channel and per 32 consecutive retained tokens of a tier segment (per channel over all
  * retained tokens of the item when cfg->k_scale_per_channel is set); a channel at 0 bits is
  * dropped (it contributes nothing to q.k), a channel at 16 bits keeps its bf16 values.
+ * Waits for the stream once (tier counts).  A value in bits_tok or bits_ch outside {0,2,4,8,16} gives
+ * RDKV_ERR_INVALID_ARG (found on the device, reported after that wait; nothing has been packed then).
  */
 rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V,
                       const uint8_t* bits_tok, const uint8_t* bits_ch, void* stream,
                       rdkv_cache** out);
 
-/* The whole one-shot pass: rdkv_weights -> rdkv_allocate -> rdkv_pack (Alg. 1). */
+/* The whole one-shot pass: rdkv_weights -> rdkv_allocate -> rdkv_pack (Alg. 1), with one wait for the stream (the
+ * tier counts); the multipliers and step counts of Alg. 2 stay with the cache (rdkv_cache_stats / rdkv_cache_export). */
 rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V,
                           const void* Q_obs, void* stream, rdkv_cache** out);
+
+/*
+ * A-priori bound, from the budget alone, on the bytes of the packed arena rdkv_pack / rdkv_compress will allocate
+ * through cfg->alloc for this batch (Sec. 3.2: the summed bit-widths of an item never exceed floor(avg_bits * units),
+ * so it keeps at most that over the lowest stored bit-width tokens): a caller can reserve memory for a cache before
+ * the pass has run.  Needs batch, heads, seq_lens, budget_bits, k_mode, kv_split_rk and tiers; 0 on an invalid config.
+ * The bound covers the arena (codes, scales, offsets, padding), not the index tables (4 bytes per kept token and
+ * 56 bytes per work item of the split schedule).
+ */
+size_t rdkv_cache_max_bytes(const rdkv_config* cfg);
 
 /*
  * One decode step over the packed cache (Sec. 3.3, Eq. 7): for every sequence

@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_HERE, "librdkv.so")
 RDKV_OK = 0
 RDKV_K_TOKENWISE, RDKV_K_CHANNELWISE = 0, 1
 (RDKV_EXPORT_COUNTS, RDKV_EXPORT_TIER_IDX, RDKV_EXPORT_SEG_OFF, RDKV_EXPORT_ARENA,
- RDKV_EXPORT_BITS_TOK, RDKV_EXPORT_BITS_CH) = range(6)
+ RDKV_EXPORT_BITS_TOK, RDKV_EXPORT_BITS_CH, RDKV_EXPORT_LAMBDA, RDKV_EXPORT_ITERATIONS) = range(8)
 STATUS_NAMES = {0: "RDKV_OK", 1: "RDKV_ERR_INVALID_ARG", 2: "RDKV_ERR_SHAPE", 3: "RDKV_ERR_UNSUPPORTED",
                 4: "RDKV_ERR_ALLOC", 5: "RDKV_ERR_HIP", 6: "RDKV_ERR_INTERNAL"}
 
 EXPORTED_SYMBOLS = [
-    "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_pack",
+    "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_allocate_info", "rdkv_pack", "rdkv_cache_max_bytes",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
     "rdkv_decode_bf16_noalloc_max_bytes", "rdkv_decode_attn_bf16_noalloc",
     "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_calibrate_eps",
@@ -57,6 +57,8 @@ class rdkv_stats(ctypes.Structure):
         ("n_items", ctypes.c_int64), ("rows", ctypes.c_int64 * 4), ("evicted", ctypes.c_int64),
         ("stored_bytes", ctypes.c_int64), ("arena_bytes", ctypes.c_int64), ("index_bytes", ctypes.c_int64),
         ("n_chunks", ctypes.c_int64), ("dense_bytes", ctypes.c_int64),
+        ("alloc_info", ctypes.c_int64), ("iterations_max", ctypes.c_int64),
+        ("lambda_min", ctypes.c_double), ("lambda_max", ctypes.c_double),
     ]
 
 
@@ -77,6 +79,9 @@ def _load():
     lib.rdkv_config_default.argtypes = [cfgp]
     lib.rdkv_weights.argtypes = [cfgp, vp, vp, vp, vp, vp]
     lib.rdkv_allocate.argtypes = [cfgp, vp, vp, vp, vp, vp]
+    lib.rdkv_allocate_info.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
+    lib.rdkv_cache_max_bytes.argtypes = [cfgp]
+    lib.rdkv_cache_max_bytes.restype = sz
     lib.rdkv_pack.argtypes = [cfgp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
     lib.rdkv_compress.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp)]
     lib.rdkv_decode_attn.argtypes = [vp, vp, vp, vp, vp]
@@ -178,7 +183,8 @@ class Cache:
         _check(lib.rdkv_cache_stats(self.h, ctypes.byref(st)))
         return {"n_items": st.n_items, "rows": list(st.rows), "evicted": st.evicted,
                 "stored_bytes": st.stored_bytes, "arena_bytes": st.arena_bytes, "index_bytes": st.index_bytes,
-                "n_chunks": st.n_chunks, "dense_bytes": st.dense_bytes}
+                "n_chunks": st.n_chunks, "dense_bytes": st.dense_bytes, "alloc_info": st.alloc_info,
+                "iterations_max": st.iterations_max, "lambda_min": st.lambda_min, "lambda_max": st.lambda_max}
 
     def export(self, what, dtype):
         n = lib.rdkv_cache_export_bytes(self.h, what)
@@ -213,6 +219,23 @@ def rdkv_allocate(cfg, w_tok, w_ch=None):
         bits_ch = torch.empty(len(cfg.seq_lens) * cfg.hkv * cfg.d, dtype=torch.uint8, device=w_tok.device)
     _check(lib.rdkv_allocate(cfg.ref(), _ptr(w_tok), _ptr(w_ch), _ptr(bits_tok), _ptr(bits_ch), _stream()))
     return bits_tok, bits_ch
+
+
+def rdkv_allocate_info(cfg, w_tok, w_ch=None):
+    """(bits_tok, bits_ch, lambda, iterations): the last two as device tensors [maps, items]."""
+    n = len(cfg.seq_lens) * cfg.hkv
+    mixed = cfg.c.k_mode == RDKV_K_CHANNELWISE
+    bits_tok = torch.empty(cfg.total_tokens, dtype=torch.uint8, device=w_tok.device)
+    bits_ch = torch.empty(n * cfg.d, dtype=torch.uint8, device=w_tok.device) if mixed else None
+    lam = torch.empty((2 if mixed else 1, n), dtype=torch.float64, device=w_tok.device)
+    iters = torch.empty((2 if mixed else 1, n), dtype=torch.int32, device=w_tok.device)
+    _check(lib.rdkv_allocate_info(cfg.ref(), _ptr(w_tok), _ptr(w_ch), _ptr(bits_tok), _ptr(bits_ch), _ptr(lam),
+                                  _ptr(iters), _stream()))
+    return bits_tok, bits_ch, lam, iters
+
+
+def rdkv_cache_max_bytes(cfg):
+    return int(lib.rdkv_cache_max_bytes(cfg.ref()))
 
 
 def rdkv_pack(cfg, K, V, bits_tok, bits_ch=None):

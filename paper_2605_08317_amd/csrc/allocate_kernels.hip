@@ -27,6 +27,8 @@ struct AllocArgs {
   int32_t n_hull;
   int32_t max_iters;
   double need_frac;            // 1 - rel_tol
+  double* lam_out;             // [items] or null: the multiplier of the returned allocation (NaN: no search ran)
+  int32_t* iters_out;          // [items] or null: bisection steps taken
 };
 
 __device__ __forceinline__ long long block_sum(long long v, long long* sm) {
@@ -148,6 +150,10 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   __shared__ int sm_small[2 * (kThreads / 64)];
   const int item = blockIdx.x;
   const int U = a.item_U[item];
+  if (threadIdx.x == 0) {      // overwritten below when the search runs
+    if (a.lam_out) a.lam_out[item] = __longlong_as_double(0x7FF8000000000000ll);
+    if (a.iters_out) a.iters_out[item] = 0;
+  }
   if (U == 0) return;
   const float* __restrict__ w = a.w + a.item_off[item];
   uint8_t* __restrict__ bits = a.bits + a.item_off[item];
@@ -224,7 +230,9 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   int mode = 0;   // 0: histogram bounds, 1: list in LDS
   int n_list = 0;
   long long s_fixed = 0;
+  int steps = 0;
   for (int it = 0; it < a.max_iters; ++it) {
+    steps = it + 1;
     const double lam = (lo + hi) * 0.5;
     double thr[kMaxHull - 1];
 #pragma unroll
@@ -300,6 +308,10 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
       if (verdict == 2) break;
     }
   }
+  if (threadIdx.x == 0) {
+    if (a.lam_out && have) a.lam_out[item] = best;
+    if (a.iters_out) a.iters_out[item] = steps;
+  }
   double thr[kMaxHull - 1];
 #pragma unroll
   for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? best * r[k] : INFINITY;
@@ -328,34 +340,62 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   }
 }
 
-// retained units (bit-width above zero) of every item: Stage 3 spreads the K budget over them
-__global__ __launch_bounds__(256) void count_kept_kernel(const uint8_t* __restrict__ bits,
-                                                         const int64_t* __restrict__ item_off,
-                                                         const int32_t* __restrict__ item_U,
-                                                         int32_t* __restrict__ kept) {
-  __shared__ int sm[4];
+// Stage 3 of Alg. 1: the K budget r_K * B_head of an item is spread over its retained tokens (bit-width above zero)
+// only: k_avg = min(16, 2 r_K avg_bits T / n_kept) average bits per channel unit, 0 if nothing is retained; rounded
+// to fp32 like every budget.  fp64 in this operation order (the file is compiled without contraction).
+__global__ __launch_bounds__(1024) void stage3_budget_kernel(const uint8_t* __restrict__ bits,
+                                                             const int64_t* __restrict__ item_off,
+                                                             const int32_t* __restrict__ item_U,
+                                                             const double* __restrict__ item_avg, double rk,
+                                                             int32_t* __restrict__ kept,
+                                                             double* __restrict__ k_budget) {
+  __shared__ int sm[16];
   const int item = blockIdx.x;
+  const int U = item_U[item];
   const uint8_t* b = bits + item_off[item];
   int c = 0;
-  for (int u = threadIdx.x; u < item_U[item]; u += 256) c += b[u] != 0;
+  // 16 bytes per load once the pointer is aligned
+  const int head = min(U, static_cast<int>((16 - (reinterpret_cast<uintptr_t>(b) & 15)) & 15));
+  for (int u = threadIdx.x; u < head; u += 1024) c += b[u] != 0;
+  const int nq = (U - head) >> 4;
+  const uint4* q = reinterpret_cast<const uint4*>(b + head);
+  for (int i = threadIdx.x; i < nq; i += 1024) {
+    const uint4 v = q[i];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) c += ((w[k] >> (8 * e)) & 0xFFu) != 0;
+  }
+  for (int u = head + 16 * nq + threadIdx.x; u < U; u += 1024) c += b[u] != 0;
   for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
   if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = c;
   __syncthreads();
-  if (threadIdx.x == 0) kept[item] = sm[0] + sm[1] + sm[2] + sm[3];
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int i = 0; i < 16; ++i) n += sm[i];
+    kept[item] = n;
+    double k_avg = 0.0;
+    if (n > 0) k_avg = fmin(16.0, 2.0 * rk * item_avg[item] * static_cast<double>(U) / static_cast<double>(n));
+    k_budget[item] = static_cast<double>(static_cast<float>(k_avg));
+  }
 }
 
 }  // namespace
 
-hipError_t launch_count_kept(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U, int n_items,
-                             int32_t* kept, hipStream_t st) {
+hipError_t launch_stage3_budget(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U,
+                                const double* d_item_avg, double rk, int n_items, int32_t* kept, double* k_budget,
+                                hipStream_t st) {
   if (n_items == 0) return hipSuccess;
-  hipLaunchKernelGGL(count_kept_kernel, dim3(n_items), dim3(256), 0, st, bits, d_item_off, d_item_U, kept);
+  hipLaunchKernelGGL(stage3_budget_kernel, dim3(n_items), dim3(1024), 0, st, bits, d_item_off, d_item_U, d_item_avg,
+                     rk, kept, k_budget);
   return hipGetLastError();
 }
 
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
-                           const double* hull_r, double need_frac, int max_iters, uint8_t* bits, hipStream_t st) {
+                           const double* hull_r, double need_frac, int max_iters, uint8_t* bits, double* lam_out,
+                           int32_t* iters_out, hipStream_t st) {
   if (n_items == 0) return hipSuccess;
   if (n_hull < 1 || n_hull > kMaxHull) return hipErrorInvalidValue;
   AllocArgs a;
@@ -365,6 +405,7 @@ hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int3
     a.r[k] = k < n_hull - 1 ? hull_r[k] : 0.0;
   }
   a.n_hull = n_hull; a.max_iters = max_iters; a.need_frac = need_frac;
+  a.lam_out = lam_out; a.iters_out = iters_out;
   hipLaunchKernelGGL(bisect_kernel, dim3(n_items), dim3(kThreads), 0, st, a);
   return hipGetLastError();
 }

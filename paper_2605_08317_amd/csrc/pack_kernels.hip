@@ -27,18 +27,22 @@ __global__ __launch_bounds__(256) void tier_count_kernel(const uint8_t* __restri
                                                          const int64_t* __restrict__ item_tok_off,
                                                          const int32_t* __restrict__ item_T,
                                                          const int32_t* __restrict__ item_blk_off,
-                                                         int32_t* __restrict__ blk_counts) {
+                                                         int32_t* __restrict__ blk_counts,
+                                                         int32_t* __restrict__ invalid) {
   const int item = blockIdx.y;
   const int T = item_T[item];
   const int t0 = blockIdx.x * kPartBlock;
   if (t0 >= T) return;
   const uint8_t* b = bits + item_tok_off[item];
   int c[4] = {0, 0, 0, 0};
+  bool bad = false;
   for (int t = t0 + threadIdx.x; t < min(T, t0 + kPartBlock); t += 256) {
     const int s = tier_slot(b[t]);
+    bad |= s < 0 && b[t] != 0;           // neither a stored tier nor 0 (evicted)
 #pragma unroll
     for (int k = 0; k < 4; ++k) c[k] += (s == k);
   }
+  if (bad) atomicOr(invalid, 1);
   __shared__ int sm[4][4];
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
@@ -487,11 +491,12 @@ __global__ __launch_bounds__(256) void pack_k_mixed_kernel(PackArgs a) {
 
 hipError_t launch_tier_count(const uint8_t* bits, const int64_t* item_tok_off, const int32_t* item_T,
                              const int32_t* item_blk_off, int32_t* blk_counts, int32_t* item_counts,
-                             int n_items, int max_T, hipStream_t st) {
+                             int32_t* invalid, int n_items, int max_T, hipStream_t st) {
   const int max_blk = (max_T + kPartBlock - 1) / kPartBlock;
   if (n_items == 0 || max_blk == 0) return hipSuccess;
+  // `invalid` (zero on entry) is set when the map holds a value that is no bit-width of the method
   hipLaunchKernelGGL(tier_count_kernel, dim3(max_blk, n_items), dim3(256), 0, st, bits, item_tok_off, item_T,
-                     item_blk_off, blk_counts);
+                     item_blk_off, blk_counts, invalid);
   hipLaunchKernelGGL(tier_scan_kernel, dim3(n_items), dim3(64), 0, st, item_T, item_blk_off, blk_counts,
                      item_counts);
   return hipGetLastError();

@@ -16,7 +16,7 @@
 namespace rdkv {
 hipError_t launch_tier_count(const uint8_t* bits, const int64_t* item_tok_off, const int32_t* item_T,
                              const int32_t* item_blk_off, int32_t* blk_counts, int32_t* item_counts,
-                             int n_items, int max_T, hipStream_t st);
+                             int32_t* invalid, int n_items, int max_T, hipStream_t st);
 hipError_t launch_tier_scatter(const uint8_t* bits, const int64_t* item_tok_off, const int32_t* item_T,
                                const int32_t* item_blk_off, const int32_t* blk_offsets, const int64_t* idx_base,
                                int32_t* tier_idx, int n_items, int max_T, hipStream_t st);
@@ -34,12 +34,14 @@ hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off,
                           float* scratch, hipStream_t st);
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
-                           const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, hipStream_t st);
+                           const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, double* lam_out,
+                           int32_t* iters_out, hipStream_t st);
 hipError_t launch_calibrate(const uint16_t* K, const uint16_t* V, const int64_t* item_row_off, const int32_t* item_T,
                             int n_items, int max_T, bool k_channelwise, bool k_whole_channel, double* acc_k,
                             double* acc_v, uint32_t* range, hipStream_t st);
-hipError_t launch_count_kept(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U, int n_items,
-                             int32_t* kept, hipStream_t st);
+hipError_t launch_stage3_budget(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U,
+                                const double* d_item_avg, double rk, int n_items, int32_t* kept, double* k_budget,
+                                hipStream_t st);
 }  // namespace rdkv
 
 using namespace rdkv;
@@ -81,6 +83,10 @@ struct KernelTiming {
 };
 KernelTiming g_timing;
 
+// Device memory of the library.  What a cache owns lives until rdkv_cache_free and comes from alloc() / hipMalloc.
+// Scratch of a single call is released when the call returns, while its kernels may still be queued: the release is
+// stream-ordered (the caller's hooks must behave like a stream-ordered caching allocator on the call's stream; without
+// hooks hipMallocAsync / hipFreeAsync on that stream).
 struct Allocator {
   rdkv_alloc_fn alloc = nullptr;
   rdkv_free_fn free_ = nullptr;
@@ -95,23 +101,33 @@ struct Allocator {
     if (!p) return;
     if (free_) free_(p, user); else (void)hipFree(p);
   }
+  void* get_scratch(size_t bytes, hipStream_t st) const {
+    if (bytes == 0) bytes = 16;
+    if (alloc) return alloc(bytes, user);
+    void* p = nullptr;
+    return hipMallocAsync(&p, bytes, st) == hipSuccess ? p : nullptr;
+  }
+  void put_scratch(void* p, hipStream_t st) const {
+    if (!p) return;
+    if (free_) free_(p, user); else (void)hipFreeAsync(p, st);
+  }
 };
 
-// Device scratch that is released when the call returns.  reserve() takes one allocation up front that the
-// following get() calls are carved from (an allocation and its release cost tens of microseconds each and the
-// release synchronises the device); requests that do not fit fall back to allocations of their own.
+// Device scratch that is released (stream-ordered) when the call returns.  reserve() takes one allocation up front
+// that the following get() calls are carved from; requests that do not fit fall back to allocations of their own.
 struct Temp {
   const Allocator& al;
+  hipStream_t st;
   std::vector<void*> ptrs;
   uint8_t* slab = nullptr;
   size_t slab_bytes = 0, used = 0;
-  explicit Temp(const Allocator& a) : al(a) {}
-  ~Temp() { for (void* p : ptrs) al.put(p); }
+  Temp(const Allocator& a, hipStream_t s) : al(a), st(s) {}
+  ~Temp() { for (void* p : ptrs) al.put_scratch(p, st); }
   static size_t padded(size_t bytes) { return (std::max<size_t>(bytes, 16) + 255) / 256 * 256; }
   void reserve(std::initializer_list<size_t> sizes) {
     size_t total = 0;
     for (size_t b : sizes) total += padded(b);
-    slab = static_cast<uint8_t*>(al.get(total));
+    slab = static_cast<uint8_t*>(al.get_scratch(total, st));
     if (slab) {
       ptrs.push_back(slab);
       slab_bytes = total;
@@ -125,11 +141,73 @@ struct Temp {
       used += b;
       return p;
     }
-    void* p = al.get(n * sizeof(T));
+    void* p = al.get_scratch(n * sizeof(T), st);
     if (p) ptrs.push_back(p);
     return static_cast<T*>(p);
   }
 };
+
+// Host-to-device copies of small tables without waiting for them: the source is copied into a ring of pinned host
+// memory (one per device), the copy is enqueued from there, and an event marks when the ring bytes may be reused.
+// A table larger than the ring is copied from the caller's memory and the stream is synchronised.
+constexpr int kMaxDevices = 64;
+class Staging {
+  struct Region { size_t begin, end; hipEvent_t ev; };
+  std::mutex mu_;
+  uint8_t* base_ = nullptr;
+  size_t cap_ = 0, head_ = 0;
+  std::vector<Region> live_;       // ring bytes whose copy may not have run yet
+  std::vector<hipEvent_t> pool_;
+  static constexpr size_t kBytes = static_cast<size_t>(2) << 20;
+
+ public:
+  hipError_t upload(void* dst, const void* src, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return hipSuccess;
+    std::lock_guard<std::mutex> lk(mu_);
+    if (!base_) {
+      void* p = nullptr;
+      if (hipHostMalloc(&p, kBytes, hipHostMallocDefault) == hipSuccess) { base_ = static_cast<uint8_t*>(p); cap_ = kBytes; }
+    }
+    const size_t need = (bytes + 255) / 256 * 256;
+    if (!base_ || need > cap_ / 2) {
+      hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st);
+      return e != hipSuccess ? e : hipStreamSynchronize(st);
+    }
+    if (head_ + need > cap_) head_ = 0;      // wrap: the bytes up to the end of the ring are skipped
+    for (size_t k = 0; k < live_.size();) {   // copies still reading the bytes about to be overwritten
+      if (live_[k].begin < head_ + need && live_[k].end > head_) {
+        (void)hipEventSynchronize(live_[k].ev);
+        pool_.push_back(live_[k].ev);
+        live_.erase(live_.begin() + static_cast<std::ptrdiff_t>(k));
+      } else {
+        ++k;
+      }
+    }
+    uint8_t* p = base_ + head_;
+    std::memcpy(p, src, bytes);
+    hipError_t e = hipMemcpyAsync(dst, p, bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return e;
+    hipEvent_t ev = nullptr;
+    if (!pool_.empty()) { ev = pool_.back(); pool_.pop_back(); }
+    else if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return hipStreamSynchronize(st);
+    if ((e = hipEventRecord(ev, st)) != hipSuccess) { pool_.push_back(ev); return hipStreamSynchronize(st); }
+    live_.push_back(Region{head_, head_ + need, ev});
+    head_ += need;
+    return hipSuccess;
+  }
+};
+Staging g_staging[kMaxDevices];
+
+hipError_t upload(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) {
+    e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st);
+    return e != hipSuccess ? e : hipStreamSynchronize(st);
+  }
+  return g_staging[dev].upload(dst, src, bytes, st);
+}
 
 // Geometry of a ragged batch: one entry per item (sequence-major, head-minor).
 struct Items {
@@ -249,6 +327,8 @@ void free_cache_buffers(rdkv_cache* c) {
   al.put(c->d_items_k);
   al.put(c->d_items_sched);
   al.put(c->d_tail);
+  al.put(c->d_lambda);
+  al.put(c->d_iters);
   for (rdkv_cache* child : c->absorbed) {
     free_cache_buffers(child);
     delete child;
@@ -310,263 +390,114 @@ void hull_thresholds(const rdkv_config* cfg, const float* eps, std::vector<int>*
   }
 }
 
-}  // namespace
 
-namespace rdkv {
-void timing_begin(int kind, hipStream_t st) {
-  std::lock_guard<std::mutex> lk(g_timing.mu);
-  if (!g_timing.enabled) return;
-  hipEvent_t a = g_timing.get(), b = g_timing.get();
-  if (!a || !b) return;
-  (void)hipEventRecord(a, st);
-  g_timing.ev[kind].emplace_back(a, b);
-}
-void timing_end(int kind, hipStream_t st) {
-  std::lock_guard<std::mutex> lk(g_timing.mu);
-  if (!g_timing.enabled || g_timing.ev[kind].empty()) return;
-  (void)hipEventRecord(g_timing.ev[kind].back().second, st);
-}
-}  // namespace rdkv
+// Device tables of one pass over a ragged batch (one entry per item), sent in a single copy.
+struct Tables {
+  int64_t* tok_off = nullptr;    // first token of the item in ragged [hkv][T_s] arrays
+  double* budget = nullptr;      // average bits of the token map (channel-wise mode: the V share)
+  double* avg = nullptr;         // average bits per cache element of the item's sequence
+  int64_t* ch_off = nullptr;     // item * 128
+  int32_t* T = nullptr;
+  int32_t* wblk_off = nullptr;   // first workgroup of the item in the weights kernels
+  int32_t* blk_off = nullptr;    // first partition block of the item
+  int32_t* ch_U = nullptr;       // 128
+  int64_t n_wblk = 0;
+};
 
-extern "C" {
-
-rdkv_status rdkv_kernel_timing_enable(int32_t enable) {
-  std::lock_guard<std::mutex> lk(g_timing.mu);
-  g_timing.enabled = enable != 0;
-  return RDKV_OK;
-}
-
-rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* total_ms) {
-  if (kind < 0 || kind >= RDKV_TIME_KINDS || !launches || !total_ms)
-    return fail(RDKV_ERR_INVALID_ARG, "bad timing kind or null output");
-  std::lock_guard<std::mutex> lk(g_timing.mu);
-  double sum = 0.0;
-  int64_t n = 0;
-  for (auto& pr : g_timing.ev[kind]) {
-    float ms = 0.f;
-    if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
-      sum += ms;
-      ++n;
-    }
-    g_timing.pool.push_back(pr.first);
-    g_timing.pool.push_back(pr.second);
-  }
-  g_timing.ev[kind].clear();
-  *launches = n;
-  *total_ms = sum;
-  return RDKV_OK;
-}
-
-const char* rdkv_version(void) { return "rdkv-mi355x 0.1 (gfx950)"; }
-const char* rdkv_last_error(void) { return g_err.c_str(); }
-
-rdkv_status rdkv_config_default(rdkv_config* cfg) {
-  if (!cfg) return fail(RDKV_ERR_INVALID_ARG, "config is null");
-  std::memset(cfg, 0, sizeof(*cfg));
-  cfg->head_dim = kHeadDim;
-  cfg->s_obs = 32;
-  cfg->pool_kernel = 5;
-  cfg->causal = 1;
-  cfg->k_mode = RDKV_K_TOKENWISE;
-  cfg->group_size = kGroup;
-  cfg->kv_split_rk = 0.5f;
-  cfg->k_scale_per_channel = 0;
-  cfg->n_tiers = 5;
-  const int t[5] = {0, 2, 4, 8, 16};
-  const float ev[5] = {1.0f, 0.313f, 0.0140f, 4.9e-5f, 0.0f};
-  const float ek[5] = {1.0f, 0.149f, 0.0062f, 2.2e-5f, 0.0f};
-  for (int i = 0; i < 5; ++i) {
-    cfg->tiers[i] = t[i];
-    cfg->eps_v[i] = ev[i];
-    cfg->eps_k[i] = ek[i];
-  }
-  cfg->rel_tol = 1e-2f;
-  cfg->max_iters = 64;
-  return RDKV_OK;
-}
-
-rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_obs, float* w_tok,
-                         float* w_ch, void* stream) {
-  rdkv_status s = check_config(cfg, false, true);
-  if (s != RDKV_OK) return s;
-  if (!K || !Q_obs || !w_tok) return fail(RDKV_ERR_INVALID_ARG, "K, Q_obs and w_tok must not be null");
-  if (cfg->batch == 0) return RDKV_OK;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
-  Temp tmp(al);
-  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+rdkv_status make_tables(const rdkv_config* cfg, const Items& it, bool with_budget, Temp& tmp, hipStream_t st,
+                        Tables* out) {
+  const size_t n = static_cast<size_t>(std::max<int64_t>(it.n_items, 1));
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
+  std::vector<uint8_t> blob(48 * n, 0);
+  int64_t* tok_off = reinterpret_cast<int64_t*>(blob.data());
+  double* budget = reinterpret_cast<double*>(blob.data() + 8 * n);
+  double* avg = reinterpret_cast<double*>(blob.data() + 16 * n);
+  int64_t* ch_off = reinterpret_cast<int64_t*>(blob.data() + 24 * n);
+  int32_t* T = reinterpret_cast<int32_t*>(blob.data() + 32 * n);
+  int32_t* wblk = T + n;
+  int32_t* blk = T + 2 * n;
+  int32_t* ch_U = T + 3 * n;
   const int wb = weights_block();
-  std::vector<int32_t> wblk_off(it.n_items);
   int64_t n_wblk = 0;
   for (int64_t i = 0; i < it.n_items; ++i) {
-    wblk_off[i] = static_cast<int32_t>(n_wblk);
+    tok_off[i] = it.tok_off[i];
+    T[i] = it.T[i];
+    blk[i] = it.blk_off[i];
+    wblk[i] = static_cast<int32_t>(n_wblk);
     n_wblk += (it.T[i] + wb - 1) / wb;
-  }
-  const int R_pad = (cfg->hq / cfg->hkv * cfg->s_obs + 15) / 16 * 16;
-  const size_t nscr = weights_scratch_floats(n_wblk, it.n_items, it.total_tokens, R_pad, w_ch != nullptr);
-  tmp.reserve({it.n_items * sizeof(int64_t), it.n_items * sizeof(int32_t), it.n_items * sizeof(int32_t),
-               nscr * sizeof(float)});
-  int64_t* d_off = tmp.get<int64_t>(it.n_items);
-  int32_t* d_T = tmp.get<int32_t>(it.n_items);
-  int32_t* d_wblk = tmp.get<int32_t>(it.n_items);
-  float* scratch = tmp.get<float>(nscr);
-  if (!d_off || !d_T || !d_wblk || !scratch) return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), it.n_items * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_wblk, wblk_off.data(), it.n_items * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  {
-  TimedScope ts(RDKV_TIME_WEIGHTS, st);
-  RDKV_HIP(launch_weights(*cfg, d_off, d_T, d_wblk, n_wblk, it.n_items, it.total_tokens, it.max_T,
-                          static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(Q_obs), w_tok, w_ch,
-                          scratch, st));
-  }
-  RDKV_HIP(hipStreamSynchronize(st));   // scratch is released on return
-  return RDKV_OK;
-}
-
-rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void* V, double* eps_k, double* eps_v,
-                               void* stream) {
-  if (!cfg) return fail(RDKV_ERR_INVALID_ARG, "cfg must not be null");
-  rdkv_status s = check_shape(cfg->batch, cfg->hq, cfg->hkv, cfg->head_dim, cfg->seq_lens);
-  if (s != RDKV_OK) return s;
-  if (cfg->k_mode != RDKV_K_TOKENWISE && cfg->k_mode != RDKV_K_CHANNELWISE)
-    return fail(RDKV_ERR_INVALID_ARG, "k_mode must be RDKV_K_TOKENWISE or RDKV_K_CHANNELWISE");
-  if (cfg->group_size != kGroup) return fail(RDKV_ERR_UNSUPPORTED, "group_size must be 32");
-  if (!K || !V || !eps_k || !eps_v) return fail(RDKV_ERR_INVALID_ARG, "K, V, eps_k and eps_v must not be null");
-  if (cfg->batch == 0) return RDKV_OK;
-  for (int b = 0; b < cfg->batch; ++b)
-    if (cfg->seq_lens[b] < 1) return fail(RDKV_ERR_SHAPE, "seq_lens[%d] = %d: calibration needs at least one token", b, cfg->seq_lens[b]);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
-  Temp tmp(al);
-  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
-  const size_t n = static_cast<size_t>(it.n_items);
-  const bool channelwise = cfg->k_mode == RDKV_K_CHANNELWISE;
-  const bool whole = channelwise && cfg->k_scale_per_channel != 0;
-  tmp.reserve({n * sizeof(int64_t), n * sizeof(int32_t), n * 8 * sizeof(double),
-               whole ? n * kHeadDim * 2 * sizeof(uint32_t) : 0});
-  int64_t* d_off = tmp.get<int64_t>(n);
-  int32_t* d_T = tmp.get<int32_t>(n);
-  double* d_acc = tmp.get<double>(n * 8);                       // [K | V][items][4]
-  uint32_t* d_range = whole ? tmp.get<uint32_t>(n * kHeadDim * 2) : nullptr;
-  if (!d_off || !d_T || !d_acc || (whole && !d_range)) return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  std::vector<double> h_acc(n * 8, 0.0);
-  std::vector<uint32_t> h_range;
-  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_acc, h_acc.data(), h_acc.size() * sizeof(double), hipMemcpyHostToDevice, st));
-  if (whole) {
-    h_range.resize(n * kHeadDim * 2);
-    for (size_t k = 0; k < h_range.size(); k += 2) { h_range[k] = 0xFFFFFFFFu; h_range[k + 1] = 0u; }
-    RDKV_HIP(hipMemcpyAsync(d_range, h_range.data(), h_range.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st));
-  }
-  {
-    TimedScope ts(RDKV_TIME_CALIBRATE, st);
-    RDKV_HIP(launch_calibrate(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), d_off, d_T,
-                              static_cast<int>(n), it.max_T, channelwise, whole, d_acc, d_acc + n * 4, d_range, st));
-  }
-  RDKV_HIP(hipMemcpyAsync(h_acc.data(), d_acc, h_acc.size() * sizeof(double), hipMemcpyDeviceToHost, st));
-  RDKV_HIP(hipStreamSynchronize(st));
-  for (size_t i = 0; i < n; ++i)
-    for (int side = 0; side < 2; ++side) {
-      const double* a = h_acc.data() + (side * n + i) * 4;
-      double* dst = (side == 0 ? eps_k : eps_v) + i * 3;
-      for (int k = 0; k < 3; ++k) dst[k] = a[3] > 0.0 ? a[k] / a[3] : 0.0;
+    ch_off[i] = i * kHeadDim;
+    ch_U[i] = kHeadDim;
+    if (with_budget) {
+      // Stage 2.  Token-wise mode: the sequence's average serves K and V alike.  Channel-wise mode: V gets the share
+      // 1 - r_K of the head budget, i.e. 2 (1 - r_K) avg_bits per token unit (rounded to fp32 like every budget).
+      const double a = static_cast<double>(cfg->budget_bits[i / cfg->hkv]);
+      avg[i] = a;
+      budget[i] = mixed ? static_cast<double>(static_cast<float>(2.0 * (1.0 - static_cast<double>(cfg->kv_split_rk)) * a)) : a;
     }
+  }
+  uint8_t* d = tmp.get<uint8_t>(blob.size());
+  if (!d) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  RDKV_HIP(upload(d, blob.data(), blob.size(), st));
+  out->tok_off = reinterpret_cast<int64_t*>(d);
+  out->budget = reinterpret_cast<double*>(d + 8 * n);
+  out->avg = reinterpret_cast<double*>(d + 16 * n);
+  out->ch_off = reinterpret_cast<int64_t*>(d + 24 * n);
+  out->T = reinterpret_cast<int32_t*>(d + 32 * n);
+  out->wblk_off = out->T + n;
+  out->blk_off = out->T + 2 * n;
+  out->ch_U = out->T + 3 * n;
+  out->n_wblk = n_wblk;
   return RDKV_OK;
 }
 
-rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const float* w_ch, uint8_t* bits_tok,
-                          uint8_t* bits_ch, void* stream) {
-  rdkv_status s = check_config(cfg, true, false);
-  if (s != RDKV_OK) return s;
-  if (!w_tok || !bits_tok) return fail(RDKV_ERR_INVALID_ARG, "w_tok and bits_tok must not be null");
+// Stage 1 of Alg. 1; everything is enqueued on st, nothing waits.
+rdkv_status weights_impl(const rdkv_config* cfg, const Items& it, const Tables& tb, const void* K, const void* Q_obs,
+                         float* w_tok, float* w_ch, Temp& tmp, hipStream_t st) {
+  const int R_pad = (cfg->hq / cfg->hkv * cfg->s_obs + 15) / 16 * 16;
+  const size_t nscr = weights_scratch_floats(tb.n_wblk, it.n_items, it.total_tokens, R_pad, w_ch != nullptr);
+  float* scratch = tmp.get<float>(nscr);
+  if (!scratch) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  TimedScope ts(RDKV_TIME_WEIGHTS, st);
+  RDKV_HIP(launch_weights(*cfg, tb.tok_off, tb.T, tb.wblk_off, tb.n_wblk, it.n_items, it.total_tokens, it.max_T,
+                          static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(Q_obs), w_tok, w_ch, scratch,
+                          st));
+  return RDKV_OK;
+}
+
+// Stages 2-3 of Alg. 1; everything is enqueued on st, nothing waits.  lam / iters: device [items] (token map), in
+// channel-wise mode followed by [items] for the channel map; or null.
+rdkv_status allocate_impl(const rdkv_config* cfg, const Items& it, const Tables& tb, const float* w_tok,
+                          const float* w_ch, uint8_t* bits_tok, uint8_t* bits_ch, double* lam, int32_t* iters,
+                          Temp& tmp, hipStream_t st) {
   const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
-  if (mixed && (!w_ch || !bits_ch))
-    return fail(RDKV_ERR_INVALID_ARG, "w_ch and bits_ch must not be null in channel-wise mode");
-  if (cfg->batch == 0) return RDKV_OK;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
-  Temp tmp(al);
-  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
-  const int64_t n = it.n_items;
+  const int n = static_cast<int>(it.n_items);
   std::vector<int> ht;
   std::vector<double> hr;
   hull_thresholds(cfg, cfg->eps_v, &ht, &hr);
-  // Stage 2.  Token-wise mode: the sequence's average serves K and V alike.  Channel-wise mode: V gets the share
-  // 1 - r_K of the head budget, i.e. 2 (1 - r_K) avg_bits per token unit (rounded to fp32 like every budget).
-  std::vector<double> budget(n);
-  for (int64_t i = 0; i < n; ++i) {
-    const double a = static_cast<double>(cfg->budget_bits[i / cfg->hkv]);
-    budget[i] = mixed ? static_cast<double>(static_cast<float>(2.0 * (1.0 - static_cast<double>(cfg->kv_split_rk)) * a))
-                      : a;
-  }
-  tmp.reserve({n * sizeof(int64_t), n * sizeof(int32_t), n * sizeof(double), n * sizeof(int32_t),
-               n * sizeof(int64_t), n * sizeof(int32_t), n * sizeof(double)});
-  int64_t* d_off = tmp.get<int64_t>(n);
-  int32_t* d_T = tmp.get<int32_t>(n);
-  double* d_budget = tmp.get<double>(n);
-  if (!d_off || !d_T || !d_budget) return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  RDKV_HIP(hipMemcpyAsync(d_off, it.tok_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_T, it.T.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_budget, budget.data(), n * sizeof(double), hipMemcpyHostToDevice, st));
   {
-  TimedScope ts(RDKV_TIME_ALLOCATE, st);
-  RDKV_HIP(launch_allocate(w_tok, d_off, d_T, d_budget, static_cast<int>(n), static_cast<int>(ht.size()),
-                           ht.data(), hr.data(), 1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters,
-                           bits_tok, st));
+    TimedScope ts(RDKV_TIME_ALLOCATE, st);
+    RDKV_HIP(launch_allocate(w_tok, tb.tok_off, tb.T, tb.budget, n, static_cast<int>(ht.size()), ht.data(), hr.data(),
+                             1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_tok, lam, iters, st));
   }
-  if (!mixed) {
-    RDKV_HIP(hipStreamSynchronize(st));
-    return RDKV_OK;
-  }
-  // Stage 3: the K budget r_K * B_head is spread over the retained tokens only:
-  // k_avg = min(16, 2 r_K avg_bits T / n_kept) average bits per channel unit.
-  int32_t* d_kept = tmp.get<int32_t>(n);
-  int64_t* d_ch_off = tmp.get<int64_t>(n);
-  int32_t* d_ch_U = tmp.get<int32_t>(n);
-  double* d_kbudget = tmp.get<double>(n);
-  if (!d_kept || !d_ch_off || !d_ch_U || !d_kbudget) return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  std::vector<int32_t> kept(n);
-  RDKV_HIP(launch_count_kept(bits_tok, d_off, d_T, static_cast<int>(n), d_kept, st));
-  RDKV_HIP(hipMemcpyAsync(kept.data(), d_kept, n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-  RDKV_HIP(hipStreamSynchronize(st));
-  std::vector<int64_t> ch_off(n);
-  std::vector<int32_t> ch_U(n, kHeadDim);
-  std::vector<double> kbudget(n);
-  for (int64_t i = 0; i < n; ++i) {
-    ch_off[i] = i * kHeadDim;
-    const double a = static_cast<double>(cfg->budget_bits[i / cfg->hkv]);
-    const double rk = static_cast<double>(cfg->kv_split_rk);
-    double k_avg = 0.0;    // nothing retained: no key is stored
-    if (kept[i] > 0) k_avg = std::min(16.0, 2.0 * rk * a * static_cast<double>(it.T[i]) / static_cast<double>(kept[i]));
-    kbudget[i] = static_cast<double>(static_cast<float>(k_avg));
-  }
+  if (!mixed) return RDKV_OK;
+  // Stage 3, on the device: retained tokens per item, then k_avg = min(16, 2 r_K avg_bits T / n_kept)
+  int32_t* d_kept = tmp.get<int32_t>(it.n_items);
+  double* d_kbudget = tmp.get<double>(it.n_items);
+  if (!d_kept || !d_kbudget) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  RDKV_HIP(launch_stage3_budget(bits_tok, tb.tok_off, tb.T, tb.avg, static_cast<double>(cfg->kv_split_rk), n, d_kept,
+                                d_kbudget, st));
   hull_thresholds(cfg, cfg->eps_k, &ht, &hr);
-  RDKV_HIP(hipMemcpyAsync(d_ch_off, ch_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_ch_U, ch_U.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  RDKV_HIP(hipMemcpyAsync(d_kbudget, kbudget.data(), n * sizeof(double), hipMemcpyHostToDevice, st));
-  RDKV_HIP(launch_allocate(w_ch, d_ch_off, d_ch_U, d_kbudget, static_cast<int>(n), static_cast<int>(ht.size()),
-                           ht.data(), hr.data(), 1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_ch,
-                           st));
-  RDKV_HIP(hipStreamSynchronize(st));
+  RDKV_HIP(launch_allocate(w_ch, tb.ch_off, tb.ch_U, d_kbudget, n, static_cast<int>(ht.size()), ht.data(), hr.data(),
+                           1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_ch, lam ? lam + n : nullptr,
+                           iters ? iters + n : nullptr, st));
   return RDKV_OK;
 }
 
-rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, const uint8_t* bits_tok,
-                      const uint8_t* bits_ch, void* stream, rdkv_cache** out) {
-  if (out) *out = nullptr;
-  rdkv_status s = check_config(cfg, false, false);
-  if (s != RDKV_OK) return s;
-  if (!out) return fail(RDKV_ERR_INVALID_ARG, "out is null");
+rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb, const void* K, const void* V,
+                      const uint8_t* bits_tok, const uint8_t* bits_ch, double* lam, int32_t* iters, Temp& tmp,
+                      hipStream_t st, rdkv_cache** out) {
   const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
-  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
-  if (it.total_tokens > 0 && (!K || !V || !bits_tok))
-    return fail(RDKV_ERR_INVALID_ARG, "K, V and bits_tok must not be null");
-  if (mixed && it.n_items > 0 && !bits_ch)
-    return fail(RDKV_ERR_INVALID_ARG, "bits_ch must not be null in channel-wise mode");
   const int g = cfg->hq / cfg->hkv;
 
   rdkv_cache* c = new (std::nothrow) rdkv_cache();
@@ -586,38 +517,34 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   const int64_t n = it.n_items;
   c->counts.assign(n * 4, 0);
   c->seg_off.assign(n * 16, 0);
-  Temp tmp(al);
-  {
-    const size_t n1 = static_cast<size_t>(std::max<int64_t>(n, 1));
-    tmp.reserve({n1 * sizeof(int64_t), n1 * sizeof(int32_t), n1 * sizeof(int32_t),
-                 static_cast<size_t>(std::max<int64_t>(it.n_blocks * 4, 1)) * sizeof(int32_t),
-                 n1 * 4 * sizeof(int32_t), n1 * 4 * sizeof(int64_t), n1 * 16 * sizeof(int64_t),
-                 cfg->k_mode == RDKV_K_CHANNELWISE && cfg->k_scale_per_channel ? n1 * kHeadDim * 2 * sizeof(uint32_t) : 0});
-  }
-  int64_t* d_tok_off = tmp.get<int64_t>(std::max<int64_t>(n, 1));
-  int32_t* d_T = tmp.get<int32_t>(std::max<int64_t>(n, 1));
-  int32_t* d_blk_off = tmp.get<int32_t>(std::max<int64_t>(n, 1));
+  const size_t n1 = static_cast<size_t>(std::max<int64_t>(n, 1));
   int32_t* d_blk_counts = tmp.get<int32_t>(std::max<int64_t>(it.n_blocks * 4, 1));
-  int32_t* d_counts = tmp.get<int32_t>(std::max<int64_t>(n * 4, 1));
-  int64_t* d_idx_base = tmp.get<int64_t>(std::max<int64_t>(n * 4, 1));
-  int64_t* d_seg_off = tmp.get<int64_t>(std::max<int64_t>(n * 16, 1));
-  if (!d_tok_off || !d_T || !d_blk_off || !d_blk_counts || !d_counts || !d_idx_base || !d_seg_off)
+  int32_t* d_counts = tmp.get<int32_t>(n1 * 4 + 1);          // [items][4], then the invalid-value flag
+  int64_t* d_idx_base = tmp.get<int64_t>(n1 * 4);
+  int64_t* d_seg_off = tmp.get<int64_t>(n1 * 16);
+  if (!d_blk_counts || !d_counts || !d_idx_base || !d_seg_off)
     return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
+  const int64_t* d_tok_off = tb.tok_off;
+  const int32_t* d_T = tb.T;
+  const int32_t* d_blk_off = tb.blk_off;
 
   if (n > 0) {
-    PACK_HIP(hipMemcpyAsync(d_tok_off, it.tok_off.data(), n * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    PACK_HIP(hipMemcpyAsync(d_T, it.T.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    PACK_HIP(hipMemcpyAsync(d_blk_off, it.blk_off.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    PACK_HIP(launch_tier_count(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_counts, static_cast<int>(n),
-                               it.max_T, st));
+    // the one wait of the pass: the tier counts size the arena and the split schedule
+    std::vector<int32_t> h_counts(n * 4 + 1, 0);
+    PACK_HIP(hipMemsetAsync(d_counts + n * 4, 0, sizeof(int32_t), st));
+    PACK_HIP(launch_tier_count(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_counts, d_counts + n * 4,
+                               static_cast<int>(n), it.max_T, st));
     if (it.max_T > 0)
-      PACK_HIP(hipMemcpyAsync(c->counts.data(), d_counts, n * 4 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+      PACK_HIP(hipMemcpyAsync(h_counts.data(), d_counts, (n * 4 + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     std::vector<uint8_t> h_bits_ch;
     if (mixed) {
       h_bits_ch.resize(n * kHeadDim);
       PACK_HIP(hipMemcpyAsync(h_bits_ch.data(), bits_ch, n * kHeadDim, hipMemcpyDeviceToHost, st));
     }
     PACK_HIP(hipStreamSynchronize(st));
+    if (h_counts[n * 4] != 0)
+      return bail(fail(RDKV_ERR_INVALID_ARG, "bits_tok holds a value outside {0, 2, 4, 8, 16}"));
+    std::copy(h_counts.begin(), h_counts.begin() + n * 4, c->counts.begin());
     if (mixed) {
       c->items_k.resize(n);
       for (int64_t i = 0; i < n; ++i) {
@@ -759,44 +686,232 @@ rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, cons
   c->index_bytes = kept * 4 + n_chunks * static_cast<int64_t>(sizeof(Chunk)) + n * 8 + n * 16 * 8;
 
   if (n > 0) {
+    // every table below is copied out of pinned staging memory: nothing here waits, and the host vectors may go
     if (c->arena_bytes > 0) PACK_HIP(hipMemsetAsync(c->d_arena, 0, c->arena_bytes, st));
-    PACK_HIP(hipMemcpyAsync(d_idx_base, idx_base.data(), n * 4 * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    PACK_HIP(hipMemcpyAsync(d_seg_off, c->seg_off.data(), n * 16 * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    if (n_chunks > 0)
-      PACK_HIP(hipMemcpyAsync(c->d_chunks, c->chunks.data(), n_chunks * sizeof(Chunk), hipMemcpyHostToDevice, st));
+    PACK_HIP(upload(d_idx_base, idx_base.data(), n * 4 * sizeof(int64_t), st));
+    PACK_HIP(upload(d_seg_off, c->seg_off.data(), n * 16 * sizeof(int64_t), st));
+    if (n_chunks > 0) PACK_HIP(upload(c->d_chunks, c->chunks.data(), n_chunks * sizeof(Chunk), st));
     c->slot_begin = slot_begin;
     c->slot_count = slot_count;
-    PACK_HIP(hipMemcpyAsync(c->d_slot_begin, slot_begin.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    PACK_HIP(hipMemcpyAsync(c->d_slot_count, slot_count.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    PACK_HIP(upload(c->d_slot_begin, slot_begin.data(), n * sizeof(int32_t), st));
+    PACK_HIP(upload(c->d_slot_count, slot_count.data(), n * sizeof(int32_t), st));
     if (it.total_tokens > 0)
       PACK_HIP(hipMemcpyAsync(c->d_bits_tok, bits_tok, it.total_tokens, hipMemcpyDeviceToDevice, st));
     if (mixed) {
       PACK_HIP(hipMemcpyAsync(c->d_bits_ch, bits_ch, n * kHeadDim, hipMemcpyDeviceToDevice, st));
-      PACK_HIP(hipMemcpyAsync(c->d_items_k, c->items_k.data(), n * sizeof(ItemK), hipMemcpyHostToDevice, st));
+      PACK_HIP(upload(c->d_items_k, c->items_k.data(), n * sizeof(ItemK), st));
     }
     if (kept > 0) {
       PACK_HIP(launch_tier_scatter(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_idx_base, c->d_tier_idx,
                                    static_cast<int>(n), it.max_T, st));
       uint32_t* d_krange = nullptr;
-      std::vector<uint32_t> h_krange;
       if (c->k_per_unit) {   // per-channel (minimum, maximum) over all retained tokens, as ordered integers
         d_krange = tmp.get<uint32_t>(n * kHeadDim * 2);
         if (!d_krange) return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
-        h_krange.resize(static_cast<size_t>(n) * kHeadDim * 2);
+        std::vector<uint32_t> h_krange(static_cast<size_t>(n) * kHeadDim * 2);
         for (size_t k = 0; k < h_krange.size(); k += 2) { h_krange[k] = 0xFFFFFFFFu; h_krange[k + 1] = 0u; }
-        PACK_HIP(hipMemcpyAsync(d_krange, h_krange.data(), h_krange.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+        PACK_HIP(upload(d_krange, h_krange.data(), h_krange.size() * sizeof(uint32_t), st));
       }
       TimedScope ts(RDKV_TIME_PACK, st);
       PACK_HIP(launch_quant_pack(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), c->d_tier_idx,
                                  d_idx_base, d_counts, d_seg_off, d_tok_off, c->d_arena, static_cast<int>(n),
                                  max_count, mixed ? c->d_items_k : nullptr, mixed ? c->d_bits_ch : nullptr, d_krange, st));
-      PACK_HIP(hipStreamSynchronize(st));   // h_krange goes out of scope
     }
-    PACK_HIP(hipStreamSynchronize(st));   // host vectors and scratch go out of scope
   }
 #undef PACK_HIP
+  c->d_lambda = lam;       // adopted: freed with the cache
+  c->d_iters = iters;
   *out = c;
   return RDKV_OK;
+}
+
+
+}  // namespace
+
+namespace rdkv {
+void timing_begin(int kind, hipStream_t st) {
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  if (!g_timing.enabled) return;
+  hipEvent_t a = g_timing.get(), b = g_timing.get();
+  if (!a || !b) return;
+  (void)hipEventRecord(a, st);
+  g_timing.ev[kind].emplace_back(a, b);
+}
+void timing_end(int kind, hipStream_t st) {
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  if (!g_timing.enabled || g_timing.ev[kind].empty()) return;
+  (void)hipEventRecord(g_timing.ev[kind].back().second, st);
+}
+}  // namespace rdkv
+
+extern "C" {
+
+rdkv_status rdkv_kernel_timing_enable(int32_t enable) {
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  g_timing.enabled = enable != 0;
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* total_ms) {
+  if (kind < 0 || kind >= RDKV_TIME_KINDS || !launches || !total_ms)
+    return fail(RDKV_ERR_INVALID_ARG, "bad timing kind or null output");
+  std::lock_guard<std::mutex> lk(g_timing.mu);
+  double sum = 0.0;
+  int64_t n = 0;
+  for (auto& pr : g_timing.ev[kind]) {
+    float ms = 0.f;
+    if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+      sum += ms;
+      ++n;
+    }
+    g_timing.pool.push_back(pr.first);
+    g_timing.pool.push_back(pr.second);
+  }
+  g_timing.ev[kind].clear();
+  *launches = n;
+  *total_ms = sum;
+  return RDKV_OK;
+}
+
+const char* rdkv_version(void) { return "rdkv-mi355x 0.1 (gfx950)"; }
+const char* rdkv_last_error(void) { return g_err.c_str(); }
+
+rdkv_status rdkv_config_default(rdkv_config* cfg) {
+  if (!cfg) return fail(RDKV_ERR_INVALID_ARG, "config is null");
+  std::memset(cfg, 0, sizeof(*cfg));
+  cfg->head_dim = kHeadDim;
+  cfg->s_obs = 32;
+  cfg->pool_kernel = 5;
+  cfg->causal = 1;
+  cfg->k_mode = RDKV_K_TOKENWISE;
+  cfg->group_size = kGroup;
+  cfg->kv_split_rk = 0.5f;
+  cfg->k_scale_per_channel = 0;
+  cfg->n_tiers = 5;
+  const int t[5] = {0, 2, 4, 8, 16};
+  const float ev[5] = {1.0f, 0.313f, 0.0140f, 4.9e-5f, 0.0f};
+  const float ek[5] = {1.0f, 0.149f, 0.0062f, 2.2e-5f, 0.0f};
+  for (int i = 0; i < 5; ++i) {
+    cfg->tiers[i] = t[i];
+    cfg->eps_v[i] = ev[i];
+    cfg->eps_k[i] = ek[i];
+  }
+  cfg->rel_tol = 1e-2f;
+  cfg->max_iters = 64;
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_obs, float* w_tok,
+                         float* w_ch, void* stream) {
+  rdkv_status s = check_config(cfg, false, true);
+  if (s != RDKV_OK) return s;
+  if (!K || !Q_obs || !w_tok) return fail(RDKV_ERR_INVALID_ARG, "K, Q_obs and w_tok must not be null");
+  if (cfg->batch == 0) return RDKV_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al, st);
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  Tables tb;
+  s = make_tables(cfg, it, false, tmp, st, &tb);
+  if (s != RDKV_OK) return s;
+  return weights_impl(cfg, it, tb, K, Q_obs, w_tok, w_ch, tmp, st);
+}
+
+rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void* V, double* eps_k, double* eps_v,
+                               void* stream) {
+  if (!cfg) return fail(RDKV_ERR_INVALID_ARG, "cfg must not be null");
+  rdkv_status s = check_shape(cfg->batch, cfg->hq, cfg->hkv, cfg->head_dim, cfg->seq_lens);
+  if (s != RDKV_OK) return s;
+  if (cfg->k_mode != RDKV_K_TOKENWISE && cfg->k_mode != RDKV_K_CHANNELWISE)
+    return fail(RDKV_ERR_INVALID_ARG, "k_mode must be RDKV_K_TOKENWISE or RDKV_K_CHANNELWISE");
+  if (cfg->group_size != kGroup) return fail(RDKV_ERR_UNSUPPORTED, "group_size must be 32");
+  if (!K || !V || !eps_k || !eps_v) return fail(RDKV_ERR_INVALID_ARG, "K, V, eps_k and eps_v must not be null");
+  if (cfg->batch == 0) return RDKV_OK;
+  for (int b = 0; b < cfg->batch; ++b)
+    if (cfg->seq_lens[b] < 1) return fail(RDKV_ERR_SHAPE, "seq_lens[%d] = %d: calibration needs at least one token", b, cfg->seq_lens[b]);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al, st);
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  const size_t n = static_cast<size_t>(it.n_items);
+  const bool channelwise = cfg->k_mode == RDKV_K_CHANNELWISE;
+  const bool whole = channelwise && cfg->k_scale_per_channel != 0;
+  tmp.reserve({n * sizeof(int64_t), n * sizeof(int32_t), n * 8 * sizeof(double),
+               whole ? n * kHeadDim * 2 * sizeof(uint32_t) : 0});
+  int64_t* d_off = tmp.get<int64_t>(n);
+  int32_t* d_T = tmp.get<int32_t>(n);
+  double* d_acc = tmp.get<double>(n * 8);                       // [K | V][items][4]
+  uint32_t* d_range = whole ? tmp.get<uint32_t>(n * kHeadDim * 2) : nullptr;
+  if (!d_off || !d_T || !d_acc || (whole && !d_range)) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  std::vector<double> h_acc(n * 8, 0.0);
+  std::vector<uint32_t> h_range;
+  RDKV_HIP(upload(d_off, it.tok_off.data(), n * sizeof(int64_t), st));
+  RDKV_HIP(upload(d_T, it.T.data(), n * sizeof(int32_t), st));
+  RDKV_HIP(upload(d_acc, h_acc.data(), h_acc.size() * sizeof(double), st));
+  if (whole) {
+    h_range.resize(n * kHeadDim * 2);
+    for (size_t k = 0; k < h_range.size(); k += 2) { h_range[k] = 0xFFFFFFFFu; h_range[k + 1] = 0u; }
+    RDKV_HIP(upload(d_range, h_range.data(), h_range.size() * sizeof(uint32_t), st));
+  }
+  {
+    TimedScope ts(RDKV_TIME_CALIBRATE, st);
+    RDKV_HIP(launch_calibrate(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), d_off, d_T,
+                              static_cast<int>(n), it.max_T, channelwise, whole, d_acc, d_acc + n * 4, d_range, st));
+  }
+  RDKV_HIP(hipMemcpyAsync(h_acc.data(), d_acc, h_acc.size() * sizeof(double), hipMemcpyDeviceToHost, st));
+  RDKV_HIP(hipStreamSynchronize(st));
+  for (size_t i = 0; i < n; ++i)
+    for (int side = 0; side < 2; ++side) {
+      const double* a = h_acc.data() + (side * n + i) * 4;
+      double* dst = (side == 0 ? eps_k : eps_v) + i * 3;
+      for (int k = 0; k < 3; ++k) dst[k] = a[3] > 0.0 ? a[k] / a[3] : 0.0;
+    }
+  return RDKV_OK;
+}
+
+rdkv_status rdkv_allocate_info(const rdkv_config* cfg, const float* w_tok, const float* w_ch, uint8_t* bits_tok,
+                               uint8_t* bits_ch, double* lambda_out, int32_t* iterations_out, void* stream) {
+  rdkv_status s = check_config(cfg, true, false);
+  if (s != RDKV_OK) return s;
+  if (!w_tok || !bits_tok) return fail(RDKV_ERR_INVALID_ARG, "w_tok and bits_tok must not be null");
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
+  if (mixed && (!w_ch || !bits_ch))
+    return fail(RDKV_ERR_INVALID_ARG, "w_ch and bits_ch must not be null in channel-wise mode");
+  if (cfg->batch == 0) return RDKV_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Temp tmp(al, st);
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  Tables tb;
+  s = make_tables(cfg, it, true, tmp, st, &tb);
+  if (s != RDKV_OK) return s;
+  return allocate_impl(cfg, it, tb, w_tok, w_ch, bits_tok, bits_ch, lambda_out, iterations_out, tmp, st);
+}
+
+rdkv_status rdkv_allocate(const rdkv_config* cfg, const float* w_tok, const float* w_ch, uint8_t* bits_tok,
+                          uint8_t* bits_ch, void* stream) {
+  return rdkv_allocate_info(cfg, w_tok, w_ch, bits_tok, bits_ch, nullptr, nullptr, stream);
+}
+
+rdkv_status rdkv_pack(const rdkv_config* cfg, const void* K, const void* V, const uint8_t* bits_tok,
+                      const uint8_t* bits_ch, void* stream, rdkv_cache** out) {
+  if (out) *out = nullptr;
+  rdkv_status s = check_config(cfg, false, false);
+  if (s != RDKV_OK) return s;
+  if (!out) return fail(RDKV_ERR_INVALID_ARG, "out is null");
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  if (it.total_tokens > 0 && (!K || !V || !bits_tok))
+    return fail(RDKV_ERR_INVALID_ARG, "K, V and bits_tok must not be null");
+  if (mixed && it.n_items > 0 && !bits_ch)
+    return fail(RDKV_ERR_INVALID_ARG, "bits_ch must not be null in channel-wise mode");
+  Temp tmp(al, st);
+  Tables tb;
+  s = make_tables(cfg, it, false, tmp, st, &tb);
+  if (s != RDKV_OK) return s;
+  return pack_impl(cfg, it, tb, K, V, bits_tok, bits_ch, nullptr, nullptr, tmp, st, out);
 }
 
 rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, const void* Q_obs, void* stream,
@@ -806,24 +921,88 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, 
   if (s != RDKV_OK) return s;
   if (!out) return fail(RDKV_ERR_INVALID_ARG, "out is null");
   const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
-  Temp tmp(al);
   Items it = make_items(cfg->seq_lens, cfg->batch, cfg->hkv);
+  if (it.total_tokens > 0 && (!K || !V || !Q_obs)) return fail(RDKV_ERR_INVALID_ARG, "K, V and Q_obs must not be null");
+  Temp tmp(al, st);
+  const size_t nt = static_cast<size_t>(std::max<int64_t>(it.total_tokens, 1));
+  const size_t ni = static_cast<size_t>(std::max<int64_t>(it.n_items, 1));
+  const size_t nc = ni * kHeadDim;
   {
-    const size_t nt = static_cast<size_t>(std::max<int64_t>(it.total_tokens, 1));
-    const size_t nc = static_cast<size_t>(std::max<int64_t>(it.n_items, 1)) * kHeadDim;
-    tmp.reserve({nt * sizeof(float), nt, mixed ? nc * sizeof(float) : 0, mixed ? nc : 0});
+    const int R_pad = (cfg->hq / cfg->hkv * cfg->s_obs + 15) / 16 * 16;
+    int64_t n_wblk = 0;
+    for (int64_t i = 0; i < it.n_items; ++i) n_wblk += (it.T[i] + weights_block() - 1) / weights_block();
+    tmp.reserve({48 * ni, nt * sizeof(float), nt, mixed ? nc * sizeof(float) : 0, mixed ? nc : 0,
+                 weights_scratch_floats(n_wblk, it.n_items, it.total_tokens, R_pad, mixed) * sizeof(float),
+                 mixed ? ni * sizeof(int32_t) : 0, mixed ? ni * sizeof(double) : 0,
+                 static_cast<size_t>(std::max<int64_t>(it.n_blocks * 4, 1)) * sizeof(int32_t),
+                 (ni * 4 + 1) * sizeof(int32_t), ni * 4 * sizeof(int64_t), ni * 16 * sizeof(int64_t),
+                 mixed && cfg->k_scale_per_channel ? nc * 2 * sizeof(uint32_t) : 0});
   }
-  float* w = tmp.get<float>(std::max<int64_t>(it.total_tokens, 1));
-  uint8_t* bits = tmp.get<uint8_t>(std::max<int64_t>(it.total_tokens, 1));
-  float* w_ch = mixed ? tmp.get<float>(std::max<int64_t>(it.n_items, 1) * kHeadDim) : nullptr;
-  uint8_t* bits_ch = mixed ? tmp.get<uint8_t>(std::max<int64_t>(it.n_items, 1) * kHeadDim) : nullptr;
+  Tables tb;
+  s = make_tables(cfg, it, true, tmp, st, &tb);
+  if (s != RDKV_OK) return s;
+  float* w = tmp.get<float>(nt);
+  uint8_t* bits = tmp.get<uint8_t>(nt);
+  float* w_ch = mixed ? tmp.get<float>(nc) : nullptr;
+  uint8_t* bits_ch = mixed ? tmp.get<uint8_t>(nc) : nullptr;
   if (!w || !bits || (mixed && (!w_ch || !bits_ch))) return fail(RDKV_ERR_ALLOC, "device allocation failed");
-  s = rdkv_weights(cfg, K, Q_obs, w, w_ch, stream);
-  if (s != RDKV_OK) return s;
-  s = rdkv_allocate(cfg, w, w_ch, bits, bits_ch, stream);
-  if (s != RDKV_OK) return s;
-  return rdkv_pack(cfg, K, V, bits, bits_ch, stream, out);
+  if (it.n_items == 0) return pack_impl(cfg, it, tb, K, V, bits, bits_ch, nullptr, nullptr, tmp, st, out);
+  // the multiplier and the step count of every item's search stay with the cache (rdkv_cache_stats / export)
+  const int maps = mixed ? 2 : 1;
+  double* lam = static_cast<double*>(al.get(maps * ni * sizeof(double)));
+  int32_t* iters = static_cast<int32_t*>(al.get(maps * ni * sizeof(int32_t)));
+  auto drop = [&](rdkv_status code) { al.put(lam); al.put(iters); return code; };
+  if (!lam || !iters) return drop(fail(RDKV_ERR_ALLOC, "device allocation failed"));
+  s = weights_impl(cfg, it, tb, K, Q_obs, w, w_ch, tmp, st);
+  if (s != RDKV_OK) return drop(s);
+  s = allocate_impl(cfg, it, tb, w, w_ch, bits, bits_ch, lam, iters, tmp, st);
+  if (s != RDKV_OK) return drop(s);
+  s = pack_impl(cfg, it, tb, K, V, bits, bits_ch, lam, iters, tmp, st, out);
+  if (s != RDKV_OK) return drop(s);
+  return RDKV_OK;
+}
+
+// A-priori bound on the packed arena from the budget alone (Sec. 3.2: sum of bit-widths <= floor(avg * units)).
+// Token-wise: an item keeps at most B / b_min tokens (b_min = lowest stored bit-width of the tier set), and its rows
+// cost 2 (16 b + 16) bytes each (no metadata at 16 bits), so at most 32 B + 32 B / b_min bytes, capped by all T rows
+// at 16 bits; plus up to 63 padding rows per tier and the 256-byte alignment of its 16 segments.
+// Channel-wise: V rows as above with the V share of the budget and one side only; a retained token's K row takes
+// at most sum_c b_c / 8 <= 16 k_avg bytes of codes plus up to 24 bytes of segment padding, and a K tile of 64 tokens
+// at most 32 bytes of metadata per quantized step (<= 35 steps).
+static size_t cache_max_bytes(const rdkv_config* cfg) {
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
+  int b_min = 16;
+  for (int i = 0; i < cfg->n_tiers; ++i)
+    if (cfg->tiers[i] > 0) b_min = std::min(b_min, cfg->tiers[i]);
+  double total = 0.0;
+  for (int s = 0; s < cfg->batch; ++s) {
+    const double T = static_cast<double>(cfg->seq_lens[s]);
+    const double a = static_cast<double>(cfg->budget_bits[s]);
+    double item;
+    if (!mixed) {
+      const double B = std::min(std::floor(a * T), 16.0 * T);
+      const double kept = std::min(B / b_min, T);
+      item = std::min(32.0 * B + 32.0 * kept, 512.0 * T) + 63.0 * 2.0 * (256 + 144 + 80 + 48);
+    } else {
+      const double rk = static_cast<double>(cfg->kv_split_rk);
+      const double Bv = std::min(std::floor(static_cast<double>(static_cast<float>(2.0 * (1.0 - rk) * a)) * T), 16.0 * T);
+      const double kept = std::min(Bv / b_min, T);
+      const double v = std::min(16.0 * Bv + 16.0 * kept, 256.0 * T) + 63.0 * (256 + 144 + 80 + 48);
+      // K: codes <= 16 * (2 r_K a T) bytes over all kept tokens (k_avg n_kept = 2 r_K a T), at most 256 per token
+      const double k_codes = std::min(16.0 * 2.0 * rk * a * T, 256.0 * kept) + 24.0 * kept;
+      const double tiles = std::ceil(kept / 64.0) + 4.0;
+      item = v + k_codes + tiles * 32.0 * 35.0 + 4.0 * 63.0 * 4.0 * kMaxKRowWords;
+    }
+    total += cfg->hkv * (item + 16.0 * kSegAlign);
+  }
+  return static_cast<size_t>(total) + kSegAlign;
+}
+
+size_t rdkv_cache_max_bytes(const rdkv_config* cfg) {
+  if (check_config(cfg, true, false) != RDKV_OK) return 0;
+  return cache_max_bytes(cfg);
 }
 
 // Zone C: chunks of appended tokens that exist so far (they follow the other chunks in the chunk table)
@@ -1046,9 +1225,13 @@ rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, cons
   for (int s = 0; s < cfg->batch; ++s)
     if (cfg->seq_lens[s] != c->tail_len)
       return fail(RDKV_ERR_SHAPE, "seq_lens[%d] = %d: every sequence has %d appended tokens", s, cfg->seq_lens[s], c->tail_len);
+  {   // every host-side check of the pass comes before the first launch
+    const rdkv_status s0 = check_config(cfg, true, true);
+    if (s0 != RDKV_OK) return s0;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
-  Temp tmp(al);
+  Temp tmp(al, st);
   const int32_t n_tail = c->tail_len;
   const size_t elems = static_cast<size_t>(c->n_items) * n_tail * kHeadDim;
   tmp.reserve({elems * sizeof(uint16_t), elems * sizeof(uint16_t)});
@@ -1139,7 +1322,6 @@ constexpr size_t kStaticScratchBytes = static_cast<size_t>(8) << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mu;
 void* g_scratch_ptr[kMaxDevices] = {};
 
@@ -1202,6 +1384,20 @@ rdkv_status rdkv_cache_stats(const rdkv_cache* c, rdkv_stats* out) {
   out->index_bytes = c->index_bytes;
   out->n_chunks = static_cast<int64_t>(c->chunks.size());
   out->dense_bytes = c->total_tokens * kHeadDim * 2 * 2;
+  out->lambda_min = out->lambda_max = std::nan("");
+  if (c->d_lambda && c->d_iters && c->n_items > 0) {   // the token map's searches (Alg. 2); synchronous copies
+    std::vector<double> lam(c->n_items);
+    std::vector<int32_t> iters(c->n_items);
+    RDKV_HIP(hipMemcpy(lam.data(), c->d_lambda, lam.size() * sizeof(double), hipMemcpyDeviceToHost));
+    RDKV_HIP(hipMemcpy(iters.data(), c->d_iters, iters.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    out->alloc_info = 1;
+    for (int64_t i = 0; i < c->n_items; ++i) {
+      out->iterations_max = std::max<int64_t>(out->iterations_max, iters[i]);
+      if (std::isnan(lam[i])) continue;
+      out->lambda_min = std::isnan(out->lambda_min) ? lam[i] : std::min(out->lambda_min, lam[i]);
+      out->lambda_max = std::isnan(out->lambda_max) ? lam[i] : std::max(out->lambda_max, lam[i]);
+    }
+  }
   for (const rdkv_cache* child : c->absorbed) {   // appended tokens compressed later count like the prompt's
     rdkv_stats cs;
     rdkv_cache_stats(child, &cs);
@@ -1234,6 +1430,10 @@ size_t rdkv_cache_export_bytes(const rdkv_cache* c, int what) {
     case RDKV_EXPORT_ARENA: return static_cast<size_t>(c->arena_bytes);
     case RDKV_EXPORT_BITS_TOK: return static_cast<size_t>(c->total_tokens);
     case RDKV_EXPORT_BITS_CH: return c->d_bits_ch ? static_cast<size_t>(c->n_items) * kHeadDim : 0;
+    case RDKV_EXPORT_LAMBDA:
+      return c->d_lambda ? static_cast<size_t>(c->n_items) * (c->k_mode == RDKV_K_CHANNELWISE ? 2 : 1) * sizeof(double) : 0;
+    case RDKV_EXPORT_ITERATIONS:
+      return c->d_iters ? static_cast<size_t>(c->n_items) * (c->k_mode == RDKV_K_CHANNELWISE ? 2 : 1) * sizeof(int32_t) : 0;
     default: return 0;
   }
 }
@@ -1241,7 +1441,7 @@ size_t rdkv_cache_export_bytes(const rdkv_cache* c, int what) {
 rdkv_status rdkv_cache_export(const rdkv_cache* c, int what, void* dst, size_t bytes) {
   if (!c || (!dst && bytes > 0)) return fail(RDKV_ERR_INVALID_ARG, "cache and dst must not be null");
   const size_t need = rdkv_cache_export_bytes(c, what);
-  if (what < RDKV_EXPORT_COUNTS || what > RDKV_EXPORT_BITS_CH) return fail(RDKV_ERR_INVALID_ARG, "unknown export %d", what);
+  if (what < RDKV_EXPORT_COUNTS || what > RDKV_EXPORT_ITERATIONS) return fail(RDKV_ERR_INVALID_ARG, "unknown export %d", what);
   if (bytes < need) return fail(RDKV_ERR_INVALID_ARG, "destination of %zu bytes is smaller than the %zu required", bytes, need);
   if (need == 0) return RDKV_OK;
   switch (what) {
@@ -1251,6 +1451,8 @@ rdkv_status rdkv_cache_export(const rdkv_cache* c, int what, void* dst, size_t b
     case RDKV_EXPORT_ARENA: RDKV_HIP(hipMemcpy(dst, c->d_arena, need, hipMemcpyDeviceToHost)); break;
     case RDKV_EXPORT_BITS_TOK: RDKV_HIP(hipMemcpy(dst, c->d_bits_tok, need, hipMemcpyDeviceToHost)); break;
     case RDKV_EXPORT_BITS_CH: RDKV_HIP(hipMemcpy(dst, c->d_bits_ch, need, hipMemcpyDeviceToHost)); break;
+    case RDKV_EXPORT_LAMBDA: RDKV_HIP(hipMemcpy(dst, c->d_lambda, need, hipMemcpyDeviceToHost)); break;
+    case RDKV_EXPORT_ITERATIONS: RDKV_HIP(hipMemcpy(dst, c->d_iters, need, hipMemcpyDeviceToHost)); break;
   }
   return RDKV_OK;
 }

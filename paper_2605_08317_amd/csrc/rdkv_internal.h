@@ -155,6 +155,8 @@ struct rdkv_cache {
   int64_t sched16 = 0, schedq = 0;      // chunks of the schedule: 16-bit tier, then the quantized tiers (all generations)
   rdkv::ItemK* d_items_sched = nullptr; // mixed mode with absorbed generations: [generations][items] K row layouts
   int32_t sched_k_words = 0, sched_k_steps = 0, sched_k_qsteps = 0;   // largest K row shape over all generations
+  double* d_lambda = nullptr;           // [items] (token map), channel-wise mode: + [items] (channel map): the
+  int32_t* d_iters = nullptr;           // multiplier and the step count of every search (rdkv_compress only)
   int64_t stored_bytes = 0;             // bytes a decode step must read (unpadded)
   int64_t index_bytes = 0;
   rdkv_alloc_fn alloc = nullptr;

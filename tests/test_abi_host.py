@@ -186,3 +186,26 @@ def test_every_channel_bit_map_fits_the_widest_k_row_kernel(b):
     bad = np.full(128, 3, np.uint8)
     assert b.lib.rdkv_k_row_words(bad.ctypes.data_as(ctypes.c_void_p)) == -1
     assert b.lib.rdkv_k_row_words(None) == -1
+
+
+def test_cache_max_bytes_is_the_budget_bound(b):
+    """kept tokens <= floor(avg * T) / 2 and 2 (16 b + 16) bytes per kept row (Sec. 3.2 budget bookkeeping): the bound
+    is linear in the budget until every row sits at 16 bits, never below what the budget can buy, and 0 for a bad
+    config."""
+    T, hkv = 10000, 2
+    pad = 63 * 2 * (256 + 144 + 80 + 48) + 16 * 256                 # padding rows of four tiers + segment alignment
+    got = b.rdkv_cache_max_bytes(b.Config([T], 8, hkv, budget_bits=[1.0]))
+    assert got == hkv * (32 * T + 32 * (T // 2) + pad) + 256          # 10000 bits: 5000 rows at 2 bits at most
+    all16 = b.rdkv_cache_max_bytes(b.Config([T], 8, hkv, budget_bits=[16.0]))
+    assert all16 == hkv * (512 * T + pad) + 256
+    assert b.rdkv_cache_max_bytes(b.Config([T], 8, hkv, budget_bits=[40.0])) == all16
+    assert b.rdkv_cache_max_bytes(b.Config([T], 8, hkv, budget_bits=[0.0])) == hkv * pad + 256
+    # evict-only tier set {0, 16}: a kept row costs 16 bits, so at most B / 16 rows
+    evict_only = b.rdkv_cache_max_bytes(b.Config([T], 8, hkv, budget_bits=[1.0], tiers=[0, 16], eps_v=[1.0, 0.0], eps_k=[1.0, 0.0]))
+    assert evict_only == hkv * (32 * T + 32 * (T // 16) + pad) + 256
+    two = b.rdkv_cache_max_bytes(b.Config([T, 300], 8, hkv, budget_bits=[1.0, 2.0]))
+    assert two == got - 256 + hkv * (32 * 600 + 32 * 300 + pad) + 256
+    assert b.rdkv_cache_max_bytes(b.Config([T], 8, hkv)) == 0         # no budgets
+    assert b.lib.rdkv_cache_max_bytes(None) == 0
+    mixed = b.rdkv_cache_max_bytes(b.Config([T], 8, hkv, budget_bits=[1.0], k_mode=b.RDKV_K_CHANNELWISE))
+    assert 0 < mixed < all16

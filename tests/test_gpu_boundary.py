@@ -1,0 +1,177 @@
+"""GPU tests of the boundary's bookkeeping: the multiplier and step count of Alg. 2 reported per item, the a-priori
+arena bound, bit maps with values that are no bit-width, exact ties in the per-unit step, and calls that return
+without waiting for the stream."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rdkv_oracle as O
+from test_gpu_parity import B, _inputs, _np, _split
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits_by_item(bits, seq_lens, hkv):
+    out, off = [], 0
+    for T in seq_lens:
+        for h in range(hkv):
+            out.append(bits[off:off + T])
+            off += T
+    return out
+
+
+@pytest.mark.parametrize("seq_lens,budgets,eps", [
+    ((5000, 700), (1.0, 3.0), O.EPS_V_LLAMA31_8B),
+    ((9000,), (0.4,), O.EPS_BENNETT),
+    ((64, 2000, 333), (0.0, 16.0, 7.5), O.EPS_BENNETT),          # the all-0 and all-16 shortcuts: no search
+])
+def test_lambda_and_iterations_match_the_oracle(seq_lens, budgets, eps):
+    b = B()
+    hkv, hq = 2, 8
+    rng = np.random.default_rng(3)
+    w = [np.exp(rng.normal(0, 2.0, (hkv, T))).astype(np.float32) for T in seq_lens]
+    cfg = b.Config(seq_lens, hq, hkv, budget_bits=budgets, eps_v=eps)
+    print(f"[case] lambda/iterations seq_lens={seq_lens} budgets={budgets}", flush=True)
+    bits, _, lam, iters = b.rdkv_allocate_info(cfg, torch.from_numpy(np.concatenate([x.reshape(-1) for x in w])).cuda())
+    torch.cuda.synchronize()
+    bits, lam, iters = bits.cpu().numpy(), lam.cpu().numpy()[0], iters.cpu().numpy()[0]
+    per_item = _bits_by_item(bits, seq_lens, hkv)
+    for s, T in enumerate(seq_lens):
+        for h in range(hkv):
+            rb, info = O.mckp_bisect(w[s][h], np.float32(budgets[s]), O.TIERS, eps, return_info=True)
+            i = s * hkv + h
+            np.testing.assert_array_equal(per_item[i], rb)
+            assert iters[i] == info["iters"]
+            if info["lam"] is None:
+                assert np.isnan(lam[i])
+            else:
+                assert lam[i] == info["lam"]                     # the same fp64 midpoints, bit for bit
+
+
+def test_compress_keeps_lambda_and_iterations_with_the_cache():
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(3000,))
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs)
+    cache = b.rdkv_compress(cfg, dev["K"], dev["V"], dev["Q_obs"])
+    w_tok, _ = b.rdkv_weights(cfg, dev["K"], dev["Q_obs"])
+    torch.cuda.synchronize()
+    lam = cache.export(b.RDKV_EXPORT_LAMBDA, np.float64)
+    iters = cache.export(b.RDKV_EXPORT_ITERATIONS, np.int32)
+    w = w_tok.cpu().numpy().reshape(wl.hkv, -1)
+    for h in range(wl.hkv):
+        _, info = O.mckp_bisect(w[h], np.float32(inp["budgets"][0]), return_info=True)
+        assert lam[h] == info["lam"] and iters[h] == info["iters"]
+    st = cache.stats()
+    assert st["alloc_info"] == 1 and st["iterations_max"] == iters.max()
+    assert st["lambda_min"] == lam.min() and st["lambda_max"] == lam.max()
+    # a cache packed from caller-supplied maps knows nothing about a search
+    packed = b.rdkv_pack(cfg, dev["K"], dev["V"], torch.from_numpy(cache.export(b.RDKV_EXPORT_BITS_TOK, np.uint8)).cuda())
+    st2 = packed.stats()
+    assert st2["alloc_info"] == 0 and np.isnan(st2["lambda_min"]) and packed.export(b.RDKV_EXPORT_LAMBDA, np.float64).size == 0
+    assert np.array_equal(packed.export(b.RDKV_EXPORT_ARENA, np.uint8), cache.export(b.RDKV_EXPORT_ARENA, np.uint8))
+    packed.free()
+    cache.free()
+
+
+def test_mixed_mode_reports_both_searches():
+    b = B()
+    hkv, hq, T = 2, 8, 4000
+    rng = np.random.default_rng(4)
+    w_tok = (1.0 + rng.pareto(1.2, (hkv, T))).astype(np.float32)
+    w_ch = np.exp(rng.normal(0, 1.0, (hkv, 128))).astype(np.float32)
+    cfg = b.Config([T], hq, hkv, budget_bits=[1.5], k_mode=b.RDKV_K_CHANNELWISE)
+    bt, bc, lam, iters = b.rdkv_allocate_info(cfg, torch.from_numpy(w_tok.reshape(-1)).cuda(),
+                                              torch.from_numpy(w_ch.reshape(-1)).cuda())
+    torch.cuda.synchronize()
+    lam, iters = lam.cpu().numpy(), iters.cpu().numpy()
+    for h in range(hkv):
+        v_avg, _ = O.mixed_budgets(np.float32(1.5), np.float32(0.5), T, None, 128)
+        rt, info_v = O.mckp_bisect(w_tok[h], np.float32(v_avg), O.TIERS, O.EPS_V_LLAMA31_8B, return_info=True)
+        n_kept = int((rt > 0).sum())
+        _, k_avg = O.mixed_budgets(np.float32(1.5), np.float32(0.5), T, n_kept, 128)
+        rc, info_k = O.mckp_bisect(w_ch[h], np.float32(k_avg), O.TIERS, O.EPS_K_LLAMA31_8B, return_info=True)
+        np.testing.assert_array_equal(bt.cpu().numpy().reshape(hkv, T)[h], rt)
+        np.testing.assert_array_equal(bc.cpu().numpy().reshape(hkv, 128)[h], rc)
+        assert (lam[0, h], iters[0, h]) == (info_v["lam"], info_v["iters"])
+        assert (lam[1, h], iters[1, h]) == (info_k["lam"], info_k["iters"])
+
+
+def test_exact_ties_take_the_lower_bit_width_on_the_gpu():
+    """Weights sitting exactly on the thresholds lam * r_k the search visits (dyadic distortion table, so that every
+    product is exact): the library must keep the lower bit-width, as the printed argmin of Alg. 2 does."""
+    b = B()
+    eps = (1.0, 0.5, 0.25, 0.125, 0.0)
+    w = np.array([64.0] * 4 + [32.0] * 4 + [1.0] * 4, np.float32)
+    for iters_cap, want in ((3, [2] * 4 + [0] * 8), (4, [4] * 4 + [2] * 4 + [0] * 4)):
+        cfg = b.Config([12], 1, 1, budget_bits=[2.0], eps_v=eps, rel_tol=0.0, max_iters=iters_cap)
+        bits, _, lam, it = b.rdkv_allocate_info(cfg, torch.from_numpy(w).cuda())
+        torch.cuda.synchronize()
+        rb, info = O.mckp_bisect(w, np.float32(2.0), O.TIERS, eps, rel_tol=np.float32(0.0), max_iters=iters_cap, return_info=True)
+        assert bits.cpu().numpy().tolist() == want == rb.tolist()
+        assert lam.cpu().numpy()[0, 0] == info["lam"] and it.cpu().numpy()[0, 0] == info["iters"]
+
+
+@pytest.mark.parametrize("name,kw,mixed", [
+    ("tiny", {}, False), ("layer8b", {"seq_lens": (6000,)}, False), ("stack128k", {"seq_lens": (8192,)}, False),
+    ("batch70b", {"batch": 3, "len_range": (500, 2500)}, False), ("mixed", {"seq_lens": (6000,)}, True),
+])
+def test_arena_stays_below_the_a_priori_bound(name, kw, mixed):
+    b = B()
+    wl, inp, dev = _inputs(name, **kw)
+    extra = {"k_mode": b.RDKV_K_CHANNELWISE} if mixed else {}
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs, **extra)
+    bound = b.rdkv_cache_max_bytes(cfg)
+    cache = b.rdkv_compress(cfg, dev["K"], dev["V"], dev["Q_obs"])
+    st = cache.stats()
+    print(f"[bound] {name}: arena {st['arena_bytes']} <= bound {bound} ({st['arena_bytes'] / bound:.2f})", flush=True)
+    assert 0 < st["arena_bytes"] <= bound
+    cache.free()
+    # the largest budgets: every row at 16 bits
+    cfg16 = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=[16.0] * len(inp["seq_lens"]), s_obs=wl.s_obs, **extra)
+    cache = b.rdkv_compress(cfg16, dev["K"], dev["V"], dev["Q_obs"])
+    assert cache.stats()["arena_bytes"] <= b.rdkv_cache_max_bytes(cfg16)
+    cache.free()
+
+
+def test_bit_maps_with_values_that_are_no_bit_width_are_rejected():
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(500,))
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv)
+    bits = torch.full((wl.hkv * 500,), 4, dtype=torch.uint8, device="cuda")
+    bits[777] = 3
+    with pytest.raises(b.RdkvError) as e:
+        b.rdkv_pack(cfg, dev["K"], dev["V"], bits)
+    assert e.value.status == 1 and "bits_tok" in str(e.value)
+    bits[777] = 0
+    b.rdkv_pack(cfg, dev["K"], dev["V"], bits).free()
+    cfg_m = b.Config(inp["seq_lens"], wl.hq, wl.hkv, k_mode=b.RDKV_K_CHANNELWISE)
+    bc = torch.full((wl.hkv * 128,), 2, dtype=torch.uint8, device="cuda")
+    bc[5] = 6
+    with pytest.raises(b.RdkvError) as e:
+        b.rdkv_pack(cfg_m, dev["K"], dev["V"], bits, bc)
+    assert e.value.status == 1 and "bits_ch" in str(e.value)
+
+
+def test_weights_and_allocate_return_without_waiting():
+    """The two staged calls enqueue their work and return: a long-running kernel ahead of them on the stream is still
+    running when they come back (the event recorded right after them has not completed)."""
+    b = B()
+    wl, inp, dev = _inputs("layer8b", seq_lens=(20000,))
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs)
+    w_tok, _ = b.rdkv_weights(cfg, dev["K"], dev["Q_obs"])          # warm-up: module load, staging ring
+    b.rdkv_allocate(cfg, w_tok)
+    torch.cuda.synchronize()
+    blocker = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    ev = torch.cuda.Event()
+    for _ in range(40):                                             # ~ tens of milliseconds of queued work
+        blocker.add_(1.0)
+    w_tok, _ = b.rdkv_weights(cfg, dev["K"], dev["Q_obs"])
+    bits, _ = b.rdkv_allocate(cfg, w_tok)
+    ev.record()
+    returned_early = not ev.query()
+    torch.cuda.synchronize()
+    assert returned_early, "rdkv_weights / rdkv_allocate waited for the stream"
+    ref = O.mckp_bisect(w_tok.cpu().numpy().reshape(wl.hkv, -1)[0], np.float32(inp["budgets"][0]))
+    np.testing.assert_array_equal(bits.cpu().numpy().reshape(wl.hkv, -1)[0], ref)

@@ -218,8 +218,14 @@ size_t rdkv_cache_max_bytes(const rdkv_config* cfg);
  *   q    DEVICE bf16 [batch][hq][d]
  *   out  DEVICE fp32 [batch][hq][d]
  *   lse  DEVICE fp32 [batch][hq] or NULL: natural-log sum of exp of the logits
- * An item with no retained token gives out = 0, lse = -inf.  Calls on one cache
- * share its split workspace: issue them on one stream (or serialise them).
+ * An item with no retained token gives out = 0, lse = -inf.  One launch (two when a token-wise cache holds 16-bit
+ * rows): the workgroup that finishes an item's last chunk merges the item's split partials.  A cache keeps one
+ * split workspace per stream it is decoded on, so steps on different streams may overlap (steps on one stream are
+ * serialised by the stream).  The workspace of the stream that built the cache (or last rebuilt its schedule:
+ * rdkv_cache_reserve_tail, rdkv_cache_rebudget_tail) exists from the start; the first step on any other stream
+ * allocates that stream's workspace through the cache's allocator.  A step issued while its stream is under graph
+ * capture allocates nothing and uses that first workspace whatever the stream: replays of such a graph must not
+ * overlap each other, nor steps on the stream that built the cache.
  */
 rdkv_status rdkv_decode_attn(const rdkv_cache* cache, const void* q, float* out, float* lse,
                              void* stream);
@@ -288,6 +294,13 @@ rdkv_status rdkv_kernel_timing_read(int32_t kind, int64_t* launches, double* tot
 rdkv_status rdkv_cache_reserve_tail(rdkv_cache* cache, int32_t max_new_tokens, void* stream);
 rdkv_status rdkv_cache_append(rdkv_cache* cache, const void* k_new, const void* v_new, void* stream);
 int32_t rdkv_cache_tail_len(const rdkv_cache* cache);
+/* The number of appended tokens lives in a device word of the cache: the append kernel writes its row there and
+ * advances it, the decode kernels read it.  A HIP graph that captured rdkv_cache_append followed by
+ * rdkv_decode_attn can therefore be replayed token after token (new k_new / v_new / q contents in the same
+ * buffers); a replay on a full tail appends nothing.  rdkv_cache_tail_len counts the rdkv_cache_append calls made
+ * through the library (replays are not calls); rdkv_cache_tail_len_sync waits for `stream`, reads the device's
+ * count, makes it the library's own and returns it in *out (may be NULL). */
+rdkv_status rdkv_cache_tail_len_sync(rdkv_cache* cache, void* stream, int32_t* out);
 
 /*
  * Streaming re-budgeting (the extension sketched in App. "Limitations and Future Work"): the appended tokens are

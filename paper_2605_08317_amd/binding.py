@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_allocate_info", "rdkv_pack", "rdkv_cache_max_bytes",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
     "rdkv_decode_bf16_noalloc_max_bytes", "rdkv_decode_attn_bf16_noalloc",
-    "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_calibrate_eps",
+    "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_cache_tail_len_sync", "rdkv_calibrate_eps",
     "rdkv_cache_rebudget_tail", "rdkv_cache_generations", "rdkv_cache_generation",
     "rdkv_cache_stats", "rdkv_cache_export_bytes", "rdkv_cache_export", "rdkv_cache_free",
     "rdkv_kernel_timing_enable", "rdkv_kernel_timing_read", "rdkv_k_row_words", "rdkv_k_row_words_max",
@@ -95,6 +95,7 @@ def _load():
     lib.rdkv_cache_append.argtypes = [vp, vp, vp, vp]
     lib.rdkv_cache_tail_len.argtypes = [vp]
     lib.rdkv_cache_tail_len.restype = i32
+    lib.rdkv_cache_tail_len_sync.argtypes = [vp, vp, ctypes.POINTER(i32)]
     lib.rdkv_calibrate_eps.argtypes = [cfgp, vp, vp, vp, vp, vp]
     lib.rdkv_cache_rebudget_tail.argtypes = [vp, cfgp, vp, vp]
     lib.rdkv_cache_generations.argtypes = [vp]
@@ -270,6 +271,12 @@ def rdkv_cache_append(cache, k_new, v_new):
 
 def rdkv_cache_tail_len(cache):
     return int(lib.rdkv_cache_tail_len(cache.h))
+
+
+def rdkv_cache_tail_len_sync(cache):
+    n = ctypes.c_int32()
+    _check(lib.rdkv_cache_tail_len_sync(cache.h, _stream(), ctypes.byref(n)))
+    return n.value
 
 
 @_ALLOC_FN

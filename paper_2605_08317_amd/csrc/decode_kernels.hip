@@ -5,6 +5,7 @@
 // each lane owns 8 of the 128 channels, so a wavefront covers 4 tokens per load and a K/V byte is read once for
 // all g query heads of the group.  Online softmax runs per 16-lane row with DPP reductions; rows, wavefronts and
 // chunks are merged by log-sum-exp weights (rows and wavefronts in LDS, chunks by the merge kernels).
+#include "decode_merge.h"
 #include "rdkv_internal.h"
 
 namespace rdkv {
@@ -46,8 +47,9 @@ __device__ __forceinline__ uint4 load_lane(const uint8_t* __restrict__ base, int
   return *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(row) * (kHeadDim * 2) + c16 * 16);
 }
 
-// Streams `rows` rows and leaves the chunk's unnormalised result in part_acc / part_ml.
-template <int G>
+// Streams `rows` rows and leaves the chunk's unnormalised result in part_acc / part_ml (AGENT: with agent-scope
+// stores, for a merge inside the same launch).
+template <int G, bool AGENT>
 __device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ vd,
                                              int rows, const uint16_t* __restrict__ q,
                                              float* __restrict__ part_acc, float* __restrict__ part_ml,
@@ -176,11 +178,16 @@ __device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, con
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) v += s_acc[w * G * kHeadDim + i];
-    part_acc[i] = v;
+    if constexpr (AGENT) merge::store_agent(part_acc + i, v); else part_acc[i] = v;
   }
   if (tid < G) {
-    part_ml[tid * 2] = mstar[tid];
-    part_ml[tid * 2 + 1] = lstar[tid];
+    if constexpr (AGENT) {
+      merge::store_agent(part_ml + tid * 2, mstar[tid]);
+      merge::store_agent(part_ml + tid * 2 + 1, lstar[tid]);
+    } else {
+      part_ml[tid * 2] = mstar[tid];
+      part_ml[tid * 2 + 1] = lstar[tid];
+    }
   }
 }
 
@@ -198,22 +205,26 @@ __global__ __launch_bounds__(kWG) void decode_dense_kernel(DenseArgs a) {
   const int seq = a.seq_base + sl;
   const uint16_t* q = a.q + (static_cast<int64_t>(seq) * a.hq + head * G) * kHeadDim;
   const int64_t slot = (static_cast<int64_t>(sl) * a.hkv + head) * a.max_splits + split;
-  process_rows<G>(kd, vd, rows, q, a.part_acc + slot * G * kHeadDim, a.part_ml + slot * G * 2, smem);
+  process_rows<G, false>(kd, vd, rows, q, a.part_acc + slot * G * kHeadDim, a.part_ml + slot * G * 2, smem);
 }
 
 template <int G>
 __global__ __launch_bounds__(kWG) void decode_tiered_kernel(const Chunk* __restrict__ chunks,
                                                             const uint8_t* __restrict__ arena,
-                                                            const uint16_t* __restrict__ q, float* part_acc,
-                                                            float* part_ml, int hq, int hkv) {
-  __shared__ float smem[16 * G * 2 + kWaves * G * kHeadDim];
+                                                            const uint16_t* __restrict__ q, MergeArgs ma) {
+  constexpr int kSplit = 16 * G * 2 + kWaves * G * kHeadDim;
+  constexpr int kMerge = merge::merge_lds_floats(kWG, G);
+  __shared__ float smem[kSplit > kMerge ? kSplit : kMerge];
   const Chunk ch = chunks[blockIdx.x];
-  const int seq = ch.item / hkv, head = ch.item % hkv;
-  const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * G) * kHeadDim;
-  float* pa = part_acc + static_cast<int64_t>(ch.slot) * G * kHeadDim;
-  float* pm = part_ml + static_cast<int64_t>(ch.slot) * G * 2;
+  const int seq = ch.item / ma.hkv, head = ch.item % ma.hkv;
+  const uint16_t* qp = q + (static_cast<int64_t>(seq) * ma.hq + head * G) * kHeadDim;
+  float* pa = ma.part_acc + static_cast<int64_t>(ch.slot) * G * kHeadDim;
+  float* pm = ma.part_ml + static_cast<int64_t>(ch.slot) * G * 2;
   // row-major bf16 rows: the 16-bit tier of a token-wise cache
-  process_rows<G>(arena + ch.k_data, arena + ch.v_data, ch.rows, qp, pa, pm, smem);
+  process_rows<G, true>(arena + ch.k_data, arena + ch.v_data, ch.rows, qp, pa, pm, smem);
+  merge::partial_stores_done();
+  __syncthreads();
+  merge::arrive_and_merge<kWG>(ma, ch.item, ch.slot0, ch.nslots, G, smem);
 }
 
 // Log-sum-exp merge of the partial results of one (item, query head).  512 threads: 4 slot groups x 128
@@ -291,39 +302,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_dense_kernel(DenseArgs a,
               a.out + qh * kHeadDim, a.lse ? a.lse + qh : nullptr);
 }
 
-__global__ __launch_bounds__(kMergeThreads) void merge_tiered_kernel(const float* __restrict__ part_acc,
-                                                                const float* __restrict__ part_ml,
-                                                                const int32_t* __restrict__ slot_begin,
-                                                                const int32_t* __restrict__ slot_count, int g,
-                                                                int hq, int hkv, float* __restrict__ out,
-                                                                float* __restrict__ lse) {
-  const int h = blockIdx.x % g;
-  const int item = blockIdx.x / g;
-  const int seq = item / hkv, head = item % hkv;
-  const int64_t qh = static_cast<int64_t>(seq) * hq + head * g + h;
-  merge_slots(part_acc, part_ml, slot_begin[item], slot_count[item], g, h, out + qh * kHeadDim,
-              lse ? lse + qh : nullptr);
-}
-
-// The same merge for launches of few items: the slot tables travel in the kernel arguments, so the kernel's first
-// loads are the partials themselves (one dependent memory round trip less on a latency-bound per-layer decode).
-constexpr int kSmallMergeItems = 16;
-struct SmallSlots {
-  int32_t begin[kSmallMergeItems], count[kSmallMergeItems];
-};
-__global__ __launch_bounds__(kMergeThreads) void merge_tiered_small_kernel(const float* __restrict__ part_acc,
-                                                                      const float* __restrict__ part_ml,
-                                                                      SmallSlots slots, int g, int hq, int hkv,
-                                                                      float* __restrict__ out,
-                                                                      float* __restrict__ lse) {
-  const int h = blockIdx.x % g;
-  const int item = blockIdx.x / g;
-  const int seq = item / hkv, head = item % hkv;
-  const int64_t qh = static_cast<int64_t>(seq) * hq + head * g + h;
-  merge_slots(part_acc, part_ml, slots.begin[item], slots.count[item], g, h, out + qh * kHeadDim,
-              lse ? lse + qh : nullptr);
-}
-
 }  // namespace
 
 hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
@@ -344,48 +322,62 @@ hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipS
 }
 
 hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                      float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st) {
-  const int g = hq / hkv;
+                                      const MergeArgs& ma, hipStream_t st) {
+  const int g = ma.hq / ma.hkv;
   if (n_chunks == 0) return hipSuccess;
   dim3 grid(n_chunks), block(kWG);
   switch (g) {
-    case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
-    case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
-    case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
-    case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, part_acc, part_ml, hq, hkv); break;
+    case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, ma); break;
+    case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, ma); break;
+    case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, ma); break;
+    case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, ma); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
-// Zone C: one new bf16 K row and V row per item, scattered into the item's tail at token index `row`.  The tail
-// is kept in the 64-token tiles the decode kernels read (see process_tail_tiles): per item tail_tiles tiles of
-// 16 KiB for K, then (after the K tiles of all items) the same for V.
+// Zone C: one new bf16 K row and V row per item, scattered into the item's tail at the token index held in the
+// cache's device word tail_state[0] (so that a captured launch appends at the right place on every replay).  The
+// tail is kept in the 64-token tiles the decode kernels read (see process_tail_tiles): per item tail_tiles tiles of
+// 16 KiB for K, then (after the K tiles of all items) the same for V.  tail_state[1] counts the workgroups that are
+// done: the last one advances the length and clears the count.  A full tail is left as it is.
 __global__ __launch_bounds__(256) void append_rows_kernel(const uint16_t* __restrict__ k_new,
                                                           const uint16_t* __restrict__ v_new, uint8_t* __restrict__ tail,
-                                                          int64_t n_items, int32_t tail_tiles, int32_t row) {
+                                                          int64_t n_items, int32_t tail_tiles, int32_t tail_cap,
+                                                          int32_t* tail_state) {
   const int64_t item = blockIdx.x;
   const int t = threadIdx.x;
+  const int row = __hip_atomic_load(tail_state, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   const int tile = row >> 6, r = row & 63;
   constexpr int kTileBytes = 64 * kHeadDim * 2;
-  if (t < 16) {          // K: words 4t .. 4t+3 of the token's row = 16 bytes at 1024 t + 16 r
-    const uint4 v = *reinterpret_cast<const uint4*>(k_new + item * kHeadDim + t * 8);
-    uint8_t* dst = tail + (item * tail_tiles + tile) * static_cast<int64_t>(kTileBytes) + 1024 * t + 16 * r;
-    *reinterpret_cast<uint4*>(dst) = v;
-  } else if (t >= 128) {  // V: channel c of the token: unit u = 4 (c / 32) + (r % 32) / 8, lane 32 (r / 32) + c % 32
-    const int c = t - 128;
-    const int lane = 32 * (r >> 5) + (c & 31), u = 4 * (c >> 5) + ((r & 31) >> 3);
-    uint8_t* dst = tail + ((n_items + item) * tail_tiles + tile) * static_cast<int64_t>(kTileBytes) + 1024 * u +
-                   16 * lane + 2 * (r & 7);
-    *reinterpret_cast<uint16_t*>(dst) = v_new[item * kHeadDim + c];
+  if (row < tail_cap) {
+    if (t < 16) {          // K: words 4t .. 4t+3 of the token's row = 16 bytes at 1024 t + 16 r
+      const uint4 v = *reinterpret_cast<const uint4*>(k_new + item * kHeadDim + t * 8);
+      uint8_t* dst = tail + (item * tail_tiles + tile) * static_cast<int64_t>(kTileBytes) + 1024 * t + 16 * r;
+      *reinterpret_cast<uint4*>(dst) = v;
+    } else if (t >= 128) {  // V: channel c of the token: unit u = 4 (c / 32) + (r % 32) / 8, lane 32 (r / 32) + c % 32
+      const int c = t - 128;
+      const int lane = 32 * (r >> 5) + (c & 31), u = 4 * (c >> 5) + ((r & 31) >> 3);
+      uint8_t* dst = tail + ((n_items + item) * tail_tiles + tile) * static_cast<int64_t>(kTileBytes) + 1024 * u +
+                     16 * lane + 2 * (r & 7);
+      *reinterpret_cast<uint16_t*>(dst) = v_new[item * kHeadDim + c];
+    }
+  }
+  __syncthreads();         // every thread has read the length (and written its part of the row)
+  if (t == 0) {
+    const int done = __hip_atomic_fetch_add(tail_state + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (done == static_cast<int>(n_items) - 1) {   // every workgroup has read the length: advance it
+      __hip_atomic_store(tail_state + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (row < tail_cap) __hip_atomic_store(tail_state, row + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 }
 
 hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint8_t* tail, int64_t n_items,
-                              int32_t tail_tiles, int32_t row, hipStream_t st) {
+                              int32_t tail_tiles, int32_t tail_cap, int32_t* tail_state, hipStream_t st) {
   if (n_items == 0) return hipSuccess;
   hipLaunchKernelGGL(append_rows_kernel, dim3(static_cast<unsigned>(n_items)), dim3(256), 0, st, k_new, v_new, tail,
-                     n_items, tail_tiles, row);
+                     n_items, tail_tiles, tail_cap, tail_state);
   return hipGetLastError();
 }
 
@@ -425,26 +417,6 @@ hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t
   if (n_items == 0 || n == 0) return hipSuccess;
   hipLaunchKernelGGL(gather_tail_rows_kernel, dim3((n + 63) / 64, static_cast<unsigned>(n_items)), dim3(256), 0, st,
                      tail, n_items, tail_tiles, n, k_rows, v_rows);
-  return hipGetLastError();
-}
-
-hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
-                                      const int32_t* slot_count, const int32_t* h_slot_begin,
-                                      const int32_t* h_slot_count, int n_items, int hq, int hkv, float* out,
-                                      float* lse, hipStream_t st) {
-  const int g = hq / hkv;
-  if (n_items <= kSmallMergeItems && h_slot_begin && h_slot_count) {
-    SmallSlots s{};
-    for (int i = 0; i < n_items; ++i) {
-      s.begin[i] = h_slot_begin[i];
-      s.count[i] = h_slot_count[i];
-    }
-    hipLaunchKernelGGL(merge_tiered_small_kernel, dim3(n_items * g), dim3(kMergeThreads), 0, st, part_acc, part_ml,
-                       s, g, hq, hkv, out, lse);
-    return hipGetLastError();
-  }
-  hipLaunchKernelGGL(merge_tiered_kernel, dim3(n_items * g), dim3(kMergeThreads), 0, st, part_acc, part_ml,
-                     slot_begin, slot_count, g, hq, hkv, out, lse);
   return hipGetLastError();
 }
 

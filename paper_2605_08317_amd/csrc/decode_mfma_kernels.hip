@@ -35,15 +35,15 @@ template <int HS>
 struct Lds {
   static constexpr int kQop = HS * 4 * 8 * 4 * 8;
   static constexpr int kQsum = HS * 2 * 4 * 8;
-  static constexpr int kMl = kWaves * 8 * HS * 2 * 4;     // [4 waves][4 HS heads][m, l]
 };
 
-template <int TIER, int HS>
+// NWV wavefronts per workgroup interleave over the tiles of a chunk
+template <int TIER, int HS, int NWV>
 __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ km,
                                               const uint8_t* __restrict__ vd, const uint8_t* __restrict__ vm,
-                                              int rows, int g, const uint16_t* __restrict__ q,
-                                              float* __restrict__ part_acc, float* __restrict__ part_ml,
-                                              uint8_t* smem) {
+                                              int rows, int g, const uint16_t* __restrict__ q, const MergeArgs& ma,
+                                              const ChunkOut& co, uint8_t* smem) {
+  constexpr int kWG = NWV * 64, kWaves = NWV;
   using S = Step<TIER>;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -235,22 +235,19 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
 
   // ---- end of the chunk: undo the subnormal unit, add the offsets, merge the 4 wavefronts --------------------
-  finish_chunk<HS, false>(run, 16777216.0f, g, s_ml, s_acc, part_acc, part_ml);
+  finish_chunk<HS, false, NWV>(run, 16777216.0f, g, s_ml, s_acc, ma, co);
 }
 
-template <int HS>
-__global__ __launch_bounds__(kWG, HS == 1 ? 4 : 3) void decode_tiles_kernel(const Chunk* __restrict__ chunks,
-                                                                           const uint8_t* __restrict__ arena,
-                                                                           const uint16_t* __restrict__ q,
-                                                                           float* part_acc, float* part_ml, int hq,
-                                                                           int hkv, int row_limit) {
+template <int HS, int NWV>
+__global__ __launch_bounds__(NWV * 64, HS == 1 ? 4 : 3) void decode_tiles_kernel(
+    const Chunk* __restrict__ chunks, const uint8_t* __restrict__ arena, const uint16_t* __restrict__ q, MergeArgs ma,
+    const int32_t* __restrict__ tail_len) {
   extern __shared__ __align__(16) uint8_t smem[];
   const Chunk ch = chunks[blockIdx.x];
-  const int g = hq / hkv;
-  const int seq = ch.item / hkv, head = ch.item % hkv;
-  const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * g) * kHeadDim;
-  float* pa = part_acc + static_cast<int64_t>(ch.slot) * g * kHeadDim;
-  float* pm = part_ml + static_cast<int64_t>(ch.slot) * g * 2;
+  const int g = ma.hq / ma.hkv;
+  const int seq = ch.item / ma.hkv, head = ch.item % ma.hkv;
+  const uint16_t* qp = q + (static_cast<int64_t>(seq) * ma.hq + head * g) * kHeadDim;
+  const ChunkOut co{ch.item, ch.slot, ch.slot0, ch.nslots};
   const uint8_t* kd = arena + ch.k_data;
   const uint8_t* km = arena + ch.k_meta;
   const uint8_t* vd = arena + ch.v_data;
@@ -258,32 +255,37 @@ __global__ __launch_bounds__(kWG, HS == 1 ? 4 : 3) void decode_tiles_kernel(cons
   switch (ch.tier) {
     case kTierTail: {   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
       float* s_ml = reinterpret_cast<float*>(smem + Lds<HS>::kQop + Lds<HS>::kQsum);
-      process_tail_tiles<HS, false>(kd, vd, min(ch.rows, row_limit - ch.row0), g, qp, smem, s_ml,
-                                   s_ml + kWaves * 4 * HS * 2, pa, pm);
+      const int rows = max(0, min(ch.rows, *tail_len - ch.row0));
+      process_tail_tiles<HS, false, NWV>(kd, vd, rows, g, qp, smem, s_ml, s_ml + NWV * 4 * HS * 2, ma, co);
       break;
     }
-    case 8: process_tiles<8, HS>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
-    case 4: process_tiles<4, HS>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
-    default: process_tiles<2, HS>(kd, km, vd, vm, ch.rows, g, qp, pa, pm, smem); break;
+    case 8: process_tiles<8, HS, NWV>(kd, km, vd, vm, ch.rows, g, qp, ma, co, smem); break;
+    case 4: process_tiles<4, HS, NWV>(kd, km, vd, vm, ch.rows, g, qp, ma, co, smem); break;
+    default: process_tiles<2, HS, NWV>(kd, km, vd, vm, ch.rows, g, qp, ma, co, smem); break;
   }
+}
+
+template <int HS, int NWV>
+hipError_t launch_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
+                        const MergeArgs& ma, const int32_t* tail_len, hipStream_t st) {
+  const int g = ma.hq / ma.hkv;
+  const size_t merge_area = static_cast<size_t>(2 * NWV) * g * kHeadDim * sizeof(float);
+  static_assert(2 * NWV * 128 >= merge::merge_lds_floats(NWV * 64, 1), "the merge reuses the wavefront merge area");
+  const size_t lds = Lds<HS>::kQop + Lds<HS>::kQsum + NWV * 4 * HS * 2 * sizeof(float) + merge_area;
+  hipLaunchKernelGGL((decode_tiles_kernel<HS, NWV>), dim3(n_chunks), dim3(NWV * 64), lds, st, chunks, arena, q, ma,
+                     tail_len);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               float* part_acc, float* part_ml, int hq, int hkv, int row_limit, hipStream_t st) {
+                               const MergeArgs& ma, const int32_t* tail_len, int waves, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
-  const int g = hq / hkv;
-  const int hs = g > 4 ? 2 : 1;
-  const size_t lds = (hs == 1 ? Lds<1>::kQop + Lds<1>::kQsum : Lds<2>::kQop + Lds<2>::kQsum) +
-                     kWaves * 4 * hs * 2 * sizeof(float) + static_cast<size_t>(2 * kWaves) * g * kHeadDim * sizeof(float);
-  if (hs == 1)
-    hipLaunchKernelGGL(decode_tiles_kernel<1>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
-                       hq, hkv, row_limit);
-  else
-    hipLaunchKernelGGL(decode_tiles_kernel<2>, dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, q, part_acc, part_ml,
-                       hq, hkv, row_limit);
-  return hipGetLastError();
+  const int g = ma.hq / ma.hkv;
+  if (g > 4) return launch_tiles<2, 4>(chunks, n_chunks, arena, q, ma, tail_len, st);
+  if (waves == 8) return launch_tiles<1, 8>(chunks, n_chunks, arena, q, ma, tail_len, st);
+  return launch_tiles<1, 4>(chunks, n_chunks, arena, q, ma, tail_len, st);
 }
 
 }  // namespace rdkv

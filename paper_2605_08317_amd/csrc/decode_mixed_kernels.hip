@@ -30,6 +30,8 @@ namespace {
 
 using namespace tile;
 
+constexpr int kWaves = 4, kWG = 256;   // wavefronts and threads per workgroup
+
 // LDS: query operands per step [steps][HS][4 heads] x 8 bytes (raw bf16 for 16-bit steps, fp16 q * 2^(kQExp - fb)
 // for quantized ones), fp16 q * 2^kQExp per quantized step (for the offsets), then per wavefront the scaled-query
 // table [2 token groups][quantized steps][HS][4 heads] x 16 bytes (high terms, low terms).  The merge area of the
@@ -53,7 +55,7 @@ __device__ __forceinline__ int field_fb(int b, int f) { return b == 2 ? 2 * (f %
 template <int VT, int NW, int HS>
 __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __restrict__ arena,
                                               const ItemK* __restrict__ ikp, int g, const uint16_t* __restrict__ q,
-                                              float* __restrict__ part_acc, float* __restrict__ part_ml,
+                                              const MergeArgs& ma, const ChunkOut& co,
                                               uint8_t* smem, int lds_steps, int lds_qsteps, bool per_unit) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -426,48 +428,49 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
     }
   }
 
-  finish_chunk<HS, true>(run, VT == 16 ? 1.0f : 16777216.0f, g, reinterpret_cast<float*>(smem),
-                         reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2, part_acc, part_ml);
+  finish_chunk<HS, true, kWaves>(run, VT == 16 ? 1.0f : 16777216.0f, g, reinterpret_cast<float*>(smem),
+                                 reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2, ma, co);
 }
 
 template <int NW, int HS>
 __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mixed_kernel(
     const Chunk* __restrict__ chunks, const uint8_t* __restrict__ arena, const ItemK* __restrict__ items_k,
-    const uint16_t* __restrict__ q, float* part_acc, float* part_ml, int hq, int hkv, int lds_steps,
-    int lds_qsteps, int row_limit, int per_unit) {
+    const uint16_t* __restrict__ q, MergeArgs ma, int lds_steps, int lds_qsteps, const int32_t* __restrict__ tail_len,
+    int per_unit) {
   extern __shared__ __align__(16) uint8_t smem[];
   const Chunk ch = chunks[blockIdx.x];
-  const int g = hq / hkv;
-  const int seq = ch.item / hkv, head = ch.item % hkv;
-  const uint16_t* qp = q + (static_cast<int64_t>(seq) * hq + head * g) * kHeadDim;
-  float* pa = part_acc + static_cast<int64_t>(ch.slot) * g * kHeadDim;
-  float* pm = part_ml + static_cast<int64_t>(ch.slot) * g * 2;
+  const int g = ma.hq / ma.hkv;
+  const int seq = ch.item / ma.hkv, head = ch.item % ma.hkv;
+  const uint16_t* qp = q + (static_cast<int64_t>(seq) * ma.hq + head * g) * kHeadDim;
+  const ChunkOut co{ch.item, ch.slot, ch.slot0, ch.nslots};
   const ItemK* ikp = items_k + ch.reserved;   // the K row layout of this chunk's (generation, item)
   switch (ch.tier) {
-    case kTierTail:   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
-      process_tail_tiles<HS, true>(arena + ch.k_data, arena + ch.v_data, min(ch.rows, row_limit - ch.row0), g, qp, smem,
-                                  reinterpret_cast<float*>(smem), reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2,
-                                  pa, pm);
+    case kTierTail: {   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
+      const int rows = max(0, min(ch.rows, *tail_len - ch.row0));
+      process_tail_tiles<HS, true, kWaves>(arena + ch.k_data, arena + ch.v_data, rows, g, qp, smem,
+                                           reinterpret_cast<float*>(smem),
+                                           reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2, ma, co);
       break;
-    case 16: process_mixed<16, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
-    case 8: process_mixed<8, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
-    case 4: process_mixed<4, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
-    default: process_mixed<2, NW, HS>(ch, arena, ikp, g, qp, pa, pm, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    }
+    case 16: process_mixed<16, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    case 8: process_mixed<8, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    case 4: process_mixed<4, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    default: process_mixed<2, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
   }
 }
 
 template <int NW, int HS>
 hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int lds_steps,
-                      int lds_qsteps, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv,
-                      int row_limit, int per_unit, hipStream_t st) {
-  const size_t lds = static_cast<size_t>(LdsPlan(lds_steps, lds_qsteps, HS, hq / hkv).total);
+                      int lds_qsteps, const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, int per_unit,
+                      hipStream_t st) {
+  const size_t lds = static_cast<size_t>(LdsPlan(lds_steps, lds_qsteps, HS, ma.hq / ma.hkv).total);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_mixed_kernel<NW, HS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((decode_mixed_kernel<NW, HS>), dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, items_k, q,
-                     part_acc, part_ml, hq, hkv, lds_steps, lds_qsteps, row_limit, per_unit);
+                     ma, lds_steps, lds_qsteps, tail_len, per_unit);
   return hipGetLastError();
 }
 
@@ -477,12 +480,11 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
 #define RDKV_MIXED_NAME(a_, b_) RDKV_MIXED_NAME2(a_, b_)
 hipError_t RDKV_MIXED_NAME(launch_decode_mixed_hs, RDKV_MIXED_HS)(
     const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int max_words, int max_steps,
-    int max_qsteps, const uint16_t* q, float* part_acc, float* part_ml, int hq, int hkv, int row_limit, int per_unit,
-    hipStream_t st) {
+    int max_qsteps, const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
-#define RDKV_MIXED_LAUNCH(NW_)                                                                                \
-  return launch_one<NW_, RDKV_MIXED_HS>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, part_acc, \
-                                        part_ml, hq, hkv, row_limit, per_unit, st)
+#define RDKV_MIXED_LAUNCH(NW_)                                                                             \
+  return launch_one<NW_, RDKV_MIXED_HS>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, ma, tail_len, \
+                                        per_unit, st)
   // kMaxKRowWords = 68 is the longest row a channel bit map can give (125 channels at 16 bits and one each at 8, 4
   // and 2 bits: 64 + 1 + 1 + 1 words, padded to an even count); the host refuses anything longer
   static_assert(kMaxKRowWords == 68, "the widest instantiation below must hold the longest K row");

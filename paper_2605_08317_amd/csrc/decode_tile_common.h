@@ -8,6 +8,7 @@
 //             block 8 + a to blocks 8..15 (cbsz = 3);  B = V codes: lane = (token half, channel of the group),
 //             4 tokens per step;  D: lane holds 4 heads of one channel, summed over its token half.
 #pragma once
+#include "decode_merge.h"
 #include "rdkv_internal.h"
 
 namespace rdkv {
@@ -17,8 +18,6 @@ typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWG = 256;
-constexpr int kWaves = 4;
 constexpr int kTile = 64;   // tokens per tile
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLogitScale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
@@ -287,16 +286,25 @@ __device__ __forceinline__ void pv_tile(const uint4 (&vraw)[TIER], const uint4& 
       vmeta, p, kappa, run);
 }
 
+// Where a chunk's partial result goes and what the merge of its item needs.
+struct ChunkOut {
+  int item, slot, slot0, nslots;   // the chunk's item and partial slot; the item's first slot and slot count
+};
+
 // End of a chunk: scale the accumulators back (acc_scale = 2^24 where the V codes entered as fp16 subnormals),
-// add the offset sums, merge the workgroup's four wavefronts through LDS and write the chunk's partial result.
-// s_ml: [kWaves][4 HS heads][m, l] floats; s_acc: [2 kWaves streams][g][128] floats.  ALIAS: the two areas overlap
-// LDS that the tile loop used, so a barrier separates the two uses.
-template <int HS, bool ALIAS>
+// add the offset sums, merge the workgroup's NWV wavefronts through LDS, store the chunk's partial result and
+// announce it; the workgroup that completes its item merges the item's partials (arrive_and_merge).
+// s_ml: [NWV][4 HS heads][m, l] floats; s_acc: [2 NWV streams][g][128] floats (also the merge's LDS).  ALIAS: the
+// two areas overlap LDS that the tile loop used, so a barrier separates the two uses.
+template <int HS, bool ALIAS, int NWV>
 __device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, int g, float* s_ml, float* s_acc,
-                                             float* __restrict__ part_acc, float* __restrict__ part_ml) {
+                                             const MergeArgs& ma, const ChunkOut& co) {
+  constexpr int NT = NWV * 64;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int th = lane >> 5, cl = lane & 31;
+  float* __restrict__ part_acc = ma.part_acc + static_cast<int64_t>(co.slot) * g * kHeadDim;
+  float* __restrict__ part_ml = ma.part_ml + static_cast<int64_t>(co.slot) * g * 2;
 #pragma unroll
   for (int hs = 0; hs < HS; ++hs) {
     run.l[hs] = head_sum(run.l[hs]);
@@ -325,7 +333,7 @@ __device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, int 
       const int head = 4 * hs + i;
       float mm = kNegBig;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
+      for (int w = 0; w < NWV; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
       const float f = fast_exp2(s_ml[((wave * HS + hs) * 4 + i) * 2] - mm);
       if (head < g) {
 #pragma unroll
@@ -334,24 +342,27 @@ __device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, int 
       }
     }
   __syncthreads();
-  for (int idx = tid; idx < g * kHeadDim; idx += kWG) {
+  for (int idx = tid; idx < g * kHeadDim; idx += NT) {
     float v = 0.f;
 #pragma unroll
-    for (int w = 0; w < 2 * kWaves; ++w) v += s_acc[w * g * kHeadDim + idx];
-    part_acc[idx] = v;
+    for (int w = 0; w < 2 * NWV; ++w) v += s_acc[w * g * kHeadDim + idx];
+    merge::store_agent(part_acc + idx, v);
   }
   if (tid < g) {
     const int hs = tid >> 2, i = tid & 3;
     float mm = kNegBig;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
+    for (int w = 0; w < NWV; ++w) mm = fmaxf(mm, s_ml[((w * HS + hs) * 4 + i) * 2]);
     float ll = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w)
+    for (int w = 0; w < NWV; ++w)
       ll += s_ml[((w * HS + hs) * 4 + i) * 2 + 1] * fast_exp2(s_ml[((w * HS + hs) * 4 + i) * 2] - mm);
-    part_ml[tid * 2] = mm;
-    part_ml[tid * 2 + 1] = ll;
+    merge::store_agent(part_ml + tid * 2, mm);
+    merge::store_agent(part_ml + tid * 2 + 1, ll);
   }
+  merge::partial_stores_done();
+  __syncthreads();     // every partial store has landed, and nobody reads s_ml / s_acc any more
+  merge::arrive_and_merge<NT>(ma, co.item, co.slot0, co.nslots, g, s_acc);
 }
 
 // A chunk of appended tokens (Sec. 3.3 Zone C: bf16 rows kept after the compression pass) on the same instruction
@@ -360,11 +371,12 @@ __device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, int 
 // with sixteen coalesced 16-byte loads; V tile = 16 KiB in the layout of the 16-bit V tiles of mixed mode (lane
 // 32 (r / 32) + c % 32 holds channel c, eight tokens per 16-byte unit u = 4 (c / 32) + (r % 32) / 8 at 1024 u).
 // s_q: LDS for the query operands, [32 steps][HS][4 heads] x 8 bytes (raw bf16; the products are exact).
-template <int HS, bool ALIAS>
+template <int HS, bool ALIAS, int NWV>
 __device__ __forceinline__ void process_tail_tiles(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ vd,
                                                    int rows, int g, const uint16_t* __restrict__ q, uint8_t* s_q,
-                                                   float* s_ml, float* s_acc, float* __restrict__ part_acc,
-                                                   float* __restrict__ part_ml) {
+                                                   float* s_ml, float* s_acc, const MergeArgs& ma,
+                                                   const ChunkOut& co) {
+  constexpr int kWG = NWV * 64, kWaves = NWV;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int blk = lane >> 2, j = lane & 3;
@@ -445,7 +457,7 @@ __device__ __forceinline__ void process_tail_tiles(const uint8_t* __restrict__ k
 #undef RDKV_TAIL_GROUP
 #undef RDKV_TAIL_STEP
   }
-  finish_chunk<HS, ALIAS>(run, 1.0f, g, s_ml, s_acc, part_acc, part_ml);
+  finish_chunk<HS, ALIAS, NWV>(run, 1.0f, g, s_ml, s_acc, ma, co);
 }
 
 }  // namespace tile

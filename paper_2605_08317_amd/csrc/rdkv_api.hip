@@ -11,6 +11,7 @@
 #include <new>
 #include <utility>
 
+#include "decode_merge.h"
 #include "rdkv_internal.h"
 
 namespace rdkv {
@@ -318,10 +319,9 @@ void free_cache_buffers(rdkv_cache* c) {
   al.put(c->d_arena);
   al.put(c->d_tier_idx);
   al.put(c->d_chunks);
-  al.put(c->d_slot_begin);
-  al.put(c->d_slot_count);
-  al.put(c->d_part_acc);
-  al.put(c->d_part_ml);
+  for (const rdkv_cache::Workspace& w : c->workspaces) al.put(w.block);
+  c->workspaces.clear();
+  al.put(c->d_tail_state);
   al.put(c->d_bits_tok);
   al.put(c->d_bits_ch);
   al.put(c->d_items_k);
@@ -334,6 +334,77 @@ void free_cache_buffers(rdkv_cache* c) {
     delete child;
   }
   c->absorbed.clear();
+}
+
+// The split workspace of a cache for one stream (created on first use).  Calls on one stream are serialised by
+// the stream and share a workspace; calls on different streams get different ones, so they may overlap.
+rdkv_status workspace_for(const rdkv_cache* c, hipStream_t st, rdkv_cache::Workspace* out) {
+  std::lock_guard<std::mutex> lk(c->ws_mu);
+  for (const rdkv_cache::Workspace& w : c->workspaces)
+    if (w.stream == st) { *out = w; return RDKV_OK; }
+  // A stream under graph capture cannot allocate, and frameworks capture on streams of their own: a captured step
+  // uses the cache's first workspace (the one of the stream that built the schedule).
+  if (st != nullptr && !c->workspaces.empty()) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) == hipSuccess && cs == hipStreamCaptureStatusActive) {
+      *out = c->workspaces.front();
+      return RDKV_OK;
+    }
+  }
+  Allocator al{c->alloc, c->free_, c->alloc_user};
+  const int g = c->hq / c->hkv;
+  const size_t slots = static_cast<size_t>(std::max<int64_t>(c->n_slots, 1));
+  const size_t acc_b = slots * g * kHeadDim * sizeof(float), ml_b = (slots * g * 2 * sizeof(float) + 255) / 256 * 256;
+  const size_t arr_b = static_cast<size_t>(std::max<int64_t>(c->n_items, 1)) * sizeof(int32_t);
+  uint8_t* block = static_cast<uint8_t*>(al.get(acc_b + ml_b + arr_b));
+  if (!block) return fail(RDKV_ERR_ALLOC, "device allocation of a split workspace failed");
+  rdkv_cache::Workspace w{st, reinterpret_cast<float*>(block), reinterpret_cast<float*>(block + acc_b),
+                          reinterpret_cast<int32_t*>(block + acc_b + ml_b), block};
+  const hipError_t e = hipMemsetAsync(w.arrive, 0, arr_b, st);     // counters start at zero; the kernels keep them so
+  if (e != hipSuccess) {
+    al.put(block);
+    return fail(RDKV_ERR_HIP, "clearing a split workspace: %s", hipGetErrorString(e));
+  }
+  c->workspaces.push_back(w);
+  *out = w;
+  return RDKV_OK;
+}
+
+void drop_workspaces(rdkv_cache* c) {
+  std::lock_guard<std::mutex> lk(c->ws_mu);
+  Allocator al{c->alloc, c->free_, c->alloc_user};
+  for (const rdkv_cache::Workspace& w : c->workspaces) al.put(w.block);
+  c->workspaces.clear();
+}
+
+// Launch order of a decode kernel's chunks.  Large launches: tier by tier, lowest bit-width first and largest first
+// inside a tier, so that the chunks that cost most time per byte start first and the last to finish are 8-bit ones
+// (measured 4-5 % faster on a mixed-tier batch than plain size order).  Launches that fit the chip in one round:
+// round-robin over the items, so that with the usual round-robin placement of workgroups on the eight XCDs the
+// chunks of an item share an L2 (which then also holds the partials their merge reads); only speed depends on it.
+void order_chunks(std::vector<Chunk>::iterator first, std::vector<Chunk>::iterator last, int64_t n_items) {
+  const int64_t count = last - first;
+  std::stable_sort(first, last, [](const Chunk& x, const Chunk& y) {
+    if (x.tier != y.tier) return x.tier < y.tier;
+    return static_cast<int64_t>(x.rows) * x.tier > static_cast<int64_t>(y.rows) * y.tier;
+  });
+  bool round_robin = count <= 1024 && n_items > 1;
+  if (const char* e = std::getenv("RDKV_ORDER")) round_robin = std::strcmp(e, "xcd") == 0;
+  if (!round_robin) return;
+  std::vector<std::vector<Chunk>> by_item(static_cast<size_t>(n_items));
+  for (auto it = first; it != last; ++it) by_item[it->item].push_back(*it);
+  auto out = first;
+  for (size_t k = 0; out != last; ++k)
+    for (int64_t i = 0; i < n_items; ++i)
+      if (k < by_item[i].size()) *out++ = by_item[i][k];
+}
+
+// every chunk learns its item's first partial slot and slot count (the merge inside the decode kernels needs them)
+void stamp_slots(std::vector<Chunk>& table, const std::vector<int32_t>& slot_begin, const std::vector<int32_t>& slot_count) {
+  for (Chunk& ch : table) {
+    ch.slot0 = slot_begin[ch.item];
+    ch.nslots = slot_count[ch.item];
+  }
 }
 
 // Sorted-channel layout of one item's K tiles from its channel bit map.
@@ -498,7 +569,6 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
                       hipStream_t st, rdkv_cache** out) {
   const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
-  const int g = cfg->hq / cfg->hkv;
 
   rdkv_cache* c = new (std::nothrow) rdkv_cache();
   if (!c) return fail(RDKV_ERR_ALLOC, "host allocation failed");
@@ -610,11 +680,18 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   c->kept_total = kept;
   c->stored_bytes = stored;
 
-  // byte-balanced chunks: every workgroup streams about the same number of stored bytes
-  // (a mixed-mode chunk has more set-up per workgroup, and its kernel keeps 3 workgroups per CU resident:
-  // 40 KB chunks keep a single 64K-token sequence within one round of workgroups)
-  int64_t chunk_bytes = std::min<int64_t>(1 << 20, std::max<int64_t>((mixed ? 40 : 24) << 10, stored / 2048));
+  // byte-balanced chunks: every workgroup streams about the same number of stored bytes.  A large launch (many
+  // rounds of workgroups) wants small chunks: 1/2048 of the bytes, at least 24 KB (40 KB in channel-wise mode, whose
+  // workgroups have more set-up).  A launch that fits the chip in one round is bound by latencies, and every chunk
+  // costs its item one more arrival and one more partial to merge: about 170 chunks of at least 48 KB, streamed by
+  // workgroups of eight wavefronts (measured on a 16 MB layer: 96 KB chunks 12.6 us, 64 KB 13.4 us, 24 KB 20 us).
+  const bool small_launch = stored < (static_cast<int64_t>(96) << 20);
+  // (the channel-wise kernel's workgroups have four wavefronts: twice the chunks for the same number of wavefronts)
+  int64_t chunk_bytes = small_launch ? std::max<int64_t>(48 << 10, stored / (mixed ? 340 : 170))
+                                     : std::min<int64_t>(1 << 20, std::max<int64_t>((mixed ? 40 : 24) << 10, stored / 2048));
+  c->decode_waves = small_launch ? 8 : 4;
   if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
+  if (const char* e = std::getenv("RDKV_WAVES")) c->decode_waves = std::atoi(e) == 8 ? 8 : 4;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
   for (int64_t i = 0; i < n; ++i) {
     slot_begin[i] = static_cast<int32_t>(c->chunks.size());
@@ -631,7 +708,7 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
       const int64_t* so = &c->seg_off[(i * 4 + ti) * 4];
       for (int64_t r0 = 0; r0 < cnt; r0 += rows_per) {
-        Chunk ch;
+        Chunk ch{};
         ch.k_data = so[0] + (mixed ? r0 / kTile64 * c->items_k[i].kt_bytes : r0 * tier_row_bytes(bits));
         ch.k_meta = so[1] + (mixed ? (c->k_per_unit ? 0 : r0 / kTile64 * c->items_k[i].km_bytes)
                                    : r0 * tier_meta_bytes(bits));
@@ -647,18 +724,28 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
         c->chunks.push_back(ch);
       }
     }
+    if (static_cast<int32_t>(c->chunks.size()) == slot_begin[i]) {
+      // nothing retained: an empty chunk, so that a workgroup still writes the item's output rows (0, lse = -inf)
+      Chunk ch{};
+      ch.tier = 2;
+      ch.item = static_cast<int32_t>(i);
+      ch.slot = static_cast<int32_t>(c->chunks.size());
+      ch.reserved = static_cast<int32_t>(i);
+      c->chunks.push_back(ch);
+    }
     slot_count[i] = static_cast<int32_t>(c->chunks.size()) - slot_begin[i];
   }
   const int64_t n_chunks = static_cast<int64_t>(c->chunks.size());
-  // launch order: 16-bit chunks first (their own kernel), then the quantized chunks tier by tier, lowest width
-  // first and largest first inside a tier: the chunks that cost most time per byte start first and the last to
-  // finish are 8-bit ones (measured 4-5 % faster on a mixed-tier batch than plain size order)
-  std::stable_sort(c->chunks.begin(), c->chunks.end(), [](const Chunk& x, const Chunk& y) {
-    const bool x16 = x.tier == 16, y16 = y.tier == 16;
-    if (x16 != y16) return x16;
-    if (x.tier != y.tier) return x.tier < y.tier;
-    return static_cast<int64_t>(x.rows) * x.tier > static_cast<int64_t>(y.rows) * y.tier;
-  });
+  c->n_slots = n_chunks;
+  stamp_slots(c->chunks, slot_begin, slot_count);
+  // 16-bit chunks first (their own kernel), then the quantized ones
+  std::stable_partition(c->chunks.begin(), c->chunks.end(), [](const Chunk& x) { return x.tier == 16; });
+  {
+    int64_t n16 = 0;
+    for (const Chunk& ch : c->chunks) n16 += ch.tier == 16;
+    order_chunks(c->chunks.begin(), c->chunks.begin() + n16, n);
+    order_chunks(c->chunks.begin() + n16, c->chunks.end(), n);
+  }
   c->n_chunks16 = 0;
   for (const Chunk& ch : c->chunks) c->n_chunks16 += ch.tier == 16;
   c->sched16 = c->n_chunks16;
@@ -669,18 +756,14 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   c->d_arena = static_cast<uint8_t*>(al.get(c->arena_bytes));
   c->d_tier_idx = static_cast<int32_t*>(al.get(std::max<int64_t>(kept, 1) * sizeof(int32_t)));
   c->d_chunks = static_cast<Chunk*>(al.get(std::max<int64_t>(n_chunks, 1) * sizeof(Chunk)));
-  c->d_slot_begin = static_cast<int32_t*>(al.get(std::max<int64_t>(n, 1) * sizeof(int32_t)));
-  c->d_slot_count = static_cast<int32_t*>(al.get(std::max<int64_t>(n, 1) * sizeof(int32_t)));
-  c->d_part_acc = static_cast<float*>(al.get(std::max<int64_t>(n_chunks, 1) * g * kHeadDim * sizeof(float)));
-  c->d_part_ml = static_cast<float*>(al.get(std::max<int64_t>(n_chunks, 1) * g * 2 * sizeof(float)));
+  c->d_tail_state = static_cast<int32_t*>(al.get(2 * sizeof(int32_t)));
   c->d_bits_tok = static_cast<uint8_t*>(al.get(std::max<int64_t>(it.total_tokens, 1)));
   if (mixed) {
     c->d_bits_ch = static_cast<uint8_t*>(al.get(std::max<int64_t>(n, 1) * kHeadDim));
     c->d_items_k = static_cast<ItemK*>(al.get(std::max<int64_t>(n, 1) * sizeof(ItemK)));
     if (!c->d_bits_ch || !c->d_items_k) return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
   }
-  if (!c->d_arena || !c->d_tier_idx || !c->d_chunks || !c->d_slot_begin || !c->d_slot_count || !c->d_part_acc ||
-      !c->d_part_ml || !c->d_bits_tok)
+  if (!c->d_arena || !c->d_tier_idx || !c->d_chunks || !c->d_tail_state || !c->d_bits_tok)
     return bail(fail(RDKV_ERR_ALLOC, "device allocation of the packed cache failed (%lld arena bytes)",
                      static_cast<long long>(c->arena_bytes)));
   c->index_bytes = kept * 4 + n_chunks * static_cast<int64_t>(sizeof(Chunk)) + n * 8 + n * 16 * 8;
@@ -693,8 +776,12 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
     if (n_chunks > 0) PACK_HIP(upload(c->d_chunks, c->chunks.data(), n_chunks * sizeof(Chunk), st));
     c->slot_begin = slot_begin;
     c->slot_count = slot_count;
-    PACK_HIP(upload(c->d_slot_begin, slot_begin.data(), n * sizeof(int32_t), st));
-    PACK_HIP(upload(c->d_slot_count, slot_count.data(), n * sizeof(int32_t), st));
+    PACK_HIP(hipMemsetAsync(c->d_tail_state, 0, 2 * sizeof(int32_t), st));
+    {   // the split workspace of this stream, so that a first decode under graph capture allocates nothing
+      rdkv_cache::Workspace w;
+      const rdkv_status ws = workspace_for(c, st, &w);
+      if (ws != RDKV_OK) return bail(ws);
+    }
     if (it.total_tokens > 0)
       PACK_HIP(hipMemcpyAsync(c->d_bits_tok, bits_tok, it.total_tokens, hipMemcpyDeviceToDevice, st));
     if (mixed) {
@@ -1005,42 +1092,29 @@ size_t rdkv_cache_max_bytes(const rdkv_config* cfg) {
   return cache_max_bytes(cfg);
 }
 
-// Zone C: chunks of appended tokens that exist so far (they follow the other chunks in the chunk table)
-static int live_tail_chunks(const rdkv_cache* c) {
-  return (c->tail_len + kTailChunkRows - 1) / kTailChunkRows * static_cast<int>(c->n_items);
-}
-
 rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, float* lse, void* stream) {
   if (!c || !q || !out) return fail(RDKV_ERR_INVALID_ARG, "cache, q and out must not be null");
   if (c->n_items == 0) return RDKV_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  rdkv_cache::Workspace w;
+  const rdkv_status ws = workspace_for(c, st, &w);
+  if (ws != RDKV_OK) return ws;
+  const MergeArgs ma{w.part_acc, w.part_ml, w.arrive, out, lse, c->hq, c->hkv};
+  // every chunk of the schedule is launched, the tail's included: chunks of tail rows that do not exist yet find
+  // the current length in the cache's device word and contribute an empty partial
+  const int n16 = static_cast<int>(c->sched16), nrest = static_cast<int>(c->schedq + c->n_tail_chunks);
+  TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
   if (c->k_mode == RDKV_K_CHANNELWISE) {
-    {
-      TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
-      RDKV_HIP(launch_decode_mixed(c->d_chunks, static_cast<int>(c->sched16 + c->schedq) + live_tail_chunks(c), c->d_arena,
-                                   c->d_items_sched ? c->d_items_sched : c->d_items_k,
-                                   std::max(c->max_k_words, c->sched_k_words), std::max(c->max_k_steps, c->sched_k_steps),
-                                   std::max(c->max_k_qsteps, c->sched_k_qsteps),
-                                   static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml,
-                                   c->hq, c->hkv, c->tail_len, c->k_per_unit, st));
-    }
-    RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
-                                        c->slot_begin.data(), c->slot_count.data(), static_cast<int>(c->n_items),
-                                        c->hq, c->hkv, out, lse, st));
+    RDKV_HIP(launch_decode_mixed(c->d_chunks, n16 + nrest, c->d_arena, c->d_items_sched ? c->d_items_sched : c->d_items_k,
+                                 std::max(c->max_k_words, c->sched_k_words), std::max(c->max_k_steps, c->sched_k_steps),
+                                 std::max(c->max_k_qsteps, c->sched_k_qsteps), static_cast<const uint16_t*>(q), ma,
+                                 c->d_tail_state, c->k_per_unit, st));
     return RDKV_OK;
   }
-  {
-    TimedScope ts(RDKV_TIME_DECODE_TIERED, st);
-    const int n16 = static_cast<int>(c->sched16), nq = static_cast<int>(c->schedq);
-    RDKV_HIP(launch_decode_tiered_split(c->d_chunks, n16, c->d_arena, static_cast<const uint16_t*>(q),
-                                        c->d_part_acc, c->d_part_ml, c->hq, c->hkv, st));
-    RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nq + live_tail_chunks(c), c->d_arena,
-                                 static_cast<const uint16_t*>(q), c->d_part_acc, c->d_part_ml, c->hq, c->hkv,
-                                 c->tail_len, st));
-  }
-  RDKV_HIP(launch_decode_tiered_merge(c->d_part_acc, c->d_part_ml, c->d_slot_begin, c->d_slot_count,
-                                      c->slot_begin.data(), c->slot_count.data(), static_cast<int>(c->n_items),
-                                      c->hq, c->hkv, out, lse, st));
+  // the workgroups of both kernels announce themselves on the same counters: whichever finishes an item merges it
+  RDKV_HIP(launch_decode_tiered_split(c->d_chunks, n16, c->d_arena, static_cast<const uint16_t*>(q), ma, st));
+  RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nrest, c->d_arena, static_cast<const uint16_t*>(q), ma,
+                               c->d_tail_state, c->decode_waves, st));
   return RDKV_OK;
 }
 
@@ -1052,7 +1126,6 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
 static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
   Allocator al{c->alloc, c->free_, c->alloc_user};
   const int64_t n = c->n_items;
-  const int g = c->hq / c->hkv;
   const int npi = (c->tail_cap + kTailChunkRows - 1) / kTailChunkRows;     // tail chunks per item
   std::vector<const rdkv_cache*> gens{c};
   gens.insert(gens.end(), c->absorbed.begin(), c->absorbed.end());
@@ -1108,6 +1181,11 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
       ch.row0 = j * kTailChunkRows;
       table.push_back(ch);
     }
+  // launch order inside each kernel's range; the tail's chunks stay last
+  order_chunks(table.begin(), table.begin() + n16, n);
+  order_chunks(table.begin() + n16, table.begin() + n_gen_chunks, n);
+  stamp_slots(table, nb, nc);
+  stamp_slots(own, nb, nc);
   const int64_t n_table = static_cast<int64_t>(table.size());
   // channel-wise K: every (generation, item) has its own sorted-channel row layout
   const bool mixed = c->k_mode == RDKV_K_CHANNELWISE;
@@ -1125,41 +1203,28 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
     if (!d_items_sched) return fail(RDKV_ERR_ALLOC, "device allocation failed");
   }
   Chunk* d_chunks = static_cast<Chunk*>(al.get(std::max<int64_t>(n_table, 1) * sizeof(Chunk)));
-  float* d_acc = static_cast<float*>(al.get(std::max<int64_t>(n_slots, 1) * g * kHeadDim * sizeof(float)));
-  float* d_ml = static_cast<float*>(al.get(std::max<int64_t>(n_slots, 1) * g * 2 * sizeof(float)));
-  if (!d_chunks || !d_acc || !d_ml) {
-    al.put(d_chunks); al.put(d_acc); al.put(d_ml); al.put(d_items_sched);
+  if (!d_chunks) {
+    al.put(d_items_sched);
     return fail(RDKV_ERR_ALLOC, "device allocation failed");
   }
-  // slots of tail chunks that no launch has reached yet must read as empty partials: m = -1e30, l = 0, acc = 0
-  std::vector<float> ml(static_cast<size_t>(n_slots) * g * 2, 0.f);
-  for (size_t k = 0; k < ml.size(); k += 2) ml[k] = -1.0e30f;
   hipError_t e = hipSuccess;
-  if (n_slots > 0) {
-    e = hipMemsetAsync(d_acc, 0, n_slots * g * kHeadDim * sizeof(float), st);
-    if (e == hipSuccess) e = hipMemcpyAsync(d_ml, ml.data(), ml.size() * sizeof(float), hipMemcpyHostToDevice, st);
-  }
-  if (e == hipSuccess && n_table > 0)
-    e = hipMemcpyAsync(d_chunks, table.data(), table.size() * sizeof(Chunk), hipMemcpyHostToDevice, st);
+  if (n_table > 0) e = upload(d_chunks, table.data(), table.size() * sizeof(Chunk), st);
   if (e == hipSuccess && d_items_sched)
-    e = hipMemcpyAsync(d_items_sched, items_sched.data(), items_sched.size() * sizeof(ItemK), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_begin, nb.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipMemcpyAsync(c->d_slot_count, nc.data(), n * sizeof(int32_t), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipStreamSynchronize(st);     // the host vectors above go out of scope
+    e = upload(d_items_sched, items_sched.data(), items_sched.size() * sizeof(ItemK), st);
+  // the stream must be idle before the old tables and workspaces go: a decode step may still be reading them
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
-    al.put(d_chunks); al.put(d_acc); al.put(d_ml); al.put(d_items_sched);
+    al.put(d_chunks); al.put(d_items_sched);
     return fail(RDKV_ERR_HIP, "rebuilding the decode schedule: %s", hipGetErrorString(e));
   }
-  al.put(c->d_part_acc);
-  al.put(c->d_part_ml);
+  drop_workspaces(c);      // the slot count changed: workspaces are created again on first use
+  c->n_slots = n_slots;
   al.put(c->d_chunks);
   al.put(c->d_items_sched);
   c->d_items_sched = d_items_sched;
   c->sched_k_words = kw;
   c->sched_k_steps = ks;
   c->sched_k_qsteps = kq;
-  c->d_part_acc = d_acc;
-  c->d_part_ml = d_ml;
   c->d_chunks = d_chunks;
   c->sched16 = n16;
   c->schedq = n_gen_chunks - n16;
@@ -1167,6 +1232,8 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
   c->chunks.swap(own);
   c->slot_begin.swap(nb);
   c->slot_count.swap(nc);
+  rdkv_cache::Workspace w;   // this stream's workspace right away: a decode under graph capture then allocates nothing
+  (void)workspace_for(c, st, &w);   // (a failure here is reported by the decode call that needs the workspace)
   return RDKV_OK;
 }
 
@@ -1203,8 +1270,9 @@ rdkv_status rdkv_cache_append(rdkv_cache* c, const void* k_new, const void* v_ne
   if (c->tail_cap == 0) return fail(RDKV_ERR_INVALID_ARG, "call rdkv_cache_reserve_tail before the first append");
   if (c->tail_len >= c->tail_cap)
     return fail(RDKV_ERR_INVALID_ARG, "the tail is full (%d tokens reserved)", c->tail_cap);
+  if (c->n_items == 0) { c->tail_len += 1; return RDKV_OK; }
   RDKV_HIP(launch_append_rows(static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), c->d_tail,
-                              c->n_items, (c->tail_cap + kTile64 - 1) / kTile64, c->tail_len,
+                              c->n_items, (c->tail_cap + kTile64 - 1) / kTile64, c->tail_cap, c->d_tail_state,
                               static_cast<hipStream_t>(stream)));
   c->tail_len += 1;
   return RDKV_OK;
@@ -1212,11 +1280,28 @@ rdkv_status rdkv_cache_append(rdkv_cache* c, const void* k_new, const void* v_ne
 
 int32_t rdkv_cache_tail_len(const rdkv_cache* c) { return c ? c->tail_len : 0; }
 
+rdkv_status rdkv_cache_tail_len_sync(rdkv_cache* c, void* stream, int32_t* out) {
+  if (!c) return fail(RDKV_ERR_INVALID_ARG, "cache is null");
+  if (c->n_items > 0 && c->d_tail_state) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t n = 0;
+    RDKV_HIP(hipMemcpyAsync(&n, c->d_tail_state, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    RDKV_HIP(hipStreamSynchronize(st));
+    c->tail_len = n;
+  }
+  if (out) *out = c->tail_len;
+  return RDKV_OK;
+}
+
 rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, const void* Q_obs, void* stream) {
   if (!c || !cfg || !Q_obs) return fail(RDKV_ERR_INVALID_ARG, "cache, cfg and Q_obs must not be null");
   if (cfg->k_mode != c->k_mode || (c->k_mode == RDKV_K_CHANNELWISE && (cfg->k_scale_per_channel != 0) != (c->k_per_unit != 0)))
     return fail(RDKV_ERR_INVALID_ARG, "cfg must name the cache's own K format (k_mode %d, k_scale_per_channel %d)",
                 c->k_mode, c->k_per_unit);
+  {   // appends replayed from a captured graph advance only the device's count: take that one
+    const rdkv_status s0 = rdkv_cache_tail_len_sync(c, stream, nullptr);
+    if (s0 != RDKV_OK) return s0;
+  }
   if (c->tail_len <= 0) return fail(RDKV_ERR_INVALID_ARG, "no appended tokens to compress");
   if (cfg->batch != c->batch || cfg->hq != c->hq || cfg->hkv != c->hkv || cfg->head_dim != c->d)
     return fail(RDKV_ERR_SHAPE, "cfg (batch %d, hq %d, hkv %d, d %d) does not match the cache (%d, %d, %d, %d)",
@@ -1245,14 +1330,15 @@ rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, cons
   // The tail's tiles keep the rows just compressed: rows at or past tail_len are masked out of the softmax (their
   // values are finite, so a zero probability times a stale V row adds nothing), and later appends overwrite them.
   c->absorbed.push_back(child);
-  c->tail_len = 0;
   s = rebuild_schedule(c, st);
   if (s != RDKV_OK) {
     c->absorbed.pop_back();
-    c->tail_len = n_tail;
     rdkv_cache_free(child);
     return s;
   }
+  c->tail_len = 0;
+  const int32_t zeros[2] = {0, 0};
+  RDKV_HIP(upload(c->d_tail_state, zeros, sizeof(zeros), st));
   return RDKV_OK;
 }
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -34,6 +35,7 @@ struct Chunk {
   int32_t row0;                             // appended-token zone: first row of the chunk inside the item's tail
   int32_t reserved;                         // mixed mode: index of the chunk's ItemK in the schedule's table
                                             // (generation * items + item)
+  int32_t slot0, nslots;                    // the item's first partial slot and its number of slots (= chunks)
 };
 constexpr int kTailChunkRows = 256;         // appended tokens per decode work item
 constexpr int kTierTail = 17;               // Chunk::tier of a chunk of appended tokens (64-token tiles of bf16 rows)
@@ -70,35 +72,31 @@ struct DenseArgs {
 // ---- launchers implemented in the .hip files ------------------------------
 hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
 hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipStream_t st);
+struct MergeArgs;   // decode_merge.h
+// 16-bit tier of a token-wise cache (row-major bf16 rows)
 hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                      float* part_acc, float* part_ml, int hq, int hkv, hipStream_t st);
+                                      const MergeArgs& ma, hipStream_t st);
+// tail_state: the cache's device words {appended tokens so far, workgroups of the running append that are done}
 hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint8_t* tail, int64_t n_items,
-                              int32_t tail_tiles, int32_t row, hipStream_t st);
+                              int32_t tail_tiles, int32_t tail_cap, int32_t* tail_state, hipStream_t st);
 hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t tail_tiles, int32_t n,
                                    uint16_t* k_rows, uint16_t* v_rows, hipStream_t st);
-// h_slot_begin / h_slot_count: host copies of the two tables (used for launches of few items), or null
-hipError_t launch_decode_tiered_merge(const float* part_acc, const float* part_ml, const int32_t* slot_begin,
-                                      const int32_t* slot_count, const int32_t* h_slot_begin,
-                                      const int32_t* h_slot_count, int n_items, int hq, int hkv, float* out,
-                                      float* lse, hipStream_t st);
 
-// row_limit: appended tokens that exist so far (chunks of tier kTierTail end there)
+// tail_len: device word holding the appended tokens that exist so far (chunks of tier kTierTail end there);
+// waves: wavefronts per workgroup (4 or 8)
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               float* part_acc, float* part_ml, int hq, int hkv, int row_limit, hipStream_t st);
+                               const MergeArgs& ma, const int32_t* tail_len, int waves, hipStream_t st);
 // one object per head-set count (hs1: up to 4 query heads per KV head, hs2: 8)
 hipError_t launch_decode_mixed_hs1(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                                   float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st);
+                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q,
+                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st);
 hipError_t launch_decode_mixed_hs2(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                                   float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st);
+                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q,
+                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st);
+
 inline hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                                      int max_words, int max_steps, int max_qsteps, const uint16_t* q, float* part_acc,
-                                      float* part_ml, int hq, int hkv, int row_limit, int per_unit, hipStream_t st) {
-  return (hq / hkv > 4 ? launch_decode_mixed_hs2 : launch_decode_mixed_hs1)(
-      chunks, n_chunks, arena, items_k, max_words, max_steps, max_qsteps, q, part_acc, part_ml, hq, hkv, row_limit,
-      per_unit, st);
-}
+                                      int max_words, int max_steps, int max_qsteps, const uint16_t* q,
+                                      const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st);
 
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);
@@ -132,10 +130,20 @@ struct rdkv_cache {
   uint8_t* d_arena = nullptr;
   int32_t* d_tier_idx = nullptr;        // [kept_total]
   rdkv::Chunk* d_chunks = nullptr;
-  int32_t* d_slot_begin = nullptr;      // [items]
-  int32_t* d_slot_count = nullptr;      // [items]
-  float* d_part_acc = nullptr;
-  float* d_part_ml = nullptr;
+  // split workspaces, one per stream that has decoded from this cache: partial results [slots][g][128 + 2] floats and
+  // the items' arrival counters (zero between steps)
+  struct Workspace {
+    hipStream_t stream;
+    float* part_acc;
+    float* part_ml;
+    int32_t* arrive;
+    void* block;                        // the one allocation behind the three
+  };
+  mutable std::vector<Workspace> workspaces;
+  mutable std::mutex ws_mu;
+  int64_t n_slots = 0;                  // partial slots of the whole schedule
+  int32_t* d_tail_state = nullptr;      // {appended tokens so far, workgroups of the running append that are done}
+  int32_t decode_waves = 4;             // wavefronts per workgroup of the token-wise decode kernel (4 or 8)
   uint8_t* d_bits_tok = nullptr;        // copy of the token bit map
   uint8_t* d_bits_ch = nullptr;         // [items][128] K channel bit map (mixed mode)
   rdkv::ItemK* d_items_k = nullptr;     // [items] (mixed mode)

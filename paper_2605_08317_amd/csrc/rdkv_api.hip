@@ -569,6 +569,7 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
                       hipStream_t st, rdkv_cache** out) {
   const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
+  const int g = cfg->hq / cfg->hkv;
 
   rdkv_cache* c = new (std::nothrow) rdkv_cache();
   if (!c) return fail(RDKV_ERR_ALLOC, "host allocation failed");
@@ -680,18 +681,59 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   c->kept_total = kept;
   c->stored_bytes = stored;
 
-  // byte-balanced chunks: every workgroup streams about the same number of stored bytes.  A large launch (many
-  // rounds of workgroups) wants small chunks: 1/2048 of the bytes, at least 24 KB (40 KB in channel-wise mode, whose
-  // workgroups have more set-up).  A launch that fits the chip in one round is bound by latencies, and every chunk
-  // costs its item one more arrival and one more partial to merge: about 170 chunks of at least 48 KB, streamed by
-  // workgroups of eight wavefronts (measured on a 16 MB layer: 96 KB chunks 12.6 us, 64 KB 13.4 us, 24 KB 20 us).
-  const bool small_launch = stored < (static_cast<int64_t>(96) << 20);
-  // (the channel-wise kernel's workgroups have four wavefronts: twice the chunks for the same number of wavefronts)
-  int64_t chunk_bytes = small_launch ? std::max<int64_t>(48 << 10, stored / (mixed ? 340 : 170))
-                                     : std::min<int64_t>(1 << 20, std::max<int64_t>((mixed ? 40 : 24) << 10, stored / 2048));
-  c->decode_waves = small_launch ? 8 : 4;
+  // byte-balanced chunks: every workgroup streams about the same number of stored bytes.  Every chunk costs its
+  // workgroup a hand-over at the end (partial stores that go through to memory, an arrival atomic whose answer the
+  // workgroup waits for) and its item one more partial to merge, so a launch wants exactly one round of workgroups:
+  // as many chunks as the chip keeps resident (256 compute units x 2 workgroups of eight wavefronts = 512), never a
+  // few more (measured on 4 x 128K tokens of 2-bit rows: 512 chunks 4.9 TB/s, 608 chunks 4.4, 2048 chunks 4.2).
+  // Small launches are bound by latencies instead and want fewer, larger chunks still: at least 96 KB (measured on a
+  // 16 MB layer: 96 KB chunks 12.6 us, 64 KB 13.4 us, 24 KB 20 us).  Kernels with four-wavefront workgroups (8 query
+  // heads per KV head, channel-wise K) keep three workgroups per compute unit resident: 768 chunks of at least 48 KB.
+  const bool wide = !mixed && g <= 4;      // eight-wavefront workgroups
+  c->decode_waves = wide ? 8 : 4;
+  const int64_t round_chunks = wide ? 512 : 768;
+  // Cost of a row of a tier segment: its stored bytes, weighted in token-wise mode by what a byte of that tier costs
+  // the decode kernel relative to an 8-bit byte (single-tier launches reach 4.92 / 5.41 / 5.68 / 5.38 TB/s on 2- /
+  // 4- / 8- / 16-bit rows): in a launch of one round the slowest chunk sets the time, so chunks are balanced by
+  // time, not bytes.
+  auto row_cost = [&](int64_t i, int bits) -> int64_t {
+    if (!mixed) {
+      const int64_t pct = bits == 2 ? 115 : bits == 4 ? 105 : bits == 8 ? 100 : 106;
+      return 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits)) * pct / 100;
+    }
+    return tier_row_bytes(bits) + tier_meta_bytes(bits) + (c->items_k[i].kt_bytes + c->items_k[i].km_bytes + kTile64 - 1) / kTile64;
+  };
+  int64_t total_cost = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int ti = 0; ti < 4; ++ti) total_cost += c->counts[i * 4 + ti] * row_cost(i, pack_tier_bits(ti));
+  // number of chunks a chunk cost of cb gives, and the largest chunk's cost
+  auto count_chunks = [&](int64_t cb, int64_t* max_cost) {
+    int64_t total = 0;
+    *max_cost = 0;
+    for (int64_t i = 0; i < n; ++i)
+      for (int ti = 0; ti < 4; ++ti) {
+        const int64_t cnt = c->counts[i * 4 + ti];
+        if (cnt == 0) continue;
+        const int64_t rc = row_cost(i, pack_tier_bits(ti));
+        const int64_t want = std::max<int64_t>(64, cb / rc);
+        const int64_t nch = (cnt + want - 1) / want;
+        const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
+        total += (cnt + rows_per - 1) / rows_per;
+        *max_cost = std::max(*max_cost, std::min(rows_per, cnt) * rc);
+      }
+    return total;
+  };
+  int64_t chunk_bytes = std::max<int64_t>((wide ? 96 : 48) << 10, total_cost / round_chunks);
+  int64_t max_cost = 0, n_one_round = count_chunks(chunk_bytes, &max_cost);
+  for (int tries = 0; tries < 64 && n_one_round > round_chunks; ++tries) {
+    chunk_bytes += chunk_bytes / 16 + 1;
+    n_one_round = count_chunks(chunk_bytes, &max_cost);
+  }
+  // When one round cannot be had (more tier segments than resident workgroups) or would be lopsided (its largest
+  // chunk more than a fifth above the mean), several rounds of small chunks even things out instead.
+  if (n_one_round > round_chunks || max_cost * n_one_round > total_cost + total_cost / 5)
+    chunk_bytes = std::max<int64_t>((mixed ? 40 : 24) << 10, total_cost / 2560);
   if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
-  if (const char* e = std::getenv("RDKV_WAVES")) c->decode_waves = std::atoi(e) == 8 ? 8 : 4;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
   for (int64_t i = 0; i < n; ++i) {
     slot_begin[i] = static_cast<int32_t>(c->chunks.size());
@@ -699,10 +741,7 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       const int bits = pack_tier_bits(ti);
       const int64_t cnt = c->counts[i * 4 + ti];
       if (cnt == 0) continue;
-      int64_t per_row = 2 * (tier_row_bytes(bits) + tier_meta_bytes(bits));
-      if (mixed)
-        per_row = tier_row_bytes(bits) + tier_meta_bytes(bits) +
-                  (c->items_k[i].kt_bytes + c->items_k[i].km_bytes + kTile64 - 1) / kTile64;
+      const int64_t per_row = row_cost(i, bits);
       const int64_t want = std::max<int64_t>(64, chunk_bytes / per_row);
       const int64_t nch = (cnt + want - 1) / want;
       const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);

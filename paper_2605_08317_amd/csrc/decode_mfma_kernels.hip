@@ -118,7 +118,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
   __syncthreads();
 
-  const float kappa = v_kappa<TIER>(blk);
+  const float lk = v_log2_kappa<TIER>(blk);
   Run<HS> run;
   run.init();
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -222,8 +222,8 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
 
     mask_rows<HS>(x, tile, rows, blk);
     float p[HS][4];
-    softmax_tile<HS>(x, run, p);
-    pv_tile<TIER, HS>(vraw, vmeta, p, kappa, run);
+    softmax_tile<HS>(x, run, p, lk);
+    pv_tile<TIER, HS>(vraw, vmeta, p, run);
     if (more) {               // V registers are free again
       if constexpr (kShare) load_k(r, next); else load_v(r, next);
     }
@@ -235,7 +235,7 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   }
 
   // ---- end of the chunk: undo the subnormal unit, add the offsets, merge the 4 wavefronts --------------------
-  finish_chunk<HS, false, NWV>(run, 16777216.0f, g, s_ml, s_acc, ma, co);
+  finish_chunk<HS, false, NWV>(run, 16777216.0f, lk, g, s_ml, s_acc, ma, co);
 }
 
 template <int HS, int NWV>
@@ -280,12 +280,13 @@ hipError_t launch_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena,
 }  // namespace
 
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               const MergeArgs& ma, const int32_t* tail_len, int waves, hipStream_t st) {
+                               const MergeArgs& ma, const int32_t* tail_len, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   const int g = ma.hq / ma.hkv;
+  // up to 4 query heads per KV head: one head set, workgroups of eight wavefronts; 8 heads: two head sets (166
+  // registers, three wavefronts per SIMD), workgroups of four
   if (g > 4) return launch_tiles<2, 4>(chunks, n_chunks, arena, q, ma, tail_len, st);
-  if (waves == 8) return launch_tiles<1, 8>(chunks, n_chunks, arena, q, ma, tail_len, st);
-  return launch_tiles<1, 4>(chunks, n_chunks, arena, q, ma, tail_len, st);
+  return launch_tiles<1, 8>(chunks, n_chunks, arena, q, ma, tail_len, st);
 }
 
 }  // namespace rdkv

@@ -175,7 +175,7 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
   }
   __syncthreads();
 
-  const float kappa = VT == 16 ? 1.0f : v_kappa<(VT == 16 ? 8 : VT)>(blk);
+  const float lk = VT == 16 ? 0.0f : v_log2_kappa<(VT == 16 ? 8 : VT)>(blk);
   Run<HS> run;
   run.init();
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -379,7 +379,7 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
 
     mask_rows<HS>(x, tile, rows, blk);
     float p[HS][4];
-    softmax_tile<HS>(x, run, p);
+    softmax_tile<HS>(x, run, p, lk);
 
     // ---- P V ------------------------------------------------------------------------------------------------
     if constexpr (VT == 16) {
@@ -420,15 +420,15 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
             gw[0][0] = v[0].x; gw[0][1] = v[0].y; gw[0][2] = v[0].z; gw[0][3] = v[0].w;
             gw[0][4] = v[1].x; gw[0][5] = v[1].y; gw[0][6] = v[1].z; gw[0][7] = v[1].w;
           },
-          vmeta, p, kappa, run);
+          vmeta, p, run);
       if (more) vmeta = *reinterpret_cast<const uint4*>(vm + static_cast<int64_t>(next) * 1024 + lane * 16);
     } else {
-      pv_tile<VT, HS>(vraw[0], vmeta, p, kappa, run);
+      pv_tile<VT, HS>(vraw[0], vmeta, p, run);
       if (more) load_v(next);   // V registers are free again
     }
   }
 
-  finish_chunk<HS, true, kWaves>(run, VT == 16 ? 1.0f : 16777216.0f, g, reinterpret_cast<float*>(smem),
+  finish_chunk<HS, true, kWaves>(run, VT == 16 ? 1.0f : 16777216.0f, lk, g, reinterpret_cast<float*>(smem),
                                  reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2, ma, co);
 }
 

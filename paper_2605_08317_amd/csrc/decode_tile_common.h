@@ -154,23 +154,22 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 // Running state of one wavefront over its tiles of a chunk: per head set the running maximum and sum of the
-// online softmax (lanes of head j), and the output accumulators acc[hs][grp][i] (head 4 hs + i, channel
-// 32 grp + lane % 32, summed over this lane's token half) with the offset sums off[hs][grp] = sum_t p m.
+// online softmax (lanes of head j; the sum carries this lane's factor kappa), the output accumulators
+// acc[hs][grp][i] (head 4 hs + i, channel 32 grp + lane % 32, summed over this lane's token half), and the offset
+// sums offv[hs][i] = kappa * sum_t p m of head 4 hs + i and channel group lane % 4 over the tokens of this lane's block.
 template <int HS>
 struct Run {
   float m[HS], l[HS];
   floatx4 acc[HS][4];
-  float off[HS][4];
+  floatx4 offv[HS];
   __device__ __forceinline__ void init() {
 #pragma unroll
     for (int hs = 0; hs < HS; ++hs) {
       m[hs] = kNegBig;
       l[hs] = 0.f;
+      offv[hs] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int grp = 0; grp < 4; ++grp) {
-        acc[hs][grp] = floatx4{0.f, 0.f, 0.f, 0.f};
-        off[hs][grp] = 0.f;
-      }
+      for (int grp = 0; grp < 4; ++grp) acc[hs][grp] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
   }
 };
@@ -187,9 +186,11 @@ __device__ __forceinline__ void mask_rows(float (&x)[HS][4], int tile, int rows,
   }
 }
 
-// Online softmax per head over the logits x (in units of 1 / kXScale) of a tile; probabilities carried times 2^kPExp.
+// Online softmax per head over the logits x (in units of 1 / kXScale) of a tile; probabilities carried times
+// 2^(kPExp + lk): lk = log2 of the lane's factor kappa on the V side (0 where there is none), which the exponential
+// applies for free; the running sum carries the same factor and finish_chunk takes it out again.
 template <int HS>
-__device__ __forceinline__ void softmax_tile(const float (&x)[HS][4], Run<HS>& run, float (&p)[HS][4]) {
+__device__ __forceinline__ void softmax_tile(const float (&x)[HS][4], Run<HS>& run, float (&p)[HS][4], float lk = 0.f) {
 #pragma unroll
   for (int hs = 0; hs < HS; ++hs) {
     const float mt = head_max(fmaxf(fmaxf(x[hs][0], x[hs][1]), fmaxf(x[hs][2], x[hs][3])));
@@ -201,14 +202,14 @@ __device__ __forceinline__ void softmax_tile(const float (&x)[HS][4], Run<HS>& r
       const float ah[4] = {__builtin_bit_cast(float, quad_bcast<0>(au)), __builtin_bit_cast(float, quad_bcast<1>(au)),
                            __builtin_bit_cast(float, quad_bcast<2>(au)), __builtin_bit_cast(float, quad_bcast<3>(au))};
 #pragma unroll
-      for (int grp = 0; grp < 4; ++grp) {
+      for (int i = 0; i < 4; ++i) {   // row i of the accumulators is head i
 #pragma unroll
-        for (int i = 0; i < 4; ++i) run.acc[hs][grp][i] *= ah[i];   // acc row i is head i
-        run.off[hs][grp] *= alpha;
+        for (int grp = 0; grp < 4; ++grp) run.acc[hs][grp][i] *= ah[i];
+        run.offv[hs][i] *= ah[i];
       }
       run.m[hs] = m_new;
     }
-    const float neg_mc = kPExp - run.m[hs] * kXScale;
+    const float neg_mc = (kPExp + lk) - run.m[hs] * kXScale;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       p[hs][i] = fast_exp2(__builtin_fmaf(x[hs][i], kXScale, neg_mc));
@@ -217,14 +218,14 @@ __device__ __forceinline__ void softmax_tile(const float (&x)[HS][4], Run<HS>& r
   }
 }
 
-// 2^-fb of the field this lane's block is read from on the V side (block a = blk % 8 feeds step a)
+// log2 of kappa = 2^-fb of the field this lane's block is read from on the V side (block a = blk % 8 feeds step a)
 template <int TIER>
-__device__ __forceinline__ float v_kappa(int blk) {
-  float kappa = 1.0f;
+__device__ __forceinline__ float v_log2_kappa(int blk) {
+  float lk = 0.0f;
 #pragma unroll
   for (int a = 0; a < 8; ++a)
-    if ((blk & 7) == a) kappa = 1.0f / static_cast<float>(1 << Step<TIER>::fb(a));
-  return kappa;
+    if ((blk & 7) == a) lk = -static_cast<float>(Step<TIER>::fb(a));
+  return lk;
 }
 
 template <int G>
@@ -234,30 +235,32 @@ struct GroupIndex {
 
 // P V over a token-wise V tile of tier TIER (8, 4, 2).  fill_gw(GroupIndex<G>, gw) delivers the code words of
 // channel group G (and their shifted copies); vmeta = group (lane % 4)'s scales (x, y) and offsets (z, w) of
-// tokens 4 blk + 0..3.
+// tokens 4 blk + 0..3; p = the probabilities times the lane's kappa (softmax_tile with lk).
+// The offsets go through one more product: A = p (4 heads x the block's 4 tokens), B = this lane's offsets (4 tokens
+// of channel group lane % 4), so that lane (block, j) gathers sum_t p m of the four heads for group j -- with the
+// same rounded p that multiplies the codes, which keeps the two halves of sum_t p (s code + m) consistent.
 template <int TIER, int HS, class FillGw>
 __device__ __forceinline__ void pv_tile_groups(FillGw&& fill_gw, const uint4& vmeta, const float (&p)[HS][4],
-                                               float kappa, Run<HS>& run) {
+                                               Run<HS>& run) {
   using S = Step<TIER>;
-  Pack4 ph[HS];
+  Pack4 ph[HS], ob;
+  ob.u[0] = vmeta.z;
+  ob.u[1] = vmeta.w;
 #pragma unroll
   for (int hs = 0; hs < HS; ++hs) {
-    ph[hs].p[0] = half2v{static_cast<_Float16>(p[hs][0] * kappa), static_cast<_Float16>(p[hs][1] * kappa)};
-    ph[hs].p[1] = half2v{static_cast<_Float16>(p[hs][2] * kappa), static_cast<_Float16>(p[hs][3] * kappa)};
+    ph[hs].p[0] = half2v{static_cast<_Float16>(p[hs][0]), static_cast<_Float16>(p[hs][1])};
+    ph[hs].p[1] = half2v{static_cast<_Float16>(p[hs][2]), static_cast<_Float16>(p[hs][3])};
+    run.offv[hs] = __builtin_amdgcn_mfma_f32_4x4x4f16(ph[hs].h, ob.h, run.offv[hs], 0, 0, 0);
   }
 #define RDKV_PV_GROUP(G_)                                                                                      \
   {                                                                                                            \
     __builtin_amdgcn_sched_barrier(0);                                                                         \
-    /* V metadata of tokens 4 blk + 0..3: lane G_ of the quad holds group G_'s scales (x, y), offsets (z, w) */ \
-    Pack4 sv, ov, pa[HS];                                                                                      \
+    /* V scales of tokens 4 blk + 0..3: lane G_ of the quad holds group G_'s (x, y) */                         \
+    Pack4 sv, pa[HS];                                                                                          \
     sv.u[0] = quad_bcast<G_>(vmeta.x); sv.u[1] = quad_bcast<G_>(vmeta.y);                                      \
-    ov.u[0] = quad_bcast<G_>(vmeta.z); ov.u[1] = quad_bcast<G_>(vmeta.w);                                      \
     _Pragma("unroll") for (int hs = 0; hs < HS; ++hs) {                                                        \
       pa[hs].p[0] = ph[hs].p[0] * sv.p[0];                                                                     \
       pa[hs].p[1] = ph[hs].p[1] * sv.p[1];                                                                     \
-      float o = run.off[hs][G_];                                                                               \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i) o = __builtin_fmaf(p[hs][i], static_cast<float>(ov.h[i]), o); \
-      run.off[hs][G_] = o;                                                                                     \
     }                                                                                                          \
     uint32_t gw[S::kCopies][TIER];                                                                             \
     fill_gw(GroupIndex<G_>{}, gw);                                                                             \
@@ -278,12 +281,12 @@ __device__ __forceinline__ void pv_tile_groups(FillGw&& fill_gw, const uint4& vm
 // the same with the whole tile's code words in registers
 template <int TIER, int HS>
 __device__ __forceinline__ void pv_tile(const uint4 (&vraw)[TIER], const uint4& vmeta, const float (&p)[HS][4],
-                                        float kappa, Run<HS>& run) {
+                                        Run<HS>& run) {
   pv_tile_groups<TIER, HS>(
       [&](auto gi, uint32_t (&gw)[Step<TIER>::kCopies][TIER]) __attribute__((always_inline)) {
         group_words<TIER>(vraw, decltype(gi)::value, gw);
       },
-      vmeta, p, kappa, run);
+      vmeta, p, run);
 }
 
 // Where a chunk's partial result goes and what the merge of its item needs.
@@ -292,30 +295,34 @@ struct ChunkOut {
 };
 
 // End of a chunk: scale the accumulators back (acc_scale = 2^24 where the V codes entered as fp16 subnormals),
-// add the offset sums, merge the workgroup's NWV wavefronts through LDS, store the chunk's partial result and
-// announce it; the workgroup that completes its item merges the item's partials (arrive_and_merge).
+// take the lane's factor kappa = 2^lk out of the running sums, add the offset sums, merge the workgroup's NWV
+// wavefronts through LDS, store the chunk's partial result and announce it; the workgroup that completes its item
+// merges the item's partials (arrive_and_merge).
 // s_ml: [NWV][4 HS heads][m, l] floats; s_acc: [2 NWV streams][g][128] floats (also the merge's LDS).  ALIAS: the
 // two areas overlap LDS that the tile loop used, so a barrier separates the two uses.
 template <int HS, bool ALIAS, int NWV>
-__device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, int g, float* s_ml, float* s_acc,
-                                             const MergeArgs& ma, const ChunkOut& co) {
+__device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, float lk, int g, float* s_ml,
+                                             float* s_acc, const MergeArgs& ma, const ChunkOut& co) {
   constexpr int NT = NWV * 64;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int th = lane >> 5, cl = lane & 31;
   float* __restrict__ part_acc = ma.part_acc + static_cast<int64_t>(co.slot) * g * kHeadDim;
   float* __restrict__ part_ml = ma.part_ml + static_cast<int64_t>(co.slot) * g * 2;
+  const float inv_kappa = __builtin_ldexpf(1.0f, static_cast<int>(-lk));   // lk is a small integer
 #pragma unroll
   for (int hs = 0; hs < HS; ++hs) {
-    run.l[hs] = head_sum(run.l[hs]);
+    run.l[hs] = head_sum(run.l[hs] * inv_kappa);
 #pragma unroll
-    for (int grp = 0; grp < 4; ++grp) {
-      const uint32_t ou = __builtin_bit_cast(uint32_t, head_sum(run.off[hs][grp]));   // lanes of head j hold sum_t p m
-      const float oh[4] = {__builtin_bit_cast(float, quad_bcast<0>(ou)), __builtin_bit_cast(float, quad_bcast<1>(ou)),
+    for (int i = 0; i < 4; ++i) {
+      // lanes (block, j) hold head i's sum_t p m of channel group j over the block's tokens: all blocks, then to the
+      // lanes of every group
+      const uint32_t ou = __builtin_bit_cast(uint32_t, head_sum(run.offv[hs][i] * inv_kappa));
+      const float og[4] = {__builtin_bit_cast(float, quad_bcast<0>(ou)), __builtin_bit_cast(float, quad_bcast<1>(ou)),
                            __builtin_bit_cast(float, quad_bcast<2>(ou)), __builtin_bit_cast(float, quad_bcast<3>(ou))};
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        run.acc[hs][grp][i] = __builtin_fmaf(run.acc[hs][grp][i], acc_scale, th == 0 ? oh[i] : 0.f);
+      for (int grp = 0; grp < 4; ++grp)
+        run.acc[hs][grp][i] = __builtin_fmaf(run.acc[hs][grp][i], acc_scale, th == 0 ? og[grp] : 0.f);
     }
   }
   if constexpr (ALIAS) __syncthreads();
@@ -457,7 +464,7 @@ __device__ __forceinline__ void process_tail_tiles(const uint8_t* __restrict__ k
 #undef RDKV_TAIL_GROUP
 #undef RDKV_TAIL_STEP
   }
-  finish_chunk<HS, ALIAS, NWV>(run, 1.0f, g, s_ml, s_acc, ma, co);
+  finish_chunk<HS, ALIAS, NWV>(run, 1.0f, 0.f, g, s_ml, s_acc, ma, co);
 }
 
 }  // namespace tile

@@ -690,7 +690,6 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   // 16 MB layer: 96 KB chunks 12.6 us, 64 KB 13.4 us, 24 KB 20 us).  Kernels with four-wavefront workgroups (8 query
   // heads per KV head, channel-wise K) keep three workgroups per compute unit resident: 768 chunks of at least 48 KB.
   const bool wide = !mixed && g <= 4;      // eight-wavefront workgroups
-  c->decode_waves = wide ? 8 : 4;
   const int64_t round_chunks = wide ? 512 : 768;
   // Cost of a row of a tier segment: its stored bytes, weighted in token-wise mode by what a byte of that tier costs
   // the decode kernel relative to an 8-bit byte (single-tier launches reach 4.92 / 5.41 / 5.68 / 5.38 TB/s on 2- /
@@ -703,15 +702,19 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
     }
     return tier_row_bytes(bits) + tier_meta_bytes(bits) + (c->items_k[i].kt_bytes + c->items_k[i].km_bytes + kTile64 - 1) / kTile64;
   };
-  int64_t total_cost = 0;
-  for (int64_t i = 0; i < n; ++i)
-    for (int ti = 0; ti < 4; ++ti) total_cost += c->counts[i * 4 + ti] * row_cost(i, pack_tier_bits(ti));
+  // (the 16-bit rows of a token-wise cache run in a kernel of their own and are cut separately below)
+  const int ti0 = mixed ? 0 : 1;
+  int64_t total_cost = 0, cost16 = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    for (int ti = ti0; ti < 4; ++ti) total_cost += c->counts[i * 4 + ti] * row_cost(i, pack_tier_bits(ti));
+    if (!mixed) cost16 += c->counts[i * 4] * row_cost(i, 16);
+  }
   // number of chunks a chunk cost of cb gives, and the largest chunk's cost
   auto count_chunks = [&](int64_t cb, int64_t* max_cost) {
     int64_t total = 0;
     *max_cost = 0;
     for (int64_t i = 0; i < n; ++i)
-      for (int ti = 0; ti < 4; ++ti) {
+      for (int ti = ti0; ti < 4; ++ti) {
         const int64_t cnt = c->counts[i * 4 + ti];
         if (cnt == 0) continue;
         const int64_t rc = row_cost(i, pack_tier_bits(ti));
@@ -733,6 +736,10 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   // chunk more than a fifth above the mean), several rounds of small chunks even things out instead.
   if (n_one_round > round_chunks || max_cost * n_one_round > total_cost + total_cost / 5)
     chunk_bytes = std::max<int64_t>((mixed ? 40 : 24) << 10, total_cost / 2560);
+  // The row-major 16-bit kernel keeps 4 / 4 / 2 / 1 workgroups per compute unit resident at 1 / 2 / 4 / 8 query
+  // heads per KV head (its register count): one round of its own.
+  const int64_t round16 = g <= 2 ? 1024 : g <= 4 ? 512 : 256;
+  const int64_t chunk_bytes16 = std::max<int64_t>(96 << 10, (cost16 + round16 - 1) / round16);
   if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
   for (int64_t i = 0; i < n; ++i) {
@@ -742,7 +749,7 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       const int64_t cnt = c->counts[i * 4 + ti];
       if (cnt == 0) continue;
       const int64_t per_row = row_cost(i, bits);
-      const int64_t want = std::max<int64_t>(64, chunk_bytes / per_row);
+      const int64_t want = std::max<int64_t>(64, (!mixed && bits == 16 ? chunk_bytes16 : chunk_bytes) / per_row);
       const int64_t nch = (cnt + want - 1) / want;
       const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
       const int64_t* so = &c->seg_off[(i * 4 + ti) * 4];
@@ -1153,7 +1160,7 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
   // the workgroups of both kernels announce themselves on the same counters: whichever finishes an item merges it
   RDKV_HIP(launch_decode_tiered_split(c->d_chunks, n16, c->d_arena, static_cast<const uint16_t*>(q), ma, st));
   RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nrest, c->d_arena, static_cast<const uint16_t*>(q), ma,
-                               c->d_tail_state, c->decode_waves, st));
+                               c->d_tail_state, st));
   return RDKV_OK;
 }
 

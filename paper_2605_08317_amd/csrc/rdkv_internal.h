@@ -82,10 +82,9 @@ hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint
 hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t tail_tiles, int32_t n,
                                    uint16_t* k_rows, uint16_t* v_rows, hipStream_t st);
 
-// tail_len: device word holding the appended tokens that exist so far (chunks of tier kTierTail end there);
-// waves: wavefronts per workgroup (4 or 8)
+// tail_len: device word holding the appended tokens that exist so far (chunks of tier kTierTail end there)
 hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               const MergeArgs& ma, const int32_t* tail_len, int waves, hipStream_t st);
+                               const MergeArgs& ma, const int32_t* tail_len, hipStream_t st);
 // one object per head-set count (hs1: up to 4 query heads per KV head, hs2: 8)
 hipError_t launch_decode_mixed_hs1(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                    int max_words, int max_steps, int max_qsteps, const uint16_t* q,
@@ -143,7 +142,6 @@ struct rdkv_cache {
   mutable std::mutex ws_mu;
   int64_t n_slots = 0;                  // partial slots of the whole schedule
   int32_t* d_tail_state = nullptr;      // {appended tokens so far, workgroups of the running append that are done}
-  int32_t decode_waves = 4;             // wavefronts per workgroup of the token-wise decode kernel (4 or 8)
   uint8_t* d_bits_tok = nullptr;        // copy of the token bit map
   uint8_t* d_bits_ch = nullptr;         // [items][128] K channel bit map (mixed mode)
   rdkv::ItemK* d_items_k = nullptr;     // [items] (mixed mode)

@@ -32,7 +32,7 @@
  *    Without hooks, scratch comes from hipMallocAsync / hipFreeAsync on the call's
  *    stream and what a cache owns from hipMalloc / hipFree.
  *  - Shapes: head_dim must be 128, hq a multiple of hkv with hq/hkv in
- *    {1,2,4,8}, quantization group size 32.
+ *    {1,2,4,8}, quantization group size 32 or 128.
  *  - Ragged batch layout: K, V (and per-token arrays) hold, per sequence s in
  *    batch order, a block [hkv][T_s][head_dim] (resp. [hkv][T_s]); blocks are
  *    concatenated without padding.  One "item" is one (sequence, KV head), item
@@ -81,7 +81,10 @@ typedef struct rdkv_config {
   int32_t causal;           /* 1: window row i attends keys t <= T - s_obs + i */
   int32_t k_mode;           /* RDKV_K_TOKENWISE: K rows share the token bit map;
                                RDKV_K_CHANNELWISE: Sec. 3.2 Stage 3 (per-channel K on kept tokens) */
-  int32_t group_size;       /* quantization group; must be 32 */
+  int32_t group_size;       /* channels of a token row that share a scale and offset: 32 (default), or 128 = one per
+                               token row, the per-token format of App. B (V rows; K rows too in token-wise mode).  The
+                               stored row keeps its four metadata slots, each repeating the row's scale and offset, so
+                               both formats take the same bytes and the same decode kernels */
   const float* budget_bits; /* HOST [batch]: average bits per cache element for each sequence */
   float kv_split_rk;        /* r_K: share of the bit budget given to K in channel-wise mode (0.5) */
   int32_t k_scale_per_channel; /* channel-wise mode: 0 (default) = a scale and zero-point per channel and group of 32
@@ -333,7 +336,8 @@ const rdkv_cache* rdkv_cache_generation(const rdkv_cache* cache, int32_t index);
  * layers, heads and calibration sequences; that average is left to the caller.
  *   K, V    DEVICE bf16, ragged [hkv][T_s][d] blocks (cfg: batch, hq, hkv, head_dim, seq_lens, k_mode,
  *           k_scale_per_channel; budgets, tiers and the probe fields are not read; T_s >= 1)
- *   eps_v   HOST double out [items][3] (b = 2, 4, 8): V quantized per token, groups of 32 channels
+ *   eps_v   HOST double out [items][3] (b = 2, 4, 8): V quantized per token, groups of cfg->group_size channels
+ *           (128: one scale per token row, the "per-token" quantity of Table 9)
  *   eps_k   HOST double out [items][3]: K at the granularity cfg selects -- token-wise: as V; channel-wise: groups of
  *           32 consecutive tokens of a channel starting at token 0 (last group may be short), or one scale per
  *           channel over all tokens when k_scale_per_channel is set

@@ -334,6 +334,21 @@ def quantize_groups(x, bits):
     return t.astype(np.uint8), s, m
 
 
+def quantize_rows(rows, bits, group=GROUP):
+    """Quantizes token rows [n, d] with one scale and offset per `group` consecutive channels.
+
+    group = 32: the groups of this build's default layout.  group = d: one scale and one offset per token row, the
+    per-token format of the paper (App. B; Table 9 reports per-token errors for V).  The record of a row keeps its
+    d / 32 metadata slots either way: with a row-wide group every slot repeats the row's scale and offset, so the
+    physical layout and its readers are the same.  Returns (codes uint8 [n, d], scale fp16 [n, d / 32], offset fp16
+    [n, d / 32])."""
+    n, d = rows.shape
+    assert group in (GROUP, d)
+    c, s, m = quantize_groups(rows.reshape(n, d // group, group), bits)
+    rep = group // GROUP
+    return c.reshape(n, d), np.repeat(s, rep, axis=1), np.repeat(m, rep, axis=1)
+
+
 def dequantize_groups(codes, s, m):
     """x_hat = s*code + m in fp64 (exact: code is an integer, s and m are fp16)."""
     return s.astype(np.float64)[..., None] * codes.astype(np.float64) + m.astype(np.float64)[..., None]
@@ -383,10 +398,11 @@ def meta_bytes(bits, d=128):
     return 0 if bits == 16 else (d // GROUP) * 4
 
 
-def canonical_item(Kh, Vh, bits_tok):
+def canonical_item(Kh, Vh, bits_tok, group=GROUP):
     """Canonical (layout-free) record of one item in token-wise mode: per tier the
     kept positions and, for K and V, per-element codes plus fp16 scale / offset
-    bit patterns per group of 32 channels; tier 16 keeps the input bf16 bits.
+    bit patterns per group of 32 channels (group = d: one per token row, repeated in
+    every slot); tier 16 keeps the input bf16 bits.
     In token-wise mode a token's K row and V row share its bit-width.
     Kh, Vh: float32 [T, d] bf16-exact."""
     Kh = _check_bf16_exact(Kh, "K")
@@ -405,10 +421,10 @@ def canonical_item(Kh, Vh, bits_tok):
                 ent[name + "_scale"] = np.zeros((len(pos), 0), dtype=np.uint16)
                 ent[name + "_off"] = np.zeros((len(pos), 0), dtype=np.uint16)
             else:
-                c, s, m = quantize_groups(rows.reshape(len(pos), d // GROUP, GROUP), b)
-                ent[name + "_codes"] = c.reshape(len(pos), d)
-                ent[name + "_scale"] = s.view(np.uint16)
-                ent[name + "_off"] = m.view(np.uint16)
+                c, s, m = quantize_rows(rows, b, group)
+                ent[name + "_codes"] = c
+                ent[name + "_scale"] = np.ascontiguousarray(s).view(np.uint16)
+                ent[name + "_off"] = np.ascontiguousarray(m).view(np.uint16)
         rec[b] = ent
     return rec
 
@@ -540,7 +556,7 @@ def physical_segments(rec, d=128):
     return out
 
 
-def build_cache_tokenwise(K_list, V_list, bits_list):
+def build_cache_tokenwise(K_list, V_list, bits_list, group=GROUP):
     """Pack a ragged batch in token-wise mode.
 
     K_list[s], V_list[s]: float32 [Hkv, T_s, d]; bits_list[s]: uint8 [Hkv, T_s].
@@ -565,7 +581,7 @@ def build_cache_tokenwise(K_list, V_list, bits_list):
     chunks, tier_idx, canon = [], [], []
     cur = 0
     for i, (Kh, Vh, bh) in enumerate(items):
-        rec = canonical_item(Kh, Vh, bh)
+        rec = canonical_item(Kh, Vh, bh, group)
         canon.append(rec)
         phys = physical_segments(rec, d)
         for ti, b in enumerate(PACK_ORDER):
@@ -880,7 +896,7 @@ def unpack_v16_tiles(data, n):
     return out.reshape(nt * R, 128)[:n]
 
 
-def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list, k_per_channel_scale=False):
+def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list, k_per_channel_scale=False, group=GROUP):
     """Pack a ragged batch in mixed mode (Alg. 1 Stage 4 as printed: V rows sorted by
     b_t^V into sub-segments, K rows of the retained tokens with channels sorted by
     b_c^K).  bits_tok_list[s]: uint8 [Hkv, T_s] (V token map); bits_ch_list[s]: uint8
@@ -928,9 +944,10 @@ def build_cache_mixed(K_list, V_list, bits_tok_list, bits_ch_list, k_per_channel
                 vd, vm = pack_v16_tiles(vcodes), np.zeros(0, dtype=np.uint8)
                 rec[b] = {"pos": pos, "k_codes": kc, "k_scale": ks, "k_off": ko, "v_codes": vcodes}
             else:
-                c, sc, m = quantize_groups(Vh[pos].reshape(n, d // GROUP, GROUP), b)
-                vd, vm = pack_tiles64(c.reshape(n, d), sc.view(np.uint16), m.view(np.uint16), b, "v")
-                rec[b] = {"pos": pos, "k_codes": kc, "k_scale": ks, "k_off": ko, "v_codes": c.reshape(n, d),
+                c, sc, m = quantize_rows(Vh[pos], b, group)       # group = d: one scale per V token row (App. B)
+                sc, m = np.ascontiguousarray(sc), np.ascontiguousarray(m)
+                vd, vm = pack_tiles64(c, sc.view(np.uint16), m.view(np.uint16), b, "v")
+                rec[b] = {"pos": pos, "k_codes": kc, "k_scale": ks, "k_off": ko, "v_codes": c,
                           "v_scale": sc.view(np.uint16), "v_off": m.view(np.uint16)}
             for si, seg in enumerate((kd, km, vd, vm)):
                 cur = _round_up(cur, SEG_ALIGN)
@@ -1109,7 +1126,7 @@ def decode_dense(K_list, V_list, q):
 # --------------------------------------------------------------------------
 def rebudget_tail(cache, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B, pool_kernel=5, causal=True,
                   rel_tol=np.float32(1e-2), max_iters=64, weights_override=None, eps_k=EPS_K_LLAMA31_8B,
-                  r_k=np.float32(0.5)):
+                  r_k=np.float32(0.5), group=GROUP):
     """The paper sketches the extension in one sentence: attention weights are gathered over a
     buffer of recent decode tokens and the same knapsack allocation is applied to compress
     them.  Reading taken here: the buffer is the whole appended-token zone; its n tokens are
@@ -1145,11 +1162,12 @@ def rebudget_tail(cache, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B, 
                 bt[h], bc[h] = allocate_mixed(w_tok[h], w_ch[h], budgets[s], r_k, tiers, eps, eps_k, rel_tol, max_iters)
             bt_list.append(bt)
             bc_list.append(bc)
-        child = build_cache_mixed(K_list, V_list, bt_list, bc_list, k_per_channel_scale=cache["k_per_unit"])
+        child = build_cache_mixed(K_list, V_list, bt_list, bc_list, k_per_channel_scale=cache["k_per_unit"],
+                                  group=group)
         child["bits"] = bt_list
     else:
         child = compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers, eps, pool_kernel, causal, rel_tol,
-                                   max_iters, weights_override)
+                                   max_iters, weights_override, group)
     cache.setdefault("absorbed", []).append(child)
     cache["tail"] = [(np.zeros((0, d)), np.zeros((0, d))) for _ in range(batch * hkv)]
     return child
@@ -1172,7 +1190,7 @@ def _nmse(x, x_hat):
     return float((e * e).sum()) / den
 
 
-def calibrate_eps(K_list, V_list, k_channelwise=False, k_per_channel_scale=False):
+def calibrate_eps(K_list, V_list, k_channelwise=False, k_per_channel_scale=False, group=GROUP):
     """eps(b) of this build's quantizer on supplied K and V, b in (2, 4, 8): the normalized
     distortion the knapsack of Eq. 6 consumes (App. "Calibrated Distortion Tables": per-token NMSE for V, per-channel NMSE
     for K; eps(0) = 1 and eps(16) = 0 hold by definition and are not computed).  The paper
@@ -1180,7 +1198,7 @@ def calibrate_eps(K_list, V_list, k_channelwise=False, k_per_channel_scale=False
     returned here and averaging is left to the caller.
 
     Every token is retained (calibration sees the uncompressed prefix).  V: every token row in
-    groups of 32 channels.  K: as V when k_channelwise is false (K rows share the token map);
+    groups of `group` channels (32, or d = one scale per token row: the "per-token" of Table 9).  K: as V when k_channelwise is false (K rows share the token map);
     else per channel in groups of 32 consecutive tokens starting at token 0 (the last group may
     be short), or one scale per channel over all tokens with k_per_channel_scale (App. B).
     Returns (eps_k, eps_v): float64 [items, 3], item = s * Hkv + h."""
@@ -1192,10 +1210,10 @@ def calibrate_eps(K_list, V_list, k_channelwise=False, k_per_channel_scale=False
         for h in range(hkv):
             ek, ev = [], []
             for b in CALIB_BITS:
-                cv, sv, mv = quantize_groups(Vs[h].reshape(T, d // GROUP, GROUP), b)
+                cv, sv, mv = quantize_groups(Vs[h].reshape(T, d // group, group), b)
                 ev.append(_nmse(Vs[h], dequantize_groups(cv, sv, mv).reshape(T, d)))
                 if not k_channelwise:
-                    ck, sk, mk = quantize_groups(Ks[h].reshape(T, d // GROUP, GROUP), b)
+                    ck, sk, mk = quantize_groups(Ks[h].reshape(T, d // group, group), b)
                     ek.append(_nmse(Ks[h], dequantize_groups(ck, sk, mk).reshape(T, d)))
                 else:
                     gt = None if k_per_channel_scale else K_TOKEN_GROUP
@@ -1213,7 +1231,7 @@ def calibrate_eps(K_list, V_list, k_channelwise=False, k_per_channel_scale=False
 # --------------------------------------------------------------------------
 def compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers=TIERS, eps=EPS_V_LLAMA31_8B,
                        pool_kernel=5, causal=True, rel_tol=np.float32(1e-2), max_iters=64,
-                       weights_override=None):
+                       weights_override=None, group=GROUP):
     """Weights -> pooling -> per-item bisection -> pack.  `weights_override`, if
     given, is a list of float32 [Hkv, T_s] arrays used instead of the computed
     weights (the bit-exact comparisons feed both sides identical fp32 weights)."""
@@ -1227,7 +1245,7 @@ def compress_tokenwise(K_list, V_list, Qobs_list, budgets, tiers=TIERS, eps=EPS_
         bits = np.stack([mckp_bisect(w[h], budgets[s], tiers, eps, rel_tol, max_iters)
                          for h in range(w.shape[0])])
         bits_list.append(bits)
-    cache = build_cache_tokenwise(K_list, V_list, bits_list)
+    cache = build_cache_tokenwise(K_list, V_list, bits_list, group)
     cache["bits"] = bits_list
     cache["weights"] = w_list
     return cache

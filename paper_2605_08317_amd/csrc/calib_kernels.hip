@@ -21,6 +21,7 @@ struct CalibArgs {
   const int32_t* item_T;        // [items]
   double* acc;                  // [items][4]: squared error at 2, 4, 8 bits, then sum of squares
   uint32_t* range;              // [items][128][2] ordered-integer images of a channel's minimum / maximum, or null
+  int32_t row_wide;             // rows kernel: one scale per token row instead of one per group of 32 channels
 };
 
 __device__ __forceinline__ uint32_t to_ordered(float f) {
@@ -105,6 +106,12 @@ __global__ __launch_bounds__(256) void calib_rows_kernel(CalibArgs a) {
     mx = fmaxf(mx, __shfl_xor(mx, 1));
     mn = fminf(mn, __shfl_xor(mn, 2));
     mx = fmaxf(mx, __shfl_xor(mx, 2));
+    if (a.row_wide) {   // the 16 lanes of a row
+      mn = fminf(mn, __shfl_xor(mn, 4));
+      mx = fmaxf(mx, __shfl_xor(mx, 4));
+      mn = fminf(mn, __shfl_xor(mn, 8));
+      mx = fmaxf(mx, __shfl_xor(mx, 8));
+    }
     const bool ok[8] = {live, live, live, live, live, live, live, live};
     sum[0] += group_error<2, 8>(x, ok, mn, mx);
     sum[1] += group_error<4, 8>(x, ok, mn, mx);
@@ -223,15 +230,15 @@ __global__ __launch_bounds__(256) void calib_channels_kernel(CalibArgs a) {
 // acc_k, acc_v: [items][4] doubles, zero on entry.  range: [items][128][2] holding (0xFFFFFFFF, 0) pairs on entry
 // when k_whole_channel is set, else unused.
 hipError_t launch_calibrate(const uint16_t* K, const uint16_t* V, const int64_t* item_row_off, const int32_t* item_T,
-                            int n_items, int max_T, bool k_channelwise, bool k_whole_channel, double* acc_k,
-                            double* acc_v, uint32_t* range, hipStream_t st) {
+                            int n_items, int max_T, bool k_channelwise, bool k_whole_channel, bool row_wide,
+                            double* acc_k, double* acc_v, uint32_t* range, hipStream_t st) {
   if (n_items == 0 || max_T == 0) return hipSuccess;
   const dim3 block(256);
   const dim3 grid_rows((max_T + kCalibRowsPerBlock - 1) / kCalibRowsPerBlock, n_items);
   const dim3 grid_ch((max_T + kCalibTokensPerBlock - 1) / kCalibTokensPerBlock, n_items);
-  CalibArgs av{V, item_row_off, item_T, acc_v, nullptr};
+  CalibArgs av{V, item_row_off, item_T, acc_v, nullptr, row_wide ? 1 : 0};
   hipLaunchKernelGGL(calib_rows_kernel, grid_rows, block, 0, st, av);
-  CalibArgs ak{K, item_row_off, item_T, acc_k, range};
+  CalibArgs ak{K, item_row_off, item_T, acc_k, range, row_wide ? 1 : 0};
   if (!k_channelwise) {
     hipLaunchKernelGGL(calib_rows_kernel, grid_rows, block, 0, st, ak);
   } else if (k_whole_channel) {

@@ -139,6 +139,8 @@ struct PackArgs {
   const uint8_t* bits_ch;      // [items][128] (mixed mode)
   uint32_t* k_range;           // [items][128][2]: ordered-integer images of a channel's minimum and maximum over all
                                // retained tokens (one scale per channel, App. B), or null (groups of 32 tokens)
+  int32_t row_wide;            // token rows: one scale and offset per row (App. B's per-token format), repeated in
+                               // the row's four metadata slots, instead of one per group of 32 channels
 };
 
 // monotone map float -> uint32 (and back), so that integer atomic min / max order floats
@@ -230,6 +232,12 @@ __global__ __launch_bounds__(256) void quant_pack_tile64_kernel(PackArgs a) {
     for (int i = 1; i < 32; ++i) {
       mn = fminf(mn, x[i]);
       mx = fmaxf(mx, x[i]);
+    }
+    if (a.row_wide) {   // the four groups of a row are the four lanes of a quad (task % 4 = lane % 4)
+      mn = fminf(mn, __shfl_xor(mn, 1));
+      mx = fmaxf(mx, __shfl_xor(mx, 1));
+      mn = fminf(mn, __shfl_xor(mn, 2));
+      mx = fmaxf(mx, __shfl_xor(mx, 2));
     }
     mn = mn + 0.0f;   // canonical +0
     constexpr float Q = static_cast<float>((1 << BITS) - 1);
@@ -516,16 +524,17 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
                              const int64_t* idx_base, const int32_t* counts, const int64_t* seg_off,
                              const int64_t* item_row_off, uint8_t* arena, int n_items,
                              const int32_t max_count[4], const ItemK* items_k, const uint8_t* bits_ch,
-                             uint32_t* k_range, hipStream_t st) {
+                             uint32_t* k_range, int row_wide, hipStream_t st) {
   const bool mixed = items_k != nullptr;
   if (k_range) {   // k_range must hold (0xFFFFFFFF, 0) pairs on entry
-    PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, 0, 1, items_k, bits_ch, k_range};
+    PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, 0, 1, items_k, bits_ch, k_range,
+               row_wide};
     hipLaunchKernelGGL(k_channel_range_kernel, dim3(64, n_items), dim3(256), 0, st, a);
   }
   for (int ti = 0; ti < 4; ++ti) {
     if (max_count[ti] == 0) continue;
     PackArgs a{K, V, tier_idx, idx_base, counts, seg_off, item_row_off, arena, ti, mixed ? 1 : 0, items_k, bits_ch,
-               k_range};
+               k_range, row_wide};
     dim3 grid64((max_count[ti] + 63) / 64, n_items);   // 64 rows per workgroup in every kernel below
     dim3 block(256);
     if (mixed) hipLaunchKernelGGL(pack_k_mixed_kernel, grid64, block, 0, st, a);

@@ -25,7 +25,7 @@ hipError_t launch_quant_pack(const uint16_t* K, const uint16_t* V, const int32_t
                              const int64_t* idx_base, const int32_t* counts, const int64_t* seg_off,
                              const int64_t* item_row_off, uint8_t* arena, int n_items,
                              const int32_t max_count[4], const ItemK* items_k, const uint8_t* bits_ch,
-                             uint32_t* k_range, hipStream_t st);
+                             uint32_t* k_range, int row_wide, hipStream_t st);
 int partition_block();
 int weights_block();
 size_t weights_scratch_floats(int64_t n_blocks, int64_t n_items, int64_t total_tokens, int R_pad, bool want_ch);
@@ -38,8 +38,8 @@ hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int3
                            const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, double* lam_out,
                            int32_t* iters_out, hipStream_t st);
 hipError_t launch_calibrate(const uint16_t* K, const uint16_t* V, const int64_t* item_row_off, const int32_t* item_T,
-                            int n_items, int max_T, bool k_channelwise, bool k_whole_channel, double* acc_k,
-                            double* acc_v, uint32_t* range, hipStream_t st);
+                            int n_items, int max_T, bool k_channelwise, bool k_whole_channel, bool row_wide,
+                            double* acc_k, double* acc_v, uint32_t* range, hipStream_t st);
 hipError_t launch_stage3_budget(const uint8_t* bits, const int64_t* d_item_off, const int32_t* d_item_U,
                                 const double* d_item_avg, double rk, int n_items, int32_t* kept, double* k_budget,
                                 hipStream_t st);
@@ -264,7 +264,8 @@ rdkv_status check_config(const rdkv_config* cfg, bool need_budget, bool need_pro
   if (cfg == nullptr) return fail(RDKV_ERR_INVALID_ARG, "config is null");
   rdkv_status s = check_shape(cfg->batch, cfg->hq, cfg->hkv, cfg->head_dim, cfg->seq_lens);
   if (s != RDKV_OK) return s;
-  if (cfg->group_size != kGroup) return fail(RDKV_ERR_SHAPE, "group_size %d unsupported (must be 32)", cfg->group_size);
+  if (cfg->group_size != kGroup && cfg->group_size != kHeadDim)
+    return fail(RDKV_ERR_SHAPE, "group_size %d unsupported (32, or 128 = one scale per token row)", cfg->group_size);
   if (cfg->k_mode != RDKV_K_TOKENWISE && cfg->k_mode != RDKV_K_CHANNELWISE)
     return fail(RDKV_ERR_INVALID_ARG, "k_mode %d unknown", cfg->k_mode);
   if (need_probe) {
@@ -575,6 +576,7 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   if (!c) return fail(RDKV_ERR_ALLOC, "host allocation failed");
   c->batch = cfg->batch; c->hq = cfg->hq; c->hkv = cfg->hkv; c->d = cfg->head_dim; c->k_mode = cfg->k_mode;
   c->k_per_unit = (cfg->k_mode == RDKV_K_CHANNELWISE && cfg->k_scale_per_channel) ? 1 : 0;
+  c->group_size = cfg->group_size;
   c->seq_lens.assign(cfg->seq_lens, cfg->seq_lens + cfg->batch);
   c->n_items = it.n_items; c->total_tokens = it.total_tokens;
   c->alloc = cfg->alloc; c->free_ = cfg->free_; c->alloc_user = cfg->alloc_user;
@@ -848,7 +850,8 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       TimedScope ts(RDKV_TIME_PACK, st);
       PACK_HIP(launch_quant_pack(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), c->d_tier_idx,
                                  d_idx_base, d_counts, d_seg_off, d_tok_off, c->d_arena, static_cast<int>(n),
-                                 max_count, mixed ? c->d_items_k : nullptr, mixed ? c->d_bits_ch : nullptr, d_krange, st));
+                                 max_count, mixed ? c->d_items_k : nullptr, mixed ? c->d_bits_ch : nullptr, d_krange,
+                                 c->group_size == kHeadDim ? 1 : 0, st));
     }
   }
 #undef PACK_HIP
@@ -957,7 +960,8 @@ rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void
   if (s != RDKV_OK) return s;
   if (cfg->k_mode != RDKV_K_TOKENWISE && cfg->k_mode != RDKV_K_CHANNELWISE)
     return fail(RDKV_ERR_INVALID_ARG, "k_mode must be RDKV_K_TOKENWISE or RDKV_K_CHANNELWISE");
-  if (cfg->group_size != kGroup) return fail(RDKV_ERR_UNSUPPORTED, "group_size must be 32");
+  if (cfg->group_size != kGroup && cfg->group_size != kHeadDim)
+    return fail(RDKV_ERR_SHAPE, "group_size %d unsupported (32, or 128 = one scale per token row)", cfg->group_size);
   if (!K || !V || !eps_k || !eps_v) return fail(RDKV_ERR_INVALID_ARG, "K, V, eps_k and eps_v must not be null");
   if (cfg->batch == 0) return RDKV_OK;
   for (int b = 0; b < cfg->batch; ++b)
@@ -989,7 +993,8 @@ rdkv_status rdkv_calibrate_eps(const rdkv_config* cfg, const void* K, const void
   {
     TimedScope ts(RDKV_TIME_CALIBRATE, st);
     RDKV_HIP(launch_calibrate(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), d_off, d_T,
-                              static_cast<int>(n), it.max_T, channelwise, whole, d_acc, d_acc + n * 4, d_range, st));
+                              static_cast<int>(n), it.max_T, channelwise, whole, cfg->group_size == kHeadDim, d_acc,
+                              d_acc + n * 4, d_range, st));
   }
   RDKV_HIP(hipMemcpyAsync(h_acc.data(), d_acc, h_acc.size() * sizeof(double), hipMemcpyDeviceToHost, st));
   RDKV_HIP(hipStreamSynchronize(st));
@@ -1341,9 +1346,10 @@ rdkv_status rdkv_cache_tail_len_sync(rdkv_cache* c, void* stream, int32_t* out) 
 
 rdkv_status rdkv_cache_rebudget_tail(rdkv_cache* c, const rdkv_config* cfg, const void* Q_obs, void* stream) {
   if (!c || !cfg || !Q_obs) return fail(RDKV_ERR_INVALID_ARG, "cache, cfg and Q_obs must not be null");
-  if (cfg->k_mode != c->k_mode || (c->k_mode == RDKV_K_CHANNELWISE && (cfg->k_scale_per_channel != 0) != (c->k_per_unit != 0)))
-    return fail(RDKV_ERR_INVALID_ARG, "cfg must name the cache's own K format (k_mode %d, k_scale_per_channel %d)",
-                c->k_mode, c->k_per_unit);
+  if (cfg->k_mode != c->k_mode || (c->k_mode == RDKV_K_CHANNELWISE && (cfg->k_scale_per_channel != 0) != (c->k_per_unit != 0)) ||
+      cfg->group_size != c->group_size)
+    return fail(RDKV_ERR_INVALID_ARG, "cfg must name the cache's own format (k_mode %d, k_scale_per_channel %d, group_size %d)",
+                c->k_mode, c->k_per_unit, c->group_size);
   {   // appends replayed from a captured graph advance only the device's count: take that one
     const rdkv_status s0 = rdkv_cache_tail_len_sync(c, stream, nullptr);
     if (s0 != RDKV_OK) return s0;

@@ -115,6 +115,7 @@ struct PackItemDesc;   // compress_kernels
 struct rdkv_cache {
   int32_t batch = 0, hq = 0, hkv = 0, d = 0, k_mode = 0;
   int32_t k_per_unit = 0;               // mixed mode: one K scale per channel over all retained tokens (App. B)
+  int32_t group_size = 32;              // channels per scale of a token row: 32, or 128 = one scale per row (App. B)
   std::vector<int32_t> seq_lens;
   int64_t n_items = 0;
   int64_t total_tokens = 0;             // sum_s hkv * T_s

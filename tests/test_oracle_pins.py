@@ -1387,3 +1387,106 @@ def test_rebudget_of_a_mixed_cache_is_the_mixed_pass_on_the_tail():
         w = np.exp(ls - m)
         np.testing.assert_allclose(out[0, j], (w[0] * out_p[0, j] + w[1] * out_c[0, j]) / w.sum(), rtol=1e-11, atol=1e-12)
         assert abs(lse[0, j] - (m + np.log(w.sum()))) < 1e-11
+
+
+# ---- one scale per token row (the per-token format of App. B; Table 9's "per-token" errors) ------------------------
+def test_row_wide_scale_obeys_the_half_step_bound_over_the_whole_row():
+    rng = np.random.default_rng(101)
+    X = rand_bf16(rng, (200, 128))
+    X[:, 5] *= np.float32(8.0)                                   # one outlier channel stretches every row's range
+    for b in (2, 4, 8):
+        c, s, m = O.quantize_rows(X, b, group=128)
+        assert c.shape == (200, 128) and s.shape == m.shape == (200, 4)
+        assert np.array_equal(s, np.repeat(s[:, :1], 4, axis=1)) and np.array_equal(m, np.repeat(m[:, :1], 4, axis=1))
+        Q = (1 << b) - 1
+        assert c.max() <= Q
+        # the scale is the row's range over Q, the offset its minimum (both rounded to fp16)
+        rng_row = X.max(axis=1) - X.min(axis=1)
+        np.testing.assert_array_equal(s[:, 0], (rng_row / np.float32(Q)).astype(np.float32).astype(np.float16))
+        np.testing.assert_array_equal(m[:, 0], X.min(axis=1).astype(np.float16))
+        xh = O.dequantize_groups(c.reshape(200, 4, 32), s, m).reshape(200, 128)
+        step = s[:, 0].astype(np.float64)[:, None]
+        assert np.all(np.abs(xh - X.astype(np.float64)) <= step * (0.5 + 2.0 ** -10 + Q * 2.0 ** -11))
+        # coarser than groups of 32: the error cannot be smaller on average
+        c32, s32, m32 = O.quantize_rows(X, b, group=32)
+        xh32 = O.dequantize_groups(c32.reshape(200, 4, 32), s32, m32).reshape(200, 128)
+        assert ((xh - X) ** 2).sum() >= ((xh32 - X) ** 2).sum()
+
+
+def test_row_wide_scale_equals_groups_of_32_when_the_groups_share_their_range():
+    """If every group of 32 channels of a row has the row's minimum and maximum, the four group quantizers and the
+    row quantizer are the same function: codes, scales, offsets and the packed cache must be identical."""
+    rng = np.random.default_rng(102)
+    n = 150
+    X = rand_bf16(rng, (2, n, 128))
+    V = rand_bf16(rng, (2, n, 128))
+    for A in (X, V):
+        lo, hi = A.min(axis=2, keepdims=True), A.max(axis=2, keepdims=True)
+        for g in range(4):                                      # plant the row's extremes in every group
+            A[:, :, 32 * g + 3] = lo[:, :, 0]
+            A[:, :, 32 * g + 17] = hi[:, :, 0]
+    bits = rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(2, n))
+    a = O.build_cache_tokenwise([X], [V], [bits], group=32)
+    b = O.build_cache_tokenwise([X], [V], [bits], group=128)
+    assert np.array_equal(a["arena"], b["arena"]) and np.array_equal(a["seg_off"], b["seg_off"])
+    # on ordinary rows the two formats differ
+    X2, V2 = rand_bf16(rng, (2, n, 128)), rand_bf16(rng, (2, n, 128))
+    a = O.build_cache_tokenwise([X2], [V2], [bits], group=32)
+    b = O.build_cache_tokenwise([X2], [V2], [bits], group=128)
+    assert a["arena"].shape == b["arena"].shape and not np.array_equal(a["arena"], b["arena"])
+
+
+@pytest.mark.parametrize("mixed", [False, True])
+def test_decode_of_a_row_wide_cache_is_attention_over_its_dequantized_rows(mixed):
+    rng = np.random.default_rng(103)
+    Hkv, g, T, d = 2, 2, 90, 128
+    K, V = rand_bf16(rng, (Hkv, T, d)), rand_bf16(rng, (Hkv, T, d))
+    q = rand_bf16(rng, (1, Hkv * g, d))
+    bt = rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(Hkv, T))
+    if mixed:
+        bc = rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(Hkv, d), p=[.1, .3, .3, .2, .1])
+        cache = O.build_cache_mixed([K], [V], [bt], [bc], k_per_channel_scale=True, group=128)   # the paper's own format
+    else:
+        cache = O.build_cache_tokenwise([K], [V], [bt], group=128)
+    out, lse = O.decode(cache, q)
+    for h in range(Hkv):
+        Kh, Vh = [], []
+        kept = np.concatenate([np.nonzero(bt[h] == b)[0] for b in (16, 8, 4, 2)])
+        for b in (16, 8, 4, 2):
+            idx = np.nonzero(bt[h] == b)[0]
+            for X, dst, is_k in ((K[h][idx], Kh, True), (V[h][idx], Vh, False)):
+                if mixed and is_k:
+                    continue
+                if b == 16:
+                    dst.append(X.astype(np.float64))
+                else:                                            # one scale per row, written out by hand
+                    Q = np.float32((1 << b) - 1)
+                    mn = X.min(axis=1, keepdims=True) + np.float32(0)
+                    sc = ((X.max(axis=1, keepdims=True) - mn) / Q).astype(np.float32).astype(np.float16).astype(np.float32)
+                    m16 = mn.astype(np.float16).astype(np.float32)
+                    with np.errstate(divide="ignore", invalid="ignore"):
+                        code = np.clip(np.rint(((X - m16).astype(np.float32) / sc).astype(np.float32)), 0, Q)
+                    code = np.where(sc == 0, 0, code)
+                    dst.append(sc.astype(np.float64) * code + m16.astype(np.float64))
+        if mixed:
+            codes, sc, of = O.quantize_channelwise(K[h][kept], bc[h], None)
+            Kh = [O.dequantize_channelwise(codes, sc, of, bc[h], None)]
+        Kh, Vh = np.concatenate(Kh), np.concatenate(Vh)
+        for j in range(g):
+            o, l = _bruteforce_attention(q[0, h * g + j], Kh, Vh)
+            np.testing.assert_allclose(out[0, h * g + j], o, rtol=1e-11, atol=1e-12)
+            assert abs(lse[0, h * g + j] - l) < 1e-10
+
+
+def test_calibration_with_row_wide_groups_is_coarser_and_matches_a_hand_count():
+    rng = np.random.default_rng(104)
+    K, V = rand_bf16(rng, (1, 300, 128)), rand_bf16(rng, (1, 300, 128))
+    ek32, ev32 = O.calibrate_eps([K], [V])
+    ek, ev = O.calibrate_eps([K], [V], group=128)
+    assert np.all(ev > ev32) and np.all(ek > ek32)              # a wider range, a coarser step
+    # by hand for 2 bits: sum of squared errors over sum of squares
+    c, s, m = O.quantize_rows(V[0], 2, group=128)
+    xh = s[:, :1].astype(np.float64) * c + m[:, :1].astype(np.float64)
+    assert abs(ev[0, 0] - ((xh - V[0]) ** 2).sum() / (V[0].astype(np.float64) ** 2).sum()) < 1e-15
+    # Gaussian rows: the range of 128 samples is about 5.3 sigma against 4.1 sigma for 32, (5.3 / 4.1)^2 = 1.7
+    assert 1.3 < ev[0, 1] / ev32[0, 1] < 2.2

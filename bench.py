@@ -188,6 +188,8 @@ def main():
     hooks = b.torch_allocator_hooks()
     cfgs = [b.Config([T], hq, hkv, budget_bits=budgets, s_obs=wl.s_obs, **hooks) for _ in range(L)]
     caches = []
+    # one untimed pass over layer 0 first: the caching allocator takes its blocks, the library its pinned staging ring
+    b.rdkv_compress(cfgs[0], Ks[0], Vs[0], Qobs_all[0:1]).free()
     b.rdkv_kernel_timing_enable(True)
     torch.cuda.synchronize()
     t0 = time.time()
@@ -254,12 +256,18 @@ def main():
     n_k, ms_k = b.rdkv_kernel_timing_read(b.RDKV_TIME_DECODE_TIERED)
     b.rdkv_kernel_timing_enable(False)
     assert torch.equal(outs, ref_out), "graph replay and eager launches disagree"
-    kern_ms = ms_k / max(n_k, 1)
+    kern_ms_eager = ms_k / max(n_k, 1)
+    # One rdkv_decode_attn call is one kernel launch (split and merge in the same kernel), so the average launch
+    # duration in the timed configuration is the timed region over its launches: HIP events on the launch stream
+    # around the K replays of the L-kernel graph.  rocprofv3's per-kernel average of the same command is committed
+    # under profiles/ and read back below; kernels in a replayed graph abut, so the two agree.
+    kern_ms = ms_step / L
     achieved = alg_bytes_layer / (kern_ms * 1e-3) / 1e9
 
     if args.per_layer_only:
         print(json.dumps({"per_layer_only": True, "ms_per_step": ms_step, "kernel_ms": kern_ms,
-                          "bytes_per_launch": alg_bytes_layer, "achieved_gbs": achieved}))
+                          "kernel_ms_eager_event_bracket": kern_ms_eager, "bytes_per_launch": alg_bytes_layer,
+                          "achieved_gbs": achieved}))
         return
 
     # where a per-layer launch spends its time: the same two kernels over a cache of 256 tokens (launch and latency
@@ -487,37 +495,61 @@ def main():
         for _ in range(reps):
             o_ref, _ = O.decode(ref, qc)
         t_dec = (time.time() - t0) / reps
+        t_dec_1 = None
+        try:                                   # the same decode with the numerical libraries held to one thread
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                t0 = time.time()
+                O.decode(ref, qc)
+                t_dec_1 = time.time() - t0
+        except Exception:
+            pass
         scale = (hkv / n_heads) * L
         got = ref_out[0, 0, :n_heads * g].cpu().numpy().astype(np.float64)
         cpu = {"value": t_dec * scale * 1e3, "unit": "ms", "cores": int(threads), "kind": "oracle",
                "sample": f"{n_heads} of {hkv} KV heads of layer 0 (1/{int(scale)} of the step), "
                          f"decode timed {reps}x and scaled; oracle compress of the sample took {t_comp:.1f} s",
+               "value_1_thread": None if t_dec_1 is None else t_dec_1 * scale * 1e3,
                "compress_ms_scaled": t_comp * scale * 1e3,
                "gpu_vs_oracle_sample_max_abs_diff": float(np.abs(got - o_ref[0]).max())}
 
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
     # calibrated against a copy of known size); null when the summary is absent
     traffic = None
+    kern_ms_rocprof = None
+    standard = args.workload == "stack128k" and not (args.ctx or args.layers or args.budget)
     tpath = os.path.join(ROOT, "profiles", "decode_stack128k_pmc_traffic.txt")
-    if os.path.exists(tpath) and args.workload == "stack128k" and not (args.ctx or args.layers or args.budget):
+    if os.path.exists(tpath) and standard:
         with open(tpath) as f:
             for line in f:
                 if line.startswith("hbm_bytes_per_launch"):
                     traffic = float(line.split("=")[1])
+    kpath = os.path.join(ROOT, "profiles", "bench_stack128k_kernel_trace.txt")
+    if os.path.exists(kpath) and standard:
+        with open(kpath) as f:
+            for line in f:
+                if line.startswith("decode_kernel_avg_us_per_layer_launch"):
+                    kern_ms_rocprof = float(line.split("=")[1]) * 1e-3
 
     result = {
         "metric": "decode-attn step latency at 128K ctx (32-layer stack, compressed KV), 1 MI355X",
         "value": ms_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16 in / fp16 MFMA operands / fp32 accumulate", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {L} layers x (Hq={hq}, Hkv={hkv}, d={d}), B=1, T={T}, "
                                f"avg budget {budgets[0]} bit/elt, token-wise tiers {{16,8,4,2,0}}, group 32",
                    "launch": "one rdkv_decode_attn call per layer, " + ("eager" if args.no_graph else "HIP graph replay"),
                    "tokens_per_s": 1e3 / ms_step},
-        "roofline": {"bound": "hbm", "kernel": "decode_tiles_kernel (per-layer launch)",
+        "roofline": {"bound": "hbm", "kernel": "decode_tiles_kernel (per-layer launch, split and merge in one kernel)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "bytes_per_launch": alg_bytes_layer, "kernel_ms": kern_ms,
-                     "launches_timed": n_k},
+                     "traffic": traffic, "traffic_source": "committed rocprofv3 --pmc summary (profiles/), not this run",
+                     "bytes_per_launch": alg_bytes_layer, "kernel_ms": kern_ms,
+                     "kernel_ms_source": "HIP events around the timed graph replays / (steps x layers): one kernel per layer",
+                     "kernel_ms_rocprof": kern_ms_rocprof,
+                     "frac_rocprof": None if not kern_ms_rocprof else alg_bytes_layer / (kern_ms_rocprof * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "kernel_ms_eager_event_bracket": kern_ms_eager, "launches_timed": args.steps * L,
+                     "note": "a 16 MB launch is latency-bound (2 us of HBM time); batched_launch and tier_sweep in "
+                             "profiles/ show the bandwidth the same kernel reaches with more bytes per launch"},
         "cpu_baseline": cpu,
         "cache": {"rows_16_8_4_2": rows, "stored_bytes": stored, "dense_bf16_bytes": dense,
                   "memory_ratio": dense / max(stored, 1), "n_chunks": n_chunks,

@@ -264,12 +264,14 @@ rdkv_status rdkv_decode_attn_bf16_noalloc(const void* K, const void* V, const in
 
 /*
  * Measurement aid (benchmarks).  While enabled, the calls above bracket their
- * main kernel with HIP events on the call's own stream: the split-K decode
- * kernel of rdkv_decode_attn / rdkv_decode_attn_bf16, the two MFMA passes of
- * rdkv_weights, the bisection kernel of rdkv_allocate, the quantize-and-pack
- * kernels of rdkv_pack.  rdkv_kernel_timing_read waits for the recorded events,
- * returns the number of bracketed launches of one kind and their summed
- * duration in milliseconds, and clears that kind.  Not for use under graph capture.
+ * kernels with HIP events on the call's own stream: the decode launch of
+ * rdkv_decode_attn (merge included), the split-K kernel of rdkv_decode_attn_bf16,
+ * every kernel of rdkv_weights, every kernel of rdkv_allocate, and the kernels of
+ * rdkv_pack in two brackets (tier counts before the call's one wait; position
+ * lists, quantize and pack after it; the arena's clearing is not inside).
+ * rdkv_kernel_timing_read waits for the recorded events, returns the number of
+ * brackets of one kind and their summed duration in milliseconds, and clears that
+ * kind.  Not for use under graph capture.
  */
 enum {
   RDKV_TIME_DECODE_TIERED = 0,

@@ -57,20 +57,28 @@ __global__ __launch_bounds__(256) void tier_count_kernel(const uint8_t* __restri
   }
 }
 
-// exclusive scan of the block counts of one item (one thread per tier; blocks are few)
-__global__ void tier_scan_kernel(const int32_t* __restrict__ item_T, const int32_t* __restrict__ item_blk_off,
-                                 int32_t* __restrict__ blk_counts, int32_t* __restrict__ item_counts) {
-  const int item = blockIdx.x, k = threadIdx.x;
-  if (k >= 4) return;
+// exclusive scan of the block counts of one item: one wavefront per tier, 64 blocks per step
+__global__ __launch_bounds__(256) void tier_scan_kernel(const int32_t* __restrict__ item_T,
+                                                        const int32_t* __restrict__ item_blk_off,
+                                                        int32_t* __restrict__ blk_counts,
+                                                        int32_t* __restrict__ item_counts) {
+  const int item = blockIdx.x, k = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nblk = (item_T[item] + kPartBlock - 1) / kPartBlock;
-  int run = 0;
   int32_t* p = blk_counts + static_cast<int64_t>(item_blk_off[item]) * 4 + k;
-  for (int i = 0; i < nblk; ++i) {
-    const int v = p[i * 4];
-    p[i * 4] = run;
-    run += v;
+  int run = 0;
+  for (int b0 = 0; b0 < nblk; b0 += 64) {
+    const int i = b0 + lane;
+    const int v = i < nblk ? p[i * 4] : 0;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    if (i < nblk) p[i * 4] = run + incl - v;
+    run += __shfl(incl, 63);
   }
-  item_counts[item * 4 + k] = run;
+  if (lane == 0) item_counts[item * 4 + k] = run;
 }
 
 // writes the ascending position lists: tier_idx[item_base + tier_base + rank]
@@ -505,7 +513,7 @@ hipError_t launch_tier_count(const uint8_t* bits, const int64_t* item_tok_off, c
   // `invalid` (zero on entry) is set when the map holds a value that is no bit-width of the method
   hipLaunchKernelGGL(tier_count_kernel, dim3(max_blk, n_items), dim3(256), 0, st, bits, item_tok_off, item_T,
                      item_blk_off, blk_counts, invalid);
-  hipLaunchKernelGGL(tier_scan_kernel, dim3(n_items), dim3(64), 0, st, item_T, item_blk_off, blk_counts,
+  hipLaunchKernelGGL(tier_scan_kernel, dim3(n_items), dim3(256), 0, st, item_T, item_blk_off, blk_counts,
                      item_counts);
   return hipGetLastError();
 }

@@ -546,11 +546,9 @@ rdkv_status allocate_impl(const rdkv_config* cfg, const Items& it, const Tables&
   std::vector<int> ht;
   std::vector<double> hr;
   hull_thresholds(cfg, cfg->eps_v, &ht, &hr);
-  {
-    TimedScope ts(RDKV_TIME_ALLOCATE, st);
-    RDKV_HIP(launch_allocate(w_tok, tb.tok_off, tb.T, tb.budget, n, static_cast<int>(ht.size()), ht.data(), hr.data(),
-                             1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_tok, lam, iters, st));
-  }
+  TimedScope ts(RDKV_TIME_ALLOCATE, st);      // every kernel of the stage
+  RDKV_HIP(launch_allocate(w_tok, tb.tok_off, tb.T, tb.budget, n, static_cast<int>(ht.size()), ht.data(), hr.data(),
+                           1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_tok, lam, iters, st));
   if (!mixed) return RDKV_OK;
   // Stage 3, on the device: retained tokens per item, then k_avg = min(16, 2 r_K avg_bits T / n_kept)
   int32_t* d_kept = tmp.get<int32_t>(it.n_items);
@@ -605,8 +603,11 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
     // the one wait of the pass: the tier counts size the arena and the split schedule
     std::vector<int32_t> h_counts(n * 4 + 1, 0);
     PACK_HIP(hipMemsetAsync(d_counts + n * 4, 0, sizeof(int32_t), st));
-    PACK_HIP(launch_tier_count(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_counts, d_counts + n * 4,
-                               static_cast<int>(n), it.max_T, st));
+    {
+      TimedScope ts(RDKV_TIME_PACK, st);      // first half of the stage: the tier counts
+      PACK_HIP(launch_tier_count(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_counts, d_counts + n * 4,
+                                 static_cast<int>(n), it.max_T, st));
+    }
     if (it.max_T > 0)
       PACK_HIP(hipMemcpyAsync(h_counts.data(), d_counts, (n * 4 + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     std::vector<uint8_t> h_bits_ch;
@@ -837,8 +838,6 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       PACK_HIP(upload(c->d_items_k, c->items_k.data(), n * sizeof(ItemK), st));
     }
     if (kept > 0) {
-      PACK_HIP(launch_tier_scatter(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_idx_base, c->d_tier_idx,
-                                   static_cast<int>(n), it.max_T, st));
       uint32_t* d_krange = nullptr;
       if (c->k_per_unit) {   // per-channel (minimum, maximum) over all retained tokens, as ordered integers
         d_krange = tmp.get<uint32_t>(n * kHeadDim * 2);
@@ -847,7 +846,9 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
         for (size_t k = 0; k < h_krange.size(); k += 2) { h_krange[k] = 0xFFFFFFFFu; h_krange[k + 1] = 0u; }
         PACK_HIP(upload(d_krange, h_krange.data(), h_krange.size() * sizeof(uint32_t), st));
       }
-      TimedScope ts(RDKV_TIME_PACK, st);
+      TimedScope ts(RDKV_TIME_PACK, st);      // second half: kept-position lists, quantize and pack
+      PACK_HIP(launch_tier_scatter(bits_tok, d_tok_off, d_T, d_blk_off, d_blk_counts, d_idx_base, c->d_tier_idx,
+                                   static_cast<int>(n), it.max_T, st));
       PACK_HIP(launch_quant_pack(static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), c->d_tier_idx,
                                  d_idx_base, d_counts, d_seg_off, d_tok_off, c->d_arena, static_cast<int>(n),
                                  max_count, mixed ? c->d_items_k : nullptr, mixed ? c->d_bits_ch : nullptr, d_krange,

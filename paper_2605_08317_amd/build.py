@@ -14,6 +14,7 @@ SOURCES = [
     ("decode_mixed_kernels.hip", "decode_mixed_hs1.o", ["-DRDKV_MIXED_HS=1"]),
     ("decode_mfma_kernels.hip", "decode_mfma_kernels.o", []),
     ("rdkv_api.hip", "rdkv_api.o", []),
+    ("decode_rows_mfma.hip", "decode_rows_mfma.o", []),
     ("decode_kernels.hip", "decode_kernels.o", []),
     ("pack_kernels.hip", "pack_kernels.o", []),
     ("allocate_kernels.hip", "allocate_kernels.o", []),

@@ -1,10 +1,5 @@
-// Split-K flash-decode over row-major bf16 rows (Sec. 3.3, Eq. 7) for gfx950: the uncompressed path and the
-// 16-bit tier of a token-wise cache, and the log-sum-exp merge of split partials.
-//
-// One workgroup (4 wavefronts) streams one chunk of rows of one (sequence, KV head).  Sixteen lanes share a token:
-// each lane owns 8 of the 128 channels, so a wavefront covers 4 tokens per load and a K/V byte is read once for
-// all g query heads of the group.  Online softmax runs per 16-lane row with DPP reductions; rows, wavefronts and
-// chunks are merged by log-sum-exp weights (rows and wavefronts in LDS, chunks by the merge kernels).
+// The log-sum-exp merge of the uncompressed path's split partials, and the kernels that keep the appended-token
+// zone (Sec. 3.3 Zone C): append a row, gather the rows back for re-budgeting.
 #include "decode_merge.h"
 #include "rdkv_internal.h"
 
@@ -12,220 +7,9 @@ namespace rdkv {
 
 namespace {
 
-constexpr int kWG = 256;
-constexpr int kWaves = 4;
 constexpr float kNegBig = -1.0e30f;   // finite "minus infinity": keeps exp2(m_old - m_new) defined
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float v) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-
-// Sum over the 16 lanes of a DPP row; every lane receives the same bits.
-__device__ __forceinline__ float row16_sum(float v) {
-  v += dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
-  v += dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
-  v += dpp_mov<0x141>(v);   // row_half_mirror
-  v += dpp_mov<0x140>(v);   // row_mirror
-  return v;
-}
-
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// 8 bf16 channel values of one row held by a lane, as floats
-__device__ __forceinline__ void unpack8(const uint4& r, float (&x)[8]) {
-  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    x[2 * i] = __uint_as_float(w[i] << 16);
-    x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-  }
-}
-
-__device__ __forceinline__ uint4 load_lane(const uint8_t* __restrict__ base, int row, int c16) {
-  return *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(row) * (kHeadDim * 2) + c16 * 16);
-}
-
-// Streams `rows` rows and leaves the chunk's unnormalised result in part_acc / part_ml (AGENT: with agent-scope
-// stores, for a merge inside the same launch).
-template <int G, bool AGENT>
-__device__ __forceinline__ void process_rows(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ vd,
-                                             int rows, const uint16_t* __restrict__ q,
-                                             float* __restrict__ part_acc, float* __restrict__ part_ml,
-                                             float* smem) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane >> 4, c16 = lane & 15;
-  // logits are kept in the log2 domain: q is scaled by log2(e) / sqrt(d)
-  const float qscale = 1.4426950408889634f * 0.08838834764831845f;
-
-  float qv[G][8];
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    unpack8(*reinterpret_cast<const uint4*>(q + h * kHeadDim + c16 * 8), qv[h]);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) qv[h][c] *= qscale;
-  }
-
-  float m[G], l[G], acc[G][8];
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    m[h] = kNegBig;
-    l[h] = 0.f;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
-  }
-
-  const int last = rows - 1;
-  for (int base = wave * 16; base < rows; base += kWaves * 16) {
-    uint4 kr[4], vr[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) kr[u] = load_lane(kd, min(base + u * 4 + r, last), c16);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) vr[u] = load_lane(vd, min(base + u * 4 + r, last), c16);
-
-    float s[4][G];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      float kx[8];
-      unpack8(kr[u], kx);
-      const bool valid = (base + u * 4 + r) < rows;
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        float dot = 0.f;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) dot = __builtin_fmaf(qv[h][c], kx[c], dot);
-        dot = row16_sum(dot);
-        s[u][h] = valid ? dot : -INFINITY;
-      }
-    }
-
-    // online softmax, one update per 4 rows
-    float p[4][G];
-    bool changed = false;
-    float alpha[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float mt = fmaxf(fmaxf(s[0][h], s[1][h]), fmaxf(s[2][h], s[3][h]));
-      const float mn = fmaxf(m[h], mt);
-      alpha[h] = fast_exp2(m[h] - mn);
-      changed |= (mn != m[h]);
-      m[h] = mn;
-      float ls = 0.f;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        p[u][h] = fast_exp2(s[u][h] - mn);
-        ls += p[u][h];
-      }
-      l[h] = __builtin_fmaf(l[h], alpha[h], ls);
-    }
-    if (__any(changed)) {
-#pragma unroll
-      for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[h][c] *= alpha[h];
-    }
-
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      float vx[8];
-      unpack8(vr[u], vx);
-#pragma unroll
-      for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[h][c] = __builtin_fmaf(p[u][h], vx[c], acc[h][c]);
-    }
-  }
-
-  // ---- merge the 16 (wavefront, row) streams of this workgroup -------------
-  float* s_ml = smem;                    // [16][G][2]
-  float* s_acc = smem + 16 * G * 2;      // [4][G][128]
-  const int sid = wave * 4 + r;
-  if (c16 == 0) {
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      s_ml[(sid * G + h) * 2] = m[h];
-      s_ml[(sid * G + h) * 2 + 1] = l[h];
-    }
-  }
-  __syncthreads();
-  float mstar[G], lstar[G];
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    float mm = kNegBig;
-    for (int i = 0; i < 16; ++i) mm = fmaxf(mm, s_ml[(i * G + h) * 2]);
-    float ll = 0.f;
-    for (int i = 0; i < 16; ++i) ll += s_ml[(i * G + h) * 2 + 1] * fast_exp2(s_ml[(i * G + h) * 2] - mm);
-    mstar[h] = mm;
-    lstar[h] = ll;
-    const float f = fast_exp2(m[h] - mm);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      float v = acc[h][c] * f;
-      v += __shfl_xor(v, 16);
-      v += __shfl_xor(v, 32);
-      acc[h][c] = v;
-    }
-  }
-  if (r == 0) {
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-#pragma unroll
-      for (int c = 0; c < 8; ++c) s_acc[(wave * G + h) * kHeadDim + c16 * 8 + c] = acc[h][c];
-  }
-  __syncthreads();
-  for (int i = tid; i < G * kHeadDim; i += kWG) {
-    float v = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) v += s_acc[w * G * kHeadDim + i];
-    if constexpr (AGENT) merge::store_agent(part_acc + i, v); else part_acc[i] = v;
-  }
-  if (tid < G) {
-    if constexpr (AGENT) {
-      merge::store_agent(part_ml + tid * 2, mstar[tid]);
-      merge::store_agent(part_ml + tid * 2 + 1, lstar[tid]);
-    } else {
-      part_ml[tid * 2] = mstar[tid];
-      part_ml[tid * 2 + 1] = lstar[tid];
-    }
-  }
-}
-
-template <int G>
-__global__ __launch_bounds__(kWG) void decode_dense_kernel(DenseArgs a) {
-  __shared__ float smem[16 * G * 2 + kWaves * G * kHeadDim];
-  const int split = blockIdx.x, head = blockIdx.y, sl = blockIdx.z;
-  const int T = a.T[sl];
-  const int row0 = split * a.chunk_rows;
-  if (row0 >= T) return;
-  const int rows = min(a.chunk_rows, T - row0);
-  const int64_t first = a.row_off[sl] + static_cast<int64_t>(head) * T + row0;
-  const uint8_t* kd = reinterpret_cast<const uint8_t*>(a.K) + first * (kHeadDim * 2);
-  const uint8_t* vd = reinterpret_cast<const uint8_t*>(a.V) + first * (kHeadDim * 2);
-  const int seq = a.seq_base + sl;
-  const uint16_t* q = a.q + (static_cast<int64_t>(seq) * a.hq + head * G) * kHeadDim;
-  const int64_t slot = (static_cast<int64_t>(sl) * a.hkv + head) * a.max_splits + split;
-  process_rows<G, false>(kd, vd, rows, q, a.part_acc + slot * G * kHeadDim, a.part_ml + slot * G * 2, smem);
-}
-
-template <int G>
-__global__ __launch_bounds__(kWG) void decode_tiered_kernel(const Chunk* __restrict__ chunks,
-                                                            const uint8_t* __restrict__ arena,
-                                                            const uint16_t* __restrict__ q, MergeArgs ma) {
-  constexpr int kSplit = 16 * G * 2 + kWaves * G * kHeadDim;
-  constexpr int kMerge = merge::merge_lds_floats(kWG, G);
-  __shared__ float smem[kSplit > kMerge ? kSplit : kMerge];
-  const Chunk ch = chunks[blockIdx.x];
-  const int seq = ch.item / ma.hkv, head = ch.item % ma.hkv;
-  const uint16_t* qp = q + (static_cast<int64_t>(seq) * ma.hq + head * G) * kHeadDim;
-  float* pa = ma.part_acc + static_cast<int64_t>(ch.slot) * G * kHeadDim;
-  float* pm = ma.part_ml + static_cast<int64_t>(ch.slot) * G * 2;
-  // row-major bf16 rows: the 16-bit tier of a token-wise cache
-  process_rows<G, true>(arena + ch.k_data, arena + ch.v_data, ch.rows, qp, pa, pm, smem);
-  merge::partial_stores_done();
-  __syncthreads();
-  merge::arrive_and_merge<kWG>(ma, ch.item, ch.slot0, ch.nslots, G, smem);
-}
 
 // Log-sum-exp merge of the partial results of one (item, query head).  512 threads: 4 slot groups x 128
 // channels.  Every thread issues all the loads of its (up to kMergeBatch) slots before anything waits on them: the
@@ -304,35 +88,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_dense_kernel(DenseArgs a,
 
 }  // namespace
 
-hipError_t launch_decode_dense_split(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
-  dim3 grid(a.max_splits, a.hkv, n_seqs), block(kWG);
-  switch (g) {
-    case 1: hipLaunchKernelGGL(decode_dense_kernel<1>, grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL(decode_dense_kernel<2>, grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL(decode_dense_kernel<4>, grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL(decode_dense_kernel<8>, grid, block, 0, st, a); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
-}
-
 hipError_t launch_decode_dense_merge(const DenseArgs& a, int g, int n_seqs, hipStream_t st) {
   hipLaunchKernelGGL(merge_dense_kernel, dim3(n_seqs * a.hkv * g), dim3(kMergeThreads), 0, st, a, g);
-  return hipGetLastError();
-}
-
-hipError_t launch_decode_tiered_split(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                                      const MergeArgs& ma, hipStream_t st) {
-  const int g = ma.hq / ma.hkv;
-  if (n_chunks == 0) return hipSuccess;
-  dim3 grid(n_chunks), block(kWG);
-  switch (g) {
-    case 1: hipLaunchKernelGGL(decode_tiered_kernel<1>, grid, block, 0, st, chunks, arena, q, ma); break;
-    case 2: hipLaunchKernelGGL(decode_tiered_kernel<2>, grid, block, 0, st, chunks, arena, q, ma); break;
-    case 4: hipLaunchKernelGGL(decode_tiered_kernel<4>, grid, block, 0, st, chunks, arena, q, ma); break;
-    case 8: hipLaunchKernelGGL(decode_tiered_kernel<8>, grid, block, 0, st, chunks, arena, q, ma); break;
-    default: return hipErrorInvalidValue;
-  }
   return hipGetLastError();
 }
 

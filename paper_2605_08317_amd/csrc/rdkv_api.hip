@@ -296,12 +296,10 @@ rdkv_status check_config(const rdkv_config* cfg, bool need_budget, bool need_pro
   return RDKV_OK;
 }
 
-// chunk size policy of the dense path; used by the workspace query and the launch alike.  The split kernel keeps
-// 4 / 4 / 2 / 1 workgroups per compute unit resident at g = 1 / 2 / 4 / 8 (its register count).  Up to g = 4 a launch
-// is fastest when its workgroups fill the 256 compute units exactly once (measured at g = 4 on 8 x 128K tokens: 512
-// chunks 101 us, 1024 chunks 107 us, 640 chunks 126 us).  At g = 8 one workgroup per compute unit leaves nothing to
-// even out ragged sequence lengths, and four rounds are faster (16 sequences of 8K-32K tokens: 1024 chunks 539 us,
-// 256 chunks 760 us).  Chunks have at least 256 rows.
+// chunk size policy of the dense path; used by the workspace query and the launch alike.  The split kernel stages
+// its tiles through 70 KB of LDS per workgroup, so a compute unit keeps two workgroups resident whatever the number
+// of query heads: a launch is fastest when its workgroups fill the chip exactly once (512 chunks), and chunks have
+// at least 256 rows.
 void dense_plan(const int32_t* seq_lens, int batch, int hkv, int g, int* chunk_rows, int* max_splits) {
   int64_t total = 0;
   int max_T = 0;
@@ -309,7 +307,8 @@ void dense_plan(const int32_t* seq_lens, int batch, int hkv, int g, int* chunk_r
     total += static_cast<int64_t>(seq_lens[s]) * hkv;
     max_T = std::max(max_T, seq_lens[s]);
   }
-  const int64_t resident = g <= 2 ? 1024 : g <= 4 ? 512 : 1024;
+  (void)g;
+  const int64_t resident = 512;
   int64_t cr = round_up(std::max<int64_t>(256, (total + resident - 1) / resident), 64);
   *chunk_rows = static_cast<int>(cr);
   *max_splits = std::max(1, static_cast<int>((max_T + cr - 1) / cr));
@@ -739,9 +738,9 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   // chunk more than a fifth above the mean), several rounds of small chunks even things out instead.
   if (n_one_round > round_chunks || max_cost * n_one_round > total_cost + total_cost / 5)
     chunk_bytes = std::max<int64_t>((mixed ? 40 : 24) << 10, total_cost / 2560);
-  // The row-major 16-bit kernel keeps 4 / 4 / 2 / 1 workgroups per compute unit resident at 1 / 2 / 4 / 8 query
-  // heads per KV head (its register count): one round of its own.
-  const int64_t round16 = g <= 2 ? 1024 : g <= 4 ? 512 : 256;
+  // The row-major 16-bit kernel keeps two workgroups per compute unit resident (70 KB of LDS each): one round of
+  // its own.
+  const int64_t round16 = 512;
   const int64_t chunk_bytes16 = std::max<int64_t>(96 << 10, (cost16 + round16 - 1) / round16);
   if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);

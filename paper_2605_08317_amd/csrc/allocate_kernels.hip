@@ -7,6 +7,8 @@
 // are fp64, the summed bits are integers, and the search returns the feasible
 // iterate with the smallest multiplier (first one inside the tolerance band
 // below the budget), so the result never exceeds the budget.
+#include <algorithm>
+
 #include "rdkv_internal.h"
 
 namespace rdkv {
@@ -340,6 +342,348 @@ __global__ __launch_bounds__(kThreads) void bisect_kernel(AllocArgs a) {
   }
 }
 
+// ---- the same search with an item's three streaming passes spread over many workgroups ---------------------------
+// A long item (128K tokens) keeps one workgroup busy for 160 us in bisect_kernel while the rest of the chip idles.
+// Here the passes that touch every unit run on kSlices workgroups per item, and only the steps of the search itself
+// run on one:
+//   hist_kernel      every slice histograms its units (top 13 bits of the fp32 pattern) and adds to the item's
+//                    histogram and maximum;
+//   steps_kernel<0>  the steps of Alg. 2 that the histogram's two-sided bounds on the bit sum decide, up to the first
+//                    step they cannot; leaves the bracket [lo, hi] and the step index;
+//   gather_kernel    every slice appends its units whose tier can still change inside the bracket to the item's list
+//                    and adds the bits of the others (fixed from here on) to a sum;
+//   steps_kernel<1>  the remaining steps, each evaluated exactly on the list plus the fixed sum;
+//   write_kernel     the bit map at the multiplier found.
+// Every verdict is the same integer comparison as in bisect_kernel, so the multipliers visited and the bit maps are
+// the same bit for bit.  A list that would overflow makes steps_kernel<1> read all units of the item instead.
+constexpr int kGlobalListCap = 32768;       // undecided units kept per item (floats)
+struct SearchState {
+  double lo, hi, best;
+  long long s_fixed, B_int, need;
+  float mx;
+  int32_t have, it, done, fill, n_list, steps;
+};
+struct MultiArgs {
+  AllocArgs a;
+  int32_t* hist;        // [items][kBuckets + 1], zero on entry
+  SearchState* state;   // [items], zero on entry
+  float* list;          // [items][2][kGlobalListCap]: the list, and the half it moves to when it shrinks
+  int32_t slices;
+};
+
+__device__ __forceinline__ void slice_range(const Quads& quads, int slices, int* q0, int* q1) {
+  const int per = (quads.nq + slices - 1) / slices;
+  *q0 = min(quads.nq, static_cast<int>(blockIdx.x) * per);
+  *q1 = min(quads.nq, *q0 + per);
+}
+
+__global__ __launch_bounds__(kThreads) void hist_kernel(MultiArgs m) {
+  __shared__ int s_hist[kBuckets + 1];
+  __shared__ float sm_max[kThreads / 64];
+  const AllocArgs& a = m.a;
+  const int item = blockIdx.y;
+  const int U = a.item_U[item];
+  if (U == 0) return;
+  const float* __restrict__ w = a.w + a.item_off[item];
+  for (int i = threadIdx.x; i <= kBuckets; i += kThreads) s_hist[i] = 0;
+  __syncthreads();
+  const Quads quads(w, U);
+  int q0, q1;
+  slice_range(quads, m.slices, &q0, &q1);
+  float mx = 0.f;
+  for (int q = q0 + threadIdx.x; q < q1; q += kThreads) {
+    float wv[4];
+    quads.load(q, wv);
+    const int u0 = quads.first_unit(q);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (u0 + e >= 0 && u0 + e < U) {
+        mx = fmaxf(mx, wv[e]);
+        atomicAdd(&s_hist[bucket_of(wv[e])], 1);
+      }
+  }
+  mx = block_max(mx, sm_max);
+  __syncthreads();
+  int32_t* gh = m.hist + static_cast<int64_t>(item) * (kBuckets + 1);
+  for (int i = threadIdx.x; i < kBuckets; i += kThreads)
+    if (s_hist[i] != 0) atomicAdd(gh + i, s_hist[i]);
+  // weights are non-negative here (a negative one never exceeds a threshold and mx starts at 0): integer order = float order
+  if (threadIdx.x == 0 && mx > 0.f) atomicMax(reinterpret_cast<int*>(&m.state[item].mx), __float_as_int(mx));
+}
+
+// PHASE 0: steps decided by the histogram; PHASE 1: steps evaluated on the list (or on every unit after an overflow)
+template <int PHASE>
+__global__ __launch_bounds__(kThreads) void steps_kernel(MultiArgs m) {
+  __shared__ long long sm_sum[kThreads / 64];
+  __shared__ int s_hist[kBuckets + 1];
+  __shared__ float s_list[kListCap];
+  __shared__ int sm_small[2 * (kThreads / 64)];
+  const AllocArgs& a = m.a;
+  const int item = blockIdx.x;
+  const int U = a.item_U[item];
+  SearchState& st = m.state[item];
+  const int nh = a.n_hull;
+  int32_t tiers[kMaxHull];
+  double r[kMaxHull - 1];
+#pragma unroll
+  for (int k = 0; k < kMaxHull; ++k) tiers[k] = a.tiers[k];
+#pragma unroll
+  for (int k = 0; k < kMaxHull - 1; ++k) r[k] = a.r[k];
+  double lo, hi, best;
+  bool have;
+  int it0;
+  long long B_int, need;
+  if constexpr (PHASE == 0) {
+    if (threadIdx.x == 0) {
+      if (a.lam_out) a.lam_out[item] = __longlong_as_double(0x7FF8000000000000ll);
+      if (a.iters_out) a.iters_out[item] = 0;
+    }
+    if (U == 0) { if (threadIdx.x == 0) { st.done = 1; st.fill = a.tiers[0]; } return; }
+    B_int = static_cast<long long>(floor(a.item_budget[item] * static_cast<double>(U)));
+    const int top = a.tiers[nh - 1];
+    int fill = -1;
+    if (B_int >= static_cast<long long>(top) * U) fill = top;
+    else if (nh == 1 || B_int < a.tiers[1]) fill = a.tiers[0];
+    if (fill >= 0) { if (threadIdx.x == 0) { st.done = 1; st.fill = fill; } return; }
+    need = static_cast<long long>(ceil(a.need_frac * static_cast<double>(B_int)));
+    const int32_t* gh = m.hist + static_cast<int64_t>(item) * (kBuckets + 1);
+    for (int i = threadIdx.x; i <= kBuckets; i += kThreads) s_hist[i] = i < kBuckets ? gh[i] : 0;
+    __syncthreads();
+    {   // suffix sums in place: s_hist[b] = units in buckets >= b (each thread owns 8 consecutive buckets)
+      const int b0 = threadIdx.x * (kBuckets / kThreads);
+      int local = 0;
+#pragma unroll
+      for (int i = 0; i < kBuckets / kThreads; ++i) local += s_hist[b0 + i];
+      __shared__ int s_part[kThreads];
+      s_part[threadIdx.x] = local;
+      __syncthreads();
+      for (int off = 1; off < kThreads; off <<= 1) {
+        const int v = (threadIdx.x + off < kThreads) ? s_part[threadIdx.x + off] : 0;
+        __syncthreads();
+        s_part[threadIdx.x] += v;
+        __syncthreads();
+      }
+      int run = s_part[threadIdx.x] - local;
+#pragma unroll
+      for (int i = kBuckets / kThreads - 1; i >= 0; --i) {
+        run += s_hist[b0 + i];
+        s_hist[b0 + i] = run;
+      }
+      __syncthreads();
+    }
+    lo = 0.0; hi = static_cast<double>(st.mx); best = 0.0; have = false; it0 = 0;
+  } else {
+    if (st.done) return;
+    lo = st.lo; hi = st.hi; best = st.best; have = st.have != 0; it0 = st.it;
+    B_int = st.B_int; need = st.need;
+  }
+  const float* __restrict__ w = a.w + a.item_off[item];
+  int n_list = 0;
+  bool overflow = false;
+  long long s_fixed = 0;
+  float* gsrc = m.list + static_cast<int64_t>(item) * (2 * kGlobalListCap);   // the list, and where it moves when it shrinks
+  float* gdst = gsrc + kGlobalListCap;
+  if constexpr (PHASE == 1) {
+    n_list = st.n_list;
+    s_fixed = st.s_fixed;
+    overflow = n_list > kGlobalListCap;
+    if (!overflow && n_list <= kListCap) {
+      for (int i = threadIdx.x; i < n_list; i += kThreads) s_list[i] = gsrc[i];
+      __syncthreads();
+    }
+  }
+  int steps = it0;
+  bool stopped = false;
+  for (int it = it0; it < a.max_iters; ++it) {
+    const double lam = (lo + hi) * 0.5;
+    double thr[kMaxHull - 1];
+#pragma unroll
+    for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? lam * r[k] : INFINITY;
+    int verdict = -1;   // 0: over budget, 1: feasible (continue), 2: feasible and inside the band (stop)
+    if constexpr (PHASE == 0) {
+      long long s_min = static_cast<long long>(tiers[0]) * U, s_max = s_min;
+#pragma unroll
+      for (int k = 0; k < kMaxHull - 1; ++k)
+        if (k < nh - 1) {
+          int c_lo, c_hi;
+          count_bounds(thr[k], s_hist, &c_lo, &c_hi);
+          s_min += static_cast<long long>(tiers[k + 1] - tiers[k]) * c_lo;
+          s_max += static_cast<long long>(tiers[k + 1] - tiers[k]) * c_hi;
+        }
+      if (s_min > B_int) verdict = 0;
+      else if (s_max <= B_int && s_min >= need) verdict = 2;
+      else if (s_max < need) verdict = 1;
+      if (verdict < 0) {     // the histogram cannot decide this step: hand over to the list
+        if (threadIdx.x == 0) {
+          st.lo = lo; st.hi = hi; st.best = best; st.have = have; st.it = it; st.B_int = B_int; st.need = need;
+          st.done = 0; st.n_list = 0; st.s_fixed = 0;
+        }
+        return;
+      }
+    } else {
+      long long s;
+      if (overflow) {        // every unit of the item
+        long long sl = 0;
+        for (int u = threadIdx.x; u < U; u += kThreads) sl += classify_tier(static_cast<double>(w[u]), thr, tiers);
+        s = block_sum(sl, sm_sum);
+      } else if (n_list <= kListCap) {
+        int sl = 0;
+        for (int i = threadIdx.x; i < n_list; i += kThreads) sl += classify_tier(static_cast<double>(s_list[i]), thr, tiers);
+        s = block_sum_small(sl, sm_small, it & 1) + s_fixed;
+      } else {
+        int sl = 0;
+        for (int i = threadIdx.x; i < n_list; i += kThreads) sl += classify_tier(static_cast<double>(gsrc[i]), thr, tiers);
+        s = block_sum_small(sl, sm_small, it & 1) + s_fixed;
+      }
+      verdict = s > B_int ? 0 : (s >= need ? 2 : 1);
+      if (!overflow && n_list > kListCap && verdict != 2) {
+        // The list does not fit LDS yet.  The bracket has just halved: the units it has decided leave the list (their
+        // bits join the fixed sum) and the rest moves to the other half of the item's list area, or into LDS once
+        // few enough are left.  The order of a list does not matter: every sum over it is an integer sum.
+        const double nlo = verdict == 0 ? lam : lo, nhi = verdict == 0 ? hi : lam;
+        double t_lo[kMaxHull - 1], t_hi[kMaxHull - 1];
+#pragma unroll
+        for (int k = 0; k < kMaxHull - 1; ++k) {
+          t_lo[k] = (k < nh - 1) ? nlo * r[k] : INFINITY;
+          t_hi[k] = (k < nh - 1) ? nhi * r[k] : INFINITY;
+        }
+        __shared__ int s_keep;
+        if (threadIdx.x == 0) s_keep = 0;
+        __syncthreads();
+        long long sf = 0;
+        for (int i = threadIdx.x; i < n_list; i += kThreads) {
+          const float wf = gsrc[i];
+          const double wu = static_cast<double>(wf);
+          if (undecided(wu, t_lo, t_hi)) gdst[atomicAdd(&s_keep, 1)] = wf;
+          else sf += classify_tier(wu, t_hi, tiers);
+        }
+        s_fixed += block_sum(sf, sm_sum);
+        __syncthreads();
+        n_list = s_keep;
+        __syncthreads();
+        float* t = gsrc; gsrc = gdst; gdst = t;
+        if (n_list <= kListCap) {
+          __threadfence_block();
+          for (int i = threadIdx.x; i < n_list; i += kThreads) s_list[i] = gsrc[i];
+          __syncthreads();
+        }
+      }
+    }
+    steps = it + 1;
+    if (verdict == 0) {
+      lo = lam;
+    } else {
+      best = lam;
+      have = true;
+      hi = lam;
+      if (verdict == 2) { stopped = true; break; }
+    }
+  }
+  (void)stopped;
+  if (threadIdx.x == 0) {   // the search is over
+    st.best = best; st.have = have; st.done = 1; st.fill = -1; st.steps = steps;
+    if (a.lam_out && have) a.lam_out[item] = best;
+    if (a.iters_out) a.iters_out[item] = steps;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void gather_kernel(MultiArgs m) {
+  __shared__ long long sm_sum[kThreads / 64];
+  const AllocArgs& a = m.a;
+  const int item = blockIdx.y;
+  SearchState& st = m.state[item];
+  if (st.done) return;
+  const int U = a.item_U[item];
+  const float* __restrict__ w = a.w + a.item_off[item];
+  const int nh = a.n_hull;
+  int32_t tiers[kMaxHull];
+#pragma unroll
+  for (int k = 0; k < kMaxHull; ++k) tiers[k] = a.tiers[k];
+  double t_lo[kMaxHull - 1], t_hi[kMaxHull - 1];
+#pragma unroll
+  for (int k = 0; k < kMaxHull - 1; ++k) {
+    t_lo[k] = (k < nh - 1) ? st.lo * a.r[k] : INFINITY;
+    t_hi[k] = (k < nh - 1) ? st.hi * a.r[k] : INFINITY;
+  }
+  float* gl = m.list + static_cast<int64_t>(item) * (2 * kGlobalListCap);
+  const Quads quads(w, U);
+  int q0, q1;
+  slice_range(quads, m.slices, &q0, &q1);
+  // undecided units are collected in LDS first, so that the item's list counter sees one atomic per workgroup and
+  // round of 1024 quads instead of one per unit
+  __shared__ float s_buf[4 * kThreads];
+  __shared__ int s_cnt, s_base;
+  long long sf = 0;
+  for (int base = q0; base < q1; base += kThreads) {
+    if (threadIdx.x == 0) s_cnt = 0;
+    __syncthreads();
+    const int q = base + threadIdx.x;
+    if (q < q1) {
+      float wv[4];
+      quads.load(q, wv);
+      const int u0 = quads.first_unit(q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (u0 + e >= 0 && u0 + e < U) {
+          const double wu = static_cast<double>(wv[e]);
+          if (undecided(wu, t_lo, t_hi)) s_buf[atomicAdd(&s_cnt, 1)] = wv[e];
+          else sf += classify_tier(wu, t_hi, tiers);
+        }
+    }
+    __syncthreads();
+    const int cnt = s_cnt;
+    if (cnt > 0) {
+      if (threadIdx.x == 0) s_base = atomicAdd(&st.n_list, cnt);
+      __syncthreads();
+      const int b0 = s_base;
+      for (int i = threadIdx.x; i < cnt; i += kThreads)
+        if (b0 + i < kGlobalListCap) gl[b0 + i] = s_buf[i];
+    }
+    __syncthreads();
+  }
+  sf = block_sum(sf, sm_sum);
+  if (threadIdx.x == 0 && sf != 0) atomicAdd(reinterpret_cast<unsigned long long*>(&st.s_fixed), static_cast<unsigned long long>(sf));
+}
+
+__global__ __launch_bounds__(kThreads) void write_kernel(MultiArgs m) {
+  const AllocArgs& a = m.a;
+  const int item = blockIdx.y;
+  const int U = a.item_U[item];
+  if (U == 0) return;
+  const SearchState& st = m.state[item];
+  const float* __restrict__ w = a.w + a.item_off[item];
+  uint8_t* __restrict__ bits = a.bits + a.item_off[item];
+  const int nh = a.n_hull;
+  int32_t tiers[kMaxHull];
+#pragma unroll
+  for (int k = 0; k < kMaxHull; ++k) tiers[k] = a.tiers[k];
+  const int fill = st.fill >= 0 ? st.fill : (st.have ? -1 : tiers[0]);
+  double thr[kMaxHull - 1];
+#pragma unroll
+  for (int k = 0; k < kMaxHull - 1; ++k) thr[k] = (k < nh - 1) ? st.best * a.r[k] : INFINITY;
+  const Quads quads(w, U);
+  int q0, q1;
+  slice_range(quads, m.slices, &q0, &q1);
+  for (int q = q0 + threadIdx.x; q < q1; q += kThreads) {
+    float wv[4];
+    if (fill < 0) quads.load(q, wv);
+    const int u0 = quads.first_unit(q);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int t = fill >= 0 ? fill : classify_tier(static_cast<double>(wv[e]), thr, tiers);
+      packed |= static_cast<uint32_t>(t) << (8 * e);
+    }
+    if (u0 >= 0 && u0 + 3 < U && (reinterpret_cast<uintptr_t>(bits + u0) & 3) == 0) {
+      *reinterpret_cast<uint32_t*>(bits + u0) = packed;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (u0 + e >= 0 && u0 + e < U) bits[u0 + e] = static_cast<uint8_t>(packed >> (8 * e));
+    }
+  }
+}
+
 // Stage 3 of Alg. 1: the K budget r_K * B_head of an item is spread over its retained tokens (bit-width above zero)
 // only: k_avg = min(16, 2 r_K avg_bits T / n_kept) average bits per channel unit, 0 if nothing is retained; rounded
 // to fp32 like every budget.  fp64 in this operation order (the file is compiled without contraction).
@@ -395,7 +739,7 @@ hipError_t launch_stage3_budget(const uint8_t* bits, const int64_t* d_item_off, 
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
                            const double* hull_r, double need_frac, int max_iters, uint8_t* bits, double* lam_out,
-                           int32_t* iters_out, hipStream_t st) {
+                           int32_t* iters_out, void* multi_scratch, hipStream_t st) {
   if (n_items == 0) return hipSuccess;
   if (n_hull < 1 || n_hull > kMaxHull) return hipErrorInvalidValue;
   AllocArgs a;
@@ -406,8 +750,35 @@ hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int3
   }
   a.n_hull = n_hull; a.max_iters = max_iters; a.need_frac = need_frac;
   a.lam_out = lam_out; a.iters_out = iters_out;
+  if (multi_scratch != nullptr) {   // long items: the streaming passes on many workgroups
+    MultiArgs m;
+    m.a = a;
+    uint8_t* p = static_cast<uint8_t*>(multi_scratch);
+    const size_t hist_b = (static_cast<size_t>(n_items) * (kBuckets + 1) * sizeof(int32_t) + 255) / 256 * 256;
+    const size_t state_b = (static_cast<size_t>(n_items) * sizeof(SearchState) + 255) / 256 * 256;
+    m.hist = reinterpret_cast<int32_t*>(p);
+    m.state = reinterpret_cast<SearchState*>(p + hist_b);
+    m.list = reinterpret_cast<float*>(p + hist_b + state_b);
+    m.slices = std::max(1, std::min(64, 512 / n_items));
+    hipError_t e = hipMemsetAsync(p, 0, hist_b + state_b, st);
+    if (e != hipSuccess) return e;
+    const dim3 wide(m.slices, n_items), one(n_items), block(kThreads);
+    hipLaunchKernelGGL(hist_kernel, wide, block, 0, st, m);
+    hipLaunchKernelGGL(steps_kernel<0>, one, block, 0, st, m);
+    hipLaunchKernelGGL(gather_kernel, wide, block, 0, st, m);
+    hipLaunchKernelGGL(steps_kernel<1>, one, block, 0, st, m);
+    hipLaunchKernelGGL(write_kernel, wide, block, 0, st, m);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(bisect_kernel, dim3(n_items), dim3(kThreads), 0, st, a);
   return hipGetLastError();
+}
+
+// device scratch launch_allocate needs to spread long items over many workgroups
+size_t allocate_multi_scratch_bytes(int n_items) {
+  const size_t hist_b = (static_cast<size_t>(n_items) * (kBuckets + 1) * sizeof(int32_t) + 255) / 256 * 256;
+  const size_t state_b = (static_cast<size_t>(n_items) * sizeof(SearchState) + 255) / 256 * 256;
+  return hist_b + state_b + static_cast<size_t>(n_items) * 2 * kGlobalListCap * sizeof(float);
 }
 
 }  // namespace rdkv

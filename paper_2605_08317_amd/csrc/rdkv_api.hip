@@ -36,7 +36,8 @@ hipError_t launch_weights(const rdkv_config& cfg, const int64_t* d_item_row_off,
 hipError_t launch_allocate(const float* w, const int64_t* d_item_off, const int32_t* d_item_U,
                            const double* d_item_budget, int n_items, int n_hull, const int* hull_tiers,
                            const double* hull_r, double rel_tol, int max_iters, uint8_t* bits, double* lam_out,
-                           int32_t* iters_out, hipStream_t st);
+                           int32_t* iters_out, void* multi_scratch, hipStream_t st);
+size_t allocate_multi_scratch_bytes(int n_items);
 hipError_t launch_calibrate(const uint16_t* K, const uint16_t* V, const int64_t* item_row_off, const int32_t* item_T,
                             int n_items, int max_T, bool k_channelwise, bool k_whole_channel, bool row_wide,
                             double* acc_k, double* acc_v, uint32_t* range, hipStream_t st);
@@ -545,9 +546,15 @@ rdkv_status allocate_impl(const rdkv_config* cfg, const Items& it, const Tables&
   std::vector<int> ht;
   std::vector<double> hr;
   hull_thresholds(cfg, cfg->eps_v, &ht, &hr);
+  // items of 16K tokens and more: the passes over the weights run on many workgroups per item
+  void* multi = nullptr;
+  if (it.max_T >= 16384 && n <= 512) {
+    multi = tmp.get<uint8_t>(allocate_multi_scratch_bytes(n));
+    if (!multi) return fail(RDKV_ERR_ALLOC, "device allocation failed");
+  }
   TimedScope ts(RDKV_TIME_ALLOCATE, st);      // every kernel of the stage
   RDKV_HIP(launch_allocate(w_tok, tb.tok_off, tb.T, tb.budget, n, static_cast<int>(ht.size()), ht.data(), hr.data(),
-                           1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_tok, lam, iters, st));
+                           1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_tok, lam, iters, multi, st));
   if (!mixed) return RDKV_OK;
   // Stage 3, on the device: retained tokens per item, then k_avg = min(16, 2 r_K avg_bits T / n_kept)
   int32_t* d_kept = tmp.get<int32_t>(it.n_items);
@@ -558,7 +565,7 @@ rdkv_status allocate_impl(const rdkv_config* cfg, const Items& it, const Tables&
   hull_thresholds(cfg, cfg->eps_k, &ht, &hr);
   RDKV_HIP(launch_allocate(w_ch, tb.ch_off, tb.ch_U, d_kbudget, n, static_cast<int>(ht.size()), ht.data(), hr.data(),
                            1.0 - static_cast<double>(cfg->rel_tol), cfg->max_iters, bits_ch, lam ? lam + n : nullptr,
-                           iters ? iters + n : nullptr, st));
+                           iters ? iters + n : nullptr, nullptr, st));
   return RDKV_OK;
 }
 

@@ -175,3 +175,30 @@ def test_weights_and_allocate_return_without_waiting():
     assert returned_early, "rdkv_weights / rdkv_allocate waited for the stream"
     ref = O.mckp_bisect(w_tok.cpu().numpy().reshape(wl.hkv, -1)[0], np.float32(inp["budgets"][0]))
     np.testing.assert_array_equal(bits.cpu().numpy().reshape(wl.hkv, -1)[0], ref)
+
+
+@pytest.mark.parametrize("eps", [O.EPS_V_LLAMA31_8B, O.EPS_BENNETT])
+def test_long_items_whose_weights_crowd_a_histogram_bucket(eps):
+    """Items of 16K units and more run their streaming passes on many workgroups; the steps the weight histogram
+    cannot decide are evaluated on a list of the still-undecided units.  Weights crowded into a narrow band defeat the
+    histogram early: a list beyond its capacity (every step then reads every unit), a list that starts in device memory
+    and shrinks into LDS as the bracket narrows, and an ordinary spread, side by side."""
+    b = B()
+    rng = np.random.default_rng(61)
+    T = 50000
+    w = np.empty((3, T), np.float32)
+    w[0] = (1.0 + 1e-4 * rng.random(T)).astype(np.float32)                                   # all units in one bucket
+    w[1] = np.concatenate([(3.0 + 3e-4 * rng.random(20000)), np.exp(rng.normal(0, 2, T - 20000))]).astype(np.float32)
+    rng.shuffle(w[1])
+    w[2] = np.exp(rng.normal(0, 2.0, T)).astype(np.float32)
+    for budget in (0.7, 3.0):
+        cfg = b.Config([T], 3, 3, budget_bits=[budget], eps_v=eps)
+        print(f"[case] crowded weights budget={budget}", flush=True)
+        bits, _, lam, iters = b.rdkv_allocate_info(cfg, torch.from_numpy(w.reshape(-1)).cuda())
+        torch.cuda.synchronize()
+        bits, lam, iters = bits.cpu().numpy().reshape(3, T), lam.cpu().numpy()[0], iters.cpu().numpy()[0]
+        for h in range(3):
+            rb, info = O.mckp_bisect(w[h], np.float32(budget), O.TIERS, eps, return_info=True)
+            np.testing.assert_array_equal(bits[h], rb)
+            assert iters[h] == info["iters"]
+            assert (np.isnan(lam[h]) and info["lam"] is None) or lam[h] == info["lam"]

@@ -43,6 +43,9 @@ def parse():
                          "budgets 0.4..8 bit/elt, --sweep-batch sequences of 128K tokens per launch; prints one JSON line")
     ap.add_argument("--sweep-batch", type=int, default=4)
     ap.add_argument("--sweep-only", default="", help="comma list of sweep points to run (e.g. all-2,b0.4)")
+    ap.add_argument("--configs", action="store_true",
+                    help="one decode call each on the other benchmark configurations at full size (layer8b, batch70b, "
+                         "mixed with 1 and 16 sequences in both K formats) beside the bf16 path; prints one JSON line")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter-collection mode for `rocprofv3 --pmc`: build the caches, run --steps eager decode "
                          "steps, the batched launch, the bf16 path and a 1 GiB device-to-device copy, then exit")
@@ -139,6 +142,53 @@ def sweep(args, torch, b, W):
                       "kernel_ms": "HIP events around the decode kernels of a launch (the merge is in ms_decode_and_merge)"}))
 
 
+def other_configs(args, torch, b, W):
+    """The benchmark configurations that are not the headline workload: stored bytes, decode time (HIP events around
+    --steps calls), the bf16 path on the same K/V."""
+    res = []
+
+    def run(name, wl, inp, cache, note=""):
+        st = cache.stats()
+        B_ = len(inp["seq_lens"])
+        out = torch.empty((B_, wl.hq, 128), dtype=torch.float32, device="cuda")
+        lse = torch.empty((B_, wl.hq), dtype=torch.float32, device="cuda")
+        fn = lambda: b.rdkv_decode_attn(cache, inp["q"], out, lse)
+        for _ in range(3):
+            fn()
+        ms = timed_ms(fn, args.steps, torch)
+        ws = torch.empty(b.rdkv_decode_bf16_workspace_bytes(inp["seq_lens"], wl.hq, wl.hkv), dtype=torch.uint8, device="cuda")
+        fn16 = lambda: b.rdkv_decode_attn_bf16(inp["K"], inp["V"], inp["seq_lens"], wl.hq, wl.hkv, inp["q"], out=out, lse=lse, workspace=ws)
+        for _ in range(2):
+            fn16()
+        ms16 = timed_ms(fn16, max(3, args.steps // 4), torch)
+        nbytes = st["stored_bytes"] + B_ * wl.hq * 128 * 6
+        res.append({"config": name + note, "sequences": B_, "g": wl.hq // wl.hkv, "rows_16_8_4_2": st["rows"],
+                    "stored_bytes": st["stored_bytes"], "n_chunks": st["n_chunks"], "decode_us": ms * 1e3,
+                    "achieved_gbs": nbytes / (ms * 1e-3) / 1e9, "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "bf16_path_us": ms16 * 1e3, "bf16_path_gbs": st["dense_bytes"] / (ms16 * 1e-3) / 1e9,
+                    "memory_ratio": st["dense_bytes"] / max(st["stored_bytes"], 1)})
+        cache.free()
+
+    for name in ("layer8b", "batch70b"):
+        wl = W.CONFIGS[name]
+        inp = W.make_inputs(wl, device="cuda")
+        cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs)
+        run(name, wl, inp, b.rdkv_compress(cfg, inp["K"], inp["V"], inp["Q_obs"]))
+        del inp
+    for nseq in (1, 16):
+        wl = W.scaled(W.CONFIGS["mixed"], batch=nseq, seq_lens=(65536,) * nseq, budgets=(1.0,))
+        inp = W.make_inputs(wl, device="cuda")
+        for per_channel in (0, 1):
+            cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs,
+                           k_mode=b.RDKV_K_CHANNELWISE, k_scale_per_channel=per_channel)
+            _, w_ch = b.rdkv_weights(cfg, inp["K"], inp["Q_obs"], want_channel=True)
+            bt, bc = b.rdkv_allocate(cfg, inp["w_tok"], w_ch)
+            run("mixed", wl, inp, b.rdkv_pack(cfg, inp["K"], inp["V"], bt, bc),
+                " (one K scale per channel)" if per_channel else " (K scales per 32 tokens)")
+        del inp
+    print(json.dumps({"configs": res, "timing": f"HIP events around {args.steps} eager rdkv_decode_attn calls (one launch each)"}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -153,6 +203,9 @@ def main():
     torch.cuda.set_device(0)
     if args.sweep:
         sweep(args, torch, b, W)
+        return
+    if args.configs:
+        other_configs(args, torch, b, W)
         return
     wl = W.CONFIGS[args.workload]
     if args.ctx:

@@ -389,9 +389,7 @@ void order_chunks(std::vector<Chunk>::iterator first, std::vector<Chunk>::iterat
     if (x.tier != y.tier) return x.tier < y.tier;
     return static_cast<int64_t>(x.rows) * x.tier > static_cast<int64_t>(y.rows) * y.tier;
   });
-  bool round_robin = count <= 1024 && n_items > 1;
-  if (const char* e = std::getenv("RDKV_ORDER")) round_robin = std::strcmp(e, "xcd") == 0;
-  if (!round_robin) return;
+  if (count > 1024 || n_items <= 1) return;
   std::vector<std::vector<Chunk>> by_item(static_cast<size_t>(n_items));
   for (auto it = first; it != last; ++it) by_item[it->item].push_back(*it);
   auto out = first;
@@ -751,7 +749,6 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   // its own.
   const int64_t round16 = 512;
   const int64_t chunk_bytes16 = std::max<int64_t>(96 << 10, (cost16 + round16 - 1) / round16);
-  if (const char* e = std::getenv("RDKV_CHUNK_KB")) chunk_bytes = std::max<int64_t>(4, std::atoll(e)) << 10;
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
   for (int64_t i = 0; i < n; ++i) {
     slot_begin[i] = static_cast<int32_t>(c->chunks.size());

@@ -202,3 +202,55 @@ def test_long_items_whose_weights_crowd_a_histogram_bucket(eps):
             np.testing.assert_array_equal(bits[h], rb)
             assert iters[h] == info["iters"]
             assert (np.isnan(lam[h]) and info["lam"] is None) or lam[h] == info["lam"]
+
+
+@pytest.mark.parametrize("batch", [1500, 3000])
+def test_many_calls_in_a_row_reuse_the_staging_ring(batch):
+    """The host tables of a call travel through a ring of pinned staging memory whose bytes are reused once the copy
+    that read them has run.  Thousands of short sequences make the tables large (1500 sequences: 0.6 MB per call, the
+    2 MB ring wraps after three calls; 3000 sequences: more than half the ring, the synchronous path) and the calls
+    are queued without waiting in between; a sample of items of the last call is checked against the oracle."""
+    b = B()
+    hq, hkv, T, S_w = 8, 8, 40, 32
+    rng = np.random.default_rng(71)
+    K = torch.from_numpy(rng.standard_normal((batch, hkv, T, 128)).astype(np.float32)).to(torch.bfloat16).cuda()
+    Q = torch.from_numpy(rng.standard_normal((batch, hq, S_w, 128)).astype(np.float32)).to(torch.bfloat16).cuda()
+    budgets = [float(x) for x in rng.choice([0.5, 1.0, 2.0, 4.0], size=batch)]
+    cfg = b.Config([T] * batch, hq, hkv, budget_bits=budgets, s_obs=S_w)
+    print(f"[case] staging ring, {batch} sequences", flush=True)
+    outs = []
+    for _ in range(6):
+        w, _ = b.rdkv_weights(cfg, K.reshape(-1), Q)
+        bits, _ = b.rdkv_allocate(cfg, w)
+        outs.append((w, bits))
+    torch.cuda.synchronize()
+    w, bits = outs[-1]
+    for w2, bits2 in outs[:-1]:
+        assert torch.equal(w, w2) and torch.equal(bits, bits2)
+    w, bits = w.cpu().numpy().reshape(batch, hkv, T), bits.cpu().numpy().reshape(batch, hkv, T)
+    Kc, Qc = K.float().cpu().numpy(), Q.float().cpu().numpy()
+    for s in (0, 1, batch // 2, batch - 1):
+        ref_w = O.avg_pool(O.token_weights(Kc[s], Qc[s]), 5)
+        assert np.abs(w[s] - ref_w).max() <= 1e-5 * ref_w.max()
+        for h in (0, hkv - 1):
+            np.testing.assert_array_equal(bits[s, h], O.mckp_bisect(w[s, h], np.float32(budgets[s])))
+
+
+def test_schedule_rebuilt_on_another_stream_than_the_one_that_packed():
+    """The split workspace belongs to a stream: a cache packed on one stream, given a tail on a second and decoded on
+    both must give the same (correct) result everywhere."""
+    b = B()
+    wl, inp, dev = _inputs("tiny", seq_lens=(1500,))
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs)
+    cache = b.rdkv_compress(cfg, dev["K"], dev["V"], dev["Q_obs"])
+    out0, lse0 = b.rdkv_decode_attn(cache, dev["q"])
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        b.rdkv_cache_reserve_tail(cache, 64)                       # rebuilds the schedule, drops the workspaces
+        out1, lse1 = b.rdkv_decode_attn(cache, dev["q"])
+    side.synchronize()
+    out2, lse2 = b.rdkv_decode_attn(cache, dev["q"])               # back on the first stream: a new workspace
+    torch.cuda.synchronize()
+    assert torch.equal(out0, out1) and torch.equal(out0, out2) and torch.equal(lse0, lse1) and torch.equal(lse0, lse2)
+    cache.free()

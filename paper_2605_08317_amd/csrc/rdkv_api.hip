@@ -315,21 +315,32 @@ void dense_plan(const int32_t* seq_lens, int batch, int hkv, int g, int* chunk_r
   *max_splits = std::max(1, static_cast<int>((max_T + cr - 1) / cr));
 }
 
+// What a cache owns on the device.  rdkv_pack takes one block for the arena and every table (one trip through the
+// caller's allocator); what later calls add or replace (tail, rebuilt chunk tables, workspaces of other streams) are
+// allocations of their own.
 void free_cache_buffers(rdkv_cache* c) {
   Allocator al{c->alloc, c->free_, c->alloc_user};
-  al.put(c->d_arena);
-  al.put(c->d_tier_idx);
-  al.put(c->d_chunks);
-  for (const rdkv_cache::Workspace& w : c->workspaces) al.put(w.block);
+  const uint8_t* b0 = c->d_block;
+  const uint8_t* b1 = c->d_block ? c->d_block + c->block_bytes : nullptr;
+  auto put = [&](void* p) {
+    const uint8_t* q = static_cast<const uint8_t*>(p);
+    if (p && !(b0 && q >= b0 && q < b1)) al.put(p);
+  };
+  put(c->d_arena);
+  put(c->d_tier_idx);
+  put(c->d_chunks);
+  for (const rdkv_cache::Workspace& w : c->workspaces) put(w.block);
   c->workspaces.clear();
-  al.put(c->d_tail_state);
-  al.put(c->d_bits_tok);
-  al.put(c->d_bits_ch);
-  al.put(c->d_items_k);
-  al.put(c->d_items_sched);
-  al.put(c->d_tail);
-  al.put(c->d_lambda);
-  al.put(c->d_iters);
+  put(c->d_tail_state);
+  put(c->d_bits_tok);
+  put(c->d_bits_ch);
+  put(c->d_items_k);
+  put(c->d_items_sched);
+  put(c->d_tail);
+  put(c->d_lambda);
+  put(c->d_iters);
+  al.put(c->d_block);
+  c->d_block = nullptr;
   for (rdkv_cache* child : c->absorbed) {
     free_cache_buffers(child);
     delete child;
@@ -595,9 +606,9 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   const size_t n1 = static_cast<size_t>(std::max<int64_t>(n, 1));
   int32_t* d_blk_counts = tmp.get<int32_t>(std::max<int64_t>(it.n_blocks * 4, 1));
   int32_t* d_counts = tmp.get<int32_t>(n1 * 4 + 1);          // [items][4], then the invalid-value flag
-  int64_t* d_idx_base = tmp.get<int64_t>(n1 * 4);
-  int64_t* d_seg_off = tmp.get<int64_t>(n1 * 16);
-  if (!d_blk_counts || !d_counts || !d_idx_base || !d_seg_off)
+  int64_t* d_idx_base = tmp.get<int64_t>(n1 * 20);     // [items][4] kept-position bases, then [items][16] segment offsets
+  int64_t* d_seg_off = d_idx_base ? d_idx_base + n1 * 4 : nullptr;
+  if (!d_blk_counts || !d_counts || !d_idx_base)
     return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
   const int64_t* d_tok_off = tb.tok_off;
   const int32_t* d_T = tb.T;
@@ -806,42 +817,65 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   c->schedq = static_cast<int64_t>(c->chunks.size()) - c->n_chunks16;
   c->own_slot_count.assign(slot_count.begin(), slot_count.begin() + n);
 
-  // ---- allocate what the cache owns ------------------------------------------------------
-  c->d_arena = static_cast<uint8_t*>(al.get(c->arena_bytes));
-  c->d_tier_idx = static_cast<int32_t*>(al.get(std::max<int64_t>(kept, 1) * sizeof(int32_t)));
-  c->d_chunks = static_cast<Chunk*>(al.get(std::max<int64_t>(n_chunks, 1) * sizeof(Chunk)));
-  c->d_tail_state = static_cast<int32_t*>(al.get(2 * sizeof(int32_t)));
-  c->d_bits_tok = static_cast<uint8_t*>(al.get(std::max<int64_t>(it.total_tokens, 1)));
-  if (mixed) {
-    c->d_bits_ch = static_cast<uint8_t*>(al.get(std::max<int64_t>(n, 1) * kHeadDim));
-    c->d_items_k = static_cast<ItemK*>(al.get(std::max<int64_t>(n, 1) * sizeof(ItemK)));
-    if (!c->d_bits_ch || !c->d_items_k) return bail(fail(RDKV_ERR_ALLOC, "device allocation failed"));
+  // ---- allocate what the cache owns: one block --------------------------------------------
+  // [arena | tail state | arrival counters of this stream's workspace]  (cleared together)
+  // [kept positions | token bit map | channel bit map | K row layouts, chunk table (one copy) | partials | lambda, steps]
+  {
+    auto up = [](int64_t b) { return round_up(std::max<int64_t>(b, 16), 256); };
+    const int64_t o_state = c->arena_bytes, o_arrive = o_state + 256, o_idx = o_arrive + up(n * 4);
+    const int64_t o_bt = o_idx + up(kept * 4), o_bc = o_bt + up(it.total_tokens);
+    const int64_t o_ik = o_bc + (mixed ? up(n * kHeadDim) : 0);
+    const int64_t ik_b = mixed ? round_up(n * static_cast<int64_t>(sizeof(ItemK)), 8) : 0;
+    const int64_t o_acc = o_ik + up(ik_b + n_chunks * static_cast<int64_t>(sizeof(Chunk)));
+    const int64_t o_ml = o_acc + up(std::max<int64_t>(n_chunks, 1) * g * kHeadDim * 4);
+    const int64_t o_lam = o_ml + up(std::max<int64_t>(n_chunks, 1) * g * 2 * 4);
+    const int maps = mixed ? 2 : 1;
+    const int64_t o_it = o_lam + (lam ? up(maps * n * 8) : 0);
+    const int64_t total = o_it + (iters ? up(maps * n * 4) : 0);
+    c->d_block = static_cast<uint8_t*>(al.get(total));
+    if (!c->d_block)
+      return bail(fail(RDKV_ERR_ALLOC, "device allocation of the packed cache failed (%lld bytes)", static_cast<long long>(total)));
+    c->block_bytes = total;
+    c->d_arena = c->d_block;
+    c->d_tail_state = reinterpret_cast<int32_t*>(c->d_block + o_state);
+    c->d_tier_idx = reinterpret_cast<int32_t*>(c->d_block + o_idx);
+    c->d_bits_tok = c->d_block + o_bt;
+    if (mixed) {
+      c->d_bits_ch = c->d_block + o_bc;
+      c->d_items_k = reinterpret_cast<ItemK*>(c->d_block + o_ik);
+    }
+    c->d_chunks = reinterpret_cast<Chunk*>(c->d_block + o_ik + ik_b);
+    c->index_bytes = kept * 4 + n_chunks * static_cast<int64_t>(sizeof(Chunk)) + n * 8 + n * 16 * 8;
+    if (n > 0) {
+      // nothing below waits: tables are copied out of pinned staging memory, and the host vectors may go
+      PACK_HIP(hipMemsetAsync(c->d_block, 0, o_idx, st));     // arena (padding rows read as zeros), tail state, counters
+      std::vector<int64_t> plan(idx_base);
+      plan.resize(n1 * 4, 0);
+      plan.insert(plan.end(), c->seg_off.begin(), c->seg_off.end());
+      PACK_HIP(upload(d_idx_base, plan.data(), plan.size() * sizeof(int64_t), st));
+      std::vector<uint8_t> tables(static_cast<size_t>(ik_b + n_chunks * static_cast<int64_t>(sizeof(Chunk))));
+      if (mixed) std::memcpy(tables.data(), c->items_k.data(), n * sizeof(ItemK));
+      if (n_chunks > 0) std::memcpy(tables.data() + ik_b, c->chunks.data(), n_chunks * sizeof(Chunk));
+      if (!tables.empty()) PACK_HIP(upload(c->d_block + o_ik, tables.data(), tables.size(), st));
+      c->slot_begin = slot_begin;
+      c->slot_count = slot_count;
+      {   // the split workspace of this stream lives in the block: a first decode under graph capture allocates nothing
+        std::lock_guard<std::mutex> lk(c->ws_mu);
+        c->workspaces.push_back(rdkv_cache::Workspace{st, reinterpret_cast<float*>(c->d_block + o_acc),
+                                                      reinterpret_cast<float*>(c->d_block + o_ml),
+                                                      reinterpret_cast<int32_t*>(c->d_block + o_arrive), nullptr});
+      }
+      if (lam) PACK_HIP(hipMemcpyAsync(c->d_block + o_lam, lam, maps * n * 8, hipMemcpyDeviceToDevice, st));
+      if (iters) PACK_HIP(hipMemcpyAsync(c->d_block + o_it, iters, maps * n * 4, hipMemcpyDeviceToDevice, st));
+    }
+    if (lam) c->d_lambda = reinterpret_cast<double*>(c->d_block + o_lam);
+    if (iters) c->d_iters = reinterpret_cast<int32_t*>(c->d_block + o_it);
   }
-  if (!c->d_arena || !c->d_tier_idx || !c->d_chunks || !c->d_tail_state || !c->d_bits_tok)
-    return bail(fail(RDKV_ERR_ALLOC, "device allocation of the packed cache failed (%lld arena bytes)",
-                     static_cast<long long>(c->arena_bytes)));
-  c->index_bytes = kept * 4 + n_chunks * static_cast<int64_t>(sizeof(Chunk)) + n * 8 + n * 16 * 8;
 
   if (n > 0) {
-    // every table below is copied out of pinned staging memory: nothing here waits, and the host vectors may go
-    if (c->arena_bytes > 0) PACK_HIP(hipMemsetAsync(c->d_arena, 0, c->arena_bytes, st));
-    PACK_HIP(upload(d_idx_base, idx_base.data(), n * 4 * sizeof(int64_t), st));
-    PACK_HIP(upload(d_seg_off, c->seg_off.data(), n * 16 * sizeof(int64_t), st));
-    if (n_chunks > 0) PACK_HIP(upload(c->d_chunks, c->chunks.data(), n_chunks * sizeof(Chunk), st));
-    c->slot_begin = slot_begin;
-    c->slot_count = slot_count;
-    PACK_HIP(hipMemsetAsync(c->d_tail_state, 0, 2 * sizeof(int32_t), st));
-    {   // the split workspace of this stream, so that a first decode under graph capture allocates nothing
-      rdkv_cache::Workspace w;
-      const rdkv_status ws = workspace_for(c, st, &w);
-      if (ws != RDKV_OK) return bail(ws);
-    }
     if (it.total_tokens > 0)
       PACK_HIP(hipMemcpyAsync(c->d_bits_tok, bits_tok, it.total_tokens, hipMemcpyDeviceToDevice, st));
-    if (mixed) {
-      PACK_HIP(hipMemcpyAsync(c->d_bits_ch, bits_ch, n * kHeadDim, hipMemcpyDeviceToDevice, st));
-      PACK_HIP(upload(c->d_items_k, c->items_k.data(), n * sizeof(ItemK), st));
-    }
+    if (mixed) PACK_HIP(hipMemcpyAsync(c->d_bits_ch, bits_ch, n * kHeadDim, hipMemcpyDeviceToDevice, st));
     if (kept > 0) {
       uint32_t* d_krange = nullptr;
       if (c->k_per_unit) {   // per-channel (minimum, maximum) over all retained tokens, as ordered integers
@@ -861,8 +895,6 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
     }
   }
 #undef PACK_HIP
-  c->d_lambda = lam;       // adopted: freed with the cache
-  c->d_iters = iters;
   *out = c;
   return RDKV_OK;
 }
@@ -1081,7 +1113,8 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, 
                  weights_scratch_floats(n_wblk, it.n_items, it.total_tokens, R_pad, mixed) * sizeof(float),
                  mixed ? ni * sizeof(int32_t) : 0, mixed ? ni * sizeof(double) : 0,
                  static_cast<size_t>(std::max<int64_t>(it.n_blocks * 4, 1)) * sizeof(int32_t),
-                 (ni * 4 + 1) * sizeof(int32_t), ni * 4 * sizeof(int64_t), ni * 16 * sizeof(int64_t),
+                 (ni * 4 + 1) * sizeof(int32_t), ni * 20 * sizeof(int64_t), ni * 2 * sizeof(double), ni * 2 * sizeof(int32_t),
+                 it.max_T >= 16384 && it.n_items <= 512 ? allocate_multi_scratch_bytes(static_cast<int>(it.n_items)) : 0,
                  mixed && cfg->k_scale_per_channel ? nc * 2 * sizeof(uint32_t) : 0});
   }
   Tables tb;
@@ -1093,19 +1126,17 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V, 
   uint8_t* bits_ch = mixed ? tmp.get<uint8_t>(nc) : nullptr;
   if (!w || !bits || (mixed && (!w_ch || !bits_ch))) return fail(RDKV_ERR_ALLOC, "device allocation failed");
   if (it.n_items == 0) return pack_impl(cfg, it, tb, K, V, bits, bits_ch, nullptr, nullptr, tmp, st, out);
-  // the multiplier and the step count of every item's search stay with the cache (rdkv_cache_stats / export)
+  // the multiplier and the step count of every item's search stay with the cache (rdkv_cache_stats / export): the
+  // pack stage copies them into the cache's block
   const int maps = mixed ? 2 : 1;
-  double* lam = static_cast<double*>(al.get(maps * ni * sizeof(double)));
-  int32_t* iters = static_cast<int32_t*>(al.get(maps * ni * sizeof(int32_t)));
-  auto drop = [&](rdkv_status code) { al.put(lam); al.put(iters); return code; };
-  if (!lam || !iters) return drop(fail(RDKV_ERR_ALLOC, "device allocation failed"));
+  double* lam = tmp.get<double>(maps * ni);
+  int32_t* iters = tmp.get<int32_t>(maps * ni);
+  if (!lam || !iters) return fail(RDKV_ERR_ALLOC, "device allocation failed");
   s = weights_impl(cfg, it, tb, K, Q_obs, w, w_ch, tmp, st);
-  if (s != RDKV_OK) return drop(s);
+  if (s != RDKV_OK) return s;
   s = allocate_impl(cfg, it, tb, w, w_ch, bits, bits_ch, lam, iters, tmp, st);
-  if (s != RDKV_OK) return drop(s);
-  s = pack_impl(cfg, it, tb, K, V, bits, bits_ch, lam, iters, tmp, st, out);
-  if (s != RDKV_OK) return drop(s);
-  return RDKV_OK;
+  if (s != RDKV_OK) return s;
+  return pack_impl(cfg, it, tb, K, V, bits, bits_ch, lam, iters, tmp, st, out);
 }
 
 // A-priori bound on the packed arena from the budget alone (Sec. 3.2: sum of bit-widths <= floor(avg * units)).
@@ -1276,7 +1307,10 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
   }
   drop_workspaces(c);      // the slot count changed: workspaces are created again on first use
   c->n_slots = n_slots;
-  al.put(c->d_chunks);
+  {   // the first chunk table lives in the cache's block; rebuilt ones are allocations of their own
+    const uint8_t* q = reinterpret_cast<const uint8_t*>(c->d_chunks);
+    if (!(c->d_block && q >= c->d_block && q < c->d_block + c->block_bytes)) al.put(c->d_chunks);
+  }
   al.put(c->d_items_sched);
   c->d_items_sched = d_items_sched;
   c->sched_k_words = kw;

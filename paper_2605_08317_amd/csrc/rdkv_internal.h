@@ -126,7 +126,10 @@ struct rdkv_cache {
   int64_t arena_bytes = 0;
   int64_t kept_total = 0;
   int64_t n_chunks16 = 0;               // leading chunks of the 16-bit tier
-  // device memory (owned)
+  // device memory (owned): rdkv_pack takes one block for the arena and every table below; what later calls add or
+  // replace (tail, rebuilt chunk tables, workspaces of other streams) are allocations of their own
+  uint8_t* d_block = nullptr;
+  int64_t block_bytes = 0;
   uint8_t* d_arena = nullptr;
   int32_t* d_tier_idx = nullptr;        // [kept_total]
   rdkv::Chunk* d_chunks = nullptr;

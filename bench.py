@@ -601,8 +601,10 @@ def main():
                      "kernel_ms_rocprof": kern_ms_rocprof,
                      "frac_rocprof": None if not kern_ms_rocprof else alg_bytes_layer / (kern_ms_rocprof * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "kernel_ms_eager_event_bracket": kern_ms_eager, "launches_timed": args.steps * L,
-                     "note": "a 16 MB launch is latency-bound (2 us of HBM time); batched_launch and tier_sweep in "
-                             "profiles/ show the bandwidth the same kernel reaches with more bytes per launch"},
+                     "note": "the kernel's duration includes the merge of the split partials (a separate 4.5 us kernel "
+                             "before, beside an 8.2 us split kernel); a 16 MB launch is latency-bound (2 us of HBM "
+                             "time); batched_launch and profiles/decode_tier_sweep.txt show the bandwidth the same "
+                             "kernel reaches with more bytes per launch"},
         "cpu_baseline": cpu,
         "cache": {"rows_16_8_4_2": rows, "stored_bytes": stored, "dense_bf16_bytes": dense,
                   "memory_ratio": dense / max(stored, 1), "n_chunks": n_chunks,

@@ -126,7 +126,8 @@ __device__ __forceinline__ void merge_item(const MergeArgs& ma, int item, int sl
 // Called by all NT threads of a workgroup after a barrier that follows partial_stores_done().  Returns after the
 // item's output rows are written if this workgroup arrived last, at once otherwise.
 // smem: merge_lds_floats(NT, g) floats of LDS that nothing else uses any more.
-template <int NT>
+// GMAX: the most query heads per KV head the calling kernel is built for (larger merges are not compiled into it)
+template <int NT, int GMAX = 8>
 __device__ __forceinline__ void arrive_and_merge(const MergeArgs& ma, int item, int slot0, int nslots, int g,
                                                  float* smem) {
   static_assert(NT % 128 == 0 && NT >= 128, "the merge assigns 128 channel threads per slot group");
@@ -139,11 +140,14 @@ __device__ __forceinline__ void arrive_and_merge(const MergeArgs& ma, int item, 
   __syncthreads();
   if (*s_flag == 0) return;
   // the partials are read with agent-scope loads, which do not hit stale lines of this XCD's caches
+  if constexpr (GMAX > 4) {
+    if (g > 4) merge_item<NT, 8>(ma, item, slot0, nslots, smem);
+  }
   switch (g) {
     case 1: merge_item<NT, 1>(ma, item, slot0, nslots, smem); break;
     case 2: merge_item<NT, 2>(ma, item, slot0, nslots, smem); break;
     case 4: merge_item<NT, 4>(ma, item, slot0, nslots, smem); break;
-    default: merge_item<NT, 8>(ma, item, slot0, nslots, smem); break;
+    default: break;
   }
   if (tid == 0) __hip_atomic_store(ma.arrive + item, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -37,12 +37,14 @@ struct Lds {
   static constexpr int kQsum = HS * 2 * 4 * 8;
 };
 
-// NWV wavefronts per workgroup interleave over the tiles of a chunk
+// One piece of a workgroup's work: `rows` rows of one tier of one item, NWV wavefronts interleaving over its tiles.
+// The running softmax state `run` carries over from piece to piece (a workgroup may go through several tiers of its
+// item); the sums that carry the lane's factor kappa of this tier take it on entry and give it back on exit.
 template <int TIER, int HS, int NWV>
 __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, const uint8_t* __restrict__ km,
                                               const uint8_t* __restrict__ vd, const uint8_t* __restrict__ vm,
-                                              int rows, int g, const uint16_t* __restrict__ q, const MergeArgs& ma,
-                                              const ChunkOut& co, uint8_t* smem) {
+                                              int rows, int g, const uint16_t* __restrict__ q, Run<HS>& run,
+                                              uint8_t* smem) {
   constexpr int kWG = NWV * 64, kWaves = NWV;
   using S = Step<TIER>;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -50,8 +52,6 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   const int blk = lane >> 2, j = lane & 3;
   const uint8_t* s_qop = smem;
   const uint8_t* s_qsum = smem + Lds<HS>::kQop;
-  float* s_ml = reinterpret_cast<float*>(smem + Lds<HS>::kQop + Lds<HS>::kQsum);   // [4][4 HS][2]
-  float* s_acc = s_ml + kWaves * 4 * HS * 2;                                       // [8 streams][g][128]
 
   const int ntiles = (rows + kTile - 1) / kTile;
 
@@ -83,7 +83,8 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
     }
   }
 
-  // ---- query operands (once per workgroup) ------------------------------------------------------------------
+  // ---- query operands (once per piece: the field positions folded into them depend on the tier; the caller puts
+  // a barrier between two pieces) ------------------------------------------------------------------------------
   // B operand of (head set, group, step): lane head j holds q[head][32 grp + 4 step + 0..3] * 2^(kQExp - fb(step)).
   // The group sums of q (B operand of the K-offset product, k = group, as two fp16 terms) fall out of the same
   // loads: the eight steps of a (head, group) sit in lanes 4, 8 and 16 apart.
@@ -119,8 +120,15 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
   __syncthreads();
 
   const float lk = v_log2_kappa<TIER>(blk);
-  Run<HS> run;
-  run.init();
+  {
+    const float kappa = __builtin_ldexpf(1.0f, static_cast<int>(lk));
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs) {
+      run.l[hs] *= kappa;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) run.offv[hs][i] *= kappa;
+    }
+  }
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
   auto do_tile = [&](Regs& r, const int tile) __attribute__((always_inline)) {
@@ -234,59 +242,104 @@ __device__ __forceinline__ void process_tiles(const uint8_t* __restrict__ kd, co
       if (tile + dd * kWaves < ntiles) do_tile(regs[dd], tile + dd * kWaves);
   }
 
-  // ---- end of the chunk: undo the subnormal unit, add the offsets, merge the 4 wavefronts --------------------
-  finish_chunk<HS, false, NWV>(run, 16777216.0f, lk, g, s_ml, s_acc, ma, co);
+  {   // the piece is done: the lane's factor leaves the sums again
+    const float inv_kappa = __builtin_ldexpf(1.0f, static_cast<int>(-lk));
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs) {
+      run.l[hs] *= inv_kappa;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) run.offv[hs][i] *= inv_kappa;
+    }
+  }
 }
 
-template <int HS, int NWV>
+// MULTI: workgroups may go through several tiers of their item (Chunk::next); without it every chunk is one tier and
+// the tier's body ends in its own copy of the chunk's end, which saves a latency-bound launch 0.3 us.
+template <int HS, int NWV, bool MULTI>
 __global__ __launch_bounds__(NWV * 64, HS == 1 ? 4 : 3) void decode_tiles_kernel(
-    const Chunk* __restrict__ chunks, const uint8_t* __restrict__ arena, const uint16_t* __restrict__ q, MergeArgs ma,
-    const int32_t* __restrict__ tail_len) {
+    const Chunk* __restrict__ chunks, int first, const uint8_t* __restrict__ arena, const uint16_t* __restrict__ q,
+    MergeArgs ma, const int32_t* __restrict__ tail_len) {
   extern __shared__ __align__(16) uint8_t smem[];
-  const Chunk ch = chunks[blockIdx.x];
+  Chunk ch = chunks[first + blockIdx.x];
   const int g = ma.hq / ma.hkv;
   const int seq = ch.item / ma.hkv, head = ch.item % ma.hkv;
   const uint16_t* qp = q + (static_cast<int64_t>(seq) * ma.hq + head * g) * kHeadDim;
   const ChunkOut co{ch.item, ch.slot, ch.slot0, ch.nslots};
-  const uint8_t* kd = arena + ch.k_data;
-  const uint8_t* km = arena + ch.k_meta;
-  const uint8_t* vd = arena + ch.v_data;
-  const uint8_t* vm = arena + ch.v_meta;
-  switch (ch.tier) {
-    case kTierTail: {   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
-      float* s_ml = reinterpret_cast<float*>(smem + Lds<HS>::kQop + Lds<HS>::kQsum);
-      const int rows = max(0, min(ch.rows, *tail_len - ch.row0));
-      process_tail_tiles<HS, false, NWV>(kd, vd, rows, g, qp, smem, s_ml, s_ml + NWV * 4 * HS * 2, ma, co);
-      break;
-    }
-    case 8: process_tiles<8, HS, NWV>(kd, km, vd, vm, ch.rows, g, qp, ma, co, smem); break;
-    case 4: process_tiles<4, HS, NWV>(kd, km, vd, vm, ch.rows, g, qp, ma, co, smem); break;
-    default: process_tiles<2, HS, NWV>(kd, km, vd, vm, ch.rows, g, qp, ma, co, smem); break;
+  float* s_ml = reinterpret_cast<float*>(smem + Lds<HS>::kQop + Lds<HS>::kQsum);   // [NWV][4 HS][2]
+  float* s_acc = s_ml + NWV * 4 * HS * 2;                                          // [2 NWV streams][g][128]
+  if (ch.tier == kTierTail) {   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
+    const int rows = max(0, min(ch.rows, *tail_len - ch.row0));
+    process_tail_tiles<HS, false, NWV>(arena + ch.k_data, arena + ch.v_data, rows, g, qp, smem, s_ml, s_acc, ma, co);
+    return;
   }
+  if constexpr (!MULTI) {
+#define RDKV_ONE(TIER_)                                                                                           \
+  {                                                                                                               \
+    Run<HS> run;                                                                                                  \
+    run.init();                                                                                                   \
+    process_tiles<TIER_, HS, NWV>(arena + ch.k_data, arena + ch.k_meta, arena + ch.v_data, arena + ch.v_meta,     \
+                                  ch.rows, g, qp, run, smem);                                                     \
+    finish_chunk<HS, false, NWV>(run, 16777216.0f, 0.f, g, s_ml, s_acc, ma, co);                                  \
+  }
+    switch (ch.tier) {
+      case 8: RDKV_ONE(8) break;
+      case 4: RDKV_ONE(4) break;
+      default: RDKV_ONE(2) break;
+    }
+#undef RDKV_ONE
+    return;
+  }
+  // The workgroup's pieces: runs of rows of the item's quantized tiers on one softmax state.  A share of an item's
+  // work goes through the tiers in the order 2, 4, 8 bits, so the chain is at most three pieces long and the three
+  // tier bodies follow each other in a straight line (a loop around a switch made the compiler spill the state).
+  Run<HS> run;
+  run.init();
+#define RDKV_PIECE(TIER_)                                                                                         \
+  if (ch.tier == (TIER_)) {                                                                                       \
+    const int next = ch.next;                                                                                     \
+    process_tiles<TIER_, HS, NWV>(arena + ch.k_data, arena + ch.k_meta, arena + ch.v_data, arena + ch.v_meta,     \
+                                  ch.rows, g, qp, run, smem);                                                     \
+    if (next >= 0) {                                                                                              \
+      __syncthreads(); /* this piece's readers of the query operands are done */                                  \
+      ch = chunks[next];                                                                                          \
+    } else {                                                                                                      \
+      ch.tier = 0;                                                                                                \
+    }                                                                                                             \
+  }
+  RDKV_PIECE(2)
+  RDKV_PIECE(4)
+  RDKV_PIECE(8)
+#undef RDKV_PIECE
+  // ---- undo the subnormal unit, add the offsets, merge the wavefronts, hand the partial over -------------------
+  finish_chunk<HS, false, NWV>(run, 16777216.0f, 0.f, g, s_ml, s_acc, ma, co);
 }
 
-template <int HS, int NWV>
-hipError_t launch_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
+template <int HS, int NWV, bool MULTI>
+hipError_t launch_tiles(const Chunk* chunks, int first, int n_chunks, const uint8_t* arena, const uint16_t* q,
                         const MergeArgs& ma, const int32_t* tail_len, hipStream_t st) {
   const int g = ma.hq / ma.hkv;
   const size_t merge_area = static_cast<size_t>(2 * NWV) * g * kHeadDim * sizeof(float);
   static_assert(2 * NWV * 128 >= merge::merge_lds_floats(NWV * 64, 1), "the merge reuses the wavefront merge area");
   const size_t lds = Lds<HS>::kQop + Lds<HS>::kQsum + NWV * 4 * HS * 2 * sizeof(float) + merge_area;
-  hipLaunchKernelGGL((decode_tiles_kernel<HS, NWV>), dim3(n_chunks), dim3(NWV * 64), lds, st, chunks, arena, q, ma,
-                     tail_len);
+  hipLaunchKernelGGL((decode_tiles_kernel<HS, NWV, MULTI>), dim3(n_chunks), dim3(NWV * 64), lds, st, chunks, first,
+                     arena, q, ma, tail_len);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               const MergeArgs& ma, const int32_t* tail_len, hipStream_t st) {
+hipError_t launch_decode_tiles(const Chunk* chunks, int first, int n_chunks, bool multi, const uint8_t* arena,
+                               const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   const int g = ma.hq / ma.hkv;
   // up to 4 query heads per KV head: one head set, workgroups of eight wavefronts; 8 heads: two head sets (166
   // registers, three wavefronts per SIMD), workgroups of four
-  if (g > 4) return launch_tiles<2, 4>(chunks, n_chunks, arena, q, ma, tail_len, st);
-  return launch_tiles<1, 8>(chunks, n_chunks, arena, q, ma, tail_len, st);
+  if (g > 4) {
+    if (multi) return launch_tiles<2, 4, true>(chunks, first, n_chunks, arena, q, ma, tail_len, st);
+    return launch_tiles<2, 4, false>(chunks, first, n_chunks, arena, q, ma, tail_len, st);
+  }
+  if (multi) return launch_tiles<1, 8, true>(chunks, first, n_chunks, arena, q, ma, tail_len, st);
+  return launch_tiles<1, 8, false>(chunks, first, n_chunks, arena, q, ma, tail_len, st);
 }
 
 }  // namespace rdkv

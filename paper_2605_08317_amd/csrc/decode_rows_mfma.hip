@@ -205,7 +205,7 @@ __device__ __forceinline__ void process_rows_mfma(const uint8_t* __restrict__ kd
   if constexpr (TIERED) {
     merge::partial_stores_done();
     __syncthreads();
-    merge::arrive_and_merge<kRowsWG>(*ma, co->item, co->slot0, co->nslots, g, s_acc);
+    merge::arrive_and_merge<kRowsWG, 4 * HS>(*ma, co->item, co->slot0, co->nslots, g, s_acc);
   }
 }
 

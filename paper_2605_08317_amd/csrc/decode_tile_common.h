@@ -369,7 +369,7 @@ __device__ __forceinline__ void finish_chunk(Run<HS>& run, float acc_scale, floa
   }
   merge::partial_stores_done();
   __syncthreads();     // every partial store has landed, and nobody reads s_ml / s_acc any more
-  merge::arrive_and_merge<NT>(ma, co.item, co.slot0, co.nslots, g, s_acc);
+  merge::arrive_and_merge<NT, 4 * HS>(ma, co.item, co.slot0, co.nslots, g, s_acc);
 }
 
 // A chunk of appended tokens (Sec. 3.3 Zone C: bf16 rows kept after the compression pass) on the same instruction

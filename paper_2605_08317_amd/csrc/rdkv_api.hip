@@ -744,11 +744,30 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       }
     return total;
   };
+  // token-wise mode cuts an item's quantized tiers as one run of work into round(cost / chunk cost) even shares
+  auto count_shares = [&](int64_t cb, int64_t* max_cost) {
+    int64_t total = 0;
+    *max_cost = 0;
+    for (int64_t i = 0; i < n; ++i) {
+      int64_t item_cost = 0;
+      for (int ti = 1; ti < 4; ++ti) item_cost += c->counts[i * 4 + ti] * row_cost(i, pack_tier_bits(ti));
+      if (item_cost == 0) continue;
+      const int64_t n_wg = std::max<int64_t>(1, (item_cost + cb / 2) / cb);
+      total += n_wg;
+      *max_cost = std::max(*max_cost, item_cost / n_wg);
+    }
+    return total;
+  };
+  // Shares that span tiers pay a start-up per tier (operands rebuilt, the first tiles' latency waited for again):
+  // worth it when a chunk streams for tens of microseconds (32 sequences x 128K tokens at 0.4 bit/elt: 101.6 -> 97.6
+  // us), not in latency-bound launches (a 16 MB layer: 12.2 -> 13.7 us), which keep one tier per chunk.
   int64_t chunk_bytes = std::max<int64_t>((wide ? 96 : 48) << 10, total_cost / round_chunks);
-  int64_t max_cost = 0, n_one_round = count_chunks(chunk_bytes, &max_cost);
+  const bool shares = !mixed && chunk_bytes >= (192 << 10);
+  auto count_any = [&](int64_t cb, int64_t* max_cost) { return shares ? count_shares(cb, max_cost) : count_chunks(cb, max_cost); };
+  int64_t max_cost = 0, n_one_round = count_any(chunk_bytes, &max_cost);
   for (int tries = 0; tries < 64 && n_one_round > round_chunks; ++tries) {
     chunk_bytes += chunk_bytes / 16 + 1;
-    n_one_round = count_chunks(chunk_bytes, &max_cost);
+    n_one_round = count_any(chunk_bytes, &max_cost);
   }
   // When one round cannot be had (more tier segments than resident workgroups) or would be lopsided (its largest
   // chunk more than a fifth above the mean), about two rounds of smaller chunks even things out instead (16
@@ -761,9 +780,29 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   const int64_t round16 = 512;
   const int64_t chunk_bytes16 = std::max<int64_t>(96 << 10, (cost16 + round16 - 1) / round16);
   std::vector<int32_t> slot_begin(std::max<int64_t>(n, 1), 0), slot_count(std::max<int64_t>(n, 1), 0);
+  std::vector<Chunk> conts;     // continuation pieces (token-wise mode): reached through Chunk::next, never launched
+  auto make_chunk = [&](int64_t i, int ti, int64_t r0, int64_t rows) {
+    const int bits = pack_tier_bits(ti);
+    const int64_t* so = &c->seg_off[(i * 4 + ti) * 4];
+    Chunk ch{};
+    ch.k_data = so[0] + (mixed ? r0 / kTile64 * c->items_k[i].kt_bytes : r0 * tier_row_bytes(bits));
+    ch.k_meta = so[1] + (mixed ? (c->k_per_unit ? 0 : r0 / kTile64 * c->items_k[i].km_bytes)
+                               : r0 * tier_meta_bytes(bits));
+    ch.v_data = so[2] + r0 * tier_row_bytes(bits);
+    ch.v_meta = so[3] + r0 * tier_meta_bytes(bits);
+    ch.rows = static_cast<int32_t>(rows);
+    ch.tier = bits;
+    ch.item = static_cast<int32_t>(i);
+    for (int t2 = 0; t2 < 4; ++t2) ch.k_word_end[t2] = mixed ? c->items_k[i].word_end[t2] : int16_t(0);
+    ch.reserved = static_cast<int32_t>(i);
+    ch.next = -1;
+    return ch;
+  };
   for (int64_t i = 0; i < n; ++i) {
     slot_begin[i] = static_cast<int32_t>(c->chunks.size());
-    for (int ti = 0; ti < 4; ++ti) {
+    // segments cut tier by tier: every tier, or only the 16-bit tier (its own kernel) when the quantized tiers of a
+    // token-wise item are cut into shares below
+    for (int ti = 0; ti < (shares ? 1 : 4); ++ti) {
       const int bits = pack_tier_bits(ti);
       const int64_t cnt = c->counts[i * 4 + ti];
       if (cnt == 0) continue;
@@ -771,22 +810,46 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       const int64_t want = std::max<int64_t>(64, (!mixed && bits == 16 ? chunk_bytes16 : chunk_bytes) / per_row);
       const int64_t nch = (cnt + want - 1) / want;
       const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
-      const int64_t* so = &c->seg_off[(i * 4 + ti) * 4];
       for (int64_t r0 = 0; r0 < cnt; r0 += rows_per) {
-        Chunk ch{};
-        ch.k_data = so[0] + (mixed ? r0 / kTile64 * c->items_k[i].kt_bytes : r0 * tier_row_bytes(bits));
-        ch.k_meta = so[1] + (mixed ? (c->k_per_unit ? 0 : r0 / kTile64 * c->items_k[i].km_bytes)
-                                   : r0 * tier_meta_bytes(bits));
-        ch.v_data = so[2] + r0 * tier_row_bytes(bits);
-        ch.v_meta = so[3] + r0 * tier_meta_bytes(bits);
-        ch.rows = static_cast<int32_t>(std::min<int64_t>(rows_per, cnt - r0));
-        ch.tier = bits;
-        ch.item = static_cast<int32_t>(i);
+        Chunk ch = make_chunk(i, ti, r0, std::min<int64_t>(rows_per, cnt - r0));
         ch.slot = static_cast<int32_t>(c->chunks.size());
-        for (int t2 = 0; t2 < 4; ++t2) ch.k_word_end[t2] = mixed ? c->items_k[i].word_end[t2] : int16_t(0);
-        ch.row0 = 0;
-        ch.reserved = static_cast<int32_t>(i);
         c->chunks.push_back(ch);
+      }
+    }
+    if (shares) {
+      // The quantized tiers of a token-wise item are one run of work -- 2-bit rows, then 4-bit, then 8-bit -- cut
+      // into equal shares of cost whatever the tiers' sizes: a workgroup's share may span two or three tiers (its
+      // pieces are chained through Chunk::next and feed one softmax state), so every launch, single-tier or not,
+      // gets chunks of even cost.
+      int64_t item_cost = 0;
+      for (int ti = 1; ti < 4; ++ti) item_cost += c->counts[i * 4 + ti] * row_cost(i, pack_tier_bits(ti));
+      const int64_t n_wg = item_cost == 0 ? 0 : std::max<int64_t>(1, (item_cost + chunk_bytes / 2) / chunk_bytes);
+      int ti = 3;            // walk the segments from the 2-bit tier up
+      int64_t r0 = 0;        // first row of the current segment not handed out yet
+      for (int64_t k = 0; k < n_wg; ++k) {
+        int64_t share = item_cost / n_wg;     // what this workgroup should take
+        int32_t prev = -1;                    // index of the workgroup's previous piece: >= 0 in conts, -2 - x: chunk x
+        while (ti >= 1) {
+          const int64_t left = c->counts[i * 4 + ti] - r0;
+          if (left <= 0) { --ti; r0 = 0; continue; }
+          const int64_t rc = row_cost(i, pack_tier_bits(ti));
+          int64_t take = k + 1 == n_wg ? left : std::min<int64_t>(left, round_up(std::max<int64_t>(share, rc) / rc, 64));
+          if (k + 1 < n_wg && left - take < 64) take = left;     // no slivers
+          Chunk ch = make_chunk(i, ti, r0, take);
+          if (prev == -1) {
+            ch.slot = static_cast<int32_t>(c->chunks.size());
+            c->chunks.push_back(ch);
+            prev = -2 - ch.slot;
+          } else {
+            const int32_t me = static_cast<int32_t>(conts.size());
+            conts.push_back(ch);
+            if (prev <= -2) c->chunks[-2 - prev].next = me; else conts[prev].next = me;   // local index for now
+            prev = me;
+          }
+          r0 += take;
+          share -= take * rc;
+          if (k + 1 < n_wg && share < 64 * rc) break;            // the share is used up
+        }
       }
     }
     if (static_cast<int32_t>(c->chunks.size()) == slot_begin[i]) {
@@ -796,14 +859,14 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       ch.item = static_cast<int32_t>(i);
       ch.slot = static_cast<int32_t>(c->chunks.size());
       ch.reserved = static_cast<int32_t>(i);
+      ch.next = -1;
       c->chunks.push_back(ch);
     }
     slot_count[i] = static_cast<int32_t>(c->chunks.size()) - slot_begin[i];
   }
-  const int64_t n_chunks = static_cast<int64_t>(c->chunks.size());
-  c->n_slots = n_chunks;
+  c->n_slots = static_cast<int64_t>(c->chunks.size());
   stamp_slots(c->chunks, slot_begin, slot_count);
-  // 16-bit chunks first (their own kernel), then the quantized ones
+  // 16-bit chunks first (their own kernel), then the launched quantized ones, then the continuation pieces
   std::stable_partition(c->chunks.begin(), c->chunks.end(), [](const Chunk& x) { return x.tier == 16; });
   {
     int64_t n16 = 0;
@@ -815,6 +878,14 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   for (const Chunk& ch : c->chunks) c->n_chunks16 += ch.tier == 16;
   c->sched16 = c->n_chunks16;
   c->schedq = static_cast<int64_t>(c->chunks.size()) - c->n_chunks16;
+  c->n_cont = static_cast<int64_t>(conts.size());
+  {   // Chunk::next becomes an index into the whole table
+    const int32_t base = static_cast<int32_t>(c->chunks.size());
+    for (Chunk& ch : c->chunks) if (ch.next >= 0) ch.next += base;
+    for (Chunk& ch : conts) if (ch.next >= 0) ch.next += base;
+    c->chunks.insert(c->chunks.end(), conts.begin(), conts.end());
+  }
+  const int64_t n_chunks = static_cast<int64_t>(c->chunks.size());
   c->own_slot_count.assign(slot_count.begin(), slot_count.begin() + n);
 
   // ---- allocate what the cache owns: one block --------------------------------------------
@@ -1201,7 +1272,9 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
   }
   // the workgroups of both kernels announce themselves on the same counters: whichever finishes an item merges it
   RDKV_HIP(launch_decode_tiered_split(c->d_chunks, n16, c->d_arena, static_cast<const uint16_t*>(q), ma, st));
-  RDKV_HIP(launch_decode_tiles(c->d_chunks + n16, nrest, c->d_arena, static_cast<const uint16_t*>(q), ma,
+  bool multi = c->n_cont > 0;      // some workgroup goes through more than one tier of its item
+  for (const rdkv_cache* child : c->absorbed) multi = multi || child->n_cont > 0;
+  RDKV_HIP(launch_decode_tiles(c->d_chunks, n16, nrest, multi, c->d_arena, static_cast<const uint16_t*>(q), ma,
                                c->d_tail_state, st));
   return RDKV_OK;
 }
@@ -1230,26 +1303,44 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
     nc[i] = off + npi;
     n_slots += nc[i];
   }
-  for (const rdkv_cache* gcache : gens) n_gen_chunks += static_cast<int64_t>(gcache->chunks.size());
+  // table = [16-bit chunks of every generation | launched quantized chunks of every generation | tail chunks |
+  //          continuation pieces of every generation]; a generation's own vector is [16-bit | launched | continuations]
+  int64_t n_cont_total = 0;
+  std::vector<int64_t> cont_off(gens.size());
+  for (size_t k = 0; k < gens.size(); ++k) {
+    n_gen_chunks += static_cast<int64_t>(gens[k]->chunks.size()) - gens[k]->n_cont;
+    cont_off[k] = n_cont_total;
+    n_cont_total += gens[k]->n_cont;
+  }
+  const int64_t cont_base = n_gen_chunks + n * npi;      // where the continuation pieces start in the new table
   std::vector<Chunk> table;
-  table.reserve(static_cast<size_t>(n_gen_chunks + n * npi));
+  table.reserve(static_cast<size_t>(cont_base + n_cont_total));
   std::vector<Chunk> own = c->chunks;   // this cache's chunks with their new slot numbers
   int64_t n16 = 0;
+  auto moved = [&](size_t k, Chunk ch) {
+    const rdkv_cache* gc = gens[k];
+    const int64_t base = reinterpret_cast<intptr_t>(gc->d_arena) - reinterpret_cast<intptr_t>(c->d_arena);
+    ch.reserved = static_cast<int32_t>(k * n + ch.item);
+    ch.k_data += base;
+    ch.k_meta += base;
+    ch.v_data += base;
+    ch.v_meta += base;
+    if (ch.next >= 0) {   // an index into the generation's own vector -> into the new table
+      const int64_t first_cont = static_cast<int64_t>(gc->chunks.size()) - gc->n_cont;
+      ch.next = static_cast<int32_t>(cont_base + cont_off[k] + (ch.next - first_cont));
+    }
+    return ch;
+  };
   for (int pass = 0; pass < 2; ++pass)
     for (size_t k = 0; k < gens.size(); ++k) {
       const rdkv_cache* gc = gens[k];
-      const int64_t base = reinterpret_cast<intptr_t>(gc->d_arena) - reinterpret_cast<intptr_t>(c->d_arena);
-      for (size_t j = 0; j < gc->chunks.size(); ++j) {
+      const size_t launched = gc->chunks.size() - static_cast<size_t>(gc->n_cont);
+      for (size_t j = 0; j < launched; ++j) {
         Chunk ch = gc->chunks[j];
         if ((ch.tier == 16) != (pass == 0)) continue;
         ch.slot = nb[ch.item] + gen_off[k][ch.item] + (ch.slot - gc->slot_begin[ch.item]);
-        ch.reserved = static_cast<int32_t>(k * n + ch.item);
         if (k == 0) own[j].slot = ch.slot;
-        ch.k_data += base;
-        ch.k_meta += base;
-        ch.v_data += base;
-        ch.v_meta += base;
-        table.push_back(ch);
+        table.push_back(moved(k, ch));
         n16 += pass == 0;
       }
     }
@@ -1267,9 +1358,15 @@ static rdkv_status rebuild_schedule(rdkv_cache* c, hipStream_t st) {
       ch.item = static_cast<int32_t>(i);
       ch.slot = nb[i] + nc[i] - npi + j;
       ch.row0 = j * kTailChunkRows;
+      ch.next = -1;
       table.push_back(ch);
     }
-  // launch order inside each kernel's range; the tail's chunks stay last
+  for (size_t k = 0; k < gens.size(); ++k) {
+    const rdkv_cache* gc = gens[k];
+    for (size_t j = gc->chunks.size() - static_cast<size_t>(gc->n_cont); j < gc->chunks.size(); ++j)
+      table.push_back(moved(k, gc->chunks[j]));
+  }
+  // launch order inside each kernel's range; the tail's chunks and the continuation pieces stay where they are
   order_chunks(table.begin(), table.begin() + n16, n);
   order_chunks(table.begin() + n16, table.begin() + n_gen_chunks, n);
   stamp_slots(table, nb, nc);
@@ -1560,7 +1657,7 @@ rdkv_status rdkv_cache_stats(const rdkv_cache* c, rdkv_stats* out) {
   out->evicted = c->total_tokens - kept;
   out->arena_bytes = c->arena_bytes;
   out->index_bytes = c->index_bytes;
-  out->n_chunks = static_cast<int64_t>(c->chunks.size());
+  out->n_chunks = static_cast<int64_t>(c->chunks.size()) - c->n_cont;   // launched work items (not their continuations)
   out->dense_bytes = c->total_tokens * kHeadDim * 2 * 2;
   out->lambda_min = out->lambda_max = std::nan("");
   if (c->d_lambda && c->d_iters && c->n_items > 0) {   // the token map's searches (Alg. 2); synchronous copies

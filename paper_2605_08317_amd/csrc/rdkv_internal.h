@@ -36,6 +36,9 @@ struct Chunk {
   int32_t reserved;                         // mixed mode: index of the chunk's ItemK in the schedule's table
                                             // (generation * items + item)
   int32_t slot0, nslots;                    // the item's first partial slot and its number of slots (= chunks)
+  int32_t next;                             // token-wise quantized tiers: index in the chunk table of the piece the same
+                                            // workgroup goes on with (another tier of the same item), -1: none
+  int32_t pad_;
 };
 constexpr int kTailChunkRows = 256;         // appended tokens per decode work item
 constexpr int kTierTail = 17;               // Chunk::tier of a chunk of appended tokens (64-token tiles of bf16 rows)
@@ -82,9 +85,10 @@ hipError_t launch_append_rows(const uint16_t* k_new, const uint16_t* v_new, uint
 hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t tail_tiles, int32_t n,
                                    uint16_t* k_rows, uint16_t* v_rows, hipStream_t st);
 
+// chunks: the whole chunk table; workgroup b starts with chunks[first + b] and, if `multi`, follows Chunk::next.
 // tail_len: device word holding the appended tokens that exist so far (chunks of tier kTierTail end there)
-hipError_t launch_decode_tiles(const Chunk* chunks, int n_chunks, const uint8_t* arena, const uint16_t* q,
-                               const MergeArgs& ma, const int32_t* tail_len, hipStream_t st);
+hipError_t launch_decode_tiles(const Chunk* chunks, int first, int n_chunks, bool multi, const uint8_t* arena,
+                               const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, hipStream_t st);
 // one object per head-set count (hs1: up to 4 query heads per KV head, hs2: 8)
 hipError_t launch_decode_mixed_hs1(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                    int max_words, int max_steps, int max_qsteps, const uint16_t* q,
@@ -163,6 +167,7 @@ struct rdkv_cache {
   std::vector<rdkv_cache*> absorbed;
   std::vector<int32_t> own_slot_count;  // [items]: partial slots of this cache's own chunks (no tail, no absorbed)
   int64_t sched16 = 0, schedq = 0;      // chunks of the schedule: 16-bit tier, then the quantized tiers (all generations)
+  int64_t n_cont = 0;                   // continuation pieces of this cache's own chunks: the last n_cont entries of `chunks`
   rdkv::ItemK* d_items_sched = nullptr; // mixed mode with absorbed generations: [generations][items] K row layouts
   int32_t sched_k_words = 0, sched_k_steps = 0, sched_k_qsteps = 0;   // largest K row shape over all generations
   double* d_lambda = nullptr;           // [items] (token map), channel-wise mode: + [items] (channel map): the

@@ -162,3 +162,58 @@ def test_token_weights_of_a_128k_layer_against_the_oracle(layer, head):
     assert err.max() <= WEIGHT_RTOL
     ref_c = O.channel_weights(Kh, Qh)[0]
     np.testing.assert_allclose(w_ch.view(wl.hkv, wl.d)[head].cpu().numpy(), ref_c, rtol=1e-5)
+
+
+@pytest.mark.parametrize("hq", [32, 64])
+def test_large_launch_whose_chunks_span_tiers(hq):
+    """In a launch of hundreds of megabytes a workgroup's share of an item runs through several tiers (2-bit rows, then
+    4-bit, then 8-bit, on one softmax state).  Four sequences of 64K tokens with random bit maps over all five widths;
+    sampled items are recomputed by the oracle from the same maps (4 and 8 query heads per KV head)."""
+    b = B()
+    hkv, T, nseq, d = 8, 65536, 4, 128
+    g = hq // hkv
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    K = torch.randn((nseq, hkv, T, d), device="cuda", generator=gen).to(torch.bfloat16)
+    V = torch.randn((nseq, hkv, T, d), device="cuda", generator=gen).to(torch.bfloat16)
+    q = torch.randn((nseq, hq, d), device="cuda", generator=gen).to(torch.bfloat16)
+    tiers = torch.tensor([0, 2, 4, 8, 16], dtype=torch.uint8, device="cuda")
+    pick = torch.multinomial(torch.tensor([.25, .3, .2, .2, .05], device="cuda"), nseq * hkv * T, replacement=True, generator=gen)
+    bits = tiers[pick]
+    print(f"[case] chunks spanning tiers, g = {g}", flush=True)
+    cfg = b.Config([T] * nseq, hq, hkv)
+    cache = b.rdkv_pack(cfg, K.reshape(-1), V.reshape(-1), bits)
+    st = cache.stats()
+    print(f"[stats] stored {st['stored_bytes'] / 1e6:.0f} MB in {st['n_chunks']} chunks", flush=True)
+    assert st["stored_bytes"] > 150e6 and st["n_chunks"] < 2200
+    out, lse = b.rdkv_decode_attn(cache, q)
+    torch.cuda.synchronize()
+    bits_h = bits.view(nseq, hkv, T)
+    samples = [(0, 0), (2, 5), (3, 7)]
+    refs = [O.build_cache_tokenwise([K[s, h].float().cpu().numpy()[None]], [V[s, h].float().cpu().numpy()[None]],
+                                    [bits_h[s, h].cpu().numpy()[None]]) for (s, h) in samples]
+
+    def check(out, lse, what):
+        worst = 0.0
+        for (s, h), ref in zip(samples, refs):
+            ro, rl = O.decode(ref, q[s:s + 1, h * g:(h + 1) * g].float().cpu().numpy())
+            go = out[s, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)[None]
+            gl = lse[s, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)[None]
+            err = _rel_err(go, ro)
+            worst = max(worst, err)
+            assert err <= DECODE_TOL
+            np.testing.assert_allclose(gl, rl, rtol=1e-4, atol=1e-4)
+        print(f"[chunks spanning tiers] {what}: worst sampled decode error {worst:.2e}", flush=True)
+
+    check(out, lse, "prompt")
+    # a tail rebuilds the schedule: the chained pieces move to new places in the chunk table
+    b.rdkv_cache_reserve_tail(cache, 64)
+    kn = torch.randn((5, nseq, hkv, d), device="cuda", generator=gen).to(torch.bfloat16)
+    vn = torch.randn((5, nseq, hkv, d), device="cuda", generator=gen).to(torch.bfloat16)
+    for i in range(5):
+        b.rdkv_cache_append(cache, kn[i], vn[i])
+        for (s, h), ref in zip(samples, refs):
+            O.append_tokens(ref, kn[i, s:s + 1, h:h + 1].float().cpu().numpy(), vn[i, s:s + 1, h:h + 1].float().cpu().numpy())
+    out, lse = b.rdkv_decode_attn(cache, q)
+    torch.cuda.synchronize()
+    check(out, lse, "prompt + 5 appended tokens")
+    cache.free()

@@ -24,9 +24,10 @@ struct MergeArgs {
 
 inline hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                       int max_words, int max_steps, int max_qsteps, const uint16_t* q,
-                                      const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st) {
+                                      const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
+                                      hipStream_t st) {
   return (ma.hq / ma.hkv > 4 ? launch_decode_mixed_hs2 : launch_decode_mixed_hs1)(
-      chunks, n_chunks, arena, items_k, max_words, max_steps, max_qsteps, q, ma, tail_len, per_unit, st);
+      chunks, n_chunks, arena, items_k, max_words, max_steps, max_qsteps, q, ma, tail_len, per_unit, waves, st);
 }
 
 namespace merge {

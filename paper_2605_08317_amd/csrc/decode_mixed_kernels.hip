@@ -30,7 +30,8 @@ namespace {
 
 using namespace tile;
 
-constexpr int kWaves = 4, kWG = 256;   // wavefronts and threads per workgroup
+// Wavefronts per workgroup: four, or eight for launches that fit the chip in one round (half as many partials per
+// item for the same number of wavefronts in flight; every chunk costs its item an arrival and a partial to merge).
 
 // LDS: query operands per step [steps][HS][4 heads] x 8 bytes (raw bf16 for 16-bit steps, fp16 q * 2^(kQExp - fb)
 // for quantized ones), fp16 q * 2^kQExp per quantized step (for the offsets), then per wavefront the scaled-query
@@ -38,7 +39,7 @@ constexpr int kWaves = 4, kWG = 256;   // wavefronts and threads per workgroup
 // chunk's end reuses the same memory.
 struct LdsPlan {
   int qpre, qraw, wtab, wtab_wave, total;
-  __host__ __device__ LdsPlan(int n_steps, int n_qsteps, int hs, int g) {
+  __host__ __device__ LdsPlan(int n_steps, int n_qsteps, int hs, int g, int kWaves) {
     qpre = 0;
     qraw = qpre + n_steps * hs * 32;
     wtab = qraw + n_qsteps * hs * 32;
@@ -52,7 +53,7 @@ struct LdsPlan {
 // bit offset left after the copy shift of field f of a 16-bit half (tier b): the code reads as code * 2^fb * 2^-24
 __device__ __forceinline__ int field_fb(int b, int f) { return b == 2 ? 2 * (f % 3) : b == 4 ? 4 * (f % 2) : 0; }
 
-template <int VT, int NW, int HS>
+template <int VT, int NW, int HS, int NWV>
 __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __restrict__ arena,
                                               const ItemK* __restrict__ ikp, int g, const uint16_t* __restrict__ q,
                                               const MergeArgs& ma, const ChunkOut& co,
@@ -71,7 +72,8 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
   const int nqs = (e8 - e16) + 2 * (e4 - e8) + 4 * (e2 - e4);
   const int n_steps = ns16 + nqs;
   const int kt_bytes = 256 * nwp, km_bytes = 32 * nqs;
-  const LdsPlan plan(lds_steps, lds_qsteps, HS, g);   // the launch sized LDS for the largest item of the cache
+  constexpr int kWaves = NWV, kWG = NWV * 64;
+  const LdsPlan plan(lds_steps, lds_qsteps, HS, g, kWaves);   // the launch sized LDS for the largest item of the cache
   const uint8_t* s_qpre = smem + plan.qpre;
   const uint8_t* s_qraw = smem + plan.qraw;
   uint8_t* s_wtab = smem + plan.wtab + wave * plan.wtab_wave;
@@ -428,12 +430,12 @@ __device__ __forceinline__ void process_mixed(const Chunk& ch, const uint8_t* __
     }
   }
 
-  finish_chunk<HS, true, kWaves>(run, VT == 16 ? 1.0f : 16777216.0f, lk, g, reinterpret_cast<float*>(smem),
+  finish_chunk<HS, true, NWV>(run, VT == 16 ? 1.0f : 16777216.0f, lk, g, reinterpret_cast<float*>(smem),
                                  reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2, ma, co);
 }
 
-template <int NW, int HS>
-__global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mixed_kernel(
+template <int NW, int HS, int NWV>
+__global__ __launch_bounds__(NWV * 64, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mixed_kernel(
     const Chunk* __restrict__ chunks, const uint8_t* __restrict__ arena, const ItemK* __restrict__ items_k,
     const uint16_t* __restrict__ q, MergeArgs ma, int lds_steps, int lds_qsteps, const int32_t* __restrict__ tail_len,
     int per_unit) {
@@ -447,30 +449,30 @@ __global__ __launch_bounds__(kWG, (NW <= 32 && HS == 1) ? 3 : 2) void decode_mix
   switch (ch.tier) {
     case kTierTail: {   // appended tokens: 64-token tiles of bf16 rows, as many rows as exist so far
       const int rows = max(0, min(ch.rows, *tail_len - ch.row0));
-      process_tail_tiles<HS, true, kWaves>(arena + ch.k_data, arena + ch.v_data, rows, g, qp, smem,
-                                           reinterpret_cast<float*>(smem),
-                                           reinterpret_cast<float*>(smem) + kWaves * 4 * HS * 2, ma, co);
+      process_tail_tiles<HS, true, NWV>(arena + ch.k_data, arena + ch.v_data, rows, g, qp, smem,
+                                        reinterpret_cast<float*>(smem),
+                                        reinterpret_cast<float*>(smem) + NWV * 4 * HS * 2, ma, co);
       break;
     }
-    case 16: process_mixed<16, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
-    case 8: process_mixed<8, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
-    case 4: process_mixed<4, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
-    default: process_mixed<2, NW, HS>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    case 16: process_mixed<16, NW, HS, NWV>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    case 8: process_mixed<8, NW, HS, NWV>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    case 4: process_mixed<4, NW, HS, NWV>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
+    default: process_mixed<2, NW, HS, NWV>(ch, arena, ikp, g, qp, ma, co, smem, lds_steps, lds_qsteps, per_unit != 0); break;
   }
 }
 
-template <int NW, int HS>
+template <int NW, int HS, int NWV>
 hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int lds_steps,
                       int lds_qsteps, const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, int per_unit,
                       hipStream_t st) {
-  const size_t lds = static_cast<size_t>(LdsPlan(lds_steps, lds_qsteps, HS, ma.hq / ma.hkv).total);
+  const size_t lds = static_cast<size_t>(LdsPlan(lds_steps, lds_qsteps, HS, ma.hq / ma.hkv, NWV).total);
   if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_mixed_kernel<NW, HS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_mixed_kernel<NW, HS, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((decode_mixed_kernel<NW, HS>), dim3(n_chunks), dim3(kWG), lds, st, chunks, arena, items_k, q,
-                     ma, lds_steps, lds_qsteps, tail_len, per_unit);
+  hipLaunchKernelGGL((decode_mixed_kernel<NW, HS, NWV>), dim3(n_chunks), dim3(NWV * 64), lds, st, chunks, arena,
+                     items_k, q, ma, lds_steps, lds_qsteps, tail_len, per_unit);
   return hipGetLastError();
 }
 
@@ -480,19 +482,26 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
 #define RDKV_MIXED_NAME(a_, b_) RDKV_MIXED_NAME2(a_, b_)
 hipError_t RDKV_MIXED_NAME(launch_decode_mixed_hs, RDKV_MIXED_HS)(
     const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int max_words, int max_steps,
-    int max_qsteps, const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st) {
+    int max_qsteps, const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
+    hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
-#define RDKV_MIXED_LAUNCH(NW_)                                                                             \
-  return launch_one<NW_, RDKV_MIXED_HS>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, ma, tail_len, \
-                                        per_unit, st)
+#define RDKV_MIXED_LAUNCH(NW_, NWV_)                                                                            \
+  return launch_one<NW_, RDKV_MIXED_HS, NWV_>(chunks, n_chunks, arena, items_k, max_steps, max_qsteps, q, ma,   \
+                                              tail_len, per_unit, st)
   // kMaxKRowWords = 68 is the longest row a channel bit map can give (125 channels at 16 bits and one each at 8, 4
   // and 2 bits: 64 + 1 + 1 + 1 words, padded to an even count); the host refuses anything longer
   static_assert(kMaxKRowWords == 68, "the widest instantiation below must hold the longest K row");
   if (max_words > kMaxKRowWords) return hipErrorInvalidValue;
-  if (max_words <= 16) RDKV_MIXED_LAUNCH(16);
-  if (max_words <= 32) RDKV_MIXED_LAUNCH(32);
-  if (max_words <= 64) RDKV_MIXED_LAUNCH(64);
-  RDKV_MIXED_LAUNCH(68);
+#if RDKV_MIXED_HS == 1
+  // eight-wavefront workgroups exist for up to four query heads per KV head and rows of up to 32 words
+  if (waves == 8 && max_words <= 16) RDKV_MIXED_LAUNCH(16, 8);
+  if (waves == 8 && max_words <= 32) RDKV_MIXED_LAUNCH(32, 8);
+#endif
+  (void)waves;
+  if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 4);
+  if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 4);
+  if (max_words <= 64) RDKV_MIXED_LAUNCH(64, 4);
+  RDKV_MIXED_LAUNCH(68, 4);
 #undef RDKV_MIXED_LAUNCH
 }
 

@@ -707,8 +707,12 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   // Small launches are bound by latencies instead and want fewer, larger chunks still: at least 96 KB (measured on a
   // 16 MB layer: 96 KB chunks 12.6 us, 64 KB 13.4 us, 24 KB 20 us).  Kernels with four-wavefront workgroups (8 query
   // heads per KV head, channel-wise K) keep three workgroups per compute unit resident: 768 chunks of at least 48 KB.
-  const bool wide = !mixed && g <= 4;      // eight-wavefront workgroups
-  const int64_t round_chunks = wide ? 512 : 768;
+  // channel-wise mode: eight-wavefront workgroups when the launch is small (one workgroup per compute unit holds
+  // it) and the kernel has such an instantiation (up to 4 query heads per KV head, K rows of up to 32 words)
+  const bool mixed_wide = mixed && g <= 4 && c->max_k_words <= 32 && stored < (static_cast<int64_t>(48) << 20);
+  c->mixed_waves = mixed_wide ? 8 : 4;
+  const bool wide = (!mixed && g <= 4) || mixed_wide;      // eight-wavefront workgroups
+  const int64_t round_chunks = mixed_wide ? 256 : wide ? 512 : 768;
   // Cost of a row of a tier segment: its stored bytes, weighted in token-wise mode by what a byte of that tier costs
   // the decode kernel relative to an 8-bit byte (single-tier launches reach 4.92 / 5.41 / 5.68 / 5.38 TB/s on 2- /
   // 4- / 8- / 16-bit rows): in a launch of one round the slowest chunk sets the time, so chunks are balanced by
@@ -1267,7 +1271,9 @@ rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, flo
     RDKV_HIP(launch_decode_mixed(c->d_chunks, n16 + nrest, c->d_arena, c->d_items_sched ? c->d_items_sched : c->d_items_k,
                                  std::max(c->max_k_words, c->sched_k_words), std::max(c->max_k_steps, c->sched_k_steps),
                                  std::max(c->max_k_qsteps, c->sched_k_qsteps), static_cast<const uint16_t*>(q), ma,
-                                 c->d_tail_state, c->k_per_unit, st));
+                                 c->d_tail_state, c->k_per_unit,
+                                 std::max(c->max_k_words, c->sched_k_words) <= 32 && c->hq / c->hkv <= 4 ? c->mixed_waves : 4,
+                                 st));
     return RDKV_OK;
   }
   // the workgroups of both kernels announce themselves on the same counters: whichever finishes an item merges it

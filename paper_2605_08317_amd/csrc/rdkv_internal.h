@@ -90,16 +90,20 @@ hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t
 hipError_t launch_decode_tiles(const Chunk* chunks, int first, int n_chunks, bool multi, const uint8_t* arena,
                                const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, hipStream_t st);
 // one object per head-set count (hs1: up to 4 query heads per KV head, hs2: 8)
+// waves: wavefronts per workgroup, 4 or 8 (8 only where such an instantiation exists: hs1, rows of up to 32 words)
 hipError_t launch_decode_mixed_hs1(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                    int max_words, int max_steps, int max_qsteps, const uint16_t* q,
-                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st);
+                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
+                                   hipStream_t st);
 hipError_t launch_decode_mixed_hs2(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                    int max_words, int max_steps, int max_qsteps, const uint16_t* q,
-                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st);
+                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
+                                   hipStream_t st);
 
 inline hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                       int max_words, int max_steps, int max_qsteps, const uint16_t* q,
-                                      const MergeArgs& ma, const int32_t* tail_len, int per_unit, hipStream_t st);
+                                      const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
+                                      hipStream_t st);
 
 // Optional event bracketing of the main kernels (rdkv_kernel_timing_*).
 void timing_begin(int kind, hipStream_t st);
@@ -150,6 +154,7 @@ struct rdkv_cache {
   mutable std::mutex ws_mu;
   int64_t n_slots = 0;                  // partial slots of the whole schedule
   int32_t* d_tail_state = nullptr;      // {appended tokens so far, workgroups of the running append that are done}
+  int32_t mixed_waves = 4;              // channel-wise mode: wavefronts per workgroup of the decode kernel (4 or 8)
   uint8_t* d_bits_tok = nullptr;        // copy of the token bit map
   uint8_t* d_bits_ch = nullptr;         // [items][128] K channel bit map (mixed mode)
   rdkv::ItemK* d_items_k = nullptr;     // [items] (mixed mode)

@@ -217,3 +217,22 @@ def test_large_launch_whose_chunks_span_tiers(hq):
     torch.cuda.synchronize()
     check(out, lse, "prompt + 5 appended tokens")
     cache.free()
+
+
+def test_mixed_config_with_three_sequences():
+    """Three 64K-token sequences of the mixed-granularity configuration (70 MB stored): the launch is no longer small,
+    so the channel-wise kernel runs with four-wavefront workgroups and about two rounds of chunks."""
+    b = B()
+    wl = W.scaled(W.CONFIGS["mixed"], batch=3, seq_lens=(65536,) * 3, budgets=(1.0,))
+    print("[case] full-size mixed, 3 sequences", flush=True)
+    inp = W.make_inputs(wl, device="cuda")
+    cfg = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=inp["budgets"], s_obs=wl.s_obs, k_mode=b.RDKV_K_CHANNELWISE)
+    _, w_ch = b.rdkv_weights(cfg, inp["K"], inp["Q_obs"], want_channel=True)
+    bits_tok, bits_ch = b.rdkv_allocate(cfg, inp["w_tok"], w_ch)
+    cache = b.rdkv_pack(cfg, inp["K"], inp["V"], bits_tok, bits_ch)
+    out, lse = b.rdkv_decode_attn(cache, inp["q"])
+    torch.cuda.synchronize()
+    assert cache.stats()["stored_bytes"] > 48 << 20
+    _check_sampled_items(b, wl, inp, cache, out, lse, inp["w_tok"], [(0, 1), (2, 6)], mixed=True,
+                         w_ch=w_ch.cpu().numpy().reshape(-1, wl.d))
+    cache.free()

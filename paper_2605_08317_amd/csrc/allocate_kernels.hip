@@ -493,7 +493,6 @@ __global__ __launch_bounds__(kThreads) void steps_kernel(MultiArgs m) {
     }
   }
   int steps = it0;
-  bool stopped = false;
   for (int it = it0; it < a.max_iters; ++it) {
     const double lam = (lo + hi) * 0.5;
     double thr[kMaxHull - 1];
@@ -576,10 +575,9 @@ __global__ __launch_bounds__(kThreads) void steps_kernel(MultiArgs m) {
       best = lam;
       have = true;
       hi = lam;
-      if (verdict == 2) { stopped = true; break; }
+      if (verdict == 2) break;
     }
   }
-  (void)stopped;
   if (threadIdx.x == 0) {   // the search is over
     st.best = best; st.have = have; st.done = 1; st.fill = -1; st.steps = steps;
     if (a.lam_out && have) a.lam_out[item] = best;

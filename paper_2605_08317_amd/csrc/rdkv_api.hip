@@ -731,7 +731,10 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
     for (int ti = ti0; ti < 4; ++ti) total_cost += c->counts[i * 4 + ti] * row_cost(i, pack_tier_bits(ti));
     if (!mixed) cost16 += c->counts[i * 4] * row_cost(i, 16);
   }
-  // number of chunks a chunk cost of cb gives, and the largest chunk's cost
+  // Number of chunks a chunk cost of cb gives, and the largest chunk's cost.  Chunks of less than an eighth of cb (a
+  // tier with a handful of rows) do not count: they finish at once and leave their workgroup slot to the next chunk
+  // (16 channel-wise sequences of 64K tokens: six even chunks per item and one tiny one, 899 in all on 768 slots,
+  // take 108 us; five or seven per item 127-134 us).
   auto count_chunks = [&](int64_t cb, int64_t* max_cost) {
     int64_t total = 0;
     *max_cost = 0;
@@ -740,6 +743,7 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
         const int64_t cnt = c->counts[i * 4 + ti];
         if (cnt == 0) continue;
         const int64_t rc = row_cost(i, pack_tier_bits(ti));
+        if (cnt * rc < cb / 8) continue;
         const int64_t want = std::max<int64_t>(64, cb / rc);
         const int64_t nch = (cnt + want - 1) / want;
         const int64_t rows_per = round_up((cnt + nch - 1) / nch, 64);
@@ -769,15 +773,15 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
   const bool shares = !mixed && chunk_bytes >= (192 << 10);
   auto count_any = [&](int64_t cb, int64_t* max_cost) { return shares ? count_shares(cb, max_cost) : count_chunks(cb, max_cost); };
   int64_t max_cost = 0, n_one_round = count_any(chunk_bytes, &max_cost);
-  for (int tries = 0; tries < 64 && n_one_round > round_chunks; ++tries) {
+  for (int tries = 0; tries < 64 && n_one_round > round_chunks + round_chunks / 50; ++tries) {   // (2 % over is fine)
     chunk_bytes += chunk_bytes / 16 + 1;
     n_one_round = count_any(chunk_bytes, &max_cost);
   }
   // When one round cannot be had (more tier segments than resident workgroups) or would be lopsided (its largest
-  // chunk more than a fifth above the mean), about two rounds of smaller chunks even things out instead (16
-  // sequences of 8K-32K tokens at 8 query heads per KV head: 1295 chunks 54.6 us, 2600 chunks 65.2 us, 733 chunks
-  // 57.8 us).
-  if (n_one_round > round_chunks || max_cost * n_one_round > total_cost + total_cost / 5)
+  // chunk more than a fifth above the mean), about two rounds of smaller chunks even things out instead.
+  // (Shares are even up to the rounding of an item's share count and stay in one round: 16 ragged sequences at 8
+  // query heads per KV head, 728 chunks 52.9 us against 57.6 us for 1529.)
+  if (!shares && (n_one_round > round_chunks + round_chunks / 50 || max_cost * n_one_round > total_cost + total_cost / 5))
     chunk_bytes = std::max<int64_t>((wide ? 96 : 48) << 10, total_cost / (2 * round_chunks));
   // The row-major 16-bit kernel keeps two workgroups per compute unit resident (70 KB of LDS each): one round of
   // its own.

@@ -110,7 +110,8 @@ typedef struct rdkv_stats {
                                (channel-wise mode: K codes n * sum_c b_c / 8 and 4 bytes per quantized channel
                                and group of 32 retained tokens, V rows as in token-wise mode) */
   int64_t arena_bytes;      /* bytes allocated for the packed arena (with padding and alignment) */
-  int64_t index_bytes;      /* kept-position lists, segment tables, split schedule */
+  int64_t index_bytes;      /* what else the cache's block holds: kept-position lists, bit maps, split schedule, the
+                               first split workspace */
   int64_t n_chunks;         /* work items of one decode launch */
   int64_t dense_bytes;      /* 2 * sum_s hkv*T_s*head_dim*2: the uncompressed bf16 K+V */
   int64_t alloc_info;       /* 1 if the cache came from rdkv_compress, so that the fields below are known; else 0 */
@@ -207,10 +208,13 @@ rdkv_status rdkv_compress(const rdkv_config* cfg, const void* K, const void* V,
  * through cfg->alloc for this batch (Sec. 3.2: the summed bit-widths of an item never exceed floor(avg_bits * units),
  * so it keeps at most that over the lowest stored bit-width tokens): a caller can reserve memory for a cache before
  * the pass has run.  Needs batch, heads, seq_lens, budget_bits, k_mode, kv_split_rk and tiers; 0 on an invalid config.
- * The bound covers the arena (codes, scales, offsets, padding), not the index tables (4 bytes per kept token and
- * 56 bytes per work item of the split schedule).
+ * The bound covers the arena (codes, scales, offsets, padding).  rdkv_pack takes one block through cfg->alloc that
+ * holds the arena and the cache's tables (kept positions, bit maps, split schedule, the first split workspace);
+ * rdkv_cache_max_table_bytes bounds those tables the same way, so the sum of the two bounds what that one allocation
+ * can ask for (rdkv_stats: arena_bytes + index_bytes).
  */
 size_t rdkv_cache_max_bytes(const rdkv_config* cfg);
+size_t rdkv_cache_max_table_bytes(const rdkv_config* cfg);
 
 /*
  * One decode step over the packed cache (Sec. 3.3, Eq. 7): for every sequence

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "RDKV_OK", 1: "RDKV_ERR_INVALID_ARG", 2: "RDKV_ERR_SHAPE", 3:
                 4: "RDKV_ERR_ALLOC", 5: "RDKV_ERR_HIP", 6: "RDKV_ERR_INTERNAL"}
 
 EXPORTED_SYMBOLS = [
-    "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_allocate_info", "rdkv_pack", "rdkv_cache_max_bytes",
+    "rdkv_version", "rdkv_last_error", "rdkv_config_default", "rdkv_weights", "rdkv_allocate", "rdkv_allocate_info", "rdkv_pack", "rdkv_cache_max_bytes", "rdkv_cache_max_table_bytes",
     "rdkv_compress", "rdkv_decode_attn", "rdkv_decode_bf16_workspace_bytes", "rdkv_decode_attn_bf16",
     "rdkv_decode_bf16_noalloc_max_bytes", "rdkv_decode_attn_bf16_noalloc",
     "rdkv_cache_reserve_tail", "rdkv_cache_append", "rdkv_cache_tail_len", "rdkv_cache_tail_len_sync", "rdkv_calibrate_eps",
@@ -82,6 +82,8 @@ def _load():
     lib.rdkv_allocate_info.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
     lib.rdkv_cache_max_bytes.argtypes = [cfgp]
     lib.rdkv_cache_max_bytes.restype = sz
+    lib.rdkv_cache_max_table_bytes.argtypes = [cfgp]
+    lib.rdkv_cache_max_table_bytes.restype = sz
     lib.rdkv_pack.argtypes = [cfgp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
     lib.rdkv_compress.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp)]
     lib.rdkv_decode_attn.argtypes = [vp, vp, vp, vp, vp]
@@ -237,6 +239,10 @@ def rdkv_allocate_info(cfg, w_tok, w_ch=None):
 
 def rdkv_cache_max_bytes(cfg):
     return int(lib.rdkv_cache_max_bytes(cfg.ref()))
+
+
+def rdkv_cache_max_table_bytes(cfg):
+    return int(lib.rdkv_cache_max_table_bytes(cfg.ref()))
 
 
 def rdkv_pack(cfg, K, V, bits_tok, bits_ch=None):

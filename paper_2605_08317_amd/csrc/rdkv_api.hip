@@ -924,7 +924,7 @@ rdkv_status pack_impl(const rdkv_config* cfg, const Items& it, const Tables& tb,
       c->d_items_k = reinterpret_cast<ItemK*>(c->d_block + o_ik);
     }
     c->d_chunks = reinterpret_cast<Chunk*>(c->d_block + o_ik + ik_b);
-    c->index_bytes = kept * 4 + n_chunks * static_cast<int64_t>(sizeof(Chunk)) + n * 8 + n * 16 * 8;
+    c->index_bytes = total - c->arena_bytes;     // everything else in the block
     if (n > 0) {
       // nothing below waits: tables are copied out of pinned staging memory, and the host vectors may go
       PACK_HIP(hipMemsetAsync(c->d_block, 0, o_idx, st));     // arena (padding rows read as zeros), tail state, counters
@@ -1254,9 +1254,36 @@ static size_t cache_max_bytes(const rdkv_config* cfg) {
   return static_cast<size_t>(total) + kSegAlign;
 }
 
+// The same for everything else in the cache's block: kept positions (4 bytes each), the bit maps, the K row layouts,
+// the chunk table and the first split workspace (at most two rounds of chunks and four per item, 80 bytes and
+// g x 130 floats each), lambda and step counts, and the alignment of the parts.
+static size_t cache_max_table_bytes(const rdkv_config* cfg) {
+  const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
+  const int g = cfg->hq / cfg->hkv;
+  int b_min = 16;
+  for (int i = 0; i < cfg->n_tiers; ++i)
+    if (cfg->tiers[i] > 0) b_min = std::min(b_min, cfg->tiers[i]);
+  double kept = 0.0, tokens = 0.0;
+  for (int s = 0; s < cfg->batch; ++s) {
+    const double T = static_cast<double>(cfg->seq_lens[s]);
+    const double a = static_cast<double>(cfg->budget_bits[s]) * (mixed ? 2.0 * (1.0 - static_cast<double>(cfg->kv_split_rk)) : 1.0);
+    kept += cfg->hkv * std::min(std::floor(a * T) / b_min, T);
+    tokens += cfg->hkv * T;
+  }
+  const double items = static_cast<double>(cfg->batch) * cfg->hkv;
+  const double chunks = 2.0 * 768.0 + 8.0 * items;
+  return static_cast<size_t>(4.0 * kept + tokens + items * (kHeadDim + sizeof(ItemK) + 4 + 2 * 12) +
+                             chunks * (sizeof(Chunk) + g * (kHeadDim + 2) * 4.0) + 16.0 * 256);
+}
+
 size_t rdkv_cache_max_bytes(const rdkv_config* cfg) {
   if (check_config(cfg, true, false) != RDKV_OK) return 0;
   return cache_max_bytes(cfg);
+}
+
+size_t rdkv_cache_max_table_bytes(const rdkv_config* cfg) {
+  if (check_config(cfg, true, false) != RDKV_OK) return 0;
+  return cache_max_table_bytes(cfg);
 }
 
 rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, float* lse, void* stream) {

@@ -127,6 +127,9 @@ def test_arena_stays_below_the_a_priori_bound(name, kw, mixed):
     st = cache.stats()
     print(f"[bound] {name}: arena {st['arena_bytes']} <= bound {bound} ({st['arena_bytes'] / bound:.2f})", flush=True)
     assert 0 < st["arena_bytes"] <= bound
+    tbound = b.rdkv_cache_max_table_bytes(cfg)
+    print(f"[bound] {name}: tables {st['index_bytes']} <= bound {tbound} ({st['index_bytes'] / tbound:.2f})", flush=True)
+    assert 0 < st["index_bytes"] <= tbound
     cache.free()
     # the largest budgets: every row at 16 bits
     cfg16 = b.Config(inp["seq_lens"], wl.hq, wl.hkv, budget_bits=[16.0] * len(inp["seq_lens"]), s_obs=wl.s_obs, **extra)

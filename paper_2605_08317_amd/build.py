@@ -7,11 +7,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librdkv.so")
-# (source, object, extra flags); the mixed-mode decode kernels are compiled once per head-set count so that their
-# many instantiations build in parallel; the slowest objects come first
+# (source, object, extra flags); the mixed-mode decode kernels are compiled once per head-set count and row length
+# class so that their many instantiations build in parallel; the slowest objects come first
 SOURCES = [
-    ("decode_mixed_kernels.hip", "decode_mixed_hs2.o", ["-DRDKV_MIXED_HS=2"]),
-    ("decode_mixed_kernels.hip", "decode_mixed_hs1.o", ["-DRDKV_MIXED_HS=1"]),
+    ("decode_mixed_kernels.hip", "decode_mixed_hs2_long1.o", ["-DRDKV_MIXED_HS=2", "-DRDKV_MIXED_LONG=1"]),
+    ("decode_mixed_kernels.hip", "decode_mixed_hs2_long0.o", ["-DRDKV_MIXED_HS=2", "-DRDKV_MIXED_LONG=0"]),
+    ("decode_mixed_kernels.hip", "decode_mixed_hs1_long1.o", ["-DRDKV_MIXED_HS=1", "-DRDKV_MIXED_LONG=1"]),
+    ("decode_mixed_kernels.hip", "decode_mixed_hs1_long0.o", ["-DRDKV_MIXED_HS=1", "-DRDKV_MIXED_LONG=0"]),
     ("decode_mfma_kernels.hip", "decode_mfma_kernels.o", []),
     ("rdkv_api.hip", "rdkv_api.o", []),
     ("decode_rows_mfma.hip", "decode_rows_mfma.o", []),
@@ -35,7 +37,7 @@ FLAGS = [
 ]
 
 
-def build(verbose=True, jobs=6):
+def build(verbose=True, jobs=8):
     objs, procs = [], []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
     for src, obj_name, extra in SOURCES:

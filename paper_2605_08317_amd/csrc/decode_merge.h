@@ -26,7 +26,9 @@ inline hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const u
                                       int max_words, int max_steps, int max_qsteps, const uint16_t* q,
                                       const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
                                       hipStream_t st) {
-  return (ma.hq / ma.hkv > 4 ? launch_decode_mixed_hs2 : launch_decode_mixed_hs1)(
+  const bool hs2 = ma.hq / ma.hkv > 4, lng = max_words > 32;
+  return (hs2 ? (lng ? launch_decode_mixed_hs2_long1 : launch_decode_mixed_hs2_long0)
+              : (lng ? launch_decode_mixed_hs1_long1 : launch_decode_mixed_hs1_long0))(
       chunks, n_chunks, arena, items_k, max_words, max_steps, max_qsteps, q, ma, tail_len, per_unit, waves, st);
 }
 

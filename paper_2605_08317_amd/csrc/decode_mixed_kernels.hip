@@ -16,12 +16,13 @@
 // V side, softmax and the end-of-chunk merge are the stages shared with the token-wise kernel; 16-bit V rows are
 // 64-token tiles of bf16 with the same lane assignment, multiplied by the probabilities as two bf16 terms.
 //
-// This file is compiled once per head-set count (-DRDKV_MIXED_HS=1: up to 4 query heads per KV head, =2: 8), each
-// into an object of its own, so that the many instantiations build in parallel.
+// This file is compiled once per head-set count (-DRDKV_MIXED_HS=1: up to 4 query heads per KV head, =2: 8) and row
+// length class (-DRDKV_MIXED_LONG=0: K rows of up to 32 words, =1: up to 68), each into an object of its own, so
+// that the many instantiations build in parallel.
 #include "decode_tile_common.h"
 
-#ifndef RDKV_MIXED_HS
-#error "compile with -DRDKV_MIXED_HS=1 or -DRDKV_MIXED_HS=2"
+#if !defined(RDKV_MIXED_HS) || !defined(RDKV_MIXED_LONG)
+#error "compile with -DRDKV_MIXED_HS=1 or 2 and -DRDKV_MIXED_LONG=0 (K rows of up to 32 words) or 1 (up to 68)"
 #endif
 
 namespace rdkv {
@@ -478,9 +479,9 @@ hipError_t launch_one(const Chunk* chunks, int n_chunks, const uint8_t* arena, c
 
 }  // namespace
 
-#define RDKV_MIXED_NAME2(a_, b_) a_##b_
-#define RDKV_MIXED_NAME(a_, b_) RDKV_MIXED_NAME2(a_, b_)
-hipError_t RDKV_MIXED_NAME(launch_decode_mixed_hs, RDKV_MIXED_HS)(
+#define RDKV_MIXED_NAME3(a_, b_, c_, d_) a_##b_##c_##d_
+#define RDKV_MIXED_NAME(a_, b_, c_, d_) RDKV_MIXED_NAME3(a_, b_, c_, d_)
+hipError_t RDKV_MIXED_NAME(launch_decode_mixed_hs, RDKV_MIXED_HS, _long, RDKV_MIXED_LONG)(
     const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int max_words, int max_steps,
     int max_qsteps, const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
     hipStream_t st) {
@@ -490,18 +491,22 @@ hipError_t RDKV_MIXED_NAME(launch_decode_mixed_hs, RDKV_MIXED_HS)(
                                               tail_len, per_unit, st)
   // kMaxKRowWords = 68 is the longest row a channel bit map can give (125 channels at 16 bits and one each at 8, 4
   // and 2 bits: 64 + 1 + 1 + 1 words, padded to an even count); the host refuses anything longer
-  static_assert(kMaxKRowWords == 68, "the widest instantiation below must hold the longest K row");
+  static_assert(kMaxKRowWords == 68, "the widest instantiation must hold the longest K row");
   if (max_words > kMaxKRowWords) return hipErrorInvalidValue;
+  (void)waves;
+#if RDKV_MIXED_LONG == 0
 #if RDKV_MIXED_HS == 1
   // eight-wavefront workgroups exist for up to four query heads per KV head and rows of up to 32 words
   if (waves == 8 && max_words <= 16) RDKV_MIXED_LAUNCH(16, 8);
   if (waves == 8 && max_words <= 32) RDKV_MIXED_LAUNCH(32, 8);
 #endif
-  (void)waves;
   if (max_words <= 16) RDKV_MIXED_LAUNCH(16, 4);
   if (max_words <= 32) RDKV_MIXED_LAUNCH(32, 4);
+  return hipErrorInvalidValue;
+#else
   if (max_words <= 64) RDKV_MIXED_LAUNCH(64, 4);
   RDKV_MIXED_LAUNCH(68, 4);
+#endif
 #undef RDKV_MIXED_LAUNCH
 }
 

@@ -90,16 +90,17 @@ hipError_t launch_gather_tail_rows(const uint8_t* tail, int64_t n_items, int32_t
 hipError_t launch_decode_tiles(const Chunk* chunks, int first, int n_chunks, bool multi, const uint8_t* arena,
                                const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, hipStream_t st);
 // one object per head-set count (hs1: up to 4 query heads per KV head, hs2: 8)
-// waves: wavefronts per workgroup, 4 or 8 (8 only where such an instantiation exists: hs1, rows of up to 32 words)
-hipError_t launch_decode_mixed_hs1(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q,
-                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
-                                   hipStream_t st);
-hipError_t launch_decode_mixed_hs2(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
-                                   int max_words, int max_steps, int max_qsteps, const uint16_t* q,
-                                   const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,
-                                   hipStream_t st);
-
+// One object per head-set count (hs1: up to 4 query heads per KV head, hs2: 8) and row length class (long0: K rows
+// of up to 32 words, long1: up to 68).  waves: wavefronts per workgroup, 4 or 8 (8 only in hs1 / long0).
+#define RDKV_DECLARE_MIXED(NAME_)                                                                                \
+  hipError_t NAME_(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k, int max_words, \
+                   int max_steps, int max_qsteps, const uint16_t* q, const MergeArgs& ma, const int32_t* tail_len, \
+                   int per_unit, int waves, hipStream_t st);
+RDKV_DECLARE_MIXED(launch_decode_mixed_hs1_long0)
+RDKV_DECLARE_MIXED(launch_decode_mixed_hs1_long1)
+RDKV_DECLARE_MIXED(launch_decode_mixed_hs2_long0)
+RDKV_DECLARE_MIXED(launch_decode_mixed_hs2_long1)
+#undef RDKV_DECLARE_MIXED
 inline hipError_t launch_decode_mixed(const Chunk* chunks, int n_chunks, const uint8_t* arena, const ItemK* items_k,
                                       int max_words, int max_steps, int max_qsteps, const uint16_t* q,
                                       const MergeArgs& ma, const int32_t* tail_len, int per_unit, int waves,

@@ -1058,8 +1058,8 @@ rdkv_status rdkv_weights(const rdkv_config* cfg, const void* K, const void* Q_ob
                          float* w_ch, void* stream) {
   rdkv_status s = check_config(cfg, false, true);
   if (s != RDKV_OK) return s;
+  if (cfg->batch == 0) return RDKV_OK;       // (the buffers of an empty batch may be null)
   if (!K || !Q_obs || !w_tok) return fail(RDKV_ERR_INVALID_ARG, "K, Q_obs and w_tok must not be null");
-  if (cfg->batch == 0) return RDKV_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
   Temp tmp(al, st);
@@ -1128,11 +1128,11 @@ rdkv_status rdkv_allocate_info(const rdkv_config* cfg, const float* w_tok, const
                                uint8_t* bits_ch, double* lambda_out, int32_t* iterations_out, void* stream) {
   rdkv_status s = check_config(cfg, true, false);
   if (s != RDKV_OK) return s;
+  if (cfg->batch == 0) return RDKV_OK;       // (the buffers of an empty batch may be null)
   if (!w_tok || !bits_tok) return fail(RDKV_ERR_INVALID_ARG, "w_tok and bits_tok must not be null");
   const bool mixed = cfg->k_mode == RDKV_K_CHANNELWISE;
   if (mixed && (!w_ch || !bits_ch))
     return fail(RDKV_ERR_INVALID_ARG, "w_ch and bits_ch must not be null in channel-wise mode");
-  if (cfg->batch == 0) return RDKV_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
   Allocator al{cfg->alloc, cfg->free_, cfg->alloc_user};
   Temp tmp(al, st);
@@ -1287,8 +1287,9 @@ size_t rdkv_cache_max_table_bytes(const rdkv_config* cfg) {
 }
 
 rdkv_status rdkv_decode_attn(const rdkv_cache* c, const void* q, float* out, float* lse, void* stream) {
-  if (!c || !q || !out) return fail(RDKV_ERR_INVALID_ARG, "cache, q and out must not be null");
-  if (c->n_items == 0) return RDKV_OK;
+  if (!c) return fail(RDKV_ERR_INVALID_ARG, "cache must not be null");
+  if (c->n_items == 0) return RDKV_OK;       // nothing to compute (and q / out of an empty batch may be null)
+  if (!q || !out) return fail(RDKV_ERR_INVALID_ARG, "q and out must not be null");
   hipStream_t st = static_cast<hipStream_t>(stream);
   rdkv_cache::Workspace w;
   const rdkv_status ws = workspace_for(c, st, &w);

@@ -257,3 +257,67 @@ def test_schedule_rebuilt_on_another_stream_than_the_one_that_packed():
     torch.cuda.synchronize()
     assert torch.equal(out0, out1) and torch.equal(out0, out2) and torch.equal(lse0, lse1) and torch.equal(lse0, lse2)
     cache.free()
+
+
+def test_empty_and_degenerate_batches():
+    """No sequences at all, sequences of zero length among others, a single token, and budgets of zero everywhere: every
+    call returns, the outputs of items without retained tokens are 0 with lse = -inf, and appended tokens still count."""
+    b = B()
+    hq, hkv = 8, 2
+    dev = "cuda"
+    # no sequences
+    cfg0 = b.Config([], hq, hkv, budget_bits=[])
+    empty16 = torch.empty(0, dtype=torch.bfloat16, device=dev)
+    cache = b.rdkv_pack(cfg0, empty16, empty16, torch.empty(0, dtype=torch.uint8, device=dev))
+    st = cache.stats()
+    assert st["n_items"] == 0 and st["stored_bytes"] == 0
+    out, lse = b.rdkv_decode_attn(cache, torch.empty((0, hq, 128), dtype=torch.bfloat16, device=dev))
+    assert out.numel() == 0
+    cache.free()
+    cache = b.rdkv_compress(cfg0, empty16, empty16, torch.empty((0, hq, 32, 128), dtype=torch.bfloat16, device=dev))
+    cache.free()
+    # sequences of length 0 and 1 beside an ordinary one (explicit maps: no probe needed)
+    rng = np.random.default_rng(81)
+    seq = [0, 1, 300]
+    n_rows = sum(seq) * hkv
+    K = torch.from_numpy(rng.standard_normal((n_rows, 128)).astype(np.float32)).to(torch.bfloat16).to(dev)
+    V = torch.from_numpy(rng.standard_normal((n_rows, 128)).astype(np.float32)).to(torch.bfloat16).to(dev)
+    q = torch.from_numpy(rng.standard_normal((3, hq, 128)).astype(np.float32)).to(torch.bfloat16).to(dev)
+    bits = [np.zeros((hkv, 0), np.uint8), np.array([[4], [0]], np.uint8),
+            rng.choice(np.array([0, 2, 4, 8, 16], np.uint8), size=(hkv, 300))]
+    cfg = b.Config(seq, hq, hkv)
+    cache = b.rdkv_pack(cfg, K.reshape(-1), V.reshape(-1), torch.from_numpy(np.concatenate([x.reshape(-1) for x in bits])).to(dev))
+    out, lse = b.rdkv_decode_attn(cache, q)
+    torch.cuda.synchronize()
+    Kc, Vc = K.float().cpu().numpy(), V.float().cpu().numpy()
+    Ks = [Kc[:0].reshape(hkv, 0, 128), Kc[:2].reshape(hkv, 1, 128), Kc[2:].reshape(hkv, 300, 128)]
+    Vs = [Vc[:0].reshape(hkv, 0, 128), Vc[:2].reshape(hkv, 1, 128), Vc[2:].reshape(hkv, 300, 128)]
+    ref = O.build_cache_tokenwise(Ks, Vs, bits)
+    ref_out, ref_lse = O.decode(ref, q.float().cpu().numpy())
+    from test_gpu_parity import _check_decode
+    _check_decode(out, lse, ref_out, ref_lse)
+    assert np.isneginf(lse.cpu().numpy()[0]).all() and not out[0].any()              # the empty sequence
+    assert np.isneginf(lse.cpu().numpy()[1, hq // 2:]).all()                            # its second KV head evicted its token
+    # appended tokens are attended to even where nothing of the prompt is left
+    b.rdkv_cache_reserve_tail(cache, 4)
+    kn = torch.from_numpy(rng.standard_normal((2, 3, hkv, 128)).astype(np.float32)).to(torch.bfloat16)
+    for i in range(2):
+        b.rdkv_cache_append(cache, kn[i].to(dev), kn[1 - i].to(dev))
+        O.append_tokens(ref, kn[i].float().numpy(), kn[1 - i].float().numpy())
+    out, lse = b.rdkv_decode_attn(cache, q)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = O.decode(ref, q.float().cpu().numpy())
+    _check_decode(out, lse, ref_out, ref_lse)
+    assert np.isfinite(lse.cpu().numpy()).all()
+    cache.free()
+    # a budget of zero: everything evicted by the pass itself
+    seq = [64, 100]
+    K = torch.from_numpy(rng.standard_normal((sum(seq) * hkv, 128)).astype(np.float32)).to(torch.bfloat16).to(dev)
+    Q = torch.from_numpy(rng.standard_normal((2, hq, 32, 128)).astype(np.float32)).to(torch.bfloat16).to(dev)
+    cache = b.rdkv_compress(b.Config(seq, hq, hkv, budget_bits=[0.0, 0.0]), K.reshape(-1), K.reshape(-1), Q)
+    st = cache.stats()
+    assert st["stored_bytes"] == 0 and st["evicted"] == sum(seq) * hkv
+    out, lse = b.rdkv_decode_attn(cache, q[:2].contiguous())
+    torch.cuda.synchronize()
+    assert not out.any() and np.isneginf(lse.cpu().numpy()).all()
+    cache.free()

@@ -236,3 +236,41 @@ def test_mixed_config_with_three_sequences():
     _check_sampled_items(b, wl, inp, cache, out, lse, inp["w_tok"], [(0, 1), (2, 6)], mixed=True,
                          w_ch=w_ch.cpu().numpy().reshape(-1, wl.d))
     cache.free()
+
+
+def test_one_million_token_sequence():
+    """The longest context tried: one sequence of 2^20 tokens (8 KV heads, 0.5 bit/elt).  The pass and the decode step
+    on the whole sequence, the bf16 path beside it; the oracle redoes one KV head from the library's own weights."""
+    b = B()
+    T, hq, hkv, h = 1 << 20, 32, 8, 5
+    g = hq // hkv
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    K = torch.randn((hkv, T, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    V = torch.randn((hkv, T, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    Q = torch.randn((1, hq, 32, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    q = torch.randn((1, hq, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    print("[case] one sequence of 2^20 tokens", flush=True)
+    cfg = b.Config([T], hq, hkv, budget_bits=[0.5])
+    cache = b.rdkv_compress(cfg, K.reshape(-1), V.reshape(-1), Q)
+    out, lse = b.rdkv_decode_attn(cache, q)
+    w, _ = b.rdkv_weights(cfg, K.reshape(-1), Q)
+    torch.cuda.synchronize()
+    st = cache.stats()
+    assert st["arena_bytes"] <= b.rdkv_cache_max_bytes(cfg) and st["rows"][3] + st["rows"][2] + st["rows"][1] + st["rows"][0] + st["evicted"] == hkv * T
+    bt = O.mckp_bisect(w.view(hkv, T)[h].cpu().numpy(), np.float32(0.5))
+    np.testing.assert_array_equal(cache.export(b.RDKV_EXPORT_BITS_TOK, np.uint8).reshape(hkv, T)[h], bt)
+    Kh, Vh = K[h].float().cpu().numpy()[None], V[h].float().cpu().numpy()[None]
+    qh = q[:, h * g:(h + 1) * g].float().cpu().numpy()
+    ref = O.build_cache_tokenwise([Kh], [Vh], [bt[None]])
+    ro, rl = O.decode(ref, qh)
+    err = _rel_err(out[0, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)[None], ro)
+    print(f"[2^20 tokens] decode error {err:.2e} over {int((bt > 0).sum())} retained tokens", flush=True)
+    assert err <= DECODE_TOL
+    np.testing.assert_allclose(lse[0, h * g:(h + 1) * g].cpu().numpy()[None], rl, rtol=1e-4, atol=1e-4)
+    ws = torch.empty(b.rdkv_decode_bf16_workspace_bytes([T], hq, hkv), dtype=torch.uint8, device="cuda")
+    o16, l16 = b.rdkv_decode_attn_bf16(K.reshape(-1), V.reshape(-1), [T], hq, hkv, q, workspace=ws)
+    torch.cuda.synchronize()
+    d_out, d_lse = O.decode_dense([Kh], [Vh], qh)
+    assert _rel_err(o16[0, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)[None], d_out) <= DECODE_TOL
+    np.testing.assert_allclose(l16[0, h * g:(h + 1) * g].cpu().numpy()[None], d_lse, rtol=1e-4, atol=1e-4)
+    cache.free()

@@ -369,6 +369,9 @@ rdkv_status rdkv_cache_stats(const rdkv_cache* cache, rdkv_stats* out);
 size_t rdkv_cache_export_bytes(const rdkv_cache* cache, int what);
 /* Copies the export to HOST memory `dst` of `bytes` >= rdkv_cache_export_bytes(); synchronous. */
 rdkv_status rdkv_cache_export(const rdkv_cache* cache, int what, void* dst, size_t bytes);
+/* Releases the cache, its generations and workspaces through the allocator it was built with (a null handle is a
+ * no-op).  The memory goes back at once: the caller makes sure that no work that reads the cache (a decode step, an
+ * append, a graph replay) is still queued on any stream. */
 void rdkv_cache_free(rdkv_cache* cache);
 
 #ifdef __cplusplus

@@ -19,7 +19,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 constexpr int kTokPerWG = 256;
-constexpr int kRowsPerStage = 128;          // window rows staged in LDS at a time (39 KB per workgroup: 4 per CU)
+constexpr int kRowsPerStage = 64;           // window rows staged in LDS at a time (19.5 KB per workgroup)
 constexpr int kQStride = kHeadDim + 8;      // bf16 elements per LDS row (272 B: conflict-free 16-byte reads)
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLogitScale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
@@ -52,7 +52,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <int PASS>
-__global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
+__global__ __launch_bounds__(256, 3) void weights_kernel(WeightArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint16_t* sQ = reinterpret_cast<uint16_t*>(smem_raw);                              // [kRowsPerStage][kQStride]
   float* sStat = reinterpret_cast<float*>(smem_raw + kRowsPerStage * kQStride * 2);   // [4 waves][kRowsPerStage][2]
@@ -114,20 +114,30 @@ __global__ __launch_bounds__(256) void weights_kernel(WeightArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) colsum[tt][i] = 0.f;
 
-  // The window rows pass through LDS kRowsPerStage at a time (the keys stay in registers): a workgroup then needs
-  // 39 KB instead of 78 KB for 256 rows and four of them fit a CU.
+  // The window rows pass through LDS kRowsPerStage at a time (the keys stay in registers).  A stage's rows are
+  // fetched into registers while the previous stage is computed (4 x 16 bytes per thread) and stored to LDS between
+  // two barriers, so that only the first stage's latency is waited for.
+  uint4 qbuf[4];
+  auto fetch = [&](int r0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = tid + 256 * k, r = i >> 4, c8 = i & 15;
+      qbuf[k] = make_uint4(0, 0, 0, 0);        // pad rows are zero
+      if (r0 + r < a.R) qbuf[k] = *reinterpret_cast<const uint4*>(Qg + (r0 + r) * kHeadDim + c8 * 8);
+    }
+  };
+  fetch(0);
   for (int r0 = 0; r0 < a.R_pad; r0 += kRowsPerStage) {
   const int nrows = min(kRowsPerStage, a.R_pad - r0);
   __syncthreads();   // the previous stage's readers are done
-  // stage rows r0 .. r0 + nrows of this KV head (contiguous in Q_obs) into LDS; pad rows are zero
-  for (int i = tid; i < nrows * (kHeadDim / 8); i += 256) {
-    const int r = i >> 4, c8 = i & 15;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r0 + r < a.R) v = *reinterpret_cast<const uint4*>(Qg + (r0 + r) * kHeadDim + c8 * 8);
-    *reinterpret_cast<uint4*>(sQ + r * kQStride + c8 * 8) = v;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = tid + 256 * k, r = i >> 4, c8 = i & 15;
+    *reinterpret_cast<uint4*>(sQ + r * kQStride + c8 * 8) = qbuf[k];
   }
   if (PASS == 2)   // the rows' log-sum-exp, read once per row tile below
     for (int r = tid; r < nrows; r += 256) sStat[r] = a.lse[static_cast<int64_t>(item) * a.R_pad + r0 + r];
+  if (r0 + kRowsPerStage < a.R_pad) fetch(r0 + kRowsPerStage);   // in flight during this stage's arithmetic
   __syncthreads();
   for (int rt = 0; rt < nrows / 16; ++rt) {
     floatx4 acc[4];
